@@ -1,0 +1,224 @@
+// Shared device/host helpers of the gfx950 2D Neighborhood Attention kernels.
+//
+// Neighbourhood definition: arXiv 2204.07143, Section 3.1 (k nearest neighbours per axis,
+// Eq. 2) and the Appendix figure "3x3 NA on a 7x7 map" (window shifted, not shrunk, at the
+// borders).  Everything in this header is index arithmetic, storage-type conversion and
+// LDS staging; the attention arithmetic lives in the kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "na2d.h"
+
+namespace na2d {
+
+constexpr int kHeadDim = 32;       // D: every NAT variant uses head dim 32 (Section 3.2)
+constexpr int kWave = 64;          // CDNA wavefront width
+
+// ---- neighbourhood index functions (one axis of length L, odd window K <= L) -----------
+
+// First key coordinate seen by query coordinate i.
+__host__ __device__ __forceinline__ int win_start(int i, int L, int K) {
+    int s = i - (K >> 1);
+    s = s < 0 ? 0 : s;
+    int hi = L - K;
+    return s > hi ? hi : s;
+}
+
+// Row/column of the bias table that window slot 0 of query coordinate i maps to:
+// key - query + (K - 1) with key = win_start(i).
+__host__ __device__ __forceinline__ int rpb_start(int i, int L, int K) {
+    return win_start(i, L, K) - i + (K - 1);
+}
+
+// Inverse neighbourhood: the queries whose window holds key coordinate j form the contiguous
+// range [inv_first(j), inv_last(j)].
+__host__ __device__ __forceinline__ int inv_first(int j, int L, int K) {
+    (void)L;
+    return j <= K - 1 ? 0 : j - (K >> 1);
+}
+__host__ __device__ __forceinline__ int inv_last(int j, int L, int K) {
+    return j >= L - K ? L - 1 : j + (K >> 1);
+}
+
+// ---- storage types -------------------------------------------------------------------
+
+typedef _Float16 f16_t;
+typedef __bf16 bf16_t;
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <typename T> struct Traits;
+template <> struct Traits<float> {
+    static constexpr int kDtype = NA2D_F32;
+    static constexpr int kKeyBytes = kHeadDim * 4;
+    static constexpr int kKeyStride = kKeyBytes + 16;   // LDS stride of one key: 36 dwords, conflict-free for b128 reads
+};
+template <> struct Traits<f16_t> {
+    static constexpr int kDtype = NA2D_F16;
+    static constexpr int kKeyBytes = kHeadDim * 2;
+    static constexpr int kKeyStride = kKeyBytes + 16;   // 20 dwords
+};
+template <> struct Traits<bf16_t> {
+    static constexpr int kDtype = NA2D_BF16;
+    static constexpr int kKeyBytes = kHeadDim * 2;
+    static constexpr int kKeyStride = kKeyBytes + 16;
+};
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(f16_t x) { return (float)x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return (float)x; }
+
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ f16_t from_f32<f16_t>(float x) { return (f16_t)x; }   // round-to-nearest-even
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; } // round-to-nearest-even
+
+// A head vector (32 elements) held in registers in its storage type, as 32-bit words.
+template <typename T> struct Vec32 {
+    static constexpr int kChunks = Traits<T>::kKeyBytes / 16;
+    static constexpr int kWords = Traits<T>::kKeyBytes / 4;
+    uint32_t w[kWords];
+};
+
+template <typename T>
+__device__ __forceinline__ void load_vec32(Vec32<T> &v, const void *p) {
+    const u32x4 *s = reinterpret_cast<const u32x4 *>(p);
+#pragma unroll
+    for (int i = 0; i < Vec32<T>::kChunks; ++i) {
+        const u32x4 t = s[i];
+        v.w[4 * i + 0] = t.x;
+        v.w[4 * i + 1] = t.y;
+        v.w[4 * i + 2] = t.z;
+        v.w[4 * i + 3] = t.w;
+    }
+}
+
+// fp32 dot product of two head vectors held in storage type.
+__device__ __forceinline__ float dot32(const Vec32<float> &a, const Vec32<float> &b) {
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) acc = __builtin_fmaf(__uint_as_float(a.w[i]), __uint_as_float(b.w[i]), acc);
+    return acc;
+}
+__device__ __forceinline__ float dot32(const Vec32<f16_t> &a, const Vec32<f16_t> &b) {
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t ua = a.w[i], ub = b.w[i];
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, ua), __builtin_bit_cast(f16x2, ub), acc, false);
+    }
+    return acc;
+}
+__device__ __forceinline__ float dot32(const Vec32<bf16_t> &a, const Vec32<bf16_t> &b) {
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t ua = a.w[i], ub = b.w[i];
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, ua), __builtin_bit_cast(bf16x2, ub), acc, false);
+    }
+    return acc;
+}
+
+// acc[0..31] += w * v  (fp32 accumulate, v in storage type).
+__device__ __forceinline__ void axpy32(float (&acc)[kHeadDim], float w, const Vec32<float> &v) {
+#pragma unroll
+    for (int i = 0; i < 32; ++i) acc[i] = __builtin_fmaf(w, __uint_as_float(v.w[i]), acc[i]);
+}
+__device__ __forceinline__ void axpy32(float (&acc)[kHeadDim], float w, const Vec32<f16_t> &v) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t u = v.w[i];
+        const f16_t lo = __builtin_bit_cast(f16_t, (uint16_t)(u & 0xffffu));
+        const f16_t hi = __builtin_bit_cast(f16_t, (uint16_t)(u >> 16));
+        acc[2 * i] = __builtin_fmaf(w, (float)lo, acc[2 * i]);
+        acc[2 * i + 1] = __builtin_fmaf(w, (float)hi, acc[2 * i + 1]);
+    }
+}
+__device__ __forceinline__ void axpy32(float (&acc)[kHeadDim], float w, const Vec32<bf16_t> &v) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t u = v.w[i];
+        acc[2 * i] = __builtin_fmaf(w, __uint_as_float(u << 16), acc[2 * i]);
+        acc[2 * i + 1] = __builtin_fmaf(w, __uint_as_float(u & 0xffff0000u), acc[2 * i + 1]);
+    }
+}
+
+// Store 32 fp32 values as one head vector in storage type (p is 16-byte aligned).
+template <typename T>
+__device__ __forceinline__ void store_vec32(void *p, const float (&x)[kHeadDim]) {
+    if constexpr (sizeof(T) == 4) {
+        f32x4 *d = reinterpret_cast<f32x4 *>(p);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) d[i] = f32x4{x[i * 4], x[i * 4 + 1], x[i * 4 + 2], x[i * 4 + 3]};
+    } else {
+        u32x4 *d = reinterpret_cast<u32x4 *>(p);
+        uint32_t w[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const T lo = from_f32<T>(x[2 * i]), hi = from_f32<T>(x[2 * i + 1]);
+            w[i] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) d[i] = u32x4{w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]};
+    }
+}
+
+// ---- alignment-preserving staging between global memory and LDS -------------------------
+//
+// A run of `nbytes` bytes starting at global byte offset g0 of `gbase` (gbase 16-byte
+// aligned, g0 a multiple of sizeof(T)) is mirrored in an LDS region at offset (g0 & 15), so
+// that 16-byte aligned global chunks map to 16-byte aligned LDS chunks.  Chunks that lie
+// fully inside the run move as one 16-byte access; the ragged first and last chunks move
+// element by element.  The region needs (nbytes + 30) rounded up to 16 bytes.
+
+template <typename T>
+__device__ __forceinline__ void stage_in(const char *gbase, size_t g0, int nbytes, char *region, int tid, int nthreads) {
+    const int mis = (int)(g0 & 15);
+    const char *ga = gbase + (g0 - mis);
+    const int span = mis + nbytes;
+    const int nchunks = (span + 15) >> 4;
+    for (int ci = tid; ci < nchunks; ci += nthreads) {
+        const int lo = ci << 4;
+        if (lo >= mis && lo + 16 <= span) {
+            *reinterpret_cast<u32x4 *>(region + lo) = *reinterpret_cast<const u32x4 *>(ga + lo);
+        } else {
+            const int b0 = lo > mis ? lo : mis, b1 = lo + 16 < span ? lo + 16 : span;
+            for (int b = b0; b < b1; b += (int)sizeof(T))
+                *reinterpret_cast<T *>(region + b) = *reinterpret_cast<const T *>(ga + b);
+        }
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ void stage_out(char *gbase, size_t g0, int nbytes, const char *region, int tid, int nthreads) {
+    const int mis = (int)(g0 & 15);
+    char *ga = gbase + (g0 - mis);
+    const int span = mis + nbytes;
+    const int nchunks = (span + 15) >> 4;
+    for (int ci = tid; ci < nchunks; ci += nthreads) {
+        const int lo = ci << 4;
+        if (lo >= mis && lo + 16 <= span) {
+            *reinterpret_cast<u32x4 *>(ga + lo) = *reinterpret_cast<const u32x4 *>(region + lo);
+        } else {
+            const int b0 = lo > mis ? lo : mis, b1 = lo + 16 < span ? lo + 16 : span;
+            for (int b = b0; b < b1; b += (int)sizeof(T))
+                *reinterpret_cast<T *>(ga + b) = *reinterpret_cast<const T *>(region + b);
+        }
+    }
+}
+
+// Bytes an LDS mirror region must have for a run of nbytes.
+__host__ __device__ constexpr int mirror_bytes(int nbytes) { return (nbytes + 30 + 15) & ~15; }
+
+// ---- host-side launch description ---------------------------------------------------
+
+struct Geo {
+    int B, heads, H, W;
+    int planes;      // B * heads
+};
+
+}  // namespace na2d

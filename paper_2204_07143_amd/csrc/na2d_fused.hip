@@ -1,0 +1,138 @@
+// Fused neighbourhood attention forward (arXiv 2204.07143, Eq. 2-4 in one kernel):
+//   out_n = softmax_{a,c}( scale * <q_n, k_{rho(n;a,c)}> + B(n, rho(n;a,c)) ) . v_{rho(n;a,c)}
+// The K*K logits and weights never reach HBM: the h*w*k^2 attention tensor is the memory
+// term of the paper's complexity table (Section 3.3) and fusing removes its round trip.
+//
+// One workgroup per TY x 16 query tile; the key halo and the value halo of the tile are staged
+// once in LDS.  Each thread owns one query and walks its window row by row with a running
+// max / running sum (online softmax), rescaling its 32 fp32 accumulators once per window row.
+#include "na2d_kernels.hpp"
+#include "na2d_tile.hpp"
+
+namespace na2d {
+
+template <typename T, int K, int TY>
+struct FusedCfg {
+    static constexpr int HALO_H = TY + K - 1, HALO_W = kTileX + K - 1;
+    static constexpr int NB = 2 * K - 1;
+    static constexpr int kThreads = kTileX * TY;
+    static constexpr int kHaloBytes = HALO_H * HALO_W * Traits<T>::kKeyStride;
+    static constexpr int kBiasBytes = ((NB * NB * 4) + 15) & ~15;
+    static constexpr int kLdsBytes = 2 * kHaloBytes + kBiasBytes;
+};
+
+template <typename T, int K>
+constexpr int fused_tile_rows() {
+    if (FusedCfg<T, K, 16>::kLdsBytes <= 80 * 1024) return 16;
+    if (FusedCfg<T, K, 8>::kLdsBytes <= 80 * 1024) return 8;
+    return 4;
+}
+
+template <typename T, int K, int TY>
+__global__ __launch_bounds__(kTileX *TY) void fused_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k,
+                                                                const T *__restrict__ v, const T *__restrict__ rpb,
+                                                                float scale, T *__restrict__ out,
+                                                                float *__restrict__ lse, int H, int W, int heads,
+                                                                int tiles_x, int tiles_y, int ntiles) {
+    using C = FusedCfg<T, K, TY>;
+    extern __shared__ __align__(16) char lds[];
+    char *khalo = lds;
+    char *vhalo = lds + C::kHaloBytes;
+    float *bias = reinterpret_cast<float *>(lds + 2 * C::kHaloBytes);
+
+    const int t = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    if (t >= ntiles) return;
+    const TileCoord tc = decode_tile(t, tiles_x, tiles_y);
+    const int ty0 = tc.tiy * TY, tx0 = tc.tix * kTileX;
+    const int tid = threadIdx.x;
+    const int hy0 = win_start(ty0, H, K), hx0 = win_start(tx0, W, K);
+    const size_t plane_q = (size_t)tc.plane * H * W;
+
+    load_halo<T, C::HALO_H, C::HALO_W>(reinterpret_cast<const char *>(k) + plane_q * Traits<T>::kKeyBytes, H, W, hy0,
+                                       hx0, khalo, tid, C::kThreads);
+    load_halo<T, C::HALO_H, C::HALO_W>(reinterpret_cast<const char *>(v) + plane_q * Traits<T>::kKeyBytes, H, W, hy0,
+                                       hx0, vhalo, tid, C::kThreads);
+    {
+        const int head = tc.plane % heads;
+        for (int i = tid; i < C::NB * C::NB; i += C::kThreads)
+            bias[i] = rpb ? to_f32(rpb[(size_t)head * C::NB * C::NB + i]) : 0.f;
+    }
+    __syncthreads();
+
+    const int lx = tid % kTileX, ly = tid / kTileX;
+    const int qy = ty0 + ly, qx = tx0 + lx;
+    if (qy < H && qx < W) {
+        Vec32<T> qv;
+        load_vec32(qv, reinterpret_cast<const char *>(q) + (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes);
+        const int sy = win_start(qy, H, K), sx = win_start(qx, W, K);
+        const int py = sy - qy + (K - 1), px = sx - qx + (K - 1);
+        const int hoff = ((sy - hy0) * C::HALO_W + (sx - hx0)) * Traits<T>::kKeyStride;
+        const float *bbase = bias + py * C::NB + px;
+        float acc[kHeadDim];
+#pragma unroll
+        for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
+        float m = -INFINITY, l = 0.f;
+#pragma unroll 1
+        for (int a = 0; a < K; ++a) {
+            float s[K];
+            float rowmax = -INFINITY;
+#pragma unroll
+            for (int c = 0; c < K; ++c) {
+                Vec32<T> kv;
+                lds_load_vec32(kv, khalo + hoff + (a * C::HALO_W + c) * Traits<T>::kKeyStride);
+                s[c] = __builtin_fmaf(scale, dot32(qv, kv), bbase[a * C::NB + c]);
+                rowmax = fmaxf(rowmax, s[c]);
+            }
+            const float mnew = fmaxf(m, rowmax);
+            const float corr = __expf(m - mnew);   // exp(-inf) = 0 on the first row
+            l *= corr;
+#pragma unroll
+            for (int d = 0; d < kHeadDim; ++d) acc[d] *= corr;
+#pragma unroll
+            for (int c = 0; c < K; ++c) {
+                const float e = __expf(s[c] - mnew);
+                l += e;
+                Vec32<T> vv;
+                lds_load_vec32(vv, vhalo + hoff + (a * C::HALO_W + c) * Traits<T>::kKeyStride);
+                axpy32(acc, e, vv);
+            }
+            m = mnew;
+        }
+        const float inv = 1.0f / l;
+#pragma unroll
+        for (int d = 0; d < kHeadDim; ++d) acc[d] *= inv;
+        store_vec32<T>(reinterpret_cast<char *>(out) + (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes, acc);
+        if (lse) lse[plane_q + (size_t)qy * W + qx] = m + __logf(l);
+    }
+}
+
+template <typename T, int K>
+static hipError_t launch_fused_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
+                                 float scale, void *out, float *lse, hipStream_t s) {
+    constexpr int TY = fused_tile_rows<T, K>();
+    using C = FusedCfg<T, K, TY>;
+    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + TY - 1) / TY;
+    const int ntiles = tiles_x * tiles_y * p.planes();
+    auto kern = fused_fwd_kernel<T, K, TY>;
+    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(ntiles)), dim3(C::kThreads), C::kLdsBytes, s,
+                       static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
+                       static_cast<const T *>(rpb), scale, static_cast<T *>(out), lse, p.H, p.W, p.heads, tiles_x,
+                       tiles_y, ntiles);
+    return hipGetLastError();
+}
+
+hipError_t launch_fused_fwd(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
+                            void *out, float *lse, hipStream_t s) {
+    NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, return (launch_fused_t<T, K>(p, q, k, v, rpb, scale, out, lse, s))));
+    return hipErrorInvalidValue;
+}
+
+}  // namespace na2d

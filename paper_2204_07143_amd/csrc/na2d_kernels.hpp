@@ -1,0 +1,53 @@
+// Internal launch interface between the C ABI layer and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "na2d.h"
+
+namespace na2d {
+
+struct Problem {
+    int B, heads, H, W, K, dtype;
+    int planes() const { return B * heads; }
+    size_t queries() const { return (size_t)B * heads * H * W; }
+    int elem_bytes() const { return dtype == NA2D_F32 ? 4 : 2; }
+};
+
+// logits = scale * <x, y_window> + bias   (QK+RPB, and grad-a with x = dout, y = v, no bias)
+hipError_t launch_qk(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
+                     hipStream_t s);
+// out = scale * sum_window w * y          (AV, and grad-q with w = ds, y = k)
+hipError_t launch_av(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);
+// out_j = scale * sum_{inverse neighbourhood} w[i, slot(i, j)] * x_i   (grad-v, grad-k)
+hipError_t launch_inverse(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
+hipError_t launch_softmax(const Problem &p, const void *logits, void *out, hipStream_t s);
+hipError_t launch_softmax_bwd(const Problem &p, const void *attn, const void *dp, void *ds, hipStream_t s);
+size_t rpb_bwd_workspace_bytes(const Problem &p);
+hipError_t launch_rpb_bwd(const Problem &p, const void *ds, float *d_rpb, void *workspace, hipStream_t s);
+hipError_t launch_fused_fwd(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
+                            void *out, float *lse, hipStream_t s);
+hipError_t launch_indices(const Problem &p, int32_t *key_index, int32_t *rpb_index, hipStream_t s);
+
+}  // namespace na2d
+
+// Expands BODY once with `T` bound to the storage type and `K` to the window side.
+#define NA2D_DISPATCH_K(kval, ...)                                   \
+    switch (kval) {                                                  \
+        case 3: { constexpr int K = 3; __VA_ARGS__; } break;         \
+        case 5: { constexpr int K = 5; __VA_ARGS__; } break;         \
+        case 7: { constexpr int K = 7; __VA_ARGS__; } break;         \
+        case 9: { constexpr int K = 9; __VA_ARGS__; } break;         \
+        case 11: { constexpr int K = 11; __VA_ARGS__; } break;       \
+        case 13: { constexpr int K = 13; __VA_ARGS__; } break;       \
+        default: return hipErrorInvalidValue;                        \
+    }
+#define NA2D_DISPATCH_T(dtval, ...)                                                  \
+    switch (dtval) {                                                                 \
+        case NA2D_F32: { using T = float; __VA_ARGS__; } break;                      \
+        case NA2D_F16: { using T = ::na2d::f16_t; __VA_ARGS__; } break;              \
+        case NA2D_BF16: { using T = ::na2d::bf16_t; __VA_ARGS__; } break;            \
+        default: return hipErrorInvalidValue;                                        \
+    }

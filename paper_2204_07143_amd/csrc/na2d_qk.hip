@@ -1,0 +1,128 @@
+// Neighbourhood logits: logits[n, a, c] = scale * <x_n, y_{rho(n; a, c)}> + bias
+// (arXiv 2204.07143, Eq. 2: QK + relative positional bias; the same contraction with
+// x = dout, y = v and no bias is grad-a of the backward pass, Appendix A).
+//
+// One workgroup per TY x 16 query tile: the (TY+K-1) x (16+K-1) key halo is staged once in
+// LDS, each thread owns one query (held in registers in its storage type) and walks its
+// K x K window with packed dot products (v_dot2 for f16/bf16), and the tile's logits are
+// gathered in LDS so that they leave the chip as 16-byte coalesced stores (a query's K*K
+// logits are not a multiple of 16 bytes, so stores are issued per contiguous tile row).
+#include "na2d_kernels.hpp"
+#include "na2d_tile.hpp"
+
+namespace na2d {
+
+template <typename T, int K, int TY>
+struct QkCfg {
+    static constexpr int HALO_H = TY + K - 1, HALO_W = kTileX + K - 1;
+    static constexpr int NB = 2 * K - 1;
+    static constexpr int KK = K * K;
+    static constexpr int kThreads = kTileX * TY;
+    static constexpr int kHaloBytes = HALO_H * HALO_W * Traits<T>::kKeyStride;
+    static constexpr int kBiasBytes = ((NB * NB * 4) + 15) & ~15;
+    static constexpr int kRowRegion = mirror_bytes(kTileX * KK * (int)sizeof(T));
+    static constexpr int kLdsBytes = kHaloBytes + kBiasBytes + TY * kRowRegion;
+};
+
+// Largest tile height whose LDS footprint lets two workgroups share a CU (160 KB LDS).
+template <typename T, int K>
+constexpr int qk_tile_rows() {
+    if (QkCfg<T, K, 16>::kLdsBytes <= 80 * 1024) return 16;
+    if (QkCfg<T, K, 8>::kLdsBytes <= 80 * 1024) return 8;
+    return 4;
+}
+
+template <typename T, int K, int TY>
+__global__ __launch_bounds__(kTileX *TY) void qk_kernel(const T *__restrict__ x, const T *__restrict__ y,
+                                                         const T *__restrict__ rpb, float scale,
+                                                         T *__restrict__ logits, int H, int W, int heads,
+                                                         int tiles_x, int tiles_y, int ntiles) {
+    using C = QkCfg<T, K, TY>;
+    extern __shared__ __align__(16) char lds[];
+    char *halo = lds;
+    float *bias = reinterpret_cast<float *>(lds + C::kHaloBytes);
+    char *rows = lds + C::kHaloBytes + C::kBiasBytes;
+
+    const int t = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    if (t >= ntiles) return;
+    const TileCoord tc = decode_tile(t, tiles_x, tiles_y);
+    const int ty0 = tc.tiy * TY, tx0 = tc.tix * kTileX;
+    const int tid = threadIdx.x;
+    const int hy0 = win_start(ty0, H, K), hx0 = win_start(tx0, W, K);
+    const size_t plane_q = (size_t)tc.plane * H * W;
+
+    load_halo<T, C::HALO_H, C::HALO_W>(reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes, H, W, hy0,
+                                       hx0, halo, tid, C::kThreads);
+    {
+        const int head = tc.plane % heads;
+        for (int i = tid; i < C::NB * C::NB; i += C::kThreads)
+            bias[i] = rpb ? to_f32(rpb[(size_t)head * C::NB * C::NB + i]) : 0.f;
+    }
+    __syncthreads();
+
+    const int lx = tid % kTileX, ly = tid / kTileX;
+    const int qy = ty0 + ly, qx = tx0 + lx;
+    // Global byte offset of this tile row's run of logits; its low 4 bits are mirrored in LDS.
+    const size_t g0 = (plane_q + (size_t)qy * W + tx0) * C::KK * sizeof(T);
+    if (qy < H && qx < W) {
+        Vec32<T> qv;
+        load_vec32(qv, reinterpret_cast<const char *>(x) + (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes);
+        const int sy = win_start(qy, H, K), sx = win_start(qx, W, K);
+        const int py = sy - qy + (K - 1), px = sx - qx + (K - 1);
+        const char *kbase = halo + ((sy - hy0) * C::HALO_W + (sx - hx0)) * Traits<T>::kKeyStride;
+        const float *bbase = bias + py * C::NB + px;
+        T *orow = reinterpret_cast<T *>(rows + ly * C::kRowRegion + (int)(g0 & 15)) + lx * C::KK;
+#pragma unroll 1
+        for (int a = 0; a < K; ++a) {
+#pragma unroll
+            for (int c = 0; c < K; ++c) {
+                Vec32<T> kv;
+                lds_load_vec32(kv, kbase + (a * C::HALO_W + c) * Traits<T>::kKeyStride);
+                const float dot = dot32(qv, kv);
+                orow[a * K + c] = from_f32<T>(__builtin_fmaf(scale, dot, bbase[a * C::NB + c]));
+            }
+        }
+    }
+    __syncthreads();
+
+    // Each wave streams out whole tile rows: one row's logits are contiguous in global memory.
+    const int wave = tid / kWave, lane = tid % kWave;
+    constexpr int kWaves = (C::kThreads + kWave - 1) / kWave;
+    const int nvalid = (W - tx0) < kTileX ? (W - tx0) : kTileX;
+    for (int r = wave; r < TY; r += kWaves) {
+        if (ty0 + r >= H) break;
+        const size_t g0r = (plane_q + (size_t)(ty0 + r) * W + tx0) * C::KK * sizeof(T);
+        stage_out<T>(reinterpret_cast<char *>(logits), g0r, nvalid * C::KK * (int)sizeof(T), rows + r * C::kRowRegion,
+                     lane, kWave < C::kThreads ? kWave : C::kThreads);
+    }
+}
+
+template <typename T, int K>
+static hipError_t launch_qk_t(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
+                              void *logits, hipStream_t s) {
+    constexpr int TY = qk_tile_rows<T, K>();
+    using C = QkCfg<T, K, TY>;
+    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + TY - 1) / TY;
+    const int ntiles = tiles_x * tiles_y * p.planes();
+    auto kern = qk_kernel<T, K, TY>;
+    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(ntiles)), dim3(C::kThreads), C::kLdsBytes, s,
+                       static_cast<const T *>(x), static_cast<const T *>(y), static_cast<const T *>(rpb), scale,
+                       static_cast<T *>(logits), p.H, p.W, p.heads, tiles_x, tiles_y, ntiles);
+    return hipGetLastError();
+}
+
+hipError_t launch_qk(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
+                     hipStream_t s) {
+    NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, return (launch_qk_t<T, K>(p, x, y, rpb, scale, logits, s))));
+    return hipErrorInvalidValue;
+}
+
+}  // namespace na2d

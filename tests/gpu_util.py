@@ -1,0 +1,114 @@
+"""Helpers of the GPU parity tests: tolerances, conversions, and a stage runner that goes
+through the C ABI (via the thin binding) only.
+
+Tolerance reading (stated once, used everywhere):
+  * fp32:  |g - o| <= 1e-5 * max(|o|, rms(o))   -- a relative 1e-5; the rms floor keeps the
+    test meaningful at zero crossings of the output.
+  * fp16 / bf16:  |g - o| <= 2e-3 + ulp(o)/2, with ulp that of the storage type at |o|.  The
+    2e-3 absolute bound is applied to the error before the final round-to-storage: a
+    correctly rounded bf16 value in [1, 2) is already up to 0.0039 away from the exact
+    result (and an fp16 value in [16, 32) up to 0.0078), so a flat 2e-3 cannot hold for any
+    implementation.  The number of elements outside the flat 2e-3 is returned for reporting.
+  * d_rpb (always fp32; sums of up to ~2e5 terms):  |g - o| <= 1e-4 * max|o|.
+  * indices: bit-exact.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2204_07143_amd import binding as na
+from paper_2204_07143_amd import synth
+
+
+def ulp(x: np.ndarray, dtype: str) -> np.ndarray:
+    mant, emin = (10, -14) if dtype == "f16" else (7, -126)
+    e = np.floor(np.log2(np.maximum(np.abs(x), 2.0 ** emin)))
+    return 2.0 ** (e - mant)
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def assert_close(name: str, got, want: np.ndarray, dtype: str) -> int:
+    """Element-wise parity check; returns the count of elements outside a flat 2e-3."""
+    g = to_np(got) if isinstance(got, torch.Tensor) else np.asarray(got, dtype=np.float64)
+    o = np.asarray(want, dtype=np.float64)
+    assert g.shape == o.shape, (name, g.shape, o.shape)
+    assert np.all(np.isfinite(g)), f"{name}: non-finite values"
+    err = np.abs(g - o)
+    if dtype == "f32":
+        tol = 1e-5 * np.maximum(np.abs(o), np.sqrt(np.mean(o * o)))
+    else:
+        tol = 2e-3 + 0.5 * ulp(o, dtype)
+    bad = err > tol
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - tol), err.shape)
+        raise AssertionError(f"{name} [{dtype}]: {int(bad.sum())} of {err.size} elements out of tolerance; worst at {i}: "
+                             f"got {g[i]!r}, want {o[i]!r}, err {err[i]:.3e}, tol {tol[i]:.3e}")
+    return int((err > 2e-3).sum())
+
+
+def assert_close_rpb(name: str, got, want: np.ndarray) -> None:
+    g = to_np(got)
+    o = np.asarray(want, dtype=np.float64)
+    tol = 1e-4 * max(np.abs(o).max(), 1e-30)
+    err = np.abs(g - o)
+    assert err.max() <= tol, f"{name}: max err {err.max():.3e} > {tol:.3e}"
+
+
+class Stages:
+    """Runs every unfused stage of forward and backward through the C ABI, keeping each
+    stage's stored output so the next oracle stage can be fed exactly what the GPU stored."""
+
+    def __init__(self, p: synth.Problem, host: dict, scale: float | None = None, use_rpb: bool = True):
+        self.p = p
+        self.k = p.k
+        self.scale = p.default_scale if scale is None else scale
+        dev = lambda x: synth.to_device(x, p.dtype)
+        self.q, self.key, self.v = dev(host["q"]), dev(host["k"]), dev(host["v"])
+        self.rpb = dev(host["rpb"]) if use_rpb else None
+        self.dout = dev(host["dout"]) if "dout" in host else None
+        self.tdtype = synth.TORCH_DTYPES[p.dtype]
+
+    def _attn(self):
+        return torch.empty((self.p.B, self.p.heads, self.p.H, self.p.W, self.p.kk), dtype=self.tdtype, device="cuda")
+
+    def forward_unfused(self):
+        self.logits = na.na2d_qk_rpb(self.q, self.key, self.rpb, self.scale, self.k, self._attn())
+        self.attn = na.na2d_softmax(self.logits, self.k, self.q, self._attn())
+        self.out = na.na2d_av(self.attn, self.v, self.k, torch.empty_like(self.q))
+        return self.out
+
+    def forward_fused(self, with_lse: bool = True):
+        self.lse = torch.empty(self.q.shape[:4], dtype=torch.float32, device="cuda") if with_lse else None
+        self.out_fused = na.na2d_fused_fwd(self.q, self.key, self.v, self.rpb, self.scale, self.k,
+                                           torch.empty_like(self.q), self.lse)
+        return self.out_fused
+
+    def backward_unfused(self):
+        self.dp = na.na2d_av_bwd_p(self.dout, self.v, self.k, self._attn())
+        self.dv = na.na2d_av_bwd_v(self.attn, self.dout, self.k, torch.empty_like(self.q))
+        self.ds = na.na2d_softmax_bwd(self.attn, self.dp, self.k, self.q, self._attn())
+        self.dq = na.na2d_qk_bwd_q(self.ds, self.key, self.scale, self.k, torch.empty_like(self.q))
+        self.dk = na.na2d_qk_bwd_k(self.ds, self.q, self.scale, self.k, torch.empty_like(self.q))
+        nb = 2 * self.k - 1
+        prob = na.problem(self.p.B, self.p.heads, self.p.H, self.p.W, self.p.D, self.k, self.tdtype)
+        ws = torch.empty(na.na2d_workspace_bytes(prob, na.WS_QK_BWD_RPB), dtype=torch.uint8, device="cuda")
+        self.d_rpb = na.na2d_qk_bwd_rpb(self.ds, self.k, self.q,
+                                        torch.empty((self.p.heads, nb, nb), dtype=torch.float32, device="cuda"), ws)
+
+    def backward_composed(self):
+        nb = 2 * self.k - 1
+        prob = na.problem(self.p.B, self.p.heads, self.p.H, self.p.W, self.p.D, self.k, self.tdtype)
+        ws = torch.empty(na.na2d_workspace_bytes(prob, na.WS_BWD), dtype=torch.uint8, device="cuda")
+        dq, dk, dv = (torch.empty_like(self.q) for _ in range(3))
+        d_rpb = torch.empty((self.p.heads, nb, nb), dtype=torch.float32, device="cuda")
+        na.na2d_bwd(self.q, self.key, self.v, self.attn, self.dout, self.scale, self.k, dq, dk, dv, d_rpb, ws)
+        return dq, dk, dv, d_rpb
+
+
+def plane(x, b: int, h: int):
+    """[B, heads, ...] -> the [1, 1, ...] slice of one plane (torch tensor or numpy array)."""
+    return x[b:b + 1, h:h + 1]

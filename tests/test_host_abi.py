@@ -1,0 +1,111 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, rejects bad arguments before touching HIP, and its index functions (the same
+__host__ __device__ code the kernels use) agree with brute force."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2204_07143_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "na2d.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(na2d_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    names = declared_symbols()
+    assert len(names) >= 17
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+    assert binding.na2d_version() >= 100
+
+
+def P(B=1, heads=1, H=14, W=14, D=32, k=3, dtype=0):
+    return binding.Na2dProblem(B, heads, H, W, D, k, dtype)
+
+
+@pytest.mark.parametrize("prob,code", [
+    (P(), 0),
+    (P(k=7, H=7, W=7), 0),
+    (P(dtype=3), -2),
+    (P(k=4), -3), (P(k=1), -3), (P(k=15, H=20, W=20), -3),
+    (P(k=7, H=6), -4), (P(k=7, W=5), -4),
+    (P(D=64), -5),
+    (P(B=0), -6), (P(H=-1), -6),
+    (P(B=4096, heads=16, H=512, W=512, k=3), -6),
+])
+def test_problem_validation(prob, code):
+    assert binding.na2d_validate_problem(prob) == code
+    assert isinstance(binding.strerror(code), str) and binding.strerror(code)
+
+
+def test_entry_points_reject_bad_arguments_before_any_hip_call():
+    lib = binding.load()
+    good = P(k=3)
+    buf = ctypes.create_string_buffer(64)
+    a16 = (ctypes.addressof(buf) + 15) & ~15
+    ok, off = ctypes.c_void_p(a16), ctypes.c_void_p(a16 + 4)
+    # null problem / null pointers / misaligned pointers / aliasing / workspace: all host-side
+    assert lib.na2d_qk_rpb(None, ok, ok, None, 1.0, ok, None) == -1
+    assert lib.na2d_qk_rpb(ctypes.byref(good), None, ok, None, 1.0, ok, None) == -1
+    assert lib.na2d_qk_rpb(ctypes.byref(good), ok, off, None, 1.0, ctypes.c_void_p(a16 + 16), None) == -7
+    assert lib.na2d_qk_rpb(ctypes.byref(good), ok, ctypes.c_void_p(a16 + 16), None, 1.0, ok, None) == -10
+    assert lib.na2d_av(ctypes.byref(P(k=4)), ok, ok, ok, None) == -3
+    assert lib.na2d_softmax(ctypes.byref(P(D=16)), ok, ok, None) == -5
+    assert lib.na2d_fused_fwd(ctypes.byref(P(k=7, H=5)), ok, ok, ok, None, 1.0, ok, None, None) == -4
+    assert lib.na2d_qk_bwd_rpb(ctypes.byref(good), ok, ctypes.c_void_p(a16 + 16), None, 0, None) == -8
+    assert lib.na2d_qk_bwd_rpb(ctypes.byref(good), ok, ctypes.c_void_p(a16 + 16), ctypes.c_void_p(a16 + 32), 8, None) == -8
+    assert lib.na2d_debug_indices(ctypes.byref(good), None, None, None) == -1
+    assert binding.strerror(-12345) == "unknown status"
+
+
+def test_workspace_sizes():
+    p = P(B=64, heads=2, H=56, W=56, k=7, dtype=1)
+    rpb = binding.na2d_workspace_bytes(p, binding.WS_QK_BWD_RPB)
+    full = binding.na2d_workspace_bytes(p, binding.WS_BWD)
+    assert rpb > 0 and rpb % 256 == 0
+    assert full >= rpb + 64 * 2 * 56 * 56 * 49 * 2
+    assert binding.na2d_workspace_bytes(P(k=4), binding.WS_BWD) == 0
+
+
+def nearest_window(i, L, k):
+    order = sorted(range(L), key=lambda j: abs(j - i))
+    return sorted(order[:k])
+
+
+@pytest.mark.parametrize("k", [3, 5, 7, 9, 11, 13])
+def test_axis_tables_match_brute_force(k):
+    for L in list(range(k, 30)) + [56, 57, 200, 334]:
+        start, qs, qe = binding.na2d_host_axis_tables(L, k)
+        windows = [nearest_window(i, L, k) for i in range(L)]
+        assert start.tolist() == [w[0] for w in windows]
+        for j in range(L):
+            seen_by = [i for i in range(L) if j in windows[i]]
+            # the inverse neighbourhood is contiguous and equals [qs, qe]
+            assert seen_by == list(range(qs[j], qe[j] + 1)), (L, k, j)
+            # k wide in the interior, k + (k-1)/2 next to one border, at most 2k-1 when the axis
+            # is so short that a key is near both borders
+            assert len(seen_by) <= (k + k // 2 if L >= 3 * k else 2 * k - 1)
+
+
+def test_axis_table_errors():
+    lib = binding.load()
+    assert lib.na2d_host_axis_tables(5, 7, None, None, None) == -4
+    assert lib.na2d_host_axis_tables(8, 4, None, None, None) == -3
+    assert lib.na2d_host_axis_tables(0, 3, None, None, None) == -6
+
+
+def test_binding_rejects_cpu_tensors():
+    x = torch.zeros(1, 1, 14, 14, 32)
+    with pytest.raises(ValueError):
+        binding.na2d_softmax(torch.zeros(1, 1, 14, 14, 9), 3, x, torch.zeros(1, 1, 14, 14, 9))
