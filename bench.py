@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the 2D Neighborhood Attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload nat_tiny_stage1] [--k 7]
+
+One "step" is one pass of the whole hot path over one batch of synthetic NAT-Tiny stage-1
+input (B=64, heads=2, 56x56, D=32, fp16, k=7 unless overridden), inputs resident in HBM:
+  forward, unfused : na2d_qk_rpb -> na2d_softmax -> na2d_av
+  forward, fused   : na2d_fused_fwd (with log-sum-exp)
+  backward         : na2d_bwd = grad-a, grad-v, softmax backward, grad-q, grad-k, grad-b
+`value` is the step's algorithmic HBM traffic divided by its wall time (GB/s); the per-call
+microseconds and per-kernel GB/s are in `kernels`.  Buffers rotate over several disjoint sets
+so that successive launches of one kernel do not find their operands in the 256 MB Infinity
+Cache.  Prints exactly one JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+METRIC = "2D NA fwd+bwd us/call and achieved HBM GB/s (% peak), NAT-Tiny shapes, k=7"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(p) -> dict:
+    """Bytes each call must move per launch: what the method itself reads and writes
+    (never the gathered-neighbourhood tensor it avoids)."""
+    e, D, kk, nq = p.elem_bytes, p.D, p.kk, p.n_queries
+    contraction = nq * (2 * D * e + kk * e)
+    return {
+        "qk_rpb": contraction, "softmax": nq * 2 * kk * e, "av": contraction,
+        "fused_fwd": nq * (4 * D * e + 4),
+        "av_bwd_p": contraction, "av_bwd_v": contraction, "softmax_bwd": nq * 3 * kk * e,
+        "qk_bwd_q": contraction, "qk_bwd_k": contraction, "qk_bwd_rpb": nq * kk * e,
+    }
+
+
+class BufferSet:
+    def __init__(self, p, host, na, synth, torch):
+        dev = lambda x: synth.to_device(x, p.dtype)
+        self.q, self.k, self.v, self.rpb, self.dout = (dev(host[n]) for n in ("q", "k", "v", "rpb", "dout"))
+        td = synth.TORCH_DTYPES[p.dtype]
+        attn_shape = (p.B, p.heads, p.H, p.W, p.kk)
+        self.logits = torch.empty(attn_shape, dtype=td, device="cuda")
+        self.attn = torch.empty(attn_shape, dtype=td, device="cuda")
+        self.dpds = torch.empty(attn_shape, dtype=td, device="cuda")
+        self.out, self.out_fused, self.dq, self.dk, self.dv = (torch.empty_like(self.q) for _ in range(5))
+        self.lse = torch.empty(self.q.shape[:4], dtype=torch.float32, device="cuda")
+        nb = 2 * p.k - 1
+        self.d_rpb = torch.empty((p.heads, nb, nb), dtype=torch.float32, device="cuda")
+        prob = na.problem(p.B, p.heads, p.H, p.W, p.D, p.k, td)
+        self.ws = torch.empty(na.na2d_workspace_bytes(prob, na.WS_BWD), dtype=torch.uint8, device="cuda")
+        self.ws_rpb = torch.empty(na.na2d_workspace_bytes(prob, na.WS_QK_BWD_RPB), dtype=torch.uint8, device="cuda")
+
+
+def make_calls(p, na, scale):
+    k = p.k
+    return {
+        "qk_rpb": lambda s: na.na2d_qk_rpb(s.q, s.k, s.rpb, scale, k, s.logits),
+        "softmax": lambda s: na.na2d_softmax(s.logits, k, s.q, s.attn),
+        "av": lambda s: na.na2d_av(s.attn, s.v, k, s.out),
+        "fused_fwd": lambda s: na.na2d_fused_fwd(s.q, s.k, s.v, s.rpb, scale, k, s.out_fused, s.lse),
+        "av_bwd_p": lambda s: na.na2d_av_bwd_p(s.dout, s.v, k, s.dpds),
+        "av_bwd_v": lambda s: na.na2d_av_bwd_v(s.attn, s.dout, k, s.dv),
+        "softmax_bwd": lambda s: na.na2d_softmax_bwd(s.attn, s.dpds, k, s.q, s.dpds),
+        "qk_bwd_q": lambda s: na.na2d_qk_bwd_q(s.dpds, s.k, scale, k, s.dq),
+        "qk_bwd_k": lambda s: na.na2d_qk_bwd_k(s.dpds, s.q, scale, k, s.dk),
+        "qk_bwd_rpb": lambda s: na.na2d_qk_bwd_rpb(s.dpds, k, s.q, s.d_rpb, s.ws_rpb),
+    }
+
+
+def step(s, calls, na, p, scale):
+    calls["qk_rpb"](s)
+    calls["softmax"](s)
+    calls["av"](s)
+    calls["fused_fwd"](s)
+    na.na2d_bwd(s.q, s.k, s.v, s.attn, s.dout, scale, p.k, s.dq, s.dk, s.dv, s.d_rpb, s.ws)
+
+
+def cpu_baseline(p, synth, budget_s: float = 20.0) -> dict:
+    """The oracle as it stands, timed on this machine's host cores over a bounded sample (a few
+    batch items of the same workload), reported in the metric's unit."""
+    import numpy as np
+    from oracle import na2d_oracle as o
+    o.build()
+    cores = o.num_threads()
+    scale = p.default_scale
+
+    def run(bs: int) -> float:
+        sp = synth.Problem(bs, p.heads, p.H, p.W, p.D, p.k, p.dtype)
+        h = {n: x.astype(np.float64) for n, x in synth.make_inputs(sp, 4242).items()}
+        t0 = time.perf_counter()
+        logits = o.qk_rpb(h["q"], h["k"], h["rpb"], scale, p.k)
+        attn = o.softmax(logits)
+        o.av(attn, h["v"], p.k)
+        o.fwd(h["q"], h["k"], h["v"], h["rpb"], scale, p.k)          # the fused forward's counterpart
+        dp = o.av_bwd_p(h["dout"], h["v"], p.k)
+        o.av_bwd_v(attn, h["dout"], p.k)
+        ds = o.softmax_bwd(attn, dp)
+        o.qk_bwd_q(ds, h["k"], scale, p.k)
+        o.qk_bwd_k(ds, h["q"], scale, p.k)
+        o.qk_bwd_rpb(ds, p.k)
+        return time.perf_counter() - t0
+
+    bs = 1
+    t = run(bs)
+    while t < budget_s / 4 and bs * 2 <= p.B:
+        bs *= 2
+        t = run(bs)
+    sp = synth.Problem(bs, p.heads, p.H, p.W, p.D, p.k, p.dtype)
+    nbytes = sum(algorithmic_bytes(sp).values())
+    return {"value": round(nbytes / t / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"one full step (same 10 calls) on batch {bs} of {p.B}, {t:.2f} s", "us_per_step_extrapolated":
+            round(t * p.B / bs * 1e6, 1)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="nat_tiny_stage1")
+    ap.add_argument("--k", type=int, default=None, help="override the kernel size (config 5 sweeps 3..13)")
+    ap.add_argument("--sets", type=int, default=3, help="disjoint buffer sets rotated between launches")
+    ap.add_argument("--kernel-iters", type=int, default=30)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives or sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2204_07143_amd import binding as na
+    from paper_2204_07143_amd import synth
+
+    na.load()  # raises if the HIP library is missing: there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    base = synth.CONFIGS[args.workload]
+    p = base if args.k is None else synth.Problem(base.B, base.heads, base.H, base.W, base.D, args.k, base.dtype)
+    scale = p.default_scale
+    host = synth.make_inputs(p, seed=1002)
+    sets = [BufferSet(p, host, na, synth, torch) for _ in range(args.sets)]
+    calls = make_calls(p, na, scale)
+    abytes = algorithmic_bytes(p)
+    step_bytes = sum(abytes.values())
+    log(f"workload {args.workload}: {p}  step = {step_bytes / 1e6:.1f} MB algorithmic, {args.sets} buffer sets")
+
+    stream = torch.cuda.current_stream()
+
+    def timed(fn, iters):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record(stream)
+        for i in range(iters):
+            fn(sets[i % len(sets)])
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / iters  # microseconds per iteration
+
+    # populate every set once (also the warm-up of every kernel), then W untimed steps
+    for s in sets:
+        step(s, calls, na, p, scale)
+    for i in range(args.warmup):
+        step(sets[i % len(sets)], calls, na, p, scale)
+    torch.cuda.synchronize()
+
+    # the timed region: exactly K steps
+    t0 = time.perf_counter()
+    us_step = timed(lambda s: step(s, calls, na, p, scale), args.steps)
+    wall = time.perf_counter() - t0
+    log(f"step: {us_step:.1f} us  ({step_bytes / us_step / 1e3:.1f} GB/s algorithmic; wall {wall:.2f} s for {args.steps} steps)")
+
+    # per-kernel: each call launched back to back over rotating buffer sets
+    kernels = {}
+    for name, fn in calls.items():
+        us = timed(fn, args.kernel_iters)
+        gbps = abytes[name] / us / 1e3
+        kernels[name] = {"us": round(us, 2), "GBps": round(gbps, 1), "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 1),
+                         "MB": round(abytes[name] / 1e6, 2)}
+        log(f"  {name:12s} {us:9.2f} us  {gbps:8.1f} GB/s  {100 * gbps / HBM_PEAK_GBPS:5.1f}% of 8 TB/s")
+    unfused_fwd = sum(kernels[n]["us"] for n in ("qk_rpb", "softmax", "av"))
+    bwd = sum(kernels[n]["us"] for n in ("av_bwd_p", "av_bwd_v", "softmax_bwd", "qk_bwd_q", "qk_bwd_k", "qk_bwd_rpb"))
+    log(f"  unfused fwd {unfused_fwd:.1f} us, fused fwd {kernels['fused_fwd']['us']:.1f} us, bwd {bwd:.1f} us")
+
+    dominant = max(kernels, key=lambda n: kernels[n]["us"])
+    achieved = kernels[dominant]["GBps"]
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "us_per_launch": kernels[dominant]["us"], "algorithmic_bytes_per_launch": abytes[dominant]}
+
+    result = {
+        "metric": METRIC, "value": round(step_bytes / us_step / 1e3, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us_step / 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": p.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload} (B={p.B}, heads={p.heads}, {p.H}x{p.W}, D={p.D}, k={p.k}, {p.dtype}): "
+                               "unfused fwd + fused fwd + bwd, one call each", "buffer_sets": args.sets},
+        "us_per_call": {"unfused_fwd": round(unfused_fwd, 1), "fused_fwd": kernels["fused_fwd"]["us"],
+                        "bwd": round(bwd, 1), "fwd_bwd_unfused": round(unfused_fwd + bwd, 1)},
+        "kernels": kernels, "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        log("timing the oracle on the host cores (bounded sample) ...")
+        result["cpu_baseline"] = cpu_baseline(p, synth)
+        log(f"  oracle: {result['cpu_baseline']}")
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
