@@ -3,136 +3,201 @@
 //   d_rpb[h, u, v] = sum over batch, queries n and slots (a, c) with
 //                    rpb_start(qy) + a = u and rpb_start(qx) + c = v of ds[n, a, c].
 //
-// Two-level reduction in a fixed order, no atomics:
-//   1. a workgroup owns up to kRpbSub chunks of consecutive queries of one plane; their ds rows
-//      are streamed through LDS with 16-byte loads; each wave walks its queries one at a time with
-//      lanes = window slots, so a query's K*K values land in K*K distinct table cells.
-//      Interior queries all map to the central K x K block and are accumulated in a register;
-//      border queries update the wave's private (2K-1)^2 LDS table.  The four wave tables are
-//      added in wave order and written to the workspace;
-//   2. a second kernel adds the workgroup partials of each head in index order.
+// Pure streaming of ds (HBM-bound), reduced in two levels in a fixed order, no atomics:
+//   1. Each wave owns whole "segments" (up to 64 consecutive queries of one image row, fewer for long rows), which it
+//      stages in its private LDS region with 16-byte loads.  Lanes are window slots, so one
+//      query's K*K values land in K*K distinct table cells.  All queries of a segment share the
+//      bias row offset; the interior run of a segment also shares the column offset and is
+//      summed in registers with independent loads; the few border queries update the wave's
+//      private (2K-1)^2 LDS table one query at a time.  The workgroup's wave tables are added
+//      in wave order and written to the workspace as one partial per workgroup;
+//   2. a second kernel adds the partials of each head: 16 waves each sum a strided subset in
+//      index order, then the 16 sub-sums are added in wave order.
 #include "na2d_kernels.hpp"
 #include "na2d_common.hpp"
 
 namespace na2d {
 
-constexpr int kRpbSub = 4;       // chunks per workgroup
 constexpr int kRpbWaves = 4;
-
-// Queries staged at once: a multiple of the wave width, at most 256, sized so that one chunk
-// of ds rows stays under 48 KB of LDS.
-__host__ __device__ constexpr int rpb_chunk(int kk, int elem_bytes) {
-    int q = (48 * 1024) / (kk * elem_bytes);
-    q = (q / kWave) * kWave;
-    return q < kWave ? kWave : (q > 256 ? 256 : q);
+// Queries per segment: at most one wave's worth, fewer when K*K rows are long, so that a
+// wave's staging region stays under 16 KB.
+__host__ __device__ constexpr int rpb_seg_q(int kk, int elem_bytes) {
+    const int q = (16 * 1024) / (kk * elem_bytes);
+    return q > 64 ? 64 : q;
 }
+constexpr int kRpbFinalWaves = 16;
 
 template <typename T, int K> struct RpbCfg {
     static constexpr int KK = K * K, NB = 2 * K - 1, CELLS = NB * NB;
-    static constexpr int kChunk = rpb_chunk(KK, (int)sizeof(T));
-    static constexpr int kQPerWave = kChunk / kRpbWaves;
-    static constexpr int kRegion = mirror_bytes(kChunk * KK * (int)sizeof(T));
-    static constexpr int kLdsBytes = kRegion + kRpbWaves * CELLS * 4;
+    static constexpr int kSegQ = rpb_seg_q(KK, (int)sizeof(T));
+    static constexpr int kRegion = mirror_bytes(kSegQ * KK * (int)sizeof(T));   // per wave
+    static constexpr int kTableBytes = ((CELLS * 4) + 15) & ~15;
+    static constexpr int kLdsBytes = kRpbWaves * (kRegion + kTableBytes);
     static constexpr int kSlotsPerLane = (KK + kWave - 1) / kWave;
 };
 
-static inline int rpb_groups_per_plane(int H, int W, int K, int elem_bytes) {
-    const int per_group = rpb_chunk(K * K, elem_bytes) * kRpbSub;
-    return (H * W + per_group - 1) / per_group;
+// Segments of one plane: rows x ceil(W / queries-per-segment).  Workgroups per plane are chosen so that the
+// launch has on the order of a thousand workgroups (partials) whatever the batch size.
+struct RpbSplit {
+    int segs_per_row, segs_per_plane, groups_per_plane, segs_per_group;
+};
+static inline RpbSplit rpb_split(int planes, int H, int W, int K, int elem_bytes) {
+    RpbSplit s;
+    const int seg_q = rpb_seg_q(K * K, elem_bytes);
+    s.segs_per_row = (W + seg_q - 1) / seg_q;
+    s.segs_per_plane = H * s.segs_per_row;
+    int groups = (1024 + planes - 1) / planes;
+    const int max_groups = (s.segs_per_plane + kRpbWaves - 1) / kRpbWaves;
+    if (groups > max_groups) groups = max_groups;
+    if (groups < 1) groups = 1;
+    s.segs_per_group = (s.segs_per_plane + groups - 1) / groups;
+    s.groups_per_plane = (s.segs_per_plane + s.segs_per_group - 1) / s.segs_per_group;
+    return s;
 }
 
 template <typename T, int K>
 __global__ __launch_bounds__(256) void rpb_partial_kernel(const T *__restrict__ ds, float *__restrict__ partial, int H,
-                                                          int W, int groups_per_plane) {
+                                                          int W, RpbSplit sp) {
     using C = RpbCfg<T, K>;
     extern __shared__ __align__(16) char lds[];
-    float *tables = reinterpret_cast<float *>(lds + C::kRegion);
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-    const int plane = blockIdx.x / groups_per_plane, group = blockIdx.x % groups_per_plane;
-    const int HW = H * W;
+    char *region = lds + wave * C::kRegion;
+    float *tables = reinterpret_cast<float *>(lds + kRpbWaves * C::kRegion);
+    float *mine = tables + wave * (C::kTableBytes / 4);
+    const int plane = blockIdx.x / sp.groups_per_plane, group = blockIdx.x % sp.groups_per_plane;
     constexpr int R = K / 2;
 
-    float *mine = tables + wave * C::CELLS;
     for (int i = lane; i < C::CELLS; i += kWave) mine[i] = 0.f;
 
     int cell_off[C::kSlotsPerLane];   // offset of this lane's slot inside the table, relative to (py, px)
-    float acc[C::kSlotsPerLane];
+    float acc_int[C::kSlotsPerLane];  // queries whose window is centred on both axes
 #pragma unroll
     for (int s = 0; s < C::kSlotsPerLane; ++s) {
         const int slot = lane + s * kWave;
         cell_off[s] = (slot / K) * C::NB + (slot % K);
-        acc[s] = 0.f;
+        acc_int[s] = 0.f;
     }
 
-    for (int sub = 0; sub < kRpbSub; ++sub) {
-        const int q0 = (group * kRpbSub + sub) * C::kChunk;
-        if (q0 >= HW) break;
-        const int nq = (HW - q0) < C::kChunk ? (HW - q0) : C::kChunk;
-        const size_t g0 = ((size_t)plane * HW + q0) * C::KK * sizeof(T);
-        __syncthreads();   // previous chunk fully consumed
-        stage_in<T>(reinterpret_cast<const char *>(ds), g0, nq * C::KK * (int)sizeof(T), lds, tid, 256);
-        __syncthreads();
-        const T *tile = reinterpret_cast<const T *>(lds + (int)(g0 & 15));
-        const int qend = (wave + 1) * C::kQPerWave < nq ? (wave + 1) * C::kQPerWave : nq;
-        for (int qi = wave * C::kQPerWave; qi < qend; ++qi) {
-            const int qlin = q0 + qi;
-            const int qy = qlin / W, qx = qlin - qy * W;
-            const int py = rpb_start(qy, H, K), px = rpb_start(qx, W, K);
-            const bool interior = (py == R) && (px == R);
-            const int base = py * C::NB + px;
+    const int seg_end = (group + 1) * sp.segs_per_group < sp.segs_per_plane ? (group + 1) * sp.segs_per_group
+                                                                            : sp.segs_per_plane;
+    for (int seg = group * sp.segs_per_group + wave; seg < seg_end; seg += kRpbWaves) {
+        const int qy = seg / sp.segs_per_row;
+        const int x0 = (seg - qy * sp.segs_per_row) * C::kSegQ;
+        const int x1 = x0 + C::kSegQ < W ? x0 + C::kSegQ : W;
+        const size_t g0 = (((size_t)plane * H + qy) * W + x0) * C::KK * sizeof(T);
+        stage_in<T>(reinterpret_cast<const char *>(ds), g0, (x1 - x0) * C::KK * (int)sizeof(T), region, lane, kWave);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const T *tile = reinterpret_cast<const T *>(region + (int)(g0 & 15));
+        const int py = rpb_start(qy, H, K);
+        // interior run of this segment: queries whose column offset is the centred one
+        const int xi0 = x0 > R ? x0 : R;
+        const int xi1 = x1 < W - R ? x1 : W - R;
+        float run[C::kSlotsPerLane];
+#pragma unroll
+        for (int s = 0; s < C::kSlotsPerLane; ++s) run[s] = 0.f;
+        if (xi1 > xi0) {
 #pragma unroll
             for (int s = 0; s < C::kSlotsPerLane; ++s) {
                 const int slot = lane + s * kWave;
                 if (slot < C::KK) {
-                    const float val = to_f32(tile[qi * C::KK + slot]);
-                    if (interior)
-                        acc[s] += val;
-                    else
-                        mine[base + cell_off[s]] += val;
+                    const T *col = tile + (xi0 - x0) * C::KK + slot;
+                    const int n = xi1 - xi0;
+                    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+                    int i = 0;
+                    for (; i + 4 <= n; i += 4) {
+                        a0 += to_f32(col[(i + 0) * C::KK]);
+                        a1 += to_f32(col[(i + 1) * C::KK]);
+                        a2 += to_f32(col[(i + 2) * C::KK]);
+                        a3 += to_f32(col[(i + 3) * C::KK]);
+                    }
+                    for (; i < n; ++i) a0 += to_f32(col[i * C::KK]);
+                    run[s] = (a0 + a1) + (a2 + a3);
                 }
+            }
+        }
+        if (py == R) {
+#pragma unroll
+            for (int s = 0; s < C::kSlotsPerLane; ++s) acc_int[s] += run[s];
+        } else if (xi1 > xi0) {
+#pragma unroll
+            for (int s = 0; s < C::kSlotsPerLane; ++s) {
+                const int slot = lane + s * kWave;
+                if (slot < C::KK) mine[py * C::NB + R + cell_off[s]] += run[s];
             }
             __builtin_amdgcn_wave_barrier();
         }
+        // border queries of the segment, one at a time (their cells overlap between queries)
+        for (int x = x0; x < x1; ++x) {
+            if (x >= xi0 && x < xi1) {
+                x = xi1 - 1;
+                continue;
+            }
+            const int base = py * C::NB + rpb_start(x, W, K);
+#pragma unroll
+            for (int s = 0; s < C::kSlotsPerLane; ++s) {
+                const int slot = lane + s * kWave;
+                if (slot < C::KK) mine[base + cell_off[s]] += to_f32(tile[(x - x0) * C::KK + slot]);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        __builtin_amdgcn_wave_barrier();   // region is reused by the next segment
     }
 #pragma unroll
     for (int s = 0; s < C::kSlotsPerLane; ++s) {
         const int slot = lane + s * kWave;
-        if (slot < C::KK) mine[R * C::NB + R + cell_off[s]] += acc[s];
+        if (slot < C::KK) mine[R * C::NB + R + cell_off[s]] += acc_int[s];
     }
     __syncthreads();
     for (int i = tid; i < C::CELLS; i += 256) {
         float s = tables[i];
 #pragma unroll
-        for (int w = 1; w < kRpbWaves; ++w) s += tables[w * C::CELLS + i];
+        for (int w = 1; w < kRpbWaves; ++w) s += tables[w * (C::kTableBytes / 4) + i];
         partial[(size_t)blockIdx.x * C::CELLS + i] = s;
     }
 }
 
-// d_rpb[h, cell] = sum over (batch, group) in index order of partial[(b * heads + h) * groups + group][cell]
-__global__ __launch_bounds__(256) void rpb_final_kernel(const float *__restrict__ partial, float *__restrict__ d_rpb,
-                                                        int B, int heads, int groups, int cells) {
-    const int cell = blockIdx.x * 256 + threadIdx.x;
-    const int h = blockIdx.y;
-    if (cell >= cells) return;
-    float lanes[4] = {0.f, 0.f, 0.f, 0.f};
-    int it = 0;
-    for (int b = 0; b < B; ++b)
-        for (int g = 0; g < groups; ++g, ++it)
-            lanes[it & 3] += partial[((size_t)(b * heads + h) * groups + g) * cells + cell];
-    d_rpb[(size_t)h * cells + cell] = (lanes[0] + lanes[1]) + (lanes[2] + lanes[3]);
+// d_rpb[h, cell] = sum over (batch, group) of partial[(b * heads + h) * groups + group][cell].
+// One workgroup of 16 waves per head: wave w adds the partials whose running index is w mod 16,
+// in index order; the 16 sub-sums are then added in wave order.
+__global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const float *__restrict__ partial,
+                                                                           float *__restrict__ d_rpb, int B, int heads,
+                                                                           int groups, int cells) {
+    extern __shared__ __align__(16) char lds[];
+    float *sub = reinterpret_cast<float *>(lds);   // [16][cells]
+    const int h = blockIdx.x;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int n = B * groups;
+    for (int cell = lane; cell < cells; cell += kWave) {
+        float acc = 0.f;
+#pragma unroll 4
+        for (int i = wave; i < n; i += kRpbFinalWaves) {
+            const int b = i / groups, g = i - b * groups;
+            acc += partial[((size_t)(b * heads + h) * groups + g) * cells + cell];
+        }
+        sub[wave * cells + cell] = acc;
+    }
+    __syncthreads();
+    for (int cell = threadIdx.x; cell < cells; cell += kRpbFinalWaves * kWave) {
+        float s = sub[cell];
+        for (int w = 1; w < kRpbFinalWaves; ++w) s += sub[w * cells + cell];
+        d_rpb[(size_t)h * cells + cell] = s;
+    }
 }
 
 size_t rpb_bwd_workspace_bytes(const Problem &p) {
     const int nb = 2 * p.K - 1;
-    return (size_t)p.planes() * rpb_groups_per_plane(p.H, p.W, p.K, p.elem_bytes()) * nb * nb * sizeof(float);
+    const RpbSplit sp = rpb_split(p.planes(), p.H, p.W, p.K, p.elem_bytes());
+    return (size_t)p.planes() * sp.groups_per_plane * nb * nb * sizeof(float);
 }
 
 template <typename T, int K>
 static hipError_t launch_rpb_bwd_t(const Problem &p, const void *ds, float *d_rpb, void *workspace, hipStream_t s) {
     using C = RpbCfg<T, K>;
-    const int groups = rpb_groups_per_plane(p.H, p.W, K, (int)sizeof(T));
+    const RpbSplit sp = rpb_split(p.planes(), p.H, p.W, K, (int)sizeof(T));
     auto kern = rpb_partial_kernel<T, K>;
-    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
+    static_assert(C::kLdsBytes <= 160 * 1024, "segments do not fit the 160 KB LDS of a CDNA4 compute unit");
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -140,12 +205,13 @@ static hipError_t launch_rpb_bwd_t(const Problem &p, const void *ds, float *d_rp
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(p.planes() * groups), dim3(256), C::kLdsBytes, s, static_cast<const T *>(ds),
-                       static_cast<float *>(workspace), p.H, p.W, groups);
+    hipLaunchKernelGGL(kern, dim3(p.planes() * sp.groups_per_plane), dim3(256), C::kLdsBytes, s,
+                       static_cast<const T *>(ds), static_cast<float *>(workspace), p.H, p.W, sp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(rpb_final_kernel, dim3((C::CELLS + 255) / 256, p.heads), dim3(256), 0, s,
-                       static_cast<const float *>(workspace), d_rpb, p.B, p.heads, groups, C::CELLS);
+    hipLaunchKernelGGL(rpb_final_kernel, dim3(p.heads), dim3(kRpbFinalWaves * kWave),
+                       kRpbFinalWaves * C::CELLS * sizeof(float), s, static_cast<const float *>(workspace), d_rpb, p.B,
+                       p.heads, sp.groups_per_plane, C::CELLS);
     return hipGetLastError();
 }
 
