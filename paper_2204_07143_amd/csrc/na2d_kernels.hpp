@@ -19,6 +19,11 @@ struct Problem {
 // logits = scale * <x, y_window> + bias   (QK+RPB, and grad-a with x = dout, y = v, no bias)
 hipError_t launch_qk(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
                      hipStream_t s);
+// the same contraction on the matrix cores (f16 / bf16 only)
+hipError_t launch_qk_mfma(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
+                          hipStream_t s);
+// Variant override for A/B timing: NA2D_VARIANT=valu forces the plain-ALU kernels.
+bool force_valu();
 // out = scale * sum_window w * y          (AV, and grad-q with w = ds, y = k)
 hipError_t launch_av(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);
 // out_j = scale * sum_{inverse neighbourhood} w[i, slot(i, j)] * x_i   (grad-v, grad-k)

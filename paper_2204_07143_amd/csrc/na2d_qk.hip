@@ -7,6 +7,9 @@
 // K x K window with packed dot products (v_dot2 for f16/bf16), and the tile's logits are
 // gathered in LDS so that they leave the chip as 16-byte coalesced stores (a query's K*K
 // logits are not a multiple of 16 bytes, so stores are issued per contiguous tile row).
+#include <stdlib.h>
+#include <string.h>
+
 #include "na2d_kernels.hpp"
 #include "na2d_tile.hpp"
 
@@ -119,8 +122,17 @@ static hipError_t launch_qk_t(const Problem &p, const void *x, const void *y, co
     return hipGetLastError();
 }
 
+bool force_valu() {
+    static const bool v = [] {
+        const char *e = getenv("NA2D_VARIANT");
+        return e != nullptr && strcmp(e, "valu") == 0;
+    }();
+    return v;
+}
+
 hipError_t launch_qk(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
                      hipStream_t s) {
+    if (p.dtype != NA2D_F32 && !force_valu()) return launch_qk_mfma(p, x, y, rpb, scale, logits, s);
     NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, return (launch_qk_t<T, K>(p, x, y, rpb, scale, logits, s))));
     return hipErrorInvalidValue;
 }

@@ -1,0 +1,221 @@
+// Neighbourhood logits on the matrix cores (f16 / bf16):
+//   logits[n, a, c] = scale * <x_n, y_{rho(n; a, c)}> + bias
+// (arXiv 2204.07143, Eq. 2; with x = dout, y = v and no bias it is grad-a, Appendix A).
+//
+// A workgroup walks a contiguous range of 16-wide x (4*WAVES)-high query tiles.  Per tile the
+// virtual key halo is staged once in LDS; each wave owns a strip of four 4 x 4 query patches.
+// Per patch: the queries are the B operand (one 16-byte global load per lane), each block of 16
+// halo keys is an A operand (one 16-byte LDS read per lane), one MFMA per block gives every
+// lane 4 dot products of "its" query.  Which of them fall inside the query's window, and where
+// they go in the k*k row, depends only on the lane and on how far the window is shifted at a
+// border; that is kept as a per-lane table of LDS addresses (entries outside the window point
+// at a dump slot), rebuilt only when the shift pattern changes.  So the steady state per result
+// is one fma (scale, bias), one convert and one 2-byte LDS store.  The strip's four row runs are
+// then streamed to global memory with 16-byte stores.
+#include "na2d_kernels.hpp"
+#include "na2d_mfma.hpp"
+#include "na2d_tile.hpp"
+
+namespace na2d {
+
+template <typename T, int K, int WAVES>
+struct QkMfmaCfg {
+    using P = Patch<K>;
+    static constexpr int TY = 4 * WAVES;
+    static constexpr int HALO_H = TY + K - 1, HALO_W = kTileX + K - 1;
+    static constexpr int KK = K * K, NB = 2 * K - 1;
+    static constexpr int kThreads = kWave * WAVES;
+    static constexpr int kHaloBytes = HALO_H * HALO_W * Traits<T>::kKeyStride;
+    static constexpr int kRowRegion = mirror_bytes(kTileX * KK * (int)sizeof(T));
+    static constexpr int kPatchStep = 4 * KK * (int)sizeof(T);   // staging distance between neighbouring patches
+    static constexpr int kDumpBytes = (32 + 3 * kPatchStep + 15) & ~15;
+    static constexpr int kWaveBytes = 4 * kRowRegion + kDumpBytes;
+    static constexpr int kLdsBytes = kHaloBytes + WAVES * kWaveBytes;
+};
+
+template <typename T, int K>
+constexpr int qk_mfma_waves() {
+    return QkMfmaCfg<T, K, 4>::kLdsBytes <= 80 * 1024 ? 4 : 2;
+}
+
+template <typename T, int K, int WAVES>
+__global__ __launch_bounds__(kWave *WAVES, 2) void qk_mfma_kernel(const T *__restrict__ x, const T *__restrict__ y,
+                                                                const T *__restrict__ rpb, float scale,
+                                                                T *__restrict__ logits, int H, int W, int heads,
+                                                                int tiles_x, int tiles_y, int ntiles,
+                                                                int tiles_per_wg) {
+    using C = QkMfmaCfg<T, K, WAVES>;
+    using P = Patch<K>;
+    constexpr int STRIDE = Traits<T>::kKeyStride;
+    extern __shared__ __align__(16) char lds[];
+
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
+    char *wreg = lds + C::kHaloBytes + wave * C::kWaveBytes;
+    const int wreg_off = C::kHaloBytes + wave * C::kWaveBytes;
+    // every lane's entries outside its window land here (plus the per-patch step)
+    const int dump_addr = wreg_off + 4 * C::kRowRegion + (lane & 7) * 2;
+
+    // A-operand offsets of this lane inside a patch halo (keys past the end re-read the last one)
+    int koff[P::NBLK];
+#pragma unroll
+    for (int b = 0; b < P::NBLK; ++b) {
+        int h = 16 * b + j;
+        h = h < P::NKEY ? h : P::NKEY - 1;
+        const int hy = P::row_of(h), hx = h - hy * P::PW;
+        koff[b] = (hy * C::HALO_W + hx) * STRIDE + g * 16;
+    }
+
+    float bias0[P::NEL];
+    int slotaddr[P::NEL];
+#pragma unroll
+    for (int e = 0; e < P::NEL; ++e) {
+        bias0[e] = 0.f;
+        slotaddr[e] = dump_addr;
+    }
+    // what the two per-lane tables were last built for
+    int cur_bias_key = -1, cur_wy = -100000, cur_wx = -100000, cur_base = 0;
+
+    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    const int t_end = (wg + 1) * tiles_per_wg < ntiles ? (wg + 1) * tiles_per_wg : ntiles;
+    for (int t = wg * tiles_per_wg; t < t_end; ++t) {
+        const TileCoord tc = decode_tile(t, tiles_x, tiles_y);
+        const int ty0 = tc.tiy * C::TY, tx0 = tc.tix * kTileX;
+        const size_t plane_q = (size_t)tc.plane * H * W;
+        const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);   // tile halo origin
+        __syncthreads();   // the previous tile's halo is no longer read
+        load_halo_virtual<T, C::HALO_H, C::HALO_W, false>(
+            reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes, H, W, hoy, hox, lds, tid, C::kThreads);
+        __syncthreads();
+
+        const int sy0 = ty0 + 4 * wave;   // first row of this wave's strip
+        if (sy0 >= H) continue;
+        const int head = tc.plane % heads;
+        const int oy = halo_origin(sy0, 4, H, K);   // patch halo origin (row)
+        const int dy = oy - (sy0 - P::R);           // 0 away from the borders
+        const int qy = sy0 + jy;
+        const bool row_ok = qy < H;
+        const size_t rowg0 = (plane_q + (size_t)qy * W + tx0) * C::KK * sizeof(T);
+        const int lanebase = wreg_off + jy * C::kRowRegion + (int)(rowg0 & 15) + jx * C::KK * (int)sizeof(T);
+        const int wy = row_ok ? win_start(qy, H, K) - oy : 100000;
+
+        u32x4 qreg[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int qx = tx0 + 4 * p + jx;
+            qreg[p] = u32x4{0u, 0u, 0u, 0u};
+            if (row_ok && qx < W)
+                qreg[p] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) +
+                                                           (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes + g * 16);
+        }
+
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int px0 = tx0 + 4 * p;
+            if (px0 < W) {
+                const int ox = halo_origin(px0, 4, W, K);
+                const int dx = ox - (px0 - P::R);
+                const int qx = px0 + jx;
+                const bool q_ok = row_ok && qx < W;
+                const int want_wy = q_ok ? wy : 100000;
+                const int want_wx = q_ok ? win_start(qx, W, K) - ox : 100000;
+                // bias of (query, key) depends on key - query only: a per-lane constant table, except
+                // that a pulled-back patch origin shifts it
+                const int bias_key = (head * 16 + dy + 8) * 16 + dx + 8;
+                if (bias_key != cur_bias_key) {
+                    cur_bias_key = bias_key;
+                    int gv = g;
+                    asm volatile("" : "+v"(gv));   // keep the index arithmetic inside this rare block
+#pragma unroll
+                    for (int e = 0; e < P::NEL; ++e) {
+                        const int h = 16 * (e >> 2) + 4 * gv + (e & 3);
+                        const int hy = P::row_of(h), hx = h - hy * P::PW;
+                        const int u = hy - jy + P::R + dy, v = hx - jx + P::R + dx;
+                        const bool ok = rpb != nullptr && h < P::NKEY && u >= 0 && u < C::NB && v >= 0 && v < C::NB;
+                        bias0[e] = ok ? to_f32(rpb[((size_t)head * C::NB + u) * C::NB + v]) : 0.f;
+                    }
+                }
+                if (__any(want_wy != cur_wy || want_wx != cur_wx || lanebase != cur_base)) {
+                    cur_wy = want_wy;
+                    cur_wx = want_wx;
+                    cur_base = lanebase;
+                    int gv = g;
+                    asm volatile("" : "+v"(gv));
+#pragma unroll
+                    for (int e = 0; e < P::NEL; ++e) {
+                        const int h = 16 * (e >> 2) + 4 * gv + (e & 3);
+                        const int hy = P::row_of(h), hx = h - hy * P::PW;
+                        const int a = hy - want_wy, c = hx - want_wx;
+                        const bool ok = h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)c < (unsigned)K;
+                        slotaddr[e] = ok ? lanebase + (a * K + c) * (int)sizeof(T) : dump_addr;
+                    }
+                }
+                const char *kp = lds + ((oy - hoy) * C::HALO_W + (ox - hox)) * STRIDE;
+                f32x4 acc[P::NBLK];
+#pragma unroll
+                for (int b = 0; b < P::NBLK; ++b) {
+                    const u32x4 a = *reinterpret_cast<const u32x4 *>(kp + koff[b]);
+                    acc[b] = mfma_16x16x32<T>(a, qreg[p], f32x4{0.f, 0.f, 0.f, 0.f});
+                }
+#pragma unroll
+                for (int e = 0; e < P::NEL; ++e) {
+                    const float v = __builtin_fmaf(scale, acc[e >> 2][e & 3], bias0[e]);
+                    *reinterpret_cast<T *>(lds + slotaddr[e] + p * C::kPatchStep) = from_f32<T>(v);
+                }
+            }
+        }
+        // this wave's four row runs are complete: stream them out (wave-private staging)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int nvalid = (W - tx0) < kTileX ? (W - tx0) : kTileX;
+#pragma unroll 1
+        for (int r = 0; r < 4; ++r) {
+            if (sy0 + r >= H) break;
+            const size_t g0r = (plane_q + (size_t)(sy0 + r) * W + tx0) * C::KK * sizeof(T);
+            stage_out<T>(reinterpret_cast<char *>(logits), g0r, nvalid * C::KK * (int)sizeof(T),
+                         wreg + r * C::kRowRegion, lane, kWave);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+template <typename T, int K>
+static hipError_t launch_qk_mfma_t(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
+                                   void *logits, hipStream_t s) {
+    constexpr int WAVES = qk_mfma_waves<T, K>();
+    using C = QkMfmaCfg<T, K, WAVES>;
+    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
+    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
+    const int ntiles = tiles_x * tiles_y * p.planes();
+    // persistent workgroups: a few per CU, each walking a contiguous range of tiles
+    const int max_wgs = 256 * 4;
+    const int tiles_per_wg = (ntiles + max_wgs - 1) / max_wgs;
+    const int nwg = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
+    auto kern = qk_mfma_kernel<T, K, WAVES>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
+                       static_cast<const T *>(x), static_cast<const T *>(y), static_cast<const T *>(rpb), scale,
+                       static_cast<T *>(logits), p.H, p.W, p.heads, tiles_x, tiles_y, ntiles, tiles_per_wg);
+    return hipGetLastError();
+}
+
+hipError_t launch_qk_mfma(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
+                          hipStream_t s) {
+    if (p.dtype == NA2D_F16) {
+        using T = f16_t;
+        NA2D_DISPATCH_K(p.K, return (launch_qk_mfma_t<T, K>(p, x, y, rpb, scale, logits, s)));
+    } else if (p.dtype == NA2D_BF16) {
+        using T = bf16_t;
+        NA2D_DISPATCH_K(p.K, return (launch_qk_mfma_t<T, K>(p, x, y, rpb, scale, logits, s)));
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace na2d
