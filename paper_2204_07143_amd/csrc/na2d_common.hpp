@@ -167,48 +167,107 @@ __device__ __forceinline__ void store_vec32(void *p, const float (&x)[kHeadDim])
     }
 }
 
+// ---- raw LDS addressing ----------------------------------------------------------------
+// 32-bit LDS byte address of a __shared__ object, and the reverse: lets kernels keep tables of
+// absolute LDS addresses in registers and store through them with plain ds_write instructions.
+typedef __attribute__((address_space(3))) char lds_char_t;
+__device__ __forceinline__ int lds_addr(const void *p) {
+    return (int)(uintptr_t)(const lds_char_t *)p;
+}
+template <typename T>
+__device__ __forceinline__ __attribute__((address_space(3))) T *lds_ptr(int addr) {
+    return (__attribute__((address_space(3))) T *)(uintptr_t)(unsigned)addr;
+}
+
 // ---- alignment-preserving staging between global memory and LDS -------------------------
 //
 // A run of `nbytes` bytes starting at global byte offset g0 of `gbase` (gbase 16-byte
 // aligned, g0 a multiple of sizeof(T)) is mirrored in an LDS region at offset (g0 & 15), so
 // that 16-byte aligned global chunks map to 16-byte aligned LDS chunks.  Chunks that lie
-// fully inside the run move as one 16-byte access; the ragged first and last chunks move
-// element by element.  The region needs (nbytes + 30) rounded up to 16 bytes.
+// fully inside the run move as one 16-byte access; the ragged head and tail (fewer than 16
+// bytes each) move element by element.  The region needs mirror_bytes(nbytes) bytes.
+//
+// All global loads of a stager are issued before the first LDS store, so a thread has its
+// whole share of the run in flight at once instead of paying one memory latency per chunk.
+// MAXBYTES bounds nbytes at compile time (it fixes the register footprint).
 
-template <typename T>
-__device__ __forceinline__ void stage_in(const char *gbase, size_t g0, int nbytes, char *region, int tid, int nthreads) {
-    const int mis = (int)(g0 & 15);
-    const char *ga = gbase + (g0 - mis);
-    const int span = mis + nbytes;
-    const int nchunks = (span + 15) >> 4;
-    for (int ci = tid; ci < nchunks; ci += nthreads) {
-        const int lo = ci << 4;
-        if (lo >= mis && lo + 16 <= span) {
-            *reinterpret_cast<u32x4 *>(region + lo) = *reinterpret_cast<const u32x4 *>(ga + lo);
-        } else {
-            const int b0 = lo > mis ? lo : mis, b1 = lo + 16 < span ? lo + 16 : span;
-            for (int b = b0; b < b1; b += (int)sizeof(T))
-                *reinterpret_cast<T *>(region + b) = *reinterpret_cast<const T *>(ga + b);
-        }
-    }
+struct RunSplit {
+    int mis, span, body_lo, body_hi;   // full 16-byte chunks cover [body_lo, body_hi)
+};
+__device__ __forceinline__ RunSplit split_run(size_t g0, int nbytes) {
+    RunSplit r;
+    r.mis = (int)(g0 & 15);
+    r.span = r.mis + nbytes;
+    r.body_lo = (r.mis + 15) & ~15;
+    r.body_hi = r.span & ~15;
+    if (r.body_hi < r.body_lo) r.body_hi = r.body_lo;   // no full chunk
+    return r;
 }
 
-template <typename T>
-__device__ __forceinline__ void stage_out(char *gbase, size_t g0, int nbytes, const char *region, int tid, int nthreads) {
-    const int mis = (int)(g0 & 15);
-    char *ga = gbase + (g0 - mis);
-    const int span = mis + nbytes;
-    const int nchunks = (span + 15) >> 4;
-    for (int ci = tid; ci < nchunks; ci += nthreads) {
-        const int lo = ci << 4;
-        if (lo >= mis && lo + 16 <= span) {
-            *reinterpret_cast<u32x4 *>(ga + lo) = *reinterpret_cast<const u32x4 *>(region + lo);
-        } else {
-            const int b0 = lo > mis ? lo : mis, b1 = lo + 16 < span ? lo + 16 : span;
-            for (int b = b0; b < b1; b += (int)sizeof(T))
-                *reinterpret_cast<T *>(ga + b) = *reinterpret_cast<const T *>(region + b);
+template <typename T, int MAXBYTES, int NTHREADS>
+struct StageIn {
+    static constexpr int kMaxChunks = (MAXBYTES + 15) / 16 + 1;
+    static constexpr int NITER = (kMaxChunks + NTHREADS - 1) / NTHREADS;
+    u32x4 v[NITER];
+    RunSplit rs;
+    const char *ga;
+
+    __device__ __forceinline__ void issue(const char *gbase, size_t g0, int nbytes, int tid) {
+        rs = split_run(g0, nbytes);
+        ga = gbase + (g0 - rs.mis);
+#pragma unroll
+        for (int it = 0; it < NITER; ++it) {
+            const int lo = rs.body_lo + ((tid + it * NTHREADS) << 4);
+            if (lo < rs.body_hi) v[it] = *reinterpret_cast<const u32x4 *>(ga + lo);
         }
     }
+    __device__ __forceinline__ void commit(char *region, int tid) const {
+#pragma unroll
+        for (int it = 0; it < NITER; ++it) {
+            const int lo = rs.body_lo + ((tid + it * NTHREADS) << 4);
+            if (lo < rs.body_hi) *reinterpret_cast<u32x4 *>(region + lo) = v[it];
+        }
+        // ragged head [mis, min(body_lo, span)) and tail [max(body_hi, body_lo) .. span): element-wise
+        const int head_end = rs.body_lo < rs.span ? rs.body_lo : rs.span;
+        const int hb = rs.mis + tid * (int)sizeof(T);
+        if (hb < head_end) *reinterpret_cast<T *>(region + hb) = *reinterpret_cast<const T *>(ga + hb);
+        const int tb = rs.body_hi + (tid - 16) * (int)sizeof(T);
+        if (tid >= 16 && rs.body_hi >= head_end && tb < rs.span)
+            *reinterpret_cast<T *>(region + tb) = *reinterpret_cast<const T *>(ga + tb);
+    }
+};
+
+// One-shot form (issue + commit).
+template <typename T, int MAXBYTES, int NTHREADS>
+__device__ __forceinline__ void stage_in(const char *gbase, size_t g0, int nbytes, char *region, int tid) {
+    StageIn<T, MAXBYTES, NTHREADS> st;
+    st.issue(gbase, g0, nbytes, tid);
+    st.commit(region, tid);
+}
+
+template <typename T, int MAXBYTES, int NTHREADS>
+__device__ __forceinline__ void stage_out(char *gbase, size_t g0, int nbytes, const char *region, int tid) {
+    constexpr int kMaxChunks = (MAXBYTES + 15) / 16 + 1;
+    constexpr int NITER = (kMaxChunks + NTHREADS - 1) / NTHREADS;
+    const RunSplit rs = split_run(g0, nbytes);
+    char *ga = gbase + (g0 - rs.mis);
+    u32x4 v[NITER];
+#pragma unroll
+    for (int it = 0; it < NITER; ++it) {
+        const int lo = rs.body_lo + ((tid + it * NTHREADS) << 4);
+        if (lo < rs.body_hi) v[it] = *reinterpret_cast<const u32x4 *>(region + lo);
+    }
+#pragma unroll
+    for (int it = 0; it < NITER; ++it) {
+        const int lo = rs.body_lo + ((tid + it * NTHREADS) << 4);
+        if (lo < rs.body_hi) *reinterpret_cast<u32x4 *>(ga + lo) = v[it];
+    }
+    const int head_end = rs.body_lo < rs.span ? rs.body_lo : rs.span;
+    const int hb = rs.mis + tid * (int)sizeof(T);
+    if (hb < head_end) *reinterpret_cast<T *>(ga + hb) = *reinterpret_cast<const T *>(region + hb);
+    const int tb = rs.body_hi + (tid - 16) * (int)sizeof(T);
+    if (tid >= 16 && rs.body_hi >= head_end && tb < rs.span)
+        *reinterpret_cast<T *>(ga + tb) = *reinterpret_cast<const T *>(region + tb);
 }
 
 // Bytes an LDS mirror region must have for a run of nbytes.

@@ -48,10 +48,10 @@ __global__ __launch_bounds__(kTileX *TY) void fused_fwd_kernel(const T *__restri
     const int hy0 = win_start(ty0, H, K), hx0 = win_start(tx0, W, K);
     const size_t plane_q = (size_t)tc.plane * H * W;
 
-    load_halo<T, C::HALO_H, C::HALO_W>(reinterpret_cast<const char *>(k) + plane_q * Traits<T>::kKeyBytes, H, W, hy0,
-                                       hx0, khalo, tid, C::kThreads);
-    load_halo<T, C::HALO_H, C::HALO_W>(reinterpret_cast<const char *>(v) + plane_q * Traits<T>::kKeyBytes, H, W, hy0,
-                                       hx0, vhalo, tid, C::kThreads);
+    load_halo<T, C::HALO_H, C::HALO_W, C::kThreads>(reinterpret_cast<const char *>(k) + plane_q * Traits<T>::kKeyBytes,
+                                                    H, W, hy0, hx0, khalo, tid);
+    load_halo<T, C::HALO_H, C::HALO_W, C::kThreads>(reinterpret_cast<const char *>(v) + plane_q * Traits<T>::kKeyBytes,
+                                                    H, W, hy0, hx0, vhalo, tid);
     {
         const int head = tc.plane % heads;
         for (int i = tid; i < C::NB * C::NB; i += C::kThreads)

@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kTileX *TY) void inverse_kernel(const T *__restrict
     const size_t plane_q = (size_t)tc.plane * H * W;
     const char *xplane = reinterpret_cast<const char *>(x) + plane_q * Traits<T>::kKeyBytes;
 
-    load_halo<T, C::RECT_H, C::RECT_W>(xplane, H, W, ry0, rx0, lds, tid, C::kThreads);
+    load_halo<T, C::RECT_H, C::RECT_W, C::kThreads>(xplane, H, W, ry0, rx0, lds, tid);
     __syncthreads();
 
     const int lx = tid % kTileX, ly = tid / kTileX;

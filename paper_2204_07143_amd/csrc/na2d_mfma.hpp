@@ -61,27 +61,4 @@ __host__ __device__ __forceinline__ int halo_origin(int q0, int n, int L, int K)
     return o > lo ? o : lo;
 }
 
-// Stage the keys of the virtual halo with origin (oy, ox) (may be negative / beyond the map)
-// into LDS with the padded per-key stride.  Positions outside the map are zero-filled when
-// ZERO is set and skipped otherwise.
-template <typename T, int ROWS, int COLS, bool ZERO>
-__device__ __forceinline__ void load_halo_virtual(const char *plane_base, int H, int W, int oy, int ox, char *lds,
-                                                  int tid, int nthreads) {
-    constexpr int CPK = Traits<T>::kKeyBytes / 16;
-    constexpr int STRIDE = Traits<T>::kKeyStride;
-    constexpr int TOTAL = ROWS * COLS * CPK;
-    for (int i = tid; i < TOTAL; i += nthreads) {
-        const int c = i % CPK;
-        const int rx = (i / CPK) % COLS;
-        const int ry = i / (CPK * COLS);
-        const int y = oy + ry, x = ox + rx;
-        if (y >= 0 && y < H && x >= 0 && x < W) {
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(plane_base + ((size_t)y * W + x) * Traits<T>::kKeyBytes + c * 16);
-            *reinterpret_cast<u32x4 *>(lds + (ry * COLS + rx) * STRIDE + c * 16) = v;
-        } else if (ZERO) {
-            *reinterpret_cast<u32x4 *>(lds + (ry * COLS + rx) * STRIDE + c * 16) = u32x4{0u, 0u, 0u, 0u};
-        }
-    }
-}
-
 }  // namespace na2d

@@ -54,8 +54,8 @@ __global__ __launch_bounds__(kTileX *TY) void qk_kernel(const T *__restrict__ x,
     const int hy0 = win_start(ty0, H, K), hx0 = win_start(tx0, W, K);
     const size_t plane_q = (size_t)tc.plane * H * W;
 
-    load_halo<T, C::HALO_H, C::HALO_W>(reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes, H, W, hy0,
-                                       hx0, halo, tid, C::kThreads);
+    load_halo<T, C::HALO_H, C::HALO_W, C::kThreads>(reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes,
+                                                    H, W, hy0, hx0, halo, tid);
     {
         const int head = tc.plane % heads;
         for (int i = tid; i < C::NB * C::NB; i += C::kThreads)
@@ -95,8 +95,8 @@ __global__ __launch_bounds__(kTileX *TY) void qk_kernel(const T *__restrict__ x,
     for (int r = wave; r < TY; r += kWaves) {
         if (ty0 + r >= H) break;
         const size_t g0r = (plane_q + (size_t)(ty0 + r) * W + tx0) * C::KK * sizeof(T);
-        stage_out<T>(reinterpret_cast<char *>(logits), g0r, nvalid * C::KK * (int)sizeof(T), rows + r * C::kRowRegion,
-                     lane, kWave < C::kThreads ? kWave : C::kThreads);
+        stage_out<T, kTileX * C::KK * (int)sizeof(T), kWave>(reinterpret_cast<char *>(logits), g0r,
+                                                             nvalid * C::KK * (int)sizeof(T), rows + r * C::kRowRegion, lane);
     }
 }
 

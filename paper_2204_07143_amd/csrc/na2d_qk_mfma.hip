@@ -2,16 +2,19 @@
 //   logits[n, a, c] = scale * <x_n, y_{rho(n; a, c)}> + bias
 // (arXiv 2204.07143, Eq. 2; with x = dout, y = v and no bias it is grad-a, Appendix A).
 //
-// A workgroup walks a contiguous range of 16-wide x (4*WAVES)-high query tiles.  Per tile the
-// virtual key halo is staged once in LDS; each wave owns a strip of four 4 x 4 query patches.
-// Per patch: the queries are the B operand (one 16-byte global load per lane), each block of 16
-// halo keys is an A operand (one 16-byte LDS read per lane), one MFMA per block gives every
-// lane 4 dot products of "its" query.  Which of them fall inside the query's window, and where
-// they go in the k*k row, depends only on the lane and on how far the window is shifted at a
-// border; that is kept as a per-lane table of LDS addresses (entries outside the window point
-// at a dump slot), rebuilt only when the shift pattern changes.  So the steady state per result
-// is one fma (scale, bias), one convert and one 2-byte LDS store.  The strip's four row runs are
-// then streamed to global memory with 16-byte stores.
+// A persistent workgroup walks a contiguous range of 16-wide x (4*WAVES)-high query tiles.
+// Per tile the key halo is staged once in LDS; each wave owns a strip of four 4 x 4 query
+// patches.  Per patch: the queries are the B operand (one 16-byte global load per lane), each
+// block of 16 halo keys is an A operand (one 16-byte LDS read per lane), one MFMA per block
+// gives every lane 4 dot products of "its" query.  Which of them fall inside the query's
+// window, and where they go in the k*k row, depends only on the lane and on how far the window
+// is shifted at a border; that is kept as a per-lane table of LDS addresses (entries outside
+// the window point at a dump slot), rebuilt only when the shift pattern changes.  So the steady
+// state per result is one fused multiply-add-convert (scale, bias) and one 2-byte LDS store.
+// The strip's four row runs are then streamed to global memory with 16-byte stores.
+//
+// The loop is software-pipelined: the next tile's halo and queries are loaded into registers
+// before the current tile is computed, so global-memory latency overlaps the matrix work.
 #include "na2d_kernels.hpp"
 #include "na2d_mfma.hpp"
 #include "na2d_tile.hpp"
@@ -26,11 +29,12 @@ struct QkMfmaCfg {
     static constexpr int KK = K * K, NB = 2 * K - 1;
     static constexpr int kThreads = kWave * WAVES;
     static constexpr int kHaloBytes = HALO_H * HALO_W * Traits<T>::kKeyStride;
+    static constexpr int kBiasBytes = ((NB * NB * 4) + 15) & ~15;
     static constexpr int kRowRegion = mirror_bytes(kTileX * KK * (int)sizeof(T));
     static constexpr int kPatchStep = 4 * KK * (int)sizeof(T);   // staging distance between neighbouring patches
-    static constexpr int kDumpBytes = (32 + 3 * kPatchStep + 15) & ~15;
+    static constexpr int kDumpBytes = (kWave * 4 + 3 * kPatchStep + 15) & ~15;
     static constexpr int kWaveBytes = 4 * kRowRegion + kDumpBytes;
-    static constexpr int kLdsBytes = kHaloBytes + WAVES * kWaveBytes;
+    static constexpr int kLdsBytes = kHaloBytes + kBiasBytes + WAVES * kWaveBytes;
 };
 
 template <typename T, int K>
@@ -38,23 +42,31 @@ constexpr int qk_mfma_waves() {
     return QkMfmaCfg<T, K, 4>::kLdsBytes <= 80 * 1024 ? 4 : 2;
 }
 
+struct QkTile {
+    int ty0, tx0, plane, hoy, hox;
+};
+
+// Two waves per SIMD for the four-wave tiles (two workgroups share a CU); the two-wave tiles of the
+// large windows keep more per-lane tables and get the whole register file instead of spilling.
 template <typename T, int K, int WAVES>
-__global__ __launch_bounds__(kWave *WAVES, 2) void qk_mfma_kernel(const T *__restrict__ x, const T *__restrict__ y,
-                                                                const T *__restrict__ rpb, float scale,
-                                                                T *__restrict__ logits, int H, int W, int heads,
-                                                                int tiles_x, int tiles_y, int ntiles,
-                                                                int tiles_per_wg) {
+__global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void qk_mfma_kernel(const T *__restrict__ x, const T *__restrict__ y,
+                                                                  const T *__restrict__ rpb, float scale,
+                                                                  T *__restrict__ logits, int H, int W, int heads,
+                                                                  int tiles_x, int tiles_y, int ntiles,
+                                                                  int tiles_per_wg) {
     using C = QkMfmaCfg<T, K, WAVES>;
     using P = Patch<K>;
     constexpr int STRIDE = Traits<T>::kKeyStride;
     extern __shared__ __align__(16) char lds[];
+    float *bias_lds = reinterpret_cast<float *>(lds + C::kHaloBytes);
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
-    char *wreg = lds + C::kHaloBytes + wave * C::kWaveBytes;
-    const int wreg_off = C::kHaloBytes + wave * C::kWaveBytes;
-    // every lane's entries outside its window land here (plus the per-patch step)
-    const int dump_addr = wreg_off + 4 * C::kRowRegion + (lane & 7) * 2;
+    // LDS addresses kept in tables are absolute, so stores through them need no base add
+    const int wreg_off = lds_addr(lds) + C::kHaloBytes + C::kBiasBytes + wave * C::kWaveBytes;
+    char *wreg = lds + C::kHaloBytes + C::kBiasBytes + wave * C::kWaveBytes;
+    // every lane's entries outside its window land here (plus the per-patch step): one bank per lane
+    const int dump_addr = wreg_off + 4 * C::kRowRegion + lane * 4;
 
     // A-operand offsets of this lane inside a patch halo (keys past the end re-read the last one)
     int koff[P::NBLK];
@@ -73,24 +85,95 @@ __global__ __launch_bounds__(kWave *WAVES, 2) void qk_mfma_kernel(const T *__res
         bias0[e] = 0.f;
         slotaddr[e] = dump_addr;
     }
-    // what the two per-lane tables were last built for
-    int cur_bias_key = -1, cur_wy = -100000, cur_wx = -100000, cur_base = 0;
+    // what the per-lane tables / the LDS bias table were last built for
+    int cur_bias_key = -1, cur_wy = -100000, cur_wx = -100000, cur_base = 0, lds_head = -1;
 
     const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    const int t_begin = wg * tiles_per_wg;
     const int t_end = (wg + 1) * tiles_per_wg < ntiles ? (wg + 1) * tiles_per_wg : ntiles;
-    for (int t = wg * tiles_per_wg; t < t_end; ++t) {
+    if (t_begin >= t_end) return;
+
+    auto tile_of = [&](int t) {
         const TileCoord tc = decode_tile(t, tiles_x, tiles_y);
-        const int ty0 = tc.tiy * C::TY, tx0 = tc.tix * kTileX;
-        const size_t plane_q = (size_t)tc.plane * H * W;
-        const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);   // tile halo origin
-        __syncthreads();   // the previous tile's halo is no longer read
-        load_halo_virtual<T, C::HALO_H, C::HALO_W, false>(
-            reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes, H, W, hoy, hox, lds, tid, C::kThreads);
+        QkTile q;
+        q.ty0 = tc.tiy * C::TY;
+        q.tx0 = tc.tix * kTileX;
+        q.plane = tc.plane;
+        q.hoy = halo_origin(q.ty0, C::TY, H, K);
+        q.hox = halo_origin(q.tx0, kTileX, W, K);
+        return q;
+    };
+
+    HaloPrefetch<T, C::HALO_H, C::HALO_W, C::kThreads> halo;
+    halo.init(W, tid);
+    u32x4 qnext[4];
+    auto prefetch = [&](const QkTile &tl) {
+        const size_t plane_q = (size_t)tl.plane * H * W;
+        halo.issue(reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes, H, W, tl.hoy, tl.hox);
+        const int qy = tl.ty0 + 4 * wave + jy;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int qx = tl.tx0 + 4 * p + jx;
+            qnext[p] = u32x4{0u, 0u, 0u, 0u};
+            if (qy < H && qx < W)
+                qnext[p] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) +
+                                                            (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes + g * 16);
+        }
+    };
+
+    // A strip's finished row runs leave for global memory one iteration late, right after the next
+    // tile's loads have been issued: stores and loads then both overlap the next tile's matrix work
+    // (stores and loads share one in-order completion counter on this architecture).
+    size_t out_plane_q = 0;
+    int out_sy0 = 0, out_tx0 = 0;
+    bool out_pending = false;
+    auto flush_strip = [&]() {
+        const int nvalid = (W - out_tx0) < kTileX ? (W - out_tx0) : kTileX;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if (out_sy0 + r < H) {
+                const size_t g0r = (out_plane_q + (size_t)(out_sy0 + r) * W + out_tx0) * C::KK * sizeof(T);
+                stage_out<T, kTileX * C::KK * (int)sizeof(T), kWave>(reinterpret_cast<char *>(logits), g0r,
+                                                                     nvalid * C::KK * (int)sizeof(T),
+                                                                     wreg + r * C::kRowRegion, lane);
+            }
+        }
+    };
+
+    QkTile cur = tile_of(t_begin);
+    prefetch(cur);
+
+    for (int t = t_begin; t < t_end; ++t) {
+        const int ty0 = cur.ty0, tx0 = cur.tx0, hoy = cur.hoy, hox = cur.hox;
+        const size_t plane_q = (size_t)cur.plane * H * W;
+        const int head = cur.plane % heads;
+        __syncthreads();   // the previous tile's halo (and bias table) is no longer read
+        halo.commit(lds);
+        if (head != lds_head) {
+            lds_head = head;
+            for (int i = tid; i < C::NB * C::NB; i += C::kThreads)
+                bias_lds[i] = rpb ? to_f32(rpb[(size_t)head * C::NB * C::NB + i]) : 0.f;
+            cur_bias_key = -1;
+        }
+        u32x4 qreg[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) qreg[p] = qnext[p];
         __syncthreads();
+        if (t + 1 < t_end) {
+            cur = tile_of(t + 1);
+            prefetch(cur);
+        }
+
+        if (out_pending) {
+            flush_strip();
+            out_pending = false;
+            // the staging reads above must stay ahead of this tile's staging writes
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
 
         const int sy0 = ty0 + 4 * wave;   // first row of this wave's strip
         if (sy0 >= H) continue;
-        const int head = tc.plane % heads;
         const int oy = halo_origin(sy0, 4, H, K);   // patch halo origin (row)
         const int dy = oy - (sy0 - P::R);           // 0 away from the borders
         const int qy = sy0 + jy;
@@ -98,16 +181,6 @@ __global__ __launch_bounds__(kWave *WAVES, 2) void qk_mfma_kernel(const T *__res
         const size_t rowg0 = (plane_q + (size_t)qy * W + tx0) * C::KK * sizeof(T);
         const int lanebase = wreg_off + jy * C::kRowRegion + (int)(rowg0 & 15) + jx * C::KK * (int)sizeof(T);
         const int wy = row_ok ? win_start(qy, H, K) - oy : 100000;
-
-        u32x4 qreg[4];
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int qx = tx0 + 4 * p + jx;
-            qreg[p] = u32x4{0u, 0u, 0u, 0u};
-            if (row_ok && qx < W)
-                qreg[p] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) +
-                                                           (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes + g * 16);
-        }
 
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
@@ -119,8 +192,8 @@ __global__ __launch_bounds__(kWave *WAVES, 2) void qk_mfma_kernel(const T *__res
                 const bool q_ok = row_ok && qx < W;
                 const int want_wy = q_ok ? wy : 100000;
                 const int want_wx = q_ok ? win_start(qx, W, K) - ox : 100000;
-                // bias of (query, key) depends on key - query only: a per-lane constant table, except
-                // that a pulled-back patch origin shifts it
+                // The bias of (query, key) depends on key - query only: a per-lane constant table,
+                // except that a displaced patch origin shifts it.
                 const int bias_key = (head * 16 + dy + 8) * 16 + dx + 8;
                 if (bias_key != cur_bias_key) {
                     cur_bias_key = bias_key;
@@ -130,9 +203,10 @@ __global__ __launch_bounds__(kWave *WAVES, 2) void qk_mfma_kernel(const T *__res
                     for (int e = 0; e < P::NEL; ++e) {
                         const int h = 16 * (e >> 2) + 4 * gv + (e & 3);
                         const int hy = P::row_of(h), hx = h - hy * P::PW;
-                        const int u = hy - jy + P::R + dy, v = hx - jx + P::R + dx;
-                        const bool ok = rpb != nullptr && h < P::NKEY && u >= 0 && u < C::NB && v >= 0 && v < C::NB;
-                        bias0[e] = ok ? to_f32(rpb[((size_t)head * C::NB + u) * C::NB + v]) : 0.f;
+                        int u = hy - jy + P::R + dy, v = hx - jx + P::R + dx;
+                        u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);   // cells outside the table belong to keys
+                        v = v < 0 ? 0 : (v > C::NB - 1 ? C::NB - 1 : v);   // outside every window: value unused
+                        bias0[e] = bias_lds[u * C::NB + v];
                     }
                 }
                 if (__any(want_wy != cur_wy || want_wx != cur_wx || lanebase != cur_base)) {
@@ -160,24 +234,21 @@ __global__ __launch_bounds__(kWave *WAVES, 2) void qk_mfma_kernel(const T *__res
 #pragma unroll
                 for (int e = 0; e < P::NEL; ++e) {
                     const float v = __builtin_fmaf(scale, acc[e >> 2][e & 3], bias0[e]);
-                    *reinterpret_cast<T *>(lds + slotaddr[e] + p * C::kPatchStep) = from_f32<T>(v);
+                    *lds_ptr<T>(slotaddr[e] + p * C::kPatchStep) = from_f32<T>(v);
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);   // keep the patches apart: interleaving them only costs registers
         }
-        // this wave's four row runs are complete: stream them out (wave-private staging)
+        // this wave's four row runs are complete (wave-private staging); they are flushed next iteration
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const int nvalid = (W - tx0) < kTileX ? (W - tx0) : kTileX;
-#pragma unroll 1
-        for (int r = 0; r < 4; ++r) {
-            if (sy0 + r >= H) break;
-            const size_t g0r = (plane_q + (size_t)(sy0 + r) * W + tx0) * C::KK * sizeof(T);
-            stage_out<T>(reinterpret_cast<char *>(logits), g0r, nvalid * C::KK * (int)sizeof(T),
-                         wreg + r * C::kRowRegion, lane, kWave);
-        }
-        __builtin_amdgcn_wave_barrier();
+        out_plane_q = plane_q;
+        out_sy0 = sy0;
+        out_tx0 = tx0;
+        out_pending = true;
     }
+    if (out_pending) flush_strip();
 }
 
 template <typename T, int K>
@@ -188,8 +259,8 @@ static hipError_t launch_qk_mfma_t(const Problem &p, const void *x, const void *
     static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const int ntiles = tiles_x * tiles_y * p.planes();
-    // persistent workgroups: a few per CU, each walking a contiguous range of tiles
-    const int max_wgs = 256 * 4;
+    // persistent workgroups: two per CU, each walking a contiguous range of tiles
+    const int max_wgs = 256 * 2;
     const int tiles_per_wg = (ntiles + max_wgs - 1) / max_wgs;
     const int nwg = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
     auto kern = qk_mfma_kernel<T, K, WAVES>;

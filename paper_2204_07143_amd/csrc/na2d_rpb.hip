@@ -85,7 +85,8 @@ __global__ __launch_bounds__(256) void rpb_partial_kernel(const T *__restrict__ 
         const int x0 = (seg - qy * sp.segs_per_row) * C::kSegQ;
         const int x1 = x0 + C::kSegQ < W ? x0 + C::kSegQ : W;
         const size_t g0 = (((size_t)plane * H + qy) * W + x0) * C::KK * sizeof(T);
-        stage_in<T>(reinterpret_cast<const char *>(ds), g0, (x1 - x0) * C::KK * (int)sizeof(T), region, lane, kWave);
+        stage_in<T, C::kSegQ * C::KK * (int)sizeof(T), kWave>(reinterpret_cast<const char *>(ds), g0,
+                                                              (x1 - x0) * C::KK * (int)sizeof(T), region, lane);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");

@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(const T *in, T *out, size_
     const int rows = (int)((nrows - row0) < (size_t)C::kRows ? (nrows - row0) : (size_t)C::kRows);
     const size_t g0 = row0 * C::KK * sizeof(T);
     const int nbytes = rows * C::KK * (int)sizeof(T);
-    stage_in<T>(reinterpret_cast<const char *>(in), g0, nbytes, lds, tid, C::kThreads);
+    stage_in<T, C::kRows * C::KK * (int)sizeof(T), C::kThreads>(reinterpret_cast<const char *>(in), g0, nbytes, lds, tid);
     __syncthreads();
     T *tile = reinterpret_cast<T *>(lds + (int)(g0 & 15));
     const int sub = tid % S::G;
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(const T *in, T *out, size_
         }
     }
     __syncthreads();
-    stage_out<T>(reinterpret_cast<char *>(out), g0, nbytes, lds, tid, C::kThreads);
+    stage_out<T, C::kRows * C::KK * (int)sizeof(T), C::kThreads>(reinterpret_cast<char *>(out), g0, nbytes, lds, tid);
 }
 
 template <typename T, int K>
@@ -89,8 +89,13 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(const T *attn, const T
     const int rows = (int)((nrows - row0) < (size_t)C::kRows ? (nrows - row0) : (size_t)C::kRows);
     const size_t g0 = row0 * C::KK * sizeof(T);
     const int nbytes = rows * C::KK * (int)sizeof(T);
-    stage_in<T>(reinterpret_cast<const char *>(attn), g0, nbytes, reg_p, tid, C::kThreads);
-    stage_in<T>(reinterpret_cast<const char *>(dp), g0, nbytes, reg_g, tid, C::kThreads);
+    {
+        StageIn<T, C::kRows * C::KK * (int)sizeof(T), C::kThreads> sp, sg;
+        sp.issue(reinterpret_cast<const char *>(attn), g0, nbytes, tid);
+        sg.issue(reinterpret_cast<const char *>(dp), g0, nbytes, tid);
+        sp.commit(reg_p, tid);
+        sg.commit(reg_g, tid);
+    }
     __syncthreads();
     const T *tp = reinterpret_cast<const T *>(reg_p + (int)(g0 & 15));
     T *tg = reinterpret_cast<T *>(reg_g + (int)(g0 & 15));
@@ -115,7 +120,7 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(const T *attn, const T
         }
     }
     __syncthreads();
-    stage_out<T>(reinterpret_cast<char *>(ds), g0, nbytes, reg_g, tid, C::kThreads);
+    stage_out<T, C::kRows * C::KK * (int)sizeof(T), C::kThreads>(reinterpret_cast<char *>(ds), g0, nbytes, reg_g, tid);
 }
 
 template <typename T, int K>
