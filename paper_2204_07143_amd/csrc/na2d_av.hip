@@ -106,6 +106,7 @@ static hipError_t launch_av_t(const Problem &p, const void *w, const void *y, fl
 }
 
 hipError_t launch_av(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s) {
+    if (p.dtype != NA2D_F32 && !force_valu()) return launch_av_mfma(p, w, y, scale, out, s);
     NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, return (launch_av_t<T, K>(p, w, y, scale, out, s))));
     return hipErrorInvalidValue;
 }

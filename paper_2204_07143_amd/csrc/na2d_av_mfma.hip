@@ -1,0 +1,258 @@
+// Neighbourhood weighted sum on the matrix cores (f16 / bf16):
+//   out[n, :] = scale * sum_{a, c} w[n, a, c] * y_{rho(n; a, c)}
+// (arXiv 2204.07143, Eq. 3-4; with w = ds, y = k it is grad-q, Appendix A).
+//
+// Same tiling as the matrix-core logits kernel: persistent workgroups walk 16 x (4*WAVES) query
+// tiles, a wave owns a strip of four 4 x 4 query patches, and a patch against its halo is a
+// dense contraction -- here over the halo positions:  out^T[d, q] = sum_pos Yt[d, pos] * P[pos, q].
+//   A operand: the values, staged transposed in LDS as Yt[channel][halo position] (8-byte reads
+//              of 4 consecutive positions; two 16-position blocks feed one 16x16x32 MFMA);
+//   B operand: the patch's weights spread over the halo positions, gathered from the tile's
+//              weight rows in LDS through a per-lane table of LDS addresses (positions outside a
+//              query's window read a zero word).  The table depends only on the lane and on the
+//              border shift of the window and is rebuilt only when that changes;
+//   result   : lane (query j, group g) holds channels 16*half + 4g .. +3 of its own query, so the
+//              scale and the 8-byte global stores need no cross-lane traffic.
+// The next tile's values and weight rows are prefetched into registers while the current tile is
+// computed.
+#include "na2d_kernels.hpp"
+#include "na2d_mfma.hpp"
+#include "na2d_tile.hpp"
+
+namespace na2d {
+
+template <typename T, int K, int WAVES>
+struct AvMfmaCfg {
+    using P = PatchT<K>;
+    static constexpr int TY = 4 * WAVES;
+    static constexpr int HALO_H = 4 * (WAVES - 1) + P::ROWS;   // farthest strip offset + rows the enumeration touches
+    static constexpr int HALO_W = 12 + P::PWP;                 // farthest patch offset + padded patch-halo width
+    static constexpr int KK = K * K;
+    static constexpr int kThreads = kWave * WAVES;
+    using Halo = TransposedHalo<T, HALO_H, HALO_W, kThreads>;
+    static constexpr int kRowBytes = kTileX * KK * (int)sizeof(T);
+    static constexpr int kRowRegion = mirror_bytes(kRowBytes);
+    static constexpr int kPatchStep = 4 * KK * (int)sizeof(T);
+    static constexpr int kZeroBytes = (3 * kPatchStep + 16 + 15) & ~15;   // what out-of-window table entries read
+    static constexpr int kWaveBytes = 4 * kRowRegion + kZeroBytes;
+    static constexpr int kLdsBytes = Halo::kBytes + WAVES * kWaveBytes;
+};
+
+template <typename T, int K>
+constexpr int av_mfma_waves() {
+    return AvMfmaCfg<T, K, 4>::kLdsBytes <= 80 * 1024 ? 4 : 2;
+}
+
+struct AvTile {
+    int ty0, tx0, plane, hoy, hox;
+};
+
+template <typename T, int K, int WAVES>
+__global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void av_mfma_kernel(const T *__restrict__ w,
+                                                                                    const T *__restrict__ y, float scale,
+                                                                                    T *__restrict__ out, int H, int W,
+                                                                                    int tiles_x, int tiles_y, int ntiles,
+                                                                                    int tiles_per_wg) {
+    using C = AvMfmaCfg<T, K, WAVES>;
+    using P = PatchT<K>;
+    using Halo = typename C::Halo;
+    constexpr int SZ = (int)sizeof(T);
+    extern __shared__ __align__(16) char lds[];
+
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
+    const int lds0 = lds_addr(lds);
+    const int wreg_off = lds0 + Halo::kBytes + wave * C::kWaveBytes;
+    char *wreg = lds + Halo::kBytes + wave * C::kWaveBytes;
+    const int zero_addr = wreg_off + 4 * C::kRowRegion;
+    for (int i = lane * 4; i < C::kZeroBytes; i += kWave * 4) *lds_ptr<uint32_t>(zero_addr + i) = 0u;
+
+    // A-operand addresses of this lane (channel j of a half, positions 16b + 4g .. +3), relative
+    // to the patch origin inside the tile halo
+    int vtoff[P::NBLK];
+#pragma unroll
+    for (int b = 0; b < P::NBLK; ++b) {
+        const int h0 = 16 * b + 4 * g;
+        const int hy = P::row_of(h0), hx0 = h0 - hy * P::PWP;
+        vtoff[b] = lds0 + j * Halo::DSTRIDE + (hy * C::HALO_W + hx0) * 2;
+    }
+    int gaddr[P::NEL];
+#pragma unroll
+    for (int e = 0; e < P::NEL; ++e) gaddr[e] = zero_addr;
+    int cur_wy = -100000, cur_wx = -100000, cur_base = 0;
+
+    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    const int t_begin = wg * tiles_per_wg;
+    const int t_end = (wg + 1) * tiles_per_wg < ntiles ? (wg + 1) * tiles_per_wg : ntiles;
+    if (t_begin >= t_end) return;
+
+    auto tile_of = [&](int t) {
+        const TileCoord tc = decode_tile(t, tiles_x, tiles_y);
+        AvTile q;
+        q.ty0 = tc.tiy * C::TY;
+        q.tx0 = tc.tix * kTileX;
+        q.plane = tc.plane;
+        q.hoy = halo_origin(q.ty0, C::TY, H, K);
+        q.hox = halo_origin(q.tx0, kTileX, W, K);
+        return q;
+    };
+
+    Halo halo;
+    halo.init(W, tid, lds0);
+    StageIn<T, C::kRowBytes, kWave> rows_in[4];
+    auto prefetch = [&](const AvTile &tl) {
+        const size_t plane_q = (size_t)tl.plane * H * W;
+        halo.issue(reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes, H, W, tl.hoy, tl.hox);
+        const int nvalid = (W - tl.tx0) < kTileX ? (W - tl.tx0) : kTileX;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int qy = tl.ty0 + 4 * wave + r;
+            const size_t g0r = (plane_q + (size_t)(qy < H ? qy : 0) * W + tl.tx0) * C::KK * SZ;
+            rows_in[r].issue(reinterpret_cast<const char *>(w), g0r, qy < H ? nvalid * C::KK * SZ : 0, lane);
+        }
+    };
+
+    AvTile cur = tile_of(t_begin);
+    prefetch(cur);
+
+    for (int t = t_begin; t < t_end; ++t) {
+        const int ty0 = cur.ty0, tx0 = cur.tx0, hoy = cur.hoy, hox = cur.hox;
+        const size_t plane_q = (size_t)cur.plane * H * W;
+        __syncthreads();   // every wave is done with the previous tile's values
+        halo.commit();
+#pragma unroll
+        for (int r = 0; r < 4; ++r) rows_in[r].commit(wreg + r * C::kRowRegion, lane);
+        __syncthreads();
+        if (t + 1 < t_end) {
+            cur = tile_of(t + 1);
+            prefetch(cur);
+        }
+
+        const int sy0 = ty0 + 4 * wave;
+        if (sy0 >= H) continue;
+        const int oy = halo_origin(sy0, 4, H, K);
+        const int qy = sy0 + jy;
+        const bool row_ok = qy < H;
+        const size_t rowg0 = (plane_q + (size_t)qy * W + tx0) * C::KK * SZ;
+        const int lanebase = wreg_off + jy * C::kRowRegion + (int)(rowg0 & 15) + jx * C::KK * SZ;
+        const int wy = row_ok ? win_start(qy, H, K) - oy : 100000;
+
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int px0 = tx0 + 4 * p;
+            if (px0 < W) {
+                const int ox = halo_origin(px0, 4, W, K);
+                const int qx = px0 + jx;
+                const bool q_ok = row_ok && qx < W;
+                const int want_wy = q_ok ? wy : 100000;
+                const int want_wx = q_ok ? win_start(qx, W, K) - ox : 100000;
+                if (__any(want_wy != cur_wy || want_wx != cur_wx || lanebase != cur_base)) {
+                    cur_wy = want_wy;
+                    cur_wx = want_wx;
+                    cur_base = lanebase;
+                    int gv = g;
+                    asm volatile("" : "+v"(gv));   // keep the index arithmetic inside this rare block
+#pragma unroll
+                    for (int e = 0; e < P::NEL; ++e) {
+                        const int h = 16 * (e >> 2) + 4 * gv + (e & 3);
+                        const int hy = P::row_of(h), hx = h - hy * P::PWP;
+                        const int a = hy - want_wy, c = hx - want_wx;
+                        const bool ok = (unsigned)a < (unsigned)K && (unsigned)c < (unsigned)K;
+                        gaddr[e] = ok ? lanebase + (a * K + c) * SZ : zero_addr;
+                    }
+                }
+                const int patch_off = ((oy - hoy) * C::HALO_W + (ox - hox)) * 2;
+                const bool aligned = (patch_off & 7) == 0;
+                f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+                for (int pb = 0; pb < P::NPAIR; ++pb) {
+                    // weights of this lane's query at positions 16b + 4g + r of the two blocks
+                    uint32_t wv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int e = 8 * pb + 2 * u;
+                        const uint32_t lo = *lds_ptr<uint16_t>(gaddr[e] + p * C::kPatchStep);
+                        const uint32_t hi = *lds_ptr<uint16_t>(gaddr[e + 1] + p * C::kPatchStep);
+                        wv[u] = lo | (hi << 16);
+                    }
+                    const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf) {
+                        const int a0 = vtoff[2 * pb] + patch_off + hf * 16 * Halo::DSTRIDE;
+                        const int a1 = vtoff[2 * pb + 1] + patch_off + hf * 16 * Halo::DSTRIDE;
+                        u32x4 aop;
+                        if (aligned) {
+                            const uint64_t lo = *lds_ptr<uint64_t>(a0);
+                            const uint64_t hi = *lds_ptr<uint64_t>(a1);
+                            aop = u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+                        } else {
+                            uint32_t q4[4];
+#pragma unroll
+                            for (int u = 0; u < 2; ++u) {
+                                q4[u] = (uint32_t)*lds_ptr<uint16_t>(a0 + 4 * u) | ((uint32_t)*lds_ptr<uint16_t>(a0 + 4 * u + 2) << 16);
+                                q4[2 + u] = (uint32_t)*lds_ptr<uint16_t>(a1 + 4 * u) | ((uint32_t)*lds_ptr<uint16_t>(a1 + 4 * u + 2) << 16);
+                            }
+                            aop = u32x4{q4[0], q4[1], q4[2], q4[3]};
+                        }
+                        acc[hf] = mfma_16x16x32<T>(aop, bop, acc[hf]);
+                    }
+                }
+                if (q_ok) {
+                    char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes + g * 8;
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf) {
+                        uint32_t o[2];
+#pragma unroll
+                        for (int u = 0; u < 2; ++u) {
+                            const T lo = from_f32<T>(acc[hf][2 * u] * scale), hi = from_f32<T>(acc[hf][2 * u + 1] * scale);
+                            o[u] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+                        }
+                        *reinterpret_cast<uint64_t *>(dst + hf * 32) = (uint64_t)o[0] | ((uint64_t)o[1] << 32);
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // the weight rows of this strip are consumed; the next commit may overwrite them
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+template <typename T, int K>
+static hipError_t launch_av_mfma_t(const Problem &p, const void *w, const void *y, float scale, void *out,
+                                   hipStream_t s) {
+    constexpr int WAVES = av_mfma_waves<T, K>();
+    using C = AvMfmaCfg<T, K, WAVES>;
+    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
+    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
+    const int ntiles = tiles_x * tiles_y * p.planes();
+    const int max_wgs = 256 * 2;
+    const int tiles_per_wg = (ntiles + max_wgs - 1) / max_wgs;
+    const int nwg = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
+    auto kern = av_mfma_kernel<T, K, WAVES>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
+                       static_cast<const T *>(w), static_cast<const T *>(y), scale, static_cast<T *>(out), p.H, p.W,
+                       tiles_x, tiles_y, ntiles, tiles_per_wg);
+    return hipGetLastError();
+}
+
+hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s) {
+    if (p.dtype == NA2D_F16) {
+        using T = f16_t;
+        NA2D_DISPATCH_K(p.K, return (launch_av_mfma_t<T, K>(p, w, y, scale, out, s)));
+    } else if (p.dtype == NA2D_BF16) {
+        using T = bf16_t;
+        NA2D_DISPATCH_K(p.K, return (launch_av_mfma_t<T, K>(p, w, y, scale, out, s)));
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace na2d

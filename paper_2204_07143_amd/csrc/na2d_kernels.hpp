@@ -26,6 +26,7 @@ hipError_t launch_qk_mfma(const Problem &p, const void *x, const void *y, const 
 bool force_valu();
 // out = scale * sum_window w * y          (AV, and grad-q with w = ds, y = k)
 hipError_t launch_av(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);
+hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);
 // out_j = scale * sum_{inverse neighbourhood} w[i, slot(i, j)] * x_i   (grad-v, grad-k)
 hipError_t launch_inverse(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
 hipError_t launch_softmax(const Problem &p, const void *logits, void *out, hipStream_t s);
