@@ -35,6 +35,8 @@ size_t rpb_bwd_workspace_bytes(const Problem &p);
 hipError_t launch_rpb_bwd(const Problem &p, const void *ds, float *d_rpb, void *workspace, hipStream_t s);
 hipError_t launch_fused_fwd(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
                             void *out, float *lse, hipStream_t s);
+hipError_t launch_fused_mfma(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
+                             void *out, float *lse, hipStream_t s);
 hipError_t launch_indices(const Problem &p, int32_t *key_index, int32_t *rpb_index, hipStream_t s);
 
 }  // namespace na2d

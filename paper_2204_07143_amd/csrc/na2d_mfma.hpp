@@ -89,7 +89,8 @@ template <int K> struct PatchT {
 // Transposed staging of a tile halo, split for software pipelining like HaloPrefetch: issue()
 // loads a thread's 16-byte chunks (8 channels of one position) into registers, zeros for
 // positions outside the map; commit() scatters each chunk into Xt[channel][position].
-template <typename T, int ROWS, int COLS, int NTHREADS>
+// COLS columns are staged per halo row; PITCH >= COLS is the row pitch of the LDS image.
+template <typename T, int ROWS, int COLS, int NTHREADS, int PITCH = COLS>
 struct TransposedHalo {
     static_assert(sizeof(T) == 2, "transposed staging is for the 16-bit types");
     static constexpr int CPK = Traits<T>::kKeyBytes / 16;
@@ -97,7 +98,7 @@ struct TransposedHalo {
     static constexpr int NITER = (TOTAL + NTHREADS - 1) / NTHREADS;
     // bytes per channel row: a multiple of 8 whose eighth is odd, so the 8-byte operand reads of
     // 16 consecutive channels fall in 16 distinct bank pairs
-    static constexpr int kRow8 = (ROWS * COLS * 2 + 7) / 8;
+    static constexpr int kRow8 = (ROWS * PITCH * 2 + 7) / 8;
     static constexpr int DSTRIDE = 8 * (kRow8 | 1);
     static constexpr int kBytes = kHeadDim * DSTRIDE;
     u32x4 v[NITER];
@@ -113,7 +114,7 @@ struct TransposedHalo {
             const int rx = (i / CPK) % COLS;
             const int ry = i / (CPK * COLS);
             goff[it] = (ry * W + rx) * Traits<T>::kKeyBytes + c * 16;
-            loff[it] = i < TOTAL ? lds_base + (8 * c) * DSTRIDE + (ry * COLS + rx) * 2 : -1;
+            loff[it] = i < TOTAL ? lds_base + (8 * c) * DSTRIDE + (ry * PITCH + rx) * 2 : -1;
             pos[it] = ry | (rx << 16);
         }
     }
@@ -125,6 +126,30 @@ struct TransposedHalo {
             v[it] = u32x4{0u, 0u, 0u, 0u};
             if (loff[it] >= 0 && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W)
                 v[it] = *reinterpret_cast<const u32x4 *>(plane_base + (origin_off + goff[it]));
+        }
+    }
+    // issue() with the global offsets / halo coordinates of another stager of the same shape (a
+    // row-major HaloPrefetch of the same tile moves exactly the same chunks): saves the registers
+    // of a second copy.  Use init_lds() instead of init() then.
+    __device__ __forceinline__ void init_lds(int tid, int lds_base) {
+#pragma unroll
+        for (int it = 0; it < NITER; ++it) {
+            const int i = tid + it * NTHREADS;
+            const int c = i % CPK;
+            const int rx = (i / CPK) % COLS;
+            const int ry = i / (CPK * COLS);
+            loff[it] = i < TOTAL ? lds_base + (8 * c) * DSTRIDE + (ry * PITCH + rx) * 2 : -1;
+        }
+    }
+    __device__ __forceinline__ void issue_like(const int (&goff_)[NITER], const int (&pos_)[NITER], const char *plane_base,
+                                               int H, int W, int oy, int ox) {
+        const int origin_off = (oy * W + ox) * Traits<T>::kKeyBytes;
+#pragma unroll
+        for (int it = 0; it < NITER; ++it) {
+            const int y = oy + (pos_[it] & 0xffff), x = ox + (pos_[it] >> 16);
+            v[it] = u32x4{0u, 0u, 0u, 0u};
+            if (loff[it] >= 0 && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W)
+                v[it] = *reinterpret_cast<const u32x4 *>(plane_base + (origin_off + goff_[it]));
         }
     }
     __device__ __forceinline__ void commit() const {

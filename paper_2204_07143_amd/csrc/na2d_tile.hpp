@@ -84,7 +84,9 @@ __device__ __forceinline__ void load_halo(const char *plane_base, int H, int W, 
 // before it computes the current tile, so the memory latency is hidden behind the compute.
 // Which halo positions a thread moves never changes, so their offsets are worked out once
 // (init) and each tile only adds its origin and checks the map bounds.
-template <typename T, int ROWS, int COLS, int NTHREADS>
+// COLS columns are staged per halo row; PITCH >= COLS is the row pitch of the LDS image (the
+// columns in between are never written by the stager).
+template <typename T, int ROWS, int COLS, int NTHREADS, int PITCH = COLS>
 struct HaloPrefetch {
     static constexpr int CPK = Traits<T>::kKeyBytes / 16;
     static constexpr int STRIDE = Traits<T>::kKeyStride;
@@ -103,7 +105,7 @@ struct HaloPrefetch {
             const int rx = (i / CPK) % COLS;
             const int ry = i / (CPK * COLS);
             goff[it] = (ry * W + rx) * Traits<T>::kKeyBytes + c * 16;
-            loff[it] = i < TOTAL ? (ry * COLS + rx) * STRIDE + c * 16 : -1;
+            loff[it] = i < TOTAL ? (ry * PITCH + rx) * STRIDE + c * 16 : -1;
             pos[it] = ry | (rx << 16);
         }
     }
