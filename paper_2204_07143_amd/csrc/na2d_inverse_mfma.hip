@@ -1,0 +1,354 @@
+// Gradients that sum over queries, on the matrix cores (f16 / bf16, K <= 7):
+//   out_j = scale * sum over queries i whose window holds j of w[i, slot(i, j)] * x_i
+// (grad-v with w = attention weights, x = dout; grad-k with w = ds, x = q; arXiv 2204.07143,
+// Appendix A).  Gathered per key over its inverse neighbourhood: no atomics, fixed order.
+//
+// A workgroup owns a 16 x (4*WAVES) key tile.  The queries that see any of its keys form a
+// rectangle of at most (TY + K-1 + R) x (16 + K-1 + R) positions (R = (K-1)/2; the + R only
+// matters next to a border, where clamped queries reach further).  Per tile the rectangle's
+// x vectors are staged transposed in LDS (Xt[channel][query position]) and its weight rows are
+// copied to LDS as they are.  A wave owns a strip of four 4 x 4 key patches; for one patch
+//   out^T[d, key] = sum_pos Xt[d, pos] * Wg[pos, key]
+// runs over the (K+R+3)-row query halo of the patch, one halo row (16 positions) per MFMA block:
+//   A operand: Xt, 8-byte LDS reads (4 consecutive query positions of one channel);
+//   B operand: the weights w[query pos][slot of this lane's key], 2-byte LDS gathers whose
+//              address is the sum of a per-lane row term (depends on the halo row and the lane's
+//              key row) and a per-lane column term (depends on the 4 halo columns of the lane and
+//              its key column); invalid combinations read a zero word.  Row terms are rebuilt when
+//              the strip's rows change class, column terms per patch (4 values);
+//   halo rows that no key of the patch is seen from are skipped (wave-uniform mask).
+// Each lane ends up with 8 channels of its own key: scale, convert, two 8-byte global stores.
+#include "na2d_kernels.hpp"
+#include "na2d_mfma.hpp"
+#include "na2d_tile.hpp"
+
+namespace na2d {
+
+template <typename T, int K, int WAVES>
+struct InvMfmaCfg {
+    static constexpr int R = K / 2;
+    static constexpr int PWI = K + R + 3;          // query-halo side of a 4 x 4 key patch
+    static_assert(PWI <= 16, "one MFMA block per query-halo row needs K + R + 3 <= 16");
+    static constexpr int NBLK = PWI + (PWI & 1);   // halo rows, padded to whole pairs
+    static constexpr int NPAIR = NBLK / 2;
+    static constexpr int TY = 4 * WAVES;
+    static constexpr int RH = 4 * (WAVES - 1) + NBLK;   // rows of the tile's query rectangle held in LDS
+    static constexpr int RW = kTileX + K - 1 + R;       // columns that hold data
+    static constexpr int PITCH = 12 + 16;               // farthest patch offset + block width
+    static constexpr int KK = K * K;
+    static constexpr int kThreads = kWave * WAVES;
+    using XHalo = TransposedHalo<T, RH, RW, kThreads, PITCH>;
+    static constexpr int kRowBytes = RW * KK * (int)sizeof(T);
+    static constexpr int kRowRegion = mirror_bytes(kRowBytes);
+    static constexpr int kWBytes = RH * kRowRegion;
+    static constexpr int kLdsBytes = XHalo::kBytes + kWBytes + 16;   // + the zero word
+    // chunk grid of the weight-row copy
+    static constexpr int kRowChunks = kRowRegion / 16;
+    static constexpr int kCopyIters = (RH * kRowChunks + kThreads - 1) / kThreads;
+};
+
+template <typename T, int K>
+constexpr int inv_mfma_waves() {
+    return InvMfmaCfg<T, K, 4>::kLdsBytes <= 80 * 1024 ? 4 : 2;
+}
+
+template <typename T, int K, int WAVES>
+__global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
+                                                                       float scale, T *__restrict__ out, int H, int W,
+                                                                       int tiles_x, int tiles_y, int ntiles,
+                                                                       int tiles_per_wg) {
+    using C = InvMfmaCfg<T, K, WAVES>;
+    using XHalo = typename C::XHalo;
+    constexpr int SZ = (int)sizeof(T);
+    constexpr int BIG = 1 << 24;   // invalid row / column terms push the sum past the zero word
+    extern __shared__ __align__(16) char lds[];
+
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int n = lane & 15, g = lane >> 4, ky = n >> 2, kx = n & 3;
+    const int lds0 = lds_addr(lds);
+    const int w0 = lds0 + XHalo::kBytes;              // weight rows
+    const int zero_addr = w0 + C::kWBytes;            // a zero word above every valid gather address
+    char *w_lds = lds + XHalo::kBytes;
+
+    // Everything the stagers do not write must hold finite numbers (it meets zero weights only).
+    for (int i = tid * 16; i < C::kLdsBytes; i += C::kThreads * 16) *lds_ptr<u32x4>(lds0 + i) = u32x4{0u, 0u, 0u, 0u};
+    __syncthreads();
+
+    // lane-constant part of the A-operand address: channel n of a half, positions 4g .. 4g+3 of a block
+    const int xt_lane = lds0 + n * XHalo::DSTRIDE + 4 * g * 2;
+
+    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    const int t_begin = wg * tiles_per_wg;
+    const int t_end = (wg + 1) * tiles_per_wg < ntiles ? (wg + 1) * tiles_per_wg : ntiles;
+
+    int rowterm[C::NBLK];
+    unsigned row_mask = 0;
+    int cur_rowkey = -1;
+
+    for (int t = t_begin; t < t_end; ++t) {
+        const TileCoord tc = decode_tile(t, tiles_x, tiles_y);
+        const int ty0 = tc.tiy * C::TY, tx0 = tc.tix * kTileX;
+        const size_t plane_q = (size_t)tc.plane * H * W;
+        const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
+        const int tx1 = tx0 + kTileX - 1 < W - 1 ? tx0 + kTileX - 1 : W - 1;
+        const int ry0 = inv_first(ty0, H, K), ry1 = inv_last(ty1, H, K);
+        const int rx0 = inv_first(tx0, W, K), rx1 = inv_last(tx1, W, K);
+        const int nrows = ry1 - ry0 + 1, ncols = rx1 - rx0 + 1;   // <= RH, <= RW
+
+        __syncthreads();   // the previous tile's LDS images are no longer read
+        // Stage the rectangle: every global load of the thread is issued before the first LDS store,
+        // so the tile pays one memory latency.  Indices advance incrementally (no divisions, and no
+        // offset tables held across the compute phase).
+        {
+            constexpr int CPK = Traits<T>::kKeyBytes / 16;          // 16-byte chunks per vector (4)
+            constexpr int NX = XHalo::NITER;                          // x chunks per thread
+            constexpr int NW = C::kCopyIters;                         // weight-row chunks per thread
+            constexpr int KSTEP = C::kThreads / CPK;                  // keys a thread advances per iteration
+            static_assert(C::kThreads % CPK == 0, "thread count must be a multiple of the chunks per vector");
+            const char *xbase = reinterpret_cast<const char *>(x) + plane_q * Traits<T>::kKeyBytes;
+            const char *wbase = reinterpret_cast<const char *>(w);
+            const int nbytes = ncols * C::KK * SZ;
+            const size_t g0first = (plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ;
+            const int row_pitch_bytes = W * C::KK * SZ;   // < 2^31: checked by the host
+            const int mis0 = (int)(g0first & 15);
+            const char *wfirst = wbase + g0first;         // first byte of the rectangle's first weight row
+            u32x4 xv[NX], wv[NW];
+            const int c = tid % CPK;
+            {
+                int key = tid / CPK;
+                int ry = key / C::RW, rx = key - ry * C::RW;
+#pragma unroll
+                for (int it = 0; it < NX; ++it) {
+                    const int y = ry0 + ry, xq = rx0 + rx;
+                    xv[it] = u32x4{0u, 0u, 0u, 0u};
+                    if (ry < C::RH && y < H && xq < W)
+                        xv[it] = *reinterpret_cast<const u32x4 *>(xbase + ((y * W + xq) * Traits<T>::kKeyBytes + c * 16));
+                    rx += KSTEP % C::RW;
+                    ry += KSTEP / C::RW;
+                    if (rx >= C::RW) {
+                        rx -= C::RW;
+                        ry += 1;
+                    }
+                }
+            }
+            {
+                int r = tid / C::kRowChunks, ci = tid - r * C::kRowChunks;
+#pragma unroll
+                for (int it = 0; it < NW; ++it) {
+                    wv[it] = u32x4{0u, 0u, 0u, 0u};
+                    if (r < nrows) {
+                        // row r starts r * pitch bytes after the first row; its 16-byte phase follows
+                        const int rel = r * row_pitch_bytes;
+                        const int mis = (mis0 + rel) & 15;
+                        const int body_lo = (mis + 15) & ~15, body_hi = (mis + nbytes) & ~15;
+                        const int lo = ci << 4;
+                        if (lo >= body_lo && lo < body_hi)
+                            wv[it] = *reinterpret_cast<const u32x4 *>(wfirst + (rel - mis + lo));
+                    }
+                    ci += C::kThreads % C::kRowChunks;
+                    r += C::kThreads / C::kRowChunks;
+                    if (ci >= C::kRowChunks) {
+                        ci -= C::kRowChunks;
+                        r += 1;
+                    }
+                }
+            }
+            // ragged head and tail of every weight row, element by element: wave `r mod WAVES` takes row r
+            for (int r = wave; r < nrows; r += WAVES) {
+                const size_t g0 = g0first + (size_t)r * row_pitch_bytes;
+                const RunSplit rs = split_run(g0, nbytes);
+                const char *ga = wbase + (g0 - rs.mis);
+                char *region = w_lds + r * C::kRowRegion;
+                const int head_end = rs.body_lo < rs.span ? rs.body_lo : rs.span;
+                const int hb = rs.mis + lane * SZ;
+                if (hb < head_end) *reinterpret_cast<T *>(region + hb) = *reinterpret_cast<const T *>(ga + hb);
+                const int tb = rs.body_hi + (lane - 16) * SZ;
+                if (lane >= 16 && tb < rs.span) *reinterpret_cast<T *>(region + tb) = *reinterpret_cast<const T *>(ga + tb);
+            }
+            {
+                int key = tid / CPK;
+                int ry = key / C::RW, rx = key - ry * C::RW;
+#pragma unroll
+                for (int it = 0; it < NX; ++it) {
+                    if (ry < C::RH) {
+                        const int base = lds0 + (8 * c) * XHalo::DSTRIDE + (ry * C::PITCH + rx) * 2;
+                        const uint32_t wd[4] = {xv[it].x, xv[it].y, xv[it].z, xv[it].w};
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            *lds_ptr<uint16_t>(base + (2 * u) * XHalo::DSTRIDE) = (uint16_t)(wd[u] & 0xffffu);
+                            *lds_ptr<uint16_t>(base + (2 * u + 1) * XHalo::DSTRIDE) = (uint16_t)(wd[u] >> 16);
+                        }
+                    }
+                    rx += KSTEP % C::RW;
+                    ry += KSTEP / C::RW;
+                    if (rx >= C::RW) {
+                        rx -= C::RW;
+                        ry += 1;
+                    }
+                }
+            }
+            {
+                int r = tid / C::kRowChunks, ci = tid - r * C::kRowChunks;
+#pragma unroll
+                for (int it = 0; it < NW; ++it) {
+                    if (r < nrows) {
+                        const int mis = (mis0 + r * row_pitch_bytes) & 15;
+                        const int body_lo = (mis + 15) & ~15, body_hi = (mis + nbytes) & ~15;
+                        const int lo = ci << 4;
+                        if (lo >= body_lo && lo < body_hi) *lds_ptr<u32x4>(w0 + r * C::kRowRegion + lo) = wv[it];
+                    }
+                    ci += C::kThreads % C::kRowChunks;
+                    r += C::kThreads / C::kRowChunks;
+                    if (ci >= C::kRowChunks) {
+                        ci -= C::kRowChunks;
+                        r += 1;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+
+        const int sy0 = ty0 + 4 * wave;   // first key row of this wave's strip
+        if (sy0 >= H) continue;
+        const int jy = sy0 + ky;
+        const int oqy = inv_first(sy0, H, K);   // first query row of the strip's halo
+        // row terms: halo row b holds query row iy = oqy + b; this lane's key row jy sits in its window at a
+        {
+            const size_t g0first = (plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ;
+            // the terms depend on the strip's rows (one strip position per wave and tile row) and on the
+            // 16-byte phase of the rectangle's first weight row
+            const int rowkey = (sy0 << 4) | (int)(g0first & 15);
+            if (rowkey != cur_rowkey) {
+                cur_rowkey = rowkey;
+                row_mask = 0;
+#pragma unroll
+                for (int b = 0; b < C::NBLK; ++b) {
+                    const int iy = oqy + b;
+                    const int a = jy - win_start(iy < H ? iy : H - 1, H, K);
+                    const bool ok = b < C::PWI && iy <= ry1 && jy < H && (unsigned)a < (unsigned)K;
+                    const size_t g0 = (plane_q + (size_t)iy * W + rx0) * C::KK * SZ;
+                    rowterm[b] = ok ? w0 + (iy - ry0) * C::kRowRegion + (int)(g0 & 15) + a * K * SZ : BIG;
+                    row_mask |= __any(ok) ? (1u << b) : 0u;
+                }
+            }
+        }
+        // The four patches of the strip share the halo rows, so they advance together through the row
+        // pairs: four independent gather / MFMA chains per step hide the LDS latency of each other.
+        int colterm[4][4];
+        int xpatch[4];
+        f32x4 acc[4][2];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int px0 = tx0 + 4 * p;
+            const int jx = px0 + kx;
+            // Halo columns start at the first query column that sees the patch, moved left to a multiple
+            // of 4 inside the rectangle so that the 8-byte operand reads stay aligned; the 16-wide block
+            // still reaches the last such column (at most K + R + 3 <= 13 of them).
+            const int oq = inv_first(px0 < W ? px0 : W - 1, W, K);
+            const int oqx = rx0 + ((oq - rx0) & ~3);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int ix = oqx + 4 * g + r;
+                const int c = jx - win_start(ix < W ? ix : W - 1, W, K);
+                const bool ok = px0 < W && ix <= rx1 && jx < W && (unsigned)c < (unsigned)K;
+                colterm[p][r] = ok ? (ix - rx0) * C::KK * SZ + c * SZ : BIG;
+            }
+            xpatch[p] = ((oqy - ry0) * C::PITCH + (oqx - rx0)) * 2;
+            acc[p][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+            acc[p][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int pb = 0; pb < C::NPAIR; ++pb) {
+            if ((row_mask >> (2 * pb)) & 3u) {
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    uint32_t wv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int b = 2 * pb + (u >> 1);
+                        const int r0 = (u & 1) * 2;
+                        int a_lo = rowterm[b] + colterm[p][r0], a_hi = rowterm[b] + colterm[p][r0 + 1];
+                        a_lo = a_lo < zero_addr ? a_lo : zero_addr;
+                        a_hi = a_hi < zero_addr ? a_hi : zero_addr;
+                        wv[u] = (uint32_t)*lds_ptr<uint16_t>(a_lo) | ((uint32_t)*lds_ptr<uint16_t>(a_hi) << 16);
+                    }
+                    const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf) {
+                        const int a0 = xt_lane + xpatch[p] + (2 * pb) * C::PITCH * 2 + hf * 16 * XHalo::DSTRIDE;
+                        const uint64_t lo = *lds_ptr<uint64_t>(a0);
+                        const uint64_t hi = *lds_ptr<uint64_t>(a0 + C::PITCH * 2);
+                        const u32x4 aop = u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+                        acc[p][hf] = mfma_16x16x32<T>(aop, bop, acc[p][hf]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int jx = tx0 + 4 * p + kx;
+            if (jy < H && jx < W) {
+                char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * Traits<T>::kKeyBytes + g * 8;
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf) {
+                    uint32_t o[2];
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const T lo = from_f32<T>(acc[p][hf][2 * u] * scale), hi = from_f32<T>(acc[p][hf][2 * u + 1] * scale);
+                        o[u] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+                    }
+                    *reinterpret_cast<uint64_t *>(dst + hf * 32) = (uint64_t)o[0] | ((uint64_t)o[1] << 32);
+                }
+            }
+        }
+    }
+}
+
+template <typename T, int K>
+static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const void *x, float scale, void *out,
+                                        hipStream_t s) {
+    constexpr int WAVES = inv_mfma_waves<T, K>();
+    using C = InvMfmaCfg<T, K, WAVES>;
+    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
+    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
+    const int ntiles = tiles_x * tiles_y * p.planes();
+    const int max_wgs = 256 * 4;
+    const int tiles_per_wg = (ntiles + max_wgs - 1) / max_wgs;
+    const int nwg = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
+    auto kern = inverse_mfma_kernel<T, K, WAVES>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
+                       static_cast<const T *>(w), static_cast<const T *>(x), scale, static_cast<T *>(out), p.H, p.W,
+                       tiles_x, tiles_y, ntiles, tiles_per_wg);
+    return hipGetLastError();
+}
+
+// The kernel sizes its LDS images for keys that are next to at most one border per axis; on axes
+// of at most 2K + 2 positions a key patch can be seen from both clamped ends at once, and such
+// (tiny) maps take the plain gather kernel instead.
+bool inverse_mfma_supported(const Problem &p) {
+    const int shortest = p.H < p.W ? p.H : p.W;
+    return p.dtype != NA2D_F32 && p.K <= 7 && shortest > 2 * p.K + 2;
+}
+
+hipError_t launch_inverse_mfma(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s) {
+#define NA2D_INV_K(TT)                                                                              \
+    switch (p.K) {                                                                                  \
+        case 3: return launch_inverse_mfma_t<TT, 3>(p, w, x, scale, out, s);                        \
+        case 5: return launch_inverse_mfma_t<TT, 5>(p, w, x, scale, out, s);                        \
+        case 7: return launch_inverse_mfma_t<TT, 7>(p, w, x, scale, out, s);                        \
+        default: return hipErrorInvalidValue;                                                       \
+    }
+    if (p.dtype == NA2D_F16) { NA2D_INV_K(f16_t) }
+    if (p.dtype == NA2D_BF16) { NA2D_INV_K(bf16_t) }
+#undef NA2D_INV_K
+    return hipErrorInvalidValue;
+}
+
+}  // namespace na2d

@@ -29,6 +29,8 @@ hipError_t launch_av(const Problem &p, const void *w, const void *y, float scale
 hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);
 // out_j = scale * sum_{inverse neighbourhood} w[i, slot(i, j)] * x_i   (grad-v, grad-k)
 hipError_t launch_inverse(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
+bool inverse_mfma_supported(const Problem &p);
+hipError_t launch_inverse_mfma(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
 hipError_t launch_softmax(const Problem &p, const void *logits, void *out, hipStream_t s);
 hipError_t launch_softmax_bwd(const Problem &p, const void *attn, const void *dp, void *ds, hipStream_t s);
 size_t rpb_bwd_workspace_bytes(const Problem &p);
