@@ -24,15 +24,18 @@
 
 namespace na2d {
 
-template <typename T, int K, int WAVES>
+template <typename T, int K, int STRIPS, int PPW>
 struct InvMfmaCfg {
     static constexpr int R = K / 2;
     static constexpr int PWI = K + R + 3;          // query-halo side of a 4 x 4 key patch
     static_assert(PWI <= 16, "one MFMA block per query-halo row needs K + R + 3 <= 16");
     static constexpr int NBLK = PWI + (PWI & 1);   // halo rows, padded to whole pairs
     static constexpr int NPAIR = NBLK / 2;
-    static constexpr int TY = 4 * WAVES;
-    static constexpr int RH = 4 * (WAVES - 1) + NBLK;   // rows of the tile's query rectangle held in LDS
+    static_assert(PPW == 1 || PPW == 2 || PPW == 4, "a strip of four patches is split evenly over its waves");
+    static constexpr int NWPS = 4 / PPW;              // waves per strip
+    static constexpr int WAVES = STRIPS * NWPS;
+    static constexpr int TY = 4 * STRIPS;
+    static constexpr int RH = 4 * (STRIPS - 1) + NBLK;   // rows of the tile's query rectangle held in LDS
     static constexpr int RW = kTileX + K - 1 + R;       // columns that hold data
     static constexpr int PITCH = 12 + 16;               // farthest patch offset + block width
     static constexpr int KK = K * K;
@@ -47,18 +50,14 @@ struct InvMfmaCfg {
     static constexpr int kCopyIters = (RH * kRowChunks + kThreads - 1) / kThreads;
 };
 
-template <typename T, int K>
-constexpr int inv_mfma_waves() {
-    return InvMfmaCfg<T, K, 4>::kLdsBytes <= 80 * 1024 ? 4 : 2;
-}
-
-template <typename T, int K, int WAVES>
-__global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
+template <typename T, int K, int STRIPS, int PPW>
+__global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 16 ? 4 : 2) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
                                                                        float scale, T *__restrict__ out, int H, int W,
                                                                        int tiles_x, int tiles_y, int ntiles,
                                                                        int tiles_per_wg) {
-    using C = InvMfmaCfg<T, K, WAVES>;
+    using C = InvMfmaCfg<T, K, STRIPS, PPW>;
     using XHalo = typename C::XHalo;
+    constexpr int WAVES = C::WAVES;
     constexpr int SZ = (int)sizeof(T);
     constexpr int BIG = 1 << 24;   // invalid row / column terms push the sum past the zero word
     extern __shared__ __align__(16) char lds[];
@@ -208,7 +207,8 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void inverse_mfma
         }
         __syncthreads();
 
-        const int sy0 = ty0 + 4 * wave;   // first key row of this wave's strip
+        const int sy0 = ty0 + 4 * (wave / C::NWPS);   // first key row of this wave's strip
+        const int p0 = (wave % C::NWPS) * PPW;        // its first patch of the strip
         if (sy0 >= H) continue;
         const int jy = sy0 + ky;
         const int oqy = inv_first(sy0, H, K);   // first query row of the strip's halo
@@ -234,12 +234,12 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void inverse_mfma
         }
         // The four patches of the strip share the halo rows, so they advance together through the row
         // pairs: four independent gather / MFMA chains per step hide the LDS latency of each other.
-        int colterm[4][4];
-        int xpatch[4];
-        f32x4 acc[4][2];
+        int colterm[PPW][4];
+        int xpatch[PPW];
+        f32x4 acc[PPW][2];
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int px0 = tx0 + 4 * p;
+        for (int p = 0; p < PPW; ++p) {
+            const int px0 = tx0 + 4 * (p0 + p);
             const int jx = px0 + kx;
             // Halo columns start at the first query column that sees the patch, moved left to a multiple
             // of 4 inside the rectangle so that the 8-byte operand reads stay aligned; the 16-wide block
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void inverse_mfma
         for (int pb = 0; pb < C::NPAIR; ++pb) {
             if ((row_mask >> (2 * pb)) & 3u) {
 #pragma unroll
-                for (int p = 0; p < 4; ++p) {
+                for (int p = 0; p < PPW; ++p) {
                     uint32_t wv[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
@@ -285,8 +285,8 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void inverse_mfma
             }
         }
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int jx = tx0 + 4 * p + kx;
+        for (int p = 0; p < PPW; ++p) {
+            const int jx = tx0 + 4 * (p0 + p) + kx;
             if (jy < H && jx < W) {
                 char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * Traits<T>::kKeyBytes + g * 8;
 #pragma unroll
@@ -307,15 +307,15 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void inverse_mfma
 template <typename T, int K>
 static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const void *x, float scale, void *out,
                                         hipStream_t s) {
-    constexpr int WAVES = inv_mfma_waves<T, K>();
-    using C = InvMfmaCfg<T, K, WAVES>;
+    constexpr int STRIPS = 2, PPW = 1;
+    using C = InvMfmaCfg<T, K, STRIPS, PPW>;
     static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const int ntiles = tiles_x * tiles_y * p.planes();
-    const int max_wgs = 256 * 4;
+    const int max_wgs = 256 * 2;
     const int tiles_per_wg = (ntiles + max_wgs - 1) / max_wgs;
     const int nwg = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
-    auto kern = inverse_mfma_kernel<T, K, WAVES>;
+    auto kern = inverse_mfma_kernel<T, K, STRIPS, PPW>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
