@@ -24,6 +24,9 @@
 
 namespace na2d {
 
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef const __attribute__((address_space(1))) void global_void_t;
+
 template <typename T, int K, int STRIPS, int PPW>
 struct InvMfmaCfg {
     static constexpr int R = K / 2;
@@ -54,7 +57,7 @@ template <typename T, int K, int STRIPS, int PPW>
 __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 16 ? 4 : 2) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
                                                                        float scale, T *__restrict__ out, int H, int W,
                                                                        int tiles_x, int tiles_y, int ntiles,
-                                                                       int tiles_per_wg) {
+                                                                       int tiles_per_wg, int nplanes) {
     using C = InvMfmaCfg<T, K, STRIPS, PPW>;
     using XHalo = typename C::XHalo;
     constexpr int WAVES = C::WAVES;
@@ -62,12 +65,12 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
     constexpr int BIG = 1 << 24;   // invalid row / column terms push the sum past the zero word
     extern __shared__ __align__(16) char lds[];
 
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int n = lane & 15, g = lane >> 4, ky = n >> 2, kx = n & 3;
     const int lds0 = lds_addr(lds);
     const int w0 = lds0 + XHalo::kBytes;              // weight rows
     const int zero_addr = w0 + C::kWBytes;            // a zero word above every valid gather address
-    char *w_lds = lds + XHalo::kBytes;
 
     // Everything the stagers do not write must hold finite numbers (it meets zero weights only).
     for (int i = tid * 16; i < C::kLdsBytes; i += C::kThreads * 16) *lds_ptr<u32x4>(lds0 + i) = u32x4{0u, 0u, 0u, 0u};
@@ -80,9 +83,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
     const int t_begin = wg * tiles_per_wg;
     const int t_end = (wg + 1) * tiles_per_wg < ntiles ? (wg + 1) * tiles_per_wg : ntiles;
 
-    int rowterm[C::NBLK];
-    unsigned row_mask = 0;
-    int cur_rowkey = -1;
+    const size_t w_bytes = (size_t)nplanes * H * W * C::KK * SZ;   // size of the weight tensor
 
     for (int t = t_begin; t < t_end; ++t) {
         const TileCoord tc = decode_tile(t, tiles_x, tiles_y);
@@ -95,33 +96,58 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
         const int nrows = ry1 - ry0 + 1, ncols = rx1 - rx0 + 1;   // <= RH, <= RW
 
         __syncthreads();   // the previous tile's LDS images are no longer read
-        // Stage the rectangle: every global load of the thread is issued before the first LDS store,
-        // so the tile pays one memory latency.  Indices advance incrementally (no divisions, and no
-        // offset tables held across the compute phase).
+        const size_t g0first = (plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ;   // first byte of the first weight row
+        const int row_pitch_bytes = W * C::KK * SZ;                              // < 2^31: checked by the host
+        // Stage the rectangle.  Weight rows go from global memory straight into LDS (no registers): a
+        // row is mirrored at its 16-byte phase, one 16-byte chunk per lane, 64 chunks per instruction;
+        // the chunks at the two ends also bring in bytes of the neighbouring rows, which nothing reads.
+        // Only a chunk that would cross the end of the tensor is copied element by element.
+        {
+            constexpr int NI = (C::kRowChunks + kWave - 1) / kWave;   // instructions per row
+            constexpr int PER_WAVE = (C::RH * NI + WAVES - 1) / WAVES;
+            const char *wbase = reinterpret_cast<const char *>(w);
+            const int nbytes = ncols * C::KK * SZ;
+#pragma unroll
+            for (int i = 0; i < PER_WAVE; ++i) {
+                const int item = wave + i * WAVES;
+                const int r = item / NI, j = item - r * NI;
+                if (r < nrows) {
+                    const size_t g0 = g0first + (size_t)r * row_pitch_bytes;
+                    const int mis = (int)(g0 & 15);
+                    const int nchunks = (mis + nbytes + 15) >> 4;
+                    const int c = j * kWave + lane;
+                    const size_t gchunk = (g0 - mis) + (size_t)c * 16;
+                    const int region = w0 + r * C::kRowRegion;
+                    if (c < nchunks) {
+                        if (gchunk + 16 <= w_bytes) {
+                            __builtin_amdgcn_global_load_lds((global_void_t *)(wbase + gchunk),
+                                                             (lds_void_t *)lds_ptr<char>(region + j * kWave * 16), 16, 0, 0);
+                        } else {
+                            for (size_t e = gchunk; e < w_bytes; e += SZ)
+                                *lds_ptr<T>(region + (int)(e - (g0 - mis))) = *reinterpret_cast<const T *>(wbase + e);
+                        }
+                    }
+                }
+            }
+        }
+        // x vectors: every load of the thread is issued before the first LDS store.  Positions outside
+        // the map load the nearest position inside it instead (finite numbers that only meet zero weights).
         {
             constexpr int CPK = Traits<T>::kKeyBytes / 16;          // 16-byte chunks per vector (4)
             constexpr int NX = XHalo::NITER;                          // x chunks per thread
-            constexpr int NW = C::kCopyIters;                         // weight-row chunks per thread
-            constexpr int KSTEP = C::kThreads / CPK;                  // keys a thread advances per iteration
+            constexpr int KSTEP = C::kThreads / CPK;                  // positions a thread advances per iteration
             static_assert(C::kThreads % CPK == 0, "thread count must be a multiple of the chunks per vector");
             const char *xbase = reinterpret_cast<const char *>(x) + plane_q * Traits<T>::kKeyBytes;
-            const char *wbase = reinterpret_cast<const char *>(w);
-            const int nbytes = ncols * C::KK * SZ;
-            const size_t g0first = (plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ;
-            const int row_pitch_bytes = W * C::KK * SZ;   // < 2^31: checked by the host
-            const int mis0 = (int)(g0first & 15);
-            const char *wfirst = wbase + g0first;         // first byte of the rectangle's first weight row
-            u32x4 xv[NX], wv[NW];
+            u32x4 xv[NX];
             const int c = tid % CPK;
             {
                 int key = tid / CPK;
                 int ry = key / C::RW, rx = key - ry * C::RW;
 #pragma unroll
                 for (int it = 0; it < NX; ++it) {
-                    const int y = ry0 + ry, xq = rx0 + rx;
-                    xv[it] = u32x4{0u, 0u, 0u, 0u};
-                    if (ry < C::RH && y < H && xq < W)
-                        xv[it] = *reinterpret_cast<const u32x4 *>(xbase + ((y * W + xq) * Traits<T>::kKeyBytes + c * 16));
+                    const int y = ry0 + ry < H - 1 ? ry0 + ry : H - 1;
+                    const int xq = rx0 + rx < W - 1 ? rx0 + rx : W - 1;
+                    xv[it] = *reinterpret_cast<const u32x4 *>(xbase + ((y * W + xq) * Traits<T>::kKeyBytes + c * 16));
                     rx += KSTEP % C::RW;
                     ry += KSTEP / C::RW;
                     if (rx >= C::RW) {
@@ -129,40 +155,6 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
                         ry += 1;
                     }
                 }
-            }
-            {
-                int r = tid / C::kRowChunks, ci = tid - r * C::kRowChunks;
-#pragma unroll
-                for (int it = 0; it < NW; ++it) {
-                    wv[it] = u32x4{0u, 0u, 0u, 0u};
-                    if (r < nrows) {
-                        // row r starts r * pitch bytes after the first row; its 16-byte phase follows
-                        const int rel = r * row_pitch_bytes;
-                        const int mis = (mis0 + rel) & 15;
-                        const int body_lo = (mis + 15) & ~15, body_hi = (mis + nbytes) & ~15;
-                        const int lo = ci << 4;
-                        if (lo >= body_lo && lo < body_hi)
-                            wv[it] = *reinterpret_cast<const u32x4 *>(wfirst + (rel - mis + lo));
-                    }
-                    ci += C::kThreads % C::kRowChunks;
-                    r += C::kThreads / C::kRowChunks;
-                    if (ci >= C::kRowChunks) {
-                        ci -= C::kRowChunks;
-                        r += 1;
-                    }
-                }
-            }
-            // ragged head and tail of every weight row, element by element: wave `r mod WAVES` takes row r
-            for (int r = wave; r < nrows; r += WAVES) {
-                const size_t g0 = g0first + (size_t)r * row_pitch_bytes;
-                const RunSplit rs = split_run(g0, nbytes);
-                const char *ga = wbase + (g0 - rs.mis);
-                char *region = w_lds + r * C::kRowRegion;
-                const int head_end = rs.body_lo < rs.span ? rs.body_lo : rs.span;
-                const int hb = rs.mis + lane * SZ;
-                if (hb < head_end) *reinterpret_cast<T *>(region + hb) = *reinterpret_cast<const T *>(ga + hb);
-                const int tb = rs.body_hi + (lane - 16) * SZ;
-                if (lane >= 16 && tb < rs.span) *reinterpret_cast<T *>(region + tb) = *reinterpret_cast<const T *>(ga + tb);
             }
             {
                 int key = tid / CPK;
@@ -186,25 +178,8 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
                     }
                 }
             }
-            {
-                int r = tid / C::kRowChunks, ci = tid - r * C::kRowChunks;
-#pragma unroll
-                for (int it = 0; it < NW; ++it) {
-                    if (r < nrows) {
-                        const int mis = (mis0 + r * row_pitch_bytes) & 15;
-                        const int body_lo = (mis + 15) & ~15, body_hi = (mis + nbytes) & ~15;
-                        const int lo = ci << 4;
-                        if (lo >= body_lo && lo < body_hi) *lds_ptr<u32x4>(w0 + r * C::kRowRegion + lo) = wv[it];
-                    }
-                    ci += C::kThreads % C::kRowChunks;
-                    r += C::kThreads / C::kRowChunks;
-                    if (ci >= C::kRowChunks) {
-                        ci -= C::kRowChunks;
-                        r += 1;
-                    }
-                }
-            }
         }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the direct-to-LDS weight rows have landed
         __syncthreads();
 
         const int sy0 = ty0 + 4 * (wave / C::NWPS);   // first key row of this wave's strip
@@ -212,25 +187,26 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
         if (sy0 >= H) continue;
         const int jy = sy0 + ky;
         const int oqy = inv_first(sy0, H, K);   // first query row of the strip's halo
-        // row terms: halo row b holds query row iy = oqy + b; this lane's key row jy sits in its window at a
-        {
-            const size_t g0first = (plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ;
-            // the terms depend on the strip's rows (one strip position per wave and tile row) and on the
-            // 16-byte phase of the rectangle's first weight row
-            const int rowkey = (sy0 << 4) | (int)(g0first & 15);
-            if (rowkey != cur_rowkey) {
-                cur_rowkey = rowkey;
-                row_mask = 0;
+        // Row terms: halo row b holds query row iy = oqy + b, whose window starts at win_start(iy); this
+        // lane's key row sits in it at a = ky + (sy0 - win_start(iy)).  Everything but ky is the same for
+        // the whole wave.
+        int rowterm[C::NBLK];
+        unsigned row_mask = 0;
 #pragma unroll
-                for (int b = 0; b < C::NBLK; ++b) {
-                    const int iy = oqy + b;
-                    const int a = jy - win_start(iy < H ? iy : H - 1, H, K);
-                    const bool ok = b < C::PWI && iy <= ry1 && jy < H && (unsigned)a < (unsigned)K;
-                    const size_t g0 = (plane_q + (size_t)iy * W + rx0) * C::KK * SZ;
-                    rowterm[b] = ok ? w0 + (iy - ry0) * C::kRowRegion + (int)(g0 & 15) + a * K * SZ : BIG;
-                    row_mask |= __any(ok) ? (1u << b) : 0u;
-                }
-            }
+        for (int b = 0; b < C::NBLK; ++b) {
+            const int iy = oqy + b;
+            const int d = sy0 - win_start(iy < H ? iy : H - 1, H, K);
+            const bool row_ok = b < C::PWI && iy <= ry1;
+            const int mis = (int)((g0first + (size_t)(iy - ry0) * row_pitch_bytes) & 15);
+            const int base = w0 + (iy - ry0) * C::kRowRegion + mis + d * K * SZ;
+            const int a = ky + d;
+            const bool ok = row_ok && jy < H && (unsigned)a < (unsigned)K;
+            rowterm[b] = ok ? base + ky * K * SZ : BIG;
+            // some key row of the strip lies in the window of query row iy
+            const int klo = d < 0 ? -d : 0;
+            int khi = K - 1 - d < 3 ? K - 1 - d : 3;
+            khi = khi < H - 1 - sy0 ? khi : H - 1 - sy0;
+            row_mask |= (row_ok && klo <= khi) ? (1u << b) : 0u;
         }
         // The four patches of the strip share the halo rows, so they advance together through the row
         // pairs: four independent gather / MFMA chains per step hide the LDS latency of each other.
@@ -325,7 +301,7 @@ static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const v
     }
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(w), static_cast<const T *>(x), scale, static_cast<T *>(out), p.H, p.W,
-                       tiles_x, tiles_y, ntiles, tiles_per_wg);
+                       tiles_x, tiles_y, ntiles, tiles_per_wg, p.planes());
     return hipGetLastError();
 }
 
