@@ -85,10 +85,22 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
 
     const size_t w_bytes = (size_t)nplanes * H * W * C::KK * SZ;   // size of the weight tensor
 
+    // Tiles are numbered down the columns of a plane (the row index runs fastest), so the tiles a
+    // workgroup takes one after the other overlap in most of their query rows and the tiles of its
+    // neighbours, running alongside, in the rest: the halo is re-read from the L2 cache while it is hot.
+    int tiy = t_begin % tiles_y;
+    int tix = (t_begin / tiles_y) % tiles_x;
+    int plane = t_begin / (tiles_y * tiles_x);
     for (int t = t_begin; t < t_end; ++t) {
-        const TileCoord tc = decode_tile(t, tiles_x, tiles_y);
-        const int ty0 = tc.tiy * C::TY, tx0 = tc.tix * kTileX;
-        const size_t plane_q = (size_t)tc.plane * H * W;
+        const int ty0 = tiy * C::TY, tx0 = tix * kTileX;
+        const size_t plane_q = (size_t)plane * H * W;
+        if (++tiy == tiles_y) {
+            tiy = 0;
+            if (++tix == tiles_x) {
+                tix = 0;
+                ++plane;
+            }
+        }
         const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
         const int tx1 = tx0 + kTileX - 1 < W - 1 ? tx0 + kTileX - 1 : W - 1;
         const int ry0 = inv_first(ty0, H, K), ry1 = inv_last(ty1, H, K);
@@ -98,36 +110,38 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
         __syncthreads();   // the previous tile's LDS images are no longer read
         const size_t g0first = (plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ;   // first byte of the first weight row
         const int row_pitch_bytes = W * C::KK * SZ;                              // < 2^31: checked by the host
+        const int mis0 = (int)(g0first & 15), pitch_phase = row_pitch_bytes & 15;   // 16-byte phase of row r: (mis0 + r * pitch_phase) & 15
         // Stage the rectangle.  Weight rows go from global memory straight into LDS (no registers): a
         // row is mirrored at its 16-byte phase, one 16-byte chunk per lane, 64 chunks per instruction;
         // the chunks at the two ends also bring in bytes of the neighbouring rows, which nothing reads.
-        // Only a chunk that would cross the end of the tensor is copied element by element.
+        // Only the one chunk that would cross the end of the tensor is copied element by element.
         {
             constexpr int NI = (C::kRowChunks + kWave - 1) / kWave;   // instructions per row
             constexpr int PER_WAVE = (C::RH * NI + WAVES - 1) / WAVES;
-            const char *wbase = reinterpret_cast<const char *>(w);
+            const char *wrow = reinterpret_cast<const char *>(w) + (g0first - mis0);   // 16-byte aligned
+            const size_t left = w_bytes - (g0first - mis0);                             // bytes up to the tensor's end
+            const int rem = left < (size_t)0x7fffffff ? (int)left : 0x7fffffff;
             const int nbytes = ncols * C::KK * SZ;
 #pragma unroll
             for (int i = 0; i < PER_WAVE; ++i) {
                 const int item = wave + i * WAVES;
                 const int r = item / NI, j = item - r * NI;
                 if (r < nrows) {
-                    const size_t g0 = g0first + (size_t)r * row_pitch_bytes;
-                    const int mis = (int)(g0 & 15);
-                    const int nchunks = (mis + nbytes + 15) >> 4;
+                    const int rel = mis0 + r * row_pitch_bytes;   // row start, from wrow
+                    const int nchunks = ((rel & 15) + nbytes + 15) >> 4;
                     const int c = j * kWave + lane;
-                    const size_t gchunk = (g0 - mis) + (size_t)c * 16;
-                    const int region = w0 + r * C::kRowRegion;
-                    if (c < nchunks) {
-                        if (gchunk + 16 <= w_bytes) {
-                            __builtin_amdgcn_global_load_lds((global_void_t *)(wbase + gchunk),
-                                                             (lds_void_t *)lds_ptr<char>(region + j * kWave * 16), 16, 0, 0);
-                        } else {
-                            for (size_t e = gchunk; e < w_bytes; e += SZ)
-                                *lds_ptr<T>(region + (int)(e - (g0 - mis))) = *reinterpret_cast<const T *>(wbase + e);
-                        }
-                    }
+                    const int off = (rel & ~15) + c * 16;
+                    if (c < nchunks && off + 16 <= rem)
+                        __builtin_amdgcn_global_load_lds((global_void_t *)(wrow + off),
+                                                         (lds_void_t *)lds_ptr<char>(w0 + r * C::kRowRegion + j * kWave * 16), 16, 0, 0);
                 }
+            }
+            const int rel_last = mis0 + (nrows - 1) * row_pitch_bytes;
+            const int end_last = rel_last + nbytes;
+            if (((end_last + 15) & ~15) > rem && wave == 0) {   // the tensor ends inside the last chunk of the last row
+                const int off = (rem & ~15) + lane * SZ;
+                if (lane < 16 / SZ && off < end_last)
+                    *lds_ptr<T>(w0 + (nrows - 1) * C::kRowRegion + (off - (rel_last & ~15))) = *reinterpret_cast<const T *>(wrow + off);
             }
         }
         // x vectors: every load of the thread is issued before the first LDS store.  Positions outside
@@ -197,7 +211,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
             const int iy = oqy + b;
             const int d = sy0 - win_start(iy < H ? iy : H - 1, H, K);
             const bool row_ok = b < C::PWI && iy <= ry1;
-            const int mis = (int)((g0first + (size_t)(iy - ry0) * row_pitch_bytes) & 15);
+            const int mis = (mis0 + (iy - ry0) * pitch_phase) & 15;
             const int base = w0 + (iy - ry0) * C::kRowRegion + mis + d * K * SZ;
             const int a = ky + d;
             const bool ok = row_ok && jy < H && (unsigned)a < (unsigned)K;
