@@ -47,7 +47,11 @@ struct InvMfmaCfg {
     static constexpr int kRowBytes = RW * KK * (int)sizeof(T);
     static constexpr int kRowRegion = mirror_bytes(kRowBytes);
     static constexpr int kWBytes = RH * kRowRegion;
-    static constexpr int kLdsBytes = XHalo::kBytes + kWBytes + 16;   // + the zero word
+    // gather-address tables of the current tile: column terms [patch][g][kx][r], row terms [strip][b][ky]
+    static constexpr int kColEntries = 4 * 4 * 4 * 4;
+    static constexpr int kRowEntries = STRIPS * NBLK * 4;
+    static constexpr int kTblBytes = (kColEntries + kRowEntries) * 4;
+    static constexpr int kLdsBytes = XHalo::kBytes + kWBytes + 16 + kTblBytes;   // + the zero word
     // chunk grid of the weight-row copy
     static constexpr int kRowChunks = kRowRegion / 16;
     static constexpr int kCopyIters = (RH * kRowChunks + kThreads - 1) / kThreads;
@@ -71,6 +75,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
     const int lds0 = lds_addr(lds);
     const int w0 = lds0 + XHalo::kBytes;              // weight rows
     const int zero_addr = w0 + C::kWBytes;            // a zero word above every valid gather address
+    const int tbl_col = zero_addr + 16, tbl_row = tbl_col + C::kColEntries * 4;
 
     // Everything the stagers do not write must hold finite numbers (it meets zero weights only).
     for (int i = tid * 16; i < C::kLdsBytes; i += C::kThreads * 16) *lds_ptr<u32x4>(lds0 + i) = u32x4{0u, 0u, 0u, 0u};
@@ -144,6 +149,31 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
                     *lds_ptr<T>(w0 + (nrows - 1) * C::kRowRegion + (off - (rel_last & ~15))) = *reinterpret_cast<const T *>(wrow + off);
             }
         }
+        // Gather-address tables, one entry per thread: the address of the weight that query (iy, ix)
+        // gives key (jy, jx) is rowterm(iy, jy) + colterm(ix, jx); a pair that does not meet gets BIG.
+        for (int e = tid; e < C::kColEntries + C::kRowEntries; e += C::kThreads) {
+            int term = BIG;
+            if (e < C::kColEntries) {
+                const int r = e & 3, kxe = (e >> 2) & 3, ge = (e >> 4) & 3, pe = e >> 6;
+                const int px0 = tx0 + 4 * pe, jx = px0 + kxe;
+                // Halo columns start at the first query column that sees the patch, moved left to a multiple
+                // of 4 inside the rectangle so that the 8-byte operand reads stay aligned; the 16-wide block
+                // still reaches the last such column (at most K + R + 3 <= 13 of them).
+                const int oq = inv_first(px0 < W ? px0 : W - 1, W, K);
+                const int ix = rx0 + ((oq - rx0) & ~3) + 4 * ge + r;
+                const int c = jx - win_start(ix < W ? ix : W - 1, W, K);
+                if (px0 < W && ix <= rx1 && jx < W && (unsigned)c < (unsigned)K) term = (ix - rx0) * C::KK * SZ + c * SZ;
+            } else {
+                const int l = e - C::kColEntries;
+                const int kye = l & 3, b = (l >> 2) % C::NBLK, strip = (l >> 2) / C::NBLK;
+                const int sy = ty0 + 4 * strip, jy = sy + kye;
+                const int iy = inv_first(sy < H ? sy : H - 1, H, K) + b;   // halo row b of the strip
+                const int a = jy - win_start(iy < H ? iy : H - 1, H, K);
+                if (b < C::PWI && iy <= ry1 && jy < H && (unsigned)a < (unsigned)K)
+                    term = w0 + (iy - ry0) * C::kRowRegion + ((mis0 + (iy - ry0) * pitch_phase) & 15) + a * K * SZ;
+            }
+            *lds_ptr<int>(tbl_col + e * 4) = term;
+        }
         // x vectors: every load of the thread is issued before the first LDS store.  Positions outside
         // the map load the nearest position inside it instead (finite numbers that only meet zero weights).
         {
@@ -199,57 +229,33 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
         const int sy0 = ty0 + 4 * (wave / C::NWPS);   // first key row of this wave's strip
         const int p0 = (wave % C::NWPS) * PPW;        // its first patch of the strip
         if (sy0 >= H) continue;
+        const int strip = wave / C::NWPS;
         const int jy = sy0 + ky;
         const int oqy = inv_first(sy0, H, K);   // first query row of the strip's halo
-        // Row terms: halo row b holds query row iy = oqy + b, whose window starts at win_start(iy); this
-        // lane's key row sits in it at a = ky + (sy0 - win_start(iy)).  Everything but ky is the same for
-        // the whole wave.
         int rowterm[C::NBLK];
-        unsigned row_mask = 0;
 #pragma unroll
-        for (int b = 0; b < C::NBLK; ++b) {
-            const int iy = oqy + b;
-            const int d = sy0 - win_start(iy < H ? iy : H - 1, H, K);
-            const bool row_ok = b < C::PWI && iy <= ry1;
-            const int mis = (mis0 + (iy - ry0) * pitch_phase) & 15;
-            const int base = w0 + (iy - ry0) * C::kRowRegion + mis + d * K * SZ;
-            const int a = ky + d;
-            const bool ok = row_ok && jy < H && (unsigned)a < (unsigned)K;
-            rowterm[b] = ok ? base + ky * K * SZ : BIG;
-            // some key row of the strip lies in the window of query row iy
-            const int klo = d < 0 ? -d : 0;
-            int khi = K - 1 - d < 3 ? K - 1 - d : 3;
-            khi = khi < H - 1 - sy0 ? khi : H - 1 - sy0;
-            row_mask |= (row_ok && klo <= khi) ? (1u << b) : 0u;
-        }
-        // The four patches of the strip share the halo rows, so they advance together through the row
-        // pairs: four independent gather / MFMA chains per step hide the LDS latency of each other.
+        for (int b = 0; b < C::NBLK; ++b) rowterm[b] = *lds_ptr<int>(tbl_row + ((strip * C::NBLK + b) * 4 + ky) * 4);
         int colterm[PPW][4];
         int xpatch[PPW];
         f32x4 acc[PPW][2];
 #pragma unroll
         for (int p = 0; p < PPW; ++p) {
             const int px0 = tx0 + 4 * (p0 + p);
-            const int jx = px0 + kx;
-            // Halo columns start at the first query column that sees the patch, moved left to a multiple
-            // of 4 inside the rectangle so that the 8-byte operand reads stay aligned; the 16-wide block
-            // still reaches the last such column (at most K + R + 3 <= 13 of them).
+            const u32x4 ct = *lds_ptr<u32x4>(tbl_col + (((p0 + p) * 4 + g) * 4 + kx) * 16);
+            colterm[p][0] = (int)ct.x;
+            colterm[p][1] = (int)ct.y;
+            colterm[p][2] = (int)ct.z;
+            colterm[p][3] = (int)ct.w;
             const int oq = inv_first(px0 < W ? px0 : W - 1, W, K);
-            const int oqx = rx0 + ((oq - rx0) & ~3);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int ix = oqx + 4 * g + r;
-                const int c = jx - win_start(ix < W ? ix : W - 1, W, K);
-                const bool ok = px0 < W && ix <= rx1 && jx < W && (unsigned)c < (unsigned)K;
-                colterm[p][r] = ok ? (ix - rx0) * C::KK * SZ + c * SZ : BIG;
-            }
+            const int oqx = rx0 + ((oq - rx0) & ~3);   // as in the column table
             xpatch[p] = ((oqy - ry0) * C::PITCH + (oqx - rx0)) * 2;
             acc[p][0] = f32x4{0.f, 0.f, 0.f, 0.f};
             acc[p][1] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
         for (int pb = 0; pb < C::NPAIR; ++pb) {
-            if ((row_mask >> (2 * pb)) & 3u) {
+            // halo rows that no key row of the strip is seen from are skipped
+            if (__any(rowterm[2 * pb] < BIG || rowterm[2 * pb + 1] < BIG)) {
 #pragma unroll
                 for (int p = 0; p < PPW; ++p) {
                     uint32_t wv[4];
