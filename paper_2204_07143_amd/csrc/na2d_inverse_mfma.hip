@@ -24,9 +24,6 @@
 
 namespace na2d {
 
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef const __attribute__((address_space(1))) void global_void_t;
-
 template <typename T, int K, int STRIPS, int PPW>
 struct InvMfmaCfg {
     static constexpr int R = K / 2;
@@ -40,10 +37,12 @@ struct InvMfmaCfg {
     static constexpr int TY = 4 * STRIPS;
     static constexpr int RH = 4 * (STRIPS - 1) + NBLK;   // rows of the tile's query rectangle held in LDS
     static constexpr int RW = kTileX + K - 1 + R;       // columns that hold data
-    static constexpr int PITCH = 12 + 16;               // farthest patch offset + block width
     static constexpr int KK = K * K;
     static constexpr int kThreads = kWave * WAVES;
-    using XHalo = TransposedHalo<T, RH, RW, kThreads, PITCH>;
+    using XHalo = HaloDma<T, RH, RW, WAVES>;
+    // the x rectangle in its natural layout, plus the positions a 16-wide operand block can reach past
+    // the last row (they stay zero and meet zero weights)
+    static constexpr int kXBytes = XHalo::kBytes + 16 * Traits<T>::kKeyBytes;
     static constexpr int kRowBytes = RW * KK * (int)sizeof(T);
     static constexpr int kRowRegion = mirror_bytes(kRowBytes);
     static constexpr int kWBytes = RH * kRowRegion;
@@ -51,7 +50,7 @@ struct InvMfmaCfg {
     static constexpr int kColEntries = 4 * 4 * 4 * 4;
     static constexpr int kRowEntries = STRIPS * NBLK * 4;
     static constexpr int kTblBytes = (kColEntries + kRowEntries) * 4;
-    static constexpr int kLdsBytes = XHalo::kBytes + kWBytes + 16 + kTblBytes;   // + the zero word
+    static constexpr int kLdsBytes = kXBytes + kWBytes + 16 + kTblBytes;   // + the zero word
     // chunk grid of the weight-row copy
     static constexpr int kRowChunks = kRowRegion / 16;
     static constexpr int kCopyIters = (RH * kRowChunks + kThreads - 1) / kThreads;
@@ -73,7 +72,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int n = lane & 15, g = lane >> 4, ky = n >> 2, kx = n & 3;
     const int lds0 = lds_addr(lds);
-    const int w0 = lds0 + XHalo::kBytes;              // weight rows
+    const int w0 = lds0 + C::kXBytes;                 // weight rows
     const int zero_addr = w0 + C::kWBytes;            // a zero word above every valid gather address
     const int tbl_col = zero_addr + 16, tbl_row = tbl_col + C::kColEntries * 4;
 
@@ -81,8 +80,12 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
     for (int i = tid * 16; i < C::kLdsBytes; i += C::kThreads * 16) *lds_ptr<u32x4>(lds0 + i) = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
 
-    // lane-constant part of the A-operand address: channel n of a half, positions 4g .. 4g+3 of a block
-    const int xt_lane = lds0 + n * XHalo::DSTRIDE + 4 * g * 2;
+    // lane-constant part of the A-operand address (transposing read): inside its group of 16, lane n
+    // points at channels 4 (n % 4) .. + 3 of position 4g + n / 4 of a block and receives channel n of
+    // positions 4g .. 4g + 3
+    const int xa_lane = lds0 + (4 * g + (n >> 2)) * Traits<T>::kKeyBytes + (n & 3) * 8;
+    XHalo xhalo;
+    xhalo.init(wave, lane);
 
     const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
     const int t_begin = wg * tiles_per_wg;
@@ -156,11 +159,9 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
             if (e < C::kColEntries) {
                 const int r = e & 3, kxe = (e >> 2) & 3, ge = (e >> 4) & 3, pe = e >> 6;
                 const int px0 = tx0 + 4 * pe, jx = px0 + kxe;
-                // Halo columns start at the first query column that sees the patch, moved left to a multiple
-                // of 4 inside the rectangle so that the 8-byte operand reads stay aligned; the 16-wide block
-                // still reaches the last such column (at most K + R + 3 <= 13 of them).
-                const int oq = inv_first(px0 < W ? px0 : W - 1, W, K);
-                const int ix = rx0 + ((oq - rx0) & ~3) + 4 * ge + r;
+                // halo columns start at the first query column that sees the patch; the 16-wide block
+                // reaches the last such column (at most K + R + 3 <= 13 of them)
+                const int ix = inv_first(px0 < W ? px0 : W - 1, W, K) + 4 * ge + r;
                 const int c = jx - win_start(ix < W ? ix : W - 1, W, K);
                 if (px0 < W && ix <= rx1 && jx < W && (unsigned)c < (unsigned)K) term = (ix - rx0) * C::KK * SZ + c * SZ;
             } else {
@@ -174,56 +175,9 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
             }
             *lds_ptr<int>(tbl_col + e * 4) = term;
         }
-        // x vectors: every load of the thread is issued before the first LDS store.  Positions outside
-        // the map load the nearest position inside it instead (finite numbers that only meet zero weights).
-        {
-            constexpr int CPK = Traits<T>::kKeyBytes / 16;          // 16-byte chunks per vector (4)
-            constexpr int NX = XHalo::NITER;                          // x chunks per thread
-            constexpr int KSTEP = C::kThreads / CPK;                  // positions a thread advances per iteration
-            static_assert(C::kThreads % CPK == 0, "thread count must be a multiple of the chunks per vector");
-            const char *xbase = reinterpret_cast<const char *>(x) + plane_q * Traits<T>::kKeyBytes;
-            u32x4 xv[NX];
-            const int c = tid % CPK;
-            {
-                int key = tid / CPK;
-                int ry = key / C::RW, rx = key - ry * C::RW;
-#pragma unroll
-                for (int it = 0; it < NX; ++it) {
-                    const int y = ry0 + ry < H - 1 ? ry0 + ry : H - 1;
-                    const int xq = rx0 + rx < W - 1 ? rx0 + rx : W - 1;
-                    xv[it] = *reinterpret_cast<const u32x4 *>(xbase + ((y * W + xq) * Traits<T>::kKeyBytes + c * 16));
-                    rx += KSTEP % C::RW;
-                    ry += KSTEP / C::RW;
-                    if (rx >= C::RW) {
-                        rx -= C::RW;
-                        ry += 1;
-                    }
-                }
-            }
-            {
-                int key = tid / CPK;
-                int ry = key / C::RW, rx = key - ry * C::RW;
-#pragma unroll
-                for (int it = 0; it < NX; ++it) {
-                    if (ry < C::RH) {
-                        const int base = lds0 + (8 * c) * XHalo::DSTRIDE + (ry * C::PITCH + rx) * 2;
-                        const uint32_t wd[4] = {xv[it].x, xv[it].y, xv[it].z, xv[it].w};
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            *lds_ptr<uint16_t>(base + (2 * u) * XHalo::DSTRIDE) = (uint16_t)(wd[u] & 0xffffu);
-                            *lds_ptr<uint16_t>(base + (2 * u + 1) * XHalo::DSTRIDE) = (uint16_t)(wd[u] >> 16);
-                        }
-                    }
-                    rx += KSTEP % C::RW;
-                    ry += KSTEP / C::RW;
-                    if (rx >= C::RW) {
-                        rx -= C::RW;
-                        ry += 1;
-                    }
-                }
-            }
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the direct-to-LDS weight rows have landed
+        // x vectors, natural layout
+        xhalo.issue(reinterpret_cast<const char *>(x) + plane_q * Traits<T>::kKeyBytes, H, W, ry0, rx0, lds0, wave);
+        wait_global_loads();
         __syncthreads();
 
         const int sy0 = ty0 + 4 * (wave / C::NWPS);   // first key row of this wave's strip
@@ -246,9 +200,8 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
             colterm[p][1] = (int)ct.y;
             colterm[p][2] = (int)ct.z;
             colterm[p][3] = (int)ct.w;
-            const int oq = inv_first(px0 < W ? px0 : W - 1, W, K);
-            const int oqx = rx0 + ((oq - rx0) & ~3);   // as in the column table
-            xpatch[p] = ((oqy - ry0) * C::PITCH + (oqx - rx0)) * 2;
+            const int oqx = inv_first(px0 < W ? px0 : W - 1, W, K);   // as in the column table
+            xpatch[p] = ((oqy - ry0) * C::RW + (oqx - rx0)) * Traits<T>::kKeyBytes;
             acc[p][0] = f32x4{0.f, 0.f, 0.f, 0.f};
             acc[p][1] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
@@ -271,10 +224,10 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
                     const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
 #pragma unroll
                     for (int hf = 0; hf < 2; ++hf) {
-                        const int a0 = xt_lane + xpatch[p] + (2 * pb) * C::PITCH * 2 + hf * 16 * XHalo::DSTRIDE;
-                        const uint64_t lo = *lds_ptr<uint64_t>(a0);
-                        const uint64_t hi = *lds_ptr<uint64_t>(a0 + C::PITCH * 2);
-                        const u32x4 aop = u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
+                        const int a0 = xa_lane + xpatch[p] + (2 * pb) * C::RW * Traits<T>::kKeyBytes + hf * 32;
+                        const u32x2 lo = lds_read_tr16(a0);
+                        const u32x2 hi = lds_read_tr16(a0 + C::RW * Traits<T>::kKeyBytes);
+                        const u32x4 aop = u32x4{lo.x, lo.y, hi.x, hi.y};
                         acc[p][hf] = mfma_16x16x32<T>(aop, bop, acc[p][hf]);
                     }
                 }

@@ -167,4 +167,69 @@ struct TransposedHalo {
     }
 };
 
+// ---- global memory -> LDS without registers, and transposing LDS reads --------------------
+//
+// gfx950 can load 16 bytes per lane from global memory straight into LDS: lane l of the wave
+// writes [lds_base + 16 l, lds_base + 16 l + 16), lds_base being the same for the whole wave
+// (inactive lanes write nothing).  The load is asynchronous and completes in vmcnt order.
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef const __attribute__((address_space(1))) void global_void_t;
+
+__device__ __forceinline__ void global_to_lds_16(const void *g, int lds_base) {
+    __builtin_amdgcn_global_load_lds((global_void_t *)g, (lds_void_t *)lds_ptr<char>(lds_base), 16, 0, 0);
+}
+// waits until every load of this wave, the direct-to-LDS ones included, has landed
+__device__ __forceinline__ void wait_global_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// A ROWS x COLS rectangle of head-dim vectors of one plane, copied into LDS in its natural
+// layout [row][col][channel] (64 bytes per position, no padding) by direct loads; the rows of
+// work items (64 chunks each) are dealt round-robin to NWAVES waves.  Positions outside the
+// map are replaced by the nearest one inside it: the kernels give them zero weight, or drop
+// their results, so any finite value serves.
+template <typename T, int ROWS, int COLS, int NWAVES>
+struct HaloDma {
+    static_assert(sizeof(T) == 2, "64-byte vectors");
+    static constexpr int CPK = Traits<T>::kKeyBytes / 16;
+    static constexpr int TOTAL = ROWS * COLS * CPK;
+    static constexpr int NITEM = (TOTAL + kWave - 1) / kWave;
+    static constexpr int PER_WAVE = (NITEM + NWAVES - 1) / NWAVES;
+    static constexpr int kBytes = TOTAL * 16;
+    int pos[PER_WAVE];   // row | col << 8 | chunk << 16 of this lane's chunk in item i, -1 past the end
+
+    __device__ __forceinline__ void init(int wave, int lane) {
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i) {
+            const int q = (wave + i * NWAVES) * kWave + lane;
+            const int pq = q / CPK, c = q % CPK;
+            const int ry = pq / COLS, rx = pq % COLS;
+            pos[i] = q < TOTAL ? (ry | (rx << 8) | (c << 16)) : -1;
+        }
+    }
+    __device__ __forceinline__ void issue(const char *plane_base, int H, int W, int oy, int ox, int lds_base, int wave) const {
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i) {
+            if (pos[i] >= 0) {
+                int y = oy + (pos[i] & 0xff), x = ox + ((pos[i] >> 8) & 0xff);
+                y = y < 0 ? 0 : (y < H - 1 ? y : H - 1);
+                x = x < 0 ? 0 : (x < W - 1 ? x : W - 1);
+                global_to_lds_16(plane_base + ((y * W + x) * Traits<T>::kKeyBytes + (pos[i] >> 16) * 16),
+                                 lds_base + (wave + i * NWAVES) * kWave * 16);
+            }
+        }
+    }
+};
+
+// Transposing 8-byte LDS read (ds_read_b64_tr_b16), checked on hardware: inside each group of 16
+// lanes, lane i receives as element j (j = 0..3) the 16-bit element (i % 4) of the 8 bytes
+// addressed by lane 4 j + i / 4 of the group.  With lane s of the group pointing at channels
+// 4 (s % 4) .. + 3 of position P[s / 4], lane i gets channel i of the four positions P[0..3]:
+// an MFMA operand whose contraction index runs over positions, read from the natural layout.
+struct u32x2 {
+    uint32_t x, y;
+};
+__device__ __forceinline__ u32x2 lds_read_tr16(int addr) {
+    const i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(uintptr_t)(unsigned)addr);
+    return __builtin_bit_cast(u32x2, v);
+}
+
 }  // namespace na2d
