@@ -160,29 +160,43 @@ __global__ __launch_bounds__(256) void rpb_partial_kernel(const T *__restrict__ 
 }
 
 // d_rpb[h, cell] = sum over (batch, group) of partial[(b * heads + h) * groups + group][cell].
-// One workgroup of 16 waves per head: wave w adds the partials whose running index is w mod 16,
-// in index order; the 16 sub-sums are then added in wave order.
+// One workgroup of 16 waves per head and block of 64 cells (a lane is a cell, so a wave reads 256
+// contiguous bytes of a partial): wave w adds the partials whose running index is w mod 16, in
+// index order, eight independent loads at a time; the 16 sub-sums are then added in wave order.
 __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const float *__restrict__ partial,
                                                                            float *__restrict__ d_rpb, int B, int heads,
                                                                            int groups, int cells) {
-    extern __shared__ __align__(16) char lds[];
-    float *sub = reinterpret_cast<float *>(lds);   // [16][cells]
-    const int h = blockIdx.x;
+    __shared__ float sub[kRpbFinalWaves][kWave];
+    const int cell_blocks = (cells + kWave - 1) / kWave;
+    const int h = blockIdx.x / cell_blocks;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int cell = (blockIdx.x % cell_blocks) * kWave + lane;
     const int n = B * groups;
-    for (int cell = lane; cell < cells; cell += kWave) {
-        float acc = 0.f;
-#pragma unroll 4
-        for (int i = wave; i < n; i += kRpbFinalWaves) {
+    float acc = 0.f;
+    if (cell < cells) {
+        constexpr int U = 8;
+        int i = wave;
+        for (; i + (U - 1) * kRpbFinalWaves < n; i += U * kRpbFinalWaves) {
+            float v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int iu = i + u * kRpbFinalWaves;
+                const int b = iu / groups, g = iu - b * groups;
+                v[u] = partial[((size_t)(b * heads + h) * groups + g) * cells + cell];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc += v[u];
+        }
+        for (; i < n; i += kRpbFinalWaves) {
             const int b = i / groups, g = i - b * groups;
             acc += partial[((size_t)(b * heads + h) * groups + g) * cells + cell];
         }
-        sub[wave * cells + cell] = acc;
     }
+    sub[wave][lane] = acc;
     __syncthreads();
-    for (int cell = threadIdx.x; cell < cells; cell += kRpbFinalWaves * kWave) {
-        float s = sub[cell];
-        for (int w = 1; w < kRpbFinalWaves; ++w) s += sub[w * cells + cell];
+    if (wave == 0 && cell < cells) {
+        float s = sub[0][lane];
+        for (int w = 1; w < kRpbFinalWaves; ++w) s += sub[w][lane];
         d_rpb[(size_t)h * cells + cell] = s;
     }
 }
@@ -210,9 +224,8 @@ static hipError_t launch_rpb_bwd_t(const Problem &p, const void *ds, float *d_rp
                        static_cast<const T *>(ds), static_cast<float *>(workspace), p.H, p.W, sp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(rpb_final_kernel, dim3(p.heads), dim3(kRpbFinalWaves * kWave),
-                       kRpbFinalWaves * C::CELLS * sizeof(float), s, static_cast<const float *>(workspace), d_rpb, p.B,
-                       p.heads, sp.groups_per_plane, C::CELLS);
+    hipLaunchKernelGGL(rpb_final_kernel, dim3(p.heads * ((C::CELLS + kWave - 1) / kWave)), dim3(kRpbFinalWaves * kWave), 0, s,
+                       static_cast<const float *>(workspace), d_rpb, p.B, p.heads, sp.groups_per_plane, C::CELLS);
     return hipGetLastError();
 }
 
