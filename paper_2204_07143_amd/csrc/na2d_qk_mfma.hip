@@ -251,6 +251,270 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void qk_mfma_kern
     if (out_pending) flush_strip();
 }
 
+// ---- small windows (K <= 7): one patch per wave, everything asynchronous -------------------
+//
+// Eight waves share a 16 x 8 query tile, one 4 x 4 patch each, so a SIMD holds four waves whose
+// LDS, matrix and conversion work overlap.  The key halo reaches LDS by direct loads in its
+// natural 64-byte-per-key layout (consecutive keys of an operand block are consecutive in LDS,
+// so the 16-byte operand reads do not collide), into one of two buffers: the next tile's halo
+// arrives while this tile is computed.  Results go to one of two staging images of the tile's
+// eight row runs (phase-free: slot tables do not depend on where a run starts in memory); wave w
+// streams row w of the previous tile to global memory while the current tile is computed.  One
+// workgroup barrier per tile.  Workgroups walk down the columns of a plane, so a wave's window
+// and bias tables change only at the top and bottom of the map.
+template <typename T, int K>
+struct QkSmallCfg {
+    using P = Patch<K>;
+    static constexpr int STRIPS = 2;
+    static constexpr int WAVES = 4 * STRIPS;
+    static constexpr int TY = 4 * STRIPS;
+    static constexpr int HALO_H = TY + K - 1, HALO_W = kTileX + K - 1;
+    using Halo = HaloDma<T, HALO_H, HALO_W, WAVES>;
+    static constexpr int KK = K * K, NB = 2 * K - 1;
+    static constexpr int kThreads = kWave * WAVES;
+    static constexpr int kHaloBytes = Halo::kBytes;
+    static constexpr int kRowBytes = kTileX * KK * (int)sizeof(T);
+    static constexpr int kRowPitch = (kRowBytes + 15) & ~15;
+    static constexpr int kStageBytes = TY * kRowPitch;
+    static constexpr int kDumpBytes = kThreads * 4;              // one word per thread for results outside its window
+    static constexpr int kParity = kStageBytes + kDumpBytes;     // distance between the two staging images
+    static constexpr int kLdsBytes = 2 * kHaloBytes + 2 * kParity;
+    static_assert(kParity < 65536, "the second staging image is reached through the 16-bit offset of the LDS store");
+};
+
+struct QkTileIdx {
+    int tiy, tix, plane;
+};
+template <int V> struct IntC {
+    static constexpr int value = V;
+};
+
+// One row run of the tile, LDS -> global: 16-byte stores for the chunks that are aligned in global
+// memory (their LDS source is then aligned to 2 bytes only), single elements at the two ends.
+template <typename T>
+__device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, int lds_row, int lane) {
+    const int mis = (int)(g0 & 15);
+    int head = (16 - mis) & 15;
+    head = head < nbytes ? head : nbytes;
+    const int nbody = (nbytes - head) >> 4;
+    char *ga = gbase + g0;
+    struct __attribute__((packed, aligned(2))) Chunk {
+        u32x4 v;
+    };
+    u32x4 v[2];
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int c = lane + it * kWave;
+        if (c < nbody) v[it] = lds_ptr<Chunk>(lds_row + head + 16 * c)->v;
+    }
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int c = lane + it * kWave;
+        if (c < nbody) *reinterpret_cast<u32x4 *>(ga + head + 16 * c) = v[it];
+    }
+    const int hb = lane * (int)sizeof(T);
+    if (hb < head) *reinterpret_cast<T *>(ga + hb) = *lds_ptr<T>(lds_row + hb);
+    const int tb = head + 16 * nbody + (lane - 16) * (int)sizeof(T);
+    if (lane >= 16 && tb < nbytes) *reinterpret_cast<T *>(ga + tb) = *lds_ptr<T>(lds_row + tb);
+}
+
+template <typename T, int K>
+__global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
+    const T *__restrict__ x, const T *__restrict__ y, const T *__restrict__ rpb, float scale, T *__restrict__ logits, int H,
+    int W, int heads, int tiles_x, int tiles_y, int ntiles, int tiles_per_wg) {
+    using C = QkSmallCfg<T, K>;
+    using P = Patch<K>;
+    static_assert(C::kRowBytes <= 2 * kWave * 16, "a row run is flushed in two passes of the wave");
+    static_assert(C::kThreads == 512, "launch bounds");
+    constexpr int SZ = (int)sizeof(T);
+    extern __shared__ __align__(16) char lds[];
+
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int strip = wave >> 2, p = wave & 3;
+    const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
+    const int lds0 = lds_addr(lds);
+    const int stage0 = lds0 + 2 * C::kHaloBytes;
+    const int my_dump = stage0 + C::kStageBytes + tid * 4;
+    // this lane's query inside the first staging image
+    const int lane_stage = stage0 + (4 * strip + jy) * C::kRowPitch + (4 * p + jx) * C::KK * SZ;
+
+    int koff[P::NBLK];   // A-operand offsets of this lane inside a patch halo (keys past the end re-read the last one)
+#pragma unroll
+    for (int b = 0; b < P::NBLK; ++b) {
+        int h = 16 * b + j;
+        h = h < P::NKEY ? h : P::NKEY - 1;
+        const int hy = P::row_of(h), hx = h - hy * P::PW;
+        koff[b] = (hy * C::HALO_W + hx) * Traits<T>::kKeyBytes + g * 16;
+    }
+    uint32_t bias2[P::NEL / 2];   // bias of this lane's results, two per register in the storage type (exact)
+    int slotaddr[P::NEL];
+#pragma unroll
+    for (int e = 0; e < P::NEL; ++e) slotaddr[e] = my_dump;
+#pragma unroll
+    for (int e = 0; e < P::NEL / 2; ++e) bias2[e] = 0u;
+    int cur_bias_key = -1, cur_wy = -100000, cur_wx = -100000;
+
+    typename C::Halo halo;
+    halo.init(wave, lane);
+
+    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    const int t_begin = wg * tiles_per_wg;
+    const int t_end = (wg + 1) * tiles_per_wg < ntiles ? (wg + 1) * tiles_per_wg : ntiles;
+    if (t_begin >= t_end) return;
+
+    // tiles are numbered down the columns of a plane
+    QkTileIdx nxt;
+    nxt.tiy = t_begin % tiles_y;
+    nxt.tix = (t_begin / tiles_y) % tiles_x;
+    nxt.plane = t_begin / (tiles_y * tiles_x);
+    auto advance = [&](QkTileIdx &c) {
+        if (++c.tiy == tiles_y) {
+            c.tiy = 0;
+            if (++c.tix == tiles_x) {
+                c.tix = 0;
+                ++c.plane;
+            }
+        }
+    };
+    u32x4 qnext;
+    // halo of tile c -> halo buffer `par`, and this lane's query chunk -> qnext
+    auto issue = [&](const QkTileIdx &c, int par) {
+        const int ty0 = c.tiy * C::TY, tx0 = c.tix * kTileX;
+        const size_t plane_q = (size_t)c.plane * H * W;
+        halo.issue(reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes, H, W, halo_origin(ty0, C::TY, H, K),
+                   halo_origin(tx0, kTileX, W, K), lds0 + par * C::kHaloBytes, wave);
+        int qy = ty0 + 4 * strip + jy, qx = tx0 + 4 * p + jx;   // queries outside the map: any vector, results dropped
+        qy = qy < H - 1 ? qy : H - 1;
+        qx = qx < W - 1 ? qx : W - 1;
+        qnext = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) +
+                                                 (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes + g * 16);
+    };
+    // row `wave` of tile c, staging image `par` -> global memory
+    auto flush = [&](const QkTileIdx &c, int par) {
+        const int ty0 = c.tiy * C::TY, tx0 = c.tix * kTileX;
+        const int qy = ty0 + wave;
+        if (qy < H) {
+            const int nvalid = (W - tx0) < kTileX ? (W - tx0) : kTileX;
+            const size_t g0 = (((size_t)c.plane * H + qy) * W + tx0) * C::KK * SZ;
+            flush_run<T>(reinterpret_cast<char *>(logits), g0, nvalid * C::KK * SZ, stage0 + par * C::kParity + wave * C::kRowPitch,
+                         lane);
+        }
+    };
+
+    auto compute = [&](const QkTileIdx &c, auto par_c, const u32x4 &qreg) {
+        constexpr int PAR = decltype(par_c)::value;
+        const int ty0 = c.tiy * C::TY, tx0 = c.tix * kTileX;
+        const int sy0 = ty0 + 4 * strip, px0 = tx0 + 4 * p;
+        if (sy0 >= H || px0 >= W) return;
+        const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);
+        const int oy = halo_origin(sy0, 4, H, K), ox = halo_origin(px0, 4, W, K);   // patch halo origin
+        const int dy = oy - (sy0 - P::R), dx = ox - (px0 - P::R);                   // 0 away from the borders
+        const int qy = sy0 + jy, qx = px0 + jx;
+        const bool q_ok = qy < H && qx < W;
+        const int want_wy = q_ok ? win_start(qy, H, K) - oy : 100000;
+        const int want_wx = q_ok ? win_start(qx, W, K) - ox : 100000;
+        // The bias of (query, key) depends on key - query only: a per-lane constant table, except that a
+        // displaced patch origin shifts it.
+        const int head = c.plane % heads;
+        const int bias_key = (head * 16 + dy + 8) * 16 + dx + 8;
+        if (bias_key != cur_bias_key) {
+            cur_bias_key = bias_key;
+            int gv = g;
+            asm volatile("" : "+v"(gv));   // keep the index arithmetic inside this rare block
+#pragma unroll
+            for (int e = 0; e < P::NEL; ++e) {
+                const int h = 16 * (e >> 2) + 4 * gv + (e & 3);
+                const int hy = P::row_of(h), hx = h - hy * P::PW;
+                int u = hy - jy + P::R + dy, v = hx - jx + P::R + dx;
+                u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);   // cells outside the table belong to keys
+                v = v < 0 ? 0 : (v > C::NB - 1 ? C::NB - 1 : v);   // outside every window: value unused
+                const uint32_t bits =
+                    rpb ? (uint32_t) reinterpret_cast<const uint16_t *>(rpb)[(size_t)head * C::NB * C::NB + u * C::NB + v] : 0u;
+                bias2[e >> 1] = (e & 1) ? (bias2[e >> 1] & 0xffffu) | (bits << 16) : bits;
+            }
+        }
+        if (__any(want_wy != cur_wy || want_wx != cur_wx)) {
+            cur_wy = want_wy;
+            cur_wx = want_wx;
+            int gv = g;
+            asm volatile("" : "+v"(gv));
+#pragma unroll
+            for (int e = 0; e < P::NEL; ++e) {
+                const int h = 16 * (e >> 2) + 4 * gv + (e & 3);
+                const int hy = P::row_of(h), hx = h - hy * P::PW;
+                const int a = hy - want_wy, cc = hx - want_wx;
+                const bool ok = h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)cc < (unsigned)K;
+                slotaddr[e] = ok ? lane_stage + (a * K + cc) * SZ : my_dump;
+            }
+        }
+        const int kp = lds0 + PAR * C::kHaloBytes + ((oy - hoy) * C::HALO_W + (ox - hox)) * Traits<T>::kKeyBytes;
+        f32x4 acc[P::NBLK];
+#pragma unroll
+        for (int b = 0; b < P::NBLK; ++b) {
+            const u32x4 a = *lds_ptr<u32x4>(kp + koff[b]);
+            acc[b] = mfma_16x16x32<T>(a, qreg, f32x4{0.f, 0.f, 0.f, 0.f});
+        }
+#pragma unroll
+        for (int e = 0; e < P::NEL; ++e) {
+            const uint16_t bb = (uint16_t)((e & 1) ? bias2[e >> 1] >> 16 : bias2[e >> 1] & 0xffffu);
+            const float v = __builtin_fmaf(scale, acc[e >> 2][e & 3], to_f32(__builtin_bit_cast(T, bb)));
+            *lds_ptr<T>(slotaddr[e] + PAR * C::kParity) = from_f32<T>(v);
+        }
+    };
+
+    QkTileIdx cur = nxt, prev = nxt;
+    issue(cur, 0);
+    bool have_prev = false;
+    int t = t_begin;
+    auto step = [&](auto par_c) {
+        constexpr int PAR = decltype(par_c)::value;
+        wait_global_loads();   // this tile's halo and query chunk have landed
+        __syncthreads();       // ... for every wave; the previous tile is fully staged, its halo no longer read
+        const u32x4 qreg = qnext;
+        if (t + 1 < t_end) {
+            advance(nxt);
+            issue(nxt, PAR ^ 1);
+        }
+        if (have_prev) flush(prev, PAR ^ 1);
+        compute(cur, par_c, qreg);
+        prev = cur;
+        cur = nxt;
+        have_prev = true;
+        ++t;
+    };
+    while (t < t_end) {
+        step(IntC<0>{});
+        if (t < t_end) step(IntC<1>{});
+    }
+    __syncthreads();
+    flush(prev, (t - t_begin - 1) & 1);
+}
+
+template <typename T, int K>
+static hipError_t launch_qk_mfma_small_t(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
+                                         void *logits, hipStream_t s) {
+    using C = QkSmallCfg<T, K>;
+    static_assert(C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
+    const int ntiles = tiles_x * tiles_y * p.planes();
+    const int max_wgs = 256 * 2;
+    const int tiles_per_wg = (ntiles + max_wgs - 1) / max_wgs;
+    const int nwg = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
+    auto kern = qk_mfma_small_kernel<T, K>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
+                       static_cast<const T *>(x), static_cast<const T *>(y), static_cast<const T *>(rpb), scale,
+                       static_cast<T *>(logits), p.H, p.W, p.heads, tiles_x, tiles_y, ntiles, tiles_per_wg);
+    return hipGetLastError();
+}
+
 template <typename T, int K>
 static hipError_t launch_qk_mfma_t(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
                                    void *logits, hipStream_t s) {
@@ -281,9 +545,15 @@ hipError_t launch_qk_mfma(const Problem &p, const void *x, const void *y, const 
                           hipStream_t s) {
     if (p.dtype == NA2D_F16) {
         using T = f16_t;
+        if (p.K == 3) return launch_qk_mfma_small_t<T, 3>(p, x, y, rpb, scale, logits, s);
+        if (p.K == 5) return launch_qk_mfma_small_t<T, 5>(p, x, y, rpb, scale, logits, s);
+        if (p.K == 7) return launch_qk_mfma_small_t<T, 7>(p, x, y, rpb, scale, logits, s);
         NA2D_DISPATCH_K(p.K, return (launch_qk_mfma_t<T, K>(p, x, y, rpb, scale, logits, s)));
     } else if (p.dtype == NA2D_BF16) {
         using T = bf16_t;
+        if (p.K == 3) return launch_qk_mfma_small_t<T, 3>(p, x, y, rpb, scale, logits, s);
+        if (p.K == 5) return launch_qk_mfma_small_t<T, 5>(p, x, y, rpb, scale, logits, s);
+        if (p.K == 7) return launch_qk_mfma_small_t<T, 7>(p, x, y, rpb, scale, logits, s);
         NA2D_DISPATCH_K(p.K, return (launch_qk_mfma_t<T, K>(p, x, y, rpb, scale, logits, s)));
     }
     return hipErrorInvalidValue;
