@@ -205,6 +205,22 @@ struct HaloDma {
             pos[i] = q < TOTAL ? (ry | (rx << 8) | (c << 16)) : -1;
         }
     }
+    // Split form for loops that copy the same rectangle of many planes: the clamped byte offsets of
+    // this lane's chunks inside a plane (-1: nothing), then one load per item from a plane's base.
+    __device__ __forceinline__ void offsets(int H, int W, int oy, int ox, int (&off)[PER_WAVE]) const {
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i) {
+            int y = oy + (pos[i] & 0xff), x = ox + ((pos[i] >> 8) & 0xff);
+            y = y < 0 ? 0 : (y < H - 1 ? y : H - 1);
+            x = x < 0 ? 0 : (x < W - 1 ? x : W - 1);
+            off[i] = pos[i] >= 0 ? (y * W + x) * Traits<T>::kKeyBytes + (pos[i] >> 16) * 16 : -1;
+        }
+    }
+    __device__ static __forceinline__ void issue_at(const char *plane_base, const int (&off)[PER_WAVE], int lds_base, int wave) {
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i)
+            if (off[i] >= 0) global_to_lds_16(plane_base + off[i], lds_base + (wave + i * NWAVES) * kWave * 16);
+    }
     __device__ __forceinline__ void issue(const char *plane_base, int H, int W, int oy, int ox, int lds_base, int wave) const {
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {

@@ -282,9 +282,6 @@ struct QkSmallCfg {
     static_assert(kParity < 65536, "the second staging image is reached through the 16-bit offset of the LDS store");
 };
 
-struct QkTileIdx {
-    int tiy, tix, plane;
-};
 template <int V> struct IntC {
     static constexpr int value = V;
 };
@@ -321,7 +318,7 @@ __device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, in
 template <typename T, int K>
 __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
     const T *__restrict__ x, const T *__restrict__ y, const T *__restrict__ rpb, float scale, T *__restrict__ logits, int H,
-    int W, int heads, int tiles_x, int tiles_y, int ntiles, int tiles_per_wg) {
+    int W, int heads, int nb, int tiles_y, int units, int splits) {
     using C = QkSmallCfg<T, K>;
     using P = Patch<K>;
     static_assert(C::kRowBytes <= 2 * kWave * 16, "a row run is flushed in two passes of the wave");
@@ -336,123 +333,96 @@ __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
     const int lds0 = lds_addr(lds);
     const int stage0 = lds0 + 2 * C::kHaloBytes;
     const int my_dump = stage0 + C::kStageBytes + tid * 4;
-    // this lane's query inside the first staging image
-    const int lane_stage = stage0 + (4 * strip + jy) * C::kRowPitch + (4 * p + jx) * C::KK * SZ;
 
-    int koff[P::NBLK];   // A-operand offsets of this lane inside a patch halo (keys past the end re-read the last one)
+    // A workgroup keeps one tile position and one head and walks a range of the batch: everything
+    // that depends on the position (halo geometry, window and bias tables, load offsets) is built once.
+    // Neighbouring positions of a plane are handled by other workgroups at about the same time, so the
+    // halo overlap is re-read from L2 while it is hot.
+    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    if (wg >= units * splits) return;
+    const int unit = wg / splits, split = wg - unit * splits;
+    const int pos = unit / heads, head = unit - pos * heads;
+    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
+    const int b_begin = (split * nb) / splits, b_end = ((split + 1) * nb) / splits;
+    if (b_begin >= b_end) return;
+
+    const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);   // tile halo origin
+    const int sy0 = ty0 + 4 * strip, px0 = tx0 + 4 * p;                                     // this wave's patch
+    const bool active = sy0 < H && px0 < W;
+    const int oy = halo_origin(sy0 < H ? sy0 : H - 1, 4, H, K), ox = halo_origin(px0 < W ? px0 : W - 1, 4, W, K);
+    const int dy = oy - (sy0 - P::R), dx = ox - (px0 - P::R);   // 0 away from the borders
+    const int qy = sy0 + jy, qx = px0 + jx;
+    const bool q_ok = qy < H && qx < W;
+
+    // A operand: offsets of this lane's keys inside the tile halo (keys past the end of the patch halo
+    // re-read its last one)
+    int koff[P::NBLK];
 #pragma unroll
     for (int b = 0; b < P::NBLK; ++b) {
         int h = 16 * b + j;
         h = h < P::NKEY ? h : P::NKEY - 1;
         const int hy = P::row_of(h), hx = h - hy * P::PW;
-        koff[b] = (hy * C::HALO_W + hx) * Traits<T>::kKeyBytes + g * 16;
+        koff[b] = lds0 + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + g * 16;
     }
-    uint32_t bias2[P::NEL / 2];   // bias of this lane's results, two per register in the storage type (exact)
+    // Where this lane's results go: result e is the dot product of query j with patch-halo key
+    // 16 (e / 4) + 4 g + e % 4.  Inside the query's window it is stored at its slot of the query's row
+    // run in the staging image, outside it goes to the lane's dump word.  The bias of (query, key)
+    // depends on key - query only (Eq. 2); it is kept two per register in the storage type.
+    uint32_t bias2[P::NEL / 2];
     int slotaddr[P::NEL];
+    {
+        const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
+        const int lane_stage = stage0 + (4 * strip + jy) * C::kRowPitch + (4 * p + jx) * C::KK * SZ;
 #pragma unroll
-    for (int e = 0; e < P::NEL; ++e) slotaddr[e] = my_dump;
-#pragma unroll
-    for (int e = 0; e < P::NEL / 2; ++e) bias2[e] = 0u;
-    int cur_bias_key = -1, cur_wy = -100000, cur_wx = -100000;
+        for (int e = 0; e < P::NEL; ++e) {
+            const int h = 16 * (e >> 2) + 4 * g + (e & 3);
+            const int hy = P::row_of(h), hx = h - hy * P::PW;
+            const int a = hy - wy, cc = hx - wx;
+            const bool ok = q_ok && h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)cc < (unsigned)K;
+            slotaddr[e] = ok ? lane_stage + (a * K + cc) * SZ : my_dump;
+            int u = hy - jy + P::R + dy, v = hx - jx + P::R + dx;
+            u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);   // cells outside the table belong to keys
+            v = v < 0 ? 0 : (v > C::NB - 1 ? C::NB - 1 : v);   // outside every window: value unused
+            const uint32_t bits =
+                rpb ? (uint32_t) reinterpret_cast<const uint16_t *>(rpb)[(size_t)head * C::NB * C::NB + u * C::NB + v] : 0u;
+            if (e & 1)
+                bias2[e >> 1] |= bits << 16;
+            else
+                bias2[e >> 1] = bits;
+        }
+    }
 
+    // loads: the halo chunks of this lane and its 16 bytes of its query, as byte offsets inside a plane
     typename C::Halo halo;
     halo.init(wave, lane);
+    int hoff[C::Halo::PER_WAVE];
+    halo.offsets(H, W, hoy, hox, hoff);
+    const int qoff = ((qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1)) * Traits<T>::kKeyBytes + g * 16;
+    const size_t plane_in = (size_t)H * W * Traits<T>::kKeyBytes;   // bytes per plane of x / y
+    const size_t plane_out = (size_t)H * W * C::KK * SZ;            // ... of the logits
+    // stores: wave w streams row w of the tile
+    const int frow = ty0 + wave;
+    const int fbytes = ((W - tx0) < kTileX ? (W - tx0) : kTileX) * C::KK * SZ;
+    const size_t foff = ((size_t)frow * W + tx0) * C::KK * SZ;
 
-    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
-    const int t_begin = wg * tiles_per_wg;
-    const int t_end = (wg + 1) * tiles_per_wg < ntiles ? (wg + 1) * tiles_per_wg : ntiles;
-    if (t_begin >= t_end) return;
-
-    // tiles are numbered down the columns of a plane
-    QkTileIdx nxt;
-    nxt.tiy = t_begin % tiles_y;
-    nxt.tix = (t_begin / tiles_y) % tiles_x;
-    nxt.plane = t_begin / (tiles_y * tiles_x);
-    auto advance = [&](QkTileIdx &c) {
-        if (++c.tiy == tiles_y) {
-            c.tiy = 0;
-            if (++c.tix == tiles_x) {
-                c.tix = 0;
-                ++c.plane;
-            }
-        }
-    };
     u32x4 qnext;
-    // halo of tile c -> halo buffer `par`, and this lane's query chunk -> qnext
-    auto issue = [&](const QkTileIdx &c, int par) {
-        const int ty0 = c.tiy * C::TY, tx0 = c.tix * kTileX;
-        const size_t plane_q = (size_t)c.plane * H * W;
-        halo.issue(reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes, H, W, halo_origin(ty0, C::TY, H, K),
-                   halo_origin(tx0, kTileX, W, K), lds0 + par * C::kHaloBytes, wave);
-        int qy = ty0 + 4 * strip + jy, qx = tx0 + 4 * p + jx;   // queries outside the map: any vector, results dropped
-        qy = qy < H - 1 ? qy : H - 1;
-        qx = qx < W - 1 ? qx : W - 1;
-        qnext = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) +
-                                                 (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes + g * 16);
+    auto issue = [&](int b, int par) {
+        const size_t plane = (size_t)b * heads + head;
+        C::Halo::issue_at(reinterpret_cast<const char *>(y) + plane * plane_in, hoff, lds0 + par * C::kHaloBytes, wave);
+        qnext = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) + plane * plane_in + qoff);
     };
-    // row `wave` of tile c, staging image `par` -> global memory
-    auto flush = [&](const QkTileIdx &c, int par) {
-        const int ty0 = c.tiy * C::TY, tx0 = c.tix * kTileX;
-        const int qy = ty0 + wave;
-        if (qy < H) {
-            const int nvalid = (W - tx0) < kTileX ? (W - tx0) : kTileX;
-            const size_t g0 = (((size_t)c.plane * H + qy) * W + tx0) * C::KK * SZ;
-            flush_run<T>(reinterpret_cast<char *>(logits), g0, nvalid * C::KK * SZ, stage0 + par * C::kParity + wave * C::kRowPitch,
-                         lane);
-        }
+    auto flush = [&](int b, int par) {
+        if (frow < H)
+            flush_run<T>(reinterpret_cast<char *>(logits), ((size_t)b * heads + head) * plane_out + foff, fbytes,
+                         stage0 + par * C::kParity + wave * C::kRowPitch, lane);
     };
-
-    auto compute = [&](const QkTileIdx &c, auto par_c, const u32x4 &qreg) {
+    auto compute = [&](auto par_c, const u32x4 &qreg) {
         constexpr int PAR = decltype(par_c)::value;
-        const int ty0 = c.tiy * C::TY, tx0 = c.tix * kTileX;
-        const int sy0 = ty0 + 4 * strip, px0 = tx0 + 4 * p;
-        if (sy0 >= H || px0 >= W) return;
-        const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);
-        const int oy = halo_origin(sy0, 4, H, K), ox = halo_origin(px0, 4, W, K);   // patch halo origin
-        const int dy = oy - (sy0 - P::R), dx = ox - (px0 - P::R);                   // 0 away from the borders
-        const int qy = sy0 + jy, qx = px0 + jx;
-        const bool q_ok = qy < H && qx < W;
-        const int want_wy = q_ok ? win_start(qy, H, K) - oy : 100000;
-        const int want_wx = q_ok ? win_start(qx, W, K) - ox : 100000;
-        // The bias of (query, key) depends on key - query only: a per-lane constant table, except that a
-        // displaced patch origin shifts it.
-        const int head = c.plane % heads;
-        const int bias_key = (head * 16 + dy + 8) * 16 + dx + 8;
-        if (bias_key != cur_bias_key) {
-            cur_bias_key = bias_key;
-            int gv = g;
-            asm volatile("" : "+v"(gv));   // keep the index arithmetic inside this rare block
-#pragma unroll
-            for (int e = 0; e < P::NEL; ++e) {
-                const int h = 16 * (e >> 2) + 4 * gv + (e & 3);
-                const int hy = P::row_of(h), hx = h - hy * P::PW;
-                int u = hy - jy + P::R + dy, v = hx - jx + P::R + dx;
-                u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);   // cells outside the table belong to keys
-                v = v < 0 ? 0 : (v > C::NB - 1 ? C::NB - 1 : v);   // outside every window: value unused
-                const uint32_t bits =
-                    rpb ? (uint32_t) reinterpret_cast<const uint16_t *>(rpb)[(size_t)head * C::NB * C::NB + u * C::NB + v] : 0u;
-                bias2[e >> 1] = (e & 1) ? (bias2[e >> 1] & 0xffffu) | (bits << 16) : bits;
-            }
-        }
-        if (__any(want_wy != cur_wy || want_wx != cur_wx)) {
-            cur_wy = want_wy;
-            cur_wx = want_wx;
-            int gv = g;
-            asm volatile("" : "+v"(gv));
-#pragma unroll
-            for (int e = 0; e < P::NEL; ++e) {
-                const int h = 16 * (e >> 2) + 4 * gv + (e & 3);
-                const int hy = P::row_of(h), hx = h - hy * P::PW;
-                const int a = hy - want_wy, cc = hx - want_wx;
-                const bool ok = h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)cc < (unsigned)K;
-                slotaddr[e] = ok ? lane_stage + (a * K + cc) * SZ : my_dump;
-            }
-        }
-        const int kp = lds0 + PAR * C::kHaloBytes + ((oy - hoy) * C::HALO_W + (ox - hox)) * Traits<T>::kKeyBytes;
+        if (!active) return;
         f32x4 acc[P::NBLK];
 #pragma unroll
         for (int b = 0; b < P::NBLK; ++b) {
-            const u32x4 a = *lds_ptr<u32x4>(kp + koff[b]);
+            const u32x4 a = *lds_ptr<u32x4>(koff[b] + PAR * C::kHaloBytes);
             acc[b] = mfma_16x16x32<T>(a, qreg, f32x4{0.f, 0.f, 0.f, 0.f});
         }
 #pragma unroll
@@ -463,32 +433,38 @@ __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
         }
     };
 
-    QkTileIdx cur = nxt, prev = nxt;
-    issue(cur, 0);
-    bool have_prev = false;
-    int t = t_begin;
+    issue(b_begin, 0);
+    int b = b_begin;
     auto step = [&](auto par_c) {
         constexpr int PAR = decltype(par_c)::value;
         wait_global_loads();   // this tile's halo and query chunk have landed
         __syncthreads();       // ... for every wave; the previous tile is fully staged, its halo no longer read
         const u32x4 qreg = qnext;
-        if (t + 1 < t_end) {
-            advance(nxt);
-            issue(nxt, PAR ^ 1);
-        }
-        if (have_prev) flush(prev, PAR ^ 1);
-        compute(cur, par_c, qreg);
-        prev = cur;
-        cur = nxt;
-        have_prev = true;
-        ++t;
+        if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
+        if (b > b_begin) flush(b - 1, PAR ^ 1);
+        compute(par_c, qreg);
+        ++b;
     };
-    while (t < t_end) {
+    while (b < b_end) {
         step(IntC<0>{});
-        if (t < t_end) step(IntC<1>{});
+        if (b < b_end) step(IntC<1>{});
     }
     __syncthreads();
-    flush(prev, (t - t_begin - 1) & 1);
+    flush(b_end - 1, (b_end - b_begin - 1) & 1);
+}
+
+// Work split of the position-stationary kernels: a unit is a (tile position, head) pair; the batch is
+// cut into `splits` ranges so that about two workgroups per compute unit exist.
+struct UnitSplit {
+    int units, splits;
+};
+static inline UnitSplit unit_split(int tiles_x, int tiles_y, int heads, int nb) {
+    UnitSplit u;
+    u.units = tiles_x * tiles_y * heads;
+    int s = (256 * 2) / u.units;
+    s = s < 1 ? 1 : s;
+    u.splits = s < nb ? s : nb;
+    return u;
 }
 
 template <typename T, int K>
@@ -497,10 +473,7 @@ static hipError_t launch_qk_mfma_small_t(const Problem &p, const void *x, const 
     using C = QkSmallCfg<T, K>;
     static_assert(C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
-    const int ntiles = tiles_x * tiles_y * p.planes();
-    const int max_wgs = 256 * 2;
-    const int tiles_per_wg = (ntiles + max_wgs - 1) / max_wgs;
-    const int nwg = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
+    const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
     auto kern = qk_mfma_small_kernel<T, K>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -509,9 +482,9 @@ static hipError_t launch_qk_mfma_small_t(const Problem &p, const void *x, const 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
+    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(x), static_cast<const T *>(y), static_cast<const T *>(rpb), scale,
-                       static_cast<T *>(logits), p.H, p.W, p.heads, tiles_x, tiles_y, ntiles, tiles_per_wg);
+                       static_cast<T *>(logits), p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits);
     return hipGetLastError();
 }
 
