@@ -290,6 +290,227 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void fused_mfma_k
     }
 }
 
+// ---- small windows (K <= 7): one patch per wave, halos loaded straight into LDS ---------------
+//
+// Eight waves share a 16 x 8 query tile, one 4 x 4 patch each (four waves per SIMD).  A workgroup
+// keeps one tile position and one head and walks a range of the batch, so the window mask, the bias
+// table and every address are built once.  The key and the value halo of a tile reach LDS by direct
+// loads in their natural layout, into one of two buffer pairs: the next tile's halos arrive while
+// this tile is computed (one workgroup barrier per tile).  Keys are read as 16-byte A operands;
+// values are read with the transposing LDS read, which hands each lane one channel of four halo
+// positions, so the PV product contracts over positions without a transposed copy.  The halo
+// positions are numbered h = hy * (K+3) + hx; MFMA pair m of the PV product contracts over the
+// blocks 2m and 2m+1 of the logits, in the order the logits' MFMA left them in the lanes.
+template <typename T, int K>
+struct FusedSmallCfg {
+    using P = Patch<K>;
+    static constexpr int STRIPS = 2;
+    static constexpr int WAVES = 4 * STRIPS;
+    static constexpr int TY = 4 * STRIPS;
+    static constexpr int HALO_H = TY + K - 1, HALO_W = kTileX + K - 1;
+    using Halo = HaloDma<T, HALO_H, HALO_W, WAVES>;
+    static constexpr int NB = 2 * K - 1;
+    static constexpr int NPAIR = (P::NBLK + 1) / 2;   // PV MFMAs per 16 channels
+    static constexpr int NBLK2 = 2 * NPAIR;           // logits blocks, padded to whole pairs
+    static constexpr int kThreads = kWave * WAVES;
+    static constexpr int kHaloBytes = Halo::kBytes;
+    static constexpr int kStageBytes = 2 * kHaloBytes;   // keys, then values
+    static constexpr int kLdsBytes = 2 * kStageBytes;
+};
+
+template <typename T, int K>
+__global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__restrict__ q, const T *__restrict__ k,
+                                                                  const T *__restrict__ v, const T *__restrict__ rpb,
+                                                                  float scale, T *__restrict__ out, float *__restrict__ lse,
+                                                                  int H, int W, int heads, int nb, int tiles_y, int units,
+                                                                  int splits) {
+    using C = FusedSmallCfg<T, K>;
+    using P = Patch<K>;
+    static_assert(C::kThreads == 512, "launch bounds");
+    constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+    extern __shared__ __align__(16) char lds[];
+
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int strip = wave >> 2, p = wave & 3;
+    const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
+    const int lds0 = lds_addr(lds);
+
+    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    if (wg >= units * splits) return;
+    const int unit = wg / splits, split = wg - unit * splits;
+    const int pos = unit / heads, head = unit - pos * heads;
+    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
+    const int b_begin = (split * nb) / splits, b_end = ((split + 1) * nb) / splits;
+    if (b_begin >= b_end) return;
+
+    const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);   // tile halo origin
+    const int sy0 = ty0 + 4 * strip, px0 = tx0 + 4 * p;                                     // this wave's patch
+    const bool active = sy0 < H && px0 < W;
+    const int oy = halo_origin(sy0 < H ? sy0 : H - 1, 4, H, K), ox = halo_origin(px0 < W ? px0 : W - 1, 4, W, K);
+    const int dy = oy - (sy0 - P::R), dx = ox - (px0 - P::R);   // 0 away from the borders
+    const int qy = sy0 + jy, qx = px0 + jx;
+    const bool q_ok = qy < H && qx < W;
+
+    // Operand addresses inside the first buffer pair.  Keys: halo position 16b + j, bytes [16g, 16g+16).
+    // Values (transposing read): inside its group of 16 lanes, lane j points at channels 4 (j % 4) .. + 3
+    // of halo position 16b + 4g + j / 4 and receives channel j of positions 16b + 4g .. + 3.
+    int koff[P::NBLK], vaddr[C::NBLK2];
+#pragma unroll
+    for (int b = 0; b < C::NBLK2; ++b) {
+        int h = 16 * b + j;
+        h = h < P::NKEY ? h : P::NKEY - 1;   // past the end: any real position (its weight is zero)
+        int hy = P::row_of(h), hx = h - hy * P::PW;
+        if (b < P::NBLK) koff[b] = lds0 + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + g * 16;
+        h = 16 * b + 4 * g + (j >> 2);
+        h = h < P::NKEY ? h : P::NKEY - 1;
+        hy = P::row_of(h);
+        hx = h - hy * P::PW;
+        vaddr[b] = lds0 + C::kHaloBytes + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + (j & 3) * 8;
+    }
+    // log2(e) * bias of (this lane's query, halo position), -inf outside the query's window; packed
+    // fp16 pairs (half the registers; the fma below reads them as mixed-precision operands)
+    f16x2 biasm[P::NEL / 2];
+    {
+        const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
+#pragma unroll
+        for (int e = 0; e < P::NEL; ++e) {
+            const int h = 16 * (e >> 2) + 4 * g + (e & 3);
+            const int hy = P::row_of(h), hx = h - hy * P::PW;
+            const int a = hy - wy, cc = hx - wx;
+            const bool ok = q_ok && h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)cc < (unsigned)K;
+            int u = hy - jy + P::R + dy, vv = hx - jx + P::R + dx;
+            u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);
+            vv = vv < 0 ? 0 : (vv > C::NB - 1 ? C::NB - 1 : vv);
+            const float bias = rpb ? kLog2e * to_f32(rpb[(size_t)head * C::NB * C::NB + u * C::NB + vv]) : 0.f;
+            biasm[e >> 1][e & 1] = (f16_t)(ok ? bias : -INFINITY);
+        }
+    }
+
+    typename C::Halo halo;
+    halo.init(wave, lane);
+    int hoff[C::Halo::PER_WAVE];
+    halo.offsets(H, W, hoy, hox, hoff);
+    const int qlin = (qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1);   // this lane's query inside a plane
+    const size_t plane_bytes = (size_t)H * W * Traits<T>::kKeyBytes;
+    const float scale2 = scale * kLog2e;
+
+    u32x4 qnext;
+    auto issue = [&](int b, int par) {
+        const size_t off = ((size_t)b * heads + head) * plane_bytes;
+        C::Halo::issue_at(reinterpret_cast<const char *>(k) + off, hoff, lds0 + par * C::kStageBytes, wave);
+        C::Halo::issue_at(reinterpret_cast<const char *>(v) + off, hoff, lds0 + par * C::kStageBytes + C::kHaloBytes, wave);
+        qnext = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(q) + off + qlin * Traits<T>::kKeyBytes + g * 16);
+    };
+    auto compute = [&](auto par_c, const u32x4 &qreg, int b) {
+        constexpr int PAR = decltype(par_c)::value;
+        if (!active) return;
+        // 1-2. logits in the exp2 domain
+        float s[4 * C::NBLK2];
+#pragma unroll
+        for (int bk = 0; bk < P::NBLK; ++bk) {
+            const u32x4 a = *lds_ptr<u32x4>(koff[bk] + PAR * C::kStageBytes);
+            const f32x4 acc = mfma_16x16x32<T>(a, qreg, f32x4{0.f, 0.f, 0.f, 0.f});
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                s[4 * bk + r] = __builtin_fmaf(scale2, acc[r], (float)biasm[(4 * bk + r) >> 1][(4 * bk + r) & 1]);
+        }
+        // 3. softmax over the query's window (spread over the 4 lanes j, j+16, j+32, j+48)
+        float m = s[0];
+#pragma unroll
+        for (int e = 1; e < P::NEL; ++e) m = fmaxf(m, s[e]);
+        m = fmaxf(m, __shfl_xor(m, 16));
+        m = fmaxf(m, __shfl_xor(m, 32));
+        m = q_ok ? m : 0.f;   // lanes without a query: keep the arithmetic finite
+        float l = 0.f;
+#pragma unroll
+        for (int e = 0; e < P::NEL; ++e) {
+            s[e] = __builtin_amdgcn_exp2f(s[e] - m);
+            l += s[e];
+        }
+#pragma unroll
+        for (int e = P::NEL; e < 4 * C::NBLK2; ++e) s[e] = 0.f;   // padding block of the last pair
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        // 4. O^T = V^T * P
+        f32x4 o[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int pb = 0; pb < C::NPAIR; ++pb) {
+            const u32x4 bop = u32x4{pack2<T>(s[8 * pb], s[8 * pb + 1]), pack2<T>(s[8 * pb + 2], s[8 * pb + 3]),
+                                    pack2<T>(s[8 * pb + 4], s[8 * pb + 5]), pack2<T>(s[8 * pb + 6], s[8 * pb + 7])};
+            // bf16 keeps 8 significant bits: a second operand carries the rounding remainder of the
+            // weights so that the product sees them to 16 bits
+            u32x4 bop_lo = u32x4{0u, 0u, 0u, 0u};
+            if constexpr (sizeof(T) == 2 && Traits<T>::kDtype == NA2D_BF16) {
+                float rem[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) rem[u] = s[8 * pb + u] - to_f32(from_f32<T>(s[8 * pb + u]));
+                bop_lo = u32x4{pack2<T>(rem[0], rem[1]), pack2<T>(rem[2], rem[3]), pack2<T>(rem[4], rem[5]),
+                               pack2<T>(rem[6], rem[7])};
+            }
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const u32x2 lo = lds_read_tr16(vaddr[2 * pb] + PAR * C::kStageBytes + hf * 32);
+                const u32x2 hi = lds_read_tr16(vaddr[2 * pb + 1] + PAR * C::kStageBytes + hf * 32);
+                const u32x4 aop = u32x4{lo.x, lo.y, hi.x, hi.y};
+                o[hf] = mfma_16x16x32<T>(aop, bop, o[hf]);
+                if constexpr (sizeof(T) == 2 && Traits<T>::kDtype == NA2D_BF16) o[hf] = mfma_16x16x32<T>(aop, bop_lo, o[hf]);
+            }
+        }
+        // 5. normalise and store this lane's 8 channels of its own query
+        if (q_ok) {
+            const float inv = 1.0f / l;
+            const size_t plane = (size_t)b * heads + head;
+            char *dst = reinterpret_cast<char *>(out) + plane * plane_bytes + qlin * Traits<T>::kKeyBytes + g * 8;
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const uint32_t lo = pack2<T>(o[hf][0] * inv, o[hf][1] * inv);
+                const uint32_t hi = pack2<T>(o[hf][2] * inv, o[hf][3] * inv);
+                *reinterpret_cast<uint64_t *>(dst + hf * 32) = (uint64_t)lo | ((uint64_t)hi << 32);
+            }
+            if (lse != nullptr && g == 0) lse[plane * H * W + qlin] = (m + __builtin_amdgcn_logf(l)) * kLn2;
+        }
+    };
+
+    issue(b_begin, 0);
+    int b = b_begin;
+    auto step = [&](auto par_c) {
+        constexpr int PAR = decltype(par_c)::value;
+        wait_global_loads();   // this tile's halos and query chunk have landed
+        __syncthreads();       // ... for every wave, and nobody still reads the other buffer pair
+        const u32x4 qreg = qnext;
+        if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
+        compute(par_c, qreg, b);
+        ++b;
+    };
+    while (b < b_end) {
+        step(IntC<0>{});
+        if (b < b_end) step(IntC<1>{});
+    }
+}
+
+template <typename T, int K>
+static hipError_t launch_fused_mfma_small_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
+                                            float scale, void *out, float *lse, hipStream_t s) {
+    using C = FusedSmallCfg<T, K>;
+    static_assert(C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
+    const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
+    auto kern = fused_mfma_small_kernel<T, K>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
+                       static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
+                       static_cast<const T *>(rpb), scale, static_cast<T *>(out), lse, p.H, p.W, p.heads, p.B, tiles_y,
+                       us.units, us.splits);
+    return hipGetLastError();
+}
+
 template <typename T, int K>
 static hipError_t launch_fused_mfma_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
                                       float scale, void *out, float *lse, hipStream_t s) {
@@ -320,9 +541,15 @@ hipError_t launch_fused_mfma(const Problem &p, const void *q, const void *k, con
                              void *out, float *lse, hipStream_t s) {
     if (p.dtype == NA2D_F16) {
         using T = f16_t;
+        if (p.K == 3) return launch_fused_mfma_small_t<T, 3>(p, q, k, v, rpb, scale, out, lse, s);
+        if (p.K == 5) return launch_fused_mfma_small_t<T, 5>(p, q, k, v, rpb, scale, out, lse, s);
+        if (p.K == 7) return launch_fused_mfma_small_t<T, 7>(p, q, k, v, rpb, scale, out, lse, s);
         NA2D_DISPATCH_K(p.K, return (launch_fused_mfma_t<T, K>(p, q, k, v, rpb, scale, out, lse, s)));
     } else if (p.dtype == NA2D_BF16) {
         using T = bf16_t;
+        if (p.K == 3) return launch_fused_mfma_small_t<T, 3>(p, q, k, v, rpb, scale, out, lse, s);
+        if (p.K == 5) return launch_fused_mfma_small_t<T, 5>(p, q, k, v, rpb, scale, out, lse, s);
+        if (p.K == 7) return launch_fused_mfma_small_t<T, 7>(p, q, k, v, rpb, scale, out, lse, s);
         NA2D_DISPATCH_K(p.K, return (launch_fused_mfma_t<T, K>(p, q, k, v, rpb, scale, out, lse, s)));
     }
     return hipErrorInvalidValue;

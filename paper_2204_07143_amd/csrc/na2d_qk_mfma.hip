@@ -282,9 +282,6 @@ struct QkSmallCfg {
     static_assert(kParity < 65536, "the second staging image is reached through the 16-bit offset of the LDS store");
 };
 
-template <int V> struct IntC {
-    static constexpr int value = V;
-};
 
 // One row run of the tile, LDS -> global: 16-byte stores for the chunks that are aligned in global
 // memory (their LDS source is then aligned to 2 bytes only), single elements at the two ends.
@@ -451,20 +448,6 @@ __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
     }
     __syncthreads();
     flush(b_end - 1, (b_end - b_begin - 1) & 1);
-}
-
-// Work split of the position-stationary kernels: a unit is a (tile position, head) pair; the batch is
-// cut into `splits` ranges so that about two workgroups per compute unit exist.
-struct UnitSplit {
-    int units, splits;
-};
-static inline UnitSplit unit_split(int tiles_x, int tiles_y, int heads, int nb) {
-    UnitSplit u;
-    u.units = tiles_x * tiles_y * heads;
-    int s = (256 * 2) / u.units;
-    s = s < 1 ? 1 : s;
-    u.splits = s < nb ? s : nb;
-    return u;
 }
 
 template <typename T, int K>

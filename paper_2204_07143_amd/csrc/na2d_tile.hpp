@@ -132,4 +132,23 @@ __device__ __forceinline__ void lds_load_vec32(Vec32<T> &v, const char *lds_key)
     load_vec32(v, lds_key);
 }
 
+// compile-time integer passed as a lambda argument
+template <int V> struct IntC {
+    static constexpr int value = V;
+};
+
+// Work split of the position-stationary kernels: a unit is a (tile position, head) pair; the batch is
+// cut into `splits` ranges so that about two workgroups per compute unit exist.
+struct UnitSplit {
+    int units, splits;
+};
+static inline UnitSplit unit_split(int tiles_x, int tiles_y, int heads, int nb) {
+    UnitSplit u;
+    u.units = tiles_x * tiles_y * heads;
+    int s = (256 * 2) / u.units;
+    s = s < 1 ? 1 : s;
+    u.splits = s < nb ? s : nb;
+    return u;
+}
+
 }  // namespace na2d
