@@ -49,9 +49,12 @@ struct FusedTile {
     int ty0, tx0, plane, hoy, hox;
 };
 
+// two floats -> one register of two storage-type values (round to nearest even; one packed
+// conversion instruction on gfx950)
 template <typename T> __device__ __forceinline__ uint32_t pack2(float a, float b) {
-    const T lo = from_f32<T>(a), hi = from_f32<T>(b);
-    return (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef T tx2_t __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){a, b}, tx2_t));
 }
 
 template <typename T, int K, int WAVES>
@@ -352,6 +355,22 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
     const int qy = sy0 + jy, qx = px0 + jx;
     const bool q_ok = qy < H && qx < W;
 
+    // the first tile's loads fly while the tables below are built
+    typename C::Halo halo;
+    halo.init(wave, lane);
+    int hoff[C::Halo::PER_WAVE];
+    halo.offsets(H, W, hoy, hox, hoff);
+    const int qlin = (qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1);   // this lane's query inside a plane
+    const size_t plane_bytes = (size_t)H * W * Traits<T>::kKeyBytes;
+    u32x4 qnext;
+    auto issue = [&](int b, int par) {
+        const size_t off = ((size_t)b * heads + head) * plane_bytes;
+        C::Halo::issue_at(reinterpret_cast<const char *>(k) + off, hoff, lds0 + par * C::kStageBytes, wave);
+        C::Halo::issue_at(reinterpret_cast<const char *>(v) + off, hoff, lds0 + par * C::kStageBytes + C::kHaloBytes, wave);
+        qnext = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(q) + off + qlin * Traits<T>::kKeyBytes + g * 16);
+    };
+    issue(b_begin, 0);
+
     // Operand addresses inside the first buffer pair.  Keys: halo position 16b + j, bytes [16g, 16g+16).
     // Values (transposing read): inside its group of 16 lanes, lane j points at channels 4 (j % 4) .. + 3
     // of halo position 16b + 4g + j / 4 and receives channel j of positions 16b + 4g .. + 3.
@@ -387,21 +406,7 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
         }
     }
 
-    typename C::Halo halo;
-    halo.init(wave, lane);
-    int hoff[C::Halo::PER_WAVE];
-    halo.offsets(H, W, hoy, hox, hoff);
-    const int qlin = (qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1);   // this lane's query inside a plane
-    const size_t plane_bytes = (size_t)H * W * Traits<T>::kKeyBytes;
     const float scale2 = scale * kLog2e;
-
-    u32x4 qnext;
-    auto issue = [&](int b, int par) {
-        const size_t off = ((size_t)b * heads + head) * plane_bytes;
-        C::Halo::issue_at(reinterpret_cast<const char *>(k) + off, hoff, lds0 + par * C::kStageBytes, wave);
-        C::Halo::issue_at(reinterpret_cast<const char *>(v) + off, hoff, lds0 + par * C::kStageBytes + C::kHaloBytes, wave);
-        qnext = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(q) + off + qlin * Traits<T>::kKeyBytes + g * 16);
-    };
     auto compute = [&](auto par_c, const u32x4 &qreg, int b) {
         constexpr int PAR = decltype(par_c)::value;
         if (!active) return;
@@ -459,7 +464,7 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
         }
         // 5. normalise and store this lane's 8 channels of its own query
         if (q_ok) {
-            const float inv = 1.0f / l;
+            const float inv = __builtin_amdgcn_rcpf(l);   // 1 ulp; the result is rounded to 11 or 8 bits
             const size_t plane = (size_t)b * heads + head;
             char *dst = reinterpret_cast<char *>(out) + plane * plane_bytes + qlin * Traits<T>::kKeyBytes + g * 8;
 #pragma unroll
@@ -472,7 +477,6 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
         }
     };
 
-    issue(b_begin, 0);
     int b = b_begin;
     auto step = [&](auto par_c) {
         constexpr int PAR = decltype(par_c)::value;
