@@ -219,6 +219,229 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void av_mfma_kern
     }
 }
 
+// ---- small windows (K <= 7): one patch per wave, operands loaded straight into LDS -----------
+//
+// Eight waves share a 16 x 8 query tile, one 4 x 4 patch each.  A workgroup keeps one tile position
+// and one head and walks a range of the batch: the per-lane gather addresses of the weights and
+// the operand addresses of the values are built once.  Per tile the value halo (natural layout)
+// and the tile's eight weight row runs (mirrored at their 16-byte phase) reach one of two LDS
+// stages by direct loads while the previous tile is computed.  Halo positions are numbered
+// h = hy * (K+3) + hx; MFMA pair m contracts over the positions 32m .. 32m+31 in the lane order
+//   lane group g, element e:  position 32m + 16 (e / 4) + 4g + e % 4.
+//   A operand: channel j of those positions, two transposing LDS reads from the value halo;
+//   B operand: the weights of query j at those positions, 2-byte gathers from its row run (zero
+//              outside its window).
+template <typename T, int K>
+struct AvSmallCfg {
+    using P = Patch<K>;
+    static constexpr int STRIPS = 2;
+    static constexpr int WAVES = 4 * STRIPS;
+    static constexpr int TY = 4 * STRIPS;
+    static constexpr int HALO_H = TY + K - 1, HALO_W = kTileX + K - 1;
+    using Halo = HaloDma<T, HALO_H, HALO_W, WAVES>;
+    static constexpr int KK = K * K;
+    static constexpr int NPAIR = (P::NBLK + 1) / 2;
+    static constexpr int NEL2 = 8 * NPAIR;            // gathered weights per lane
+    static constexpr int kThreads = kWave * WAVES;
+    static constexpr int kHaloBytes = Halo::kBytes;
+    static constexpr int kRowBytes = kTileX * KK * (int)sizeof(T);
+    static constexpr int kRowRegion = mirror_bytes(kRowBytes);
+    static constexpr int kRowChunks = (kRowBytes + 15 + 15) / 16;   // 16-byte chunks a run can touch
+    static_assert(kRowChunks <= 2 * kWave, "a row run is loaded by two instructions of one wave");
+    static constexpr int kWBytes = TY * kRowRegion;
+    static constexpr int kStageBytes = kHaloBytes + kWBytes + 16;   // + the zero word
+    static constexpr int kLdsBytes = 2 * kStageBytes;
+    static_assert(kStageBytes < 65536, "the second stage is reached through the 16-bit offset of the LDS reads");
+};
+
+template <typename T, int K>
+__global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restrict__ w, const T *__restrict__ y, float scale,
+                                                               T *__restrict__ out, int H, int W, int heads, int nb,
+                                                               int tiles_y, int units, int splits) {
+    using C = AvSmallCfg<T, K>;
+    using P = Patch<K>;
+    static_assert(C::kThreads == 512, "launch bounds");
+    constexpr int SZ = (int)sizeof(T);
+    extern __shared__ __align__(16) char lds[];
+
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int strip = wave >> 2, p = wave & 3;
+    const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
+    const int lds0 = lds_addr(lds);
+    const int w0 = lds0 + C::kHaloBytes, zero_addr = w0 + C::kWBytes;
+
+    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    if (wg >= units * splits) return;
+    const int unit = wg / splits, split = wg - unit * splits;
+    const int pos = unit / heads, head = unit - pos * heads;
+    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
+    const int b_begin = (split * nb) / splits, b_end = ((split + 1) * nb) / splits;
+    if (b_begin >= b_end) return;
+
+    // the zero words (one per stage) are never written by the loads
+    if (tid < 8) *lds_ptr<uint32_t>(zero_addr + (tid >> 2) * C::kStageBytes + (tid & 3) * 4) = 0u;
+
+    const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);   // tile halo origin
+    const int sy0 = ty0 + 4 * strip, px0 = tx0 + 4 * p;                                     // this wave's patch
+    const bool active = sy0 < H && px0 < W;
+    const int oy = halo_origin(sy0 < H ? sy0 : H - 1, 4, H, K), ox = halo_origin(px0 < W ? px0 : W - 1, 4, W, K);
+    const int qy = sy0 + jy, qx = px0 + jx;
+    const bool q_ok = qy < H && qx < W;
+
+    // loads: value halo chunks of this lane; weight row run `wave` of the tile (two chunks per lane)
+    typename C::Halo halo;
+    halo.init(wave, lane);
+    int hoff[C::Halo::PER_WAVE];
+    halo.offsets(H, W, hoy, hox, hoff);
+    const size_t plane_y = (size_t)H * W * Traits<T>::kKeyBytes;   // bytes per plane of y / out
+    const size_t plane_w = (size_t)H * W * C::KK * SZ;             // ... of the weights
+    const size_t w_bytes = plane_w * heads * nb;
+    const int wrow = ty0 + wave;                                    // the row this wave loads
+    const int wrow_bytes = ((W - tx0) < kTileX ? (W - tx0) : kTileX) * C::KK * SZ;
+    const size_t wrow_off = ((size_t)(wrow < H ? wrow : H - 1) * W + tx0) * C::KK * SZ;
+    auto issue = [&](int b, int par) {
+        const size_t plane = (size_t)b * heads + head;
+        C::Halo::issue_at(reinterpret_cast<const char *>(y) + plane * plane_y, hoff, lds0 + par * C::kStageBytes, wave);
+        if (wrow < H) {
+            const size_t g0 = plane * plane_w + wrow_off;
+            const int mis = (int)(g0 & 15);
+            const int nchunks = (mis + wrow_bytes + 15) >> 4;
+            const char *src = reinterpret_cast<const char *>(w) + (g0 - mis);
+            const size_t left = w_bytes - (g0 - mis);   // bytes up to the end of the tensor
+            const int region = w0 + par * C::kStageBytes + wave * C::kRowRegion;
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int c = lane + it * kWave;
+                if (c < nchunks) {
+                    if ((size_t)(c + 1) * 16 <= left) {
+                        global_to_lds_16(src + c * 16, region + it * kWave * 16);
+                    } else {   // the chunk that would cross the end of the tensor: element by element
+                        for (int e = c * 16; e < mis + wrow_bytes; e += SZ)
+                            *lds_ptr<T>(region + e) = *reinterpret_cast<const T *>(src + e);
+                    }
+                }
+            }
+        }
+    };
+    issue(b_begin, 0);
+
+    // Operand addresses inside the first stage.
+    // Values (transposing read): inside its group of 16 lanes, lane j points at channels 4 (j % 4) .. + 3
+    // of halo position 16b + 4g + j / 4 and receives channel j of positions 16b + 4g .. + 3.
+    int vaddr[2 * C::NPAIR];
+#pragma unroll
+    for (int b = 0; b < 2 * C::NPAIR; ++b) {
+        int h = 16 * b + 4 * g + (j >> 2);
+        h = h < P::NKEY ? h : P::NKEY - 1;   // past the end: any real position (its weight is zero)
+        const int hy = P::row_of(h), hx = h - hy * P::PW;
+        vaddr[b] = lds0 + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + (j & 3) * 8;
+    }
+    // Weights: LDS address of this lane's query's weight for halo position 16 (e / 4) + 4g + e % 4, the
+    // zero word where the position is outside the query's window.  The addresses hold the 16-byte
+    // phase the query's row run has in the first plane of the range; later planes add the difference.
+    const size_t qrow_off = ((size_t)(qy < H ? qy : H - 1) * W + tx0) * C::KK * SZ;
+    auto phase_of = [&](int b) { return (int)((((size_t)b * heads + head) * plane_w + qrow_off) & 15); };
+    const int phase0 = phase_of(b_begin);
+    const bool phase_varies = (plane_w & 15) != 0;
+    int gaddr[C::NEL2];
+    {
+        const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
+        const int lane_row = w0 + (4 * strip + jy) * C::kRowRegion + phase0 + (4 * p + jx) * C::KK * SZ;
+#pragma unroll
+        for (int e = 0; e < C::NEL2; ++e) {
+            const int h = 16 * (e >> 2) + 4 * g + (e & 3);
+            const int hy = P::row_of(h), hx = h - hy * P::PW;
+            const int a = hy - wy, cc = hx - wx;
+            const bool ok = q_ok && h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)cc < (unsigned)K;
+            gaddr[e] = ok ? lane_row + (a * K + cc) * SZ : zero_addr;
+        }
+    }
+    const int qlin = (qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1);
+
+    auto compute = [&](auto par_c, auto shift_c, int b) {
+        constexpr int PAR = decltype(par_c)::value;
+        constexpr bool SHIFT = decltype(shift_c)::value != 0;
+        if (!active) return;
+        const int dph = SHIFT ? phase_of(b) - phase0 : 0;
+        f32x4 o[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int pb = 0; pb < C::NPAIR; ++pb) {
+            uint32_t wv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int a_lo = gaddr[8 * pb + 2 * u], a_hi = gaddr[8 * pb + 2 * u + 1];
+                if (SHIFT) {   // entries that point at the zero word stay there
+                    a_lo = a_lo == zero_addr ? a_lo : a_lo + dph;
+                    a_hi = a_hi == zero_addr ? a_hi : a_hi + dph;
+                }
+                wv[u] = (uint32_t)*lds_ptr<uint16_t>(a_lo + PAR * C::kStageBytes) |
+                        ((uint32_t)*lds_ptr<uint16_t>(a_hi + PAR * C::kStageBytes) << 16);
+            }
+            const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const u32x2 lo = lds_read_tr16(vaddr[2 * pb] + PAR * C::kStageBytes + hf * 32);
+                const u32x2 hi = lds_read_tr16(vaddr[2 * pb + 1] + PAR * C::kStageBytes + hf * 32);
+                o[hf] = mfma_16x16x32<T>(u32x4{lo.x, lo.y, hi.x, hi.y}, bop, o[hf]);
+            }
+        }
+        if (q_ok) {
+            char *dst = reinterpret_cast<char *>(out) + ((size_t)b * heads + head) * plane_y + qlin * Traits<T>::kKeyBytes + g * 8;
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                uint32_t ov[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+                    typedef T tx2_t __attribute__((ext_vector_type(2)));
+                    ov[u] = __builtin_bit_cast(
+                        uint32_t, __builtin_convertvector((f32x2_t){o[hf][2 * u] * scale, o[hf][2 * u + 1] * scale}, tx2_t));
+                }
+                *reinterpret_cast<uint64_t *>(dst + hf * 32) = (uint64_t)ov[0] | ((uint64_t)ov[1] << 32);
+            }
+        }
+    };
+
+    int b = b_begin;
+    auto step = [&](auto par_c) {
+        constexpr int PAR = decltype(par_c)::value;
+        wait_global_loads();   // this tile's halo and weight rows have landed
+        __syncthreads();       // ... for every wave, and nobody still reads the other stage
+        if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
+        if (phase_varies)
+            compute(par_c, IntC<1>{}, b);
+        else
+            compute(par_c, IntC<0>{}, b);
+        ++b;
+    };
+    while (b < b_end) {
+        step(IntC<0>{});
+        if (b < b_end) step(IntC<1>{});
+    }
+}
+
+template <typename T, int K>
+static hipError_t launch_av_mfma_small_t(const Problem &p, const void *w, const void *y, float scale, void *out,
+                                         hipStream_t s) {
+    using C = AvSmallCfg<T, K>;
+    static_assert(C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
+    const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
+    auto kern = av_mfma_small_kernel<T, K>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
+                       static_cast<const T *>(w), static_cast<const T *>(y), scale, static_cast<T *>(out), p.H, p.W,
+                       p.heads, p.B, tiles_y, us.units, us.splits);
+    return hipGetLastError();
+}
+
 template <typename T, int K>
 static hipError_t launch_av_mfma_t(const Problem &p, const void *w, const void *y, float scale, void *out,
                                    hipStream_t s) {
@@ -247,9 +470,15 @@ static hipError_t launch_av_mfma_t(const Problem &p, const void *w, const void *
 hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s) {
     if (p.dtype == NA2D_F16) {
         using T = f16_t;
+        if (p.K == 3) return launch_av_mfma_small_t<T, 3>(p, w, y, scale, out, s);
+        if (p.K == 5) return launch_av_mfma_small_t<T, 5>(p, w, y, scale, out, s);
+        if (p.K == 7) return launch_av_mfma_small_t<T, 7>(p, w, y, scale, out, s);
         NA2D_DISPATCH_K(p.K, return (launch_av_mfma_t<T, K>(p, w, y, scale, out, s)));
     } else if (p.dtype == NA2D_BF16) {
         using T = bf16_t;
+        if (p.K == 3) return launch_av_mfma_small_t<T, 3>(p, w, y, scale, out, s);
+        if (p.K == 5) return launch_av_mfma_small_t<T, 5>(p, w, y, scale, out, s);
+        if (p.K == 7) return launch_av_mfma_small_t<T, 7>(p, w, y, scale, out, s);
         NA2D_DISPATCH_K(p.K, return (launch_av_mfma_t<T, K>(p, w, y, scale, out, s)));
     }
     return hipErrorInvalidValue;
