@@ -392,6 +392,7 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
     f16x2 biasm[P::NEL / 2];
     {
         const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
+        int bidx[P::NEL];   // cell of the bias table, -1 outside the window
 #pragma unroll
         for (int e = 0; e < P::NEL; ++e) {
             const int h = 16 * (e >> 2) + 4 * g + (e & 3);
@@ -401,9 +402,19 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
             int u = hy - jy + P::R + dy, vv = hx - jx + P::R + dx;
             u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);
             vv = vv < 0 ? 0 : (vv > C::NB - 1 ? C::NB - 1 : vv);
-            const float bias = rpb ? kLog2e * to_f32(rpb[(size_t)head * C::NB * C::NB + u * C::NB + vv]) : 0.f;
-            biasm[e >> 1][e & 1] = (f16_t)(ok ? bias : -INFINITY);
+            bidx[e] = ok ? u * C::NB + vv : -1;
         }
+        // all loads of the bias table in flight at once (one uniform branch on the table's presence)
+        float bias[P::NEL];
+#pragma unroll
+        for (int e = 0; e < P::NEL; ++e) bias[e] = 0.f;
+        if (rpb != nullptr) {
+            const T *tbl = rpb + (size_t)head * C::NB * C::NB;
+#pragma unroll
+            for (int e = 0; e < P::NEL; ++e) bias[e] = kLog2e * to_f32(tbl[bidx[e] < 0 ? 0 : bidx[e]]);
+        }
+#pragma unroll
+        for (int e = 0; e < P::NEL; ++e) biasm[e >> 1][e & 1] = (f16_t)(bidx[e] >= 0 ? bias[e] : -INFINITY);
     }
 
     const float scale2 = scale * kLog2e;

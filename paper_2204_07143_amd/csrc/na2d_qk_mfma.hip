@@ -351,44 +351,6 @@ __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
     const int qy = sy0 + jy, qx = px0 + jx;
     const bool q_ok = qy < H && qx < W;
 
-    // A operand: offsets of this lane's keys inside the tile halo (keys past the end of the patch halo
-    // re-read its last one)
-    int koff[P::NBLK];
-#pragma unroll
-    for (int b = 0; b < P::NBLK; ++b) {
-        int h = 16 * b + j;
-        h = h < P::NKEY ? h : P::NKEY - 1;
-        const int hy = P::row_of(h), hx = h - hy * P::PW;
-        koff[b] = lds0 + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + g * 16;
-    }
-    // Where this lane's results go: result e is the dot product of query j with patch-halo key
-    // 16 (e / 4) + 4 g + e % 4.  Inside the query's window it is stored at its slot of the query's row
-    // run in the staging image, outside it goes to the lane's dump word.  The bias of (query, key)
-    // depends on key - query only (Eq. 2); it is kept two per register in the storage type.
-    uint32_t bias2[P::NEL / 2];
-    int slotaddr[P::NEL];
-    {
-        const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
-        const int lane_stage = stage0 + (4 * strip + jy) * C::kRowPitch + (4 * p + jx) * C::KK * SZ;
-#pragma unroll
-        for (int e = 0; e < P::NEL; ++e) {
-            const int h = 16 * (e >> 2) + 4 * g + (e & 3);
-            const int hy = P::row_of(h), hx = h - hy * P::PW;
-            const int a = hy - wy, cc = hx - wx;
-            const bool ok = q_ok && h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)cc < (unsigned)K;
-            slotaddr[e] = ok ? lane_stage + (a * K + cc) * SZ : my_dump;
-            int u = hy - jy + P::R + dy, v = hx - jx + P::R + dx;
-            u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);   // cells outside the table belong to keys
-            v = v < 0 ? 0 : (v > C::NB - 1 ? C::NB - 1 : v);   // outside every window: value unused
-            const uint32_t bits =
-                rpb ? (uint32_t) reinterpret_cast<const uint16_t *>(rpb)[(size_t)head * C::NB * C::NB + u * C::NB + v] : 0u;
-            if (e & 1)
-                bias2[e >> 1] |= bits << 16;
-            else
-                bias2[e >> 1] = bits;
-        }
-    }
-
     // loads: the halo chunks of this lane and its 16 bytes of its query, as byte offsets inside a plane
     typename C::Halo halo;
     halo.init(wave, lane);
@@ -408,6 +370,53 @@ __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
         C::Halo::issue_at(reinterpret_cast<const char *>(y) + plane * plane_in, hoff, lds0 + par * C::kHaloBytes, wave);
         qnext = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) + plane * plane_in + qoff);
     };
+    issue(b_begin, 0);   // the first tile's loads fly while the tables below are built
+
+    // A operand: offsets of this lane's keys inside the tile halo (keys past the end of the patch halo
+    // re-read its last one)
+    int koff[P::NBLK];
+#pragma unroll
+    for (int b = 0; b < P::NBLK; ++b) {
+        int h = 16 * b + j;
+        h = h < P::NKEY ? h : P::NKEY - 1;
+        const int hy = P::row_of(h), hx = h - hy * P::PW;
+        koff[b] = lds0 + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + g * 16;
+    }
+    // Where this lane's results go: result e is the dot product of query j with patch-halo key
+    // 16 (e / 4) + 4 g + e % 4.  Inside the query's window it is stored at its slot of the query's row
+    // run in the staging image, outside it goes to the lane's dump word.  The bias of (query, key)
+    // depends on key - query only (Eq. 2); it is kept two per register in the storage type.
+    uint32_t bias2[P::NEL / 2];
+    int slotaddr[P::NEL];
+    {
+        const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
+        const int lane_stage = stage0 + (4 * strip + jy) * C::kRowPitch + (4 * p + jx) * C::KK * SZ;
+        int bidx[P::NEL];
+#pragma unroll
+        for (int e = 0; e < P::NEL; ++e) {
+            const int h = 16 * (e >> 2) + 4 * g + (e & 3);
+            const int hy = P::row_of(h), hx = h - hy * P::PW;
+            const int a = hy - wy, cc = hx - wx;
+            const bool ok = q_ok && h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)cc < (unsigned)K;
+            slotaddr[e] = ok ? lane_stage + (a * K + cc) * SZ : my_dump;
+            int u = hy - jy + P::R + dy, v = hx - jx + P::R + dx;
+            u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);   // cells outside the table belong to keys
+            v = v < 0 ? 0 : (v > C::NB - 1 ? C::NB - 1 : v);   // outside every window: value unused
+            bidx[e] = u * C::NB + v;
+        }
+        // all loads of the bias table in flight at once (one uniform branch on the table's presence)
+        uint32_t bits[P::NEL];
+#pragma unroll
+        for (int e = 0; e < P::NEL; ++e) bits[e] = 0u;
+        if (rpb != nullptr) {
+            const uint16_t *tbl = reinterpret_cast<const uint16_t *>(rpb) + (size_t)head * C::NB * C::NB;
+#pragma unroll
+            for (int e = 0; e < P::NEL; ++e) bits[e] = tbl[bidx[e]];
+        }
+#pragma unroll
+        for (int e = 0; e < P::NEL / 2; ++e) bias2[e] = bits[2 * e] | (bits[2 * e + 1] << 16);
+    }
+
     auto flush = [&](int b, int par) {
         if (frow < H)
             flush_run<T>(reinterpret_cast<char *>(logits), ((size_t)b * heads + head) * plane_out + foff, fbytes,
@@ -430,7 +439,6 @@ __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
         }
     };
 
-    issue(b_begin, 0);
     int b = b_begin;
     auto step = [&](auto par_c) {
         constexpr int PAR = decltype(par_c)::value;
