@@ -341,8 +341,11 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
 
     const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
     if (wg >= units * splits) return;
-    const int unit = wg / splits, split = wg - unit * splits;
-    const int pos = unit / heads, head = unit - pos * heads;
+    // neighbouring workgroups take neighbouring tile positions of the same planes (the position index
+    // runs fastest), so the positions whose halos overlap run at the same time on the same XCD and
+    // the overlap is read from HBM once
+    const int npos = units / heads;
+    const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
     const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
     const int b_begin = (split * nb) / splits, b_end = ((split + 1) * nb) / splits;
     if (b_begin >= b_end) return;
