@@ -122,10 +122,13 @@ int na2d_qk_bwd_rpb(const na2d_problem *p, const void *ds, float *d_rpb, void *w
                     void *stream);
 
 /*
- * Whole backward of out = NA(q, k, v, rpb): runs grad-a, grad-v, softmax backward, grad-q,
- * grad-k and (if d_rpb != NULL) grad-b, in that order.  `attn` is the softmax output of the
- * forward.  `workspace` must hold na2d_workspace_bytes(p, NA2D_WS_BWD) bytes (it carries the
- * dp/ds tensor and the grad-b partials).
+ * Whole backward of out = NA(q, k, v, rpb): grad-a, grad-v, softmax backward, grad-q, grad-k
+ * and (if d_rpb != NULL) grad-b.  For the 16-bit types with k <= 7, grad-a and the softmax
+ * backward run as one kernel and dp is never stored (so ds is computed from the unrounded dp);
+ * otherwise the six steps run one after the other exactly as the separate entry points do.
+ * `attn` is the softmax output of the forward.  `workspace` must hold
+ * na2d_workspace_bytes(p, NA2D_WS_BWD) bytes; on return it starts with the ds tensor
+ * ([B, heads, H, W, k*k], problem dtype), followed by the grad-b partials.
  */
 int na2d_bwd(const na2d_problem *p, const void *q, const void *k, const void *v, const void *attn,
              const void *dout, float scale, void *dq, void *dk, void *dv, float *d_rpb,

@@ -182,9 +182,14 @@ int na2d_bwd(const na2d_problem *p, const void *q, const void *k, const void *v,
     void *dpds = ws;   // dp, overwritten in place by ds
     const size_t attn_bytes = (pr.queries() * p->k * p->k * pr.elem_bytes() + 255) & ~(size_t)255;
     void *rpb_ws = ws + attn_bytes;
-    if (launch_qk(pr, dout, v, nullptr, 1.0f, dpds, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);      // grad-a
-    if (launch_inverse(pr, attn, dout, 1.0f, dv, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);        // grad-v
-    if (launch_softmax_bwd(pr, attn, dpds, dpds, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);        // ds
+    if (bwd_fused_supported(pr)) {   // grad-a and the softmax backward in one kernel: dp never reaches memory
+        if (launch_bwd_fused(pr, attn, dout, v, dpds, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);
+        if (launch_inverse(pr, attn, dout, 1.0f, dv, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);    // grad-v
+    } else {
+        if (launch_qk(pr, dout, v, nullptr, 1.0f, dpds, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);  // grad-a
+        if (launch_inverse(pr, attn, dout, 1.0f, dv, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);    // grad-v
+        if (launch_softmax_bwd(pr, attn, dpds, dpds, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);    // ds
+    }
     if (launch_av(pr, dpds, k, scale, dq, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);               // grad-q
     if (launch_inverse(pr, dpds, q, scale, dk, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);          // grad-k
     if (d_rpb && launch_rpb_bwd(pr, dpds, d_rpb, rpb_ws, s) != hipSuccess) return from_hip(hipErrorLaunchFailure); // grad-b

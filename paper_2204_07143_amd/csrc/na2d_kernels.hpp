@@ -24,6 +24,9 @@ hipError_t launch_qk_mfma(const Problem &p, const void *x, const void *y, const 
                           hipStream_t s);
 // Variant override for A/B timing: NA2D_VARIANT=valu forces the plain-ALU kernels.
 bool force_valu();
+// grad-a fused with the softmax backward (f16 / bf16, K <= 7): ds from attn, dout and v
+bool bwd_fused_supported(const Problem &p);
+hipError_t launch_bwd_fused(const Problem &p, const void *attn, const void *dout, const void *v, void *ds, hipStream_t s);
 // out = scale * sum_window w * y          (AV, and grad-q with w = ds, y = k)
 hipError_t launch_av(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);
 hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);

@@ -106,7 +106,10 @@ class Stages:
         dq, dk, dv = (torch.empty_like(self.q) for _ in range(3))
         d_rpb = torch.empty((self.p.heads, nb, nb), dtype=torch.float32, device="cuda")
         na.na2d_bwd(self.q, self.key, self.v, self.attn, self.dout, self.scale, self.k, dq, dk, dv, d_rpb, ws)
-        return dq, dk, dv, d_rpb
+        # the workspace starts with the ds tensor the call computed (attention-shaped, problem dtype)
+        n = self.attn.numel()
+        ds = ws[: n * self.attn.element_size()].view(self.attn.dtype).view(self.attn.shape)
+        return dq, dk, dv, d_rpb, ds
 
 
 def plane(x, b: int, h: int):

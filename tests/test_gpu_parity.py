@@ -69,11 +69,28 @@ def run_all(oracle, p: synth.Problem, seed: int, planes=None, backward=True, use
     if backward and use_rpb:
         # grad-b sums over the batch: needs the whole ds tensor
         assert_close_rpb("grad-b", st.d_rpb, oracle.qk_bwd_rpb(to_np(st.ds), p.k))
-        # the composed backward is the same kernels in the same order: bitwise equal
-        dq, dk, dv, d_rpb = st.backward_composed()
+        # The composed backward either runs the same kernels as the stages (then everything is bitwise
+        # equal to them) or fuses grad-a with the softmax backward (16-bit types, k <= 7: dp is never
+        # rounded to the storage type).  The fused result is checked like the stages: its ds (left in
+        # the workspace) against the oracle's softmax backward of the exact dp, and grad-q / grad-k /
+        # grad-b against the oracle fed that ds.  grad-v does not depend on ds: always bitwise equal.
+        dq, dk, dv, d_rpb, ds_c = st.backward_composed()
         torch.cuda.synchronize()
-        for a, b_, n in ((dq, st.dq, "dq"), (dk, st.dk, "dk"), (dv, st.dv, "dv"), (d_rpb, st.d_rpb, "d_rpb")):
-            assert torch.equal(a, b_), f"na2d_bwd {n} differs from the stage-by-stage result"
+        assert torch.equal(dv, st.dv), "na2d_bwd dv differs from the stage-by-stage result"
+        if torch.equal(ds_c, st.ds):
+            for a, b_, n in ((dq, st.dq, "dq"), (dk, st.dk, "dk"), (d_rpb, st.d_rpb, "d_rpb")):
+                assert torch.equal(a, b_), f"na2d_bwd {n} differs from the stage-by-stage result"
+        else:
+            assert p.dtype != "f32" and p.k <= 7, "only the 16-bit small-window backward is fused"
+            for (b, h) in planes:
+                tag = f"na2d_bwd plane({b},{h})"
+                q, key, v, dout = (plane(host[n], b, h).astype(np.float64) for n in ("q", "k", "v", "dout"))
+                g_attn = to_np(plane(st.attn, b, h))
+                assert_close(f"{tag} ds", plane(ds_c, b, h), oracle.softmax_bwd(g_attn, oracle.av_bwd_p(dout, v, p.k)), p.dtype)
+                g_ds = to_np(plane(ds_c, b, h))
+                assert_close(f"{tag} grad-q", plane(dq, b, h), oracle.qk_bwd_q(g_ds, key, st.scale, p.k), p.dtype)
+                assert_close(f"{tag} grad-k", plane(dk, b, h), oracle.qk_bwd_k(g_ds, q, st.scale, p.k), p.dtype)
+            assert_close_rpb("na2d_bwd grad-b", d_rpb, oracle.qk_bwd_rpb(to_np(ds_c), p.k))
     return st, host, flat
 
 
