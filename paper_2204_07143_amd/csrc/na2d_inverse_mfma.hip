@@ -24,7 +24,10 @@
 
 namespace na2d {
 
-template <typename T, int K, int STRIPS, int PPW>
+// COMPACT: LDS images sized for the rectangle of a tile away from the ragged end of the map,
+// (TY + K-1) x (16 + K-1) positions; three workgroups then share a CU.  The launcher uses it when every
+// tile of the map fits (always the case when H and W are multiples of the tile, e.g. 56 x 56).
+template <typename T, int K, int STRIPS, int PPW, bool COMPACT>
 struct InvMfmaCfg {
     static constexpr int R = K / 2;
     static constexpr int PWI = K + R + 3;          // query-halo side of a 4 x 4 key patch
@@ -35,14 +38,14 @@ struct InvMfmaCfg {
     static constexpr int NWPS = 4 / PPW;              // waves per strip
     static constexpr int WAVES = STRIPS * NWPS;
     static constexpr int TY = 4 * STRIPS;
-    static constexpr int RH = 4 * (STRIPS - 1) + NBLK;   // rows of the tile's query rectangle held in LDS
-    static constexpr int RW = kTileX + K - 1 + R;       // columns that hold data
+    static constexpr int RH = COMPACT ? TY + K - 1 : 4 * (STRIPS - 1) + NBLK;   // rows of the tile's query rectangle held in LDS
+    static constexpr int RW = COMPACT ? kTileX + K - 1 : kTileX + K - 1 + R;  // columns that hold data
     static constexpr int KK = K * K;
     static constexpr int kThreads = kWave * WAVES;
     using XHalo = HaloDma<T, RH, RW, WAVES>;
-    // the x rectangle in its natural layout, plus the positions a 16-wide operand block can reach past
-    // the last row (they stay zero and meet zero weights)
-    static constexpr int kXBytes = XHalo::kBytes + 16 * Traits<T>::kKeyBytes;
+    // the x rectangle in its natural layout, plus the positions an operand block can reach past it: a
+    // 16-wide block that starts up to 12 columns into the row after the last one (they meet zero weights)
+    static constexpr int kXBytes = XHalo::kBytes + 28 * Traits<T>::kKeyBytes;
     static constexpr int kRowBytes = RW * KK * (int)sizeof(T);
     static constexpr int kRowRegion = mirror_bytes(kRowBytes);
     static constexpr int kWBytes = RH * kRowRegion;
@@ -56,12 +59,12 @@ struct InvMfmaCfg {
     static constexpr int kCopyIters = (RH * kRowChunks + kThreads - 1) / kThreads;
 };
 
-template <typename T, int K, int STRIPS, int PPW>
-__global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 16 ? 4 : 2) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
+template <typename T, int K, int STRIPS, int PPW, bool COMPACT>
+__global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), COMPACT ? 6 : (2 * STRIPS * (4 / PPW) >= 16 ? 4 : 2)) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
                                                                        float scale, T *__restrict__ out, int H, int W,
                                                                        int tiles_x, int tiles_y, int ntiles,
                                                                        int tiles_per_wg, int nplanes) {
-    using C = InvMfmaCfg<T, K, STRIPS, PPW>;
+    using C = InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>;
     using XHalo = typename C::XHalo;
     constexpr int WAVES = C::WAVES;
     constexpr int SZ = (int)sizeof(T);
@@ -253,18 +256,20 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), 2 * STRIPS *(4 / PPW) >= 
     }
 }
 
-template <typename T, int K>
-static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const void *x, float scale, void *out,
+template <typename T, int K, bool COMPACT>
+static hipError_t launch_inverse_mfma_c(const Problem &p, const void *w, const void *x, float scale, void *out,
                                         hipStream_t s) {
     constexpr int STRIPS = 2, PPW = 1;
-    using C = InvMfmaCfg<T, K, STRIPS, PPW>;
-    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
+    using C = InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>;
+    constexpr int kWgPerCu = COMPACT ? 3 : 2;
+    // LDS is handed out in 512-byte units
+    static_assert(kWgPerCu * ((C::kLdsBytes + 511) / 512 * 512) <= 160 * 1024, "the workgroups of a CU share its 160 KB of LDS");
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const int ntiles = tiles_x * tiles_y * p.planes();
-    const int max_wgs = 256 * 2;
+    const int max_wgs = 256 * kWgPerCu;
     const int tiles_per_wg = (ntiles + max_wgs - 1) / max_wgs;
     const int nwg = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
-    auto kern = inverse_mfma_kernel<T, K, STRIPS, PPW>;
+    auto kern = inverse_mfma_kernel<T, K, STRIPS, PPW, COMPACT>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -276,6 +281,27 @@ static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const v
                        static_cast<const T *>(w), static_cast<const T *>(x), scale, static_cast<T *>(out), p.H, p.W,
                        tiles_x, tiles_y, ntiles, tiles_per_wg, p.planes());
     return hipGetLastError();
+}
+
+// Does the query rectangle of every 16 x 8 key tile fit (8 + K-1) x (16 + K-1) positions?
+static bool compact_fits(const Problem &p) {
+    const int K = p.K, TY = 8;
+    for (int ty0 = 0; ty0 < p.H; ty0 += TY) {
+        const int ty1 = ty0 + TY - 1 < p.H - 1 ? ty0 + TY - 1 : p.H - 1;
+        if (inv_last(ty1, p.H, K) - inv_first(ty0, p.H, K) + 1 > TY + K - 1) return false;
+    }
+    for (int tx0 = 0; tx0 < p.W; tx0 += kTileX) {
+        const int tx1 = tx0 + kTileX - 1 < p.W - 1 ? tx0 + kTileX - 1 : p.W - 1;
+        if (inv_last(tx1, p.W, K) - inv_first(tx0, p.W, K) + 1 > kTileX + K - 1) return false;
+    }
+    return true;
+}
+
+template <typename T, int K>
+static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const void *x, float scale, void *out,
+                                        hipStream_t s) {
+    return compact_fits(p) ? launch_inverse_mfma_c<T, K, true>(p, w, x, scale, out, s)
+                           : launch_inverse_mfma_c<T, K, false>(p, w, x, scale, out, s);
 }
 
 // The kernel sizes its LDS images for keys that are next to at most one border per axis; on axes
