@@ -54,13 +54,18 @@ struct InvMfmaCfg {
     static constexpr int kRowEntries = STRIPS * NBLK * 4;
     static constexpr int kTblBytes = (kColEntries + kRowEntries) * 4;
     static constexpr int kLdsBytes = kXBytes + kWBytes + 16 + kTblBytes;   // + the zero word
+    // workgroups that share a CU (LDS is handed out in 512-byte units) and the waves per SIMD that gives
+    static constexpr int kLdsAlloc = (kLdsBytes + 511) / 512 * 512;
+    static constexpr int kWgPerCu = (160 * 1024) / kLdsAlloc < (COMPACT ? 3 : 2) ? (160 * 1024) / kLdsAlloc : (COMPACT ? 3 : 2);
+    static_assert(kWgPerCu >= 1, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
+    static constexpr int kWavesPerSimd = kWgPerCu * WAVES / 4;
     // chunk grid of the weight-row copy
     static constexpr int kRowChunks = kRowRegion / 16;
     static constexpr int kCopyIters = (RH * kRowChunks + kThreads - 1) / kThreads;
 };
 
 template <typename T, int K, int STRIPS, int PPW, bool COMPACT>
-__global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), COMPACT ? 6 : (2 * STRIPS * (4 / PPW) >= 16 ? 4 : 2)) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
+__global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>::kWavesPerSimd)) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
                                                                        float scale, T *__restrict__ out, int H, int W,
                                                                        int tiles_x, int tiles_y, int ntiles,
                                                                        int tiles_per_wg, int nplanes) {
@@ -261,9 +266,7 @@ static hipError_t launch_inverse_mfma_c(const Problem &p, const void *w, const v
                                         hipStream_t s) {
     constexpr int STRIPS = 2, PPW = 1;
     using C = InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>;
-    constexpr int kWgPerCu = COMPACT ? 3 : 2;
-    // LDS is handed out in 512-byte units
-    static_assert(kWgPerCu * ((C::kLdsBytes + 511) / 512 * 512) <= 160 * 1024, "the workgroups of a CU share its 160 KB of LDS");
+    constexpr int kWgPerCu = C::kWgPerCu;
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const int ntiles = tiles_x * tiles_y * p.planes();
     const int max_wgs = 256 * kWgPerCu;
@@ -283,19 +286,20 @@ static hipError_t launch_inverse_mfma_c(const Problem &p, const void *w, const v
     return hipGetLastError();
 }
 
-// Does the query rectangle of every 16 x 8 key tile fit (8 + K-1) x (16 + K-1) positions?
-static bool compact_fits(const Problem &p) {
+// Does the query rectangle of every 16 x 8 key tile fit rows x cols positions?
+static bool rect_fits(const Problem &p, int rows, int cols) {
     const int K = p.K, TY = 8;
     for (int ty0 = 0; ty0 < p.H; ty0 += TY) {
         const int ty1 = ty0 + TY - 1 < p.H - 1 ? ty0 + TY - 1 : p.H - 1;
-        if (inv_last(ty1, p.H, K) - inv_first(ty0, p.H, K) + 1 > TY + K - 1) return false;
+        if (inv_last(ty1, p.H, K) - inv_first(ty0, p.H, K) + 1 > rows) return false;
     }
     for (int tx0 = 0; tx0 < p.W; tx0 += kTileX) {
         const int tx1 = tx0 + kTileX - 1 < p.W - 1 ? tx0 + kTileX - 1 : p.W - 1;
-        if (inv_last(tx1, p.W, K) - inv_first(tx0, p.W, K) + 1 > kTileX + K - 1) return false;
+        if (inv_last(tx1, p.W, K) - inv_first(tx0, p.W, K) + 1 > cols) return false;
     }
     return true;
 }
+static bool compact_fits(const Problem &p) { return rect_fits(p, 8 + p.K - 1, kTileX + p.K - 1); }
 
 template <typename T, int K>
 static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const void *x, float scale, void *out,
@@ -304,12 +308,14 @@ static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const v
                            : launch_inverse_mfma_c<T, K, false>(p, w, x, scale, out, s);
 }
 
-// The kernel sizes its LDS images for keys that are next to at most one border per axis; on axes
-// of at most 2K + 2 positions a key patch can be seen from both clamped ends at once, and such
-// (tiny) maps take the plain gather kernel instead.
+// The kernel sizes its LDS images for key patches and key tiles that are next to at most one border
+// per axis: a 4 x 4 patch seen from both clamped ends at once (axes of at most 2K + 2 positions) or a
+// 16 x 8 tile whose query rectangle exceeds (8 + K-1 + R) x (16 + K-1 + R) (short axes again) does not
+// fit, and such small maps take the plain gather kernel instead.
 bool inverse_mfma_supported(const Problem &p) {
     const int shortest = p.H < p.W ? p.H : p.W;
-    return p.dtype != NA2D_F32 && p.K <= 7 && shortest > 2 * p.K + 2;
+    const int R = p.K / 2;
+    return p.dtype != NA2D_F32 && p.K <= 9 && shortest > 2 * p.K + 2 && rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
 }
 
 hipError_t launch_inverse_mfma(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s) {
@@ -318,6 +324,7 @@ hipError_t launch_inverse_mfma(const Problem &p, const void *w, const void *x, f
         case 3: return launch_inverse_mfma_t<TT, 3>(p, w, x, scale, out, s);                        \
         case 5: return launch_inverse_mfma_t<TT, 5>(p, w, x, scale, out, s);                        \
         case 7: return launch_inverse_mfma_t<TT, 7>(p, w, x, scale, out, s);                        \
+        case 9: return launch_inverse_mfma_t<TT, 9>(p, w, x, scale, out, s);                        \
         default: return hipErrorInvalidValue;                                                       \
     }
     if (p.dtype == NA2D_F16) { NA2D_INV_K(f16_t) }

@@ -108,7 +108,7 @@ def test_config1_tiny_fp32(oracle):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
-@pytest.mark.parametrize("H,W,k", [(7, 7, 7), (3, 3, 3), (13, 13, 13), (14, 14, 7), (13, 40, 13), (33, 9, 9), (28, 28, 7)])
+@pytest.mark.parametrize("H,W,k", [(7, 7, 7), (3, 3, 3), (13, 13, 13), (14, 14, 7), (13, 40, 13), (33, 9, 9), (28, 28, 7), (23, 45, 9)])
 def test_degenerate_and_border_heavy_maps(oracle, H, W, k, dtype):
     # k = H = W is the self-attention limit (every window is the whole map); short axes make
     # keys sit near both borders at once
