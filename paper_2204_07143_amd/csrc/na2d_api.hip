@@ -190,9 +190,16 @@ int na2d_bwd(const na2d_problem *p, const void *q, const void *k, const void *v,
         if (launch_inverse(pr, attn, dout, 1.0f, dv, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);    // grad-v
         if (launch_softmax_bwd(pr, attn, dpds, dpds, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);    // ds
     }
-    if (launch_av(pr, dpds, k, scale, dq, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);               // grad-q
-    if (launch_inverse(pr, dpds, q, scale, dk, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);          // grad-k
-    if (d_rpb && launch_rpb_bwd(pr, dpds, d_rpb, rpb_ws, s) != hipSuccess) return from_hip(hipErrorLaunchFailure); // grad-b
+    if (d_rpb && av_rpb_supported(pr)) {   // grad-q also leaves the partial bias gradients: ds is read once less
+        float *partial = static_cast<float *>(rpb_ws);
+        if (launch_av_rpb(pr, dpds, k, scale, dq, partial, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);
+        if (launch_rpb_final_av(pr, partial, d_rpb, av_rpb_split(pr), s) != hipSuccess) return from_hip(hipErrorLaunchFailure);
+        if (launch_inverse(pr, dpds, q, scale, dk, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);      // grad-k
+    } else {
+        if (launch_av(pr, dpds, k, scale, dq, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);           // grad-q
+        if (launch_inverse(pr, dpds, q, scale, dk, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);      // grad-k
+        if (d_rpb && launch_rpb_bwd(pr, dpds, d_rpb, rpb_ws, s) != hipSuccess) return from_hip(hipErrorLaunchFailure); // grad-b
+    }
     return NA2D_OK;
 }
 

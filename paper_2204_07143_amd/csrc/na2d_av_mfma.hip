@@ -250,14 +250,19 @@ struct AvSmallCfg {
     static_assert(kRowChunks <= 2 * kWave, "a row run is loaded by two instructions of one wave");
     static constexpr int kWBytes = TY * kRowRegion;
     static constexpr int kStageBytes = kHaloBytes + kWBytes + 16;   // + the zero word
-    static constexpr int kLdsBytes = 2 * kStageBytes;
+    static constexpr int kLdsStages = 2 * kStageBytes;
+    static constexpr int kRpbBytes = WAVES * (2 * K - 1) * (2 * K - 1) * 4;   // per-wave bias-gradient tables (grad-b variant)
+    static constexpr int kLdsBytes = kLdsStages + kRpbBytes;
     static_assert(kStageBytes < 65536, "the second stage is reached through the 16-bit offset of the LDS reads");
 };
 
-template <typename T, int K>
+// RPB: the kernel also sums the weights it gathers, per lane and halo position, over its planes; at
+// the end the workgroup adds them up per cell of the (2K-1)^2 bias table in a fixed order and writes
+// one partial bias gradient (with w = ds this is grad-b, arXiv 2204.07143 Appendix A; Eq. 2's B).
+template <typename T, int K, bool RPB>
 __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restrict__ w, const T *__restrict__ y, float scale,
-                                                               T *__restrict__ out, int H, int W, int heads, int nb,
-                                                               int tiles_y, int units, int splits) {
+                                                               T *__restrict__ out, float *__restrict__ rpb_partial, int H,
+                                                               int W, int heads, int nb, int tiles_y, int units, int splits) {
     using C = AvSmallCfg<T, K>;
     using P = Patch<K>;
     static_assert(C::kThreads == 512, "launch bounds");
@@ -332,9 +337,9 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
     // Operand addresses inside the first stage.
     // Values (transposing read): inside its group of 16 lanes, lane j points at channels 4 (j % 4) .. + 3
     // of halo position 16b + 4g + j / 4 and receives channel j of positions 16b + 4g .. + 3.
-    int vaddr[2 * C::NPAIR];
+    int vaddr[P::NBLK];   // a padding block of the last pair re-reads the last real block (its weights are zero)
 #pragma unroll
-    for (int b = 0; b < 2 * C::NPAIR; ++b) {
+    for (int b = 0; b < P::NBLK; ++b) {
         int h = 16 * b + 4 * g + (j >> 2);
         h = h < P::NKEY ? h : P::NKEY - 1;   // past the end: any real position (its weight is zero)
         const int hy = P::row_of(h), hx = h - hy * P::PW;
@@ -346,46 +351,89 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
     const size_t qrow_off = ((size_t)(qy < H ? qy : H - 1) * W + tx0) * C::KK * SZ;
     auto phase_of = [&](int b) { return (int)((((size_t)b * heads + head) * plane_w + qrow_off) & 15); };
     const int phase0 = phase_of(b_begin);
+    int cur_phase = phase0;
     const bool phase_varies = (plane_w & 15) != 0;
-    int gaddr[C::NEL2];
+    unsigned in_window = 0;   // bit e: entry e points into the row run
+    int gaddr[P::NEL];   // the padding block of the last pair has no entries: its weights are zero
     {
         const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
         const int lane_row = w0 + (4 * strip + jy) * C::kRowRegion + phase0 + (4 * p + jx) * C::KK * SZ;
 #pragma unroll
-        for (int e = 0; e < C::NEL2; ++e) {
+        for (int e = 0; e < P::NEL; ++e) {
             const int h = 16 * (e >> 2) + 4 * g + (e & 3);
             const int hy = P::row_of(h), hx = h - hy * P::PW;
             const int a = hy - wy, cc = hx - wx;
             const bool ok = q_ok && h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)cc < (unsigned)K;
             gaddr[e] = ok ? lane_row + (a * K + cc) * SZ : zero_addr;
+            in_window |= ok ? (1u << e) : 0u;
         }
     }
     const int qlin = (qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1);
 
-    auto compute = [&](auto par_c, auto shift_c, int b) {
+    // RPB: wave w sums row run w of the weights per window slot (lane = slot).  All queries of the run
+    // share the bias row offset; the queries away from the left and right border also share the column
+    // offset and are summed in a register; the few border queries update the wave's private
+    // (2K-1)^2 table in LDS one at a time.
+    constexpr int NB = 2 * K - 1, CELLS = NB * NB;
+    const int rtbl = lds0 + C::kLdsStages + wave * CELLS * 4;
+    float racc = 0.f;
+    const int rpy = rpb_start(wrow < H ? wrow : H - 1, H, K);
+    const int nvalid = (W - tx0) < kTileX ? (W - tx0) : kTileX;
+    const int xi0 = (tx0 > P::R ? tx0 : P::R) - tx0;                                   // interior queries of the run:
+    const int xi1 = ((tx0 + nvalid) < (W - P::R) ? (tx0 + nvalid) : (W - P::R)) - tx0;   // [xi0, xi1)
+    const int slot_cell = (lane / K) * NB + (lane % K);   // this lane's slot inside the table, relative to (py, px)
+    if constexpr (RPB) {
+        for (int i = tid; i < C::WAVES * CELLS; i += C::kThreads) *lds_ptr<float>(lds0 + C::kLdsStages + i * 4) = 0.f;
+    }
+    auto row_sums = [&](auto par_c, int b) {
         constexpr int PAR = decltype(par_c)::value;
-        constexpr bool SHIFT = decltype(shift_c)::value != 0;
+        if (wrow >= H || lane >= C::KK) return;
+        const int run = w0 + PAR * C::kStageBytes + wave * C::kRowRegion +
+                        (int)((((size_t)b * heads + head) * plane_w + wrow_off) & 15) + lane * SZ;
+        // all sixteen reads in flight at once (queries past the end of the run re-read its first one)
+        float v[kTileX];
+#pragma unroll
+        for (int i = 0; i < kTileX; ++i) v[i] = to_f32(*lds_ptr<T>(run + (i < nvalid ? i : 0) * C::KK * SZ));
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int i = 0; i < kTileX; i += 2) {
+            s0 += (i >= xi0 && i < xi1) ? v[i] : 0.f;
+            s1 += (i + 1 >= xi0 && i + 1 < xi1) ? v[i + 1] : 0.f;
+        }
+        racc += s0 + s1;
+        if (xi0 > 0 || xi1 < nvalid) {   // border queries (the leftmost / rightmost tile of the map only)
+#pragma unroll
+            for (int i = 0; i < kTileX; ++i) {
+                if (i < nvalid && !(i >= xi0 && i < xi1)) {
+                    const int cell = rtbl + ((rpy * NB + rpb_start(tx0 + i, W, K)) + slot_cell) * 4;
+                    *lds_ptr<float>(cell) += v[i];
+                }
+            }
+        }
+    };
+
+    auto compute = [&](auto par_c, int b) {
+        constexpr int PAR = decltype(par_c)::value;
         if (!active) return;
-        const int dph = SHIFT ? phase_of(b) - phase0 : 0;
         f32x4 o[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
         for (int pb = 0; pb < C::NPAIR; ++pb) {
             uint32_t wv[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                int a_lo = gaddr[8 * pb + 2 * u], a_hi = gaddr[8 * pb + 2 * u + 1];
-                if (SHIFT) {   // entries that point at the zero word stay there
-                    a_lo = a_lo == zero_addr ? a_lo : a_lo + dph;
-                    a_hi = a_hi == zero_addr ? a_hi : a_hi + dph;
+                const int e = 8 * pb + 2 * u;
+                if (e >= P::NEL) {
+                    wv[u] = 0u;
+                    continue;
                 }
-                wv[u] = (uint32_t)*lds_ptr<uint16_t>(a_lo + PAR * C::kStageBytes) |
-                        ((uint32_t)*lds_ptr<uint16_t>(a_hi + PAR * C::kStageBytes) << 16);
+                wv[u] = (uint32_t)*lds_ptr<uint16_t>(gaddr[e] + PAR * C::kStageBytes) |
+                        ((uint32_t)*lds_ptr<uint16_t>(gaddr[e + 1] + PAR * C::kStageBytes) << 16);
             }
             const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 const u32x2 lo = lds_read_tr16(vaddr[2 * pb] + PAR * C::kStageBytes + hf * 32);
-                const u32x2 hi = lds_read_tr16(vaddr[2 * pb + 1] + PAR * C::kStageBytes + hf * 32);
+                const u32x2 hi = lds_read_tr16(vaddr[2 * pb + 1 < P::NBLK ? 2 * pb + 1 : P::NBLK - 1] + PAR * C::kStageBytes + hf * 32);
                 o[hf] = mfma_16x16x32<T>(u32x4{lo.x, lo.y, hi.x, hi.y}, bop, o[hf]);
             }
         }
@@ -412,26 +460,42 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
         wait_global_loads();   // this tile's halo and weight rows have landed
         __syncthreads();       // ... for every wave, and nobody still reads the other stage
         if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
-        if (phase_varies)
-            compute(par_c, IntC<1>{}, b);
-        else
-            compute(par_c, IntC<0>{}, b);
+        if (phase_varies) {   // the table follows the phase of this plane's row run (in-window entries only)
+            const int ph = phase_of(b), d = ph - cur_phase;
+            cur_phase = ph;
+#pragma unroll
+            for (int e = 0; e < P::NEL; ++e) gaddr[e] += ((in_window >> e) & 1u) ? d : 0;
+        }
+        compute(par_c, b);
+        if constexpr (RPB) row_sums(par_c, b);
         ++b;
     };
     while (b < b_end) {
         step(IntC<0>{});
         if (b < b_end) step(IntC<1>{});
     }
+
+    if constexpr (RPB) {
+        // interior sums into the wave's table, then the eight tables are added in wave order
+        if (wrow < H && lane < C::KK && xi1 > xi0) *lds_ptr<float>(rtbl + ((rpy * NB + P::R) + slot_cell) * 4) += racc;
+        __syncthreads();
+        for (int cell = tid; cell < CELLS; cell += C::kThreads) {
+            float sum = *lds_ptr<float>(lds0 + C::kLdsStages + cell * 4);
+#pragma unroll
+            for (int wv_ = 1; wv_ < C::WAVES; ++wv_) sum += *lds_ptr<float>(lds0 + C::kLdsStages + (wv_ * CELLS + cell) * 4);
+            rpb_partial[(size_t)wg * CELLS + cell] = sum;
+        }
+    }
 }
 
-template <typename T, int K>
+template <typename T, int K, bool RPB = false>
 static hipError_t launch_av_mfma_small_t(const Problem &p, const void *w, const void *y, float scale, void *out,
-                                         hipStream_t s) {
+                                         hipStream_t s, float *rpb_partial = nullptr) {
     using C = AvSmallCfg<T, K>;
     static_assert(C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
-    auto kern = av_mfma_small_kernel<T, K>;
+    auto kern = av_mfma_small_kernel<T, K, RPB>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -440,9 +504,34 @@ static hipError_t launch_av_mfma_small_t(const Problem &p, const void *w, const 
         attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
-                       static_cast<const T *>(w), static_cast<const T *>(y), scale, static_cast<T *>(out), p.H, p.W,
-                       p.heads, p.B, tiles_y, us.units, us.splits);
+                       static_cast<const T *>(w), static_cast<const T *>(y), scale, static_cast<T *>(out), rpb_partial, p.H,
+                       p.W, p.heads, p.B, tiles_y, us.units, us.splits);
     return hipGetLastError();
+}
+
+// grad-q together with partial bias gradients (one per workgroup, av_rpb_partials() of them)
+bool av_rpb_supported(const Problem &p) { return p.dtype != NA2D_F32 && p.K <= 7 && !force_valu(); }
+AvRpbSplit av_rpb_split(const Problem &p) {
+    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + 8 - 1) / 8;
+    const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
+    AvRpbSplit r;
+    r.npos = us.units / p.heads;
+    r.splits = us.splits;
+    return r;
+}
+hipError_t launch_av_rpb(const Problem &p, const void *w, const void *y, float scale, void *out, float *rpb_partial,
+                         hipStream_t s) {
+#define NA2D_AVR_K(TT)                                                                                        \
+    switch (p.K) {                                                                                            \
+        case 3: return launch_av_mfma_small_t<TT, 3, true>(p, w, y, scale, out, s, rpb_partial);              \
+        case 5: return launch_av_mfma_small_t<TT, 5, true>(p, w, y, scale, out, s, rpb_partial);              \
+        case 7: return launch_av_mfma_small_t<TT, 7, true>(p, w, y, scale, out, s, rpb_partial);              \
+        default: return hipErrorInvalidValue;                                                                 \
+    }
+    if (p.dtype == NA2D_F16) { NA2D_AVR_K(f16_t) }
+    if (p.dtype == NA2D_BF16) { NA2D_AVR_K(bf16_t) }
+#undef NA2D_AVR_K
+    return hipErrorInvalidValue;
 }
 
 template <typename T, int K>

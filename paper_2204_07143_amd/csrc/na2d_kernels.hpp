@@ -38,6 +38,16 @@ hipError_t launch_softmax(const Problem &p, const void *logits, void *out, hipSt
 hipError_t launch_softmax_bwd(const Problem &p, const void *attn, const void *dp, void *ds, hipStream_t s);
 size_t rpb_bwd_workspace_bytes(const Problem &p);
 hipError_t launch_rpb_bwd(const Problem &p, const void *ds, float *d_rpb, void *workspace, hipStream_t s);
+// grad-q that also leaves partial bias gradients (f16 / bf16, K <= 7): workgroup wg of the launch covers
+// tile position wg % npos, head (wg / npos) % heads and batch range wg / (npos * heads) of `splits`
+struct AvRpbSplit {
+    int npos, splits;
+};
+bool av_rpb_supported(const Problem &p);
+AvRpbSplit av_rpb_split(const Problem &p);
+hipError_t launch_av_rpb(const Problem &p, const void *w, const void *y, float scale, void *out, float *rpb_partial,
+                         hipStream_t s);
+hipError_t launch_rpb_final_av(const Problem &p, const float *partial, float *d_rpb, AvRpbSplit sp, hipStream_t s);
 hipError_t launch_fused_fwd(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
                             void *out, float *lse, hipStream_t s);
 hipError_t launch_fused_mfma(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,

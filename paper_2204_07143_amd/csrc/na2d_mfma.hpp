@@ -219,7 +219,7 @@ struct HaloDma {
     __device__ static __forceinline__ void issue_at(const char *plane_base, const int (&off)[PER_WAVE], int lds_base, int wave) {
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i)
-            if (off[i] >= 0) global_to_lds_16(plane_base + off[i], lds_base + (wave + i * NWAVES) * kWave * 16);
+            if (off[i] >= 0) global_to_lds_16(plane_base + (unsigned)off[i], lds_base + (wave + i * NWAVES) * kWave * 16);
     }
     __device__ __forceinline__ void issue(const char *plane_base, int H, int W, int oy, int ox, int lds_base, int wave) const {
 #pragma unroll

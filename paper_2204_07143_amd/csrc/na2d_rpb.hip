@@ -201,10 +201,62 @@ __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const 
     }
 }
 
+// d_rpb[h, cell] from the partials the grad-q kernel leaves: workgroup wg = (split * heads + h) * npos + pos
+// holds partial[wg][cell].  Same shape as rpb_final_kernel: one workgroup of 16 waves per head and block
+// of 64 cells, wave w adds the partials whose running index (split * npos + pos) is w mod 16, in index
+// order, eight loads at a time; the 16 sub-sums are added in wave order.
+__global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_av_kernel(const float *__restrict__ partial,
+                                                                              float *__restrict__ d_rpb, int heads, int npos,
+                                                                              int splits, int cells) {
+    __shared__ float sub[kRpbFinalWaves][kWave];
+    const int cell_blocks = (cells + kWave - 1) / kWave;
+    const int h = blockIdx.x / cell_blocks;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int cell = (blockIdx.x % cell_blocks) * kWave + lane;
+    const int n = npos * splits;
+    float acc = 0.f;
+    if (cell < cells) {
+        constexpr int U = 8;
+        auto at = [&](int i) {
+            const int sp = i / npos, ps = i - sp * npos;
+            return partial[((size_t)(sp * heads + h) * npos + ps) * cells + cell];
+        };
+        int i = wave;
+        for (; i + (U - 1) * kRpbFinalWaves < n; i += U * kRpbFinalWaves) {
+            float v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = at(i + u * kRpbFinalWaves);
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc += v[u];
+        }
+        for (; i < n; i += kRpbFinalWaves) acc += at(i);
+    }
+    sub[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && cell < cells) {
+        float s = sub[0][lane];
+        for (int w = 1; w < kRpbFinalWaves; ++w) s += sub[w][lane];
+        d_rpb[(size_t)h * cells + cell] = s;
+    }
+}
+
+hipError_t launch_rpb_final_av(const Problem &p, const float *partial, float *d_rpb, AvRpbSplit sp, hipStream_t s) {
+    const int nb = 2 * p.K - 1, cells = nb * nb;
+    hipLaunchKernelGGL(rpb_final_av_kernel, dim3(p.heads * ((cells + kWave - 1) / kWave)), dim3(kRpbFinalWaves * kWave), 0, s,
+                       partial, d_rpb, p.heads, sp.npos, sp.splits, cells);
+    return hipGetLastError();
+}
+
 size_t rpb_bwd_workspace_bytes(const Problem &p) {
     const int nb = 2 * p.K - 1;
     const RpbSplit sp = rpb_split(p.planes(), p.H, p.W, p.K, p.elem_bytes());
-    return (size_t)p.planes() * sp.groups_per_plane * nb * nb * sizeof(float);
+    size_t bytes = (size_t)p.planes() * sp.groups_per_plane * nb * nb * sizeof(float);
+    if (av_rpb_supported(p)) {   // the composed backward keeps one partial per workgroup of the grad-q kernel
+        const AvRpbSplit a = av_rpb_split(p);
+        const size_t alt = (size_t)a.npos * p.heads * a.splits * nb * nb * sizeof(float);
+        bytes = bytes > alt ? bytes : alt;
+    }
+    return bytes;
 }
 
 template <typename T, int K>
