@@ -26,6 +26,8 @@ FLAGS = [
     # packed-FP32 VALU forms stay off: plain fp32 math only
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+    # per-kernel register / scratch report, checked below: no kernel of this library may spill
+    "-Rpass-analysis=kernel-resource-usage",
 ]
 
 
@@ -43,10 +45,37 @@ def _compile(src: str, force: bool, hdr_time: float) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
-    warn = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l and l.strip())
+    _check_no_scratch(src, r.stderr)
+    warn = "\n".join(l for l in r.stderr.splitlines()
+                     if "packed-fp32-ops" not in l and "kernel-resource-usage" not in l and l.strip()
+                     and not _is_remark_context(l))
     if warn:
         sys.stderr.write(warn + "\n")
     return obj
+
+
+def _is_remark_context(line: str) -> bool:
+    """Source-echo lines that clang prints under a remark (`  56 | ...`, `     | ^`)."""
+    t = line.lstrip()
+    return t.startswith("|") or (t.split("|")[0].strip().isdigit() and "|" in t)
+
+
+def _check_no_scratch(src: str, stderr: str) -> None:
+    """Every kernel must keep its whole state in registers (ScratchSize 0): spilled builds have
+    coincided with wrong results, so a spill fails the build (the object is removed)."""
+    name, bad = None, []
+    for line in stderr.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split("[")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in line:
+            n = int(line.split("ScratchSize [bytes/lane]:")[1].split("[")[0].strip())
+            if n:
+                bad.append(f"{name}: {n} bytes/lane")
+    if bad:
+        obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+        if os.path.exists(obj):
+            os.remove(obj)
+        raise RuntimeError(f"{os.path.basename(src)}: kernels spill to scratch:\n  " + "\n  ".join(bad))
 
 
 def build(force: bool = False, jobs: int | None = None) -> str:
