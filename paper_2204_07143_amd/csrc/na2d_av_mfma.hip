@@ -335,15 +335,17 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
     issue(b_begin, 0);
 
     // Operand addresses inside the first stage.
-    // Values (transposing read): inside its group of 16 lanes, lane j points at channels 4 (j % 4) .. + 3
-    // of halo position 16b + 4g + j / 4 and receives channel j of positions 16b + 4g .. + 3.
+    // Values (transposing read): inside its group of 16 lanes, lane j points at four channels of halo
+    // position 16b + 4g + j / 4 and receives the j-th channel of positions 16b + 4g .. + 3.  The channels
+    // are dealt so that MFMA row m of half hf is channel 8 (m / 4) + 4 hf + m % 4: a lane then ends
+    // up with the eight consecutive channels 8g .. 8g + 7 of its query, one 16-byte store.
     int vaddr[P::NBLK];   // a padding block of the last pair re-reads the last real block (its weights are zero)
 #pragma unroll
     for (int b = 0; b < P::NBLK; ++b) {
         int h = 16 * b + 4 * g + (j >> 2);
         h = h < P::NKEY ? h : P::NKEY - 1;   // past the end: any real position (its weight is zero)
         const int hy = P::row_of(h), hx = h - hy * P::PW;
-        vaddr[b] = lds0 + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + (j & 3) * 8;
+        vaddr[b] = lds0 + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + (j & 3) * 16;
     }
     // Weights: LDS address of this lane's query's weight for halo position 16 (e / 4) + 4g + e % 4, the
     // zero word where the position is outside the query's window.  The addresses hold the 16-byte
@@ -353,19 +355,25 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
     const int phase0 = phase_of(b_begin);
     int cur_phase = phase0;
     const bool phase_varies = (plane_w & 15) != 0;
-    unsigned in_window = 0;   // bit e: entry e points into the row run
+    // Built per group of four consecutive halo positions (e / 4): the positions of a group that lie inside
+    // the query's window are in one halo row (a halo row holds K + 3 positions, the window K of them),
+    // normally the row of the group's first position; when that position is already right of the window,
+    // the group runs on into the next halo row and only that part can be inside.
     int gaddr[P::NEL];   // the padding block of the last pair has no entries: its weights are zero
     {
         const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
         const int lane_row = w0 + (4 * strip + jy) * C::kRowRegion + phase0 + (4 * p + jx) * C::KK * SZ;
 #pragma unroll
-        for (int e = 0; e < P::NEL; ++e) {
-            const int h = 16 * (e >> 2) + 4 * g + (e & 3);
-            const int hy = P::row_of(h), hx = h - hy * P::PW;
-            const int a = hy - wy, cc = hx - wx;
-            const bool ok = q_ok && h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)cc < (unsigned)K;
-            gaddr[e] = ok ? lane_row + (a * K + cc) * SZ : zero_addr;
-            in_window |= ok ? (1u << e) : 0u;
+        for (int G = 0; G < P::NBLK; ++G) {
+            const int h0 = 16 * G + 4 * g;
+            const int hy0 = P::row_of(h0), hx0 = h0 - hy0 * P::PW;
+            const bool wrap = hx0 > wx + K - 1;
+            const int a = hy0 + (wrap ? 1 : 0) - wy;
+            int c0 = hx0 - (wrap ? P::PW : 0) - wx;   // window column of the group's first position (may be negative)
+            const int base = lane_row + (a * K + c0) * SZ;
+            c0 = (q_ok && (unsigned)a < (unsigned)K) ? c0 : 64;   // no row of the window: every column test fails
+#pragma unroll
+            for (int i = 0; i < 4; ++i) gaddr[4 * G + i] = (unsigned)(c0 + i) < (unsigned)K ? base + i * SZ : zero_addr;
         }
     }
     const int qlin = (qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1);
@@ -432,25 +440,22 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
             const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
-                const u32x2 lo = lds_read_tr16(vaddr[2 * pb] + PAR * C::kStageBytes + hf * 32);
-                const u32x2 hi = lds_read_tr16(vaddr[2 * pb + 1 < P::NBLK ? 2 * pb + 1 : P::NBLK - 1] + PAR * C::kStageBytes + hf * 32);
+                const u32x2 lo = lds_read_tr16(vaddr[2 * pb] + PAR * C::kStageBytes + hf * 8);
+                const u32x2 hi = lds_read_tr16(vaddr[2 * pb + 1 < P::NBLK ? 2 * pb + 1 : P::NBLK - 1] + PAR * C::kStageBytes + hf * 8);
                 o[hf] = mfma_16x16x32<T>(u32x4{lo.x, lo.y, hi.x, hi.y}, bop, o[hf]);
             }
         }
         if (q_ok) {
-            char *dst = reinterpret_cast<char *>(out) + ((size_t)b * heads + head) * plane_y + qlin * Traits<T>::kKeyBytes + g * 8;
+            char *dst = reinterpret_cast<char *>(out) + ((size_t)b * heads + head) * plane_y + qlin * Traits<T>::kKeyBytes + g * 16;
+            uint32_t ov[4];
 #pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                uint32_t ov[2];
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    typedef float f32x2_t __attribute__((ext_vector_type(2)));
-                    typedef T tx2_t __attribute__((ext_vector_type(2)));
-                    ov[u] = __builtin_bit_cast(
-                        uint32_t, __builtin_convertvector((f32x2_t){o[hf][2 * u] * scale, o[hf][2 * u + 1] * scale}, tx2_t));
-                }
-                *reinterpret_cast<uint64_t *>(dst + hf * 32) = (uint64_t)ov[0] | ((uint64_t)ov[1] << 32);
+            for (int u = 0; u < 4; ++u) {
+                typedef float f32x2_t __attribute__((ext_vector_type(2)));
+                typedef T tx2_t __attribute__((ext_vector_type(2)));
+                const int hf = u >> 1, r = 2 * (u & 1);
+                ov[u] = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){o[hf][r] * scale, o[hf][r + 1] * scale}, tx2_t));
             }
+            *reinterpret_cast<u32x4 *>(dst) = u32x4{ov[0], ov[1], ov[2], ov[3]};   // channels 8g .. 8g + 7
         }
     };
 
@@ -464,7 +469,7 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
             const int ph = phase_of(b), d = ph - cur_phase;
             cur_phase = ph;
 #pragma unroll
-            for (int e = 0; e < P::NEL; ++e) gaddr[e] += ((in_window >> e) & 1u) ? d : 0;
+            for (int e = 0; e < P::NEL; ++e) gaddr[e] += gaddr[e] != zero_addr ? d : 0;
         }
         compute(par_c, b);
         if constexpr (RPB) row_sums(par_c, b);

@@ -67,14 +67,25 @@ struct InvMfmaCfg {
 template <typename T, int K, int STRIPS, int PPW, bool COMPACT>
 __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>::kWavesPerSimd)) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
                                                                        float scale, T *__restrict__ out, int H, int W,
-                                                                       int tiles_x, int tiles_y, int ntiles,
-                                                                       int tiles_per_wg, int nplanes) {
+                                                                       int heads, int nb, int tiles_y, int units, int splits) {
     using C = InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>;
     using XHalo = typename C::XHalo;
     constexpr int WAVES = C::WAVES;
     constexpr int SZ = (int)sizeof(T);
     constexpr int BIG = 1 << 24;   // invalid row / column terms push the sum past the zero word
     extern __shared__ __align__(16) char lds[];
+
+    // A workgroup keeps one tile position and one head and walks a range of the batch: the tile's
+    // geometry, the column terms and (while the 16-byte phase of the weight rows stays the same) the row
+    // terms are worked out once.  Neighbouring workgroups take neighbouring positions (numbered down the
+    // columns of the map) of the same planes at the same time, so the query rows and columns that
+    // adjacent tiles share are fetched from memory once and found in the L2 cache by the others.
+    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    if (wg >= units * splits) return;
+    const int npos = units / heads;
+    const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
+    const int b_begin = (split * nb) / splits, b_end = ((split + 1) * nb) / splits;
+    if (b_begin >= b_end) return;
 
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -86,47 +97,51 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
 
     // Everything the stagers do not write must hold finite numbers (it meets zero weights only).
     for (int i = tid * 16; i < C::kLdsBytes; i += C::kThreads * 16) *lds_ptr<u32x4>(lds0 + i) = u32x4{0u, 0u, 0u, 0u};
-    __syncthreads();
 
     // lane-constant part of the A-operand address (transposing read): inside its group of 16, lane n
     // points at channels 4 (n % 4) .. + 3 of position 4g + n / 4 of a block and receives channel n of
     // positions 4g .. 4g + 3
     const int xa_lane = lds0 + (4 * g + (n >> 2)) * Traits<T>::kKeyBytes + (n & 3) * 8;
+
+    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
+    const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
+    const int tx1 = tx0 + kTileX - 1 < W - 1 ? tx0 + kTileX - 1 : W - 1;
+    const int ry0 = inv_first(ty0, H, K), ry1 = inv_last(ty1, H, K);
+    const int rx0 = inv_first(tx0, W, K), rx1 = inv_last(tx1, W, K);
+    const int nrows = ry1 - ry0 + 1, ncols = rx1 - rx0 + 1;   // <= RH, <= RW
+    const int row_pitch_bytes = W * C::KK * SZ;                // < 2^31: checked by the host
+    const int pitch_phase = row_pitch_bytes & 15;
+    const int nbytes = ncols * C::KK * SZ;
+    const size_t w_bytes = (size_t)nb * heads * H * W * C::KK * SZ;   // size of the weight tensor
+
     XHalo xhalo;
     xhalo.init(wave, lane);
+    int xoff[XHalo::PER_WAVE];
+    xhalo.offsets(H, W, ry0, rx0, xoff);
 
-    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
-    const int t_begin = wg * tiles_per_wg;
-    const int t_end = (wg + 1) * tiles_per_wg < ntiles ? (wg + 1) * tiles_per_wg : ntiles;
+    const int strip = wave / C::NWPS;
+    const int sy0 = ty0 + 4 * strip;              // first key row of this wave's strip
+    const int p0 = (wave % C::NWPS) * PPW;        // its first patch of the strip
+    const int jy = sy0 + ky;
+    const int oqy = inv_first(sy0 < H ? sy0 : H - 1, H, K);   // first query row of the strip's halo
+    int rowterm[C::NBLK];
+    int colterm[PPW][4];
+    int xpatch[PPW];
+#pragma unroll
+    for (int p = 0; p < PPW; ++p) {
+        const int px0 = tx0 + 4 * (p0 + p);
+        const int oqx = inv_first(px0 < W ? px0 : W - 1, W, K);   // as in the column table
+        xpatch[p] = ((oqy - ry0) * C::RW + (oqx - rx0)) * Traits<T>::kKeyBytes;
+    }
+    int mis_tables = -1;   // weight-row phase the tables in LDS were built for
+    __syncthreads();
 
-    const size_t w_bytes = (size_t)nplanes * H * W * C::KK * SZ;   // size of the weight tensor
-
-    // Tiles are numbered down the columns of a plane (the row index runs fastest), so the tiles a
-    // workgroup takes one after the other overlap in most of their query rows and the tiles of its
-    // neighbours, running alongside, in the rest: the halo is re-read from the L2 cache while it is hot.
-    int tiy = t_begin % tiles_y;
-    int tix = (t_begin / tiles_y) % tiles_x;
-    int plane = t_begin / (tiles_y * tiles_x);
-    for (int t = t_begin; t < t_end; ++t) {
-        const int ty0 = tiy * C::TY, tx0 = tix * kTileX;
-        const size_t plane_q = (size_t)plane * H * W;
-        if (++tiy == tiles_y) {
-            tiy = 0;
-            if (++tix == tiles_x) {
-                tix = 0;
-                ++plane;
-            }
-        }
-        const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
-        const int tx1 = tx0 + kTileX - 1 < W - 1 ? tx0 + kTileX - 1 : W - 1;
-        const int ry0 = inv_first(ty0, H, K), ry1 = inv_last(ty1, H, K);
-        const int rx0 = inv_first(tx0, W, K), rx1 = inv_last(tx1, W, K);
-        const int nrows = ry1 - ry0 + 1, ncols = rx1 - rx0 + 1;   // <= RH, <= RW
-
-        __syncthreads();   // the previous tile's LDS images are no longer read
+    for (int b = b_begin; b < b_end; ++b) {
+        const size_t plane_q = ((size_t)b * heads + head) * H * W;
         const size_t g0first = (plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ;   // first byte of the first weight row
-        const int row_pitch_bytes = W * C::KK * SZ;                              // < 2^31: checked by the host
-        const int mis0 = (int)(g0first & 15), pitch_phase = row_pitch_bytes & 15;   // 16-byte phase of row r: (mis0 + r * pitch_phase) & 15
+        const int mis0 = (int)(g0first & 15);   // 16-byte phase of row r: (mis0 + r * pitch_phase) & 15
+
+        if (b > b_begin) __syncthreads();   // the previous tile's LDS images are no longer read
         // Stage the rectangle.  Weight rows go from global memory straight into LDS (no registers): a
         // row is mirrored at its 16-byte phase, one 16-byte chunk per lane, 64 chunks per instruction;
         // the chunks at the two ends also bring in bytes of the neighbouring rows, which nothing reads.
@@ -137,7 +152,6 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
             const char *wrow = reinterpret_cast<const char *>(w) + (g0first - mis0);   // 16-byte aligned
             const size_t left = w_bytes - (g0first - mis0);                             // bytes up to the tensor's end
             const int rem = left < (size_t)0x7fffffff ? (int)left : 0x7fffffff;
-            const int nbytes = ncols * C::KK * SZ;
 #pragma unroll
             for (int i = 0; i < PER_WAVE; ++i) {
                 const int item = wave + i * WAVES;
@@ -160,56 +174,55 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
                     *lds_ptr<T>(w0 + (nrows - 1) * C::kRowRegion + (off - (rel_last & ~15))) = *reinterpret_cast<const T *>(wrow + off);
             }
         }
+        // x vectors, natural layout
+        XHalo::issue_at(reinterpret_cast<const char *>(x) + plane_q * Traits<T>::kKeyBytes, xoff, lds0, wave);
+
         // Gather-address tables, one entry per thread: the address of the weight that query (iy, ix)
         // gives key (jy, jx) is rowterm(iy, jy) + colterm(ix, jx); a pair that does not meet gets BIG.
-        for (int e = tid; e < C::kColEntries + C::kRowEntries; e += C::kThreads) {
-            int term = BIG;
-            if (e < C::kColEntries) {
-                const int r = e & 3, kxe = (e >> 2) & 3, ge = (e >> 4) & 3, pe = e >> 6;
-                const int px0 = tx0 + 4 * pe, jx = px0 + kxe;
-                // halo columns start at the first query column that sees the patch; the 16-wide block
-                // reaches the last such column (at most K + R + 3 <= 13 of them)
-                const int ix = inv_first(px0 < W ? px0 : W - 1, W, K) + 4 * ge + r;
-                const int c = jx - win_start(ix < W ? ix : W - 1, W, K);
-                if (px0 < W && ix <= rx1 && jx < W && (unsigned)c < (unsigned)K) term = (ix - rx0) * C::KK * SZ + c * SZ;
-            } else {
-                const int l = e - C::kColEntries;
-                const int kye = l & 3, b = (l >> 2) % C::NBLK, strip = (l >> 2) / C::NBLK;
-                const int sy = ty0 + 4 * strip, jy = sy + kye;
-                const int iy = inv_first(sy < H ? sy : H - 1, H, K) + b;   // halo row b of the strip
-                const int a = jy - win_start(iy < H ? iy : H - 1, H, K);
-                if (b < C::PWI && iy <= ry1 && jy < H && (unsigned)a < (unsigned)K)
-                    term = w0 + (iy - ry0) * C::kRowRegion + ((mis0 + (iy - ry0) * pitch_phase) & 15) + a * K * SZ;
+        const bool rebuild = mis0 != mis_tables;   // same for the whole workgroup
+        if (rebuild) {
+            for (int e = tid; e < C::kColEntries + C::kRowEntries; e += C::kThreads) {
+                int term = BIG;
+                if (e < C::kColEntries) {
+                    const int r = e & 3, kxe = (e >> 2) & 3, ge = (e >> 4) & 3, pe = e >> 6;
+                    const int px0 = tx0 + 4 * pe, jx = px0 + kxe;
+                    // halo columns start at the first query column that sees the patch; the 16-wide block
+                    // reaches the last such column (at most K + R + 3 <= 13 of them)
+                    const int ix = inv_first(px0 < W ? px0 : W - 1, W, K) + 4 * ge + r;
+                    const int c = jx - win_start(ix < W ? ix : W - 1, W, K);
+                    if (px0 < W && ix <= rx1 && jx < W && (unsigned)c < (unsigned)K) term = (ix - rx0) * C::KK * SZ + c * SZ;
+                } else {
+                    const int l = e - C::kColEntries;
+                    const int kye = l & 3, bb = (l >> 2) % C::NBLK, st = (l >> 2) / C::NBLK;
+                    const int sy = ty0 + 4 * st, jyy = sy + kye;
+                    const int iy = inv_first(sy < H ? sy : H - 1, H, K) + bb;   // halo row bb of the strip
+                    const int a = jyy - win_start(iy < H ? iy : H - 1, H, K);
+                    if (bb < C::PWI && iy <= ry1 && jyy < H && (unsigned)a < (unsigned)K)
+                        term = w0 + (iy - ry0) * C::kRowRegion + ((mis0 + (iy - ry0) * pitch_phase) & 15) + a * K * SZ;
+                }
+                *lds_ptr<int>(tbl_col + e * 4) = term;
             }
-            *lds_ptr<int>(tbl_col + e * 4) = term;
+            mis_tables = mis0;
         }
-        // x vectors, natural layout
-        xhalo.issue(reinterpret_cast<const char *>(x) + plane_q * Traits<T>::kKeyBytes, H, W, ry0, rx0, lds0, wave);
         wait_global_loads();
         __syncthreads();
-
-        const int sy0 = ty0 + 4 * (wave / C::NWPS);   // first key row of this wave's strip
-        const int p0 = (wave % C::NWPS) * PPW;        // its first patch of the strip
-        if (sy0 >= H) continue;
-        const int strip = wave / C::NWPS;
-        const int jy = sy0 + ky;
-        const int oqy = inv_first(sy0, H, K);   // first query row of the strip's halo
-        int rowterm[C::NBLK];
+        if (rebuild) {
 #pragma unroll
-        for (int b = 0; b < C::NBLK; ++b) rowterm[b] = *lds_ptr<int>(tbl_row + ((strip * C::NBLK + b) * 4 + ky) * 4);
-        int colterm[PPW][4];
-        int xpatch[PPW];
+            for (int bb = 0; bb < C::NBLK; ++bb) rowterm[bb] = *lds_ptr<int>(tbl_row + ((strip * C::NBLK + bb) * 4 + ky) * 4);
+#pragma unroll
+            for (int p = 0; p < PPW; ++p) {
+                const u32x4 ct = *lds_ptr<u32x4>(tbl_col + (((p0 + p) * 4 + g) * 4 + kx) * 16);
+                colterm[p][0] = (int)ct.x;
+                colterm[p][1] = (int)ct.y;
+                colterm[p][2] = (int)ct.z;
+                colterm[p][3] = (int)ct.w;
+            }
+        }
+        if (sy0 >= H) continue;
+
         f32x4 acc[PPW][2];
 #pragma unroll
         for (int p = 0; p < PPW; ++p) {
-            const int px0 = tx0 + 4 * (p0 + p);
-            const u32x4 ct = *lds_ptr<u32x4>(tbl_col + (((p0 + p) * 4 + g) * 4 + kx) * 16);
-            colterm[p][0] = (int)ct.x;
-            colterm[p][1] = (int)ct.y;
-            colterm[p][2] = (int)ct.z;
-            colterm[p][3] = (int)ct.w;
-            const int oqx = inv_first(px0 < W ? px0 : W - 1, W, K);   // as in the column table
-            xpatch[p] = ((oqy - ry0) * C::RW + (oqx - rx0)) * Traits<T>::kKeyBytes;
             acc[p][0] = f32x4{0.f, 0.f, 0.f, 0.f};
             acc[p][1] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
@@ -222,9 +235,9 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
                     uint32_t wv[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        const int b = 2 * pb + (u >> 1);
+                        const int bb = 2 * pb + (u >> 1);
                         const int r0 = (u & 1) * 2;
-                        int a_lo = rowterm[b] + colterm[p][r0], a_hi = rowterm[b] + colterm[p][r0 + 1];
+                        int a_lo = rowterm[bb] + colterm[p][r0], a_hi = rowterm[bb] + colterm[p][r0 + 1];
                         a_lo = a_lo < zero_addr ? a_lo : zero_addr;
                         a_hi = a_hi < zero_addr ? a_hi : zero_addr;
                         wv[u] = (uint32_t)*lds_ptr<uint16_t>(a_lo) | ((uint32_t)*lds_ptr<uint16_t>(a_hi) << 16);
@@ -268,10 +281,11 @@ static hipError_t launch_inverse_mfma_c(const Problem &p, const void *w, const v
     using C = InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>;
     constexpr int kWgPerCu = C::kWgPerCu;
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
-    const int ntiles = tiles_x * tiles_y * p.planes();
-    const int max_wgs = 256 * kWgPerCu;
-    const int tiles_per_wg = (ntiles + max_wgs - 1) / max_wgs;
-    const int nwg = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
+    // (tile position, head) units, the batch cut into ranges so that every workgroup slot of the chip is used
+    const int units = tiles_x * tiles_y * p.heads;
+    int splits = (256 * kWgPerCu) / units;
+    splits = splits < 1 ? 1 : (splits < p.B ? splits : p.B);
+    const int nwg = units * splits;
     auto kern = inverse_mfma_kernel<T, K, STRIPS, PPW, COMPACT>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -282,7 +296,7 @@ static hipError_t launch_inverse_mfma_c(const Problem &p, const void *w, const v
     }
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(w), static_cast<const T *>(x), scale, static_cast<T *>(out), p.H, p.W,
-                       tiles_x, tiles_y, ntiles, tiles_per_wg, p.planes());
+                       p.heads, p.B, tiles_y, units, splits);
     return hipGetLastError();
 }
 
