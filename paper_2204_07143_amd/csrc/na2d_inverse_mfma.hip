@@ -162,8 +162,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
                     const int c = j * kWave + lane;
                     const int off = (rel & ~15) + c * 16;
                     if (c < nchunks && off + 16 <= rem)
-                        __builtin_amdgcn_global_load_lds((global_void_t *)(wrow + off),
-                                                         (lds_void_t *)lds_ptr<char>(w0 + r * C::kRowRegion + j * kWave * 16), 16, 0, 0);
+                        global_to_lds_16(wrow + off, w0 + r * C::kRowRegion + j * kWave * 16);
                 }
             }
             const int rel_last = mis0 + (nrows - 1) * row_pitch_bytes;

@@ -172,11 +172,18 @@ struct TransposedHalo {
 // gfx950 can load 16 bytes per lane from global memory straight into LDS: lane l of the wave
 // writes [lds_base + 16 l, lds_base + 16 l + 16), lds_base being the same for the whole wave
 // (inactive lanes write nothing).  The load is asynchronous and completes in vmcnt order.
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef const __attribute__((address_space(1))) void global_void_t;
-
+// It is written as inline assembly, not through the compiler builtin: for the builtin the compiler
+// assumes that every later LDS read may alias the data still in flight and puts a wait for all
+// outstanding loads in front of the first LDS read that follows, which serialises a pipeline that
+// loads stage n + 1 while stage n is read.  The kernels order these loads against their LDS reads
+// themselves: wait_global_loads() and a workgroup barrier before a stage is read, a barrier after
+// its last read before it is loaded again.  M0 holds the LDS base (one wait state before its use).
 __device__ __forceinline__ void global_to_lds_16(const void *g, int lds_base) {
-    __builtin_amdgcn_global_load_lds((global_void_t *)g, (lds_void_t *)lds_ptr<char>(lds_base), 16, 0, 0);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base) : "memory");
+}
+// the same from a wave-uniform base pointer plus a 32-bit byte offset per lane
+__device__ __forceinline__ void global_to_lds_16(const char *base, unsigned off, int lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
 }
 // waits until every load of this wave, the direct-to-LDS ones included, has landed
 __device__ __forceinline__ void wait_global_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -219,7 +226,7 @@ struct HaloDma {
     __device__ static __forceinline__ void issue_at(const char *plane_base, const int (&off)[PER_WAVE], int lds_base, int wave) {
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i)
-            if (off[i] >= 0) global_to_lds_16(plane_base + (unsigned)off[i], lds_base + (wave + i * NWAVES) * kWave * 16);
+            if (off[i] >= 0) global_to_lds_16(plane_base, (unsigned)off[i], lds_base + (wave + i * NWAVES) * kWave * 16);
     }
     __device__ __forceinline__ void issue(const char *plane_base, int H, int W, int oy, int ox, int lds_base, int wave) const {
 #pragma unroll
@@ -228,7 +235,7 @@ struct HaloDma {
                 int y = oy + (pos[i] & 0xff), x = ox + ((pos[i] >> 8) & 0xff);
                 y = y < 0 ? 0 : (y < H - 1 ? y : H - 1);
                 x = x < 0 ? 0 : (x < W - 1 ? x : W - 1);
-                global_to_lds_16(plane_base + ((y * W + x) * Traits<T>::kKeyBytes + (pos[i] >> 16) * 16),
+                global_to_lds_16(plane_base, (unsigned)((y * W + x) * Traits<T>::kKeyBytes + (pos[i] >> 16) * 16),
                                  lds_base + (wave + i * NWAVES) * kWave * 16);
             }
         }
