@@ -177,13 +177,14 @@ struct TransposedHalo {
 // outstanding loads in front of the first LDS read that follows, which serialises a pipeline that
 // loads stage n + 1 while stage n is read.  The kernels order these loads against their LDS reads
 // themselves: wait_global_loads() and a workgroup barrier before a stage is read, a barrier after
-// its last read before it is loaded again.  M0 holds the LDS base (one wait state before its use).
+// its last read before it is loaded again.  M0 holds the LDS base (one wait state before its use);
+// it is taken through readfirstlane so that it sits in a scalar register whatever the caller passes.
 __device__ __forceinline__ void global_to_lds_16(const void *g, int lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base) : "memory");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
 }
 // the same from a wave-uniform base pointer plus a 32-bit byte offset per lane
 __device__ __forceinline__ void global_to_lds_16(const char *base, unsigned off, int lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
 }
 // waits until every load of this wave, the direct-to-LDS ones included, has landed
 __device__ __forceinline__ void wait_global_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }

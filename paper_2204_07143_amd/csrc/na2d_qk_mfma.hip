@@ -394,18 +394,31 @@ __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
     {
         const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
         const int lane_stage = stage0 + (4 * strip + jy) * C::kRowPitch + (4 * p + jx) * C::KK * SZ;
+        // Built per group of four consecutive halo positions (e / 4): the positions of a group that lie
+        // inside the query's window are in one halo row (a halo row holds K + 3 positions, the window K of
+        // them), normally the row of the group's first position; when that one is already right of the
+        // window, the group runs on into the next halo row and only that part can be inside.
         int bidx[P::NEL];
 #pragma unroll
-        for (int e = 0; e < P::NEL; ++e) {
-            const int h = 16 * (e >> 2) + 4 * g + (e & 3);
-            const int hy = P::row_of(h), hx = h - hy * P::PW;
-            const int a = hy - wy, cc = hx - wx;
-            const bool ok = q_ok && h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)cc < (unsigned)K;
-            slotaddr[e] = ok ? lane_stage + (a * K + cc) * SZ : my_dump;
-            int u = hy - jy + P::R + dy, v = hx - jx + P::R + dx;
+        for (int G = 0; G < P::NBLK; ++G) {
+            const int h0 = 16 * G + 4 * g;
+            const int hy0 = P::row_of(h0), hx0 = h0 - hy0 * P::PW;
+            const bool wrap = hx0 > wx + K - 1;
+            const int hy = hy0 + (wrap ? 1 : 0), hxf = hx0 - (wrap ? P::PW : 0);   // halo row, column of the first position
+            const int a = hy - wy;
+            int c0 = hxf - wx;   // window column of the group's first position (may be negative)
+            const int base = lane_stage + (a * K + c0) * SZ;
+            c0 = (q_ok && (unsigned)a < (unsigned)K) ? c0 : 64;   // no row of the window: every column test fails
+            int u = hy - jy + P::R + dy;
             u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);   // cells outside the table belong to keys
-            v = v < 0 ? 0 : (v > C::NB - 1 ? C::NB - 1 : v);   // outside every window: value unused
-            bidx[e] = u * C::NB + v;
+            const int v0 = hxf - jx + P::R + dx;               // outside every window: value unused
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                slotaddr[4 * G + i] = (unsigned)(c0 + i) < (unsigned)K ? base + i * SZ : my_dump;
+                int v = v0 + i;
+                v = v < 0 ? 0 : (v > C::NB - 1 ? C::NB - 1 : v);
+                bidx[4 * G + i] = u * C::NB + v;
+            }
         }
         // all loads of the bias table in flight at once (one uniform branch on the table's presence)
         uint32_t bits[P::NEL];
