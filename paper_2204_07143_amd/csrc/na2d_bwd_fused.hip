@@ -137,19 +137,25 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
     const int phase0 = phase_of(b_begin);
     int cur_phase = phase0;
     const bool phase_varies = (plane_w & 15) != 0;
-    unsigned in_window = 0;   // bit e: entry e points into the row run
+    // Built per group of four consecutive halo positions (e / 4): the positions of a group that lie inside
+    // the query's window are in one halo row (a halo row holds K + 3 positions, the window K of them),
+    // normally the row of the group's first position; when that one is already right of the window, the
+    // group runs on into the next halo row and only that part can be inside.
     int gaddr[P::NEL];
     {
         const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
         const int lane_row = w0 + (4 * strip + jy) * C::kRowRegion + phase0 + (4 * p + jx) * C::KK * SZ;
 #pragma unroll
-        for (int e = 0; e < P::NEL; ++e) {
-            const int h = 16 * (e >> 2) + 4 * g + (e & 3);
-            const int hy = P::row_of(h), hx = h - hy * P::PW;
-            const int a = hy - wy, cc = hx - wx;
-            const bool ok = q_ok && h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)cc < (unsigned)K;
-            gaddr[e] = ok ? lane_row + (a * K + cc) * SZ : my_zero;
-            in_window |= ok ? (1u << e) : 0u;
+        for (int G = 0; G < P::NBLK; ++G) {
+            const int h0 = 16 * G + 4 * g;
+            const int hy0 = P::row_of(h0), hx0 = h0 - hy0 * P::PW;
+            const bool wrap = hx0 > wx + K - 1;
+            const int a = hy0 + (wrap ? 1 : 0) - wy;
+            int c0 = hx0 - (wrap ? P::PW : 0) - wx;   // window column of the group's first position (may be negative)
+            const int base = lane_row + (a * K + c0) * SZ;
+            c0 = (q_ok && (unsigned)a < (unsigned)K) ? c0 : 64;   // no row of the window: every column test fails
+#pragma unroll
+            for (int i = 0; i < 4; ++i) gaddr[4 * G + i] = (unsigned)(c0 + i) < (unsigned)K ? base + i * SZ : my_zero;
         }
     }
     auto compute = [&](auto par_c, int b) {
@@ -218,7 +224,7 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
             const int ph = phase_of(b), d = ph - cur_phase;
             cur_phase = ph;
 #pragma unroll
-            for (int e = 0; e < P::NEL; ++e) gaddr[e] += ((in_window >> e) & 1u) ? d : 0;
+            for (int e = 0; e < P::NEL; ++e) gaddr[e] += gaddr[e] != my_zero ? d : 0;
         }
         compute(par_c, b);
         ++b;

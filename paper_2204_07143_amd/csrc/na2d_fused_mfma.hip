@@ -375,8 +375,10 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
     issue(b_begin, 0);
 
     // Operand addresses inside the first buffer pair.  Keys: halo position 16b + j, bytes [16g, 16g+16).
-    // Values (transposing read): inside its group of 16 lanes, lane j points at channels 4 (j % 4) .. + 3
-    // of halo position 16b + 4g + j / 4 and receives channel j of positions 16b + 4g .. + 3.
+    // Values (transposing read): inside its group of 16 lanes, lane j points at four channels of halo
+    // position 16b + 4g + j / 4 and receives the j-th channel of positions 16b + 4g .. + 3.  The channels
+    // are dealt so that MFMA row m of half hf is channel 8 (m / 4) + 4 hf + m % 4: a lane then ends
+    // up with the eight consecutive channels 8g .. 8g + 7 of its query, one 16-byte store.
     int koff[P::NBLK], vaddr[C::NBLK2];
 #pragma unroll
     for (int b = 0; b < C::NBLK2; ++b) {
@@ -388,24 +390,29 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
         h = h < P::NKEY ? h : P::NKEY - 1;
         hy = P::row_of(h);
         hx = h - hy * P::PW;
-        vaddr[b] = lds0 + C::kHaloBytes + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + (j & 3) * 8;
+        vaddr[b] = lds0 + C::kHaloBytes + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + (j & 3) * 16;
     }
     // log2(e) * bias of (this lane's query, halo position), -inf outside the query's window; packed
     // fp16 pairs (half the registers; the fma below reads them as mixed-precision operands)
     f16x2 biasm[P::NEL / 2];
     {
         const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
+        // Built per group of four consecutive halo positions (e / 4): the positions of a group that lie
+        // inside the query's window are in one halo row (a halo row holds K + 3 positions, the window K of
+        // them), normally the row of the group's first position; when that one is already right of the
+        // window, the group runs on into the next halo row and only that part can be inside.
         int bidx[P::NEL];   // cell of the bias table, -1 outside the window
 #pragma unroll
-        for (int e = 0; e < P::NEL; ++e) {
-            const int h = 16 * (e >> 2) + 4 * g + (e & 3);
-            const int hy = P::row_of(h), hx = h - hy * P::PW;
-            const int a = hy - wy, cc = hx - wx;
-            const bool ok = q_ok && h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)cc < (unsigned)K;
-            int u = hy - jy + P::R + dy, vv = hx - jx + P::R + dx;
-            u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);
-            vv = vv < 0 ? 0 : (vv > C::NB - 1 ? C::NB - 1 : vv);
-            bidx[e] = ok ? u * C::NB + vv : -1;
+        for (int G = 0; G < P::NBLK; ++G) {
+            const int h0 = 16 * G + 4 * g;
+            const int hy0 = P::row_of(h0), hx0 = h0 - hy0 * P::PW;
+            const bool wrap = hx0 > wx + K - 1;
+            const int hy = hy0 + (wrap ? 1 : 0), hxf = hx0 - (wrap ? P::PW : 0);   // halo row, column of the first position
+            const int a = hy - wy;
+            const int c0 = (q_ok && (unsigned)a < (unsigned)K) ? hxf - wx : 64;   // no row of the window: every column test fails
+            const int cell0 = (hy - jy + P::R + dy) * C::NB + (hxf - jx + P::R + dx);   // inside the table wherever the window test holds
+#pragma unroll
+            for (int i = 0; i < 4; ++i) bidx[4 * G + i] = (unsigned)(c0 + i) < (unsigned)K ? cell0 + i : -1;
         }
         // all loads of the bias table in flight at once (one uniform branch on the table's presence)
         float bias[P::NEL];
@@ -469,24 +476,20 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
             }
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
-                const u32x2 lo = lds_read_tr16(vaddr[2 * pb] + PAR * C::kStageBytes + hf * 32);
-                const u32x2 hi = lds_read_tr16(vaddr[2 * pb + 1] + PAR * C::kStageBytes + hf * 32);
+                const u32x2 lo = lds_read_tr16(vaddr[2 * pb] + PAR * C::kStageBytes + hf * 8);
+                const u32x2 hi = lds_read_tr16(vaddr[2 * pb + 1] + PAR * C::kStageBytes + hf * 8);
                 const u32x4 aop = u32x4{lo.x, lo.y, hi.x, hi.y};
                 o[hf] = mfma_16x16x32<T>(aop, bop, o[hf]);
                 if constexpr (sizeof(T) == 2 && Traits<T>::kDtype == NA2D_BF16) o[hf] = mfma_16x16x32<T>(aop, bop_lo, o[hf]);
             }
         }
-        // 5. normalise and store this lane's 8 channels of its own query
+        // 5. normalise and store this lane's 8 channels (8g .. 8g + 7) of its own query
         if (q_ok) {
             const float inv = __builtin_amdgcn_rcpf(l);   // 1 ulp; the result is rounded to 11 or 8 bits
             const size_t plane = (size_t)b * heads + head;
-            char *dst = reinterpret_cast<char *>(out) + plane * plane_bytes + qlin * Traits<T>::kKeyBytes + g * 8;
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                const uint32_t lo = pack2<T>(o[hf][0] * inv, o[hf][1] * inv);
-                const uint32_t hi = pack2<T>(o[hf][2] * inv, o[hf][3] * inv);
-                *reinterpret_cast<uint64_t *>(dst + hf * 32) = (uint64_t)lo | ((uint64_t)hi << 32);
-            }
+            char *dst = reinterpret_cast<char *>(out) + plane * plane_bytes + qlin * Traits<T>::kKeyBytes + g * 16;
+            *reinterpret_cast<u32x4 *>(dst) = u32x4{pack2<T>(o[0][0] * inv, o[0][1] * inv), pack2<T>(o[0][2] * inv, o[0][3] * inv),
+                                                    pack2<T>(o[1][0] * inv, o[1][1] * inv), pack2<T>(o[1][2] * inv, o[1][3] * inv)};
             if (lse != nullptr && g == 0) lse[plane * H * W + qlin] = (m + __builtin_amdgcn_logf(l)) * kLn2;
         }
     };

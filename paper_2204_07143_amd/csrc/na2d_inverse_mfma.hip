@@ -17,7 +17,7 @@
 //              its key column); invalid combinations read a zero word.  Row terms are rebuilt when
 //              the strip's rows change class, column terms per patch (4 values);
 //   halo rows that no key of the patch is seen from are skipped (wave-uniform mask).
-// Each lane ends up with 8 channels of its own key: scale, convert, two 8-byte global stores.
+// Each lane ends up with 8 consecutive channels of its own key: scale, convert, one 16-byte global store.
 #include "na2d_kernels.hpp"
 #include "na2d_mfma.hpp"
 #include "na2d_tile.hpp"
@@ -99,9 +99,10 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
     for (int i = tid * 16; i < C::kLdsBytes; i += C::kThreads * 16) *lds_ptr<u32x4>(lds0 + i) = u32x4{0u, 0u, 0u, 0u};
 
     // lane-constant part of the A-operand address (transposing read): inside its group of 16, lane n
-    // points at channels 4 (n % 4) .. + 3 of position 4g + n / 4 of a block and receives channel n of
-    // positions 4g .. 4g + 3
-    const int xa_lane = lds0 + (4 * g + (n >> 2)) * Traits<T>::kKeyBytes + (n & 3) * 8;
+    // points at four channels of position 4g + n / 4 of a block and receives the n-th channel of positions
+    // 4g .. 4g + 3.  The channels are dealt so that MFMA row m of half hf is channel 8 (m / 4) + 4 hf + m % 4:
+    // a lane then ends up with the eight consecutive channels 8g .. 8g + 7 of its key, one 16-byte store.
+    const int xa_lane = lds0 + (4 * g + (n >> 2)) * Traits<T>::kKeyBytes + (n & 3) * 16;
 
     const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
     const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
@@ -244,7 +245,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
                     const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
 #pragma unroll
                     for (int hf = 0; hf < 2; ++hf) {
-                        const int a0 = xa_lane + xpatch[p] + (2 * pb) * C::RW * Traits<T>::kKeyBytes + hf * 32;
+                        const int a0 = xa_lane + xpatch[p] + (2 * pb) * C::RW * Traits<T>::kKeyBytes + hf * 8;
                         const u32x2 lo = lds_read_tr16(a0);
                         const u32x2 hi = lds_read_tr16(a0 + C::RW * Traits<T>::kKeyBytes);
                         const u32x4 aop = u32x4{lo.x, lo.y, hi.x, hi.y};
@@ -257,17 +258,15 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
         for (int p = 0; p < PPW; ++p) {
             const int jx = tx0 + 4 * (p0 + p) + kx;
             if (jy < H && jx < W) {
-                char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * Traits<T>::kKeyBytes + g * 8;
+                char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * Traits<T>::kKeyBytes + g * 16;
+                uint32_t o[4];
 #pragma unroll
-                for (int hf = 0; hf < 2; ++hf) {
-                    uint32_t o[2];
-#pragma unroll
-                    for (int u = 0; u < 2; ++u) {
-                        const T lo = from_f32<T>(acc[p][hf][2 * u] * scale), hi = from_f32<T>(acc[p][hf][2 * u + 1] * scale);
-                        o[u] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
-                    }
-                    *reinterpret_cast<uint64_t *>(dst + hf * 32) = (uint64_t)o[0] | ((uint64_t)o[1] << 32);
+                for (int u = 0; u < 4; ++u) {
+                    const int hf = u >> 1, r = 2 * (u & 1);
+                    const T lo = from_f32<T>(acc[p][hf][r] * scale), hi = from_f32<T>(acc[p][hf][r + 1] * scale);
+                    o[u] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
                 }
+                *reinterpret_cast<u32x4 *>(dst) = u32x4{o[0], o[1], o[2], o[3]};   // channels 8g .. 8g + 7
             }
         }
     }
