@@ -67,7 +67,7 @@ typedef struct {
 } na2d_problem;
 
 /* Which call a workspace size is asked for (na2d_workspace_bytes). */
-typedef enum { NA2D_WS_QK_BWD_RPB = 0, NA2D_WS_BWD = 1 } na2d_ws_kind;
+typedef enum { NA2D_WS_QK_BWD_RPB = 0, NA2D_WS_BWD = 1, NA2D_WS_FUSED_BWD = 2 } na2d_ws_kind;
 
 /* ---- forward ------------------------------------------------------------------ */
 
@@ -133,6 +133,29 @@ int na2d_qk_bwd_rpb(const na2d_problem *p, const void *ds, float *d_rpb, void *w
 int na2d_bwd(const na2d_problem *p, const void *q, const void *k, const void *v, const void *attn,
              const void *dout, float scale, void *dq, void *dk, void *dv, float *d_rpb,
              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Whole backward without the k*k tensors (the step next to the fused forward; the paper has no fused
+ * path and names NA as an implicit GEMM as future work, Appendix A): dq, dk, dv and (if d_rpb != NULL)
+ * d_rpb of out = NA(q, k, v, rpb) from q, k, v, rpb, dout and `lse`, the log-sum-exp that
+ * na2d_fused_fwd stored for every query.  The attention weights are recomputed per tile as
+ * exp(scale <q, k> + bias - lse) and neither they nor dp / ds reach memory.  `rpb` may be NULL
+ * (no bias in the forward).  No output may alias an input or another output.
+ * For the 16-bit types with k <= 7 (maps whose key tiles all see at most (8 + k-1) x (16 + k-1)
+ * queries) this runs two kernels: query patches (dq, the partial bias gradients and
+ * delta_n = sum_j P[n, j] dP[n, j]) and key patches (dk, dv); d_rpb is then summed with LDS atomics, and
+ * for k = 7 the order in which the contributions of two waves meet is not fixed, so its last bits can
+ * differ between runs.  Every other case recomputes the attention weights into the workspace and runs
+ * the unfused backward (bitwise reproducible).
+ * `workspace` must hold na2d_workspace_bytes(p, NA2D_WS_FUSED_BWD) bytes; no initialisation needed.
+ */
+int na2d_fused_bwd(const na2d_problem *p, const void *q, const void *k, const void *v, const void *rpb,
+                   float scale, const float *lse, const void *dout, void *dq, void *dk, void *dv, float *d_rpb,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* 1 if na2d_fused_bwd runs its two fused kernels for this problem, 0 if it recomputes the attention
+ * weights and runs the unfused steps, a negative na2d_status for an invalid problem.  Host only. */
+int na2d_fused_bwd_is_fused(const na2d_problem *p);
 
 /* Bytes of device workspace the given call needs for this problem (0 on invalid problems). */
 size_t na2d_workspace_bytes(const na2d_problem *p, int kind);

@@ -17,11 +17,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libna2d.so")
 
 DTYPE_CODES = {torch.float32: 0, torch.float16: 1, torch.bfloat16: 2}
-WS_QK_BWD_RPB, WS_BWD = 0, 1
+WS_QK_BWD_RPB, WS_BWD, WS_FUSED_BWD = 0, 1, 2
 
 EXPORTS = (
     "na2d_qk_rpb", "na2d_softmax", "na2d_av", "na2d_fused_fwd", "na2d_av_bwd_p", "na2d_av_bwd_v",
-    "na2d_softmax_bwd", "na2d_qk_bwd_q", "na2d_qk_bwd_k", "na2d_qk_bwd_rpb", "na2d_bwd",
+    "na2d_softmax_bwd", "na2d_qk_bwd_q", "na2d_qk_bwd_k", "na2d_qk_bwd_rpb", "na2d_bwd", "na2d_fused_bwd",
+    "na2d_fused_bwd_is_fused",
     "na2d_workspace_bytes", "na2d_debug_indices", "na2d_host_axis_tables", "na2d_validate_problem",
     "na2d_strerror", "na2d_version",
 )
@@ -62,9 +63,11 @@ def load() -> ctypes.CDLL:
             "na2d_qk_bwd_k": [pp, vp, vp, f, vp, vp],
             "na2d_qk_bwd_rpb": [pp, vp, vp, vp, ctypes.c_size_t, vp],
             "na2d_bwd": [pp, vp, vp, vp, vp, vp, f, vp, vp, vp, vp, vp, ctypes.c_size_t, vp],
+            "na2d_fused_bwd": [pp, vp, vp, vp, vp, f, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp],
             "na2d_debug_indices": [pp, vp, vp, vp],
             "na2d_host_axis_tables": [ctypes.c_int32, ctypes.c_int32, vp, vp, vp],
             "na2d_validate_problem": [pp],
+            "na2d_fused_bwd_is_fused": [pp],
         }
         for name, argtypes in sigs.items():
             fn = getattr(lib, name)
@@ -215,6 +218,21 @@ def na2d_bwd(q, k_, v, attn, dout, scale: float, kernel: int, dq, dk, dv, d_rpb,
                            _ptr(d_rpb, torch.float32, _rpb_shape(q, kernel)) if d_rpb is not None else None,
                            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
     return dq, dk, dv, d_rpb
+
+
+def na2d_fused_bwd(q, k_, v, rpb, scale: float, lse, dout, kernel: int, dq, dk, dv, d_rpb, workspace):
+    p = _problem_of(q, kernel)
+    _check(load().na2d_fused_bwd(ctypes.byref(p), _ptr(q), _ptr(k_, q.dtype, q.shape), _ptr(v, q.dtype, q.shape),
+                                 _ptr(rpb, q.dtype, _rpb_shape(q, kernel)) if rpb is not None else None, scale,
+                                 _ptr(lse, torch.float32, q.shape[:4]), _ptr(dout, q.dtype, q.shape),
+                                 _ptr(dq, q.dtype, q.shape), _ptr(dk, q.dtype, q.shape), _ptr(dv, q.dtype, q.shape),
+                                 _ptr(d_rpb, torch.float32, _rpb_shape(q, kernel)) if d_rpb is not None else None,
+                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+    return dq, dk, dv, d_rpb
+
+
+def na2d_fused_bwd_is_fused(p: Na2dProblem) -> int:
+    return int(load().na2d_fused_bwd_is_fused(ctypes.byref(p)))
 
 
 def na2d_debug_indices(H: int, W: int, kernel: int, key_index, rpb_index):

@@ -146,9 +146,14 @@ size_t na2d_workspace_bytes(const na2d_problem *p, int kind) {
     const Problem pr = to_problem(p);
     const size_t rpb = (rpb_bwd_workspace_bytes(pr) + 255) & ~(size_t)255;
     if (kind == NA2D_WS_QK_BWD_RPB) return rpb;
-    if (kind == NA2D_WS_BWD) {
-        const size_t attn = (pr.queries() * p->k * p->k * pr.elem_bytes() + 255) & ~(size_t)255;
-        return attn + rpb;
+    const size_t attn = (pr.queries() * p->k * p->k * pr.elem_bytes() + 255) & ~(size_t)255;
+    if (kind == NA2D_WS_BWD) return attn + rpb;
+    if (kind == NA2D_WS_FUSED_BWD) {
+        if (!fused_bwd_supported(pr)) return attn + attn + rpb;
+        const AvRpbSplit sp = fused_bwd_split(pr);
+        const int nbc = 2 * pr.K - 1;
+        const size_t partials = ((size_t)sp.npos * pr.heads * sp.splits * nbc * nbc * sizeof(float) + 255) & ~(size_t)255;
+        return ((pr.queries() * sizeof(float) + 255) & ~(size_t)255) + partials;
     }
     return 0;
 }
@@ -162,25 +167,11 @@ int na2d_qk_bwd_rpb(const na2d_problem *p, const void *ds, float *d_rpb, void *w
     return from_hip(launch_rpb_bwd(to_problem(p), ds, d_rpb, workspace, static_cast<hipStream_t>(stream)));
 }
 
-int na2d_bwd(const na2d_problem *p, const void *q, const void *k, const void *v, const void *attn, const void *dout,
-             float scale, void *dq, void *dk, void *dv, float *d_rpb, void *workspace, size_t workspace_bytes,
-             void *stream) {
-    NA2D_CHECK_PROBLEM(p);
-    NA2D_REQUIRE(q); NA2D_REQUIRE(k); NA2D_REQUIRE(v); NA2D_REQUIRE(attn); NA2D_REQUIRE(dout);
-    NA2D_REQUIRE(dq); NA2D_REQUIRE(dk); NA2D_REQUIRE(dv); NA2D_OPTIONAL(d_rpb);
-    if (!workspace || misaligned(workspace) || workspace_bytes < na2d_workspace_bytes(p, NA2D_WS_BWD))
-        return NA2D_ERR_WORKSPACE;
-    const void *ins[5] = {q, k, v, attn, dout};
-    void *outs[3] = {dq, dk, dv};
-    for (void *o : outs)
-        for (const void *i : ins)
-            if (o == i) return NA2D_ERR_ALIAS;
-    if (dq == dk || dq == dv || dk == dv) return NA2D_ERR_ALIAS;
-    const Problem pr = to_problem(p);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    char *ws = static_cast<char *>(workspace);
+// The unfused backward on validated arguments: `ws` holds NA2D_WS_BWD bytes.
+static int run_bwd(const Problem &pr, const void *q, const void *k, const void *v, const void *attn, const void *dout,
+                   float scale, void *dq, void *dk, void *dv, float *d_rpb, char *ws, hipStream_t s) {
     void *dpds = ws;   // dp, overwritten in place by ds
-    const size_t attn_bytes = (pr.queries() * p->k * p->k * pr.elem_bytes() + 255) & ~(size_t)255;
+    const size_t attn_bytes = (pr.queries() * pr.K * pr.K * pr.elem_bytes() + 255) & ~(size_t)255;
     void *rpb_ws = ws + attn_bytes;
     if (bwd_fused_supported(pr)) {   // grad-a and the softmax backward in one kernel: dp never reaches memory
         if (launch_bwd_fused(pr, attn, dout, v, dpds, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);
@@ -201,6 +192,70 @@ int na2d_bwd(const na2d_problem *p, const void *q, const void *k, const void *v,
         if (d_rpb && launch_rpb_bwd(pr, dpds, d_rpb, rpb_ws, s) != hipSuccess) return from_hip(hipErrorLaunchFailure); // grad-b
     }
     return NA2D_OK;
+}
+
+int na2d_bwd(const na2d_problem *p, const void *q, const void *k, const void *v, const void *attn, const void *dout,
+             float scale, void *dq, void *dk, void *dv, float *d_rpb, void *workspace, size_t workspace_bytes,
+             void *stream) {
+    NA2D_CHECK_PROBLEM(p);
+    NA2D_REQUIRE(q); NA2D_REQUIRE(k); NA2D_REQUIRE(v); NA2D_REQUIRE(attn); NA2D_REQUIRE(dout);
+    NA2D_REQUIRE(dq); NA2D_REQUIRE(dk); NA2D_REQUIRE(dv); NA2D_OPTIONAL(d_rpb);
+    if (!workspace || misaligned(workspace) || workspace_bytes < na2d_workspace_bytes(p, NA2D_WS_BWD))
+        return NA2D_ERR_WORKSPACE;
+    const void *ins[5] = {q, k, v, attn, dout};
+    void *outs[3] = {dq, dk, dv};
+    for (void *o : outs)
+        for (const void *i : ins)
+            if (o == i) return NA2D_ERR_ALIAS;
+    if (dq == dk || dq == dv || dk == dv) return NA2D_ERR_ALIAS;
+    return run_bwd(to_problem(p), q, k, v, attn, dout, scale, dq, dk, dv, d_rpb, static_cast<char *>(workspace),
+                   static_cast<hipStream_t>(stream));
+}
+
+int na2d_fused_bwd_is_fused(const na2d_problem *p) {
+    NA2D_CHECK_PROBLEM(p);
+    return fused_bwd_supported(to_problem(p)) ? 1 : 0;
+}
+
+// Workspace of the fused backward.  Two-kernel path: delta [B, heads, H, W] fp32, then one partial bias
+// gradient per workgroup of the first kernel.  Otherwise: the recomputed attention weights, then the
+// workspace of the unfused backward.
+static size_t fused_bwd_delta_bytes(const Problem &pr) { return (pr.queries() * sizeof(float) + 255) & ~(size_t)255; }
+static size_t fused_bwd_attn_bytes(const Problem &pr) { return (pr.queries() * pr.K * pr.K * pr.elem_bytes() + 255) & ~(size_t)255; }
+
+int na2d_fused_bwd(const na2d_problem *p, const void *q, const void *k, const void *v, const void *rpb, float scale,
+                   const float *lse, const void *dout, void *dq, void *dk, void *dv, float *d_rpb, void *workspace,
+                   size_t workspace_bytes, void *stream) {
+    NA2D_CHECK_PROBLEM(p);
+    NA2D_REQUIRE(q); NA2D_REQUIRE(k); NA2D_REQUIRE(v); NA2D_OPTIONAL(rpb); NA2D_REQUIRE(lse); NA2D_REQUIRE(dout);
+    NA2D_REQUIRE(dq); NA2D_REQUIRE(dk); NA2D_REQUIRE(dv); NA2D_OPTIONAL(d_rpb);
+    if (!workspace || misaligned(workspace) || workspace_bytes < na2d_workspace_bytes(p, NA2D_WS_FUSED_BWD))
+        return NA2D_ERR_WORKSPACE;
+    const void *ins[6] = {q, k, v, rpb, lse, dout};
+    void *outs[4] = {dq, dk, dv, d_rpb};
+    for (void *o : outs)
+        for (const void *i : ins)
+            if (o && o == i) return NA2D_ERR_ALIAS;
+    if (dq == dk || dq == dv || dk == dv) return NA2D_ERR_ALIAS;
+    const Problem pr = to_problem(p);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    if (fused_bwd_supported(pr)) {
+        float *delta = reinterpret_cast<float *>(ws);
+        float *partial = d_rpb ? reinterpret_cast<float *>(ws + fused_bwd_delta_bytes(pr)) : nullptr;
+        if (launch_fbwd_q(pr, q, k, v, rpb, scale, lse, dout, dq, delta, partial, s) != hipSuccess)
+            return from_hip(hipErrorLaunchFailure);
+        if (launch_fbwd_kv(pr, q, k, v, rpb, scale, lse, delta, dout, dk, dv, s) != hipSuccess)
+            return from_hip(hipErrorLaunchFailure);
+        if (d_rpb && launch_rpb_final_av(pr, partial, d_rpb, fused_bwd_split(pr), s) != hipSuccess)
+            return from_hip(hipErrorLaunchFailure);
+        return NA2D_OK;
+    }
+    // the attention weights once more (logits, softmax in place), then the unfused steps
+    void *attn = ws;
+    if (launch_qk(pr, q, k, rpb, scale, attn, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);
+    if (launch_softmax(pr, attn, attn, s) != hipSuccess) return from_hip(hipErrorLaunchFailure);
+    return run_bwd(pr, q, k, v, attn, dout, scale, dq, dk, dv, d_rpb, ws + fused_bwd_attn_bytes(pr), s);
 }
 
 int na2d_debug_indices(const na2d_problem *p, int32_t *key_index, int32_t *rpb_index, void *stream) {

@@ -48,6 +48,13 @@ AvRpbSplit av_rpb_split(const Problem &p);
 hipError_t launch_av_rpb(const Problem &p, const void *w, const void *y, float scale, void *out, float *rpb_partial,
                          hipStream_t s);
 hipError_t launch_rpb_final_av(const Problem &p, const float *partial, float *d_rpb, AvRpbSplit sp, hipStream_t s);
+// fused backward (two kernels): query patches -> dq, delta, partial bias gradients; key patches -> dk, dv
+bool fused_bwd_supported(const Problem &p);
+AvRpbSplit fused_bwd_split(const Problem &p);
+hipError_t launch_fbwd_q(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
+                         const float *lse, const void *dout, void *dq, float *delta, float *rpb_partial, hipStream_t s);
+hipError_t launch_fbwd_kv(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
+                          const float *lse, const float *delta, const void *dout, void *dk, void *dv, hipStream_t s);
 hipError_t launch_fused_fwd(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
                             void *out, float *lse, hipStream_t s);
 hipError_t launch_fused_mfma(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,

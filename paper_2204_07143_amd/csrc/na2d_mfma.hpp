@@ -32,6 +32,20 @@ template <> __device__ __forceinline__ f32x4 mfma_16x16x32<bf16_t>(u32x4 a, u32x
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// The half-depth instruction (contraction over 16): lane l holds row / column l % 16 and the
+// k-elements 4*(l/16) .. 4*(l/16)+3 of the A / B operand (8 bytes); the result layout is the same.
+struct u32x2;
+typedef short i16x4_t __attribute__((ext_vector_type(4)));
+template <typename T> __device__ __forceinline__ f32x4 mfma_16x16x16(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, f32x4 c);
+template <> __device__ __forceinline__ f32x4 mfma_16x16x16<f16_t>(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, f32x4 c) {
+    const uint64_t a = (uint64_t)a0 | ((uint64_t)a1 << 32), b = (uint64_t)b0 | ((uint64_t)b1 << 32);
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, a), __builtin_bit_cast(f16x4, b), c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x4 mfma_16x16x16<bf16_t>(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, f32x4 c) {
+    const uint64_t a = (uint64_t)a0 | ((uint64_t)a1 << 32), b = (uint64_t)b0 | ((uint64_t)b1 << 32);
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(i16x4_t, a), __builtin_bit_cast(i16x4_t, b), c, 0, 0, 0);
+}
+
 // Geometry of a 4 x 4 query patch.  Patch-halo coordinates are "virtual": position (hy, hx)
 // is key (oy + hy, ox + hx) whether or not that lies inside the map, with (oy, ox) =
 // halo_origin() of the patch.  The windows of 4 consecutive queries span at most K + 3
@@ -185,6 +199,10 @@ __device__ __forceinline__ void global_to_lds_16(const void *g, int lds_base) {
 // the same from a wave-uniform base pointer plus a 32-bit byte offset per lane
 __device__ __forceinline__ void global_to_lds_16(const char *base, unsigned off, int lds_base) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
+}
+// four bytes per lane: lane l writes [lds_base + 4 l, lds_base + 4 l + 4)
+__device__ __forceinline__ void global_to_lds_4(const char *base, unsigned off, int lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
 }
 // waits until every load of this wave, the direct-to-LDS ones included, has landed
 __device__ __forceinline__ void wait_global_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }

@@ -112,6 +112,17 @@ class Stages:
         return dq, dk, dv, d_rpb, ds
 
 
+    def backward_fused(self, with_rpb_grad: bool = True):
+        """na2d_fused_bwd on the lse that forward_fused() stored."""
+        nb = 2 * self.k - 1
+        prob = na.problem(self.p.B, self.p.heads, self.p.H, self.p.W, self.p.D, self.k, self.tdtype)
+        ws = torch.empty(na.na2d_workspace_bytes(prob, na.WS_FUSED_BWD), dtype=torch.uint8, device="cuda")
+        dq, dk, dv = (torch.empty_like(self.q) for _ in range(3))
+        d_rpb = torch.empty((self.p.heads, nb, nb), dtype=torch.float32, device="cuda") if with_rpb_grad else None
+        na.na2d_fused_bwd(self.q, self.key, self.v, self.rpb, self.scale, self.lse, self.dout, self.k, dq, dk, dv, d_rpb, ws)
+        return dq, dk, dv, d_rpb
+
+
 def plane(x, b: int, h: int):
     """[B, heads, ...] -> the [1, 1, ...] slice of one plane (torch tensor or numpy array)."""
     return x[b:b + 1, h:h + 1]

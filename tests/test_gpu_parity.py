@@ -91,7 +91,45 @@ def run_all(oracle, p: synth.Problem, seed: int, planes=None, backward=True, use
                 assert_close(f"{tag} grad-q", plane(dq, b, h), oracle.qk_bwd_q(g_ds, key, st.scale, p.k), p.dtype)
                 assert_close(f"{tag} grad-k", plane(dk, b, h), oracle.qk_bwd_k(g_ds, q, st.scale, p.k), p.dtype)
             assert_close_rpb("na2d_bwd grad-b", d_rpb, oracle.qk_bwd_rpb(to_np(ds_c), p.k))
+    if backward:
+        check_fused_backward(oracle, st, host, planes, use_rpb)
     return st, host, flat
+
+
+def check_fused_backward(oracle, st: Stages, host: dict, planes, use_rpb: bool):
+    """na2d_fused_bwd (inputs: q, k, v, rpb, dout and the fused forward's lse).  Where it runs its two fused
+    kernels, everything is computed in fp32 from the inputs, so it is compared with the all-double oracle's
+    gradients: dq / dk / dv on the given planes, d_rpb (a sum over the batch) on the whole tensors.  Where it
+    falls back to the unfused steps (fp32, k >= 9, maps with awkward ragged tiles) it recomputes the attention
+    weights with the same kernels as the unfused forward and must reproduce na2d_bwd bit for bit."""
+    p = st.p
+    dq, dk, dv, d_rpb = st.backward_fused(with_rpb_grad=True)
+    torch.cuda.synchronize()
+    prob = na.problem(p.B, p.heads, p.H, p.W, p.D, p.k, st.tdtype)
+    if na.na2d_fused_bwd_is_fused(prob):
+        assert p.dtype != "f32" and p.k <= 7
+        for (b, h) in planes:
+            tag = f"na2d_fused_bwd plane({b},{h})"
+            q, key, v, dout = (plane(host[n], b, h).astype(np.float64) for n in ("q", "k", "v", "dout"))
+            rpb = host["rpb"][h:h + 1].astype(np.float64) if use_rpb else None
+            o_dq, o_dk, o_dv, _ = oracle.bwd(q, key, v, rpb, st.scale, dout, p.k)
+            assert_close(f"{tag} dq", plane(dq, b, h), o_dq, p.dtype)
+            assert_close(f"{tag} dk", plane(dk, b, h), o_dk, p.dtype)
+            assert_close(f"{tag} dv", plane(dv, b, h), o_dv, p.dtype)
+        # without a bias the gradient with respect to it still exists: the oracle gets a table of zeros
+        rpb_all = host["rpb"].astype(np.float64) if use_rpb else np.zeros_like(host["rpb"], dtype=np.float64)
+        want = oracle.bwd(*(host[n].astype(np.float64) for n in ("q", "k", "v")), rpb_all, st.scale,
+                          host["dout"].astype(np.float64), p.k)[3]
+        assert_close_rpb("na2d_fused_bwd d_rpb", d_rpb, want)
+    else:
+        c_dq, c_dk, c_dv, c_d_rpb, _ = st.backward_composed()
+        torch.cuda.synchronize()
+        for a, b_, n in ((dq, c_dq, "dq"), (dk, c_dk, "dk"), (dv, c_dv, "dv"), (d_rpb, c_d_rpb, "d_rpb")):
+            assert torch.equal(a, b_), f"na2d_fused_bwd (unfused steps) {n} differs from na2d_bwd"
+    # without the bias gradient the other three results are the same bits
+    dq2, dk2, dv2, _ = st.backward_fused(with_rpb_grad=False)
+    torch.cuda.synchronize()
+    assert torch.equal(dq, dq2) and torch.equal(dk, dk2) and torch.equal(dv, dv2)
 
 
 # ---- small shapes, every element (several tiles, ragged tails, every k and dtype) -----------
