@@ -8,6 +8,7 @@ input (B=64, heads=2, 56x56, D=32, fp16, k=7 unless overridden), inputs resident
   forward, unfused : na2d_qk_rpb -> na2d_softmax -> na2d_av
   forward, fused   : na2d_fused_fwd (with log-sum-exp)
   backward         : na2d_bwd = grad-a, grad-v, softmax backward, grad-q, grad-k, grad-b
+  backward, fused  : na2d_fused_bwd (from the fused forward's log-sum-exp)
 `value` is the step's algorithmic HBM traffic divided by its wall time (GB/s); the per-call
 microseconds and per-kernel GB/s are in `kernels`.  Buffers rotate over several disjoint sets
 so that successive launches of one kernel do not find their operands in the 256 MB Infinity
@@ -43,6 +44,8 @@ def algorithmic_bytes(p) -> dict:
         "fused_fwd": nq * (4 * D * e + 4),
         "av_bwd_p": contraction, "av_bwd_v": contraction, "softmax_bwd": nq * 3 * kk * e,
         "qk_bwd_q": contraction, "qk_bwd_k": contraction, "qk_bwd_rpb": nq * kk * e,
+        # q, k, v, dout and lse in; dq, dk, dv out (the bias gradient is a few hundred bytes)
+        "fused_bwd": nq * (7 * D * e + 4),
     }
 
 
@@ -62,6 +65,7 @@ class BufferSet:
         prob = na.problem(p.B, p.heads, p.H, p.W, p.D, p.k, td)
         self.ws = torch.empty(na.na2d_workspace_bytes(prob, na.WS_BWD), dtype=torch.uint8, device="cuda")
         self.ws_rpb = torch.empty(na.na2d_workspace_bytes(prob, na.WS_QK_BWD_RPB), dtype=torch.uint8, device="cuda")
+        self.ws_fused = torch.empty(na.na2d_workspace_bytes(prob, na.WS_FUSED_BWD), dtype=torch.uint8, device="cuda")
 
 
 def make_calls(p, na, scale):
@@ -77,6 +81,8 @@ def make_calls(p, na, scale):
         "qk_bwd_q": lambda s: na.na2d_qk_bwd_q(s.dpds, s.k, scale, k, s.dq),
         "qk_bwd_k": lambda s: na.na2d_qk_bwd_k(s.dpds, s.q, scale, k, s.dk),
         "qk_bwd_rpb": lambda s: na.na2d_qk_bwd_rpb(s.dpds, k, s.q, s.d_rpb, s.ws_rpb),
+        "fused_bwd": lambda s: na.na2d_fused_bwd(s.q, s.k, s.v, s.rpb, scale, s.lse, s.dout, k, s.dq, s.dk, s.dv,
+                                                 s.d_rpb, s.ws_fused),
     }
 
 
@@ -86,6 +92,7 @@ def step(s, calls, na, p, scale):
     calls["av"](s)
     calls["fused_fwd"](s)
     na.na2d_bwd(s.q, s.k, s.v, s.attn, s.dout, scale, p.k, s.dq, s.dk, s.dv, s.d_rpb, s.ws)
+    calls["fused_bwd"](s)
 
 
 def cpu_baseline(p, synth, budget_s: float = 20.0) -> dict:
@@ -111,6 +118,7 @@ def cpu_baseline(p, synth, budget_s: float = 20.0) -> dict:
         o.qk_bwd_q(ds, h["k"], scale, p.k)
         o.qk_bwd_k(ds, h["q"], scale, p.k)
         o.qk_bwd_rpb(ds, p.k)
+        o.bwd(h["q"], h["k"], h["v"], h["rpb"], scale, h["dout"], p.k)   # the fused backward's counterpart
         return time.perf_counter() - t0
 
     bs = 1
@@ -121,7 +129,7 @@ def cpu_baseline(p, synth, budget_s: float = 20.0) -> dict:
     sp = synth.Problem(bs, p.heads, p.H, p.W, p.D, p.k, p.dtype)
     nbytes = sum(algorithmic_bytes(sp).values())
     return {"value": round(nbytes / t / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": f"one full step (same 10 calls) on batch {bs} of {p.B}, {t:.2f} s", "us_per_step_extrapolated":
+            "sample": f"one full step (same 11 calls) on batch {bs} of {p.B}, {t:.2f} s", "us_per_step_extrapolated":
             round(t * p.B / bs * 1e6, 1)}
 
 
@@ -209,12 +217,14 @@ def main() -> int:
         log(f"  {name:12s} {us:9.2f} us  {gbps:8.1f} GB/s  {100 * gbps / HBM_PEAK_GBPS:5.1f}% of 8 TB/s")
     unfused_fwd = sum(kernels[n]["us"] for n in ("qk_rpb", "softmax", "av"))
     bwd = sum(kernels[n]["us"] for n in ("av_bwd_p", "av_bwd_v", "softmax_bwd", "qk_bwd_q", "qk_bwd_k", "qk_bwd_rpb"))
-    log(f"  unfused fwd {unfused_fwd:.1f} us, fused fwd {kernels['fused_fwd']['us']:.1f} us, bwd {bwd:.1f} us")
+    log(f"  unfused fwd {unfused_fwd:.1f} us, fused fwd {kernels['fused_fwd']['us']:.1f} us, bwd {bwd:.1f} us, "
+        f"fused bwd {kernels['fused_bwd']['us']:.1f} us")
 
     # The same K steps once more with HIP events around every launch (on the launch stream): the average
     # duration of each kernel inside the step, where it runs between the others.  Entry points that
     # run the same device kernel are grouped; the dominant kernel is the group with the most time.
-    order = ["qk_rpb", "softmax", "av", "fused_fwd", "av_bwd_p", "av_bwd_v", "softmax_bwd", "qk_bwd_q", "qk_bwd_k", "qk_bwd_rpb"]
+    order = ["qk_rpb", "softmax", "av", "fused_fwd", "av_bwd_p", "av_bwd_v", "softmax_bwd", "qk_bwd_q", "qk_bwd_k", "qk_bwd_rpb",
+             "fused_bwd"]
     evs = {n: [] for n in order}
     torch.cuda.synchronize()
     for i in range(args.steps):
@@ -229,7 +239,8 @@ def main() -> int:
     in_step = {n: sum(a.elapsed_time(b) for a, b in evs[n]) * 1e3 / len(evs[n]) for n in order}
     groups = {"qk_mfma (qk_rpb, av_bwd_p)": ["qk_rpb", "av_bwd_p"], "av_mfma (av, qk_bwd_q)": ["av", "qk_bwd_q"],
               "inverse_mfma (av_bwd_v, qk_bwd_k)": ["av_bwd_v", "qk_bwd_k"], "fused_mfma (fused_fwd)": ["fused_fwd"],
-              "softmax": ["softmax"], "softmax_bwd": ["softmax_bwd"], "rpb_partial + rpb_final (qk_bwd_rpb)": ["qk_bwd_rpb"]}
+              "softmax": ["softmax"], "softmax_bwd": ["softmax_bwd"], "rpb_partial + rpb_final (qk_bwd_rpb)": ["qk_bwd_rpb"],
+              "fbwd_q + fbwd_kv (fused_bwd)": ["fused_bwd"]}
     dominant = max(groups, key=lambda g: sum(in_step[n] for n in groups[g]))
     members = groups[dominant]
     avg_us = sum(in_step[n] for n in members) / len(members)
@@ -255,9 +266,11 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us_step / 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": p.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload} (B={p.B}, heads={p.heads}, {p.H}x{p.W}, D={p.D}, k={p.k}, {p.dtype}): "
-                               "unfused fwd + fused fwd + bwd, one call each", "buffer_sets": args.sets},
+                               "unfused fwd + fused fwd + bwd + fused bwd, one call each", "buffer_sets": args.sets},
         "us_per_call": {"unfused_fwd": round(unfused_fwd, 1), "fused_fwd": kernels["fused_fwd"]["us"],
-                        "bwd": round(bwd, 1), "fwd_bwd_unfused": round(unfused_fwd + bwd, 1)},
+                        "bwd": round(bwd, 1), "fused_bwd": kernels["fused_bwd"]["us"],
+                        "fwd_bwd_unfused": round(unfused_fwd + bwd, 1),
+                        "fwd_bwd_fused": round(kernels["fused_fwd"]["us"] + kernels["fused_bwd"]["us"], 1)},
         "kernels": kernels, "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -38,11 +38,13 @@ template <typename T> __device__ __forceinline__ uint32_t pack2_t(float a, float
 //   dq^T += K_blk^T dS^T                     the half-depth MFMA (keys through the transposing LDS read).
 // Recomputing the two products is cheaper than keeping P and dP of the whole halo in registers.
 // Every dS is also added to its cell of a (2K-1)^2 table in LDS (Eq. 2's B differentiated: the bias cell of a
-// (query, position) pair depends on their offset only); the workgroup's tables, added in a fixed order at
-// the end, are one partial bias gradient.  The 64 lanes of one such add hit 64 different cells.  Where the
-// tables of all eight waves do not fit beside the halo buffers (K = 7) two waves share one, and the order
-// in which their contributions meet is not fixed: the last bits of the bias gradient can then differ
-// between runs.
+// (query, position) pair depends on their offset only).  The tables are 64-bit fixed point (42 fraction
+// bits) and the adds are integer atomics: on this chip an LDS integer add costs a few cycles per wave
+// instruction where the floating-point add costs about 200, and integer addition does not depend on the
+// order of the operands, so the bias gradient is bitwise reproducible although waves share tables.  A
+// workgroup's tables, added up and converted to fp32 at the end, are one partial bias gradient.
+// (Range: a cell's sum over the workgroup's planes must stay below 2^21 in magnitude, far beyond what 16-bit
+// inputs whose gradients are representable at all produce; resolution 2^-42.  A non-finite dS counts as 0.)
 template <typename T, int K>
 struct FbwdQCfg {
     using P = Patch<K>;
@@ -57,9 +59,9 @@ struct FbwdQCfg {
     static constexpr int kThreads = kWave * WAVES;
     static constexpr int kHaloBytes = Halo::kBytes;
     static constexpr int kStageBytes = 2 * kHaloBytes;   // keys, then values
-    // Bias-gradient tables (fp32, one more word for results outside the window) behind the buffers: one per
-    // wave where two workgroups still fit a compute unit's 160 KB, else as many as fit (waves then share)
-    static constexpr int kTblBytes = (CELLS + 1) * 4;
+    // Bias-gradient tables behind the buffers, 64-bit fixed point (see below): as many as fit beside two
+    // workgroups' buffers in a compute unit's 160 KB, at most one per wave
+    static constexpr int kTblBytes = CELLS * 8;
     static constexpr int kTblFit = (80 * 1024 - 2 * kStageBytes) / kTblBytes;
     static constexpr int NTBL = kTblFit >= WAVES ? WAVES : (kTblFit >= 4 ? 4 : (kTblFit >= 2 ? 2 : 1));
     static_assert(kTblFit >= 1, "no room for a bias-gradient table");
@@ -166,7 +168,10 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
 #pragma unroll
         for (int i = 0; i < 4; ++i) cell[i] = (unsigned)(c0 + i) < (unsigned)K ? cell0 + i : -1;
     };
-    uint32_t cellp[RPB ? P::NBLK : 1];   // table cell of result 4G + i in byte i of word G (the extra word outside the window)
+    // table cell of result 4G + i in byte i of word G; outside the window (where dS is exactly 0 and adding it
+    // changes nothing) a cell that differs from lane to lane, so that the adds of one instruction do not pile
+    // up on one address
+    uint32_t cellp[RPB ? P::NBLK : 1];
     {
         const T *tbl = rpb != nullptr ? rpb + (size_t)head * C::CELLS : nullptr;
 #pragma unroll
@@ -183,7 +188,7 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
                     if (G0 + u < P::NBLK) {
                         uint32_t w = 0;
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) w |= (uint32_t)(c4[i] >= 0 ? c4[i] : C::CELLS) << (8 * i);
+                        for (int i = 0; i < 4; ++i) w |= (uint32_t)(c4[i] >= 0 ? c4[i] : lane % C::CELLS) << (8 * i);
                         cellp[G0 + u] = w;
                     }
                 }
@@ -203,7 +208,7 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
     const int tbl0 = lds0 + 2 * C::kStageBytes;
     const int mytbl = tbl0 + (wave % C::NTBL) * C::kTblBytes;
     if constexpr (RPB) {
-        for (int i = tid; i < C::NTBL * (C::CELLS + 1); i += C::kThreads) *lds_ptr<float>(tbl0 + i * 4) = 0.f;
+        for (int i = tid; i < C::NTBL * C::CELLS; i += C::kThreads) *lds_ptr<unsigned long long>(tbl0 + i * 8) = 0ull;
     }
 
     const float scale2 = scale * kLog2e;
@@ -249,9 +254,13 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
             for (int r = 0; r < 4; ++r) {
                 const int e = 4 * bk + r;
                 dsv[r] = weight(e, sacc[r]) * (pacc[r] - delta);   // exactly 0 outside the window
-                if constexpr (RPB)
-                    __hip_atomic_fetch_add(lds_ptr<float>(mytbl + ((cellp[bk] >> (8 * r)) & 0xffu) * 4), dsv[r], __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_WORKGROUP);
+                if constexpr (RPB) {
+                    // dS * 2^10 as integer part (32 bits, signed) and fraction (32 bits): 2^42 dS in 64 bits
+                    const float y = dsv[r] * 1024.f, fl = __builtin_floorf(y);
+                    const unsigned long long fx = ((unsigned long long)(uint32_t)(int)fl << 32) | (uint32_t)((y - fl) * 4294967296.f);
+                    __hip_atomic_fetch_add(lds_ptr<unsigned long long>(mytbl + ((cellp[bk] >> (8 * r)) & 0xffu) * 8), fx,
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
             }
             const uint32_t b0 = pack2_t<T>(dsv[0], dsv[1]), b1 = pack2_t<T>(dsv[2], dsv[3]);
             const int ta = tr_addr(lv, bk) + PAR * C::kStageBytes;
@@ -296,13 +305,13 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
     }
 
     if constexpr (RPB) {
-        // the tables, added in table order: one partial bias gradient per workgroup
+        // the tables added up (integers: any order), then to fp32: one partial bias gradient per workgroup
         __syncthreads();
         for (int cell = tid; cell < C::CELLS; cell += C::kThreads) {
-            float sum = *lds_ptr<float>(tbl0 + cell * 4);
+            long long sum = 0;
 #pragma unroll
-            for (int t = 1; t < C::NTBL; ++t) sum += *lds_ptr<float>(tbl0 + t * C::kTblBytes + cell * 4);
-            rpb_partial[(size_t)wg * C::CELLS + cell] = sum;
+            for (int t = 0; t < C::NTBL; ++t) sum += (long long)*lds_ptr<unsigned long long>(tbl0 + t * C::kTblBytes + cell * 8);
+            rpb_partial[(size_t)wg * C::CELLS + cell] = (float)((double)sum * (1.0 / 4398046511104.0));   // 2^-42
         }
     }
 }

@@ -126,10 +126,12 @@ def check_fused_backward(oracle, st: Stages, host: dict, planes, use_rpb: bool):
         torch.cuda.synchronize()
         for a, b_, n in ((dq, c_dq, "dq"), (dk, c_dk, "dk"), (dv, c_dv, "dv"), (d_rpb, c_d_rpb, "d_rpb")):
             assert torch.equal(a, b_), f"na2d_fused_bwd (unfused steps) {n} differs from na2d_bwd"
-    # without the bias gradient the other three results are the same bits
+    # without the bias gradient the other three results are the same bits; a second run reproduces all four
     dq2, dk2, dv2, _ = st.backward_fused(with_rpb_grad=False)
+    dq3, dk3, dv3, d_rpb3 = st.backward_fused(with_rpb_grad=True)
     torch.cuda.synchronize()
     assert torch.equal(dq, dq2) and torch.equal(dk, dk2) and torch.equal(dv, dv2)
+    assert torch.equal(dq, dq3) and torch.equal(dk, dk3) and torch.equal(dv, dv3) and torch.equal(d_rpb, d_rpb3)
 
 
 # ---- small shapes, every element (several tiles, ragged tails, every k and dtype) -----------
