@@ -127,8 +127,9 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
     };
     if (b_begin < b_end) issue(b_begin, 0);
 
-    // Operand addresses inside the first buffer pair, recomputed where they are used from an opaque copy of the
-    // lane index (fifteen more registers held across the loop would not fit beside the bias-gradient sums).
+    // Operand addresses inside the first buffer pair; those of the transposing reads are recomputed where they
+    // are used, from an opaque copy of the lane index (eight more registers held across the loop cost more
+    // than the arithmetic).
     // Keys / values as A operand rows: halo position 16b + j, bytes [16g, 16g+16).  Keys through the
     // transposing read: inside its group of 16 lanes, lane j points at four channels of halo position
     // 16b + 4g + j / 4 and receives the j-th channel of positions 16b + 4g .. + 3; the channels are dealt so
@@ -141,6 +142,9 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
         const int hy = P::row_of(h), hx = h - hy * P::PW;
         return kbase + (hy * C::HALO_W + hx) * Traits<T>::kKeyBytes + (lv >> 4) * 16;
     };
+    int koff[P::NBLK];   // used twice per plane: kept
+#pragma unroll
+    for (int b = 0; b < P::NBLK; ++b) koff[b] = row_addr(lane, b);
     auto tr_addr = [&](int lv, int b) {   // transposing read of block b
         int h = 16 * b + 4 * (lv >> 4) + ((lv & 15) >> 2);
         h = h < P::NKEY ? h : P::NKEY - 1;
@@ -222,7 +226,7 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
 #pragma unroll
         for (int e = 0; e < P::NEL / 2; ++e) asm volatile("" : "+v"(biasm[e]));
         auto block = [&](int bk, f32x4 &sacc, f32x4 &pacc) {
-            const int ra = row_addr(lv, bk) + PAR * C::kStageBytes;
+            const int ra = koff[bk] + PAR * C::kStageBytes;
             const u32x4 ak = *lds_ptr<u32x4>(ra);
             const u32x4 av = *lds_ptr<u32x4>(ra + C::kHaloBytes);
             sacc = mfma_16x16x32<T>(ak, qreg, f32x4{0.f, 0.f, 0.f, 0.f});
