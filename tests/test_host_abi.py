@@ -67,6 +67,18 @@ def test_entry_points_reject_bad_arguments_before_any_hip_call():
     assert lib.na2d_qk_bwd_rpb(ctypes.byref(good), ok, ctypes.c_void_p(a16 + 16), ctypes.c_void_p(a16 + 32), 8, None) == -8
     assert lib.na2d_debug_indices(ctypes.byref(good), None, None, None) == -1
     assert binding.strerror(-12345) == "unknown status"
+    # fused backward: q, k, v, rpb, scale, lse, dout, dq, dk, dv, d_rpb, workspace, bytes, stream
+    ptr = lambda i: ctypes.c_void_p(a16 + 16 * i)
+    fb = lambda *a: lib.na2d_fused_bwd(ctypes.byref(good), *a)
+    assert fb(ptr(0), ptr(0), ptr(0), None, 1.0, None, ptr(0), ptr(1), ptr(2), ptr(3), None, ptr(0), 1 << 20, None) == -1      # no lse
+    assert fb(ptr(0), ptr(0), ptr(0), None, 1.0, off, ptr(0), ptr(1), ptr(2), ptr(3), None, ptr(0), 1 << 20, None) == -7       # misaligned lse
+    assert fb(ptr(0), ptr(0), ptr(0), None, 1.0, ptr(0), ptr(0), ptr(0), ptr(2), ptr(3), None, ptr(0), 1 << 20, None) == -10   # dq aliases q
+    assert fb(ptr(0), ptr(0), ptr(0), None, 1.0, ptr(0), ptr(0), ptr(1), ptr(1), ptr(3), None, ptr(0), 1 << 20, None) == -10   # dk aliases dq
+    assert fb(ptr(0), ptr(0), ptr(0), None, 1.0, ptr(0), ptr(0), ptr(1), ptr(2), ptr(3), None, None, 1 << 20, None) == -8      # no workspace
+    assert fb(ptr(0), ptr(0), ptr(0), None, 1.0, ptr(0), ptr(0), ptr(1), ptr(2), ptr(3), None, ptr(0), 16, None) == -8         # too small
+    assert lib.na2d_fused_bwd(ctypes.byref(P(k=4)), ptr(0), ptr(0), ptr(0), None, 1.0, ptr(0), ptr(0), ptr(1), ptr(2), ptr(3),
+                              None, ptr(0), 1 << 20, None) == -3
+    assert lib.na2d_fused_bwd_is_fused(None) == -1
 
 
 def test_workspace_sizes():
@@ -76,6 +88,17 @@ def test_workspace_sizes():
     assert rpb > 0 and rpb % 256 == 0
     assert full >= rpb + 64 * 2 * 56 * 56 * 49 * 2
     assert binding.na2d_workspace_bytes(P(k=4), binding.WS_BWD) == 0
+    # fused backward: the two-kernel path needs delta (one fp32 per query) and the partial bias gradients,
+    # far less than one attention tensor; the other path holds the attention weights and the unfused workspace
+    fused = binding.na2d_workspace_bytes(p, binding.WS_FUSED_BWD)
+    assert binding.na2d_fused_bwd_is_fused(p) == 1
+    assert 64 * 2 * 56 * 56 * 4 <= fused < 64 * 2 * 56 * 56 * 49 * 2 and fused % 256 == 0
+    for other in (P(B=2, heads=2, H=56, W=56, k=7, dtype=0), P(B=2, heads=2, H=56, W=56, k=9, dtype=1)):   # fp32; k > 7
+        assert binding.na2d_fused_bwd_is_fused(other) == 0
+        assert binding.na2d_workspace_bytes(other, binding.WS_FUSED_BWD) >= binding.na2d_workspace_bytes(other, binding.WS_BWD)
+    for H, W, k in ((28, 28, 7), (20, 16, 5), (19, 37, 5), (7, 7, 7), (14, 14, 7), (3, 3, 3)):   # ragged / far-border tiles included
+        assert binding.na2d_fused_bwd_is_fused(P(B=2, heads=2, H=H, W=W, k=k, dtype=2)) == 1
+    assert binding.na2d_fused_bwd_is_fused(P(k=4)) == -3
 
 
 def nearest_window(i, L, k):
