@@ -1,0 +1,294 @@
+// Gradients that sum over queries, on the matrix cores, walking down a column of key tiles (f16 / bf16,
+// K <= 7):
+//   out_j = scale * sum over queries i whose window holds j of w[i, slot(i, j)] * x_i
+// (grad-v with w = attention weights, x = dout; grad-k with w = ds, x = q; arXiv 2204.07143, Appendix A).
+//
+// The arithmetic is that of the tile kernel in na2d_inverse_mfma.hip (4 x 4 key patches, one per wave, a
+// block of 16 query positions per row of the query rectangle, weights gathered through row + column
+// address terms, x through the transposing LDS read).  What differs is how the query rectangle reaches
+// LDS.  A 16 x 8 key tile is seen from 8 + K-1 query rows, and vertically adjacent tiles share K-1 of them:
+// a workgroup therefore owns one column of tiles of one plane and keeps the query rows (their weight rows
+// and their x vectors) in a ring of 2*8 + K-1 row slots, slot = row mod ring size.  Per tile only the 8
+// rows that are new are loaded (direct-to-LDS), and they are loaded while the previous tile is computed:
+// 43 % fewer bytes through the L2-to-LDS path that bounds the tile kernel, overlapped with the gathers.
+// Neighbouring workgroups take neighbouring columns of the same plane at the same time, so the query
+// columns that adjacent columns of tiles share are fetched from HBM once.
+#include "na2d_kernels.hpp"
+#include "na2d_mfma.hpp"
+#include "na2d_tile.hpp"
+
+namespace na2d {
+
+template <typename T, int K>
+struct InvRingCfg {
+    static constexpr int R = K / 2;
+    static constexpr int PWI = K + R + 3;          // query-halo side of a 4 x 4 key patch
+    static constexpr int NBLK = PWI + (PWI & 1);   // halo rows, padded to whole pairs
+    static constexpr int NPAIR = NBLK / 2;
+    static constexpr int STRIPS = 2, WAVES = 4 * STRIPS, TY = 4 * STRIPS;
+    static constexpr int RH = TY + K - 1;          // query rows that see a tile (tiles next to at most the near border)
+    static constexpr int RW = kTileX + K - 1;      // ... and columns
+    static constexpr int NR = RH + TY;             // ring slots: the rows of a tile and the new rows of the next one
+    static constexpr int KK = K * K;
+    static constexpr int kThreads = kWave * WAVES;
+    static constexpr int KB = Traits<T>::kKeyBytes;
+    static constexpr int kXRow = RW * KB;                         // x vectors of one query row, natural layout
+    static constexpr int kXBytes = NR * kXRow + 6 * KB;           // + the reach of a 16-wide block past the last slot
+    static constexpr int kXItems = (RW * (KB / 16) + kWave - 1) / kWave;   // 64-lane loads per x row
+    static constexpr int kRowBytes = RW * KK * (int)sizeof(T);
+    static constexpr int kRowRegion = mirror_bytes(kRowBytes);    // a weight row, mirrored at its 16-byte phase
+    static constexpr int kWItems = (kRowRegion / 16 + kWave - 1) / kWave;   // 64-lane loads per weight row
+    static constexpr int kWBytes = NR * kRowRegion;
+    static constexpr int kColEntries = 4 * 4 * 4 * 4;             // [patch][g][kx][r]
+    static constexpr int kRowEntries = STRIPS * NBLK * 4;         // [strip][b][ky]
+    static constexpr int kLdsBytes = kXBytes + kWBytes + 16 + (kColEntries + kRowEntries) * 4;
+    static_assert(kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+    static constexpr int kMaxNew = RH;                            // rows loaded at once: the first tile's
+    static constexpr int kRowsPerWave = (kMaxNew + WAVES - 1) / WAVES;
+};
+
+template <typename T, int K>
+__global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restrict__ w, const T *__restrict__ x, float scale,
+                                                              T *__restrict__ out, int H, int W, int tiles_x, int tiles_y,
+                                                              int nplanes) {
+    using C = InvRingCfg<T, K>;
+    constexpr int SZ = (int)sizeof(T);
+    constexpr int BIG = 1 << 24;   // invalid row / column terms push the sum past the zero word
+    extern __shared__ __align__(16) char lds[];
+
+    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    if (wg >= nplanes * tiles_x) return;
+    const int plane = wg / tiles_x, tix = wg - plane * tiles_x;
+
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int n = lane & 15, g = lane >> 4, ky = n >> 2, kx = n & 3;
+    const int lds0 = lds_addr(lds);
+    const int x0 = lds0;                               // x ring
+    const int w0 = lds0 + C::kXBytes;                  // weight ring
+    const int zero_addr = w0 + C::kWBytes;             // a zero word above every valid gather address
+    const int tbl_col = zero_addr + 16, tbl_row = tbl_col + C::kColEntries * 4;
+
+    // Everything the loads do not write must hold finite numbers (it meets zero weights only).
+    for (int i = tid * 16; i < C::kLdsBytes; i += C::kThreads * 16) *lds_ptr<u32x4>(lds0 + i) = u32x4{0u, 0u, 0u, 0u};
+
+    const int tx0 = tix * kTileX;
+    const int tx1 = tx0 + kTileX - 1 < W - 1 ? tx0 + kTileX - 1 : W - 1;
+    const int rx0 = inv_first(tx0, W, K), rx1 = inv_last(tx1, W, K);
+    const int ncols = rx1 - rx0 + 1;   // <= RW: checked by the host
+    const size_t plane_q = (size_t)plane * H * W;
+    const size_t w_bytes = (size_t)nplanes * H * W * C::KK * SZ;   // size of the weight tensor
+    const int row_pitch_bytes = W * C::KK * SZ;                    // < 2^31: checked by the host
+    const size_t wbase = (plane_q + rx0) * C::KK * SZ;             // first weight byte of query row 0 of the rectangle's columns
+    const int wrow_bytes = ncols * C::KK * SZ;
+
+    // x loads of a row: this lane's chunks, as byte offsets inside a query row (columns clamped into the map)
+    int xcol[C::kXItems];
+#pragma unroll
+    for (int j = 0; j < C::kXItems; ++j) {
+        const int q = j * kWave + lane;
+        int xx = rx0 + q / (C::KB / 16);
+        xx = xx < W - 1 ? xx : W - 1;
+        xcol[j] = q < C::RW * (C::KB / 16) ? xx * C::KB + (q % (C::KB / 16)) * 16 : -1;
+    }
+    // Loads the query rows [r_begin, r_end) into their ring slots: row r_begin + wave, + WAVES, ... per wave.
+    auto load_rows = [&](int r_begin, int r_end) {
+#pragma unroll
+        for (int u = 0; u < C::kRowsPerWave; ++u) {
+            const int iy = r_begin + wave + u * C::WAVES;
+            if (iy >= r_end) break;
+            const int slot = iy % C::NR;
+            // x vectors
+            const char *xrow = reinterpret_cast<const char *>(x) + (plane_q + (size_t)iy * W) * C::KB;
+#pragma unroll
+            for (int j = 0; j < C::kXItems; ++j)
+                if (xcol[j] >= 0) global_to_lds_16(xrow, (unsigned)xcol[j], x0 + slot * C::kXRow + j * kWave * 16);
+            // weight row, mirrored at its 16-byte phase: one 16-byte chunk per lane; the chunks at the two ends also
+            // bring in bytes of the neighbouring rows, which nothing reads.  Only the one chunk that would cross the
+            // end of the tensor is copied element by element.
+            const size_t g0 = wbase + (size_t)iy * row_pitch_bytes;
+            const int mis = (int)(g0 & 15);
+            const int nchunks = (mis + wrow_bytes + 15) >> 4;
+            const char *src = reinterpret_cast<const char *>(w) + (g0 - mis);
+            const size_t left = w_bytes - (g0 - mis);
+            const int region = w0 + slot * C::kRowRegion;
+#pragma unroll
+            for (int j = 0; j < C::kWItems; ++j) {
+                const int c = j * kWave + lane;
+                if (c < nchunks) {
+                    if ((size_t)(c + 1) * 16 <= left) {
+                        global_to_lds_16(src, (unsigned)(c * 16), region + j * kWave * 16);
+                    } else {
+                        for (int e = c * 16; e < mis + wrow_bytes; e += SZ)
+                            *lds_ptr<T>(region + e) = *reinterpret_cast<const T *>(src + e);
+                    }
+                }
+            }
+        }
+    };
+
+    // lane-constant part of the A-operand address (transposing read): inside its group of 16, lane n points at
+    // four channels of position 4g + n / 4 of a block and receives the n-th channel of positions 4g .. 4g + 3.  The
+    // channels are dealt so that MFMA row m of half hf is channel 8 (m / 4) + 4 hf + m % 4: a lane then ends up
+    // with the eight consecutive channels 8g .. 8g + 7 of its key, one 16-byte store.
+    const int strip = wave >> 2, p = wave & 3;
+    const int px0 = tx0 + 4 * p;
+    const int oqx = inv_first(px0 < W ? px0 : W - 1, W, K);   // first query column that sees the patch
+    const int xa_lane = x0 + (oqx - rx0 + 4 * g + (n >> 2)) * C::KB + (n & 3) * 16;
+    const int jx = px0 + kx;
+    const int wphase0 = (int)(wbase & 15), pitch_phase = row_pitch_bytes & 15;   // phase of row iy: (wphase0 + iy * pitch_phase) & 15
+
+    __syncthreads();   // the zero fill is done
+    // column terms: the same for every tile of the column
+    for (int e = tid; e < C::kColEntries; e += C::kThreads) {
+        const int r = e & 3, kxe = (e >> 2) & 3, ge = (e >> 4) & 3, pe = e >> 6;
+        const int pp0 = tx0 + 4 * pe, jxe = pp0 + kxe;
+        const int ix = inv_first(pp0 < W ? pp0 : W - 1, W, K) + 4 * ge + r;
+        const int c = jxe - win_start(ix < W ? ix : W - 1, W, K);
+        int term = BIG;
+        if (pp0 < W && ix <= rx1 && jxe < W && (unsigned)c < (unsigned)K) term = (ix - rx0) * C::KK * SZ + c * SZ;
+        *lds_ptr<int>(tbl_col + e * 4) = term;
+    }
+    // the rows of the first tile
+    {
+        const int ty1 = C::TY - 1 < H - 1 ? C::TY - 1 : H - 1;
+        load_rows(0, inv_last(ty1, H, K) + 1);
+    }
+    wait_global_loads();
+    __syncthreads();
+    int colterm[4];
+    {
+        const u32x4 ct = *lds_ptr<u32x4>(tbl_col + ((p * 4 + g) * 4 + kx) * 16);
+        colterm[0] = (int)ct.x;
+        colterm[1] = (int)ct.y;
+        colterm[2] = (int)ct.z;
+        colterm[3] = (int)ct.w;
+    }
+
+    for (int t = 0; t < tiles_y; ++t) {
+        const int ty0 = t * C::TY;
+        const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
+        const int ry1 = inv_last(ty1, H, K);   // last query row of this tile's rectangle (the first is inv_first(ty0))
+        // the next tile's new rows go to the slots that the tile before this one has left
+        if (t + 1 < tiles_y) {
+            const int ny1 = ty1 + C::TY < H - 1 ? ty1 + C::TY : H - 1;
+            load_rows(ry1 + 1, inv_last(ny1, H, K) + 1);
+        }
+        // row terms of this tile, one entry per thread: the address of the weight that query (iy, ix) gives key
+        // (jy, jx) is rowterm(iy, jy) + colterm(ix, jx); a pair that does not meet gets BIG
+        for (int e = tid; e < C::kRowEntries; e += C::kThreads) {
+            const int kye = e & 3, bb = (e >> 2) % C::NBLK, st = (e >> 2) / C::NBLK;
+            const int sy = ty0 + 4 * st, jyy = sy + kye;
+            const int iy = inv_first(sy < H ? sy : H - 1, H, K) + bb;   // halo row bb of the strip
+            const int a = jyy - win_start(iy < H ? iy : H - 1, H, K);
+            int term = BIG;
+            if (bb < C::PWI && iy <= ry1 && jyy < H && (unsigned)a < (unsigned)K)
+                term = w0 + (iy % C::NR) * C::kRowRegion + ((wphase0 + iy * pitch_phase) & 15) + a * K * SZ;
+            *lds_ptr<int>(tbl_row + e * 4) = term;
+        }
+        __syncthreads();
+
+        const int sy0 = ty0 + 4 * strip;   // first key row of this wave's strip
+        if (sy0 < H && px0 < W) {
+            const int jy = sy0 + ky;
+            const int oqy = inv_first(sy0, H, K);   // first query row of the strip's halo
+            int rowterm[C::NBLK];
+#pragma unroll
+            for (int bb = 0; bb < C::NBLK; ++bb) rowterm[bb] = *lds_ptr<int>(tbl_row + ((strip * C::NBLK + bb) * 4 + ky) * 4);
+            f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+            int slot = oqy % C::NR;   // ring slot of halo row 0; the following rows follow, wrapping
+#pragma unroll
+            for (int pb = 0; pb < C::NPAIR; ++pb) {
+                const int s_lo = slot, s_hi = slot + 1 < C::NR ? slot + 1 : 0;
+                slot = s_hi + 1 < C::NR ? s_hi + 1 : 0;
+                // halo rows that no key row of the strip is seen from are skipped
+                if (__any(rowterm[2 * pb] < BIG || rowterm[2 * pb + 1] < BIG)) {
+                    uint32_t wv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int bb = 2 * pb + (u >> 1);
+                        const int r0 = (u & 1) * 2;
+                        int a_lo = rowterm[bb] + colterm[r0], a_hi = rowterm[bb] + colterm[r0 + 1];
+                        a_lo = a_lo < zero_addr ? a_lo : zero_addr;
+                        a_hi = a_hi < zero_addr ? a_hi : zero_addr;
+                        wv[u] = (uint32_t)*lds_ptr<uint16_t>(a_lo) | ((uint32_t)*lds_ptr<uint16_t>(a_hi) << 16);
+                    }
+                    const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf) {
+                        const u32x2 lo = lds_read_tr16(xa_lane + s_lo * C::kXRow + hf * 8);
+                        const u32x2 hi = lds_read_tr16(xa_lane + s_hi * C::kXRow + hf * 8);
+                        acc[hf] = mfma_16x16x32<T>(u32x4{lo.x, lo.y, hi.x, hi.y}, bop, acc[hf]);
+                    }
+                }
+            }
+            if (jy < H && jx < W) {
+                char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * C::KB + g * 16;
+                uint32_t o[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int hf = u >> 1, r = 2 * (u & 1);
+                    const T lo = from_f32<T>(acc[hf][r] * scale), hi = from_f32<T>(acc[hf][r + 1] * scale);
+                    o[u] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+                }
+                *reinterpret_cast<u32x4 *>(dst) = u32x4{o[0], o[1], o[2], o[3]};   // channels 8g .. 8g + 7
+            }
+        }
+        wait_global_loads();   // the next tile's rows have landed
+        __syncthreads();       // ... for every wave; this tile's rows and row terms are no longer read
+    }
+}
+
+template <typename T, int K>
+static hipError_t launch_inverse_ring_t(const Problem &p, const void *w, const void *x, float scale, void *out,
+                                        hipStream_t s) {
+    using C = InvRingCfg<T, K>;
+    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
+    const int nwg = p.planes() * tiles_x;
+    auto kern = inverse_ring_kernel<T, K>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s, static_cast<const T *>(w),
+                       static_cast<const T *>(x), scale, static_cast<T *>(out), p.H, p.W, tiles_x, tiles_y, p.planes());
+    return hipGetLastError();
+}
+
+// The ring holds 8 + K-1 rows per tile: every tile's query rectangle must fit that (and 16 + K-1 columns), which
+// excludes maps with a tile next to the far border whose clamped queries reach further (the tile kernel takes those).
+bool inverse_ring_supported(const Problem &p) {
+    if (p.dtype == NA2D_F32 || p.K > 7) return false;
+    const int K = p.K, TY = 8;
+    // a 4 x 4 key patch seen from both clamped ends of an axis at once (axes of at most 2K + 2 positions) has
+    // more than K + R + 3 query rows or columns: one MFMA block per row no longer covers it
+    if ((p.H < p.W ? p.H : p.W) <= 2 * K + 2) return false;
+    for (int ty0 = 0; ty0 < p.H; ty0 += TY) {
+        const int ty1 = ty0 + TY - 1 < p.H - 1 ? ty0 + TY - 1 : p.H - 1;
+        if (inv_last(ty1, p.H, K) - inv_first(ty0, p.H, K) + 1 > TY + K - 1) return false;
+    }
+    for (int tx0 = 0; tx0 < p.W; tx0 += kTileX) {
+        const int tx1 = tx0 + kTileX - 1 < p.W - 1 ? tx0 + kTileX - 1 : p.W - 1;
+        if (inv_last(tx1, p.W, K) - inv_first(tx0, p.W, K) + 1 > kTileX + K - 1) return false;
+    }
+    return true;
+}
+
+hipError_t launch_inverse_ring(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s) {
+#define NA2D_INVR_K(TT)                                                               \
+    switch (p.K) {                                                                    \
+        case 3: return launch_inverse_ring_t<TT, 3>(p, w, x, scale, out, s);          \
+        case 5: return launch_inverse_ring_t<TT, 5>(p, w, x, scale, out, s);          \
+        case 7: return launch_inverse_ring_t<TT, 7>(p, w, x, scale, out, s);          \
+        default: return hipErrorInvalidValue;                                         \
+    }
+    if (p.dtype == NA2D_F16) { NA2D_INVR_K(f16_t) }
+    if (p.dtype == NA2D_BF16) { NA2D_INVR_K(bf16_t) }
+#undef NA2D_INVR_K
+    return hipErrorInvalidValue;
+}
+
+}  // namespace na2d

@@ -32,6 +32,8 @@ hipError_t launch_av(const Problem &p, const void *w, const void *y, float scale
 hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);
 // out_j = scale * sum_{inverse neighbourhood} w[i, slot(i, j)] * x_i   (grad-v, grad-k)
 hipError_t launch_inverse(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
+bool inverse_ring_supported(const Problem &p);
+hipError_t launch_inverse_ring(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
 bool inverse_mfma_supported(const Problem &p);
 hipError_t launch_inverse_mfma(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
 hipError_t launch_softmax(const Problem &p, const void *logits, void *out, hipStream_t s);
