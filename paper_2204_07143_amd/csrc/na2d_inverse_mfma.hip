@@ -1,23 +1,25 @@
-// Gradients that sum over queries, on the matrix cores (f16 / bf16, K <= 7):
+// Gradients that sum over queries, on the matrix cores (f16 / bf16, K <= 9), one key tile per step:
 //   out_j = scale * sum over queries i whose window holds j of w[i, slot(i, j)] * x_i
 // (grad-v with w = attention weights, x = dout; grad-k with w = ds, x = q; arXiv 2204.07143,
 // Appendix A).  Gathered per key over its inverse neighbourhood: no atomics, fixed order.
 //
-// A workgroup owns a 16 x (4*WAVES) key tile.  The queries that see any of its keys form a
-// rectangle of at most (TY + K-1 + R) x (16 + K-1 + R) positions (R = (K-1)/2; the + R only
-// matters next to a border, where clamped queries reach further).  Per tile the rectangle's
-// x vectors are staged transposed in LDS (Xt[channel][query position]) and its weight rows are
-// copied to LDS as they are.  A wave owns a strip of four 4 x 4 key patches; for one patch
-//   out^T[d, key] = sum_pos Xt[d, pos] * Wg[pos, key]
-// runs over the (K+R+3)-row query halo of the patch, one halo row (16 positions) per MFMA block:
-//   A operand: Xt, 8-byte LDS reads (4 consecutive query positions of one channel);
+// A workgroup owns a 16 x 8 key tile position and one head and walks a range of the batch (eight waves, one
+// 4 x 4 key patch each).  The queries that see any key of the tile form a rectangle of at most
+// (8 + K-1 + R) x (16 + K-1 + R) positions (R = (K-1)/2; the + R only matters next to the far border, where
+// clamped queries reach further).  Per plane the rectangle's weight rows (mirrored at their 16-byte phase)
+// and x vectors (natural layout) reach LDS by direct loads.  For one patch
+//   out^T[d, key] = sum_pos x^T[d, pos] * Wg[pos, key]
+// runs over the rows of the rectangle that see the patch, one row (16 positions) per MFMA block:
+//   A operand: x through the transposing LDS read (4 consecutive query positions of one channel);
 //   B operand: the weights w[query pos][slot of this lane's key], 2-byte LDS gathers whose
 //              address is the sum of a per-lane row term (depends on the halo row and the lane's
 //              key row) and a per-lane column term (depends on the 4 halo columns of the lane and
-//              its key column); invalid combinations read a zero word.  Row terms are rebuilt when
-//              the strip's rows change class, column terms per patch (4 values);
-//   halo rows that no key of the patch is seen from are skipped (wave-uniform mask).
+//              its key column); invalid combinations read a zero word.  Both kinds of terms are built
+//              once per tile position into small LDS tables (one entry per thread);
+//   halo rows that no key row of the strip is seen from are skipped (wave-uniform mask).
 // Each lane ends up with 8 consecutive channels of its own key: scale, convert, one 16-byte global store.
+// For K <= 7 on maps without far-border tiles the column-walking kernel (na2d_inverse_ring.hip) is used
+// instead; this one serves K = 9 and the remaining maps.
 #include "na2d_kernels.hpp"
 #include "na2d_mfma.hpp"
 #include "na2d_tile.hpp"
