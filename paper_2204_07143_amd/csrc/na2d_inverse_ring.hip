@@ -50,15 +50,19 @@ struct InvRingCfg {
 template <typename T, int K>
 __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restrict__ w, const T *__restrict__ x, float scale,
                                                               T *__restrict__ out, int H, int W, int tiles_x, int tiles_y,
-                                                              int nplanes) {
+                                                              int nplanes, int nseg) {
     using C = InvRingCfg<T, K>;
     constexpr int SZ = (int)sizeof(T);
     constexpr int BIG = 1 << 24;   // invalid row / column terms push the sum past the zero word
     extern __shared__ __align__(16) char lds[];
 
+    // workgroup -> (plane, segment of the column, column); the column index runs fastest.  A column is cut into
+    // nseg segments of consecutive tiles when there are too few planes x columns to fill the chip.
     const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
-    if (wg >= nplanes * tiles_x) return;
-    const int plane = wg / tiles_x, tix = wg - plane * tiles_x;
+    if (wg >= nplanes * tiles_x * nseg) return;
+    const int tix = wg % tiles_x, seg = (wg / tiles_x) % nseg, plane = wg / (tiles_x * nseg);
+    const int t_begin = (seg * tiles_y) / nseg, t_end = ((seg + 1) * tiles_y) / nseg;
+    if (t_begin >= t_end) return;
 
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -149,10 +153,11 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
         if (pp0 < W && ix <= rx1 && jxe < W && (unsigned)c < (unsigned)K) term = (ix - rx0) * C::KK * SZ + c * SZ;
         *lds_ptr<int>(tbl_col + e * 4) = term;
     }
-    // the rows of the first tile
+    // the rows of the segment's first tile
     {
-        const int ty1 = C::TY - 1 < H - 1 ? C::TY - 1 : H - 1;
-        load_rows(0, inv_last(ty1, H, K) + 1);
+        const int ty0 = t_begin * C::TY;
+        const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
+        load_rows(inv_first(ty0, H, K), inv_last(ty1, H, K) + 1);
     }
     wait_global_loads();
     __syncthreads();
@@ -165,12 +170,12 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
         colterm[3] = (int)ct.w;
     }
 
-    for (int t = 0; t < tiles_y; ++t) {
+    for (int t = t_begin; t < t_end; ++t) {
         const int ty0 = t * C::TY;
         const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
         const int ry1 = inv_last(ty1, H, K);   // last query row of this tile's rectangle (the first is inv_first(ty0))
         // the next tile's new rows go to the slots that the tile before this one has left
-        if (t + 1 < tiles_y) {
+        if (t + 1 < t_end) {
             const int ny1 = ty1 + C::TY < H - 1 ? ty1 + C::TY : H - 1;
             load_rows(ry1 + 1, inv_last(ny1, H, K) + 1);
         }
@@ -244,7 +249,10 @@ static hipError_t launch_inverse_ring_t(const Problem &p, const void *w, const v
                                         hipStream_t s) {
     using C = InvRingCfg<T, K>;
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
-    const int nwg = p.planes() * tiles_x;
+    // segments per column: enough workgroups for the chip's 512 slots, at least two tiles each where possible
+    int nseg = 512 / (p.planes() * tiles_x);
+    nseg = nseg < 1 ? 1 : (nseg > (tiles_y + 1) / 2 ? (tiles_y + 1) / 2 : nseg);
+    const int nwg = p.planes() * tiles_x * nseg;
     auto kern = inverse_ring_kernel<T, K>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -254,7 +262,7 @@ static hipError_t launch_inverse_ring_t(const Problem &p, const void *w, const v
         attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s, static_cast<const T *>(w),
-                       static_cast<const T *>(x), scale, static_cast<T *>(out), p.H, p.W, tiles_x, tiles_y, p.planes());
+                       static_cast<const T *>(x), scale, static_cast<T *>(out), p.H, p.W, tiles_x, tiles_y, p.planes(), nseg);
     return hipGetLastError();
 }
 
