@@ -33,7 +33,8 @@ struct InvRingCfg {
     static constexpr int kThreads = kWave * WAVES;
     static constexpr int KB = Traits<T>::kKeyBytes;
     static constexpr int kXRow = RW * KB;                         // x vectors of one query row, natural layout
-    static constexpr int kXBytes = NR * kXRow + 6 * KB;           // + the reach of a 16-wide block past the last slot
+    // + the reach of a 16-wide block (it starts up to 12 columns into a row) past the last slot
+    static constexpr int kXBytes = NR * kXRow + (28 - RW) * KB;
     static constexpr int kXItems = (RW * (KB / 16) + kWave - 1) / kWave;   // 64-lane loads per x row
     static constexpr int kRowBytes = RW * KK * (int)sizeof(T);
     static constexpr int kRowRegion = mirror_bytes(kRowBytes);    // a weight row, mirrored at its 16-byte phase
