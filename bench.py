@@ -157,6 +157,45 @@ def measured_traffic(workload: str, p, kernel_group: str):
     return None
 
 
+def composite_nat_tiny(p1, na, synth, torch, stream, iters: int) -> dict:
+    """One NAT-Tiny forward's (and forward + backward's) worth of neighbourhood attention at the bench
+    batch: the four stages of the model (Section 3.2: 3, 4, 18 and 5 layers on 56, 28, 14 and 7 wide
+    maps with 2, 4, 8 and 16 heads of dim 32), each layer one fused forward (plus one fused backward),
+    every stage timed on its own over rotating buffer sets and weighted by its layer count."""
+    layers = (3, 4, 18, 5)
+    stages, fwd_us, bwd_us, fwd_bytes, bwd_bytes = [], 0.0, 0.0, 0, 0
+    for i, nl in enumerate(layers):
+        sp = synth.Problem(p1.B, p1.heads << i, p1.H >> i, p1.W >> i, p1.D, p1.k, p1.dtype)
+        host = synth.make_inputs(sp, seed=1100 + i)
+        sets = [BufferSet(sp, host, na, synth, torch) for _ in range(3)]
+        calls = make_calls(sp, na, sp.default_scale)
+        ab = algorithmic_bytes(sp)
+        us = {}
+        for name in ("fused_fwd", "fused_bwd"):
+            for st in sets:
+                calls[name](st)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a.record(stream)
+            for j in range(iters):
+                calls[name](sets[j % len(sets)])
+            b.record(stream)
+            torch.cuda.synchronize()
+            us[name] = a.elapsed_time(b) * 1e3 / iters
+        stages.append({"map": f"{sp.H}x{sp.W}", "heads": sp.heads, "layers": nl, "fused_fwd_us": round(us["fused_fwd"], 2),
+                       "fused_bwd_us": round(us["fused_bwd"], 2)})
+        fwd_us += nl * us["fused_fwd"]
+        bwd_us += nl * us["fused_bwd"]
+        fwd_bytes += nl * ab["fused_fwd"]
+        bwd_bytes += nl * ab["fused_bwd"]
+        del sets
+    log(f"  composite NAT-Tiny (30 layers, batch {p1.B}): NA forward {fwd_us:.0f} us, forward + backward {fwd_us + bwd_us:.0f} us")
+    return {"what": f"NAT-Tiny's 30 NA layers at batch {p1.B}, {p1.dtype}, k={p1.k}: fused forward (+ fused backward) per layer",
+            "fwd_us": round(fwd_us, 1), "fwd_bwd_us": round(fwd_us + bwd_us, 1),
+            "fwd_GBps": round(fwd_bytes / fwd_us / 1e3, 1), "fwd_bwd_GBps": round((fwd_bytes + bwd_bytes) / (fwd_us + bwd_us) / 1e3, 1),
+            "stages": stages}
+
+
 def inverse_kernel_name(workload: str, p) -> str:
     """grad-v / grad-k run one of two device kernels, chosen by the library from the map and kernel
     size (the column-walking `inverse_ring` or the tile kernel `inverse_mfma`); the name reported is
@@ -277,6 +316,10 @@ def main() -> int:
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args.workload, p, dominant),
                 "us_per_launch": round(avg_us, 2), "algorithmic_bytes_per_launch": int(avg_bytes)}
 
+    composite = None
+    if args.workload == "nat_tiny_stage1" and args.k is None:
+        composite = composite_nat_tiny(p, na, synth, torch, stream, args.kernel_iters)
+
     if args.copy_probe:   # 128 MiB device-to-device copies: 2 x 128 MiB of HBM traffic each
         src = torch.empty(128 << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -296,6 +339,8 @@ def main() -> int:
                         "fwd_bwd_fused": round(kernels["fused_fwd"]["us"] + kernels["fused_bwd"]["us"], 1)},
         "kernels": kernels, "roofline": roofline,
     }
+    if composite is not None:
+        result["composite"] = composite
     if not args.no_cpu_baseline:
         log("timing the oracle on the host cores (bounded sample) ...")
         result["cpu_baseline"] = cpu_baseline(p, synth)

@@ -215,3 +215,46 @@ def test_softmax_shift_invariance_and_extremes(oracle):
     one_hot[0, 4] = 0.0
     p = oracle.softmax(one_hot)
     assert p[0, 4] == 1.0 and p.sum() == 1.0
+
+
+# ---- SASA through zero padding (Section 3.1: SASA's sliding window can run on the NA kernels if
+# the input is zero-padded; the windows of the un-padded positions are then all centred) ----------
+
+def sasa_brute_force(q, k, v, bias_centre, scale, ks):
+    """Stand-alone self attention with a centred ks x ks window and zero padding: keys outside the
+    map are zero vectors that still take part in the softmax.  bias_centre[h, dy + r, dx + r]."""
+    B, Hh, H, W, D = q.shape
+    r = ks // 2
+    out = np.zeros_like(q)
+    for b in range(B):
+        for h in range(Hh):
+            for y in range(H):
+                for x in range(W):
+                    logit = np.empty(ks * ks)
+                    vals = np.zeros((ks * ks, D))
+                    for dy in range(-r, r + 1):
+                        for dx in range(-r, r + 1):
+                            s = (dy + r) * ks + dx + r
+                            yy, xx = y + dy, x + dx
+                            inside = 0 <= yy < H and 0 <= xx < W
+                            kv = k[b, h, yy, xx] if inside else np.zeros(D)
+                            if inside:
+                                vals[s] = v[b, h, yy, xx]
+                            logit[s] = scale * float(q[b, h, y, x] @ kv) + bias_centre[h, dy + r, dx + r]
+                    e = np.exp(logit - logit.max())
+                    out[b, h, y, x] = (e / e.sum()) @ vals
+    return out
+
+
+@pytest.mark.parametrize("H,W,ks", [(5, 6, 3), (6, 7, 5), (4, 9, 7)])
+def test_sasa_equals_na_on_zero_padded_input(oracle, H, W, ks):
+    g = rng(300 + ks)
+    B, Hh, D, r = 2, 2, 4, ks // 2
+    q, k, v = (g.standard_normal((B, Hh, H, W, D)) for _ in range(3))
+    rpb = 0.5 * g.standard_normal((Hh, 2 * ks - 1, 2 * ks - 1))
+    scale = 0.37
+    pad = lambda t: np.pad(t, ((0, 0), (0, 0), (r, r), (r, r), (0, 0)))
+    na_out = oracle.fwd(pad(q), pad(k), pad(v), rpb, scale, ks)[:, :, r:r + H, r:r + W]
+    # a centred window uses the central ks x ks block of the relative bias table
+    want = sasa_brute_force(q, k, v, rpb[:, r:r + ks, r:r + ks], scale, ks)
+    np.testing.assert_allclose(na_out, want, rtol=1e-12, atol=1e-13)
