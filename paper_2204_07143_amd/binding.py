@@ -28,6 +28,12 @@ EXPORTS = (
 )
 
 
+EXPORTS_1D = (
+    "na1d_validate_problem", "na1d_qk_rpb", "na1d_softmax", "na1d_av", "na1d_fused_fwd", "na1d_av_bwd_p", "na1d_av_bwd_v",
+    "na1d_softmax_bwd", "na1d_qk_bwd_q", "na1d_qk_bwd_k", "na1d_qk_bwd_rpb", "na1d_workspace_bytes",
+)
+
+
 class Na2dError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"na2d status {status}: {message}")
@@ -36,6 +42,10 @@ class Na2dError(RuntimeError):
 
 class Na2dProblem(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("B", "heads", "H", "W", "D", "k", "dtype")]
+
+
+class Na1dProblem(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "heads", "L", "D", "k", "dtype")]
 
 
 _lib = None
@@ -73,6 +83,26 @@ def load() -> ctypes.CDLL:
             fn = getattr(lib, name)
             fn.argtypes = argtypes
             fn.restype = ctypes.c_int
+        p1 = ctypes.POINTER(Na1dProblem)
+        sigs_1d = {
+            "na1d_validate_problem": [p1],
+            "na1d_qk_rpb": [p1, vp, vp, vp, f, vp, vp],
+            "na1d_softmax": [p1, vp, vp, vp],
+            "na1d_av": [p1, vp, vp, vp, vp],
+            "na1d_fused_fwd": [p1, vp, vp, vp, vp, f, vp, vp, vp],
+            "na1d_av_bwd_p": [p1, vp, vp, vp, vp],
+            "na1d_av_bwd_v": [p1, vp, vp, vp, vp],
+            "na1d_softmax_bwd": [p1, vp, vp, vp, vp],
+            "na1d_qk_bwd_q": [p1, vp, vp, f, vp, vp],
+            "na1d_qk_bwd_k": [p1, vp, vp, f, vp, vp],
+            "na1d_qk_bwd_rpb": [p1, vp, vp, vp, ctypes.c_size_t, vp],
+        }
+        for name, argtypes in sigs_1d.items():
+            fn = getattr(lib, name)
+            fn.argtypes = argtypes
+            fn.restype = ctypes.c_int
+        lib.na1d_workspace_bytes.argtypes = [p1]
+        lib.na1d_workspace_bytes.restype = ctypes.c_size_t
         lib.na2d_workspace_bytes.argtypes = [pp, ctypes.c_int]
         lib.na2d_workspace_bytes.restype = ctypes.c_size_t
         lib.na2d_strerror.argtypes = [ctypes.c_int]
@@ -259,3 +289,108 @@ def na2d_validate_problem(p: Na2dProblem) -> int:
 
 def na2d_version() -> int:
     return int(load().na2d_version())
+
+
+# ---- 1D entry points (include/na1d.h): tensors are [B, heads, L, D], [B, heads, L, k], [heads, 2k-1] ----------
+
+def problem_1d(B: int, heads: int, L: int, D: int, k: int, dtype) -> Na1dProblem:
+    code = DTYPE_CODES[dtype] if dtype in DTYPE_CODES else int(dtype)
+    return Na1dProblem(B, heads, L, D, k, code)
+
+
+def _p1(x: torch.Tensor, k: int) -> Na1dProblem:
+    if x.dim() != 4:
+        raise ValueError("expected a [B, heads, L, D] tensor")
+    B, heads, L, D = x.shape
+    return problem_1d(B, heads, L, D, k, x.dtype)
+
+
+def _attn1(x, k):
+    return (*x.shape[:3], k)
+
+
+def _rpb1(x, k):
+    return (x.shape[1], 2 * k - 1)
+
+
+def na1d_validate_problem(p: Na1dProblem) -> int:
+    return int(load().na1d_validate_problem(ctypes.byref(p)))
+
+
+def na1d_qk_rpb(q, k_, rpb, scale: float, kernel: int, logits):
+    p = _p1(q, kernel)
+    _check(load().na1d_qk_rpb(ctypes.byref(p), _ptr(q), _ptr(k_, q.dtype, q.shape),
+                              _ptr(rpb, q.dtype, _rpb1(q, kernel)) if rpb is not None else None, scale,
+                              _ptr(logits, q.dtype, _attn1(q, kernel)), _stream()))
+    return logits
+
+
+def na1d_softmax(logits, kernel: int, like, out):
+    p = _p1(like, kernel)
+    _check(load().na1d_softmax(ctypes.byref(p), _ptr(logits, like.dtype, _attn1(like, kernel)),
+                               _ptr(out, like.dtype, _attn1(like, kernel)), _stream()))
+    return out
+
+
+def na1d_av(attn, v, kernel: int, out):
+    p = _p1(v, kernel)
+    _check(load().na1d_av(ctypes.byref(p), _ptr(attn, v.dtype, _attn1(v, kernel)), _ptr(v), _ptr(out, v.dtype, v.shape),
+                          _stream()))
+    return out
+
+
+def na1d_fused_fwd(q, k_, v, rpb, scale: float, kernel: int, out, lse=None):
+    p = _p1(q, kernel)
+    _check(load().na1d_fused_fwd(ctypes.byref(p), _ptr(q), _ptr(k_, q.dtype, q.shape), _ptr(v, q.dtype, q.shape),
+                                 _ptr(rpb, q.dtype, _rpb1(q, kernel)) if rpb is not None else None, scale,
+                                 _ptr(out, q.dtype, q.shape),
+                                 _ptr(lse, torch.float32, q.shape[:3]) if lse is not None else None, _stream()))
+    return out
+
+
+def na1d_av_bwd_p(dout, v, kernel: int, dp):
+    p = _p1(v, kernel)
+    _check(load().na1d_av_bwd_p(ctypes.byref(p), _ptr(dout, v.dtype, v.shape), _ptr(v), _ptr(dp, v.dtype, _attn1(v, kernel)),
+                                _stream()))
+    return dp
+
+
+def na1d_av_bwd_v(attn, dout, kernel: int, dv):
+    p = _p1(dout, kernel)
+    _check(load().na1d_av_bwd_v(ctypes.byref(p), _ptr(attn, dout.dtype, _attn1(dout, kernel)), _ptr(dout),
+                                _ptr(dv, dout.dtype, dout.shape), _stream()))
+    return dv
+
+
+def na1d_softmax_bwd(attn, dp, kernel: int, like, ds):
+    p = _p1(like, kernel)
+    shape = _attn1(like, kernel)
+    _check(load().na1d_softmax_bwd(ctypes.byref(p), _ptr(attn, like.dtype, shape), _ptr(dp, like.dtype, shape),
+                                   _ptr(ds, like.dtype, shape), _stream()))
+    return ds
+
+
+def na1d_qk_bwd_q(ds, k_, scale: float, kernel: int, dq):
+    p = _p1(k_, kernel)
+    _check(load().na1d_qk_bwd_q(ctypes.byref(p), _ptr(ds, k_.dtype, _attn1(k_, kernel)), _ptr(k_), scale,
+                                _ptr(dq, k_.dtype, k_.shape), _stream()))
+    return dq
+
+
+def na1d_qk_bwd_k(ds, q, scale: float, kernel: int, dk):
+    p = _p1(q, kernel)
+    _check(load().na1d_qk_bwd_k(ctypes.byref(p), _ptr(ds, q.dtype, _attn1(q, kernel)), _ptr(q), scale,
+                                _ptr(dk, q.dtype, q.shape), _stream()))
+    return dk
+
+
+def na1d_workspace_bytes(p: Na1dProblem) -> int:
+    return int(load().na1d_workspace_bytes(ctypes.byref(p)))
+
+
+def na1d_qk_bwd_rpb(ds, kernel: int, like, d_rpb, workspace):
+    p = _p1(like, kernel)
+    _check(load().na1d_qk_bwd_rpb(ctypes.byref(p), _ptr(ds, like.dtype, _attn1(like, kernel)),
+                                  _ptr(d_rpb, torch.float32, _rpb1(like, kernel)), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream()))
+    return d_rpb

@@ -56,6 +56,37 @@ CONFIGS = {
 }
 
 
+@dataclass(frozen=True)
+class Problem1D:
+    B: int
+    heads: int
+    L: int
+    D: int
+    k: int
+    dtype: str
+
+    @property
+    def n_queries(self) -> int:
+        return self.B * self.heads * self.L
+
+    @property
+    def elem_bytes(self) -> int:
+        return 4 if self.dtype == "f32" else 2
+
+    @property
+    def default_scale(self) -> float:
+        return float(self.D) ** -0.5
+
+
+# 1D workloads.  The paper ships a 1D module but measures nothing on it, so the shapes are the 2D ones read
+# as sequences: the tokens of NAT-Tiny's first stage (56 x 56 = 3136 per image) with the same batch, heads,
+# head dim and window.
+CONFIGS_1D = {
+    "seq_3136_k7": Problem1D(64, 2, 3136, 32, 7, "f16"),
+    "seq_3136_k31_bf16": Problem1D(64, 2, 3136, 32, 31, "bf16"),
+}
+
+
 def round_to(x: np.ndarray, dtype: str) -> np.ndarray:
     """Round an fp32 array to the storage dtype (nearest-even) and return it as fp32."""
     if dtype == "f32":
@@ -76,6 +107,18 @@ def make_inputs(p: Problem, seed: int, rpb_std: float = 0.02, with_dout: bool = 
     out["rpb"] = round_to((rpb_std * g.standard_normal((p.heads, nb, nb), dtype=np.float32)), p.dtype)
     if with_dout:
         out["dout"] = round_to(g.standard_normal(shape, dtype=np.float32), p.dtype)
+    return out
+
+
+def make_inputs_1d(p: Problem1D, seed: int, rpb_std: float = 0.02) -> dict:
+    """The 1D counterpart of make_inputs: q, k, v, rpb [heads, 2k-1], dout, in that order."""
+    g = np.random.default_rng(seed)
+    shape = (p.B, p.heads, p.L, p.D)
+    out = {}
+    for name in ("q", "k", "v"):
+        out[name] = round_to(g.standard_normal(shape, dtype=np.float32), p.dtype)
+    out["rpb"] = round_to(rpb_std * g.standard_normal((p.heads, 2 * p.k - 1), dtype=np.float32), p.dtype)
+    out["dout"] = round_to(g.standard_normal(shape, dtype=np.float32), p.dtype)
     return out
 
 

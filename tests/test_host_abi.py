@@ -14,10 +14,10 @@ from paper_2204_07143_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "na2d.h")).read()
+def declared_symbols(header="na2d.h", prefix="na2d_"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(na2d_[a-z0-9_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(" + prefix + r"[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -28,6 +28,11 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), n
     assert sorted(binding.EXPORTS) == names
     assert binding.na2d_version() >= 100
+    names_1d = declared_symbols("na1d.h", "na1d_")
+    assert len(names_1d) == 12
+    for n in names_1d:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS_1D) == names_1d
 
 
 def P(B=1, heads=1, H=14, W=14, D=32, k=3, dtype=0):
@@ -132,3 +137,43 @@ def test_binding_rejects_cpu_tensors():
     x = torch.zeros(1, 1, 14, 14, 32)
     with pytest.raises(ValueError):
         binding.na2d_softmax(torch.zeros(1, 1, 14, 14, 9), 3, x, torch.zeros(1, 1, 14, 14, 9))
+
+
+def P1(B=1, heads=1, L=20, D=32, k=3, dtype=0):
+    return binding.Na1dProblem(B, heads, L, D, k, dtype)
+
+
+@pytest.mark.parametrize("prob,code", [
+    (P1(), 0), (P1(k=7, L=7), 0), (P1(k=63, L=63), 0),
+    (P1(dtype=5), -2),
+    (P1(k=4), -3), (P1(k=1), -3), (P1(k=65, L=100), -3),
+    (P1(k=7, L=6), -4),
+    (P1(D=16), -5),
+    (P1(B=0), -6), (P1(L=-3), -6), (P1(B=1 << 16, heads=64, L=1 << 12), -6),
+])
+def test_1d_problem_validation(prob, code):
+    assert binding.na1d_validate_problem(prob) == code
+
+
+def test_1d_entry_points_reject_bad_arguments_before_any_hip_call():
+    lib = binding.load()
+    good = P1(k=5)
+    buf = ctypes.create_string_buffer(64)
+    a16 = (ctypes.addressof(buf) + 15) & ~15
+    ok, off = ctypes.c_void_p(a16), ctypes.c_void_p(a16 + 4)
+    r = ctypes.byref(good)
+    assert lib.na1d_qk_rpb(None, ok, ok, None, 1.0, ok, None) == -1
+    assert lib.na1d_qk_rpb(r, None, ok, None, 1.0, ok, None) == -1
+    assert lib.na1d_qk_rpb(r, ok, ok, off, 1.0, ctypes.c_void_p(a16 + 16), None) == -7
+    assert lib.na1d_qk_rpb(r, ok, ctypes.c_void_p(a16 + 16), None, 1.0, ok, None) == -10
+    assert lib.na1d_av(r, ok, ctypes.c_void_p(a16 + 16), ok, None) == -10
+    assert lib.na1d_fused_fwd(r, ok, ok, ok, None, 1.0, ok, None, None) == -10
+    assert lib.na1d_av_bwd_v(r, ok, off, ctypes.c_void_p(a16 + 16), None) == -7
+    assert lib.na1d_softmax_bwd(r, ok, ctypes.c_void_p(a16 + 16), ok, None) == -10
+    assert lib.na1d_qk_bwd_rpb(r, ok, ctypes.c_void_p(a16 + 16), None, 0, None) == -8
+    assert lib.na1d_qk_bwd_rpb(r, ok, ctypes.c_void_p(a16 + 16), ctypes.c_void_p(a16 + 32), 8, None) == -8
+    assert lib.na1d_qk_bwd_rpb(ctypes.byref(P1(k=6)), ok, ok, ok, 1 << 20, None) == -3
+    # workspace: one (2k-1)-cell table of 64-bit integers per (plane, tile of 256 positions; 128 for k > 31)
+    assert binding.na1d_workspace_bytes(P1(B=3, heads=2, L=1000, k=7)) == 3 * 2 * 4 * 13 * 8
+    assert binding.na1d_workspace_bytes(P1(B=1, heads=1, L=1000, k=33)) == 8 * 65 * 8
+    assert binding.na1d_workspace_bytes(P1(k=4)) == 0
