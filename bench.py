@@ -196,6 +196,64 @@ def composite_nat_tiny(p1, na, synth, torch, stream, iters: int) -> dict:
             "stages": stages}
 
 
+def bench_na1d(na, synth, torch, stream, iters: int) -> dict:
+    """The 1D entry points on the sequence workload (NAT-Tiny's first-stage tokens read as a sequence:
+    B=64, heads=2, L=3136, D=32, k=7, f16), each call timed on its own over rotating buffer sets.
+    Algorithmic bytes per query: contractions 2*D*e + k*e, softmax 2*k*e, softmax backward 3*k*e, bias
+    gradient k*e, fused forward 4*D*e + 4."""
+    p = synth.CONFIGS_1D["seq_3136_k7"]
+    host = synth.make_inputs_1d(p, seed=1200)
+    td, k, e, scale = synth.TORCH_DTYPES[p.dtype], p.k, p.elem_bytes, p.default_scale
+    prob = na.problem_1d(p.B, p.heads, p.L, p.D, k, td)
+
+    class S:
+        pass
+    sets = []
+    for _ in range(3):
+        s = S()
+        s.q, s.k, s.v, s.rpb, s.dout = (synth.to_device(host[n], p.dtype) for n in ("q", "k", "v", "rpb", "dout"))
+        attn_like = lambda: torch.empty((p.B, p.heads, p.L, k), dtype=td, device="cuda")
+        s.logits, s.attn, s.dp = attn_like(), attn_like(), attn_like()
+        s.out, s.dq, s.dk, s.dv = (torch.empty_like(s.q) for _ in range(4))
+        s.lse = torch.empty((p.B, p.heads, p.L), dtype=torch.float32, device="cuda")
+        s.d_rpb = torch.empty((p.heads, 2 * k - 1), dtype=torch.float32, device="cuda")
+        s.ws = torch.empty(na.na1d_workspace_bytes(prob), dtype=torch.uint8, device="cuda")
+        sets.append(s)
+    nq = p.n_queries
+    contraction = nq * (2 * p.D * e + k * e)
+    calls = {
+        "qk_rpb": (lambda s: na.na1d_qk_rpb(s.q, s.k, s.rpb, scale, k, s.logits), contraction),
+        "softmax": (lambda s: na.na1d_softmax(s.logits, k, s.q, s.attn), nq * 2 * k * e),
+        "av": (lambda s: na.na1d_av(s.attn, s.v, k, s.out), contraction),
+        "fused_fwd": (lambda s: na.na1d_fused_fwd(s.q, s.k, s.v, s.rpb, scale, k, s.out, s.lse), nq * (4 * p.D * e + 4)),
+        "av_bwd_p": (lambda s: na.na1d_av_bwd_p(s.dout, s.v, k, s.dp), contraction),
+        "av_bwd_v": (lambda s: na.na1d_av_bwd_v(s.attn, s.dout, k, s.dv), contraction),
+        "softmax_bwd": (lambda s: na.na1d_softmax_bwd(s.attn, s.dp, k, s.q, s.dp), nq * 3 * k * e),
+        "qk_bwd_q": (lambda s: na.na1d_qk_bwd_q(s.dp, s.k, scale, k, s.dq), contraction),
+        "qk_bwd_k": (lambda s: na.na1d_qk_bwd_k(s.dp, s.q, scale, k, s.dk), contraction),
+        "qk_bwd_rpb": (lambda s: na.na1d_qk_bwd_rpb(s.dp, k, s.q, s.d_rpb, s.ws), nq * k * e),
+    }
+    res, total_us, total_bytes = {}, 0.0, 0
+    for name, (fn, nbytes) in calls.items():
+        for st in sets:
+            fn(st)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record(stream)
+        for j in range(iters):
+            fn(sets[j % len(sets)])
+        b.record(stream)
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / iters
+        res[name] = {"us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1), "pct_hbm_peak": round(100 * nbytes / us / 1e3 / HBM_PEAK_GBPS, 1),
+                     "MB": round(nbytes / 1e6, 2)}
+        total_us += us
+        total_bytes += nbytes
+        log(f"  na1d {name:12s} {us:9.2f} us  {nbytes / us / 1e3:8.1f} GB/s")
+    return {"workload": f"seq_3136_k7 (B={p.B}, heads={p.heads}, L={p.L}, D={p.D}, k={k}, {p.dtype})",
+            "us_all_calls": round(total_us, 1), "GBps_all_calls": round(total_bytes / total_us / 1e3, 1), "kernels": res}
+
+
 def inverse_kernel_name(workload: str, p) -> str:
     """grad-v / grad-k run one of two device kernels, chosen by the library from the map and kernel
     size (the column-walking `inverse_ring` or the tile kernel `inverse_mfma`); the name reported is
@@ -316,9 +374,10 @@ def main() -> int:
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args.workload, p, dominant),
                 "us_per_launch": round(avg_us, 2), "algorithmic_bytes_per_launch": int(avg_bytes)}
 
-    composite = None
+    composite, na1d = None, None
     if args.workload == "nat_tiny_stage1" and args.k is None:
         composite = composite_nat_tiny(p, na, synth, torch, stream, args.kernel_iters)
+        na1d = bench_na1d(na, synth, torch, stream, args.kernel_iters)
 
     if args.copy_probe:   # 128 MiB device-to-device copies: 2 x 128 MiB of HBM traffic each
         src = torch.empty(128 << 20, dtype=torch.uint8, device="cuda")
@@ -341,6 +400,7 @@ def main() -> int:
     }
     if composite is not None:
         result["composite"] = composite
+        result["na1d"] = na1d
     if not args.no_cpu_baseline:
         log("timing the oracle on the host cores (bounded sample) ...")
         result["cpu_baseline"] = cpu_baseline(p, synth)

@@ -29,9 +29,13 @@
  *    The bias cell of (query i, key j) is rpb[head, jy - iy + k - 1, jx - ix + k - 1].
  *  - Arithmetic: storage in the problem dtype (round-to-nearest-even on store), all dot
  *    products, the softmax and all sums accumulated in fp32.
- *  - Supported: D = 32 (every NAT variant has head dim 32, Section 3.2), odd
- *    k in {3, 5, 7, 9, 11, 13} (Appendix A, "Tiled Neighborhood Attention") with
- *    k <= min(H, W); k = H = W is the self-attention limit (Section 3.1).
+ *  - Supported: odd k in {3, 5, 7, 9, 11, 13} (Appendix A, "Tiled Neighborhood Attention")
+ *    with k <= min(H, W); k = H = W is the self-attention limit (Section 3.1).  Head dims
+ *    D in {16, 32, 64, 128}.  D = 32 (every NAT variant, Section 3.2) runs the matrix-core
+ *    kernels in the 16-bit types; the other head dims run plain-ALU kernels whose tiles must
+ *    fit the 160 KB LDS: every k for D = 16 and for D = 64 in the 16-bit types, k <= 9 for
+ *    D = 128 in the 16-bit types and for D = 64 in fp32, k = 3 for D = 128 in fp32
+ *    (anything else: NA2D_ERR_HEAD_DIM).
  *  - Return value: NA2D_OK (0) or a negative na2d_status.  All argument errors are
  *    detected on the host before any HIP call; on error nothing is enqueued.
  */
@@ -53,7 +57,7 @@ typedef enum {
     NA2D_ERR_DTYPE = -2,       /* dtype is not one of na2d_dtype */
     NA2D_ERR_KERNEL_SIZE = -3, /* k even, or not in {3,5,7,9,11,13} */
     NA2D_ERR_TOO_SMALL = -4,   /* k > min(H, W): the neighbourhood is undefined */
-    NA2D_ERR_HEAD_DIM = -5,    /* D != 32 */
+    NA2D_ERR_HEAD_DIM = -5,    /* D not in {16, 32, 64, 128}, or too large for this k and dtype (see above) */
     NA2D_ERR_SHAPE = -6,       /* non-positive extent, or a tensor beyond 2^31-1 elements */
     NA2D_ERR_ALIGN = -7,       /* a data pointer is not 16-byte aligned */
     NA2D_ERR_WORKSPACE = -8,   /* workspace missing or smaller than na2d_workspace_bytes() */

@@ -83,6 +83,31 @@ __device__ __forceinline__ void run_out(char *gbase, size_t g0, int nbytes, cons
         *reinterpret_cast<T *>(ga + tb) = *reinterpret_cast<const T *>(region + tb);
 }
 
+// The head vectors a tile's threads hold (fp32, one per thread) -> memory as one contiguous run: each thread
+// parks its vector in LDS (padded stride, the staging area of the inputs, which nobody reads any more after
+// the barrier), then the run leaves in coalesced 16-byte chunks.  Called by every thread of the workgroup.
+template <typename T, int NT>
+__device__ __forceinline__ void store_tile(const float (&acc)[kHeadDim], bool live, char *stage, char *gdst, int n, int tid) {
+    constexpr int CPK = Traits<T>::kKeyBytes / 16, STRIDE = Traits<T>::kKeyStride;
+    __syncthreads();
+    if (live) store_vec32<T>(stage + tid * STRIDE, acc);
+    __syncthreads();
+    const int nchunks = n * CPK;
+    for (int c0 = tid; c0 < nchunks; c0 += 4 * NT) {
+        u32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * NT;
+            if (c < nchunks) v[u] = *reinterpret_cast<const u32x4 *>(stage + (c / CPK) * STRIDE + (c % CPK) * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * NT;
+            if (c < nchunks) *reinterpret_cast<u32x4 *>(gdst + (size_t)c * 16) = v[u];
+        }
+    }
+}
+
 __host__ __device__ constexpr int align16(int n) { return (n + 15) & ~15; }
 
 struct Tile {
@@ -160,14 +185,14 @@ __global__ __launch_bounds__(TQ) void av1d_kernel(const T *__restrict__ w, const
     const size_t g0 = ((size_t)t.plane * L + t.t0) * K * sizeof(T);
     run_in<T, TQ>(reinterpret_cast<const char *>(w), g0, t.n * K * (int)sizeof(T), rows, tid);
     __syncthreads();
+    float acc[kHeadDim];
+#pragma unroll
+    for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
     if (tid < t.n) {
         const int i = t.t0 + tid;
         const int s = win_start(i, L, K);
         const char *yb = halo + (s - h0) * STRIDE;
         const T *wrow = reinterpret_cast<const T *>(rows + (int)(g0 & 15)) + tid * K;
-        float acc[kHeadDim];
-#pragma unroll
-        for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
         for (int a = 0; a < K; ++a) {
             Vec32<T> yv;
             load_vec32(yv, yb + a * STRIDE);
@@ -175,8 +200,8 @@ __global__ __launch_bounds__(TQ) void av1d_kernel(const T *__restrict__ w, const
         }
 #pragma unroll
         for (int d = 0; d < kHeadDim; ++d) acc[d] *= scale;
-        store_vec32<T>(reinterpret_cast<char *>(out) + ((size_t)t.plane * L + i) * KBYTES, acc);
     }
+    store_tile<T, TQ>(acc, tid < t.n, halo, reinterpret_cast<char *>(out) + ((size_t)t.plane * L + t.t0) * KBYTES, t.n, tid);
 }
 
 // ---- grad-v / grad-k: gather over the inverse neighbourhood -------------------------------------
@@ -201,13 +226,13 @@ __global__ __launch_bounds__(TQ) void inverse1d_kernel(const T *__restrict__ w, 
     const size_t g0 = ((size_t)t.plane * L + i0) * K * sizeof(T);
     run_in<T, TQ>(reinterpret_cast<const char *>(w), g0, (i1 - i0 + 1) * K * (int)sizeof(T), rows, tid);
     __syncthreads();
+    float acc[kHeadDim];
+#pragma unroll
+    for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
     if (tid < t.n) {
         const int j = t.t0 + tid;
         const int qa = inv_first(j, L, K), qb = inv_last(j, L, K);
         const T *wbase = reinterpret_cast<const T *>(rows + (int)(g0 & 15));
-        float acc[kHeadDim];
-#pragma unroll
-        for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
         for (int i = qa; i <= qb; ++i) {
             const int a = j - win_start(i, L, K);   // slot of key j in query i's window
             Vec32<T> xv;
@@ -216,8 +241,8 @@ __global__ __launch_bounds__(TQ) void inverse1d_kernel(const T *__restrict__ w, 
         }
 #pragma unroll
         for (int d = 0; d < kHeadDim; ++d) acc[d] *= scale;
-        store_vec32<T>(reinterpret_cast<char *>(out) + ((size_t)t.plane * L + j) * KBYTES, acc);
     }
+    store_tile<T, TQ>(acc, tid < t.n, halo, reinterpret_cast<char *>(out) + ((size_t)t.plane * L + t.t0) * KBYTES, t.n, tid);
 }
 
 // ---- softmax and its backward ----------------------------------------------------------------
@@ -295,6 +320,9 @@ __global__ __launch_bounds__(TQ) void fused1d_kernel(const T *__restrict__ q, co
     for (int i = tid; i < 2 * K - 1; i += TQ)
         bias[i] = rpb ? to_f32(rpb[(size_t)(t.plane % heads) * (2 * K - 1) + i]) * kLog2e : 0.f;
     __syncthreads();
+    float acc[kHeadDim];
+#pragma unroll
+    for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
     if (tid < t.n) {
         const int i = t.t0 + tid;
         Vec32<T> qv;
@@ -305,9 +333,6 @@ __global__ __launch_bounds__(TQ) void fused1d_kernel(const T *__restrict__ q, co
         const float scale2 = scale * kLog2e;
         // online softmax in the exp2 domain: running maximum m, running sum l, running weighted sum acc
         float m = -INFINITY, l = 0.f;
-        float acc[kHeadDim];
-#pragma unroll
-        for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
         for (int a = 0; a < K; ++a) {
             Vec32<T> kv, vv;
             load_vec32(kv, khalo + off + a * STRIDE);
@@ -325,9 +350,9 @@ __global__ __launch_bounds__(TQ) void fused1d_kernel(const T *__restrict__ q, co
         const float inv = 1.0f / l;
 #pragma unroll
         for (int d = 0; d < kHeadDim; ++d) acc[d] *= inv;
-        store_vec32<T>(reinterpret_cast<char *>(out) + ((size_t)t.plane * L + i) * KBYTES, acc);
         if (lse) lse[(size_t)t.plane * L + i] = (m + __builtin_amdgcn_logf(l)) * kLn2;
     }
+    store_tile<T, TQ>(acc, tid < t.n, khalo, reinterpret_cast<char *>(out) + ((size_t)t.plane * L + t.t0) * KBYTES, t.n, tid);
 }
 
 // ---- grad-b ------------------------------------------------------------------------------------
@@ -381,18 +406,33 @@ __global__ __launch_bounds__(TQ) void rpb_partial1d_kernel(const T *__restrict__
     for (int u = tid; u < NB; u += TQ) partial[(size_t)blockIdx.x * NB + u] = (long long)tbl[u];
 }
 
-// one wave per (head, cell): adds the tables of every (batch, tile) of that head
-__global__ __launch_bounds__(kWave) void rpb_final1d_kernel(const long long *__restrict__ partial, float *__restrict__ d_rpb,
-                                                            int B, int heads, int tiles, int NB) {
+// one workgroup per (head, cell): adds the tables of every (batch, tile) of that head
+constexpr int kFinalThreads = 256;
+__global__ __launch_bounds__(kFinalThreads) void rpb_final1d_kernel(const long long *__restrict__ partial,
+                                                                    float *__restrict__ d_rpb, int B, int heads, int tiles,
+                                                                    int NB) {
+    __shared__ long long wave_sum[kFinalThreads / kWave];
     const int h = blockIdx.x / NB, u = blockIdx.x % NB;
+    const int total = B * tiles;
     long long sum = 0;
-    for (int n = threadIdx.x; n < B * tiles; n += kWave) {
-        const int b = n / tiles, tl = n % tiles;
-        sum += partial[(((size_t)b * heads + h) * tiles + tl) * NB + u];
+    for (int n0 = threadIdx.x; n0 < total; n0 += 4 * kFinalThreads) {
+        long long v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + j * kFinalThreads;
+            v[j] = n < total ? partial[(((size_t)(n / tiles) * heads + h) * tiles + n % tiles) * NB + u] : 0ll;
+        }
+        sum += (v[0] + v[1]) + (v[2] + v[3]);
     }
 #pragma unroll
     for (int sh = 1; sh < kWave; sh <<= 1) sum += __shfl_xor(sum, sh, kWave);
-    if (threadIdx.x == 0) d_rpb[(size_t)h * NB + u] = (float)((double)sum * (1.0 / 4398046511104.0));   // 2^-42
+    if ((threadIdx.x & (kWave - 1)) == 0) wave_sum[threadIdx.x / kWave] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long tot = 0;
+        for (int w = 0; w < kFinalThreads / kWave; ++w) tot += wave_sum[w];
+        d_rpb[(size_t)h * NB + u] = (float)((double)tot * (1.0 / 4398046511104.0));   // 2^-42
+    }
 }
 
 // ---- launchers ---------------------------------------------------------------------------------
@@ -535,7 +575,7 @@ static hipError_t rpb_t(const Problem &p, const void *ds, float *d_rpb, void *wo
     hipLaunchKernelGGL(kern, dim3(p.planes() * tiles), dim3(TQ), bytes, s, static_cast<const T *>(ds), partial, p.L, p.K, tiles);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
     const int NB = 2 * p.K - 1;
-    hipLaunchKernelGGL(rpb_final1d_kernel, dim3(p.heads * NB), dim3(kWave), 0, s, partial, d_rpb, p.B, p.heads, tiles, NB);
+    hipLaunchKernelGGL(rpb_final1d_kernel, dim3(p.heads * NB), dim3(kFinalThreads), 0, s, partial, d_rpb, p.B, p.heads, tiles, NB);
     return hipGetLastError();
 }
 hipError_t launch_rpb_grad(const Problem &p, const void *ds, float *d_rpb, void *workspace, hipStream_t s) {

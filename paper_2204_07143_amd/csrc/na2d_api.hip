@@ -5,6 +5,7 @@
 #include "na2d.h"
 #include "na2d_common.hpp"
 #include "na2d_kernels.hpp"
+#include "na2d_valu_cfg.hpp"
 
 namespace na2d {
 
@@ -15,7 +16,7 @@ static int validate(const na2d_problem *p) {
     const int k = p->k;
     if ((k & 1) == 0 || k < 3 || k > 13) return NA2D_ERR_KERNEL_SIZE;
     if (k > p->H || k > p->W) return NA2D_ERR_TOO_SMALL;
-    if (p->D != kHeadDim) return NA2D_ERR_HEAD_DIM;
+    if (!head_dim_supported(p->dtype, k, p->D)) return NA2D_ERR_HEAD_DIM;
     // Index arithmetic inside the kernels is 64-bit for byte offsets, but element counts of a
     // tensor must fit int32 so that per-plane and per-row products cannot overflow.
     const int64_t nq = (int64_t)p->B * p->heads * p->H * p->W;
@@ -26,7 +27,7 @@ static int validate(const na2d_problem *p) {
 
 static inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-static Problem to_problem(const na2d_problem *p) { return Problem{p->B, p->heads, p->H, p->W, p->k, p->dtype}; }
+static Problem to_problem(const na2d_problem *p) { return Problem{p->B, p->heads, p->H, p->W, p->k, p->dtype, p->D}; }
 
 static int from_hip(hipError_t e) {
     if (e == hipSuccess) return NA2D_OK;
@@ -284,7 +285,7 @@ const char *na2d_strerror(int status) {
         case NA2D_ERR_DTYPE: return "unknown dtype";
         case NA2D_ERR_KERNEL_SIZE: return "kernel size must be odd and one of 3, 5, 7, 9, 11, 13";
         case NA2D_ERR_TOO_SMALL: return "kernel size exceeds the feature map (k > min(H, W))";
-        case NA2D_ERR_HEAD_DIM: return "head dim must be 32";
+        case NA2D_ERR_HEAD_DIM: return "head dim must be 16, 32, 64 or 128 (and small enough for the kernel size: see na2d.h)";
         case NA2D_ERR_SHAPE: return "non-positive extent or tensor too large";
         case NA2D_ERR_ALIGN: return "pointer is not 16-byte aligned";
         case NA2D_ERR_WORKSPACE: return "workspace missing, misaligned or too small";

@@ -7,31 +7,16 @@
 // with 16-byte loads; each thread owns one query and accumulates its 32 outputs in fp32.
 #include "na2d_kernels.hpp"
 #include "na2d_tile.hpp"
+#include "na2d_valu_cfg.hpp"
 
 namespace na2d {
 
-template <typename T, int K, int TY>
-struct AvCfg {
-    static constexpr int HALO_H = TY + K - 1, HALO_W = kTileX + K - 1;
-    static constexpr int KK = K * K;
-    static constexpr int kThreads = kTileX * TY;
-    static constexpr int kHaloBytes = HALO_H * HALO_W * Traits<T>::kKeyStride;
-    static constexpr int kRowRegion = mirror_bytes(kTileX * KK * (int)sizeof(T));
-    static constexpr int kLdsBytes = kHaloBytes + TY * kRowRegion;
-};
-
-template <typename T, int K>
-constexpr int av_tile_rows() {
-    if (AvCfg<T, K, 16>::kLdsBytes <= 80 * 1024) return 16;
-    if (AvCfg<T, K, 8>::kLdsBytes <= 80 * 1024) return 8;
-    return 4;
-}
-
-template <typename T, int K, int TY>
+template <typename T, int K, int TY, int D>
 __global__ __launch_bounds__(kTileX *TY) void av_kernel(const T *__restrict__ w, const T *__restrict__ y, float scale,
                                                          T *__restrict__ out, int H, int W, int tiles_x, int tiles_y,
                                                          int ntiles) {
-    using C = AvCfg<T, K, TY>;
+    using C = AvCfg<T, K, TY, D>;
+    constexpr int KBYTES = VecTraits<T, D>::kKeyBytes, STRIDE = VecTraits<T, D>::kKeyStride;
     extern __shared__ __align__(16) char lds[];
     char *halo = lds;
     char *rows = lds + C::kHaloBytes;
@@ -44,7 +29,7 @@ __global__ __launch_bounds__(kTileX *TY) void av_kernel(const T *__restrict__ w,
     const int hy0 = win_start(ty0, H, K), hx0 = win_start(tx0, W, K);
     const size_t plane_q = (size_t)tc.plane * H * W;
 
-    load_halo<T, C::HALO_H, C::HALO_W, C::kThreads>(reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes,
+    load_halo<T, C::HALO_H, C::HALO_W, C::kThreads, false, D>(reinterpret_cast<const char *>(y) + plane_q * KBYTES,
                                                     H, W, hy0, hx0, halo, tid);
     {
         const int wave = tid / kWave, lane = tid % kWave;
@@ -64,34 +49,34 @@ __global__ __launch_bounds__(kTileX *TY) void av_kernel(const T *__restrict__ w,
     if (qy < H && qx < W) {
         const size_t g0 = (plane_q + (size_t)qy * W + tx0) * C::KK * sizeof(T);
         const int sy = win_start(qy, H, K), sx = win_start(qx, W, K);
-        const char *vbase = halo + ((sy - hy0) * C::HALO_W + (sx - hx0)) * Traits<T>::kKeyStride;
+        const char *vbase = halo + ((sy - hy0) * C::HALO_W + (sx - hx0)) * STRIDE;
         const T *wrow = reinterpret_cast<const T *>(rows + ly * C::kRowRegion + (int)(g0 & 15)) + lx * C::KK;
-        float acc[kHeadDim];
+        float acc[D];
 #pragma unroll
-        for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
+        for (int d = 0; d < D; ++d) acc[d] = 0.f;
 #pragma unroll 1
         for (int a = 0; a < K; ++a) {
 #pragma unroll
             for (int c = 0; c < K; ++c) {
-                Vec32<T> vv;
-                lds_load_vec32(vv, vbase + (a * C::HALO_W + c) * Traits<T>::kKeyStride);
+                VecN<T, D> vv;
+                lds_load_vec32(vv, vbase + (a * C::HALO_W + c) * STRIDE);
                 axpy32(acc, to_f32(wrow[a * K + c]), vv);
             }
         }
 #pragma unroll
-        for (int d = 0; d < kHeadDim; ++d) acc[d] *= scale;
-        store_vec32<T>(reinterpret_cast<char *>(out) + (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes, acc);
+        for (int d = 0; d < D; ++d) acc[d] *= scale;
+        store_vec32<T>(reinterpret_cast<char *>(out) + (plane_q + (size_t)qy * W + qx) * KBYTES, acc);
     }
 }
 
-template <typename T, int K>
+template <typename T, int K, int D>
 static hipError_t launch_av_t(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s) {
-    constexpr int TY = av_tile_rows<T, K>();
-    using C = AvCfg<T, K, TY>;
+    if constexpr (!valu_fits<T, K, D>()) return hipErrorInvalidValue; else {
+    constexpr int TY = tile_rows<AvCfg, T, K, D>();
+    using C = AvCfg<T, K, TY, D>;
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + TY - 1) / TY;
     const int ntiles = tiles_x * tiles_y * p.planes();
-    auto kern = av_kernel<T, K, TY>;
-    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
+    auto kern = av_kernel<T, K, TY, D>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -103,11 +88,12 @@ static hipError_t launch_av_t(const Problem &p, const void *w, const void *y, fl
                        static_cast<const T *>(w), static_cast<const T *>(y), scale, static_cast<T *>(out), p.H, p.W,
                        tiles_x, tiles_y, ntiles);
     return hipGetLastError();
+    }
 }
 
 hipError_t launch_av(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s) {
-    if (p.dtype != NA2D_F32 && !force_valu()) return launch_av_mfma(p, w, y, scale, out, s);
-    NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, return (launch_av_t<T, K>(p, w, y, scale, out, s))));
+    if (p.D == kHeadDim && p.dtype != NA2D_F32 && !force_valu()) return launch_av_mfma(p, w, y, scale, out, s);
+    NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, NA2D_DISPATCH_D(p.D, return (launch_av_t<T, K, D>(p, w, y, scale, out, s)))));
     return hipErrorInvalidValue;
 }
 

@@ -13,7 +13,7 @@
 
 namespace na2d {
 
-constexpr int kHeadDim = 32;       // D: every NAT variant uses head dim 32 (Section 3.2)
+constexpr int kHeadDim = 32;       // D of every NAT variant (Section 3.2): the matrix-core kernels are built for it
 constexpr int kWave = 64;          // CDNA wavefront width
 
 // ---- neighbourhood index functions (one axis of length L, odd window K <= L) -----------
@@ -77,18 +77,27 @@ template <> __device__ __forceinline__ float from_f32<float>(float x) { return x
 template <> __device__ __forceinline__ f16_t from_f32<f16_t>(float x) { return (f16_t)x; }   // round-to-nearest-even
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; } // round-to-nearest-even
 
-// A head vector (32 elements) held in registers in its storage type, as 32-bit words.
-template <typename T> struct Vec32 {
-    static constexpr int kChunks = Traits<T>::kKeyBytes / 16;
-    static constexpr int kWords = Traits<T>::kKeyBytes / 4;
-    uint32_t w[kWords];
+// Byte size of a head vector of D elements and its padded LDS stride (+16 bytes: consecutive keys start
+// 4 banks apart, so 16-byte LDS reads of neighbouring keys do not collide).
+template <typename T, int D> struct VecTraits {
+    static_assert(D % 8 == 0, "a head vector is a whole number of 16-byte chunks in every storage type");
+    static constexpr int kKeyBytes = D * (int)sizeof(T);
+    static constexpr int kKeyStride = kKeyBytes + 16;
 };
 
-template <typename T>
-__device__ __forceinline__ void load_vec32(Vec32<T> &v, const void *p) {
+// A head vector (D elements) held in registers in its storage type, as 32-bit words.
+template <typename T, int D = kHeadDim> struct VecN {
+    static constexpr int kChunks = VecTraits<T, D>::kKeyBytes / 16;
+    static constexpr int kWords = VecTraits<T, D>::kKeyBytes / 4;
+    uint32_t w[kWords];
+};
+template <typename T> using Vec32 = VecN<T, kHeadDim>;
+
+template <typename T, int D>
+__device__ __forceinline__ void load_vec32(VecN<T, D> &v, const void *p) {
     const u32x4 *s = reinterpret_cast<const u32x4 *>(p);
 #pragma unroll
-    for (int i = 0; i < Vec32<T>::kChunks; ++i) {
+    for (int i = 0; i < VecN<T, D>::kChunks; ++i) {
         const u32x4 t = s[i];
         v.w[4 * i + 0] = t.x;
         v.w[4 * i + 1] = t.y;
@@ -98,39 +107,44 @@ __device__ __forceinline__ void load_vec32(Vec32<T> &v, const void *p) {
 }
 
 // fp32 dot product of two head vectors held in storage type.
-__device__ __forceinline__ float dot32(const Vec32<float> &a, const Vec32<float> &b) {
+template <int D>
+__device__ __forceinline__ float dot32(const VecN<float, D> &a, const VecN<float, D> &b) {
     float acc = 0.f;
 #pragma unroll
-    for (int i = 0; i < 32; ++i) acc = __builtin_fmaf(__uint_as_float(a.w[i]), __uint_as_float(b.w[i]), acc);
+    for (int i = 0; i < D; ++i) acc = __builtin_fmaf(__uint_as_float(a.w[i]), __uint_as_float(b.w[i]), acc);
     return acc;
 }
-__device__ __forceinline__ float dot32(const Vec32<f16_t> &a, const Vec32<f16_t> &b) {
+template <int D>
+__device__ __forceinline__ float dot32(const VecN<f16_t, D> &a, const VecN<f16_t, D> &b) {
     float acc = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < D / 2; ++i) {
         const uint32_t ua = a.w[i], ub = b.w[i];
         acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, ua), __builtin_bit_cast(f16x2, ub), acc, false);
     }
     return acc;
 }
-__device__ __forceinline__ float dot32(const Vec32<bf16_t> &a, const Vec32<bf16_t> &b) {
+template <int D>
+__device__ __forceinline__ float dot32(const VecN<bf16_t, D> &a, const VecN<bf16_t, D> &b) {
     float acc = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < D / 2; ++i) {
         const uint32_t ua = a.w[i], ub = b.w[i];
         acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, ua), __builtin_bit_cast(bf16x2, ub), acc, false);
     }
     return acc;
 }
 
-// acc[0..31] += w * v  (fp32 accumulate, v in storage type).
-__device__ __forceinline__ void axpy32(float (&acc)[kHeadDim], float w, const Vec32<float> &v) {
+// acc[0..D-1] += w * v  (fp32 accumulate, v in storage type).
+template <int D>
+__device__ __forceinline__ void axpy32(float (&acc)[D], float w, const VecN<float, D> &v) {
 #pragma unroll
-    for (int i = 0; i < 32; ++i) acc[i] = __builtin_fmaf(w, __uint_as_float(v.w[i]), acc[i]);
+    for (int i = 0; i < D; ++i) acc[i] = __builtin_fmaf(w, __uint_as_float(v.w[i]), acc[i]);
 }
-__device__ __forceinline__ void axpy32(float (&acc)[kHeadDim], float w, const Vec32<f16_t> &v) {
+template <int D>
+__device__ __forceinline__ void axpy32(float (&acc)[D], float w, const VecN<f16_t, D> &v) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < D / 2; ++i) {
         const uint32_t u = v.w[i];
         const f16_t lo = __builtin_bit_cast(f16_t, (uint16_t)(u & 0xffffu));
         const f16_t hi = __builtin_bit_cast(f16_t, (uint16_t)(u >> 16));
@@ -138,32 +152,33 @@ __device__ __forceinline__ void axpy32(float (&acc)[kHeadDim], float w, const Ve
         acc[2 * i + 1] = __builtin_fmaf(w, (float)hi, acc[2 * i + 1]);
     }
 }
-__device__ __forceinline__ void axpy32(float (&acc)[kHeadDim], float w, const Vec32<bf16_t> &v) {
+template <int D>
+__device__ __forceinline__ void axpy32(float (&acc)[D], float w, const VecN<bf16_t, D> &v) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < D / 2; ++i) {
         const uint32_t u = v.w[i];
         acc[2 * i] = __builtin_fmaf(w, __uint_as_float(u << 16), acc[2 * i]);
         acc[2 * i + 1] = __builtin_fmaf(w, __uint_as_float(u & 0xffff0000u), acc[2 * i + 1]);
     }
 }
 
-// Store 32 fp32 values as one head vector in storage type (p is 16-byte aligned).
-template <typename T>
-__device__ __forceinline__ void store_vec32(void *p, const float (&x)[kHeadDim]) {
+// Store D fp32 values as one head vector in storage type (p is 16-byte aligned).
+template <typename T, int D>
+__device__ __forceinline__ void store_vec32(void *p, const float (&x)[D]) {
     if constexpr (sizeof(T) == 4) {
         f32x4 *d = reinterpret_cast<f32x4 *>(p);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) d[i] = f32x4{x[i * 4], x[i * 4 + 1], x[i * 4 + 2], x[i * 4 + 3]};
+        for (int i = 0; i < D / 4; ++i) d[i] = f32x4{x[i * 4], x[i * 4 + 1], x[i * 4 + 2], x[i * 4 + 3]};
     } else {
         u32x4 *d = reinterpret_cast<u32x4 *>(p);
-        uint32_t w[16];
+        uint32_t w[D / 2];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < D / 2; ++i) {
             const T lo = from_f32<T>(x[2 * i]), hi = from_f32<T>(x[2 * i + 1]);
             w[i] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) d[i] = u32x4{w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]};
+        for (int i = 0; i < D / 8; ++i) d[i] = u32x4{w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]};
     }
 }
 

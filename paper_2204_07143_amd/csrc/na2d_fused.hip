@@ -8,33 +8,18 @@
 // max / running sum (online softmax), rescaling its 32 fp32 accumulators once per window row.
 #include "na2d_kernels.hpp"
 #include "na2d_tile.hpp"
+#include "na2d_valu_cfg.hpp"
 
 namespace na2d {
 
-template <typename T, int K, int TY>
-struct FusedCfg {
-    static constexpr int HALO_H = TY + K - 1, HALO_W = kTileX + K - 1;
-    static constexpr int NB = 2 * K - 1;
-    static constexpr int kThreads = kTileX * TY;
-    static constexpr int kHaloBytes = HALO_H * HALO_W * Traits<T>::kKeyStride;
-    static constexpr int kBiasBytes = ((NB * NB * 4) + 15) & ~15;
-    static constexpr int kLdsBytes = 2 * kHaloBytes + kBiasBytes;
-};
-
-template <typename T, int K>
-constexpr int fused_tile_rows() {
-    if (FusedCfg<T, K, 16>::kLdsBytes <= 80 * 1024) return 16;
-    if (FusedCfg<T, K, 8>::kLdsBytes <= 80 * 1024) return 8;
-    return 4;
-}
-
-template <typename T, int K, int TY>
+template <typename T, int K, int TY, int D>
 __global__ __launch_bounds__(kTileX *TY) void fused_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k,
                                                                 const T *__restrict__ v, const T *__restrict__ rpb,
                                                                 float scale, T *__restrict__ out,
                                                                 float *__restrict__ lse, int H, int W, int heads,
                                                                 int tiles_x, int tiles_y, int ntiles) {
-    using C = FusedCfg<T, K, TY>;
+    using C = FusedCfg<T, K, TY, D>;
+    constexpr int KBYTES = VecTraits<T, D>::kKeyBytes, STRIDE = VecTraits<T, D>::kKeyStride;
     extern __shared__ __align__(16) char lds[];
     char *khalo = lds;
     char *vhalo = lds + C::kHaloBytes;
@@ -48,9 +33,9 @@ __global__ __launch_bounds__(kTileX *TY) void fused_fwd_kernel(const T *__restri
     const int hy0 = win_start(ty0, H, K), hx0 = win_start(tx0, W, K);
     const size_t plane_q = (size_t)tc.plane * H * W;
 
-    load_halo<T, C::HALO_H, C::HALO_W, C::kThreads>(reinterpret_cast<const char *>(k) + plane_q * Traits<T>::kKeyBytes,
+    load_halo<T, C::HALO_H, C::HALO_W, C::kThreads, false, D>(reinterpret_cast<const char *>(k) + plane_q * KBYTES,
                                                     H, W, hy0, hx0, khalo, tid);
-    load_halo<T, C::HALO_H, C::HALO_W, C::kThreads>(reinterpret_cast<const char *>(v) + plane_q * Traits<T>::kKeyBytes,
+    load_halo<T, C::HALO_H, C::HALO_W, C::kThreads, false, D>(reinterpret_cast<const char *>(v) + plane_q * KBYTES,
                                                     H, W, hy0, hx0, vhalo, tid);
     {
         const int head = tc.plane % heads;
@@ -62,15 +47,15 @@ __global__ __launch_bounds__(kTileX *TY) void fused_fwd_kernel(const T *__restri
     const int lx = tid % kTileX, ly = tid / kTileX;
     const int qy = ty0 + ly, qx = tx0 + lx;
     if (qy < H && qx < W) {
-        Vec32<T> qv;
-        load_vec32(qv, reinterpret_cast<const char *>(q) + (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes);
+        VecN<T, D> qv;
+        load_vec32(qv, reinterpret_cast<const char *>(q) + (plane_q + (size_t)qy * W + qx) * KBYTES);
         const int sy = win_start(qy, H, K), sx = win_start(qx, W, K);
         const int py = sy - qy + (K - 1), px = sx - qx + (K - 1);
-        const int hoff = ((sy - hy0) * C::HALO_W + (sx - hx0)) * Traits<T>::kKeyStride;
+        const int hoff = ((sy - hy0) * C::HALO_W + (sx - hx0)) * STRIDE;
         const float *bbase = bias + py * C::NB + px;
-        float acc[kHeadDim];
+        float acc[D];
 #pragma unroll
-        for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
+        for (int d = 0; d < D; ++d) acc[d] = 0.f;
         float m = -INFINITY, l = 0.f;
 #pragma unroll 1
         for (int a = 0; a < K; ++a) {
@@ -78,8 +63,8 @@ __global__ __launch_bounds__(kTileX *TY) void fused_fwd_kernel(const T *__restri
             float rowmax = -INFINITY;
 #pragma unroll
             for (int c = 0; c < K; ++c) {
-                Vec32<T> kv;
-                lds_load_vec32(kv, khalo + hoff + (a * C::HALO_W + c) * Traits<T>::kKeyStride);
+                VecN<T, D> kv;
+                lds_load_vec32(kv, khalo + hoff + (a * C::HALO_W + c) * STRIDE);
                 s[c] = __builtin_fmaf(scale, dot32(qv, kv), bbase[a * C::NB + c]);
                 rowmax = fmaxf(rowmax, s[c]);
             }
@@ -87,34 +72,34 @@ __global__ __launch_bounds__(kTileX *TY) void fused_fwd_kernel(const T *__restri
             const float corr = __expf(m - mnew);   // exp(-inf) = 0 on the first row
             l *= corr;
 #pragma unroll
-            for (int d = 0; d < kHeadDim; ++d) acc[d] *= corr;
+            for (int d = 0; d < D; ++d) acc[d] *= corr;
 #pragma unroll
             for (int c = 0; c < K; ++c) {
                 const float e = __expf(s[c] - mnew);
                 l += e;
-                Vec32<T> vv;
-                lds_load_vec32(vv, vhalo + hoff + (a * C::HALO_W + c) * Traits<T>::kKeyStride);
+                VecN<T, D> vv;
+                lds_load_vec32(vv, vhalo + hoff + (a * C::HALO_W + c) * STRIDE);
                 axpy32(acc, e, vv);
             }
             m = mnew;
         }
         const float inv = 1.0f / l;
 #pragma unroll
-        for (int d = 0; d < kHeadDim; ++d) acc[d] *= inv;
-        store_vec32<T>(reinterpret_cast<char *>(out) + (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes, acc);
+        for (int d = 0; d < D; ++d) acc[d] *= inv;
+        store_vec32<T>(reinterpret_cast<char *>(out) + (plane_q + (size_t)qy * W + qx) * KBYTES, acc);
         if (lse) lse[plane_q + (size_t)qy * W + qx] = m + __logf(l);
     }
 }
 
-template <typename T, int K>
+template <typename T, int K, int D>
 static hipError_t launch_fused_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
                                  float scale, void *out, float *lse, hipStream_t s) {
-    constexpr int TY = fused_tile_rows<T, K>();
-    using C = FusedCfg<T, K, TY>;
+    if constexpr (!valu_fits<T, K, D>()) return hipErrorInvalidValue; else {
+    constexpr int TY = tile_rows<FusedCfg, T, K, D>();
+    using C = FusedCfg<T, K, TY, D>;
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + TY - 1) / TY;
     const int ntiles = tiles_x * tiles_y * p.planes();
-    auto kern = fused_fwd_kernel<T, K, TY>;
-    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
+    auto kern = fused_fwd_kernel<T, K, TY, D>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -127,12 +112,13 @@ static hipError_t launch_fused_t(const Problem &p, const void *q, const void *k,
                        static_cast<const T *>(rpb), scale, static_cast<T *>(out), lse, p.H, p.W, p.heads, tiles_x,
                        tiles_y, ntiles);
     return hipGetLastError();
+    }
 }
 
 hipError_t launch_fused_fwd(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
                             void *out, float *lse, hipStream_t s) {
-    if (p.dtype != NA2D_F32 && !force_valu()) return launch_fused_mfma(p, q, k, v, rpb, scale, out, lse, s);
-    NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, return (launch_fused_t<T, K>(p, q, k, v, rpb, scale, out, lse, s))));
+    if (p.D == kHeadDim && p.dtype != NA2D_F32 && !force_valu()) return launch_fused_mfma(p, q, k, v, rpb, scale, out, lse, s);
+    NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, NA2D_DISPATCH_D(p.D, return (launch_fused_t<T, K, D>(p, q, k, v, rpb, scale, out, lse, s)))));
     return hipErrorInvalidValue;
 }
 

@@ -628,7 +628,7 @@ hipError_t launch_fbwd_kv(const Problem &p, const void *q, const void *k, const 
 // close to both borders) does not fit, and such maps take the unfused steps instead.
 bool fused_bwd_supported(const Problem &p) {
     const int R = p.K / 2;
-    return p.dtype != NA2D_F32 && p.K <= 7 && !force_valu() && kv_rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
+    return p.D == kHeadDim && p.dtype != NA2D_F32 && p.K <= 7 && !force_valu() && kv_rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
 }
 
 AvRpbSplit fused_bwd_split(const Problem &p) {

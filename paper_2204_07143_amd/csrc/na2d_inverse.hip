@@ -9,31 +9,16 @@
 // key tile; the x vectors of the tile's query rectangle are staged once in LDS.
 #include "na2d_kernels.hpp"
 #include "na2d_tile.hpp"
+#include "na2d_valu_cfg.hpp"
 
 namespace na2d {
 
-template <typename T, int K, int TY>
-struct InvCfg {
-    // Query rectangle of a tile: at most tile + (K-1) + (K-1)/2 on an axis unless the tile
-    // touches both borders of a short axis; the rare remainder is read from global memory.
-    static constexpr int RECT_H = TY + K - 1 + K / 2, RECT_W = kTileX + K - 1 + K / 2;
-    static constexpr int KK = K * K;
-    static constexpr int kThreads = kTileX * TY;
-    static constexpr int kLdsBytes = RECT_H * RECT_W * Traits<T>::kKeyStride;
-};
-
-template <typename T, int K>
-constexpr int inv_tile_rows() {
-    if (InvCfg<T, K, 16>::kLdsBytes <= 80 * 1024) return 16;
-    if (InvCfg<T, K, 8>::kLdsBytes <= 80 * 1024) return 8;
-    return 4;
-}
-
-template <typename T, int K, int TY>
+template <typename T, int K, int TY, int D>
 __global__ __launch_bounds__(kTileX *TY) void inverse_kernel(const T *__restrict__ w, const T *__restrict__ x,
                                                               float scale, T *__restrict__ out, int H, int W,
                                                               int tiles_x, int tiles_y, int ntiles) {
-    using C = InvCfg<T, K, TY>;
+    using C = InvCfg<T, K, TY, D>;
+    constexpr int KBYTES = VecTraits<T, D>::kKeyBytes, STRIDE = VecTraits<T, D>::kKeyStride;
     extern __shared__ __align__(16) char lds[];
 
     const int t = xcd_contiguous_block(blockIdx.x, gridDim.x);
@@ -43,9 +28,9 @@ __global__ __launch_bounds__(kTileX *TY) void inverse_kernel(const T *__restrict
     const int tid = threadIdx.x;
     const int ry0 = inv_first(ty0, H, K), rx0 = inv_first(tx0, W, K);
     const size_t plane_q = (size_t)tc.plane * H * W;
-    const char *xplane = reinterpret_cast<const char *>(x) + plane_q * Traits<T>::kKeyBytes;
+    const char *xplane = reinterpret_cast<const char *>(x) + plane_q * KBYTES;
 
-    load_halo<T, C::RECT_H, C::RECT_W, C::kThreads>(xplane, H, W, ry0, rx0, lds, tid);
+    load_halo<T, C::RECT_H, C::RECT_W, C::kThreads, false, D>(xplane, H, W, ry0, rx0, lds, tid);
     __syncthreads();
 
     const int lx = tid % kTileX, ly = tid / kTileX;
@@ -53,39 +38,39 @@ __global__ __launch_bounds__(kTileX *TY) void inverse_kernel(const T *__restrict
     if (jy < H && jx < W) {
         const int fy = inv_first(jy, H, K), ey = inv_last(jy, H, K);
         const int fx = inv_first(jx, W, K), ex = inv_last(jx, W, K);
-        float acc[kHeadDim];
+        float acc[D];
 #pragma unroll
-        for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
+        for (int d = 0; d < D; ++d) acc[d] = 0.f;
         for (int iy = fy; iy <= ey; ++iy) {
             const int a = jy - win_start(iy, H, K);
             const T *wrow = w + (plane_q + (size_t)iy * W) * C::KK + a * K;
             for (int ix = fx; ix <= ex; ++ix) {
                 const int c = jx - win_start(ix, W, K);
                 const float wt = to_f32(wrow[(size_t)ix * C::KK + c]);
-                Vec32<T> xv;
+                VecN<T, D> xv;
                 const int ry = iy - ry0, rx = ix - rx0;
                 if (ry < C::RECT_H && rx < C::RECT_W)
-                    lds_load_vec32(xv, lds + (ry * C::RECT_W + rx) * Traits<T>::kKeyStride);
+                    lds_load_vec32(xv, lds + (ry * C::RECT_W + rx) * STRIDE);
                 else
-                    load_vec32(xv, xplane + ((size_t)iy * W + ix) * Traits<T>::kKeyBytes);
+                    load_vec32(xv, xplane + ((size_t)iy * W + ix) * KBYTES);
                 axpy32(acc, wt, xv);
             }
         }
 #pragma unroll
-        for (int d = 0; d < kHeadDim; ++d) acc[d] *= scale;
-        store_vec32<T>(reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * Traits<T>::kKeyBytes, acc);
+        for (int d = 0; d < D; ++d) acc[d] *= scale;
+        store_vec32<T>(reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * KBYTES, acc);
     }
 }
 
-template <typename T, int K>
+template <typename T, int K, int D>
 static hipError_t launch_inverse_t(const Problem &p, const void *w, const void *x, float scale, void *out,
                                    hipStream_t s) {
-    constexpr int TY = inv_tile_rows<T, K>();
-    using C = InvCfg<T, K, TY>;
+    if constexpr (!valu_fits<T, K, D>()) return hipErrorInvalidValue; else {
+    constexpr int TY = tile_rows<InvCfg, T, K, D>();
+    using C = InvCfg<T, K, TY, D>;
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + TY - 1) / TY;
     const int ntiles = tiles_x * tiles_y * p.planes();
-    auto kern = inverse_kernel<T, K, TY>;
-    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
+    auto kern = inverse_kernel<T, K, TY, D>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -97,12 +82,13 @@ static hipError_t launch_inverse_t(const Problem &p, const void *w, const void *
                        static_cast<const T *>(w), static_cast<const T *>(x), scale, static_cast<T *>(out), p.H, p.W,
                        tiles_x, tiles_y, ntiles);
     return hipGetLastError();
+    }
 }
 
 hipError_t launch_inverse(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s) {
-    if (inverse_ring_supported(p) && !force_valu()) return launch_inverse_ring(p, w, x, scale, out, s);
-    if (inverse_mfma_supported(p) && !force_valu()) return launch_inverse_mfma(p, w, x, scale, out, s);
-    NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, return (launch_inverse_t<T, K>(p, w, x, scale, out, s))));
+    if (p.D == kHeadDim && inverse_ring_supported(p) && !force_valu()) return launch_inverse_ring(p, w, x, scale, out, s);
+    if (p.D == kHeadDim && inverse_mfma_supported(p) && !force_valu()) return launch_inverse_mfma(p, w, x, scale, out, s);
+    NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, NA2D_DISPATCH_D(p.D, return (launch_inverse_t<T, K, D>(p, w, x, scale, out, s)))));
     return hipErrorInvalidValue;
 }
 

@@ -270,7 +270,7 @@ static hipError_t launch_inverse_ring_t(const Problem &p, const void *w, const v
 // The ring holds 8 + K-1 rows per tile: every tile's query rectangle must fit that (and 16 + K-1 columns), which
 // excludes maps with a tile next to the far border whose clamped queries reach further (the tile kernel takes those).
 bool inverse_ring_supported(const Problem &p) {
-    if (p.dtype == NA2D_F32 || p.K > 7) return false;
+    if (p.D != kHeadDim || p.dtype == NA2D_F32 || p.K > 7) return false;
     const int K = p.K, TY = 8;
     // a 4 x 4 key patch seen from both clamped ends of an axis at once (axes of at most 2K + 2 positions) has
     // more than K + R + 3 query rows or columns: one MFMA block per row no longer covers it

@@ -11,6 +11,7 @@ namespace na2d {
 
 struct Problem {
     int B, heads, H, W, K, dtype;
+    int D = 32;
     int planes() const { return B * heads; }
     size_t queries() const { return (size_t)B * heads * H * W; }
     int elem_bytes() const { return dtype == NA2D_F32 ? 4 : 2; }
@@ -75,6 +76,15 @@ hipError_t launch_indices(const Problem &p, int32_t *key_index, int32_t *rpb_ind
         case 11: { constexpr int K = 11; __VA_ARGS__; } break;       \
         case 13: { constexpr int K = 13; __VA_ARGS__; } break;       \
         default: return hipErrorInvalidValue;                        \
+    }
+// Head dims the plain-ALU kernels are built for (the matrix-core kernels serve D = 32 only).
+#define NA2D_DISPATCH_D(dval, ...)                                    \
+    switch (dval) {                                                   \
+        case 16: { constexpr int D = 16; __VA_ARGS__; } break;        \
+        case 32: { constexpr int D = 32; __VA_ARGS__; } break;        \
+        case 64: { constexpr int D = 64; __VA_ARGS__; } break;        \
+        case 128: { constexpr int D = 128; __VA_ARGS__; } break;      \
+        default: return hipErrorInvalidValue;                         \
     }
 #define NA2D_DISPATCH_T(dtval, ...)                                                  \
     switch (dtval) {                                                                 \

@@ -12,35 +12,17 @@
 
 #include "na2d_kernels.hpp"
 #include "na2d_tile.hpp"
+#include "na2d_valu_cfg.hpp"
 
 namespace na2d {
 
-template <typename T, int K, int TY>
-struct QkCfg {
-    static constexpr int HALO_H = TY + K - 1, HALO_W = kTileX + K - 1;
-    static constexpr int NB = 2 * K - 1;
-    static constexpr int KK = K * K;
-    static constexpr int kThreads = kTileX * TY;
-    static constexpr int kHaloBytes = HALO_H * HALO_W * Traits<T>::kKeyStride;
-    static constexpr int kBiasBytes = ((NB * NB * 4) + 15) & ~15;
-    static constexpr int kRowRegion = mirror_bytes(kTileX * KK * (int)sizeof(T));
-    static constexpr int kLdsBytes = kHaloBytes + kBiasBytes + TY * kRowRegion;
-};
-
-// Largest tile height whose LDS footprint lets two workgroups share a CU (160 KB LDS).
-template <typename T, int K>
-constexpr int qk_tile_rows() {
-    if (QkCfg<T, K, 16>::kLdsBytes <= 80 * 1024) return 16;
-    if (QkCfg<T, K, 8>::kLdsBytes <= 80 * 1024) return 8;
-    return 4;
-}
-
-template <typename T, int K, int TY>
+template <typename T, int K, int TY, int D>
 __global__ __launch_bounds__(kTileX *TY) void qk_kernel(const T *__restrict__ x, const T *__restrict__ y,
                                                          const T *__restrict__ rpb, float scale,
                                                          T *__restrict__ logits, int H, int W, int heads,
                                                          int tiles_x, int tiles_y, int ntiles) {
-    using C = QkCfg<T, K, TY>;
+    using C = QkCfg<T, K, TY, D>;
+    constexpr int KBYTES = VecTraits<T, D>::kKeyBytes, STRIDE = VecTraits<T, D>::kKeyStride;
     extern __shared__ __align__(16) char lds[];
     char *halo = lds;
     float *bias = reinterpret_cast<float *>(lds + C::kHaloBytes);
@@ -54,7 +36,7 @@ __global__ __launch_bounds__(kTileX *TY) void qk_kernel(const T *__restrict__ x,
     const int hy0 = win_start(ty0, H, K), hx0 = win_start(tx0, W, K);
     const size_t plane_q = (size_t)tc.plane * H * W;
 
-    load_halo<T, C::HALO_H, C::HALO_W, C::kThreads>(reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes,
+    load_halo<T, C::HALO_H, C::HALO_W, C::kThreads, false, D>(reinterpret_cast<const char *>(y) + plane_q * KBYTES,
                                                     H, W, hy0, hx0, halo, tid);
     {
         const int head = tc.plane % heads;
@@ -68,19 +50,19 @@ __global__ __launch_bounds__(kTileX *TY) void qk_kernel(const T *__restrict__ x,
     // Global byte offset of this tile row's run of logits; its low 4 bits are mirrored in LDS.
     const size_t g0 = (plane_q + (size_t)qy * W + tx0) * C::KK * sizeof(T);
     if (qy < H && qx < W) {
-        Vec32<T> qv;
-        load_vec32(qv, reinterpret_cast<const char *>(x) + (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes);
+        VecN<T, D> qv;
+        load_vec32(qv, reinterpret_cast<const char *>(x) + (plane_q + (size_t)qy * W + qx) * KBYTES);
         const int sy = win_start(qy, H, K), sx = win_start(qx, W, K);
         const int py = sy - qy + (K - 1), px = sx - qx + (K - 1);
-        const char *kbase = halo + ((sy - hy0) * C::HALO_W + (sx - hx0)) * Traits<T>::kKeyStride;
+        const char *kbase = halo + ((sy - hy0) * C::HALO_W + (sx - hx0)) * STRIDE;
         const float *bbase = bias + py * C::NB + px;
         T *orow = reinterpret_cast<T *>(rows + ly * C::kRowRegion + (int)(g0 & 15)) + lx * C::KK;
 #pragma unroll 1
         for (int a = 0; a < K; ++a) {
 #pragma unroll
             for (int c = 0; c < K; ++c) {
-                Vec32<T> kv;
-                lds_load_vec32(kv, kbase + (a * C::HALO_W + c) * Traits<T>::kKeyStride);
+                VecN<T, D> kv;
+                lds_load_vec32(kv, kbase + (a * C::HALO_W + c) * STRIDE);
                 const float dot = dot32(qv, kv);
                 orow[a * K + c] = from_f32<T>(__builtin_fmaf(scale, dot, bbase[a * C::NB + c]));
             }
@@ -100,15 +82,15 @@ __global__ __launch_bounds__(kTileX *TY) void qk_kernel(const T *__restrict__ x,
     }
 }
 
-template <typename T, int K>
+template <typename T, int K, int D>
 static hipError_t launch_qk_t(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
                               void *logits, hipStream_t s) {
-    constexpr int TY = qk_tile_rows<T, K>();
-    using C = QkCfg<T, K, TY>;
+    if constexpr (!valu_fits<T, K, D>()) return hipErrorInvalidValue; else {
+    constexpr int TY = tile_rows<QkCfg, T, K, D>();
+    using C = QkCfg<T, K, TY, D>;
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + TY - 1) / TY;
     const int ntiles = tiles_x * tiles_y * p.planes();
-    auto kern = qk_kernel<T, K, TY>;
-    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
+    auto kern = qk_kernel<T, K, TY, D>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -120,6 +102,15 @@ static hipError_t launch_qk_t(const Problem &p, const void *x, const void *y, co
                        static_cast<const T *>(x), static_cast<const T *>(y), static_cast<const T *>(rpb), scale,
                        static_cast<T *>(logits), p.H, p.W, p.heads, tiles_x, tiles_y, ntiles);
     return hipGetLastError();
+    }
+}
+
+bool head_dim_supported(int dtype, int K, int D) {
+    auto probe = [&]() -> hipError_t {
+        NA2D_DISPATCH_T(dtype, NA2D_DISPATCH_K(K, NA2D_DISPATCH_D(D, return (valu_fits<T, K, D>() ? hipSuccess : hipErrorInvalidValue))));
+        return hipErrorInvalidValue;
+    };
+    return probe() == hipSuccess;
 }
 
 bool force_valu() {
@@ -132,8 +123,8 @@ bool force_valu() {
 
 hipError_t launch_qk(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
                      hipStream_t s) {
-    if (p.dtype != NA2D_F32 && !force_valu()) return launch_qk_mfma(p, x, y, rpb, scale, logits, s);
-    NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, return (launch_qk_t<T, K>(p, x, y, rpb, scale, logits, s))));
+    if (p.D == kHeadDim && p.dtype != NA2D_F32 && !force_valu()) return launch_qk_mfma(p, x, y, rpb, scale, logits, s);
+    NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, NA2D_DISPATCH_D(p.D, return (launch_qk_t<T, K, D>(p, x, y, rpb, scale, logits, s)))));
     return hipErrorInvalidValue;
 }
 

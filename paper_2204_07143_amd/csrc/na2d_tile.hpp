@@ -41,10 +41,11 @@ __device__ __forceinline__ TileCoord decode_tile(int t, int tiles_x, int tiles_y
 // coordinates): positions outside the map are zero-filled when ZERO is set and skipped
 // otherwise (no window ever reads them).  Loads are issued in batches of up to 4 per thread
 // before the matching LDS stores, so a thread keeps its share of the halo in flight at once.
-template <typename T, int ROWS, int COLS, int NTHREADS, bool ZERO = false>
+template <typename T, int ROWS, int COLS, int NTHREADS, bool ZERO = false, int D = kHeadDim>
 __device__ __forceinline__ void load_halo(const char *plane_base, int H, int W, int oy, int ox, char *lds, int tid) {
-    constexpr int CPK = Traits<T>::kKeyBytes / 16;
-    constexpr int STRIDE = Traits<T>::kKeyStride;
+    constexpr int KBYTES = VecTraits<T, D>::kKeyBytes;
+    constexpr int CPK = KBYTES / 16;
+    constexpr int STRIDE = VecTraits<T, D>::kKeyStride;
     constexpr int TOTAL = ROWS * COLS * CPK;
     constexpr int NITER = (TOTAL + NTHREADS - 1) / NTHREADS;
     constexpr int BATCH = 4;
@@ -68,7 +69,7 @@ __device__ __forceinline__ void load_halo(const char *plane_base, int H, int W, 
                 const bool in_tile = i < TOTAL;
                 const bool in_map = y >= 0 && y < H && x >= 0 && x < W;
                 if (in_tile && in_map)
-                    v[u] = *reinterpret_cast<const u32x4 *>(plane_base + ((size_t)y * W + x) * Traits<T>::kKeyBytes + c * 16);
+                    v[u] = *reinterpret_cast<const u32x4 *>(plane_base + ((size_t)y * W + x) * KBYTES + c * 16);
                 if (in_tile && (in_map || ZERO)) dst[u] = (ry * COLS + rx) * STRIDE + c * 16;
             }
         }
@@ -127,8 +128,8 @@ struct HaloPrefetch {
     }
 };
 
-template <typename T>
-__device__ __forceinline__ void lds_load_vec32(Vec32<T> &v, const char *lds_key) {
+template <typename T, int D>
+__device__ __forceinline__ void lds_load_vec32(VecN<T, D> &v, const char *lds_key) {
     load_vec32(v, lds_key);
 }
 

@@ -53,6 +53,10 @@ CONFIGS = {
     "nat_tiny_l4_bf16": Problem(128, 16, 7, 7, 32, 7, "bf16"),
     "detection_like": Problem(2, 2, 200, 334, 32, 7, "f16"),
     "segmentation_like": Problem(8, 2, 128, 128, 32, 7, "f16"),
+    # other head dims (NAT itself always uses 32): the first-stage map with the same 64 channels as one head of
+    # 64, and as four heads of 16
+    "stage1_head_dim_64": Problem(64, 1, 56, 56, 64, 7, "f16"),
+    "stage1_head_dim_16": Problem(64, 4, 56, 56, 16, 7, "f16"),
 }
 
 

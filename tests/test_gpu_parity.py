@@ -208,6 +208,8 @@ FULL = [
     ("nat_tiny_l4_bf16", False),    # 7x7, k = 7: full self attention
     ("detection_like", True),       # 200 x 334: ragged tiles on both axes, many tiles per column
     ("segmentation_like", True),
+    ("stage1_head_dim_64", True),   # head dims other than 32 run the plain-ALU kernels
+    ("stage1_head_dim_16", True),
 ]
 
 
@@ -232,6 +234,24 @@ def test_full_size_config_sampled_planes(oracle, name, backward):
 def test_config5_kernel_size_sweep_fwd_bwd(oracle, k):
     p = synth.Problem(64, 2, 56, 56, 32, k, "f16")
     run_all(oracle, p, seed=5000 + k, planes=[(0, 0), (63, 1)], backward=True)
+
+
+# ---- head dims other than 32: every (dtype, D, k) class the library accepts, and the ones it refuses ------------
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("D,k", [(16, 3), (16, 7), (16, 13), (64, 5), (64, 9), (64, 13), (128, 3), (128, 9)])
+def test_generic_head_dims(oracle, dtype, D, k):
+    p = synth.Problem(2, 2, 19, 22, D, k, dtype)
+    prob = na.problem(p.B, p.heads, p.H, p.W, D, k, synth.TORCH_DTYPES[dtype])
+    if na.na2d_validate_problem(prob) != 0:
+        # the fp32 tiles of the largest head dims do not fit the LDS for larger windows: refused, never a wrong result
+        assert dtype == "f32" and (D, k) in ((64, 13), (128, 9))
+        q = torch.zeros((p.B, p.heads, p.H, p.W, D), dtype=torch.float32, device="cuda")
+        with pytest.raises(na.Na2dError) as e:
+            na.na2d_fused_fwd(q, q.clone(), q.clone(), None, 1.0, k, torch.empty_like(q))
+        assert e.value.status == -5
+        return
+    run_all(oracle, p, seed=9000 + D + k)
 
 
 def test_gather_gradients_are_bitwise_reproducible():

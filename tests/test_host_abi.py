@@ -45,7 +45,8 @@ def P(B=1, heads=1, H=14, W=14, D=32, k=3, dtype=0):
     (P(dtype=3), -2),
     (P(k=4), -3), (P(k=1), -3), (P(k=15, H=20, W=20), -3),
     (P(k=7, H=6), -4), (P(k=7, W=5), -4),
-    (P(D=64), -5),
+    (P(D=64), 0), (P(D=16, k=13, H=20, W=20), 0), (P(D=128, k=9, H=20, W=20, dtype=1), 0),
+    (P(D=48), -5), (P(D=8), -5), (P(D=128, k=5, H=20, W=20, dtype=0), -5), (P(D=64, k=11, H=20, W=20, dtype=0), -5),
     (P(B=0), -6), (P(H=-1), -6),
     (P(B=4096, heads=16, H=512, W=512, k=3), -6),
 ])
@@ -66,7 +67,7 @@ def test_entry_points_reject_bad_arguments_before_any_hip_call():
     assert lib.na2d_qk_rpb(ctypes.byref(good), ok, off, None, 1.0, ctypes.c_void_p(a16 + 16), None) == -7
     assert lib.na2d_qk_rpb(ctypes.byref(good), ok, ctypes.c_void_p(a16 + 16), None, 1.0, ok, None) == -10
     assert lib.na2d_av(ctypes.byref(P(k=4)), ok, ok, ok, None) == -3
-    assert lib.na2d_softmax(ctypes.byref(P(D=16)), ok, ok, None) == -5
+    assert lib.na2d_softmax(ctypes.byref(P(D=24)), ok, ok, None) == -5
     assert lib.na2d_fused_fwd(ctypes.byref(P(k=7, H=5)), ok, ok, ok, None, 1.0, ok, None, None) == -4
     assert lib.na2d_qk_bwd_rpb(ctypes.byref(good), ok, ctypes.c_void_p(a16 + 16), None, 0, None) == -8
     assert lib.na2d_qk_bwd_rpb(ctypes.byref(good), ok, ctypes.c_void_p(a16 + 16), ctypes.c_void_p(a16 + 32), 8, None) == -8
