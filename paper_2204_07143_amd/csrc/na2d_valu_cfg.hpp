@@ -52,12 +52,23 @@ struct FusedCfg {
     static constexpr int kLdsBytes = 2 * kHaloBytes + kBiasBytes;
 };
 
-// Largest tile height whose LDS footprint lets two workgroups share a compute unit, else the smallest.
+// Tile height: the one that keeps the most waves resident on a compute unit (workgroups that fit the LDS x waves
+// per workgroup, at most 32 waves), the taller tile on a tie (its halo is shared by more queries; measured faster).
 template <template <typename, int, int, int> class Cfg, typename T, int K, int D>
 constexpr int tile_rows() {
-    if (Cfg<T, K, 16, D>::kLdsBytes <= kLdsLimit / 2) return 16;
-    if (Cfg<T, K, 8, D>::kLdsBytes <= kLdsLimit / 2) return 8;
-    return 4;
+    int best = 4, best_waves = 0;
+    const int lds[3] = {Cfg<T, K, 4, D>::kLdsBytes, Cfg<T, K, 8, D>::kLdsBytes, Cfg<T, K, 16, D>::kLdsBytes};
+    for (int i = 0; i < 3; ++i) {
+        const int ty = 4 << i, waves_per_wg = ty * kTileX / kWave;
+        int wgs = lds[i] > 0 ? kLdsLimit / lds[i] : 0;
+        int waves = wgs * waves_per_wg;
+        waves = waves > 32 ? 32 : waves;
+        if (waves >= best_waves && waves > 0) {
+            best = ty;
+            best_waves = waves;
+        }
+    }
+    return best;
 }
 template <template <typename, int, int, int> class Cfg, typename T, int K, int D>
 constexpr bool tile_fits() {
