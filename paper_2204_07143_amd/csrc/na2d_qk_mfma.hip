@@ -283,14 +283,15 @@ struct QkSmallCfg {
 };
 
 
-// One row run of the tile, LDS -> global: 16-byte stores for the chunks that are aligned in global
-// memory (their LDS source is then aligned to 2 bytes only), single elements at the two ends.
+// One row run of the tile, LDS -> global.  The run starts on a 16-byte boundary in LDS but anywhere (a multiple
+// of the element size) in global memory: it leaves as 16-byte stores to addresses that are aligned to the
+// element only, which the chip's global memory path takes as they are (the compiler itself emits them for such
+// pointers), and whose 64 lanes still cover one contiguous kilobyte.  Aligning the stores instead would put the
+// misalignment on the LDS side, where a 16-byte read at a 2-byte phase costs eight reads.  The elements past
+// the last whole chunk (ragged tiles only) go one by one.
 template <typename T>
 __device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, int lds_row, int lane) {
-    const int mis = (int)(g0 & 15);
-    int head = (16 - mis) & 15;
-    head = head < nbytes ? head : nbytes;
-    const int nbody = (nbytes - head) >> 4;
+    const int nbody = nbytes >> 4;
     char *ga = gbase + g0;
     struct __attribute__((packed, aligned(2))) Chunk {
         u32x4 v;
@@ -299,17 +300,15 @@ __device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, in
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const int c = lane + it * kWave;
-        if (c < nbody) v[it] = lds_ptr<Chunk>(lds_row + head + 16 * c)->v;
+        if (c < nbody) v[it] = *lds_ptr<u32x4>(lds_row + 16 * c);
     }
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const int c = lane + it * kWave;
-        if (c < nbody) *reinterpret_cast<u32x4 *>(ga + head + 16 * c) = v[it];
+        if (c < nbody) reinterpret_cast<Chunk *>(ga + 16 * c)->v = v[it];
     }
-    const int hb = lane * (int)sizeof(T);
-    if (hb < head) *reinterpret_cast<T *>(ga + hb) = *lds_ptr<T>(lds_row + hb);
-    const int tb = head + 16 * nbody + (lane - 16) * (int)sizeof(T);
-    if (lane >= 16 && tb < nbytes) *reinterpret_cast<T *>(ga + tb) = *lds_ptr<T>(lds_row + tb);
+    const int tb = 16 * nbody + lane * (int)sizeof(T);
+    if (tb < nbytes) *reinterpret_cast<T *>(ga + tb) = *lds_ptr<T>(lds_row + tb);
 }
 
 template <typename T, int K>

@@ -162,7 +162,7 @@ __global__ __launch_bounds__(256) void rpb_partial_kernel(const T *__restrict__ 
 // d_rpb[h, cell] = sum over (batch, group) of partial[(b * heads + h) * groups + group][cell].
 // One workgroup of 16 waves per head and block of 64 cells (a lane is a cell, so a wave reads 256
 // contiguous bytes of a partial): wave w adds the partials whose running index is w mod 16, in
-// index order, eight independent loads at a time; the 16 sub-sums are then added in wave order.
+// index order, sixteen independent loads at a time; the 16 sub-sums are then added in wave order.
 __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const float *__restrict__ partial,
                                                                            float *__restrict__ d_rpb, int B, int heads,
                                                                            int groups, int cells) {
@@ -174,22 +174,17 @@ __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const 
     const int n = B * groups;
     float acc = 0.f;
     if (cell < cells) {
-        constexpr int U = 8;
-        int i = wave;
-        for (; i + (U - 1) * kRpbFinalWaves < n; i += U * kRpbFinalWaves) {
+        constexpr int U = 16;   // loads in flight per lane; past the end they are skipped (adding 0 changes nothing)
+        for (int i = wave; i < n; i += U * kRpbFinalWaves) {
             float v[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int iu = i + u * kRpbFinalWaves;
                 const int b = iu / groups, g = iu - b * groups;
-                v[u] = partial[((size_t)(b * heads + h) * groups + g) * cells + cell];
+                v[u] = iu < n ? partial[((size_t)(b * heads + h) * groups + g) * cells + cell] : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) acc += v[u];
-        }
-        for (; i < n; i += kRpbFinalWaves) {
-            const int b = i / groups, g = i - b * groups;
-            acc += partial[((size_t)(b * heads + h) * groups + g) * cells + cell];
         }
     }
     sub[wave][lane] = acc;
@@ -204,7 +199,7 @@ __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const 
 // d_rpb[h, cell] from the partials the grad-q kernel leaves: workgroup wg = (split * heads + h) * npos + pos
 // holds partial[wg][cell].  Same shape as rpb_final_kernel: one workgroup of 16 waves per head and block
 // of 64 cells, wave w adds the partials whose running index (split * npos + pos) is w mod 16, in index
-// order, eight loads at a time; the 16 sub-sums are added in wave order.
+// order, sixteen loads at a time; the 16 sub-sums are added in wave order.
 __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_av_kernel(const float *__restrict__ partial,
                                                                               float *__restrict__ d_rpb, int heads, int npos,
                                                                               int splits, int cells) {
@@ -216,20 +211,18 @@ __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_av_kernel(con
     const int n = npos * splits;
     float acc = 0.f;
     if (cell < cells) {
-        constexpr int U = 8;
+        constexpr int U = 16;   // loads in flight per lane; past the end they are skipped (adding 0 changes nothing)
         auto at = [&](int i) {
             const int sp = i / npos, ps = i - sp * npos;
             return partial[((size_t)(sp * heads + h) * npos + ps) * cells + cell];
         };
-        int i = wave;
-        for (; i + (U - 1) * kRpbFinalWaves < n; i += U * kRpbFinalWaves) {
+        for (int i = wave; i < n; i += U * kRpbFinalWaves) {
             float v[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = at(i + u * kRpbFinalWaves);
+            for (int u = 0; u < U; ++u) v[u] = i + u * kRpbFinalWaves < n ? at(i + u * kRpbFinalWaves) : 0.f;
 #pragma unroll
             for (int u = 0; u < U; ++u) acc += v[u];
         }
-        for (; i < n; i += kRpbFinalWaves) acc += at(i);
     }
     sub[wave][lane] = acc;
     __syncthreads();

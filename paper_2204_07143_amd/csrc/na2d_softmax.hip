@@ -23,14 +23,32 @@ template <typename T, int K> struct SoftmaxCfg {
     static constexpr int kRegion = mirror_bytes(kRows * KK * (int)sizeof(T));
 };
 
+// Butterfly over the G lanes of a row group (G = 4, 8 or 16, groups aligned to G lanes), every lane ending with
+// the group's result.  The exchanges are data-parallel-primitive moves inside the vector ALU (lane ^ 1 and
+// lane ^ 2 as quad permutations, then the mirror of the half row and of the row, which bring the other half's
+// partial result once both halves are uniform): no trip through the LDS pipe, which the row data already loads.
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v) {
+    const int r = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true);
+    return __builtin_bit_cast(float, r);
+}
+constexpr int kDppXor1 = 0xB1;          // quad_perm [1, 0, 3, 2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm [2, 3, 0, 1]
+constexpr int kDppHalfMirror = 0x141;   // lane i <-> 7 - i inside each group of 8
+constexpr int kDppMirror = 0x140;       // lane i <-> 15 - i inside each row of 16
 template <int G> __device__ __forceinline__ float group_max(float v) {
-#pragma unroll
-    for (int o = G / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    static_assert(G == 4 || G == 8 || G == 16, "row groups");
+    v = fmaxf(v, dpp_move<kDppXor1>(v));
+    v = fmaxf(v, dpp_move<kDppXor2>(v));
+    if constexpr (G >= 8) v = fmaxf(v, dpp_move<kDppHalfMirror>(v));
+    if constexpr (G >= 16) v = fmaxf(v, dpp_move<kDppMirror>(v));
     return v;
 }
 template <int G> __device__ __forceinline__ float group_sum(float v) {
-#pragma unroll
-    for (int o = G / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    static_assert(G == 4 || G == 8 || G == 16, "row groups");
+    v += dpp_move<kDppXor1>(v);
+    v += dpp_move<kDppXor2>(v);
+    if constexpr (G >= 8) v += dpp_move<kDppHalfMirror>(v);
+    if constexpr (G >= 16) v += dpp_move<kDppMirror>(v);
     return v;
 }
 
