@@ -262,7 +262,10 @@ struct AvSmallCfg {
 template <typename T, int K, bool RPB>
 __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restrict__ w, const T *__restrict__ y, float scale,
                                                                T *__restrict__ out, float *__restrict__ rpb_partial, int H,
-                                                               int W, int heads, int nb, int tiles_y, int units, int splits) {
+                                                               int W, int heads, int nb, int tiles_y, int units, int splits,
+                                                               int pitch) {
+    // `pitch`: bytes between consecutive positions of y and out.  The kernel works on 32 channels; a longer
+    // head vector is served one 32-channel slice per launch (y and out then point at the slice).
     using C = AvSmallCfg<T, K>;
     using P = Patch<K>;
     static_assert(C::kThreads == 512, "launch bounds");
@@ -301,8 +304,8 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
     typename C::Halo halo;
     halo.init(wave, lane);
     int hoff[C::Halo::PER_WAVE];
-    halo.offsets(H, W, hoy, hox, hoff);
-    const size_t plane_y = (size_t)H * W * Traits<T>::kKeyBytes;   // bytes per plane of y / out
+    halo.offsets(H, W, hoy, hox, hoff, pitch);
+    const size_t plane_y = (size_t)H * W * pitch;                  // bytes per plane of y / out
     const size_t plane_w = (size_t)H * W * C::KK * SZ;             // ... of the weights
     const size_t w_bytes = plane_w * heads * nb;
     const int wrow = ty0 + wave;                                    // the row this wave loads
@@ -446,7 +449,7 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
             }
         }
         if (q_ok) {
-            char *dst = reinterpret_cast<char *>(out) + ((size_t)b * heads + head) * plane_y + qlin * Traits<T>::kKeyBytes + g * 16;
+            char *dst = reinterpret_cast<char *>(out) + ((size_t)b * heads + head) * plane_y + (size_t)qlin * pitch + g * 16;
             uint32_t ov[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -508,10 +511,15 @@ static hipError_t launch_av_mfma_small_t(const Problem &p, const void *w, const 
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
-                       static_cast<const T *>(w), static_cast<const T *>(y), scale, static_cast<T *>(out), rpb_partial, p.H,
-                       p.W, p.heads, p.B, tiles_y, us.units, us.splits);
-    return hipGetLastError();
+    // one launch per 32-channel slice of the head vector (the weights are read again by each)
+    for (int sl = 0; sl < p.D / kHeadDim; ++sl) {
+        hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
+                           static_cast<const T *>(w), static_cast<const T *>(y) + sl * kHeadDim, scale,
+                           static_cast<T *>(out) + sl * kHeadDim, rpb_partial, p.H, p.W, p.heads, p.B, tiles_y, us.units,
+                           us.splits, p.D * (int)sizeof(T));
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // grad-q together with partial bias gradients (one per workgroup, av_rpb_partials() of them)
@@ -562,6 +570,11 @@ static hipError_t launch_av_mfma_t(const Problem &p, const void *w, const void *
                        static_cast<const T *>(w), static_cast<const T *>(y), scale, static_cast<T *>(out), p.H, p.W,
                        tiles_x, tiles_y, ntiles, tiles_per_wg);
     return hipGetLastError();
+}
+
+bool av_mfma_supported(const Problem &p) {
+    if (p.dtype == NA2D_F32 || force_valu()) return false;
+    return p.D == kHeadDim || (p.D % kHeadDim == 0 && p.K <= 7);   // slices only in the small-window kernel
 }
 
 hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s) {

@@ -69,7 +69,10 @@ struct InvMfmaCfg {
 template <typename T, int K, int STRIPS, int PPW, bool COMPACT>
 __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>::kWavesPerSimd)) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
                                                                        float scale, T *__restrict__ out, int H, int W,
-                                                                       int heads, int nb, int tiles_y, int units, int splits) {
+                                                                       int heads, int nb, int tiles_y, int units, int splits,
+                                                                       int pitch) {
+    // `pitch`: bytes between consecutive positions of x and out (a longer head vector is served one 32-channel
+    // slice per launch, x and out pointing at the slice)
     using C = InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>;
     using XHalo = typename C::XHalo;
     constexpr int WAVES = C::WAVES;
@@ -120,7 +123,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
     XHalo xhalo;
     xhalo.init(wave, lane);
     int xoff[XHalo::PER_WAVE];
-    xhalo.offsets(H, W, ry0, rx0, xoff);
+    xhalo.offsets(H, W, ry0, rx0, xoff, pitch);
 
     const int strip = wave / C::NWPS;
     const int sy0 = ty0 + 4 * strip;              // first key row of this wave's strip
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
             }
         }
         // x vectors, natural layout
-        XHalo::issue_at(reinterpret_cast<const char *>(x) + plane_q * Traits<T>::kKeyBytes, xoff, lds0, wave);
+        XHalo::issue_at(reinterpret_cast<const char *>(x) + plane_q * pitch, xoff, lds0, wave);
 
         // Gather-address tables, one entry per thread: the address of the weight that query (iy, ix)
         // gives key (jy, jx) is rowterm(iy, jy) + colterm(ix, jx); a pair that does not meet gets BIG.
@@ -260,7 +263,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
         for (int p = 0; p < PPW; ++p) {
             const int jx = tx0 + 4 * (p0 + p) + kx;
             if (jy < H && jx < W) {
-                char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * Traits<T>::kKeyBytes + g * 16;
+                char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * pitch + g * 16;
                 uint32_t o[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -294,10 +297,14 @@ static hipError_t launch_inverse_mfma_c(const Problem &p, const void *w, const v
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
-                       static_cast<const T *>(w), static_cast<const T *>(x), scale, static_cast<T *>(out), p.H, p.W,
-                       p.heads, p.B, tiles_y, units, splits);
-    return hipGetLastError();
+    for (int sl = 0; sl < p.D / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector
+        hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
+                           static_cast<const T *>(w), static_cast<const T *>(x) + sl * kHeadDim, scale,
+                           static_cast<T *>(out) + sl * kHeadDim, p.H, p.W, p.heads, p.B, tiles_y, units, splits,
+                           p.D * (int)sizeof(T));
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // Does the query rectangle of every 16 x 8 key tile fit rows x cols positions?
@@ -329,7 +336,7 @@ static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const v
 bool inverse_mfma_supported(const Problem &p) {
     const int shortest = p.H < p.W ? p.H : p.W;
     const int R = p.K / 2;
-    return p.D == kHeadDim && p.dtype != NA2D_F32 && p.K <= 9 && shortest > 2 * p.K + 2 && rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
+    return p.D % kHeadDim == 0 && p.dtype != NA2D_F32 && p.K <= 9 && shortest > 2 * p.K + 2 && rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
 }
 
 hipError_t launch_inverse_mfma(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s) {

@@ -51,7 +51,9 @@ struct InvRingCfg {
 template <typename T, int K>
 __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restrict__ w, const T *__restrict__ x, float scale,
                                                               T *__restrict__ out, int H, int W, int tiles_x, int tiles_y,
-                                                              int nplanes, int nseg) {
+                                                              int nplanes, int nseg, int pitch) {
+    // `pitch`: bytes between consecutive positions of x and out (a longer head vector is served one 32-channel
+    // slice per launch, x and out pointing at the slice)
     using C = InvRingCfg<T, K>;
     constexpr int SZ = (int)sizeof(T);
     constexpr int BIG = 1 << 24;   // invalid row / column terms push the sum past the zero word
@@ -94,7 +96,7 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
         const int q = j * kWave + lane;
         int xx = rx0 + q / (C::KB / 16);
         xx = xx < W - 1 ? xx : W - 1;
-        xcol[j] = q < C::RW * (C::KB / 16) ? xx * C::KB + (q % (C::KB / 16)) * 16 : -1;
+        xcol[j] = q < C::RW * (C::KB / 16) ? xx * pitch + (q % (C::KB / 16)) * 16 : -1;
     }
     // Loads the query rows [r_begin, r_end) into their ring slots: row r_begin + wave, + WAVES, ... per wave.
     auto load_rows = [&](int r_begin, int r_end) {
@@ -104,7 +106,7 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
             if (iy >= r_end) break;
             const int slot = iy % C::NR;
             // x vectors
-            const char *xrow = reinterpret_cast<const char *>(x) + (plane_q + (size_t)iy * W) * C::KB;
+            const char *xrow = reinterpret_cast<const char *>(x) + (plane_q + (size_t)iy * W) * pitch;
 #pragma unroll
             for (int j = 0; j < C::kXItems; ++j)
                 if (xcol[j] >= 0) global_to_lds_16(xrow, (unsigned)xcol[j], x0 + slot * C::kXRow + j * kWave * 16);
@@ -229,7 +231,7 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
                 }
             }
             if (jy < H && jx < W) {
-                char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * C::KB + g * 16;
+                char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * pitch + g * 16;
                 uint32_t o[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -262,15 +264,19 @@ static hipError_t launch_inverse_ring_t(const Problem &p, const void *w, const v
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s, static_cast<const T *>(w),
-                       static_cast<const T *>(x), scale, static_cast<T *>(out), p.H, p.W, tiles_x, tiles_y, p.planes(), nseg);
-    return hipGetLastError();
+    for (int sl = 0; sl < p.D / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector
+        hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s, static_cast<const T *>(w),
+                           static_cast<const T *>(x) + sl * kHeadDim, scale, static_cast<T *>(out) + sl * kHeadDim, p.H, p.W,
+                           tiles_x, tiles_y, p.planes(), nseg, p.D * (int)sizeof(T));
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // The ring holds 8 + K-1 rows per tile: every tile's query rectangle must fit that (and 16 + K-1 columns), which
 // excludes maps with a tile next to the far border whose clamped queries reach further (the tile kernel takes those).
 bool inverse_ring_supported(const Problem &p) {
-    if (p.D != kHeadDim || p.dtype == NA2D_F32 || p.K > 7) return false;
+    if (p.D % kHeadDim != 0 || p.dtype == NA2D_F32 || p.K > 7) return false;
     const int K = p.K, TY = 8;
     // a 4 x 4 key patch seen from both clamped ends of an axis at once (axes of at most 2K + 2 positions) has
     // more than K + R + 3 query rows or columns: one MFMA block per row no longer covers it

@@ -23,6 +23,8 @@ hipError_t launch_qk(const Problem &p, const void *x, const void *y, const void 
 // the same contraction on the matrix cores (f16 / bf16 only)
 hipError_t launch_qk_mfma(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
                           hipStream_t s);
+// D = 32, and for k <= 7 also D = 64 (two 32-channel slices accumulated in the matrix cores)
+bool qk_mfma_supported(const Problem &p);
 // Variant override for A/B timing: NA2D_VARIANT=valu forces the plain-ALU kernels.
 bool force_valu();
 // grad-a fused with the softmax backward (f16 / bf16, K <= 7): ds from attn, dout and v
@@ -31,6 +33,8 @@ hipError_t launch_bwd_fused(const Problem &p, const void *attn, const void *dout
 // out = scale * sum_window w * y          (AV, and grad-q with w = ds, y = k)
 hipError_t launch_av(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);
 hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);
+// the matrix-core kernels take D = 32, and for k <= 7 any multiple of 32 as one launch per 32-channel slice
+bool av_mfma_supported(const Problem &p);
 // out_j = scale * sum_{inverse neighbourhood} w[i, slot(i, j)] * x_i   (grad-v, grad-k)
 hipError_t launch_inverse(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
 bool inverse_ring_supported(const Problem &p);

@@ -123,7 +123,7 @@ bool force_valu() {
 
 hipError_t launch_qk(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
                      hipStream_t s) {
-    if (p.D == kHeadDim && p.dtype != NA2D_F32 && !force_valu()) return launch_qk_mfma(p, x, y, rpb, scale, logits, s);
+    if (qk_mfma_supported(p)) return launch_qk_mfma(p, x, y, rpb, scale, logits, s);
     NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, NA2D_DISPATCH_D(p.D, return (launch_qk_t<T, K, D>(p, x, y, rpb, scale, logits, s)))));
     return hipErrorInvalidValue;
 }

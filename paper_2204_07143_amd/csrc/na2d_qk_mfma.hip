@@ -262,7 +262,9 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void qk_mfma_kern
 // streams row w of the previous tile to global memory while the current tile is computed.  One
 // workgroup barrier per tile.  Workgroups walk down the columns of a plane, so a wave's window
 // and bias tables change only at the top and bottom of the map.
-template <typename T, int K>
+// NS: 32-channel slices of the head vector (head dim 32 NS).  Each slice of the halo is its own 64-byte-per-key
+// image in LDS and one more MFMA into the same accumulators.
+template <typename T, int K, int NS = 1>
 struct QkSmallCfg {
     using P = Patch<K>;
     static constexpr int STRIPS = 2;
@@ -272,13 +274,16 @@ struct QkSmallCfg {
     using Halo = HaloDma<T, HALO_H, HALO_W, WAVES>;
     static constexpr int KK = K * K, NB = 2 * K - 1;
     static constexpr int kThreads = kWave * WAVES;
-    static constexpr int kHaloBytes = Halo::kBytes;
+    static constexpr int kHaloBytes = Halo::kBytes;          // one slice
+    static constexpr int kHaloAll = NS * kHaloBytes;         // one stage
+    static constexpr int kKeyBytesG = NS * Traits<T>::kKeyBytes;   // bytes per position in memory
     static constexpr int kRowBytes = kTileX * KK * (int)sizeof(T);
     static constexpr int kRowPitch = (kRowBytes + 15) & ~15;
     static constexpr int kStageBytes = TY * kRowPitch;
     static constexpr int kDumpBytes = kThreads * 4;              // one word per thread for results outside its window
     static constexpr int kParity = kStageBytes + kDumpBytes;     // distance between the two staging images
-    static constexpr int kLdsBytes = 2 * kHaloBytes + 2 * kParity;
+    static constexpr int kLdsBytes = 2 * kHaloAll + 2 * kParity;
+    static constexpr int kWavesPerSimd = kLdsBytes <= 80 * 1024 ? 4 : 2;   // two workgroups, or one, per compute unit
     static_assert(kParity < 65536, "the second staging image is reached through the 16-bit offset of the LDS store");
 };
 
@@ -311,11 +316,11 @@ __device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, in
     if (tb < nbytes) *reinterpret_cast<T *>(ga + tb) = *lds_ptr<T>(lds_row + tb);
 }
 
-template <typename T, int K>
-__global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
+template <typename T, int K, int NS>
+__global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk_mfma_small_kernel(
     const T *__restrict__ x, const T *__restrict__ y, const T *__restrict__ rpb, float scale, T *__restrict__ logits, int H,
     int W, int heads, int nb, int tiles_y, int units, int splits) {
-    using C = QkSmallCfg<T, K>;
+    using C = QkSmallCfg<T, K, NS>;
     using P = Patch<K>;
     static_assert(C::kRowBytes <= 2 * kWave * 16, "a row run is flushed in two passes of the wave");
     static_assert(C::kThreads == 512, "launch bounds");
@@ -327,7 +332,7 @@ __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
     const int strip = wave >> 2, p = wave & 3;
     const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
     const int lds0 = lds_addr(lds);
-    const int stage0 = lds0 + 2 * C::kHaloBytes;
+    const int stage0 = lds0 + 2 * C::kHaloAll;
     const int my_dump = stage0 + C::kStageBytes + tid * 4;
 
     // A workgroup keeps one tile position and one head and walks a range of the batch: everything
@@ -357,20 +362,25 @@ __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
     typename C::Halo halo;
     halo.init(wave, lane);
     int hoff[C::Halo::PER_WAVE];
-    halo.offsets(H, W, hoy, hox, hoff);
-    const int qoff = ((qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1)) * Traits<T>::kKeyBytes + g * 16;
-    const size_t plane_in = (size_t)H * W * Traits<T>::kKeyBytes;   // bytes per plane of x / y
+    halo.offsets(H, W, hoy, hox, hoff, C::kKeyBytesG);
+    const int qoff = ((qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1)) * C::kKeyBytesG + g * 16;
+    const size_t plane_in = (size_t)H * W * C::kKeyBytesG;          // bytes per plane of x / y
     const size_t plane_out = (size_t)H * W * C::KK * SZ;            // ... of the logits
     // stores: wave w streams row w of the tile
     const int frow = ty0 + wave;
     const int fbytes = ((W - tx0) < kTileX ? (W - tx0) : kTileX) * C::KK * SZ;
     const size_t foff = ((size_t)frow * W + tx0) * C::KK * SZ;
 
-    u32x4 qnext;
+    u32x4 qnext[NS];
     auto issue = [&](int b, int par) {
         const size_t plane = (size_t)b * heads + head;
-        C::Halo::issue_at(reinterpret_cast<const char *>(y) + plane * plane_in, hoff, lds0 + par * C::kHaloBytes, wave);
-        qnext = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) + plane * plane_in + qoff);
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+            C::Halo::issue_at(reinterpret_cast<const char *>(y) + plane * plane_in + sl * Traits<T>::kKeyBytes, hoff,
+                              lds0 + par * C::kHaloAll + sl * C::kHaloBytes, wave);
+            qnext[sl] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) + plane * plane_in + qoff +
+                                                          sl * Traits<T>::kKeyBytes);
+        }
     };
     issue(b_begin, 0);   // the first tile's loads fly while the tables below are built
 
@@ -437,14 +447,18 @@ __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
             flush_run<T>(reinterpret_cast<char *>(logits), ((size_t)b * heads + head) * plane_out + foff, fbytes,
                          stage0 + par * C::kParity + wave * C::kRowPitch, lane);
     };
-    auto compute = [&](auto par_c, const u32x4 &qreg) {
+    auto compute = [&](auto par_c, const u32x4 (&qreg)[NS]) {
         constexpr int PAR = decltype(par_c)::value;
         if (!active) return;
         f32x4 acc[P::NBLK];
 #pragma unroll
         for (int b = 0; b < P::NBLK; ++b) {
-            const u32x4 a = *lds_ptr<u32x4>(koff[b] + PAR * C::kHaloBytes);
-            acc[b] = mfma_16x16x32<T>(a, qreg, f32x4{0.f, 0.f, 0.f, 0.f});
+            acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int sl = 0; sl < NS; ++sl) {
+                const u32x4 a = *lds_ptr<u32x4>(koff[b] + PAR * C::kHaloAll + sl * C::kHaloBytes);
+                acc[b] = mfma_16x16x32<T>(a, qreg[sl], acc[b]);
+            }
         }
 #pragma unroll
         for (int e = 0; e < P::NEL; ++e) {
@@ -459,7 +473,9 @@ __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
         constexpr int PAR = decltype(par_c)::value;
         wait_global_loads();   // this tile's halo and query chunk have landed
         __syncthreads();       // ... for every wave; the previous tile is fully staged, its halo no longer read
-        const u32x4 qreg = qnext;
+        u32x4 qreg[NS];
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) qreg[sl] = qnext[sl];
         if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
         if (b > b_begin) flush(b - 1, PAR ^ 1);
         compute(par_c, qreg);
@@ -473,14 +489,15 @@ __global__ __launch_bounds__(512, 4) void qk_mfma_small_kernel(
     flush(b_end - 1, (b_end - b_begin - 1) & 1);
 }
 
-template <typename T, int K>
-static hipError_t launch_qk_mfma_small_t(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
-                                         void *logits, hipStream_t s) {
-    using C = QkSmallCfg<T, K>;
-    static_assert(C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+template <typename T, int K, int NS>
+static hipError_t launch_qk_mfma_small_ns(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
+                                          void *logits, hipStream_t s) {
+    using C = QkSmallCfg<T, K, NS>;
+    static_assert(NS > 1 || C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+    static_assert(C::kLdsBytes <= 160 * 1024, "LDS of a compute unit");
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
-    auto kern = qk_mfma_small_kernel<T, K>;
+    auto kern = qk_mfma_small_kernel<T, K, NS>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -492,6 +509,13 @@ static hipError_t launch_qk_mfma_small_t(const Problem &p, const void *x, const 
                        static_cast<const T *>(x), static_cast<const T *>(y), static_cast<const T *>(rpb), scale,
                        static_cast<T *>(logits), p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits);
     return hipGetLastError();
+}
+
+template <typename T, int K>
+static hipError_t launch_qk_mfma_small_t(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
+                                         void *logits, hipStream_t s) {
+    if (p.D == 2 * kHeadDim) return launch_qk_mfma_small_ns<T, K, 2>(p, x, y, rpb, scale, logits, s);
+    return launch_qk_mfma_small_ns<T, K, 1>(p, x, y, rpb, scale, logits, s);
 }
 
 template <typename T, int K>
@@ -518,6 +542,11 @@ static hipError_t launch_qk_mfma_t(const Problem &p, const void *x, const void *
                        static_cast<const T *>(x), static_cast<const T *>(y), static_cast<const T *>(rpb), scale,
                        static_cast<T *>(logits), p.H, p.W, p.heads, tiles_x, tiles_y, ntiles, tiles_per_wg);
     return hipGetLastError();
+}
+
+bool qk_mfma_supported(const Problem &p) {
+    if (p.dtype == NA2D_F32 || force_valu()) return false;
+    return p.D == kHeadDim || (p.D == 2 * kHeadDim && p.K <= 7);   // two slices only in the small-window kernel
 }
 
 hipError_t launch_qk_mfma(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
