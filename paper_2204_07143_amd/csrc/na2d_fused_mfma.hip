@@ -304,7 +304,9 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void fused_mfma_k
 // positions, so the PV product contracts over positions without a transposed copy.  The halo
 // positions are numbered h = hy * (K+3) + hx; MFMA pair m of the PV product contracts over the
 // blocks 2m and 2m+1 of the logits, in the order the logits' MFMA left them in the lanes.
-template <typename T, int K>
+// NS: 32-channel slices of the head vector (head dim 32 NS).  Every slice of the key and of the value halo is
+// its own 64-byte-per-position image; the logits accumulate one MFMA per slice, the PV product runs per slice.
+template <typename T, int K, int NS = 1>
 struct FusedSmallCfg {
     using P = Patch<K>;
     static constexpr int STRIPS = 2;
@@ -316,18 +318,20 @@ struct FusedSmallCfg {
     static constexpr int NPAIR = (P::NBLK + 1) / 2;   // PV MFMAs per 16 channels
     static constexpr int NBLK2 = 2 * NPAIR;           // logits blocks, padded to whole pairs
     static constexpr int kThreads = kWave * WAVES;
-    static constexpr int kHaloBytes = Halo::kBytes;
-    static constexpr int kStageBytes = 2 * kHaloBytes;   // keys, then values
+    static constexpr int kHaloBytes = Halo::kBytes;             // one slice of one operand
+    static constexpr int kStageBytes = 2 * NS * kHaloBytes;     // the key slices, then the value slices
     static constexpr int kLdsBytes = 2 * kStageBytes;
+    static constexpr int kKeyBytesG = NS * Traits<T>::kKeyBytes;   // bytes per position in memory
+    static constexpr int kWavesPerSimd = kLdsBytes <= 80 * 1024 ? 4 : 2;   // two workgroups, or one, per compute unit
 };
 
-template <typename T, int K>
-__global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__restrict__ q, const T *__restrict__ k,
+template <typename T, int K, int NS>
+__global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void fused_mfma_small_kernel(const T *__restrict__ q, const T *__restrict__ k,
                                                                   const T *__restrict__ v, const T *__restrict__ rpb,
                                                                   float scale, T *__restrict__ out, float *__restrict__ lse,
                                                                   int H, int W, int heads, int nb, int tiles_y, int units,
                                                                   int splits) {
-    using C = FusedSmallCfg<T, K>;
+    using C = FusedSmallCfg<T, K, NS>;
     using P = Patch<K>;
     static_assert(C::kThreads == 512, "launch bounds");
     constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
@@ -362,15 +366,20 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
     typename C::Halo halo;
     halo.init(wave, lane);
     int hoff[C::Halo::PER_WAVE];
-    halo.offsets(H, W, hoy, hox, hoff);
+    halo.offsets(H, W, hoy, hox, hoff, C::kKeyBytesG);
     const int qlin = (qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1);   // this lane's query inside a plane
-    const size_t plane_bytes = (size_t)H * W * Traits<T>::kKeyBytes;
-    u32x4 qnext;
+    const size_t plane_bytes = (size_t)H * W * C::kKeyBytesG;
+    u32x4 qnext[NS];
     auto issue = [&](int b, int par) {
         const size_t off = ((size_t)b * heads + head) * plane_bytes;
-        C::Halo::issue_at(reinterpret_cast<const char *>(k) + off, hoff, lds0 + par * C::kStageBytes, wave);
-        C::Halo::issue_at(reinterpret_cast<const char *>(v) + off, hoff, lds0 + par * C::kStageBytes + C::kHaloBytes, wave);
-        qnext = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(q) + off + qlin * Traits<T>::kKeyBytes + g * 16);
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+            const size_t so = off + sl * Traits<T>::kKeyBytes;
+            C::Halo::issue_at(reinterpret_cast<const char *>(k) + so, hoff, lds0 + par * C::kStageBytes + sl * C::kHaloBytes, wave);
+            C::Halo::issue_at(reinterpret_cast<const char *>(v) + so, hoff,
+                              lds0 + par * C::kStageBytes + (NS + sl) * C::kHaloBytes, wave);
+            qnext[sl] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(q) + so + (size_t)qlin * C::kKeyBytesG + g * 16);
+        }
     };
     issue(b_begin, 0);
 
@@ -390,7 +399,7 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
         h = h < P::NKEY ? h : P::NKEY - 1;
         hy = P::row_of(h);
         hx = h - hy * P::PW;
-        vaddr[b] = lds0 + C::kHaloBytes + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + (j & 3) * 16;
+        vaddr[b] = lds0 + NS * C::kHaloBytes + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + (j & 3) * 16;
     }
     // log2(e) * bias of (this lane's query, halo position), -inf outside the query's window; packed
     // fp16 pairs (half the registers; the fma below reads them as mixed-precision operands)
@@ -428,15 +437,19 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
     }
 
     const float scale2 = scale * kLog2e;
-    auto compute = [&](auto par_c, const u32x4 &qreg, int b) {
+    auto compute = [&](auto par_c, const u32x4 (&qreg)[NS], int b) {
         constexpr int PAR = decltype(par_c)::value;
         if (!active) return;
         // 1-2. logits in the exp2 domain
         float s[4 * C::NBLK2];
 #pragma unroll
         for (int bk = 0; bk < P::NBLK; ++bk) {
-            const u32x4 a = *lds_ptr<u32x4>(koff[bk] + PAR * C::kStageBytes);
-            const f32x4 acc = mfma_16x16x32<T>(a, qreg, f32x4{0.f, 0.f, 0.f, 0.f});
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int sl = 0; sl < NS; ++sl) {
+                const u32x4 a = *lds_ptr<u32x4>(koff[bk] + PAR * C::kStageBytes + sl * C::kHaloBytes);
+                acc = mfma_16x16x32<T>(a, qreg[sl], acc);
+            }
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 s[4 * bk + r] = __builtin_fmaf(scale2, acc[r], (float)biasm[(4 * bk + r) >> 1][(4 * bk + r) & 1]);
@@ -459,7 +472,9 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
         // 4. O^T = V^T * P
-        f32x4 o[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+        f32x4 o[NS][2];
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) o[sl][0] = o[sl][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int pb = 0; pb < C::NPAIR; ++pb) {
             const u32x4 bop = u32x4{pack2<T>(s[8 * pb], s[8 * pb + 1]), pack2<T>(s[8 * pb + 2], s[8 * pb + 3]),
@@ -475,21 +490,28 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
                                pack2<T>(rem[6], rem[7])};
             }
 #pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                const u32x2 lo = lds_read_tr16(vaddr[2 * pb] + PAR * C::kStageBytes + hf * 8);
-                const u32x2 hi = lds_read_tr16(vaddr[2 * pb + 1] + PAR * C::kStageBytes + hf * 8);
-                const u32x4 aop = u32x4{lo.x, lo.y, hi.x, hi.y};
-                o[hf] = mfma_16x16x32<T>(aop, bop, o[hf]);
-                if constexpr (sizeof(T) == 2 && Traits<T>::kDtype == NA2D_BF16) o[hf] = mfma_16x16x32<T>(aop, bop_lo, o[hf]);
+            for (int sl = 0; sl < NS; ++sl) {
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf) {
+                    const u32x2 lo = lds_read_tr16(vaddr[2 * pb] + PAR * C::kStageBytes + sl * C::kHaloBytes + hf * 8);
+                    const u32x2 hi = lds_read_tr16(vaddr[2 * pb + 1] + PAR * C::kStageBytes + sl * C::kHaloBytes + hf * 8);
+                    const u32x4 aop = u32x4{lo.x, lo.y, hi.x, hi.y};
+                    o[sl][hf] = mfma_16x16x32<T>(aop, bop, o[sl][hf]);
+                    if constexpr (sizeof(T) == 2 && Traits<T>::kDtype == NA2D_BF16)
+                        o[sl][hf] = mfma_16x16x32<T>(aop, bop_lo, o[sl][hf]);
+                }
             }
         }
         // 5. normalise and store this lane's 8 channels (8g .. 8g + 7) of its own query
         if (q_ok) {
             const float inv = __builtin_amdgcn_rcpf(l);   // 1 ulp; the result is rounded to 11 or 8 bits
             const size_t plane = (size_t)b * heads + head;
-            char *dst = reinterpret_cast<char *>(out) + plane * plane_bytes + qlin * Traits<T>::kKeyBytes + g * 16;
-            *reinterpret_cast<u32x4 *>(dst) = u32x4{pack2<T>(o[0][0] * inv, o[0][1] * inv), pack2<T>(o[0][2] * inv, o[0][3] * inv),
-                                                    pack2<T>(o[1][0] * inv, o[1][1] * inv), pack2<T>(o[1][2] * inv, o[1][3] * inv)};
+            char *dst = reinterpret_cast<char *>(out) + plane * plane_bytes + (size_t)qlin * C::kKeyBytesG + g * 16;
+#pragma unroll
+            for (int sl = 0; sl < NS; ++sl)   // channels 32 sl + 8g .. + 7
+                *reinterpret_cast<u32x4 *>(dst + sl * Traits<T>::kKeyBytes) =
+                    u32x4{pack2<T>(o[sl][0][0] * inv, o[sl][0][1] * inv), pack2<T>(o[sl][0][2] * inv, o[sl][0][3] * inv),
+                          pack2<T>(o[sl][1][0] * inv, o[sl][1][1] * inv), pack2<T>(o[sl][1][2] * inv, o[sl][1][3] * inv)};
             if (lse != nullptr && g == 0) lse[plane * H * W + qlin] = (m + __builtin_amdgcn_logf(l)) * kLn2;
         }
     };
@@ -499,7 +521,9 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
         constexpr int PAR = decltype(par_c)::value;
         wait_global_loads();   // this tile's halos and query chunk have landed
         __syncthreads();       // ... for every wave, and nobody still reads the other buffer pair
-        const u32x4 qreg = qnext;
+        u32x4 qreg[NS];
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) qreg[sl] = qnext[sl];
         if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
         compute(par_c, qreg, b);
         ++b;
@@ -510,14 +534,15 @@ __global__ __launch_bounds__(512, 4) void fused_mfma_small_kernel(const T *__res
     }
 }
 
-template <typename T, int K>
-static hipError_t launch_fused_mfma_small_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
-                                            float scale, void *out, float *lse, hipStream_t s) {
-    using C = FusedSmallCfg<T, K>;
-    static_assert(C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+template <typename T, int K, int NS>
+static hipError_t launch_fused_mfma_small_ns(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
+                                             float scale, void *out, float *lse, hipStream_t s) {
+    using C = FusedSmallCfg<T, K, NS>;
+    static_assert(NS > 1 || C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+    static_assert(C::kLdsBytes <= 160 * 1024, "LDS of a compute unit");
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
-    auto kern = fused_mfma_small_kernel<T, K>;
+    auto kern = fused_mfma_small_kernel<T, K, NS>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -530,6 +555,13 @@ static hipError_t launch_fused_mfma_small_t(const Problem &p, const void *q, con
                        static_cast<const T *>(rpb), scale, static_cast<T *>(out), lse, p.H, p.W, p.heads, p.B, tiles_y,
                        us.units, us.splits);
     return hipGetLastError();
+}
+
+template <typename T, int K>
+static hipError_t launch_fused_mfma_small_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
+                                            float scale, void *out, float *lse, hipStream_t s) {
+    if (p.D == 2 * kHeadDim) return launch_fused_mfma_small_ns<T, K, 2>(p, q, k, v, rpb, scale, out, lse, s);
+    return launch_fused_mfma_small_ns<T, K, 1>(p, q, k, v, rpb, scale, out, lse, s);
 }
 
 template <typename T, int K>
@@ -556,6 +588,11 @@ static hipError_t launch_fused_mfma_t(const Problem &p, const void *q, const voi
                        static_cast<const T *>(rpb), scale, static_cast<T *>(out), lse, p.H, p.W, p.heads, tiles_x,
                        tiles_y, ntiles, tiles_per_wg);
     return hipGetLastError();
+}
+
+bool fused_mfma_supported(const Problem &p) {
+    if (p.dtype == NA2D_F32 || force_valu()) return false;
+    return p.D == kHeadDim || (p.D == 2 * kHeadDim && p.K <= 7);   // two slices only in the small-window kernel
 }
 
 hipError_t launch_fused_mfma(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,

@@ -64,6 +64,8 @@ hipError_t launch_fbwd_kv(const Problem &p, const void *q, const void *k, const 
                           const float *lse, const float *delta, const void *dout, void *dk, void *dv, hipStream_t s);
 hipError_t launch_fused_fwd(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
                             void *out, float *lse, hipStream_t s);
+// D = 32, and for k <= 7 also D = 64 (two 32-channel slices)
+bool fused_mfma_supported(const Problem &p);
 hipError_t launch_fused_mfma(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
                              void *out, float *lse, hipStream_t s);
 hipError_t launch_indices(const Problem &p, int32_t *key_index, int32_t *rpb_index, hipStream_t s);
