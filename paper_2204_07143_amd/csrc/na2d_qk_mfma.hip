@@ -2,259 +2,17 @@
 //   logits[n, a, c] = scale * <x_n, y_{rho(n; a, c)}> + bias
 // (arXiv 2204.07143, Eq. 2; with x = dout, y = v and no bias it is grad-a, Appendix A).
 //
-// A persistent workgroup walks a contiguous range of 16-wide x (4*WAVES)-high query tiles.
-// Per tile the key halo is staged once in LDS; each wave owns a strip of four 4 x 4 query
-// patches.  Per patch: the queries are the B operand (one 16-byte global load per lane), each
-// block of 16 halo keys is an A operand (one 16-byte LDS read per lane), one MFMA per block
-// gives every lane 4 dot products of "its" query.  Which of them fall inside the query's
-// window, and where they go in the k*k row, depends only on the lane and on how far the window
-// is shifted at a border; that is kept as a per-lane table of LDS addresses (entries outside
-// the window point at a dump slot), rebuilt only when the shift pattern changes.  So the steady
-// state per result is one fused multiply-add-convert (scale, bias) and one 2-byte LDS store.
-// The strip's four row runs are then streamed to global memory with 16-byte stores.
-//
-// The loop is software-pipelined: the next tile's halo and queries are loaded into registers
-// before the current tile is computed, so global-memory latency overlaps the matrix work.
-#include "na2d_kernels.hpp"
-#include "na2d_mfma.hpp"
-#include "na2d_tile.hpp"
-
-namespace na2d {
-
-template <typename T, int K, int WAVES>
-struct QkMfmaCfg {
-    using P = Patch<K>;
-    static constexpr int TY = 4 * WAVES;
-    static constexpr int HALO_H = TY + K - 1, HALO_W = kTileX + K - 1;
-    static constexpr int KK = K * K, NB = 2 * K - 1;
-    static constexpr int kThreads = kWave * WAVES;
-    static constexpr int kHaloBytes = HALO_H * HALO_W * Traits<T>::kKeyStride;
-    static constexpr int kBiasBytes = ((NB * NB * 4) + 15) & ~15;
-    static constexpr int kRowRegion = mirror_bytes(kTileX * KK * (int)sizeof(T));
-    static constexpr int kPatchStep = 4 * KK * (int)sizeof(T);   // staging distance between neighbouring patches
-    static constexpr int kDumpBytes = (kWave * 4 + 3 * kPatchStep + 15) & ~15;
-    static constexpr int kWaveBytes = 4 * kRowRegion + kDumpBytes;
-    static constexpr int kLdsBytes = kHaloBytes + kBiasBytes + WAVES * kWaveBytes;
-};
-
-template <typename T, int K>
-constexpr int qk_mfma_waves() {
-    return QkMfmaCfg<T, K, 4>::kLdsBytes <= 80 * 1024 ? 4 : 2;
-}
-
-struct QkTile {
-    int ty0, tx0, plane, hoy, hox;
-};
-
-// Two waves per SIMD for the four-wave tiles (two workgroups share a CU); the two-wave tiles of the
-// large windows keep more per-lane tables and get the whole register file instead of spilling.
-template <typename T, int K, int WAVES>
-__global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void qk_mfma_kernel(const T *__restrict__ x, const T *__restrict__ y,
-                                                                  const T *__restrict__ rpb, float scale,
-                                                                  T *__restrict__ logits, int H, int W, int heads,
-                                                                  int tiles_x, int tiles_y, int ntiles,
-                                                                  int tiles_per_wg) {
-    using C = QkMfmaCfg<T, K, WAVES>;
-    using P = Patch<K>;
-    constexpr int STRIDE = Traits<T>::kKeyStride;
-    extern __shared__ __align__(16) char lds[];
-    float *bias_lds = reinterpret_cast<float *>(lds + C::kHaloBytes);
-
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-    const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
-    // LDS addresses kept in tables are absolute, so stores through them need no base add
-    const int wreg_off = lds_addr(lds) + C::kHaloBytes + C::kBiasBytes + wave * C::kWaveBytes;
-    char *wreg = lds + C::kHaloBytes + C::kBiasBytes + wave * C::kWaveBytes;
-    // every lane's entries outside its window land here (plus the per-patch step): one bank per lane
-    const int dump_addr = wreg_off + 4 * C::kRowRegion + lane * 4;
-
-    // A-operand offsets of this lane inside a patch halo (keys past the end re-read the last one)
-    int koff[P::NBLK];
-#pragma unroll
-    for (int b = 0; b < P::NBLK; ++b) {
-        int h = 16 * b + j;
-        h = h < P::NKEY ? h : P::NKEY - 1;
-        const int hy = P::row_of(h), hx = h - hy * P::PW;
-        koff[b] = (hy * C::HALO_W + hx) * STRIDE + g * 16;
-    }
-
-    float bias0[P::NEL];
-    int slotaddr[P::NEL];
-#pragma unroll
-    for (int e = 0; e < P::NEL; ++e) {
-        bias0[e] = 0.f;
-        slotaddr[e] = dump_addr;
-    }
-    // what the per-lane tables / the LDS bias table were last built for
-    int cur_bias_key = -1, cur_wy = -100000, cur_wx = -100000, cur_base = 0, lds_head = -1;
-
-    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
-    const int t_begin = wg * tiles_per_wg;
-    const int t_end = (wg + 1) * tiles_per_wg < ntiles ? (wg + 1) * tiles_per_wg : ntiles;
-    if (t_begin >= t_end) return;
-
-    auto tile_of = [&](int t) {
-        const TileCoord tc = decode_tile(t, tiles_x, tiles_y);
-        QkTile q;
-        q.ty0 = tc.tiy * C::TY;
-        q.tx0 = tc.tix * kTileX;
-        q.plane = tc.plane;
-        q.hoy = halo_origin(q.ty0, C::TY, H, K);
-        q.hox = halo_origin(q.tx0, kTileX, W, K);
-        return q;
-    };
-
-    HaloPrefetch<T, C::HALO_H, C::HALO_W, C::kThreads> halo;
-    halo.init(W, tid);
-    u32x4 qnext[4];
-    auto prefetch = [&](const QkTile &tl) {
-        const size_t plane_q = (size_t)tl.plane * H * W;
-        halo.issue(reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes, H, W, tl.hoy, tl.hox);
-        const int qy = tl.ty0 + 4 * wave + jy;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int qx = tl.tx0 + 4 * p + jx;
-            qnext[p] = u32x4{0u, 0u, 0u, 0u};
-            if (qy < H && qx < W)
-                qnext[p] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) +
-                                                            (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes + g * 16);
-        }
-    };
-
-    // A strip's finished row runs leave for global memory one iteration late, right after the next
-    // tile's loads have been issued: stores and loads then both overlap the next tile's matrix work
-    // (stores and loads share one in-order completion counter on this architecture).
-    size_t out_plane_q = 0;
-    int out_sy0 = 0, out_tx0 = 0;
-    bool out_pending = false;
-    auto flush_strip = [&]() {
-        const int nvalid = (W - out_tx0) < kTileX ? (W - out_tx0) : kTileX;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            if (out_sy0 + r < H) {
-                const size_t g0r = (out_plane_q + (size_t)(out_sy0 + r) * W + out_tx0) * C::KK * sizeof(T);
-                stage_out<T, kTileX * C::KK * (int)sizeof(T), kWave>(reinterpret_cast<char *>(logits), g0r,
-                                                                     nvalid * C::KK * (int)sizeof(T),
-                                                                     wreg + r * C::kRowRegion, lane);
-            }
-        }
-    };
-
-    QkTile cur = tile_of(t_begin);
-    prefetch(cur);
-
-    for (int t = t_begin; t < t_end; ++t) {
-        const int ty0 = cur.ty0, tx0 = cur.tx0, hoy = cur.hoy, hox = cur.hox;
-        const size_t plane_q = (size_t)cur.plane * H * W;
-        const int head = cur.plane % heads;
-        __syncthreads();   // the previous tile's halo (and bias table) is no longer read
-        halo.commit(lds);
-        if (head != lds_head) {
-            lds_head = head;
-            for (int i = tid; i < C::NB * C::NB; i += C::kThreads)
-                bias_lds[i] = rpb ? to_f32(rpb[(size_t)head * C::NB * C::NB + i]) : 0.f;
-            cur_bias_key = -1;
-        }
-        u32x4 qreg[4];
-#pragma unroll
-        for (int p = 0; p < 4; ++p) qreg[p] = qnext[p];
-        __syncthreads();
-        if (t + 1 < t_end) {
-            cur = tile_of(t + 1);
-            prefetch(cur);
-        }
-
-        if (out_pending) {
-            flush_strip();
-            out_pending = false;
-            // the staging reads above must stay ahead of this tile's staging writes
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-        }
-
-        const int sy0 = ty0 + 4 * wave;   // first row of this wave's strip
-        if (sy0 >= H) continue;
-        const int oy = halo_origin(sy0, 4, H, K);   // patch halo origin (row)
-        const int dy = oy - (sy0 - P::R);           // 0 away from the borders
-        const int qy = sy0 + jy;
-        const bool row_ok = qy < H;
-        const size_t rowg0 = (plane_q + (size_t)qy * W + tx0) * C::KK * sizeof(T);
-        const int lanebase = wreg_off + jy * C::kRowRegion + (int)(rowg0 & 15) + jx * C::KK * (int)sizeof(T);
-        const int wy = row_ok ? win_start(qy, H, K) - oy : 100000;
-
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int px0 = tx0 + 4 * p;
-            if (px0 < W) {
-                const int ox = halo_origin(px0, 4, W, K);
-                const int dx = ox - (px0 - P::R);
-                const int qx = px0 + jx;
-                const bool q_ok = row_ok && qx < W;
-                const int want_wy = q_ok ? wy : 100000;
-                const int want_wx = q_ok ? win_start(qx, W, K) - ox : 100000;
-                // The bias of (query, key) depends on key - query only: a per-lane constant table,
-                // except that a displaced patch origin shifts it.
-                const int bias_key = (head * 16 + dy + 8) * 16 + dx + 8;
-                if (bias_key != cur_bias_key) {
-                    cur_bias_key = bias_key;
-                    int gv = g;
-                    asm volatile("" : "+v"(gv));   // keep the index arithmetic inside this rare block
-#pragma unroll
-                    for (int e = 0; e < P::NEL; ++e) {
-                        const int h = 16 * (e >> 2) + 4 * gv + (e & 3);
-                        const int hy = P::row_of(h), hx = h - hy * P::PW;
-                        int u = hy - jy + P::R + dy, v = hx - jx + P::R + dx;
-                        u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);   // cells outside the table belong to keys
-                        v = v < 0 ? 0 : (v > C::NB - 1 ? C::NB - 1 : v);   // outside every window: value unused
-                        bias0[e] = bias_lds[u * C::NB + v];
-                    }
-                }
-                if (__any(want_wy != cur_wy || want_wx != cur_wx || lanebase != cur_base)) {
-                    cur_wy = want_wy;
-                    cur_wx = want_wx;
-                    cur_base = lanebase;
-                    int gv = g;
-                    asm volatile("" : "+v"(gv));
-#pragma unroll
-                    for (int e = 0; e < P::NEL; ++e) {
-                        const int h = 16 * (e >> 2) + 4 * gv + (e & 3);
-                        const int hy = P::row_of(h), hx = h - hy * P::PW;
-                        const int a = hy - want_wy, c = hx - want_wx;
-                        const bool ok = h < P::NKEY && (unsigned)a < (unsigned)K && (unsigned)c < (unsigned)K;
-                        slotaddr[e] = ok ? lanebase + (a * K + c) * (int)sizeof(T) : dump_addr;
-                    }
-                }
-                const char *kp = lds + ((oy - hoy) * C::HALO_W + (ox - hox)) * STRIDE;
-                f32x4 acc[P::NBLK];
-#pragma unroll
-                for (int b = 0; b < P::NBLK; ++b) {
-                    const u32x4 a = *reinterpret_cast<const u32x4 *>(kp + koff[b]);
-                    acc[b] = mfma_16x16x32<T>(a, qreg[p], f32x4{0.f, 0.f, 0.f, 0.f});
-                }
-#pragma unroll
-                for (int e = 0; e < P::NEL; ++e) {
-                    const float v = __builtin_fmaf(scale, acc[e >> 2][e & 3], bias0[e]);
-                    *lds_ptr<T>(slotaddr[e] + p * C::kPatchStep) = from_f32<T>(v);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);   // keep the patches apart: interleaving them only costs registers
-        }
-        // this wave's four row runs are complete (wave-private staging); they are flushed next iteration
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        out_plane_q = plane_q;
-        out_sy0 = sy0;
-        out_tx0 = tx0;
-        out_pending = true;
-    }
-    if (out_pending) flush_strip();
-}
-
-// ---- small windows (K <= 7): one patch per wave, everything asynchronous -------------------
+// Per 4 x 4 patch of queries: the queries are the B operand (one 16-byte global load per lane), each
+// block of 16 positions of the patch halo is an A operand (one 16-byte LDS read per lane), one MFMA
+// per block gives every lane 4 dot products of "its" query.  Which of them fall inside the query's
+// window, and where they go in the k*k row, depends only on the lane and on how far the window is
+// shifted at a border; that is kept as a per-lane table of LDS addresses (entries outside the
+// window point at a dump word).  So the steady state per result is one fused multiply-add-convert
+// (scale, bias) and one 2-byte LDS store.
 //
 // Eight waves share a 16 x 8 query tile, one 4 x 4 patch each, so a SIMD holds four waves whose
-// LDS, matrix and conversion work overlap.  The key halo reaches LDS by direct loads in its
+// LDS, matrix and conversion work overlap (two where the images of a large window or of a second
+// 32-channel slice fill the LDS: k >= 9, head dim 64).  The key halo reaches LDS by direct loads in its
 // natural 64-byte-per-key layout (consecutive keys of an operand block are consecutive in LDS,
 // so the 16-byte operand reads do not collide), into one of two buffers: the next tile's halo
 // arrives while this tile is computed.  Results go to one of two staging images of the tile's
@@ -262,6 +20,12 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void qk_mfma_kern
 // streams row w of the previous tile to global memory while the current tile is computed.  One
 // workgroup barrier per tile.  Workgroups walk down the columns of a plane, so a wave's window
 // and bias tables change only at the top and bottom of the map.
+#include "na2d_kernels.hpp"
+#include "na2d_mfma.hpp"
+#include "na2d_tile.hpp"
+
+namespace na2d {
+
 // NS: 32-channel slices of the head vector (head dim 32 NS).  Each slice of the halo is its own 64-byte-per-key
 // image in LDS and one more MFMA into the same accumulators.
 template <typename T, int K, int NS = 1>
@@ -294,23 +58,26 @@ struct QkSmallCfg {
 // pointers), and whose 64 lanes still cover one contiguous kilobyte.  Aligning the stores instead would put the
 // misalignment on the LDS side, where a 16-byte read at a 2-byte phase costs eight reads.  The elements past
 // the last whole chunk (ragged tiles only) go one by one.
-template <typename T>
+template <typename T, int PASSES>
 __device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, int lds_row, int lane) {
     const int nbody = nbytes >> 4;
     char *ga = gbase + g0;
     struct __attribute__((packed, aligned(2))) Chunk {
         u32x4 v;
     };
-    u32x4 v[2];
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-        const int c = lane + it * kWave;
-        if (c < nbody) v[it] = *lds_ptr<u32x4>(lds_row + 16 * c);
-    }
+    for (int it0 = 0; it0 < PASSES; it0 += 2) {   // two chunks per lane in flight
+        u32x4 v[2];
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-        const int c = lane + it * kWave;
-        if (c < nbody) reinterpret_cast<Chunk *>(ga + 16 * c)->v = v[it];
+        for (int it = it0; it < it0 + 2 && it < PASSES; ++it) {
+            const int c = lane + it * kWave;
+            if (c < nbody) v[it - it0] = *lds_ptr<u32x4>(lds_row + 16 * c);
+        }
+#pragma unroll
+        for (int it = it0; it < it0 + 2 && it < PASSES; ++it) {
+            const int c = lane + it * kWave;
+            if (c < nbody) reinterpret_cast<Chunk *>(ga + 16 * c)->v = v[it - it0];
+        }
     }
     const int tb = 16 * nbody + lane * (int)sizeof(T);
     if (tb < nbytes) *reinterpret_cast<T *>(ga + tb) = *lds_ptr<T>(lds_row + tb);
@@ -322,7 +89,7 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
     int W, int heads, int nb, int tiles_y, int units, int splits) {
     using C = QkSmallCfg<T, K, NS>;
     using P = Patch<K>;
-    static_assert(C::kRowBytes <= 2 * kWave * 16, "a row run is flushed in two passes of the wave");
+    constexpr int kFlushPasses = (C::kRowBytes + kWave * 16 - 1) / (kWave * 16);   // 16-byte chunks per lane and row run
     static_assert(C::kThreads == 512, "launch bounds");
     constexpr int SZ = (int)sizeof(T);
     extern __shared__ __align__(16) char lds[];
@@ -398,8 +165,16 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
     // 16 (e / 4) + 4 g + e % 4.  Inside the query's window it is stored at its slot of the query's row
     // run in the staging image, outside it goes to the lane's dump word.  The bias of (query, key)
     // depends on key - query only (Eq. 2); it is kept two per register in the storage type.
+    // Large windows (up to 64 results per lane) keep the store addresses two per register, as 16-bit offsets
+    // from the first staging image; small windows keep them as absolute addresses, one per register.
+    constexpr bool PACKED = K > 7;
+    static_assert(C::kParity < 65536, "offsets inside a staging image fit 16 bits");
     uint32_t bias2[P::NEL / 2];
-    int slotaddr[P::NEL];
+    int slotaddr[PACKED ? P::NEL / 2 : P::NEL];
+    auto slot_of = [&](int e) -> int {
+        if constexpr (PACKED) return stage0 + (int)((e & 1) ? (uint32_t)slotaddr[e >> 1] >> 16 : (uint32_t)slotaddr[e >> 1] & 0xffffu);
+        else return slotaddr[e];
+    };
     {
         const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
         const int lane_stage = stage0 + (4 * strip + jy) * C::kRowPitch + (4 * p + jx) * C::KK * SZ;
@@ -407,64 +182,90 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
         // inside the query's window are in one halo row (a halo row holds K + 3 positions, the window K of
         // them), normally the row of the group's first position; when that one is already right of the
         // window, the group runs on into the next halo row and only that part can be inside.
-        int bidx[P::NEL];
+        // Groups are handled four at a time: their sixteen loads of the bias table are in flight together (one
+        // uniform branch on the table's presence per batch) without the indices of the whole patch halo being
+        // alive at once (large windows have up to 64 results per lane).
+        const uint16_t *tbl = rpb != nullptr ? reinterpret_cast<const uint16_t *>(rpb) + (size_t)head * C::NB * C::NB : nullptr;
 #pragma unroll
-        for (int G = 0; G < P::NBLK; ++G) {
-            const int h0 = 16 * G + 4 * g;
-            const int hy0 = P::row_of(h0), hx0 = h0 - hy0 * P::PW;
-            const bool wrap = hx0 > wx + K - 1;
-            const int hy = hy0 + (wrap ? 1 : 0), hxf = hx0 - (wrap ? P::PW : 0);   // halo row, column of the first position
-            const int a = hy - wy;
-            int c0 = hxf - wx;   // window column of the group's first position (may be negative)
-            const int base = lane_stage + (a * K + c0) * SZ;
-            c0 = (q_ok && (unsigned)a < (unsigned)K) ? c0 : 64;   // no row of the window: every column test fails
-            int u = hy - jy + P::R + dy;
-            u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);   // cells outside the table belong to keys
-            const int v0 = hxf - jx + P::R + dx;               // outside every window: value unused
+        for (int G0 = 0; G0 < P::NBLK; G0 += 4) {
+            int bidx[16];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                slotaddr[4 * G + i] = (unsigned)(c0 + i) < (unsigned)K ? base + i * SZ : my_dump;
-                int v = v0 + i;
-                v = v < 0 ? 0 : (v > C::NB - 1 ? C::NB - 1 : v);
-                bidx[4 * G + i] = u * C::NB + v;
+            for (int G = G0; G < G0 + 4 && G < P::NBLK; ++G) {
+                const int h0 = 16 * G + 4 * g;
+                const int hy0 = P::row_of(h0), hx0 = h0 - hy0 * P::PW;
+                const bool wrap = hx0 > wx + K - 1;
+                const int hy = hy0 + (wrap ? 1 : 0), hxf = hx0 - (wrap ? P::PW : 0);   // halo row, column of the first position
+                const int a = hy - wy;
+                int c0 = hxf - wx;   // window column of the group's first position (may be negative)
+                const int base = lane_stage + (a * K + c0) * SZ;
+                c0 = (q_ok && (unsigned)a < (unsigned)K) ? c0 : 64;   // no row of the window: every column test fails
+                int u = hy - jy + P::R + dy;
+                u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);   // cells outside the table belong to keys
+                const int v0 = hxf - jx + P::R + dx;               // outside every window: value unused
+                int sa[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    sa[i] = (unsigned)(c0 + i) < (unsigned)K ? base + i * SZ : my_dump;
+                    int v = v0 + i;
+                    v = v < 0 ? 0 : (v > C::NB - 1 ? C::NB - 1 : v);
+                    bidx[4 * (G - G0) + i] = u * C::NB + v;
+                }
+                if constexpr (PACKED) {
+                    slotaddr[2 * G] = (sa[0] - stage0) | ((sa[1] - stage0) << 16);
+                    slotaddr[2 * G + 1] = (sa[2] - stage0) | ((sa[3] - stage0) << 16);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) slotaddr[4 * G + i] = sa[i];
+                }
             }
+            uint32_t bits[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) bits[e] = 0u;
+            if (tbl != nullptr) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    if (4 * G0 + e < P::NEL) bits[e] = tbl[bidx[e]];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (2 * G0 + e < P::NEL / 2) bias2[2 * G0 + e] = bits[2 * e] | (bits[2 * e + 1] << 16);
+            if constexpr (K > 7) __builtin_amdgcn_sched_barrier(0);   // keep the batches apart: one batch of temporaries at a time
         }
-        // all loads of the bias table in flight at once (one uniform branch on the table's presence)
-        uint32_t bits[P::NEL];
-#pragma unroll
-        for (int e = 0; e < P::NEL; ++e) bits[e] = 0u;
-        if (rpb != nullptr) {
-            const uint16_t *tbl = reinterpret_cast<const uint16_t *>(rpb) + (size_t)head * C::NB * C::NB;
-#pragma unroll
-            for (int e = 0; e < P::NEL; ++e) bits[e] = tbl[bidx[e]];
-        }
-#pragma unroll
-        for (int e = 0; e < P::NEL / 2; ++e) bias2[e] = bits[2 * e] | (bits[2 * e + 1] << 16);
     }
 
     auto flush = [&](int b, int par) {
         if (frow < H)
-            flush_run<T>(reinterpret_cast<char *>(logits), ((size_t)b * heads + head) * plane_out + foff, fbytes,
+            flush_run<T, kFlushPasses>(reinterpret_cast<char *>(logits), ((size_t)b * heads + head) * plane_out + foff, fbytes,
                          stage0 + par * C::kParity + wave * C::kRowPitch, lane);
     };
     auto compute = [&](auto par_c, const u32x4 (&qreg)[NS]) {
         constexpr int PAR = decltype(par_c)::value;
         if (!active) return;
-        f32x4 acc[P::NBLK];
+        // blocks in batches of eight: the MFMAs of a batch are issued back to back, then its 32 results are
+        // stored; large windows (up to 16 blocks) never hold more than eight accumulators
+        constexpr int BATCH = 8;
 #pragma unroll
-        for (int b = 0; b < P::NBLK; ++b) {
-            acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int b0 = 0; b0 < P::NBLK; b0 += BATCH) {
+            f32x4 acc[BATCH];
 #pragma unroll
-            for (int sl = 0; sl < NS; ++sl) {
-                const u32x4 a = *lds_ptr<u32x4>(koff[b] + PAR * C::kHaloAll + sl * C::kHaloBytes);
-                acc[b] = mfma_16x16x32<T>(a, qreg[sl], acc[b]);
+            for (int u = 0; u < BATCH; ++u) {
+                const int bk = b0 + u;
+                if (bk >= P::NBLK) break;
+                acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int sl = 0; sl < NS; ++sl) {
+                    const u32x4 a = *lds_ptr<u32x4>(koff[bk] + PAR * C::kHaloAll + sl * C::kHaloBytes);
+                    acc[u] = mfma_16x16x32<T>(a, qreg[sl], acc[u]);
+                }
             }
-        }
 #pragma unroll
-        for (int e = 0; e < P::NEL; ++e) {
-            const uint16_t bb = (uint16_t)((e & 1) ? bias2[e >> 1] >> 16 : bias2[e >> 1] & 0xffffu);
-            const float v = __builtin_fmaf(scale, acc[e >> 2][e & 3], to_f32(__builtin_bit_cast(T, bb)));
-            *lds_ptr<T>(slotaddr[e] + PAR * C::kParity) = from_f32<T>(v);
+            for (int u = 0; u < 4 * BATCH; ++u) {
+                const int e = 4 * b0 + u;
+                if (e >= P::NEL) break;
+                const uint16_t bb = (uint16_t)((e & 1) ? bias2[e >> 1] >> 16 : bias2[e >> 1] & 0xffffu);
+                const float v = __builtin_fmaf(scale, acc[u >> 2][u & 3], to_f32(__builtin_bit_cast(T, bb)));
+                *lds_ptr<T>(slot_of(e) + PAR * C::kParity) = from_f32<T>(v);
+            }
         }
     };
 
@@ -493,7 +294,7 @@ template <typename T, int K, int NS>
 static hipError_t launch_qk_mfma_small_ns(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
                                           void *logits, hipStream_t s) {
     using C = QkSmallCfg<T, K, NS>;
-    static_assert(NS > 1 || C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+    static_assert(NS > 1 || K > 7 || C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
     static_assert(C::kLdsBytes <= 160 * 1024, "LDS of a compute unit");
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
@@ -514,34 +315,10 @@ static hipError_t launch_qk_mfma_small_ns(const Problem &p, const void *x, const
 template <typename T, int K>
 static hipError_t launch_qk_mfma_small_t(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
                                          void *logits, hipStream_t s) {
-    if (p.D == 2 * kHeadDim) return launch_qk_mfma_small_ns<T, K, 2>(p, x, y, rpb, scale, logits, s);
-    return launch_qk_mfma_small_ns<T, K, 1>(p, x, y, rpb, scale, logits, s);
-}
-
-template <typename T, int K>
-static hipError_t launch_qk_mfma_t(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
-                                   void *logits, hipStream_t s) {
-    constexpr int WAVES = qk_mfma_waves<T, K>();
-    using C = QkMfmaCfg<T, K, WAVES>;
-    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
-    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
-    const int ntiles = tiles_x * tiles_y * p.planes();
-    // persistent workgroups: two per CU, each walking a contiguous range of tiles
-    const int max_wgs = 256 * 2;
-    const int tiles_per_wg = (ntiles + max_wgs - 1) / max_wgs;
-    const int nwg = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
-    auto kern = qk_mfma_kernel<T, K, WAVES>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
+    if constexpr (K <= 7) {
+        if (p.D == 2 * kHeadDim) return launch_qk_mfma_small_ns<T, K, 2>(p, x, y, rpb, scale, logits, s);
     }
-    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
-                       static_cast<const T *>(x), static_cast<const T *>(y), static_cast<const T *>(rpb), scale,
-                       static_cast<T *>(logits), p.H, p.W, p.heads, tiles_x, tiles_y, ntiles, tiles_per_wg);
-    return hipGetLastError();
+    return launch_qk_mfma_small_ns<T, K, 1>(p, x, y, rpb, scale, logits, s);
 }
 
 bool qk_mfma_supported(const Problem &p) {
@@ -553,16 +330,10 @@ hipError_t launch_qk_mfma(const Problem &p, const void *x, const void *y, const 
                           hipStream_t s) {
     if (p.dtype == NA2D_F16) {
         using T = f16_t;
-        if (p.K == 3) return launch_qk_mfma_small_t<T, 3>(p, x, y, rpb, scale, logits, s);
-        if (p.K == 5) return launch_qk_mfma_small_t<T, 5>(p, x, y, rpb, scale, logits, s);
-        if (p.K == 7) return launch_qk_mfma_small_t<T, 7>(p, x, y, rpb, scale, logits, s);
-        NA2D_DISPATCH_K(p.K, return (launch_qk_mfma_t<T, K>(p, x, y, rpb, scale, logits, s)));
+        NA2D_DISPATCH_K(p.K, return (launch_qk_mfma_small_t<T, K>(p, x, y, rpb, scale, logits, s)));
     } else if (p.dtype == NA2D_BF16) {
         using T = bf16_t;
-        if (p.K == 3) return launch_qk_mfma_small_t<T, 3>(p, x, y, rpb, scale, logits, s);
-        if (p.K == 5) return launch_qk_mfma_small_t<T, 5>(p, x, y, rpb, scale, logits, s);
-        if (p.K == 7) return launch_qk_mfma_small_t<T, 7>(p, x, y, rpb, scale, logits, s);
-        NA2D_DISPATCH_K(p.K, return (launch_qk_mfma_t<T, K>(p, x, y, rpb, scale, logits, s)));
+        NA2D_DISPATCH_K(p.K, return (launch_qk_mfma_small_t<T, K>(p, x, y, rpb, scale, logits, s)));
     }
     return hipErrorInvalidValue;
 }
