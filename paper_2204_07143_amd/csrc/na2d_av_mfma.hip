@@ -2,224 +2,8 @@
 //   out[n, :] = scale * sum_{a, c} w[n, a, c] * y_{rho(n; a, c)}
 // (arXiv 2204.07143, Eq. 3-4; with w = ds, y = k it is grad-q, Appendix A).
 //
-// Same tiling as the matrix-core logits kernel: persistent workgroups walk 16 x (4*WAVES) query
-// tiles, a wave owns a strip of four 4 x 4 query patches, and a patch against its halo is a
-// dense contraction -- here over the halo positions:  out^T[d, q] = sum_pos Yt[d, pos] * P[pos, q].
-//   A operand: the values, staged transposed in LDS as Yt[channel][halo position] (8-byte reads
-//              of 4 consecutive positions; two 16-position blocks feed one 16x16x32 MFMA);
-//   B operand: the patch's weights spread over the halo positions, gathered from the tile's
-//              weight rows in LDS through a per-lane table of LDS addresses (positions outside a
-//              query's window read a zero word).  The table depends only on the lane and on the
-//              border shift of the window and is rebuilt only when that changes;
-//   result   : lane (query j, group g) holds channels 16*half + 4g .. +3 of its own query, so the
-//              scale and the 8-byte global stores need no cross-lane traffic.
-// The next tile's values and weight rows are prefetched into registers while the current tile is
-// computed.
-#include "na2d_kernels.hpp"
-#include "na2d_mfma.hpp"
-#include "na2d_tile.hpp"
-
-namespace na2d {
-
-template <typename T, int K, int WAVES>
-struct AvMfmaCfg {
-    using P = PatchT<K>;
-    static constexpr int TY = 4 * WAVES;
-    static constexpr int HALO_H = 4 * (WAVES - 1) + P::ROWS;   // farthest strip offset + rows the enumeration touches
-    static constexpr int HALO_W = 12 + P::PWP;                 // farthest patch offset + padded patch-halo width
-    static constexpr int KK = K * K;
-    static constexpr int kThreads = kWave * WAVES;
-    using Halo = TransposedHalo<T, HALO_H, HALO_W, kThreads>;
-    static constexpr int kRowBytes = kTileX * KK * (int)sizeof(T);
-    static constexpr int kRowRegion = mirror_bytes(kRowBytes);
-    static constexpr int kPatchStep = 4 * KK * (int)sizeof(T);
-    static constexpr int kZeroBytes = (3 * kPatchStep + 16 + 15) & ~15;   // what out-of-window table entries read
-    static constexpr int kWaveBytes = 4 * kRowRegion + kZeroBytes;
-    static constexpr int kLdsBytes = Halo::kBytes + WAVES * kWaveBytes;
-};
-
-template <typename T, int K>
-constexpr int av_mfma_waves() {
-    return AvMfmaCfg<T, K, 4>::kLdsBytes <= 80 * 1024 ? 4 : 2;
-}
-
-struct AvTile {
-    int ty0, tx0, plane, hoy, hox;
-};
-
-template <typename T, int K, int WAVES>
-__global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void av_mfma_kernel(const T *__restrict__ w,
-                                                                                    const T *__restrict__ y, float scale,
-                                                                                    T *__restrict__ out, int H, int W,
-                                                                                    int tiles_x, int tiles_y, int ntiles,
-                                                                                    int tiles_per_wg) {
-    using C = AvMfmaCfg<T, K, WAVES>;
-    using P = PatchT<K>;
-    using Halo = typename C::Halo;
-    constexpr int SZ = (int)sizeof(T);
-    extern __shared__ __align__(16) char lds[];
-
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-    const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
-    const int lds0 = lds_addr(lds);
-    const int wreg_off = lds0 + Halo::kBytes + wave * C::kWaveBytes;
-    char *wreg = lds + Halo::kBytes + wave * C::kWaveBytes;
-    const int zero_addr = wreg_off + 4 * C::kRowRegion;
-    for (int i = lane * 4; i < C::kZeroBytes; i += kWave * 4) *lds_ptr<uint32_t>(zero_addr + i) = 0u;
-
-    // A-operand addresses of this lane (channel j of a half, positions 16b + 4g .. +3), relative
-    // to the patch origin inside the tile halo
-    int vtoff[P::NBLK];
-#pragma unroll
-    for (int b = 0; b < P::NBLK; ++b) {
-        const int h0 = 16 * b + 4 * g;
-        const int hy = P::row_of(h0), hx0 = h0 - hy * P::PWP;
-        vtoff[b] = lds0 + j * Halo::DSTRIDE + (hy * C::HALO_W + hx0) * 2;
-    }
-    int gaddr[P::NEL];
-#pragma unroll
-    for (int e = 0; e < P::NEL; ++e) gaddr[e] = zero_addr;
-    int cur_wy = -100000, cur_wx = -100000, cur_base = 0;
-
-    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
-    const int t_begin = wg * tiles_per_wg;
-    const int t_end = (wg + 1) * tiles_per_wg < ntiles ? (wg + 1) * tiles_per_wg : ntiles;
-    if (t_begin >= t_end) return;
-
-    auto tile_of = [&](int t) {
-        const TileCoord tc = decode_tile(t, tiles_x, tiles_y);
-        AvTile q;
-        q.ty0 = tc.tiy * C::TY;
-        q.tx0 = tc.tix * kTileX;
-        q.plane = tc.plane;
-        q.hoy = halo_origin(q.ty0, C::TY, H, K);
-        q.hox = halo_origin(q.tx0, kTileX, W, K);
-        return q;
-    };
-
-    Halo halo;
-    halo.init(W, tid, lds0);
-    StageIn<T, C::kRowBytes, kWave> rows_in[4];
-    auto prefetch = [&](const AvTile &tl) {
-        const size_t plane_q = (size_t)tl.plane * H * W;
-        halo.issue(reinterpret_cast<const char *>(y) + plane_q * Traits<T>::kKeyBytes, H, W, tl.hoy, tl.hox);
-        const int nvalid = (W - tl.tx0) < kTileX ? (W - tl.tx0) : kTileX;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int qy = tl.ty0 + 4 * wave + r;
-            const size_t g0r = (plane_q + (size_t)(qy < H ? qy : 0) * W + tl.tx0) * C::KK * SZ;
-            rows_in[r].issue(reinterpret_cast<const char *>(w), g0r, qy < H ? nvalid * C::KK * SZ : 0, lane);
-        }
-    };
-
-    AvTile cur = tile_of(t_begin);
-    prefetch(cur);
-
-    for (int t = t_begin; t < t_end; ++t) {
-        const int ty0 = cur.ty0, tx0 = cur.tx0, hoy = cur.hoy, hox = cur.hox;
-        const size_t plane_q = (size_t)cur.plane * H * W;
-        __syncthreads();   // every wave is done with the previous tile's values
-        halo.commit();
-#pragma unroll
-        for (int r = 0; r < 4; ++r) rows_in[r].commit(wreg + r * C::kRowRegion, lane);
-        __syncthreads();
-        if (t + 1 < t_end) {
-            cur = tile_of(t + 1);
-            prefetch(cur);
-        }
-
-        const int sy0 = ty0 + 4 * wave;
-        if (sy0 >= H) continue;
-        const int oy = halo_origin(sy0, 4, H, K);
-        const int qy = sy0 + jy;
-        const bool row_ok = qy < H;
-        const size_t rowg0 = (plane_q + (size_t)qy * W + tx0) * C::KK * SZ;
-        const int lanebase = wreg_off + jy * C::kRowRegion + (int)(rowg0 & 15) + jx * C::KK * SZ;
-        const int wy = row_ok ? win_start(qy, H, K) - oy : 100000;
-
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int px0 = tx0 + 4 * p;
-            if (px0 < W) {
-                const int ox = halo_origin(px0, 4, W, K);
-                const int qx = px0 + jx;
-                const bool q_ok = row_ok && qx < W;
-                const int want_wy = q_ok ? wy : 100000;
-                const int want_wx = q_ok ? win_start(qx, W, K) - ox : 100000;
-                if (__any(want_wy != cur_wy || want_wx != cur_wx || lanebase != cur_base)) {
-                    cur_wy = want_wy;
-                    cur_wx = want_wx;
-                    cur_base = lanebase;
-                    int gv = g;
-                    asm volatile("" : "+v"(gv));   // keep the index arithmetic inside this rare block
-#pragma unroll
-                    for (int e = 0; e < P::NEL; ++e) {
-                        const int h = 16 * (e >> 2) + 4 * gv + (e & 3);
-                        const int hy = P::row_of(h), hx = h - hy * P::PWP;
-                        const int a = hy - want_wy, c = hx - want_wx;
-                        const bool ok = (unsigned)a < (unsigned)K && (unsigned)c < (unsigned)K;
-                        gaddr[e] = ok ? lanebase + (a * K + c) * SZ : zero_addr;
-                    }
-                }
-                const int patch_off = ((oy - hoy) * C::HALO_W + (ox - hox)) * 2;
-                const bool aligned = (patch_off & 7) == 0;
-                f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-                for (int pb = 0; pb < P::NPAIR; ++pb) {
-                    // weights of this lane's query at positions 16b + 4g + r of the two blocks
-                    uint32_t wv[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int e = 8 * pb + 2 * u;
-                        const uint32_t lo = *lds_ptr<uint16_t>(gaddr[e] + p * C::kPatchStep);
-                        const uint32_t hi = *lds_ptr<uint16_t>(gaddr[e + 1] + p * C::kPatchStep);
-                        wv[u] = lo | (hi << 16);
-                    }
-                    const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
-#pragma unroll
-                    for (int hf = 0; hf < 2; ++hf) {
-                        const int a0 = vtoff[2 * pb] + patch_off + hf * 16 * Halo::DSTRIDE;
-                        const int a1 = vtoff[2 * pb + 1] + patch_off + hf * 16 * Halo::DSTRIDE;
-                        u32x4 aop;
-                        if (aligned) {
-                            const uint64_t lo = *lds_ptr<uint64_t>(a0);
-                            const uint64_t hi = *lds_ptr<uint64_t>(a1);
-                            aop = u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
-                        } else {
-                            uint32_t q4[4];
-#pragma unroll
-                            for (int u = 0; u < 2; ++u) {
-                                q4[u] = (uint32_t)*lds_ptr<uint16_t>(a0 + 4 * u) | ((uint32_t)*lds_ptr<uint16_t>(a0 + 4 * u + 2) << 16);
-                                q4[2 + u] = (uint32_t)*lds_ptr<uint16_t>(a1 + 4 * u) | ((uint32_t)*lds_ptr<uint16_t>(a1 + 4 * u + 2) << 16);
-                            }
-                            aop = u32x4{q4[0], q4[1], q4[2], q4[3]};
-                        }
-                        acc[hf] = mfma_16x16x32<T>(aop, bop, acc[hf]);
-                    }
-                }
-                if (q_ok) {
-                    char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes + g * 8;
-#pragma unroll
-                    for (int hf = 0; hf < 2; ++hf) {
-                        uint32_t o[2];
-#pragma unroll
-                        for (int u = 0; u < 2; ++u) {
-                            const T lo = from_f32<T>(acc[hf][2 * u] * scale), hi = from_f32<T>(acc[hf][2 * u + 1] * scale);
-                            o[u] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
-                        }
-                        *reinterpret_cast<uint64_t *>(dst + hf * 32) = (uint64_t)o[0] | ((uint64_t)o[1] << 32);
-                    }
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // the weight rows of this strip are consumed; the next commit may overwrite them
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-    }
-}
-
-// ---- small windows (K <= 7): one patch per wave, operands loaded straight into LDS -----------
+// A 4 x 4 patch of queries against its halo is a dense contraction over the halo positions:
+//   out^T[d, q] = sum_pos Y^T[d, pos] * P[pos, q].
 //
 // Eight waves share a 16 x 8 query tile, one 4 x 4 patch each.  A workgroup keeps one tile position
 // and one head and walks a range of the batch: the per-lane gather addresses of the weights and
@@ -231,6 +15,12 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void av_mfma_kern
 //   A operand: channel j of those positions, two transposing LDS reads from the value halo;
 //   B operand: the weights of query j at those positions, 2-byte gathers from its row run (zero
 //              outside its window).
+#include "na2d_kernels.hpp"
+#include "na2d_mfma.hpp"
+#include "na2d_tile.hpp"
+
+namespace na2d {
+
 template <typename T, int K>
 struct AvSmallCfg {
     using P = Patch<K>;
@@ -247,20 +37,23 @@ struct AvSmallCfg {
     static constexpr int kRowBytes = kTileX * KK * (int)sizeof(T);
     static constexpr int kRowRegion = mirror_bytes(kRowBytes);
     static constexpr int kRowChunks = (kRowBytes + 15 + 15) / 16;   // 16-byte chunks a run can touch
-    static_assert(kRowChunks <= 2 * kWave, "a row run is loaded by two instructions of one wave");
+    static constexpr int kRowPasses = (kRowChunks + kWave - 1) / kWave;   // load instructions of one wave per row run
     static constexpr int kWBytes = TY * kRowRegion;
     static constexpr int kStageBytes = kHaloBytes + kWBytes + 16;   // + the zero word
     static constexpr int kLdsStages = 2 * kStageBytes;
-    static constexpr int kRpbBytes = WAVES * (2 * K - 1) * (2 * K - 1) * 4;   // per-wave bias-gradient tables (grad-b variant)
+    // per-wave bias-gradient tables (the grad-b variant exists for k <= 7 only)
+    static constexpr int kRpbBytes = K <= 7 ? WAVES * (2 * K - 1) * (2 * K - 1) * 4 : 0;
     static constexpr int kLdsBytes = kLdsStages + kRpbBytes;
-    static_assert(kStageBytes < 65536, "the second stage is reached through the 16-bit offset of the LDS reads");
+    static constexpr int kWavesPerSimd = kLdsBytes <= 80 * 1024 ? 4 : 2;   // two workgroups, or one, per compute unit
+    static_assert(K > 7 || kStageBytes < 65536, "the second stage is reached through the 16-bit offset of the LDS reads");
+    static_assert(kWBytes + 16 <= 65536, "offsets inside a stage's weight rows fit 16 bits");
 };
 
 // RPB: the kernel also sums the weights it gathers, per lane and halo position, over its planes; at
 // the end the workgroup adds them up per cell of the (2K-1)^2 bias table in a fixed order and writes
 // one partial bias gradient (with w = ds this is grad-b, arXiv 2204.07143 Appendix A; Eq. 2's B).
 template <typename T, int K, bool RPB>
-__global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restrict__ w, const T *__restrict__ y, float scale,
+__global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfma_small_kernel(const T *__restrict__ w, const T *__restrict__ y, float scale,
                                                                T *__restrict__ out, float *__restrict__ rpb_partial, int H,
                                                                int W, int heads, int nb, int tiles_y, int units, int splits,
                                                                int pitch) {
@@ -322,7 +115,7 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
             const size_t left = w_bytes - (g0 - mis);   // bytes up to the end of the tensor
             const int region = w0 + par * C::kStageBytes + wave * C::kRowRegion;
 #pragma unroll
-            for (int it = 0; it < 2; ++it) {
+            for (int it = 0; it < C::kRowPasses; ++it) {
                 const int c = lane + it * kWave;
                 if (c < nchunks) {
                     if ((size_t)(c + 1) * 16 <= left) {
@@ -362,10 +155,14 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
     // the query's window are in one halo row (a halo row holds K + 3 positions, the window K of them),
     // normally the row of the group's first position; when that position is already right of the window,
     // the group runs on into the next halo row and only that part can be inside.
-    int gaddr[P::NEL];   // the padding block of the last pair has no entries: its weights are zero
+    // Large windows (up to 64 weights per lane) keep the addresses two per register, as 16-bit offsets from the
+    // start of the stage's weight rows and without the phase, which is added when they are used: the entry of
+    // a position outside the window is the zero area, sixteen zero bytes, so that it reads zero at any phase.
+    constexpr bool PACKED = K > 7;
+    int gaddr[PACKED ? P::NEL / 2 : P::NEL];   // the padding block of the last pair has no entries: its weights are zero
     {
         const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
-        const int lane_row = w0 + (4 * strip + jy) * C::kRowRegion + phase0 + (4 * p + jx) * C::KK * SZ;
+        const int lane_row = w0 + (4 * strip + jy) * C::kRowRegion + (PACKED ? 0 : phase0) + (4 * p + jx) * C::KK * SZ;
 #pragma unroll
         for (int G = 0; G < P::NBLK; ++G) {
             const int h0 = 16 * G + 4 * g;
@@ -375,8 +172,16 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
             int c0 = hx0 - (wrap ? P::PW : 0) - wx;   // window column of the group's first position (may be negative)
             const int base = lane_row + (a * K + c0) * SZ;
             c0 = (q_ok && (unsigned)a < (unsigned)K) ? c0 : 64;   // no row of the window: every column test fails
+            int ga[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) gaddr[4 * G + i] = (unsigned)(c0 + i) < (unsigned)K ? base + i * SZ : zero_addr;
+            for (int i = 0; i < 4; ++i) ga[i] = (unsigned)(c0 + i) < (unsigned)K ? base + i * SZ : zero_addr;
+            if constexpr (PACKED) {
+                gaddr[2 * G] = (ga[0] - w0) | ((ga[1] - w0) << 16);
+                gaddr[2 * G + 1] = (ga[2] - w0) | ((ga[3] - w0) << 16);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) gaddr[4 * G + i] = ga[i];
+            }
         }
     }
     const int qlin = (qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1);
@@ -437,8 +242,15 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
                     wv[u] = 0u;
                     continue;
                 }
-                wv[u] = (uint32_t)*lds_ptr<uint16_t>(gaddr[e] + PAR * C::kStageBytes) |
-                        ((uint32_t)*lds_ptr<uint16_t>(gaddr[e + 1] + PAR * C::kStageBytes) << 16);
+                if constexpr (PACKED) {   // e is even: both addresses sit in one register
+                    const uint32_t pk = (uint32_t)gaddr[e >> 1];
+                    const int wbase = w0 + cur_phase + PAR * C::kStageBytes;
+                    wv[u] = (uint32_t)*lds_ptr<uint16_t>(wbase + (int)(pk & 0xffffu)) |
+                            ((uint32_t)*lds_ptr<uint16_t>(wbase + (int)(pk >> 16)) << 16);
+                } else {
+                    wv[u] = (uint32_t)*lds_ptr<uint16_t>(gaddr[e] + PAR * C::kStageBytes) |
+                            ((uint32_t)*lds_ptr<uint16_t>(gaddr[e + 1] + PAR * C::kStageBytes) << 16);
+                }
             }
             const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
 #pragma unroll
@@ -471,8 +283,10 @@ __global__ __launch_bounds__(512, 4) void av_mfma_small_kernel(const T *__restri
         if (phase_varies) {   // the table follows the phase of this plane's row run (in-window entries only)
             const int ph = phase_of(b), d = ph - cur_phase;
             cur_phase = ph;
+            if constexpr (!PACKED) {
 #pragma unroll
-            for (int e = 0; e < P::NEL; ++e) gaddr[e] += gaddr[e] != zero_addr ? d : 0;
+                for (int e = 0; e < P::NEL; ++e) gaddr[e] += gaddr[e] != zero_addr ? d : 0;
+            }
         }
         compute(par_c, b);
         if constexpr (RPB) row_sums(par_c, b);
@@ -500,7 +314,8 @@ template <typename T, int K, bool RPB = false>
 static hipError_t launch_av_mfma_small_t(const Problem &p, const void *w, const void *y, float scale, void *out,
                                          hipStream_t s, float *rpb_partial = nullptr) {
     using C = AvSmallCfg<T, K>;
-    static_assert(C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+    static_assert(K > 7 || C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+    static_assert(C::kLdsBytes <= 160 * 1024, "LDS of a compute unit");
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
     auto kern = av_mfma_small_kernel<T, K, RPB>;
@@ -547,49 +362,18 @@ hipError_t launch_av_rpb(const Problem &p, const void *w, const void *y, float s
     return hipErrorInvalidValue;
 }
 
-template <typename T, int K>
-static hipError_t launch_av_mfma_t(const Problem &p, const void *w, const void *y, float scale, void *out,
-                                   hipStream_t s) {
-    constexpr int WAVES = av_mfma_waves<T, K>();
-    using C = AvMfmaCfg<T, K, WAVES>;
-    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
-    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
-    const int ntiles = tiles_x * tiles_y * p.planes();
-    const int max_wgs = 256 * 2;
-    const int tiles_per_wg = (ntiles + max_wgs - 1) / max_wgs;
-    const int nwg = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
-    auto kern = av_mfma_kernel<T, K, WAVES>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
-                       static_cast<const T *>(w), static_cast<const T *>(y), scale, static_cast<T *>(out), p.H, p.W,
-                       tiles_x, tiles_y, ntiles, tiles_per_wg);
-    return hipGetLastError();
-}
-
 bool av_mfma_supported(const Problem &p) {
-    if (p.dtype == NA2D_F32 || force_valu()) return false;
-    return p.D == kHeadDim || (p.D % kHeadDim == 0 && p.K <= 7);   // slices only in the small-window kernel
+    // any multiple of 32 channels: one launch per 32-channel slice
+    return p.dtype != NA2D_F32 && !force_valu() && p.D % kHeadDim == 0;
 }
 
 hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s) {
     if (p.dtype == NA2D_F16) {
         using T = f16_t;
-        if (p.K == 3) return launch_av_mfma_small_t<T, 3>(p, w, y, scale, out, s);
-        if (p.K == 5) return launch_av_mfma_small_t<T, 5>(p, w, y, scale, out, s);
-        if (p.K == 7) return launch_av_mfma_small_t<T, 7>(p, w, y, scale, out, s);
-        NA2D_DISPATCH_K(p.K, return (launch_av_mfma_t<T, K>(p, w, y, scale, out, s)));
+        NA2D_DISPATCH_K(p.K, return (launch_av_mfma_small_t<T, K>(p, w, y, scale, out, s)));
     } else if (p.dtype == NA2D_BF16) {
         using T = bf16_t;
-        if (p.K == 3) return launch_av_mfma_small_t<T, 3>(p, w, y, scale, out, s);
-        if (p.K == 5) return launch_av_mfma_small_t<T, 5>(p, w, y, scale, out, s);
-        if (p.K == 7) return launch_av_mfma_small_t<T, 7>(p, w, y, scale, out, s);
-        NA2D_DISPATCH_K(p.K, return (launch_av_mfma_t<T, K>(p, w, y, scale, out, s)));
+        NA2D_DISPATCH_K(p.K, return (launch_av_mfma_small_t<T, K>(p, w, y, scale, out, s)));
     }
     return hipErrorInvalidValue;
 }
