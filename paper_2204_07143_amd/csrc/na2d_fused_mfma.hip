@@ -2,298 +2,18 @@
 //   out_n = softmax_{a,c}( scale * <q_n, k_{rho(n;a,c)}> + B(n, rho(n;a,c)) ) . v_{rho(n;a,c)}
 // (arXiv 2204.07143, Eq. 2-4 in one kernel; the k*k logits and weights never leave the chip).
 //
-// Persistent workgroups walk 16 x (4*WAVES) query tiles; a wave owns a strip of four 4 x 4 query
-// patches.  For one patch and the (K+3)^2 halo positions its windows can touch:
-//   1. S^T = K_halo * Q^T    one 16x16x32 MFMA per block of 16 halo positions (keys row-major in
-//                            LDS, queries straight from global memory);
+// For one 4 x 4 patch of queries and the (K+3)^2 halo positions its windows can touch:
+//   1. S^T = K_halo * Q^T    one 16x16x32 MFMA per block of 16 halo positions (keys in their natural
+//                            layout in LDS, queries straight from global memory);
 //   2. logits               one fma per result against a per-lane table that holds the bias of
 //                            (query, position) and -inf where the position is outside the query's
 //                            window (scale and bias are pre-multiplied by log2 e);
-//   3. softmax              row max and row sum: 31 register ops plus two cross-lane steps each
+//   3. softmax              row max and row sum in registers plus two cross-lane steps each
 //                            (a query's positions are spread over 4 lanes), exp2 in fp32;
 //   4. O^T = V_halo^T * P    the un-normalised weights, converted to the storage type, are already
-//                            in the B-operand layout of the next MFMA; values come from LDS staged
-//                            transposed (Vt[channel][position], 8-byte reads);
+//                            in the B-operand layout of the next MFMA; values through the
+//                            transposing LDS read;
 //   5. out = O / sum, lse    each lane owns 8 channels of its own query: no cross-lane traffic.
-// The next tile's keys, values and queries are prefetched into registers during the current tile.
-#include "na2d_kernels.hpp"
-#include "na2d_mfma.hpp"
-#include "na2d_tile.hpp"
-
-namespace na2d {
-
-template <typename T, int K, int WAVES>
-struct FusedMfmaCfg {
-    using P = PatchT<K>;
-    static constexpr int TY = 4 * WAVES;
-    // Positions past the patch halo (padding of the last block) are redirected to real ones, so
-    // the tile halo only needs the PW rows of the farthest strip.
-    static constexpr int HALO_H = 4 * (WAVES - 1) + P::PW;
-    static constexpr int HALO_W = 12 + P::PWP;        // row pitch of the LDS images
-    static constexpr int HALO_COLS = kTileX + K - 1;  // columns that hold halo data (the rest stays zero)
-    static constexpr int NB = 2 * K - 1;
-    static constexpr int kThreads = kWave * WAVES;
-    using VHalo = TransposedHalo<T, HALO_H, HALO_COLS, kThreads, HALO_W>;
-    using KHalo = HaloPrefetch<T, HALO_H, HALO_COLS, kThreads, HALO_W>;
-    static constexpr int kKBytes = HALO_H * HALO_W * Traits<T>::kKeyStride;
-    static constexpr int kBiasBytes = ((NB * NB * 4) + 15) & ~15;
-    static constexpr int kLdsBytes = kKBytes + VHalo::kBytes + kBiasBytes;
-};
-
-template <typename T, int K>
-constexpr int fused_mfma_waves() {
-    return FusedMfmaCfg<T, K, 4>::kLdsBytes <= 80 * 1024 ? 4 : 2;
-}
-
-struct FusedTile {
-    int ty0, tx0, plane, hoy, hox;
-};
-
-// two floats -> one register of two storage-type values (round to nearest even; one packed
-// conversion instruction on gfx950)
-template <typename T> __device__ __forceinline__ uint32_t pack2(float a, float b) {
-    typedef float f32x2_t __attribute__((ext_vector_type(2)));
-    typedef T tx2_t __attribute__((ext_vector_type(2)));
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){a, b}, tx2_t));
-}
-
-template <typename T, int K, int WAVES>
-__global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void fused_mfma_kernel(
-    const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, const T *__restrict__ rpb, float scale,
-    T *__restrict__ out, float *__restrict__ lse, int H, int W, int heads, int tiles_x, int tiles_y, int ntiles,
-    int tiles_per_wg) {
-    using C = FusedMfmaCfg<T, K, WAVES>;
-    using P = PatchT<K>;
-    using VHalo = typename C::VHalo;
-    using KHalo = typename C::KHalo;
-    constexpr int STRIDE = Traits<T>::kKeyStride;
-    constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
-    extern __shared__ __align__(16) char lds[];
-    char *k_lds = lds;
-    float *bias_lds = reinterpret_cast<float *>(lds + C::kKBytes + VHalo::kBytes);
-
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-    const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
-    const int lds0 = lds_addr(lds);
-    const int vt0 = lds0 + C::kKBytes;
-
-    // Operand addresses of this lane relative to the patch origin inside the tile halo.
-    int koff[P::NBLK];    // keys: position 16b + j, bytes [16g, 16g + 16)
-    int vtoff[P::NBLK];   // values: channel j of a half, positions 16b + 4g .. +3
-#pragma unroll
-    for (int b = 0; b < P::NBLK; ++b) {
-        int h = 16 * b + j;
-        h = h < P::NPOS ? h : P::NPOS - 1;
-        int hy = P::row_of(h), hx = h - hy * P::PWP;
-        koff[b] = lds0 + (hy * C::HALO_W + hx) * STRIDE + g * 16;
-        int h0 = 16 * b + 4 * g;
-        h0 = h0 <= P::NPOS - 4 ? h0 : P::NPOS - 4;
-        hy = P::row_of(h0);
-        hx = h0 - hy * P::PWP;
-        vtoff[b] = vt0 + j * VHalo::DSTRIDE + (hy * C::HALO_W + hx) * 2;
-    }
-
-    // log2(e) * bias of (this lane's query, position), -inf outside the window; kept as packed
-    // fp16 pairs (half the registers; the fma below reads them as mixed-precision operands)
-    f16x2 biasm[P::NEL / 2];
-#pragma unroll
-    for (int e = 0; e < P::NEL / 2; ++e) biasm[e] = f16x2{(f16_t)-INFINITY, (f16_t)-INFINITY};
-    int cur_key = -1, cur_wy = -100000, cur_wx = -100000, lds_head = -1;
-
-    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
-    const int t_begin = wg * tiles_per_wg;
-    const int t_end = (wg + 1) * tiles_per_wg < ntiles ? (wg + 1) * tiles_per_wg : ntiles;
-    if (t_begin >= t_end) return;
-
-    auto tile_of = [&](int t) {
-        const TileCoord tc = decode_tile(t, tiles_x, tiles_y);
-        FusedTile f;
-        f.ty0 = tc.tiy * C::TY;
-        f.tx0 = tc.tix * kTileX;
-        f.plane = tc.plane;
-        f.hoy = halo_origin(f.ty0, C::TY, H, K);
-        f.hox = halo_origin(f.tx0, kTileX, W, K);
-        return f;
-    };
-
-    // The pitch padding of both LDS images is read for positions outside every window (their
-    // weights are exactly zero), so it must hold finite numbers: zero it once.
-    for (int i = tid * 16; i < C::kKBytes + VHalo::kBytes; i += C::kThreads * 16)
-        *lds_ptr<u32x4>(lds0 + i) = u32x4{0u, 0u, 0u, 0u};
-    __syncthreads();
-
-    KHalo khalo;
-    VHalo vhalo;
-    khalo.init(W, tid);
-    vhalo.init_lds(tid, vt0);
-    u32x4 qnext[4];
-    auto prefetch = [&](const FusedTile &tl) {
-        const size_t plane_q = (size_t)tl.plane * H * W;
-        khalo.issue(reinterpret_cast<const char *>(k) + plane_q * Traits<T>::kKeyBytes, H, W, tl.hoy, tl.hox);
-        vhalo.issue_like(khalo.goff, khalo.pos, reinterpret_cast<const char *>(v) + plane_q * Traits<T>::kKeyBytes, H, W,
-                         tl.hoy, tl.hox);
-        const int qy = tl.ty0 + 4 * wave + jy;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int qx = tl.tx0 + 4 * p + jx;
-            qnext[p] = u32x4{0u, 0u, 0u, 0u};
-            if (qy < H && qx < W)
-                qnext[p] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(q) +
-                                                            (plane_q + (size_t)qy * W + qx) * Traits<T>::kKeyBytes + g * 16);
-        }
-    };
-
-    FusedTile cur = tile_of(t_begin);
-    prefetch(cur);
-    const float scale2 = scale * kLog2e;
-
-    for (int t = t_begin; t < t_end; ++t) {
-        const int ty0 = cur.ty0, tx0 = cur.tx0, hoy = cur.hoy, hox = cur.hox;
-        const size_t plane_q = (size_t)cur.plane * H * W;
-        const int head = cur.plane % heads;
-        __syncthreads();   // every wave is done with the previous tile's keys and values
-        khalo.commit(k_lds);
-        vhalo.commit();
-        if (head != lds_head) {
-            lds_head = head;
-            for (int i = tid; i < C::NB * C::NB; i += C::kThreads)
-                bias_lds[i] = rpb ? kLog2e * to_f32(rpb[(size_t)head * C::NB * C::NB + i]) : 0.f;
-            cur_key = -1;
-        }
-        u32x4 qreg[4];
-#pragma unroll
-        for (int p = 0; p < 4; ++p) qreg[p] = qnext[p];
-        __syncthreads();
-        if (t + 1 < t_end) {
-            cur = tile_of(t + 1);
-            prefetch(cur);
-        }
-
-        const int sy0 = ty0 + 4 * wave;
-        if (sy0 >= H) continue;
-        const int oy = halo_origin(sy0, 4, H, K);
-        const int dy = oy - (sy0 - P::R);
-        const int qy = sy0 + jy;
-        const bool row_ok = qy < H;
-        const int wy = row_ok ? win_start(qy, H, K) - oy : 100000;
-
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int px0 = tx0 + 4 * p;
-            if (px0 < W) {
-                const int ox = halo_origin(px0, 4, W, K);
-                const int dx = ox - (px0 - P::R);
-                const int qx = px0 + jx;
-                const bool q_ok = row_ok && qx < W;
-                const int want_wy = q_ok ? wy : 100000;
-                const int want_wx = q_ok ? win_start(qx, W, K) - ox : 100000;
-                const int key = (head * 16 + dy + 8) * 16 + dx + 8;
-                if (__any(key != cur_key || want_wy != cur_wy || want_wx != cur_wx)) {
-                    cur_key = key;
-                    cur_wy = want_wy;
-                    cur_wx = want_wx;
-                    int gv = g;
-                    asm volatile("" : "+v"(gv));   // keep the index arithmetic inside this rare block
-#pragma unroll
-                    for (int e = 0; e < P::NEL; ++e) {
-                        const int h = 16 * (e >> 2) + 4 * gv + (e & 3);
-                        const int hy = P::row_of(h), hx = h - hy * P::PWP;
-                        const int a = hy - want_wy, c = hx - want_wx;
-                        const bool ok = h < P::NPOS && (unsigned)a < (unsigned)K && (unsigned)c < (unsigned)K;
-                        int u = hy - jy + P::R + dy, vv = hx - jx + P::R + dx;
-                        u = u < 0 ? 0 : (u > C::NB - 1 ? C::NB - 1 : u);
-                        vv = vv < 0 ? 0 : (vv > C::NB - 1 ? C::NB - 1 : vv);
-                        biasm[e >> 1][e & 1] = (f16_t)(ok ? bias_lds[u * C::NB + vv] : -INFINITY);
-                    }
-                }
-                const int kpatch = ((oy - hoy) * C::HALO_W + (ox - hox)) * STRIDE;
-                const int vpatch = ((oy - hoy) * C::HALO_W + (ox - hox)) * 2;
-                const bool aligned = (vpatch & 7) == 0;
-
-                // 1-2. logits in the exp2 domain
-                float s[P::NEL];
-#pragma unroll
-                for (int b = 0; b < P::NBLK; ++b) {
-                    const u32x4 a = *lds_ptr<u32x4>(koff[b] + kpatch);
-                    const f32x4 acc = mfma_16x16x32<T>(a, qreg[p], f32x4{0.f, 0.f, 0.f, 0.f});
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        s[4 * b + r] = __builtin_fmaf(scale2, acc[r], (float)biasm[(4 * b + r) >> 1][(4 * b + r) & 1]);
-                }
-                // 3. softmax over the query's window (spread over the 4 lanes j, j+16, j+32, j+48)
-                float m = s[0];
-#pragma unroll
-                for (int e = 1; e < P::NEL; ++e) m = fmaxf(m, s[e]);
-                m = fmaxf(m, __shfl_xor(m, 16));
-                m = fmaxf(m, __shfl_xor(m, 32));
-                m = q_ok ? m : 0.f;   // lanes without a query: keep the arithmetic finite
-                float l = 0.f;
-#pragma unroll
-                for (int e = 0; e < P::NEL; ++e) {
-                    s[e] = __builtin_amdgcn_exp2f(s[e] - m);
-                    l += s[e];
-                }
-                l += __shfl_xor(l, 16);
-                l += __shfl_xor(l, 32);
-                // 4. O^T = Vt * P
-                f32x4 o[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-                for (int pb = 0; pb < P::NPAIR; ++pb) {
-                    const u32x4 bop = u32x4{pack2<T>(s[8 * pb], s[8 * pb + 1]), pack2<T>(s[8 * pb + 2], s[8 * pb + 3]),
-                                            pack2<T>(s[8 * pb + 4], s[8 * pb + 5]), pack2<T>(s[8 * pb + 6], s[8 * pb + 7])};
-                    // bf16 keeps 8 significant bits: a second operand carries the rounding remainder of
-                    // the weights so that the product sees them to 16 bits
-                    u32x4 bop_lo = u32x4{0u, 0u, 0u, 0u};
-                    if constexpr (sizeof(T) == 2 && Traits<T>::kDtype == NA2D_BF16) {
-                        float rem[8];
-#pragma unroll
-                        for (int u = 0; u < 8; ++u) rem[u] = s[8 * pb + u] - to_f32(from_f32<T>(s[8 * pb + u]));
-                        bop_lo = u32x4{pack2<T>(rem[0], rem[1]), pack2<T>(rem[2], rem[3]), pack2<T>(rem[4], rem[5]),
-                                       pack2<T>(rem[6], rem[7])};
-                    }
-#pragma unroll
-                    for (int hf = 0; hf < 2; ++hf) {
-                        const int a0 = vtoff[2 * pb] + vpatch + hf * 16 * VHalo::DSTRIDE;
-                        const int a1 = vtoff[2 * pb + 1] + vpatch + hf * 16 * VHalo::DSTRIDE;
-                        u32x4 aop;
-                        if (aligned) {
-                            const uint64_t lo = *lds_ptr<uint64_t>(a0);
-                            const uint64_t hi = *lds_ptr<uint64_t>(a1);
-                            aop = u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
-                        } else {
-                            uint32_t q4[4];
-#pragma unroll
-                            for (int u = 0; u < 2; ++u) {
-                                q4[u] = (uint32_t)*lds_ptr<uint16_t>(a0 + 4 * u) | ((uint32_t)*lds_ptr<uint16_t>(a0 + 4 * u + 2) << 16);
-                                q4[2 + u] = (uint32_t)*lds_ptr<uint16_t>(a1 + 4 * u) | ((uint32_t)*lds_ptr<uint16_t>(a1 + 4 * u + 2) << 16);
-                            }
-                            aop = u32x4{q4[0], q4[1], q4[2], q4[3]};
-                        }
-                        o[hf] = mfma_16x16x32<T>(aop, bop, o[hf]);
-                        if constexpr (sizeof(T) == 2 && Traits<T>::kDtype == NA2D_BF16)
-                            o[hf] = mfma_16x16x32<T>(aop, bop_lo, o[hf]);
-                    }
-                }
-                // 5. normalise and store this lane's 8 channels of its own query
-                if (q_ok) {
-                    const float inv = 1.0f / l;
-                    const size_t qlin = plane_q + (size_t)qy * W + qx;
-                    char *dst = reinterpret_cast<char *>(out) + qlin * Traits<T>::kKeyBytes + g * 8;
-#pragma unroll
-                    for (int hf = 0; hf < 2; ++hf) {
-                        const uint32_t lo = pack2<T>(o[hf][0] * inv, o[hf][1] * inv);
-                        const uint32_t hi = pack2<T>(o[hf][2] * inv, o[hf][3] * inv);
-                        *reinterpret_cast<uint64_t *>(dst + hf * 32) = (uint64_t)lo | ((uint64_t)hi << 32);
-                    }
-                    if (lse != nullptr && g == 0) lse[qlin] = (m + __builtin_amdgcn_logf(l)) * kLn2;
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-}
-
-// ---- small windows (K <= 7): one patch per wave, halos loaded straight into LDS ---------------
 //
 // Eight waves share a 16 x 8 query tile, one 4 x 4 patch each (four waves per SIMD).  A workgroup
 // keeps one tile position and one head and walks a range of the batch, so the window mask, the bias
@@ -304,6 +24,20 @@ __global__ __launch_bounds__(kWave *WAVES, WAVES == 4 ? 2 : 1) void fused_mfma_k
 // positions, so the PV product contracts over positions without a transposed copy.  The halo
 // positions are numbered h = hy * (K+3) + hx; MFMA pair m of the PV product contracts over the
 // blocks 2m and 2m+1 of the logits, in the order the logits' MFMA left them in the lanes.
+#include "na2d_kernels.hpp"
+#include "na2d_mfma.hpp"
+#include "na2d_tile.hpp"
+
+namespace na2d {
+
+// two floats -> one register of two storage-type values (round to nearest even; one packed
+// conversion instruction on gfx950)
+template <typename T> __device__ __forceinline__ uint32_t pack2(float a, float b) {
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef T tx2_t __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){a, b}, tx2_t));
+}
+
 // NS: 32-channel slices of the head vector (head dim 32 NS).  Every slice of the key and of the value halo is
 // its own 64-byte-per-position image; the logits accumulate one MFMA per slice, the PV product runs per slice.
 template <typename T, int K, int NS = 1>
@@ -538,7 +272,7 @@ template <typename T, int K, int NS>
 static hipError_t launch_fused_mfma_small_ns(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
                                              float scale, void *out, float *lse, hipStream_t s) {
     using C = FusedSmallCfg<T, K, NS>;
-    static_assert(NS > 1 || C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+    static_assert(NS > 1 || K > 7 || C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
     static_assert(C::kLdsBytes <= 160 * 1024, "LDS of a compute unit");
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
@@ -560,34 +294,10 @@ static hipError_t launch_fused_mfma_small_ns(const Problem &p, const void *q, co
 template <typename T, int K>
 static hipError_t launch_fused_mfma_small_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
                                             float scale, void *out, float *lse, hipStream_t s) {
-    if (p.D == 2 * kHeadDim) return launch_fused_mfma_small_ns<T, K, 2>(p, q, k, v, rpb, scale, out, lse, s);
-    return launch_fused_mfma_small_ns<T, K, 1>(p, q, k, v, rpb, scale, out, lse, s);
-}
-
-template <typename T, int K>
-static hipError_t launch_fused_mfma_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
-                                      float scale, void *out, float *lse, hipStream_t s) {
-    constexpr int WAVES = fused_mfma_waves<T, K>();
-    using C = FusedMfmaCfg<T, K, WAVES>;
-    static_assert(C::kLdsBytes <= 160 * 1024, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
-    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
-    const int ntiles = tiles_x * tiles_y * p.planes();
-    const int max_wgs = 256 * 2;
-    const int tiles_per_wg = (ntiles + max_wgs - 1) / max_wgs;
-    const int nwg = (ntiles + tiles_per_wg - 1) / tiles_per_wg;
-    auto kern = fused_mfma_kernel<T, K, WAVES>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
+    if constexpr (K <= 7) {
+        if (p.D == 2 * kHeadDim) return launch_fused_mfma_small_ns<T, K, 2>(p, q, k, v, rpb, scale, out, lse, s);
     }
-    hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
-                       static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
-                       static_cast<const T *>(rpb), scale, static_cast<T *>(out), lse, p.H, p.W, p.heads, tiles_x,
-                       tiles_y, ntiles, tiles_per_wg);
-    return hipGetLastError();
+    return launch_fused_mfma_small_ns<T, K, 1>(p, q, k, v, rpb, scale, out, lse, s);
 }
 
 bool fused_mfma_supported(const Problem &p) {
@@ -599,16 +309,10 @@ hipError_t launch_fused_mfma(const Problem &p, const void *q, const void *k, con
                              void *out, float *lse, hipStream_t s) {
     if (p.dtype == NA2D_F16) {
         using T = f16_t;
-        if (p.K == 3) return launch_fused_mfma_small_t<T, 3>(p, q, k, v, rpb, scale, out, lse, s);
-        if (p.K == 5) return launch_fused_mfma_small_t<T, 5>(p, q, k, v, rpb, scale, out, lse, s);
-        if (p.K == 7) return launch_fused_mfma_small_t<T, 7>(p, q, k, v, rpb, scale, out, lse, s);
-        NA2D_DISPATCH_K(p.K, return (launch_fused_mfma_t<T, K>(p, q, k, v, rpb, scale, out, lse, s)));
+        NA2D_DISPATCH_K(p.K, return (launch_fused_mfma_small_t<T, K>(p, q, k, v, rpb, scale, out, lse, s)));
     } else if (p.dtype == NA2D_BF16) {
         using T = bf16_t;
-        if (p.K == 3) return launch_fused_mfma_small_t<T, 3>(p, q, k, v, rpb, scale, out, lse, s);
-        if (p.K == 5) return launch_fused_mfma_small_t<T, 5>(p, q, k, v, rpb, scale, out, lse, s);
-        if (p.K == 7) return launch_fused_mfma_small_t<T, 7>(p, q, k, v, rpb, scale, out, lse, s);
-        NA2D_DISPATCH_K(p.K, return (launch_fused_mfma_t<T, K>(p, q, k, v, rpb, scale, out, lse, s)));
+        NA2D_DISPATCH_K(p.K, return (launch_fused_mfma_small_t<T, K>(p, q, k, v, rpb, scale, out, lse, s)));
     }
     return hipErrorInvalidValue;
 }

@@ -75,112 +75,6 @@ __host__ __device__ __forceinline__ int halo_origin(int q0, int n, int L, int K)
     return o > lo ? o : lo;
 }
 
-// ---- operands whose contraction index is the key position ---------------------------------
-//
-// For out = sum_keys w * v (Eq. 3-4) and for the gradients that sum over queries, the MFMA
-// contraction runs over spatial positions, so the vectors (v, k, dout or q) are needed
-// "transposed": a lane must hold several consecutive positions of ONE channel.  They are
-// therefore staged in LDS as Xt[channel][halo position], written with 2-byte scatter stores
-// once per tile and read back as MFMA operands with 8-byte reads.
-//
-// Patch-halo enumeration for these kernels: h = hy * PWP + hx with the row width PWP = PW
-// rounded up to a multiple of 4, so that the 4 consecutive positions a lane needs never wrap
-// a halo row.  Columns PW..PWP-1 and the rows past PW are padding: their weights are zero and
-// their Xt entries are zero-filled.
-template <int K> struct PatchT {
-    static constexpr int R = K / 2;
-    static constexpr int PW = 4 + K - 1;
-    static constexpr int PWP = (PW + 3) & ~3;
-    static constexpr int NPOS = PW * PWP;
-    static constexpr int NPAIR = (NPOS + 31) / 32;   // pairs of 16-position blocks (one 16x16x32 MFMA each)
-    static constexpr int NBLK = 2 * NPAIR;
-    static constexpr int NEL = NBLK * 4;
-    static constexpr int ROWS = (32 * NPAIR + PWP - 1) / PWP;   // halo rows the enumeration can touch (>= PW)
-    static constexpr unsigned kMagic = (1u << 16) / PWP + 1;
-    __device__ static __forceinline__ int row_of(int h) { return (int)(((unsigned)h * kMagic) >> 16); }
-};
-
-// Transposed staging of a tile halo, split for software pipelining like HaloPrefetch: issue()
-// loads a thread's 16-byte chunks (8 channels of one position) into registers, zeros for
-// positions outside the map; commit() scatters each chunk into Xt[channel][position].
-// COLS columns are staged per halo row; PITCH >= COLS is the row pitch of the LDS image.
-template <typename T, int ROWS, int COLS, int NTHREADS, int PITCH = COLS>
-struct TransposedHalo {
-    static_assert(sizeof(T) == 2, "transposed staging is for the 16-bit types");
-    static constexpr int CPK = Traits<T>::kKeyBytes / 16;
-    static constexpr int TOTAL = ROWS * COLS * CPK;
-    static constexpr int NITER = (TOTAL + NTHREADS - 1) / NTHREADS;
-    // bytes per channel row: a multiple of 8 whose eighth is odd, so the 8-byte operand reads of
-    // 16 consecutive channels fall in 16 distinct bank pairs
-    static constexpr int kRow8 = (ROWS * PITCH * 2 + 7) / 8;
-    static constexpr int DSTRIDE = 8 * (kRow8 | 1);
-    static constexpr int kBytes = kHeadDim * DSTRIDE;
-    u32x4 v[NITER];
-    int goff[NITER];
-    int loff[NITER];   // LDS address of channel 8c at this position, -1 for padding past the end
-    int pos[NITER];
-
-    __device__ __forceinline__ void init(int W, int tid, int lds_base) {
-#pragma unroll
-        for (int it = 0; it < NITER; ++it) {
-            const int i = tid + it * NTHREADS;
-            const int c = i % CPK;
-            const int rx = (i / CPK) % COLS;
-            const int ry = i / (CPK * COLS);
-            goff[it] = (ry * W + rx) * Traits<T>::kKeyBytes + c * 16;
-            loff[it] = i < TOTAL ? lds_base + (8 * c) * DSTRIDE + (ry * PITCH + rx) * 2 : -1;
-            pos[it] = ry | (rx << 16);
-        }
-    }
-    __device__ __forceinline__ void issue(const char *plane_base, int H, int W, int oy, int ox) {
-        const int origin_off = (oy * W + ox) * Traits<T>::kKeyBytes;
-#pragma unroll
-        for (int it = 0; it < NITER; ++it) {
-            const int y = oy + (pos[it] & 0xffff), x = ox + (pos[it] >> 16);
-            v[it] = u32x4{0u, 0u, 0u, 0u};
-            if (loff[it] >= 0 && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W)
-                v[it] = *reinterpret_cast<const u32x4 *>(plane_base + (origin_off + goff[it]));
-        }
-    }
-    // issue() with the global offsets / halo coordinates of another stager of the same shape (a
-    // row-major HaloPrefetch of the same tile moves exactly the same chunks): saves the registers
-    // of a second copy.  Use init_lds() instead of init() then.
-    __device__ __forceinline__ void init_lds(int tid, int lds_base) {
-#pragma unroll
-        for (int it = 0; it < NITER; ++it) {
-            const int i = tid + it * NTHREADS;
-            const int c = i % CPK;
-            const int rx = (i / CPK) % COLS;
-            const int ry = i / (CPK * COLS);
-            loff[it] = i < TOTAL ? lds_base + (8 * c) * DSTRIDE + (ry * PITCH + rx) * 2 : -1;
-        }
-    }
-    __device__ __forceinline__ void issue_like(const int (&goff_)[NITER], const int (&pos_)[NITER], const char *plane_base,
-                                               int H, int W, int oy, int ox) {
-        const int origin_off = (oy * W + ox) * Traits<T>::kKeyBytes;
-#pragma unroll
-        for (int it = 0; it < NITER; ++it) {
-            const int y = oy + (pos_[it] & 0xffff), x = ox + (pos_[it] >> 16);
-            v[it] = u32x4{0u, 0u, 0u, 0u};
-            if (loff[it] >= 0 && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W)
-                v[it] = *reinterpret_cast<const u32x4 *>(plane_base + (origin_off + goff_[it]));
-        }
-    }
-    __device__ __forceinline__ void commit() const {
-#pragma unroll
-        for (int it = 0; it < NITER; ++it) {
-            if (loff[it] >= 0) {
-                const uint32_t w[4] = {v[it].x, v[it].y, v[it].z, v[it].w};
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    *lds_ptr<uint16_t>(loff[it] + (2 * u) * DSTRIDE) = (uint16_t)(w[u] & 0xffffu);
-                    *lds_ptr<uint16_t>(loff[it] + (2 * u + 1) * DSTRIDE) = (uint16_t)(w[u] >> 16);
-                }
-            }
-        }
-    }
-};
-
 // ---- global memory -> LDS without registers, and transposing LDS reads --------------------
 //
 // gfx950 can load 16 bytes per lane from global memory straight into LDS: lane l of the wave

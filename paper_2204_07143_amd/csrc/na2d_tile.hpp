@@ -79,55 +79,6 @@ __device__ __forceinline__ void load_halo(const char *plane_base, int H, int W, 
     }
 }
 
-// The same staging split in two, for software pipelining across tiles: issue() starts the
-// global loads of a thread's share of the halo into registers (positions outside the map become
-// zeros), commit() writes them to LDS later.  A persistent workgroup issues the next tile's halo
-// before it computes the current tile, so the memory latency is hidden behind the compute.
-// Which halo positions a thread moves never changes, so their offsets are worked out once
-// (init) and each tile only adds its origin and checks the map bounds.
-// COLS columns are staged per halo row; PITCH >= COLS is the row pitch of the LDS image (the
-// columns in between are never written by the stager).
-template <typename T, int ROWS, int COLS, int NTHREADS, int PITCH = COLS>
-struct HaloPrefetch {
-    static constexpr int CPK = Traits<T>::kKeyBytes / 16;
-    static constexpr int STRIDE = Traits<T>::kKeyStride;
-    static constexpr int TOTAL = ROWS * COLS * CPK;
-    static constexpr int NITER = (TOTAL + NTHREADS - 1) / NTHREADS;
-    u32x4 v[NITER];
-    int goff[NITER];   // byte offset from the halo's origin key in global memory
-    int loff[NITER];   // byte offset in the LDS halo, -1 for the padding past the last chunk
-    int pos[NITER];    // halo row | halo col << 16
-
-    __device__ __forceinline__ void init(int W, int tid) {
-#pragma unroll
-        for (int it = 0; it < NITER; ++it) {
-            const int i = tid + it * NTHREADS;
-            const int c = i % CPK;
-            const int rx = (i / CPK) % COLS;
-            const int ry = i / (CPK * COLS);
-            goff[it] = (ry * W + rx) * Traits<T>::kKeyBytes + c * 16;
-            loff[it] = i < TOTAL ? (ry * PITCH + rx) * STRIDE + c * 16 : -1;
-            pos[it] = ry | (rx << 16);
-        }
-    }
-    // plane_base + origin_off addresses key (oy, ox); origin_off may be negative near a border.
-    __device__ __forceinline__ void issue(const char *plane_base, int H, int W, int oy, int ox) {
-        const int origin_off = (oy * W + ox) * Traits<T>::kKeyBytes;
-#pragma unroll
-        for (int it = 0; it < NITER; ++it) {
-            const int y = oy + (pos[it] & 0xffff), x = ox + (pos[it] >> 16);
-            v[it] = u32x4{0u, 0u, 0u, 0u};
-            if (loff[it] >= 0 && (unsigned)y < (unsigned)H && (unsigned)x < (unsigned)W)
-                v[it] = *reinterpret_cast<const u32x4 *>(plane_base + (origin_off + goff[it]));
-        }
-    }
-    __device__ __forceinline__ void commit(char *lds) const {
-#pragma unroll
-        for (int it = 0; it < NITER; ++it)
-            if (loff[it] >= 0) *reinterpret_cast<u32x4 *>(lds + loff[it]) = v[it];
-    }
-};
-
 template <typename T, int D>
 __device__ __forceinline__ void lds_load_vec32(VecN<T, D> &v, const char *lds_key) {
     load_vec32(v, lds_key);
