@@ -155,6 +155,15 @@ def test_degenerate_and_border_heavy_maps(oracle, H, W, k, dtype):
     run_all(oracle, synth.Problem(3, 2, H, W, 32, k, dtype), seed=7 * H + W + k)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("H,W,k", [(40, 50, 11), (45, 70, 13), (34, 33, 9)])
+def test_large_windows_many_tiles_odd_batch(oracle, H, W, k, dtype):
+    # several tile rows and columns, ragged on both axes, a batch that does not divide by the workgroups'
+    # split of it, no bias on the 13-wide window
+    run_all(oracle, synth.Problem(5, 3, H, W, 32, k, dtype), seed=40 * H + W + k, use_rpb=(k != 13),
+            planes=[(0, 0), (2, 1), (4, 2)])
+
+
 def test_no_bias_and_custom_scale(oracle):
     p = synth.Problem(1, 2, 20, 18, 32, 5, "f16")
     run_all(oracle, p, seed=5, use_rpb=False, scale=0.11)
