@@ -1,0 +1,298 @@
+// Gradients that sum over queries, on the matrix cores, for large windows (f16 / bf16, K >= 9): the query
+// rectangle of a key tile is streamed through LDS two rows at a time.
+//   out_j = scale * sum over queries i whose window holds j of w[i, slot(i, j)] * x_i
+// (grad-v with w = attention weights, x = dout; grad-k with w = ds, x = q; arXiv 2204.07143, Appendix A).
+//
+// The arithmetic is that of the tile kernel in na2d_inverse_mfma.hip: a 16 x 8 key tile per workgroup, one 4 x 4
+// key patch per wave; for a patch
+//   out^T[d, key] = sum_pos x^T[d, pos] * Wg[pos, key]
+// with x through the transposing LDS read and the weights w[query pos][slot of this lane's key] as 2-byte LDS
+// gathers (zero word where query and key do not meet).  At K = 13 one weight row of the tile's query rectangle
+// is 11 KB and the rectangle has up to 26 of them: it cannot sit in LDS as a whole.  So the rows pass through
+// two small stages, a pair of rows at a time (a pair is the contraction depth of one MFMA: 2 rows x 16 columns),
+// the next pair loading while the current one is multiplied; the accumulators of a patch stay in registers for
+// the whole rectangle.  A patch is seen from up to K + (K-1)/2 + 3 <= 22 query columns: two column blocks of 16.
+// The gather address is row term + column term: the column terms (which window column of query ix holds key
+// column jx) are per-lane constants, the row terms (window row of query iy for key row jy) are two compares per
+// row.  Rows that see no key of a wave's strip are skipped.  One workgroup barrier per pair of rows.
+// A workgroup keeps one tile position and one head and walks a range of the batch; (plane, pair) steps form one
+// pipeline, so the first pair of the next plane loads under the last pair of this one.
+#include "na2d_kernels.hpp"
+#include "na2d_mfma.hpp"
+#include "na2d_tile.hpp"
+
+namespace na2d {
+
+template <typename T, int K>
+struct InvRowsCfg {
+    static constexpr int R = K / 2;
+    static constexpr int PWI = K + R + 3;            // query columns (rows) that can see a 4 x 4 key patch
+    static constexpr int NCB = (PWI + 15) / 16;      // 16-column MFMA blocks per row
+    static constexpr int STRIPS = 2, WAVES = 4 * STRIPS, TY = 4 * STRIPS;
+    static constexpr int RW = kTileX + K - 1 + R;    // columns of a tile's query rectangle (next to one border at most)
+    static constexpr int CH = 2;                     // rows per stage
+    static constexpr int KK = K * K;
+    static constexpr int kThreads = kWave * WAVES;
+    static constexpr int KB = Traits<T>::kKeyBytes;
+    static constexpr int kXRow = RW * KB;
+    // + the reach of the last column block (it starts up to 12 columns into a row) past the last row of the stage
+    static constexpr int kXSlack = (12 + 16 * NCB > RW ? 12 + 16 * NCB - RW : 0) * KB;
+    static constexpr int kXStage = CH * kXRow + kXSlack;
+    static constexpr int kXItems = (RW * (KB / 16) + kWave - 1) / kWave;      // 64-lane loads per x row
+    static constexpr int kRowBytes = RW * KK * (int)sizeof(T);
+    static constexpr int kRowRegion = mirror_bytes(kRowBytes);                // a weight row, mirrored at its 16-byte phase
+    static constexpr int kWItems = (kRowRegion / 16 + kWave - 1) / kWave;     // 64-lane loads per weight row
+    static constexpr int kWStage = CH * kRowRegion;
+    static constexpr int kStageBytes = kXStage + kWStage + 16;                // + the zero word
+    static constexpr int kLdsBytes = 2 * kStageBytes;
+    static constexpr int kItems = CH * (kWItems + kXItems);                   // load instructions per stage
+    static constexpr int kItemsPerWave = (kItems + WAVES - 1) / WAVES;
+    static_assert(kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
+    static_assert(16 * NCB >= PWI, "column blocks cover the patch halo");
+};
+
+template <typename T, int K>
+__global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restrict__ w, const T *__restrict__ x, float scale,
+                                                              T *__restrict__ out, int H, int W, int heads, int nb,
+                                                              int tiles_y, int units, int splits, int pitch) {
+    // `pitch`: bytes between consecutive positions of x and out (a longer head vector is served one 32-channel
+    // slice per launch, x and out pointing at the slice)
+    using C = InvRowsCfg<T, K>;
+    constexpr int SZ = (int)sizeof(T);
+    constexpr int BIG = 1 << 24;   // invalid row / column terms push the sum past the zero word
+    extern __shared__ __align__(16) char lds[];
+
+    const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
+    if (wg >= units * splits) return;
+    const int npos = units / heads;
+    const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
+    const int b_begin = (split * nb) / splits, b_end = ((split + 1) * nb) / splits;
+    if (b_begin >= b_end) return;
+
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int n = lane & 15, g = lane >> 4, ky = n >> 2, kx = n & 3;
+    const int lds0 = lds_addr(lds);
+
+    // Everything the loads do not write must hold finite numbers (it meets zero weights only); the zero words too.
+    for (int i = tid * 16; i < C::kLdsBytes; i += C::kThreads * 16) *lds_ptr<u32x4>(lds0 + i) = u32x4{0u, 0u, 0u, 0u};
+
+    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
+    const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
+    const int tx1 = tx0 + kTileX - 1 < W - 1 ? tx0 + kTileX - 1 : W - 1;
+    const int ry0 = inv_first(ty0, H, K), ry1 = inv_last(ty1, H, K);
+    const int rx0 = inv_first(tx0, W, K), rx1 = inv_last(tx1, W, K);
+    const int nrows = ry1 - ry0 + 1, ncols = rx1 - rx0 + 1;   // ncols <= RW: checked by the host
+    const int npairs = (nrows + 1) >> 1;
+    const int row_pitch_bytes = W * C::KK * SZ;                // < 2^31: checked by the host
+    const int pitch_phase = row_pitch_bytes & 15;
+    const int wrow_bytes = ncols * C::KK * SZ;
+    const size_t w_bytes = (size_t)nb * heads * H * W * C::KK * SZ;   // size of the weight tensor
+
+    // this wave's patch and this lane's key
+    const int strip = wave >> 2, p = wave & 3;
+    const int sy0 = ty0 + 4 * strip, px0 = tx0 + 4 * p;
+    const bool active = sy0 < H && px0 < W;
+    const int jy = sy0 + ky, jx = px0 + kx;
+    const int oqx = inv_first(px0 < W ? px0 : W - 1, W, K);   // first query column that sees the patch
+    // query rows that see the strip: [sq0, sq1]
+    const int sq0 = inv_first(sy0 < H ? sy0 : H - 1, H, K);
+    const int sq1 = inv_last(sy0 + 3 < H - 1 ? sy0 + 3 : H - 1, H, K);
+
+    // column terms: block cb, position 4g + r of it is query column oqx + 16 cb + 4g + r
+    int colterm[C::NCB][4];
+#pragma unroll
+    for (int cb = 0; cb < C::NCB; ++cb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int ix = oqx + 16 * cb + 4 * g + r;
+            const int c = jx - win_start(ix < W ? ix : W - 1, W, K);
+            colterm[cb][r] = (active && ix <= rx1 && jx < W && (unsigned)c < (unsigned)K) ? (ix - rx0) * C::KK * SZ + c * SZ : BIG;
+        }
+    }
+    // lane-constant part of the A-operand address inside a stage's x rows (transposing read): inside its group of
+    // 16, lane n points at four channels of position 4g + n / 4 of a block and receives the n-th channel of
+    // positions 4g .. 4g + 3.  The channels are dealt so that MFMA row m of half hf is channel 8 (m / 4) + 4 hf +
+    // m % 4: a lane ends up with the eight consecutive channels 8g .. 8g + 7 of its key, one 16-byte store.
+    const int xa_lane = (oqx - rx0 + 4 * g + (n >> 2)) * C::KB + (n & 3) * 16;
+
+    // loads: this lane's x chunks of a row, as byte offsets inside a query row (columns clamped into the map)
+    int xcol[C::kXItems];
+#pragma unroll
+    for (int j = 0; j < C::kXItems; ++j) {
+        const int q = j * kWave + lane;
+        int xx = rx0 + q / (C::KB / 16);
+        xx = xx < W - 1 ? xx : W - 1;
+        xcol[j] = q < C::RW * (C::KB / 16) ? xx * pitch + (q % (C::KB / 16)) * 16 : -1;
+    }
+    // Loads pair `pr` of plane `b` into stage `par`: the stage's load instructions (per row: the weight row,
+    // mirrored at its 16-byte phase, then the x vectors) are dealt round-robin to the waves.
+    auto issue = [&](int b, int pr, int par) {
+        const size_t plane_q = ((size_t)b * heads + head) * H * W;
+        const int stage = lds0 + par * C::kStageBytes;
+#pragma unroll
+        for (int u = 0; u < C::kItemsPerWave; ++u) {
+            const int item = wave + u * C::WAVES;
+            if (item >= C::kItems) break;
+            const int rr = item / (C::kWItems + C::kXItems), j = item - rr * (C::kWItems + C::kXItems);
+            const int iy = ry0 + 2 * pr + rr;
+            if (iy > ry1) continue;
+            if (j < C::kWItems) {
+                const size_t g0 = (plane_q + (size_t)iy * W + rx0) * C::KK * SZ;
+                const int mis = (int)(g0 & 15);
+                const int nchunks = (mis + wrow_bytes + 15) >> 4;
+                const char *src = reinterpret_cast<const char *>(w) + (g0 - mis);
+                const size_t left = w_bytes - (g0 - mis);   // bytes up to the end of the tensor
+                const int region = stage + C::kXStage + rr * C::kRowRegion;
+                const int c = j * kWave + lane;
+                if (c < nchunks) {
+                    if ((size_t)(c + 1) * 16 <= left) {
+                        global_to_lds_16(src, (unsigned)(c * 16), region + j * kWave * 16);
+                    } else {   // the chunk that would cross the end of the tensor: element by element
+                        for (int e = c * 16; e < mis + wrow_bytes; e += SZ)
+                            *lds_ptr<T>(region + e) = *reinterpret_cast<const T *>(src + e);
+                    }
+                }
+            } else {
+                const int jj = j - C::kWItems;
+                const char *xrow = reinterpret_cast<const char *>(x) + (plane_q + (size_t)iy * W) * pitch;
+                // (xcol is indexed by a compile-time constant after unrolling: jj takes each value once per row)
+#pragma unroll
+                for (int q = 0; q < C::kXItems; ++q)
+                    if (q == jj && xcol[q] >= 0) global_to_lds_16(xrow, (unsigned)xcol[q], stage + rr * C::kXRow + q * kWave * 16);
+            }
+        }
+    };
+
+    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    // One step: pair `pr` of plane `b`, staged in `par`.
+    auto compute = [&](int b, int pr, int par) {
+        if (active) {
+            const size_t plane_q = ((size_t)b * heads + head) * H * W;
+            const int stage = lds0 + par * C::kStageBytes;
+            const int zero_addr = stage + C::kXStage + C::kWStage;
+            const int mis0 = (int)(((plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ) & 15);   // phase of the rectangle's first row
+            // row terms of the pair's two rows for this lane's key row
+            int rowterm[2];
+#pragma unroll
+            for (int rr = 0; rr < 2; ++rr) {
+                const int iy = ry0 + 2 * pr + rr;
+                const int a = jy - win_start(iy < H ? iy : H - 1, H, K);
+                const bool ok = iy <= ry1 && jy < H && (unsigned)a < (unsigned)K;
+                rowterm[rr] = ok ? stage + C::kXStage + rr * C::kRowRegion + ((mis0 + (iy - ry0) * pitch_phase) & 15) + a * K * SZ : BIG;
+            }
+            const int iy0 = ry0 + 2 * pr;
+            if (iy0 + 1 >= sq0 && iy0 <= sq1) {   // the pair holds a row that sees the strip (wave-uniform)
+#pragma unroll
+                for (int cb = 0; cb < C::NCB; ++cb) {
+                    uint32_t wv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int rr = u >> 1, r0 = (u & 1) * 2;
+                        int a_lo = rowterm[rr] + colterm[cb][r0], a_hi = rowterm[rr] + colterm[cb][r0 + 1];
+                        a_lo = a_lo < zero_addr ? a_lo : zero_addr;
+                        a_hi = a_hi < zero_addr ? a_hi : zero_addr;
+                        wv[u] = (uint32_t)*lds_ptr<uint16_t>(a_lo) | ((uint32_t)*lds_ptr<uint16_t>(a_hi) << 16);
+                    }
+                    const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf) {
+                        const int a0 = stage + xa_lane + cb * 16 * C::KB + hf * 8;
+                        const u32x2 lo = lds_read_tr16(a0);
+                        const u32x2 hi = lds_read_tr16(a0 + C::kXRow);
+                        acc[hf] = mfma_16x16x32<T>(u32x4{lo.x, lo.y, hi.x, hi.y}, bop, acc[hf]);
+                    }
+                }
+            }
+            if (pr == npairs - 1) {   // the rectangle is done: this lane's eight channels of its key
+                if (jy < H && jx < W) {
+                    char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * pitch + g * 16;
+                    uint32_t o[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int hf = u >> 1, r = 2 * (u & 1);
+                        const T lo = from_f32<T>(acc[hf][r] * scale), hi = from_f32<T>(acc[hf][r + 1] * scale);
+                        o[u] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+                    }
+                    *reinterpret_cast<u32x4 *>(dst) = u32x4{o[0], o[1], o[2], o[3]};   // channels 8g .. 8g + 7
+                }
+                acc[0] = acc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+    };
+
+    __syncthreads();   // the zero fill is done before the first loads land
+    issue(b_begin, 0, 0);
+    int b = b_begin, pr = 0, par = 0;
+    while (b < b_end) {
+        wait_global_loads();   // this step's rows have landed
+        __syncthreads();       // ... for every wave, and nobody still reads the other stage
+        int nb_ = b, npr = pr + 1;
+        if (npr == npairs) {
+            npr = 0;
+            ++nb_;
+        }
+        if (nb_ < b_end) issue(nb_, npr, par ^ 1);
+        compute(b, pr, par);
+        b = nb_;
+        pr = npr;
+        par ^= 1;
+    }
+}
+
+template <typename T, int K>
+static hipError_t launch_inverse_rows_t(const Problem &p, const void *w, const void *x, float scale, void *out,
+                                        hipStream_t s) {
+    using C = InvRowsCfg<T, K>;
+    const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
+    const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
+    auto kern = inverse_rows_kernel<T, K>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    for (int sl = 0; sl < p.D / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector
+        hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
+                           static_cast<const T *>(w), static_cast<const T *>(x) + sl * kHeadDim, scale,
+                           static_cast<T *>(out) + sl * kHeadDim, p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits,
+                           p.D * (int)sizeof(T));
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// Every tile's query rectangle must be at most RW columns wide (rows are streamed, any number of them), and a
+// patch must be seen from at most 16 NCB columns: both hold for every map with K <= min(H, W) (a tile next to both
+// ends of a short axis has at most W <= 2K + 2 columns).  Checked anyway.
+bool inverse_rows_supported(const Problem &p) {
+    if (p.D % kHeadDim != 0 || p.dtype == NA2D_F32 || p.K < 11) return false;
+    const int K = p.K, RW = kTileX + K - 1 + K / 2, NCOL = 16 * ((K + K / 2 + 3 + 15) / 16);
+    if ((int64_t)p.W * K * K * 4 >= (int64_t)1 << 31) return false;   // a row of weights as a 32-bit byte count
+    for (int tx0 = 0; tx0 < p.W; tx0 += kTileX) {
+        const int tx1 = tx0 + kTileX - 1 < p.W - 1 ? tx0 + kTileX - 1 : p.W - 1;
+        if (inv_last(tx1, p.W, K) - inv_first(tx0, p.W, K) + 1 > RW) return false;
+        for (int px0 = tx0; px0 <= tx1; px0 += 4) {
+            const int px1 = px0 + 3 < p.W - 1 ? px0 + 3 : p.W - 1;
+            if (inv_last(px1, p.W, K) - inv_first(px0, p.W, K) + 1 > NCOL) return false;
+        }
+    }
+    return true;
+}
+
+hipError_t launch_inverse_rows(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s) {
+#define NA2D_INVW_K(TT)                                                               \
+    switch (p.K) {                                                                    \
+        case 11: return launch_inverse_rows_t<TT, 11>(p, w, x, scale, out, s);        \
+        case 13: return launch_inverse_rows_t<TT, 13>(p, w, x, scale, out, s);        \
+        default: return hipErrorInvalidValue;                                         \
+    }
+    if (p.dtype == NA2D_F16) { NA2D_INVW_K(f16_t) }
+    if (p.dtype == NA2D_BF16) { NA2D_INVW_K(bf16_t) }
+#undef NA2D_INVW_K
+    return hipErrorInvalidValue;
+}
+
+}  // namespace na2d
