@@ -218,6 +218,7 @@ def bench_na1d(na, synth, torch, stream, iters: int) -> dict:
         s.lse = torch.empty((p.B, p.heads, p.L), dtype=torch.float32, device="cuda")
         s.d_rpb = torch.empty((p.heads, 2 * k - 1), dtype=torch.float32, device="cuda")
         s.ws = torch.empty(na.na1d_workspace_bytes(prob), dtype=torch.uint8, device="cuda")
+        s.ws_fused = torch.empty(na.na1d_fused_bwd_workspace_bytes(prob), dtype=torch.uint8, device="cuda")
         sets.append(s)
     nq = p.n_queries
     contraction = nq * (2 * p.D * e + k * e)
@@ -232,6 +233,9 @@ def bench_na1d(na, synth, torch, stream, iters: int) -> dict:
         "qk_bwd_q": (lambda s: na.na1d_qk_bwd_q(s.dp, s.k, scale, k, s.dq), contraction),
         "qk_bwd_k": (lambda s: na.na1d_qk_bwd_k(s.dp, s.q, scale, k, s.dk), contraction),
         "qk_bwd_rpb": (lambda s: na.na1d_qk_bwd_rpb(s.dp, k, s.q, s.d_rpb, s.ws), nq * k * e),
+        # q, k, v, dout and lse in; dq, dk, dv out
+        "fused_bwd": (lambda s: na.na1d_fused_bwd(s.q, s.k, s.v, s.rpb, scale, s.lse, s.dout, k, s.dq, s.dk, s.dv, s.d_rpb,
+                                                  s.ws_fused), nq * (7 * p.D * e + 4)),
     }
     res, total_us, total_bytes = {}, 0.0, 0
     for name, (fn, nbytes) in calls.items():
@@ -247,8 +251,9 @@ def bench_na1d(na, synth, torch, stream, iters: int) -> dict:
         us = a.elapsed_time(b) * 1e3 / iters
         res[name] = {"us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1), "pct_hbm_peak": round(100 * nbytes / us / 1e3 / HBM_PEAK_GBPS, 1),
                      "MB": round(nbytes / 1e6, 2)}
-        total_us += us
-        total_bytes += nbytes
+        if name != "fused_bwd":   # the fused backward is an alternative to the six unfused steps, not one more call
+            total_us += us
+            total_bytes += nbytes
         log(f"  na1d {name:12s} {us:9.2f} us  {nbytes / us / 1e3:8.1f} GB/s")
     return {"workload": f"seq_3136_k7 (B={p.B}, heads={p.heads}, L={p.L}, D={p.D}, k={k}, {p.dtype})",
             "us_all_calls": round(total_us, 1), "GBps_all_calls": round(total_bytes / total_us / 1e3, 1), "kernels": res}

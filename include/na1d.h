@@ -77,6 +77,17 @@ int na1d_qk_bwd_rpb(const na1d_problem *p, const void *ds, float *d_rpb, void *w
                     void *stream);
 size_t na1d_workspace_bytes(const na1d_problem *p);
 
+/* Whole backward without the k-wide tensors (the 1D counterpart of na2d_fused_bwd): dq, dk, dv and (if
+ * d_rpb != NULL) d_rpb of out = NA(q, k, v, rpb) from q, k, v, rpb, dout and `lse`, the log-sum-exp that
+ * na1d_fused_fwd stored for every query.  The attention weights are recomputed as
+ * exp(scale <q, k> + bias - lse).  `rpb` may be NULL (no bias in the forward).  No output may alias an input
+ * or another output.  d_rpb is summed in 64-bit fixed point as in na1d_qk_bwd_rpb (bitwise reproducible).
+ * `workspace` must hold na1d_fused_bwd_workspace_bytes(p) bytes; no initialisation needed. */
+int na1d_fused_bwd(const na1d_problem *p, const void *q, const void *k, const void *v, const void *rpb, float scale,
+                   const float *lse, const void *dout, void *dq, void *dk, void *dv, float *d_rpb, void *workspace,
+                   size_t workspace_bytes, void *stream);
+size_t na1d_fused_bwd_workspace_bytes(const na1d_problem *p);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,6 +31,7 @@ EXPORTS = (
 EXPORTS_1D = (
     "na1d_validate_problem", "na1d_qk_rpb", "na1d_softmax", "na1d_av", "na1d_fused_fwd", "na1d_av_bwd_p", "na1d_av_bwd_v",
     "na1d_softmax_bwd", "na1d_qk_bwd_q", "na1d_qk_bwd_k", "na1d_qk_bwd_rpb", "na1d_workspace_bytes",
+    "na1d_fused_bwd", "na1d_fused_bwd_workspace_bytes",
 )
 
 
@@ -96,6 +97,7 @@ def load() -> ctypes.CDLL:
             "na1d_qk_bwd_q": [p1, vp, vp, f, vp, vp],
             "na1d_qk_bwd_k": [p1, vp, vp, f, vp, vp],
             "na1d_qk_bwd_rpb": [p1, vp, vp, vp, ctypes.c_size_t, vp],
+            "na1d_fused_bwd": [p1, vp, vp, vp, vp, f, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp],
         }
         for name, argtypes in sigs_1d.items():
             fn = getattr(lib, name)
@@ -103,6 +105,8 @@ def load() -> ctypes.CDLL:
             fn.restype = ctypes.c_int
         lib.na1d_workspace_bytes.argtypes = [p1]
         lib.na1d_workspace_bytes.restype = ctypes.c_size_t
+        lib.na1d_fused_bwd_workspace_bytes.argtypes = [p1]
+        lib.na1d_fused_bwd_workspace_bytes.restype = ctypes.c_size_t
         lib.na2d_workspace_bytes.argtypes = [pp, ctypes.c_int]
         lib.na2d_workspace_bytes.restype = ctypes.c_size_t
         lib.na2d_strerror.argtypes = [ctypes.c_int]
@@ -394,3 +398,18 @@ def na1d_qk_bwd_rpb(ds, kernel: int, like, d_rpb, workspace):
                                   _ptr(d_rpb, torch.float32, _rpb1(like, kernel)), _ptr(workspace),
                                   workspace.numel() * workspace.element_size(), _stream()))
     return d_rpb
+
+
+def na1d_fused_bwd_workspace_bytes(p: Na1dProblem) -> int:
+    return int(load().na1d_fused_bwd_workspace_bytes(ctypes.byref(p)))
+
+
+def na1d_fused_bwd(q, k_, v, rpb, scale: float, lse, dout, kernel: int, dq, dk, dv, d_rpb, workspace):
+    p = _p1(q, kernel)
+    _check(load().na1d_fused_bwd(ctypes.byref(p), _ptr(q), _ptr(k_, q.dtype, q.shape), _ptr(v, q.dtype, q.shape),
+                                 _ptr(rpb, q.dtype, _rpb1(q, kernel)) if rpb is not None else None, scale,
+                                 _ptr(lse, torch.float32, q.shape[:3]), _ptr(dout, q.dtype, q.shape),
+                                 _ptr(dq, q.dtype, q.shape), _ptr(dk, q.dtype, q.shape), _ptr(dv, q.dtype, q.shape),
+                                 _ptr(d_rpb, torch.float32, _rpb1(q, kernel)) if d_rpb is not None else None,
+                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+    return dq, dk, dv, d_rpb

@@ -129,4 +129,26 @@ int na1d_qk_bwd_rpb(const na1d_problem *p, const void *ds, float *d_rpb, void *w
     return from_hip(launch_rpb_grad(to_problem(p), ds, d_rpb, workspace, static_cast<hipStream_t>(stream)));
 }
 
+size_t na1d_fused_bwd_workspace_bytes(const na1d_problem *p) {
+    if (validate(p) != NA2D_OK) return 0;
+    return fused_bwd_workspace_bytes(to_problem(p));
+}
+
+int na1d_fused_bwd(const na1d_problem *p, const void *q, const void *k, const void *v, const void *rpb, float scale,
+                   const float *lse, const void *dout, void *dq, void *dk, void *dv, float *d_rpb, void *workspace,
+                   size_t workspace_bytes, void *stream) {
+    NA1D_CHECK_PROBLEM(p);
+    NA1D_REQUIRE(q); NA1D_REQUIRE(k); NA1D_REQUIRE(v); NA1D_OPTIONAL(rpb); NA1D_REQUIRE(lse); NA1D_REQUIRE(dout);
+    NA1D_REQUIRE(dq); NA1D_REQUIRE(dk); NA1D_REQUIRE(dv); NA1D_OPTIONAL(d_rpb);
+    if (!workspace || misaligned(workspace) || workspace_bytes < fused_bwd_workspace_bytes(to_problem(p))) return NA2D_ERR_WORKSPACE;
+    const void *ins[6] = {q, k, v, rpb, lse, dout};
+    void *outs[4] = {dq, dk, dv, d_rpb};
+    for (void *o : outs)
+        for (const void *i : ins)
+            if (o && o == i) return NA2D_ERR_ALIAS;
+    if (dq == dk || dq == dv || dk == dv) return NA2D_ERR_ALIAS;
+    return from_hip(launch_fused_bwd(to_problem(p), q, k, v, rpb, scale, lse, dout, dq, dk, dv, d_rpb, workspace,
+                                     static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -435,6 +435,159 @@ __global__ __launch_bounds__(kFinalThreads) void rpb_final1d_kernel(const long l
     }
 }
 
+// ---- fused backward ----------------------------------------------------------------------------
+// dq, dk, dv and d_rpb from q, k, v, rpb, dout and the forward's log-sum-exp: the weights are recomputed as
+// exp(scale <q, k> + bias - lse), so no k-wide tensor is read or written.  Two kernels, because dq sums over a
+// query's window and dk / dv over a key's inverse neighbourhood:
+//   * query side (one thread per query): a first sweep over the window sums delta = sum_a P_a dP_a
+//     (dP_a = <dout, v_a>), a second one forms dS_a = P_a (dP_a - delta), accumulates dq += dS_a k_a and adds
+//     dS_a to the bias-gradient table (64-bit fixed point, as in the unfused bias gradient).  Recomputing the two
+//     dot products is cheaper than parking 2 k values per query (k is a run-time argument, up to 63);
+//   * key side (one thread per key, k_j and v_j in registers): for every query i that sees key j,
+//     P = exp(scale <q_i, k_j> + bias - lse_i), dP = <dout_i, v_j>, dS = P (dP - delta_i), dv += P dout_i,
+//     dk += scale dS q_i, with q, dout, lse and delta of the tile's queries staged in LDS.
+
+constexpr float kLog2eF = 1.4426950408889634f;
+
+template <typename T, int TQ>
+__host__ __device__ constexpr int fbwd_q_lds_bytes(int K) {
+    return 2 * (TQ + K - 1) * Traits<T>::kKeyStride + align16((2 * K - 1) * 4) + (2 * K - 1) * 8;
+}
+
+template <typename T, int TQ>
+__global__ __launch_bounds__(TQ) void fbwd1d_q_kernel(const T *__restrict__ q, const T *__restrict__ k,
+                                                      const T *__restrict__ v, const T *__restrict__ rpb, float scale,
+                                                      const float *__restrict__ lse, const T *__restrict__ dout,
+                                                      T *__restrict__ dq, float *__restrict__ delta_out,
+                                                      long long *__restrict__ partial, int L, int heads, int K, int tiles) {
+    constexpr int KBYTES = Traits<T>::kKeyBytes, STRIDE = Traits<T>::kKeyStride;
+    extern __shared__ __align__(16) char lds[];
+    const int NB = 2 * K - 1, R = K >> 1;
+    char *khalo = lds, *vhalo = lds + (TQ + K - 1) * STRIDE;
+    float *bias = reinterpret_cast<float *>(lds + 2 * (TQ + K - 1) * STRIDE);
+    unsigned long long *tbl = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(bias) + align16(NB * 4));
+    const int tid = threadIdx.x;
+    const Tile t = decode<TQ>(L, tiles);
+    const int h0 = win_start(t.t0, L, K), h1 = win_start(t.t0 + t.n - 1, L, K) + K;
+    const size_t hoff = ((size_t)t.plane * L + h0) * KBYTES;
+    load_vectors<T, TQ>(reinterpret_cast<const char *>(k) + hoff, h1 - h0, khalo, tid);
+    load_vectors<T, TQ>(reinterpret_cast<const char *>(v) + hoff, h1 - h0, vhalo, tid);
+    for (int i = tid; i < NB; i += TQ) {
+        bias[i] = rpb ? to_f32(rpb[(size_t)(t.plane % heads) * NB + i]) * kLog2eF : 0.f;
+        tbl[i] = 0ull;
+    }
+    __syncthreads();
+    const bool live = tid < t.n;
+    const int i = t.t0 + (live ? tid : 0);
+    const size_t qi = (size_t)t.plane * L + i;
+    Vec32<T> qv, gv;
+    load_vec32(qv, reinterpret_cast<const char *>(q) + qi * KBYTES);
+    load_vec32(gv, reinterpret_cast<const char *>(dout) + qi * KBYTES);
+    const float lse2 = lse[qi] * kLog2eF, scale2 = scale * kLog2eF;
+    const int s = win_start(i, L, K);
+    const int off = (s - h0) * STRIDE;
+    const int cell0 = s - i + K - 1;
+    const bool centred = cell0 == R;
+    const float *bb = bias + cell0;
+    // sweep 1: delta
+    float delta = 0.f;
+    for (int a = 0; a < K; ++a) {
+        Vec32<T> kv, vv;
+        load_vec32(kv, khalo + off + a * STRIDE);
+        load_vec32(vv, vhalo + off + a * STRIDE);
+        const float pw = __builtin_amdgcn_exp2f(__builtin_fmaf(scale2, dot32(qv, kv), bb[a]) - lse2);
+        delta = __builtin_fmaf(pw, dot32(gv, vv), delta);
+    }
+    // sweep 2: dS, dq, bias gradient
+    float acc[kHeadDim];
+#pragma unroll
+    for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
+    for (int a = 0; a < K; ++a) {
+        Vec32<T> kv, vv;
+        load_vec32(kv, khalo + off + a * STRIDE);
+        load_vec32(vv, vhalo + off + a * STRIDE);
+        const float pw = __builtin_amdgcn_exp2f(__builtin_fmaf(scale2, dot32(qv, kv), bb[a]) - lse2);
+        const float ds = live ? pw * (dot32(gv, vv) - delta) : 0.f;
+        axpy32(acc, ds, kv);
+        if (partial != nullptr) {   // the same for every thread
+            const long long fx = to_fixed42(ds);
+            long long tot = centred ? fx : 0ll;
+#pragma unroll
+            for (int sh = 1; sh < kWave; sh <<= 1) tot += __shfl_xor(tot, sh, kWave);
+            if ((tid & (kWave - 1)) == 0)
+                __hip_atomic_fetch_add(tbl + R + a, (unsigned long long)tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (live && !centred)
+                __hip_atomic_fetch_add(tbl + cell0 + a, (unsigned long long)fx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < kHeadDim; ++d) acc[d] *= scale;
+    if (live) delta_out[qi] = delta;
+    store_tile<T, TQ>(acc, live, khalo, reinterpret_cast<char *>(dq) + ((size_t)t.plane * L + t.t0) * KBYTES, t.n, tid);
+    if (partial != nullptr)   // (store_tile's barriers have passed: every atomic of the workgroup is done)
+        for (int u = tid; u < NB; u += TQ) partial[(size_t)blockIdx.x * NB + u] = (long long)tbl[u];
+}
+
+template <typename T, int TQ>
+__host__ __device__ constexpr int fbwd_kv_lds_bytes(int K) {
+    return 2 * (TQ + 2 * (K - 1)) * Traits<T>::kKeyStride + 2 * align16((TQ + 2 * (K - 1)) * 4) + align16((2 * K - 1) * 4);
+}
+
+template <typename T, int TQ>
+__global__ __launch_bounds__(TQ) void fbwd1d_kv_kernel(const T *__restrict__ q, const T *__restrict__ k,
+                                                       const T *__restrict__ v, const T *__restrict__ rpb, float scale,
+                                                       const float *__restrict__ lse, const float *__restrict__ delta,
+                                                       const T *__restrict__ dout, T *__restrict__ dk, T *__restrict__ dv,
+                                                       int L, int heads, int K, int tiles) {
+    constexpr int KBYTES = Traits<T>::kKeyBytes, STRIDE = Traits<T>::kKeyStride;
+    extern __shared__ __align__(16) char lds[];
+    const int NB = 2 * K - 1, NQ = TQ + 2 * (K - 1);
+    char *qhalo = lds, *ghalo = lds + NQ * STRIDE;
+    float *lse_s = reinterpret_cast<float *>(lds + 2 * NQ * STRIDE);
+    float *delta_s = lse_s + align16(NQ * 4) / 4;
+    float *bias = delta_s + align16(NQ * 4) / 4;
+    const int tid = threadIdx.x;
+    const Tile t = decode<TQ>(L, tiles);
+    const int i0 = inv_first(t.t0, L, K), i1 = inv_last(t.t0 + t.n - 1, L, K);   // the queries that see the tile: at most NQ
+    const size_t ioff = (size_t)t.plane * L + i0;
+    load_vectors<T, TQ>(reinterpret_cast<const char *>(q) + ioff * KBYTES, i1 - i0 + 1, qhalo, tid);
+    load_vectors<T, TQ>(reinterpret_cast<const char *>(dout) + ioff * KBYTES, i1 - i0 + 1, ghalo, tid);
+    for (int u = tid; u <= i1 - i0; u += TQ) {
+        lse_s[u] = lse[ioff + u] * kLog2eF;
+        delta_s[u] = delta[ioff + u];
+    }
+    for (int u = tid; u < NB; u += TQ) bias[u] = rpb ? to_f32(rpb[(size_t)(t.plane % heads) * NB + u]) * kLog2eF : 0.f;
+    __syncthreads();
+    const bool live = tid < t.n;
+    const int j = t.t0 + (live ? tid : 0);
+    const size_t kj = (size_t)t.plane * L + j;
+    Vec32<T> kv, vv;
+    load_vec32(kv, reinterpret_cast<const char *>(k) + kj * KBYTES);
+    load_vec32(vv, reinterpret_cast<const char *>(v) + kj * KBYTES);
+    const float scale2 = scale * kLog2eF;
+    float dk_acc[kHeadDim], dv_acc[kHeadDim];
+#pragma unroll
+    for (int d = 0; d < kHeadDim; ++d) dk_acc[d] = dv_acc[d] = 0.f;
+    if (live) {
+        const int qa = inv_first(j, L, K), qb = inv_last(j, L, K);
+        for (int i = qa; i <= qb; ++i) {
+            Vec32<T> qv, gv;
+            load_vec32(qv, qhalo + (i - i0) * STRIDE);
+            load_vec32(gv, ghalo + (i - i0) * STRIDE);
+            const float pw = __builtin_amdgcn_exp2f(__builtin_fmaf(scale2, dot32(qv, kv), bias[j - i + K - 1]) - lse_s[i - i0]);
+            const float ds = pw * (dot32(gv, vv) - delta_s[i - i0]);
+            axpy32(dv_acc, pw, gv);
+            axpy32(dk_acc, ds, qv);
+        }
+#pragma unroll
+        for (int d = 0; d < kHeadDim; ++d) dk_acc[d] *= scale;
+    }
+    char *gbase_k = reinterpret_cast<char *>(dk) + ((size_t)t.plane * L + t.t0) * KBYTES;
+    char *gbase_v = reinterpret_cast<char *>(dv) + ((size_t)t.plane * L + t.t0) * KBYTES;
+    store_tile<T, TQ>(dk_acc, live, qhalo, gbase_k, t.n, tid);
+    store_tile<T, TQ>(dv_acc, live, ghalo, gbase_v, t.n, tid);
+}
+
 // ---- launchers ---------------------------------------------------------------------------------
 
 // Dynamic LDS beyond 64 KB needs the attribute; it is set once per kernel, to the most the kernel can ask for.
@@ -580,6 +733,56 @@ static hipError_t rpb_t(const Problem &p, const void *ds, float *d_rpb, void *wo
 }
 hipError_t launch_rpb_grad(const Problem &p, const void *ds, float *d_rpb, void *workspace, hipStream_t s) {
     NA1D_DISPATCH(p, return (rpb_t<T, TQ>(p, ds, d_rpb, workspace, s)));
+    return hipErrorInvalidValue;
+}
+
+size_t fused_bwd_workspace_bytes(const Problem &p) {
+    const size_t delta_bytes = ((size_t)p.planes() * p.L * sizeof(float) + 255) & ~(size_t)255;
+    return delta_bytes + rpb_workspace_bytes(p);
+}
+
+template <typename T, int TQ>
+static hipError_t fused_bwd_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
+                              const float *lse, const void *dout, void *dq, void *dk, void *dv, float *d_rpb,
+                              void *workspace, hipStream_t s) {
+    const int tiles = tiles_of<TQ>(p), NB = 2 * p.K - 1;
+    float *delta = static_cast<float *>(workspace);
+    const size_t delta_bytes = ((size_t)p.planes() * p.L * sizeof(float) + 255) & ~(size_t)255;
+    long long *partial = d_rpb ? reinterpret_cast<long long *>(static_cast<char *>(workspace) + delta_bytes) : nullptr;
+    {
+        auto kern = fbwd1d_q_kernel<T, TQ>;
+        static_assert(fbwd_q_lds_bytes<T, TQ>(max_k<TQ>()) <= 160 * 1024, "LDS");
+        static bool attr = false;
+        if (hipError_t e = allow_lds(kern, fbwd_q_lds_bytes<T, TQ>(max_k<TQ>()), attr); e != hipSuccess) return e;
+        const int bytes = fbwd_q_lds_bytes<T, TQ>(p.K);
+        hipLaunchKernelGGL(kern, dim3(p.planes() * tiles), dim3(TQ), bytes, s,
+                           static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
+                           static_cast<const T *>(rpb), scale, lse, static_cast<const T *>(dout), static_cast<T *>(dq), delta,
+                           partial, p.L, p.heads, p.K, tiles);
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    }
+    {
+        auto kern = fbwd1d_kv_kernel<T, TQ>;
+        static_assert(fbwd_kv_lds_bytes<T, TQ>(max_k<TQ>()) <= 160 * 1024, "LDS");
+        static bool attr = false;
+        if (hipError_t e = allow_lds(kern, fbwd_kv_lds_bytes<T, TQ>(max_k<TQ>()), attr); e != hipSuccess) return e;
+        const int bytes = fbwd_kv_lds_bytes<T, TQ>(p.K);
+        hipLaunchKernelGGL(kern, dim3(p.planes() * tiles), dim3(TQ), bytes, s,
+                           static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
+                           static_cast<const T *>(rpb), scale, lse, delta, static_cast<const T *>(dout), static_cast<T *>(dk),
+                           static_cast<T *>(dv), p.L, p.heads, p.K, tiles);
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    }
+    if (d_rpb) {
+        hipLaunchKernelGGL(rpb_final1d_kernel, dim3(p.heads * NB), dim3(kFinalThreads), 0, s, partial, d_rpb, p.B, p.heads, tiles, NB);
+        return hipGetLastError();
+    }
+    return hipSuccess;
+}
+hipError_t launch_fused_bwd(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
+                            const float *lse, const void *dout, void *dq, void *dk, void *dv, float *d_rpb, void *workspace,
+                            hipStream_t s) {
+    NA1D_DISPATCH(p, return (fused_bwd_t<T, TQ>(p, q, k, v, rpb, scale, lse, dout, dq, dk, dv, d_rpb, workspace, s)));
     return hipErrorInvalidValue;
 }
 

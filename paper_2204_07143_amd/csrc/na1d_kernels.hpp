@@ -28,5 +28,10 @@ hipError_t launch_fused_fwd(const Problem &p, const void *q, const void *k, cons
                             void *out, float *lse, hipStream_t s);
 size_t rpb_workspace_bytes(const Problem &p);
 hipError_t launch_rpb_grad(const Problem &p, const void *ds, float *d_rpb, void *workspace, hipStream_t s);
+// whole backward from q, k, v, rpb, dout and the forward's log-sum-exp (no k-wide tensor in memory)
+size_t fused_bwd_workspace_bytes(const Problem &p);
+hipError_t launch_fused_bwd(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
+                            const float *lse, const void *dout, void *dq, void *dk, void *dv, float *d_rpb, void *workspace,
+                            hipStream_t s);
 
 }  // namespace na1d

@@ -111,6 +111,37 @@ class _NA2D(torch.autograd.Function):
         return dq, dk, dv, (d32.to(rpb.dtype) if want_bias else None), None, None
 
 
+class _NA1D(torch.autograd.Function):
+    """The 1D operator on [B, heads, L, D] tensors (bias [heads, 2k-1]): fused forward, fused backward."""
+
+    @staticmethod
+    def forward(ctx, q, k, v, rpb, kernel_size, scale):
+        q, k, v = q.contiguous(), k.contiguous(), v.contiguous()
+        rpb_c = None if rpb is None else rpb.contiguous()
+        out = torch.empty_like(q)
+        lse = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
+        na.na1d_fused_fwd(q, k, v, rpb_c, scale, kernel_size, out, lse)
+        ctx.save_for_backward(q, k, v, lse) if rpb_c is None else ctx.save_for_backward(q, k, v, lse, rpb_c)
+        ctx.kernel_size, ctx.scale, ctx.has_rpb = kernel_size, scale, rpb is not None
+        return out
+
+    @staticmethod
+    def backward(ctx, dout):
+        if ctx.has_rpb:
+            q, k, v, lse, rpb = ctx.saved_tensors
+        else:
+            (q, k, v, lse), rpb = ctx.saved_tensors, None
+        ks = ctx.kernel_size
+        B, heads, L, D = q.shape
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        want_bias = ctx.has_rpb and ctx.needs_input_grad[3]
+        d32 = torch.empty((heads, 2 * ks - 1), dtype=torch.float32, device=q.device) if want_bias else None
+        ws = torch.empty(max(16, na.na1d_fused_bwd_workspace_bytes(na.problem_1d(B, heads, L, D, ks, q.dtype))),
+                         dtype=torch.uint8, device=q.device)
+        na.na1d_fused_bwd(q, k, v, rpb, ctx.scale, lse, dout.contiguous(), ks, dq, dk, dv, d32, ws)
+        return dq, dk, dv, (d32.to(rpb.dtype) if want_bias else None), None, None
+
+
 def _scale_of(q, scale):
     return float(q.shape[-1]) ** -0.5 if scale is None else float(scale)
 
@@ -128,6 +159,11 @@ def na2d_av(attn, v, kernel_size: int):
 def na2d(q, k, v, rpb=None, kernel_size: int = 7, scale: float | None = None):
     """2D neighbourhood attention, fused; differentiable in q, k, v and rpb."""
     return _NA2D.apply(q, k, v, rpb, int(kernel_size), _scale_of(q, scale))
+
+
+def na1d(q, k, v, rpb=None, kernel_size: int = 7, scale: float | None = None):
+    """1D neighbourhood attention ([B, heads, L, D]), fused; differentiable in q, k, v and rpb."""
+    return _NA1D.apply(q, k, v, rpb, int(kernel_size), _scale_of(q, scale))
 
 
 def na2d_unfused(q, k, v, rpb=None, kernel_size: int = 7, scale: float | None = None):

@@ -95,6 +95,27 @@ def test_two_function_split_matches_stage_calls_and_oracle(oracle):
         assert torch.equal(F.na2d_unfused(q, key, v, rpb, k), out)
 
 
+def test_1d_operator_gradients():
+    from oracle import na1d_oracle as o1
+    p = synth.Problem1D(2, 2, 300, 32, 9, "f16")
+    host = synth.make_inputs_1d(p, 7500)
+    dev = lambda n: synth.to_device(host[n], p.dtype).requires_grad_(True)
+    q, key, v, rpb = dev("q"), dev("k"), dev("v"), dev("rpb")
+    dout = synth.to_device(host["dout"], p.dtype)
+    out = F.na1d(q, key, v, rpb, kernel_size=9)
+    out.backward(dout)
+    torch.cuda.synchronize()
+    h = {n: host[n].astype(np.float64) for n in host}
+    assert_close("na1d out", out, o1.fwd(h["q"], h["k"], h["v"], h["rpb"], p.default_scale, 9), "f16")
+    o_dq, o_dk, o_dv, o_db = o1.bwd(h["q"], h["k"], h["v"], h["rpb"], p.default_scale, h["dout"], 9)
+    assert_close("na1d dq", q.grad, o_dq, "f16")
+    assert_close("na1d dk", key.grad, o_dk, "f16")
+    assert_close("na1d dv", v.grad, o_dv, "f16")
+    # the wrapper hands the fp32 bias gradient back in the bias's dtype: half an ulp of that on top
+    err = np.abs(to_np(rpb.grad) - o_db)
+    assert (err <= 1e-4 * np.abs(o_db).max() + np.abs(o_db) * 2.0 ** -11).all()
+
+
 @pytest.mark.parametrize("dtype,ks", [("f16", 7), ("f32", 3)])
 def test_sasa_through_zero_padding(dtype, ks):
     """Section 3.1: a centred sliding window with zero padding (SASA) is NA on the zero-padded map, read at the

@@ -46,6 +46,19 @@ def run_1d(p: synth.Problem1D, seed: int, planes=None, use_rpb=True, scale=None,
     torch.cuda.synchronize()
     assert torch.equal(logits_c, attn) and torch.equal(dp_c, ds)
     assert torch.equal(out_f, out_f2) and torch.equal(d_rpb, d_rpb2)
+    # fused backward (from the fused forward's lse): everything is computed in fp32 from the inputs, so it is
+    # compared with the all-double oracle; a run without the bias gradient and a repeat give the same bits
+    ws_f = torch.empty(na.na1d_fused_bwd_workspace_bytes(prob), dtype=torch.uint8, device="cuda")
+    fdq, fdk, fdv = (torch.empty_like(q) for _ in range(3))
+    fd_rpb = torch.empty((p.heads, 2 * k - 1), dtype=torch.float32, device="cuda")
+    na.na1d_fused_bwd(q, key, v, rpb, scale, lse, dout, k, fdq, fdk, fdv, fd_rpb, ws_f)
+    fdq2, fdk2, fdv2 = (torch.empty_like(q) for _ in range(3))
+    na.na1d_fused_bwd(q, key, v, rpb, scale, lse, dout, k, fdq2, fdk2, fdv2, None, ws_f)
+    fdq3, fdk3, fdv3, fd_rpb3 = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q), torch.empty_like(fd_rpb)
+    na.na1d_fused_bwd(q, key, v, rpb, scale, lse, dout, k, fdq3, fdk3, fdv3, fd_rpb3, ws_f)
+    torch.cuda.synchronize()
+    assert torch.equal(fdq, fdq2) and torch.equal(fdk, fdk2) and torch.equal(fdv, fdv2)
+    assert torch.equal(fdq, fdq3) and torch.equal(fdk, fdk3) and torch.equal(fdv, fdv3) and torch.equal(fd_rpb, fd_rpb3)
 
     if planes is None:
         planes = [(b, h) for b in range(p.B) for h in range(p.heads)]
@@ -67,7 +80,16 @@ def run_1d(p: synth.Problem1D, seed: int, planes=None, use_rpb=True, scale=None,
         assert_close(f"{tag} softmax-bwd", sl(ds), o1.softmax_bwd(to_np(sl(attn)), to_np(sl(dp))), dt)
         assert_close(f"{tag} grad-q", sl(dq), o1.qk_bwd_q(to_np(sl(ds)), f64("k"), scale, k), dt)
         assert_close(f"{tag} grad-k", sl(dk), o1.qk_bwd_k(to_np(sl(ds)), f64("q"), scale, k), dt)
+        o_dq, o_dk, o_dv, _ = o1.bwd(f64("q"), f64("k"), f64("v"), r, scale, f64("dout"), k)
+        assert_close(f"{tag} fused dq", sl(fdq), o_dq, dt)
+        assert_close(f"{tag} fused dk", sl(fdk), o_dk, dt)
+        assert_close(f"{tag} fused dv", sl(fdv), o_dv, dt)
     assert_close_rpb("1d grad-b", d_rpb, o1.qk_bwd_rpb(to_np(ds), k))
+    # the bias gradient sums over the batch: the whole tensors (a table of zeros stands in where there is no bias)
+    h64 = {n: host[n].astype(np.float64) for n in ("q", "k", "v", "dout")}
+    rpb_all = host["rpb"].astype(np.float64) if use_rpb else np.zeros_like(host["rpb"], dtype=np.float64)
+    want_b = o1.bwd(h64["q"], h64["k"], h64["v"], rpb_all, scale, h64["dout"], k)[3]
+    assert_close_rpb("1d fused grad-b", fd_rpb, want_b)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])

@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
     assert sorted(binding.EXPORTS) == names
     assert binding.na2d_version() >= 100
     names_1d = declared_symbols("na1d.h", "na1d_")
-    assert len(names_1d) == 12
+    assert len(names_1d) == 14
     for n in names_1d:
         assert hasattr(lib, n), n
     assert sorted(binding.EXPORTS_1D) == names_1d
@@ -178,3 +178,10 @@ def test_1d_entry_points_reject_bad_arguments_before_any_hip_call():
     assert binding.na1d_workspace_bytes(P1(B=3, heads=2, L=1000, k=7)) == 3 * 2 * 4 * 13 * 8
     assert binding.na1d_workspace_bytes(P1(B=1, heads=1, L=1000, k=33)) == 8 * 65 * 8
     assert binding.na1d_workspace_bytes(P1(k=4)) == 0
+    # fused backward: delta [B, heads, L] fp32 (rounded up to 256 bytes), then the bias-gradient tables
+    assert binding.na1d_fused_bwd_workspace_bytes(P1(B=3, heads=2, L=1000, k=7)) == (3 * 2 * 1000 * 4 + 255) // 256 * 256 + 3 * 2 * 4 * 13 * 8
+    assert lib.na1d_fused_bwd(r, ok, ok, ok, None, 1.0, ok, ok, ok, ctypes.c_void_p(a16 + 16), ctypes.c_void_p(a16 + 32), None,
+                              ok, 1 << 20, None) == -10
+    assert lib.na1d_fused_bwd(r, ok, ok, ok, None, 1.0, None, ok, ok, ok, ok, None, ok, 1 << 20, None) == -1
+    assert lib.na1d_fused_bwd(r, ok, ok, ok, None, 1.0, ok, ok, ctypes.c_void_p(a16 + 16), ctypes.c_void_p(a16 + 32),
+                              ctypes.c_void_p(a16 + 48), None, ok, 8, None) == -8
