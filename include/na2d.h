@@ -32,8 +32,9 @@
  *  - Supported: odd k in {3, 5, 7, 9, 11, 13} (Appendix A, "Tiled Neighborhood Attention")
  *    with k <= min(H, W); k = H = W is the self-attention limit (Section 3.1).  Head dims
  *    D in {16, 32, 64, 128}.  D = 32 (every NAT variant, Section 3.2) runs the matrix-core
- *    kernels in the 16-bit types, and so do D = 64 (and, for the weighted sums, D = 128) with
- *    k <= 7; the rest runs plain-ALU kernels.  Accepted are the combinations whose plain-ALU
+ *    kernels in the 16-bit types; so do the weighted sums (av, grad-q, grad-v, grad-k) for
+ *    D = 64 and 128, and the logits, grad-a and the fused forward for D = 64 with k <= 7; the
+ *    rest runs plain-ALU kernels.  Accepted are the combinations whose plain-ALU
  *    tiles fit the 160 KB LDS: every k for D = 16 and for D = 64 in the 16-bit types, k <= 9
  *    for D = 128 in the 16-bit types and for D = 64 in fp32, k = 3 for D = 128 in fp32
  *    (anything else: NA2D_ERR_HEAD_DIM).

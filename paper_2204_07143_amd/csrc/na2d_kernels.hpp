@@ -33,7 +33,7 @@ hipError_t launch_bwd_fused(const Problem &p, const void *attn, const void *dout
 // out = scale * sum_window w * y          (AV, and grad-q with w = ds, y = k)
 hipError_t launch_av(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);
 hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);
-// the matrix-core kernels take D = 32, and for k <= 7 any multiple of 32 as one launch per 32-channel slice
+// the matrix-core kernel takes any multiple of 32 channels, one launch per 32-channel slice
 bool av_mfma_supported(const Problem &p);
 // out_j = scale * sum_{inverse neighbourhood} w[i, slot(i, j)] * x_i   (grad-v, grad-k)
 hipError_t launch_inverse(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
