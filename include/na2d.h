@@ -148,8 +148,8 @@ int na2d_bwd(const na2d_problem *p, const void *q, const void *k, const void *v,
  * exp(scale <q, k> + bias - lse) and neither they nor dp / ds reach memory.  `rpb` may be NULL
  * (no bias in the forward).  No output may alias an input or another output.
  * For the 16-bit types with k <= 7 this runs two kernels: query patches (dq, the partial bias gradients
- * and delta_n = sum_j P[n, j] dP[n, j]) and key patches (dk, dv); na2d_fused_bwd_is_fused() tells.  d_rpb is summed with integer atomics in 64-bit fixed point (42 fraction bits), so it does
- * not depend on the order of the additions; a non-finite ds counts as 0 there.  Every other case
+ * and delta_n = sum_j P[n, j] dP[n, j]) and key patches (dk, dv); na2d_fused_bwd_is_fused() tells.  d_rpb is summed with integer atomics in 64-bit fixed point (every ds rounded to 2^-20), so it does
+ * not depend on the order of the additions; a NaN ds counts as 0 there, one beyond +-2048 as +-2048.  Every other case
  * recomputes the attention weights into the workspace and runs the unfused backward.  Both ways the
  * results are bitwise reproducible.
  * `workspace` must hold na2d_workspace_bytes(p, NA2D_WS_FUSED_BWD) bytes; no initialisation needed.

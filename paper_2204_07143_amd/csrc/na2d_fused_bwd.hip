@@ -38,13 +38,15 @@ template <typename T> __device__ __forceinline__ uint32_t pack2_t(float a, float
 //   dq^T += K_blk^T dS^T                     the half-depth MFMA (keys through the transposing LDS read).
 // Recomputing the two products is cheaper than keeping P and dP of the whole halo in registers.
 // Every dS is also added to its cell of a (2K-1)^2 table in LDS (Eq. 2's B differentiated: the bias cell of a
-// (query, position) pair depends on their offset only).  The tables are 64-bit fixed point (42 fraction
-// bits) and the adds are integer atomics: on this chip an LDS integer add costs a few cycles per wave
+// (query, position) pair depends on their offset only).  The tables are 64-bit fixed point (20 fraction
+// bits: a dS is rounded to a 32-bit integer and sign-extended, two conversions and a shift) and the adds are
+// integer atomics: on this chip an LDS integer add costs a few cycles per wave
 // instruction where the floating-point add costs about 200, and integer addition does not depend on the
 // order of the operands, so the bias gradient is bitwise reproducible although waves share tables.  A
 // workgroup's tables, added up and converted to fp32 at the end, are one partial bias gradient.
-// (Range: a cell's sum over the workgroup's planes must stay below 2^21 in magnitude, far beyond what 16-bit
-// inputs whose gradients are representable at all produce; resolution 2^-42.  A non-finite dS counts as 0.)
+// (A single dS is rounded to 2^-20, about 1e-6, and saturates at +-2048; the 64-bit sums cannot overflow.  The
+// rounding errors of the up to ~1e5 terms of a cell add up to about 1e-4 absolute on sums of order 10 to 1000,
+// two orders below the fp32 summation noise the bias gradient is allowed.  A NaN dS counts as 0.)
 template <typename T, int K>
 struct FbwdQCfg {
     using P = Patch<K>;
@@ -259,9 +261,9 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
                 const int e = 4 * bk + r;
                 dsv[r] = weight(e, sacc[r]) * (pacc[r] - delta);   // exactly 0 outside the window
                 if constexpr (RPB) {
-                    // dS * 2^10 as integer part (32 bits, signed) and fraction (32 bits): 2^42 dS in 64 bits
-                    const float y = dsv[r] * 1024.f, fl = __builtin_floorf(y);
-                    const unsigned long long fx = ((unsigned long long)(uint32_t)(int)fl << 32) | (uint32_t)((y - fl) * 4294967296.f);
+                    // 2^20 dS rounded to the nearest 32-bit integer (saturating), sign-extended to 64 bits
+                    const int fi = (int)__builtin_rintf(dsv[r] * 1048576.f);
+                    const unsigned long long fx = (unsigned long long)(long long)fi;
                     __hip_atomic_fetch_add(lds_ptr<unsigned long long>(mytbl + ((cellp[bk] >> (8 * r)) & 0xffu) * 8), fx,
                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
@@ -315,7 +317,7 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
             long long sum = 0;
 #pragma unroll
             for (int t = 0; t < C::NTBL; ++t) sum += (long long)*lds_ptr<unsigned long long>(tbl0 + t * C::kTblBytes + cell * 8);
-            rpb_partial[(size_t)wg * C::CELLS + cell] = (float)((double)sum * (1.0 / 4398046511104.0));   // 2^-42
+            rpb_partial[(size_t)wg * C::CELLS + cell] = (float)((double)sum * (1.0 / 1048576.0));   // 2^-20
         }
     }
 }
