@@ -1,5 +1,6 @@
-// Gradients that sum over queries, on the matrix cores, for large windows (f16 / bf16, K >= 9): the query
-// rectangle of a key tile is streamed through LDS two rows at a time.
+// Gradients that sum over queries, on the matrix cores, where the query rectangle of a key tile does not fit the
+// LDS images of the other two kernels (f16 / bf16): large windows (K >= 11), and maps with an axis so short that a
+// tile is seen from both of its ends.  The rectangle is streamed through LDS two rows at a time.
 //   out_j = scale * sum over queries i whose window holds j of w[i, slot(i, j)] * x_i
 // (grad-v with w = attention weights, x = dout; grad-k with w = ds, x = q; arXiv 2204.07143, Appendix A).
 //
@@ -268,7 +269,7 @@ static hipError_t launch_inverse_rows_t(const Problem &p, const void *w, const v
 // patch must be seen from at most 16 NCB columns: both hold for every map with K <= min(H, W) (a tile next to both
 // ends of a short axis has at most W <= 2K + 2 columns).  Checked anyway.
 bool inverse_rows_supported(const Problem &p) {
-    if (p.D % kHeadDim != 0 || p.dtype == NA2D_F32 || p.K < 11) return false;
+    if (p.D % kHeadDim != 0 || p.dtype == NA2D_F32) return false;
     const int K = p.K, RW = kTileX + K - 1 + K / 2, NCOL = 16 * ((K + K / 2 + 3 + 15) / 16);
     if ((int64_t)p.W * K * K * 4 >= (int64_t)1 << 31) return false;   // a row of weights as a 32-bit byte count
     for (int tx0 = 0; tx0 < p.W; tx0 += kTileX) {
@@ -285,6 +286,10 @@ bool inverse_rows_supported(const Problem &p) {
 hipError_t launch_inverse_rows(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s) {
 #define NA2D_INVW_K(TT)                                                               \
     switch (p.K) {                                                                    \
+        case 3: return launch_inverse_rows_t<TT, 3>(p, w, x, scale, out, s);          \
+        case 5: return launch_inverse_rows_t<TT, 5>(p, w, x, scale, out, s);          \
+        case 7: return launch_inverse_rows_t<TT, 7>(p, w, x, scale, out, s);          \
+        case 9: return launch_inverse_rows_t<TT, 9>(p, w, x, scale, out, s);          \
         case 11: return launch_inverse_rows_t<TT, 11>(p, w, x, scale, out, s);        \
         case 13: return launch_inverse_rows_t<TT, 13>(p, w, x, scale, out, s);        \
         default: return hipErrorInvalidValue;                                         \

@@ -40,7 +40,7 @@ hipError_t launch_inverse(const Problem &p, const void *w, const void *x, float 
 bool inverse_ring_supported(const Problem &p);
 hipError_t launch_inverse_ring(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
 bool inverse_mfma_supported(const Problem &p);
-// large windows (K >= 11): the query rectangle streamed through LDS two rows at a time
+// what the two kernels above do not take (K >= 11, very short axes): the query rectangle streamed through LDS two rows at a time
 bool inverse_rows_supported(const Problem &p);
 hipError_t launch_inverse_rows(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
 hipError_t launch_inverse_mfma(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
