@@ -80,7 +80,8 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
     const int npos = units / heads;
     const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
     const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
-    const int b_begin = (split * nb) / splits, b_end = ((split + 1) * nb) / splits;
+    const int brange = batch_range_of(split, head, heads, splits);
+    const int b_begin = range_begin(brange, splits, nb), b_end = range_begin(brange + 1, splits, nb);
     if (b_begin >= b_end) return;
 
     // the zero words (one per stage) are never written by the loads

@@ -89,7 +89,8 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
     if (wg >= units * splits) return;
     const int npos = units / heads;
     const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
-    const int b_begin = (split * nb) / splits, b_end = ((split + 1) * nb) / splits;
+    const int brange = batch_range_of(split, head, heads, splits);
+    const int b_begin = range_begin(brange, splits, nb), b_end = range_begin(brange + 1, splits, nb);
     if (b_begin >= b_end) return;
 
     const int tid = threadIdx.x, lane = tid % kWave;

@@ -114,7 +114,8 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
     const int npos = units / heads;
     const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
     const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
-    const int b_begin = (split * nb) / splits, b_end = ((split + 1) * nb) / splits;
+    const int brange = batch_range_of(split, head, heads, splits);
+    const int b_begin = range_begin(brange, splits, nb), b_end = range_begin(brange + 1, splits, nb);
     if (b_begin >= b_end) return;
 
     const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);   // tile halo origin

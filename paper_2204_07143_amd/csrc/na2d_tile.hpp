@@ -102,5 +102,14 @@ static inline UnitSplit unit_split(int tiles_x, int tiles_y, int heads, int nb) 
     u.splits = s < nb ? s : nb;
     return u;
 }
+// First batch item of range `split` of `splits`.  Ranges differ by at most one item and the longer ones come
+// first: the workgroups that are dispatched first carry the extra tile, not the ones that start last.
+__host__ __device__ inline int range_begin(int split, int splits, int nb) { return (split * nb + splits - 1) / splits; }
+// Which range the workgroups of (split, head) take: rotated per head, so that the longer ranges of different heads
+// sit in different parts of the grid (different XCDs) instead of side by side.  All tile positions of one
+// (split, head) keep the same range: they share halo rows and run together.
+__device__ inline int batch_range_of(int split, int head, int heads, int splits) {
+    return (split + (head * splits) / heads) % splits;
+}
 
 }  // namespace na2d
