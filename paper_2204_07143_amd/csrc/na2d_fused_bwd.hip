@@ -85,7 +85,7 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
 
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int strip = wave >> 2, p = wave & 3;
+    const int strip = wave >> 2, p = patch_of_wave(wave);
     const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
     const int lds0 = lds_addr(lds);
 
@@ -452,7 +452,7 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
         soff = (y * W + x) * 4;
     }
 
-    const int strip = wave >> 2, p = wave & 3;
+    const int strip = wave >> 2, p = patch_of_wave(wave);
     const int sy0 = ty0 + 4 * strip, px0 = tx0 + 4 * p;   // this wave's key patch
     const bool active = sy0 < H && px0 < W;
     const int jy = sy0 + ky, jx = px0 + kx;                // this lane's key

@@ -73,7 +73,7 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
 
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int strip = wave >> 2, p = wave & 3;
+    const int strip = wave >> 2, p = patch_of_wave(wave);
     const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
     const int lds0 = lds_addr(lds);
 

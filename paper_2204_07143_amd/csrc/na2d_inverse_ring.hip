@@ -138,7 +138,7 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
     // four channels of position 4g + n / 4 of a block and receives the n-th channel of positions 4g .. 4g + 3.  The
     // channels are dealt so that MFMA row m of half hf is channel 8 (m / 4) + 4 hf + m % 4: a lane then ends up
     // with the eight consecutive channels 8g .. 8g + 7 of its key, one 16-byte store.
-    const int strip = wave >> 2, p = wave & 3;
+    const int strip = wave >> 2, p = patch_of_wave(wave);
     const int px0 = tx0 + 4 * p;
     const int oqx = inv_first(px0 < W ? px0 : W - 1, W, K);   // first query column that sees the patch
     const int xa_lane = x0 + (oqx - rx0 + 4 * g + (n >> 2)) * C::KB + (n & 3) * 16;

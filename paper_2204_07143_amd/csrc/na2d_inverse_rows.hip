@@ -92,7 +92,7 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
     const size_t w_bytes = (size_t)nb * heads * H * W * C::KK * SZ;   // size of the weight tensor
 
     // this wave's patch and this lane's key
-    const int strip = wave >> 2, p = wave & 3;
+    const int strip = wave >> 2, p = patch_of_wave(wave);
     const int sy0 = ty0 + 4 * strip, px0 = tx0 + 4 * p;
     const bool active = sy0 < H && px0 < W;
     const int jy = sy0 + ky, jx = px0 + kx;

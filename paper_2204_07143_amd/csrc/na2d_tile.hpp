@@ -89,6 +89,12 @@ template <int V> struct IntC {
     static constexpr int value = V;
 };
 
+// Which 4 x 4 patch of its strip (the upper or the lower four rows of the 16 x 8 tile: wave / 4) a wave takes.
+// Waves w and w + 4 share a SIMD; the rotation by two puts their patches on different halves of the tile, so a
+// tile that is only half inside the map (at the right border, or a map narrower than nine positions) keeps one
+// active wave on every SIMD instead of two on half of them.
+__device__ inline int patch_of_wave(int wave) { return (wave + 2 * (wave >> 2)) & 3; }
+
 // Work split of the position-stationary kernels: a unit is a (tile position, head) pair; the batch is
 // cut into `splits` ranges so that about two workgroups per compute unit exist.
 struct UnitSplit {
