@@ -14,6 +14,7 @@
 //     packed dot instructions for the 16-bit types, all sums are fp32.
 // k is a run-time argument (odd, <= 63); TQ is 256, or 128 for k > 31 so that the LDS images fit.
 #include "na1d_kernels.hpp"
+#include "lds_attr.hpp"
 #include "na2d_common.hpp"
 #include "na2d_kernels.hpp"   // the dtype dispatch macro
 
@@ -590,14 +591,8 @@ __global__ __launch_bounds__(TQ) void fbwd1d_kv_kernel(const T *__restrict__ q, 
 
 // ---- launchers ---------------------------------------------------------------------------------
 
-// Dynamic LDS beyond 64 KB needs the attribute; it is set once per kernel, to the most the kernel can ask for.
-template <typename Kern>
-static hipError_t allow_lds(Kern kern, int max_bytes, bool &done) {
-    if (done) return hipSuccess;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, max_bytes);
-    done = e == hipSuccess;
-    return e;
-}
+// Dynamic LDS beyond 64 KB needs the attribute (allow_lds); it is set to the most the kernel can ask for.
+using na2d::allow_lds;
 template <int TQ> constexpr int max_k() { return TQ == 256 ? 31 : kMaxK; }
 
 #define NA1D_DISPATCH(p, ...)                                                            \
@@ -619,7 +614,7 @@ static hipError_t qk_t(const Problem &p, const void *x, const void *y, const voi
     auto kern = qk1d_kernel<T, TQ>;
     static_assert(qk_lds_bytes<T, TQ>(max_k<TQ>()) <= 160 * 1024, "LDS");
     const int bytes = qk_lds_bytes<T, TQ>(p.K), tiles = tiles_of<TQ>(p);
-    static bool attr = false;
+    static na2d::LdsAllowed attr;
     if (hipError_t e = allow_lds(kern, qk_lds_bytes<T, TQ>(max_k<TQ>()), attr); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.planes() * tiles), dim3(TQ), bytes, s, static_cast<const T *>(x),
                        static_cast<const T *>(y), static_cast<const T *>(rpb), scale, static_cast<T *>(out), p.L, p.heads,
@@ -636,7 +631,7 @@ static hipError_t av_t(const Problem &p, const void *w, const void *y, float sca
     auto kern = av1d_kernel<T, TQ>;
     static_assert(av_lds_bytes<T, TQ>(max_k<TQ>()) <= 160 * 1024, "LDS");
     const int bytes = av_lds_bytes<T, TQ>(p.K), tiles = tiles_of<TQ>(p);
-    static bool attr = false;
+    static na2d::LdsAllowed attr;
     if (hipError_t e = allow_lds(kern, av_lds_bytes<T, TQ>(max_k<TQ>()), attr); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.planes() * tiles), dim3(TQ), bytes, s, static_cast<const T *>(w),
                        static_cast<const T *>(y), scale, static_cast<T *>(out), p.L, p.K, tiles);
@@ -652,7 +647,7 @@ static hipError_t inverse_t(const Problem &p, const void *w, const void *x, floa
     auto kern = inverse1d_kernel<T, TQ>;
     static_assert(inv_lds_bytes<T, TQ>(max_k<TQ>()) <= 160 * 1024, "LDS");
     const int bytes = inv_lds_bytes<T, TQ>(p.K), tiles = tiles_of<TQ>(p);
-    static bool attr = false;
+    static na2d::LdsAllowed attr;
     if (hipError_t e = allow_lds(kern, inv_lds_bytes<T, TQ>(max_k<TQ>()), attr); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.planes() * tiles), dim3(TQ), bytes, s, static_cast<const T *>(w),
                        static_cast<const T *>(x), scale, static_cast<T *>(out), p.L, p.K, tiles);
@@ -667,7 +662,7 @@ template <typename T, int TQ>
 static hipError_t softmax_t(const Problem &p, const void *logits, void *out, hipStream_t s) {
     auto kern = softmax1d_kernel<T, TQ>;
     const int bytes = mirror_bytes(TQ * p.K * (int)sizeof(T)), tiles = tiles_of<TQ>(p);
-    static bool attr = false;
+    static na2d::LdsAllowed attr;
     if (hipError_t e = allow_lds(kern, mirror_bytes(TQ * max_k<TQ>() * (int)sizeof(T)), attr); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.planes() * tiles), dim3(TQ), bytes, s, static_cast<const T *>(logits),
                        static_cast<T *>(out), p.L, p.K, tiles);
@@ -682,7 +677,7 @@ template <typename T, int TQ>
 static hipError_t softmax_bwd_t(const Problem &p, const void *attn, const void *dp, void *ds, hipStream_t s) {
     auto kern = softmax_bwd1d_kernel<T, TQ>;
     const int bytes = 2 * mirror_bytes(TQ * p.K * (int)sizeof(T)), tiles = tiles_of<TQ>(p);
-    static bool attr = false;
+    static na2d::LdsAllowed attr;
     if (hipError_t e = allow_lds(kern, 2 * mirror_bytes(TQ * max_k<TQ>() * (int)sizeof(T)), attr); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.planes() * tiles), dim3(TQ), bytes, s, static_cast<const T *>(attn),
                        static_cast<const T *>(dp), static_cast<T *>(ds), p.L, p.K, tiles);
@@ -699,7 +694,7 @@ static hipError_t fused_t(const Problem &p, const void *q, const void *k, const 
     auto kern = fused1d_kernel<T, TQ>;
     static_assert(fused_lds_bytes<T, TQ>(max_k<TQ>()) <= 160 * 1024, "LDS");
     const int bytes = fused_lds_bytes<T, TQ>(p.K), tiles = tiles_of<TQ>(p);
-    static bool attr = false;
+    static na2d::LdsAllowed attr;
     if (hipError_t e = allow_lds(kern, fused_lds_bytes<T, TQ>(max_k<TQ>()), attr); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.planes() * tiles), dim3(TQ), bytes, s, static_cast<const T *>(q),
                        static_cast<const T *>(k), static_cast<const T *>(v), static_cast<const T *>(rpb), scale,
@@ -722,7 +717,7 @@ template <typename T, int TQ>
 static hipError_t rpb_t(const Problem &p, const void *ds, float *d_rpb, void *workspace, hipStream_t s) {
     auto kern = rpb_partial1d_kernel<T, TQ>;
     const int bytes = rpb_lds_bytes<T, TQ>(p.K), tiles = tiles_of<TQ>(p);
-    static bool attr = false;
+    static na2d::LdsAllowed attr;
     if (hipError_t e = allow_lds(kern, rpb_lds_bytes<T, TQ>(max_k<TQ>()), attr); e != hipSuccess) return e;
     long long *partial = static_cast<long long *>(workspace);
     hipLaunchKernelGGL(kern, dim3(p.planes() * tiles), dim3(TQ), bytes, s, static_cast<const T *>(ds), partial, p.L, p.K, tiles);
@@ -752,7 +747,7 @@ static hipError_t fused_bwd_t(const Problem &p, const void *q, const void *k, co
     {
         auto kern = fbwd1d_q_kernel<T, TQ>;
         static_assert(fbwd_q_lds_bytes<T, TQ>(max_k<TQ>()) <= 160 * 1024, "LDS");
-        static bool attr = false;
+        static na2d::LdsAllowed attr;
         if (hipError_t e = allow_lds(kern, fbwd_q_lds_bytes<T, TQ>(max_k<TQ>()), attr); e != hipSuccess) return e;
         const int bytes = fbwd_q_lds_bytes<T, TQ>(p.K);
         hipLaunchKernelGGL(kern, dim3(p.planes() * tiles), dim3(TQ), bytes, s,
@@ -764,7 +759,7 @@ static hipError_t fused_bwd_t(const Problem &p, const void *q, const void *k, co
     {
         auto kern = fbwd1d_kv_kernel<T, TQ>;
         static_assert(fbwd_kv_lds_bytes<T, TQ>(max_k<TQ>()) <= 160 * 1024, "LDS");
-        static bool attr = false;
+        static na2d::LdsAllowed attr;
         if (hipError_t e = allow_lds(kern, fbwd_kv_lds_bytes<T, TQ>(max_k<TQ>()), attr); e != hipSuccess) return e;
         const int bytes = fbwd_kv_lds_bytes<T, TQ>(p.K);
         hipLaunchKernelGGL(kern, dim3(p.planes() * tiles), dim3(TQ), bytes, s,

@@ -320,13 +320,8 @@ static hipError_t launch_av_mfma_small_t(const Problem &p, const void *w, const 
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
     auto kern = av_mfma_small_kernel<T, K, RPB>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsAllowed allowed;
+    if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     // one launch per 32-channel slice of the head vector (the weights are read again by each)
     for (int sl = 0; sl < p.D / kHeadDim; ++sl) {
         hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,

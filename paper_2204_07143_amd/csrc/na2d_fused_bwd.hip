@@ -333,13 +333,8 @@ static hipError_t launch_fbwd_q_t(const Problem &p, const void *q, const void *k
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
     const bool with_rpb = rpb_partial != nullptr;
     auto kern = with_rpb ? fbwd_q_kernel<T, K, true> : fbwd_q_kernel<T, K, false>;
-    static bool attr_set[2] = {false, false};
-    if (!attr_set[with_rpb]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set[with_rpb] = true;
-    }
+    static LdsAllowed allowed[2];
+    if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed[with_rpb]); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
                        static_cast<const T *>(rpb), scale, lse, static_cast<const T *>(dout), static_cast<T *>(dq), delta,
@@ -589,13 +584,8 @@ static hipError_t launch_fbwd_kv_c(const Problem &p, const void *q, const void *
     int splits = (256 * C::kWgPerCu) / units;
     splits = splits < 1 ? 1 : (splits < p.B ? splits : p.B);
     auto kern = fbwd_kv_kernel<T, K, COMPACT>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsAllowed allowed;
+    if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(units * splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
                        static_cast<const T *>(rpb), scale, lse, delta, static_cast<const T *>(dout), static_cast<T *>(dk),

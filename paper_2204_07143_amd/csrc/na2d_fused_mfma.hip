@@ -278,13 +278,8 @@ static hipError_t launch_fused_mfma_small_ns(const Problem &p, const void *q, co
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
     auto kern = fused_mfma_small_kernel<T, K, NS>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsAllowed allowed;
+    if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
                        static_cast<const T *>(rpb), scale, static_cast<T *>(out), lse, p.H, p.W, p.heads, p.B, tiles_y,

@@ -291,13 +291,8 @@ static hipError_t launch_inverse_mfma_c(const Problem &p, const void *w, const v
     splits = splits < 1 ? 1 : (splits < p.B ? splits : p.B);
     const int nwg = units * splits;
     auto kern = inverse_mfma_kernel<T, K, STRIPS, PPW, COMPACT>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsAllowed allowed;
+    if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     for (int sl = 0; sl < p.D / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector
         hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
                            static_cast<const T *>(w), static_cast<const T *>(x) + sl * kHeadDim, scale,

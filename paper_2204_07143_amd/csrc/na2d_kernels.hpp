@@ -5,6 +5,7 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "lds_attr.hpp"
 #include "na2d.h"
 
 namespace na2d {

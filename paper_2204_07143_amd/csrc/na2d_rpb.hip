@@ -258,13 +258,8 @@ static hipError_t launch_rpb_bwd_t(const Problem &p, const void *ds, float *d_rp
     const RpbSplit sp = rpb_split(p.planes(), p.H, p.W, K, (int)sizeof(T));
     auto kern = rpb_partial_kernel<T, K>;
     static_assert(C::kLdsBytes <= 160 * 1024, "segments do not fit the 160 KB LDS of a CDNA4 compute unit");
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsAllowed allowed;
+    if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.planes() * sp.groups_per_plane), dim3(256), C::kLdsBytes, s,
                        static_cast<const T *>(ds), static_cast<float *>(workspace), p.H, p.W, sp);
     hipError_t e = hipGetLastError();

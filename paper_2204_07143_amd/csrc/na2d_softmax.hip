@@ -150,13 +150,8 @@ static hipError_t launch_softmax_t(const Problem &p, const void *in, void *out, 
     const size_t nrows = p.queries();
     const unsigned grid = (unsigned)((nrows + C::kRows - 1) / C::kRows);
     auto kern = softmax_kernel<T, K>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::kRegion);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsAllowed allowed;
+    if (hipError_t e = allow_lds(kern, C::kRegion, allowed); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), C::kRegion, s, static_cast<const T *>(in),
                        static_cast<T *>(out), nrows);
     return hipGetLastError();
@@ -169,13 +164,8 @@ static hipError_t launch_softmax_bwd_t(const Problem &p, const void *attn, const
     const unsigned grid = (unsigned)((nrows + C::kRows - 1) / C::kRows);
     auto kern = softmax_bwd_kernel<T, K>;
     static_assert(2 * C::kRegion <= 160 * 1024, "rows do not fit the 160 KB LDS of a CDNA4 compute unit");
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * C::kRegion);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsAllowed allowed;
+    if (hipError_t e = allow_lds(kern, 2 * C::kRegion, allowed); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(C::kThreads), 2 * C::kRegion, s, static_cast<const T *>(attn),
                        static_cast<const T *>(dp), static_cast<T *>(ds), nrows);
     return hipGetLastError();
