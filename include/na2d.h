@@ -60,7 +60,8 @@ typedef enum {
     NA2D_ERR_KERNEL_SIZE = -3, /* k even, or not in {3,5,7,9,11,13} */
     NA2D_ERR_TOO_SMALL = -4,   /* k > min(H, W): the neighbourhood is undefined */
     NA2D_ERR_HEAD_DIM = -5,    /* D not in {16, 32, 64, 128}, or too large for this k and dtype (see above) */
-    NA2D_ERR_SHAPE = -6,       /* non-positive extent, or a tensor beyond 2^31-1 elements */
+    NA2D_ERR_SHAPE = -6,       /* non-positive extent, a tensor beyond 2^31-1 elements, or one (batch, head)
+                                  plane of a tensor beyond 2^31-1 bytes */
     NA2D_ERR_ALIGN = -7,       /* a data pointer is not 16-byte aligned */
     NA2D_ERR_WORKSPACE = -8,   /* workspace missing or smaller than na2d_workspace_bytes() */
     NA2D_ERR_LAUNCH = -9,      /* hipGetLastError() reported a launch failure */

@@ -18,6 +18,9 @@ static int validate(const na1d_problem *p) {
     const int64_t nq = (int64_t)p->B * p->heads * p->L;
     const int64_t widest = p->k > p->D ? p->k : p->D;
     if (nq * widest > (int64_t)INT32_MAX) return NA2D_ERR_SHAPE;
+    // ... and one (batch, head) plane of any tensor stays below 2^31 bytes
+    const int64_t elem = p->dtype == NA2D_F32 ? 4 : 2;
+    if ((int64_t)p->L * widest * elem > (int64_t)INT32_MAX) return NA2D_ERR_SHAPE;
     return NA2D_OK;
 }
 

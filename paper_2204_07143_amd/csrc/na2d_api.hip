@@ -22,6 +22,9 @@ static int validate(const na2d_problem *p) {
     const int64_t nq = (int64_t)p->B * p->heads * p->H * p->W;
     const int64_t widest = k * k > p->D ? k * k : p->D;
     if (nq * widest > (int64_t)INT32_MAX) return NA2D_ERR_SHAPE;
+    // ... and one (batch, head) plane of any tensor stays below 2^31 bytes: offsets inside a plane are 32-bit
+    const int64_t elem = p->dtype == NA2D_F32 ? 4 : 2;
+    if ((int64_t)p->H * p->W * widest * elem > (int64_t)INT32_MAX) return NA2D_ERR_SHAPE;
     return NA2D_OK;
 }
 

@@ -49,6 +49,9 @@ def P(B=1, heads=1, H=14, W=14, D=32, k=3, dtype=0):
     (P(D=48), -5), (P(D=8), -5), (P(D=128, k=5, H=20, W=20, dtype=0), -5), (P(D=64, k=11, H=20, W=20, dtype=0), -5),
     (P(B=0), -6), (P(H=-1), -6),
     (P(B=4096, heads=16, H=512, W=512, k=3), -6),
+    # one (batch, head) plane of the attention tensor: below / beyond 2^31 bytes (offsets inside a plane are 32-bit)
+    (P(B=1, heads=1, H=4096, W=4096, k=7, dtype=1), 0), (P(B=1, heads=1, H=6000, W=6000, k=7, dtype=1), -6),
+    (P(B=1, heads=1, H=3000, W=3000, k=7, dtype=0), 0), (P(B=1, heads=1, H=4096, W=4096, k=7, dtype=0), -6),
 ])
 def test_problem_validation(prob, code):
     assert binding.na2d_validate_problem(prob) == code
