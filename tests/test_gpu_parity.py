@@ -164,6 +164,13 @@ def test_large_windows_many_tiles_odd_batch(oracle, H, W, k, dtype):
             planes=[(0, 0), (2, 1), (4, 2)])
 
 
+@pytest.mark.parametrize("B,heads,H,W,k,dtype", [(40, 3, 20, 20, 7, "f16"), (37, 5, 9, 17, 5, "bf16"), (70, 1, 8, 16, 7, "f16")])
+def test_batch_ranges_cover_every_plane(oracle, B, heads, H, W, k, dtype):
+    # more batch items than ranges, ranges of unequal length, rotated per head by an amount that does not
+    # divide their number: every plane is checked, so a plane that no workgroup takes (or two take) shows
+    run_all(oracle, synth.Problem(B, heads, H, W, 32, k, dtype), seed=B + heads + H + W + k)
+
+
 def test_no_bias_and_custom_scale(oracle):
     p = synth.Problem(1, 2, 20, 18, 32, 5, "f16")
     run_all(oracle, p, seed=5, use_rpb=False, scale=0.11)
