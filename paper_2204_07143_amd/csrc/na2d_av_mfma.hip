@@ -55,7 +55,7 @@ struct AvSmallCfg {
 template <typename T, int K, bool RPB>
 __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfma_small_kernel(const T *__restrict__ w, const T *__restrict__ y, float scale,
                                                                T *__restrict__ out, float *__restrict__ rpb_partial, int H,
-                                                               int W, int heads, int nb, int tiles_y, int units, int splits,
+                                                               int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd,
                                                                int pitch) {
     // `pitch`: bytes between consecutive positions of y and out.  The kernel works on 32 channels; a longer
     // head vector is served one 32-channel slice per launch (y and out then point at the slice).
@@ -77,11 +77,9 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
     // neighbouring workgroups take neighbouring tile positions of the same planes (the position index
     // runs fastest), so the positions whose halos overlap run at the same time on the same XCD and
     // the overlap is read from HBM once
-    const int npos = units / heads;
-    const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
-    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
-    const int brange = batch_range_of(split, head, heads, splits);
-    const int b_begin = range_begin(brange, splits, nb), b_end = range_begin(brange + 1, splits, nb);
+    const WorkItem work = decode_work(wg, heads, tiles_y, splits, gd);
+    const int head = work.head, ty0 = work.ty * C::TY, tx0 = work.tx * kTileX;
+    const int b_begin = work.b_begin, b_end = work.b_end;
     if (b_begin >= b_end) return;
 
     // the zero words (one per stage) are never written by the loads
@@ -327,7 +325,7 @@ static hipError_t launch_av_mfma_small_t(const Problem &p, const void *w, const 
         hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                            static_cast<const T *>(w), static_cast<const T *>(y) + sl * kHeadDim, scale,
                            static_cast<T *>(out) + sl * kHeadDim, rpb_partial, p.H, p.W, p.heads, p.B, tiles_y, us.units,
-                           us.splits, p.D * (int)sizeof(T));
+                           us.splits, us.gd, p.D * (int)sizeof(T));
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
     }
     return hipSuccess;

@@ -48,7 +48,7 @@ struct BwdFusedCfg {
 template <typename T, int K>
 __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__restrict__ attn, const T *__restrict__ dout,
                                                                  const T *__restrict__ v, T *__restrict__ ds, int H, int W,
-                                                                 int heads, int nb, int tiles_y, int units, int splits) {
+                                                                 int heads, int nb, int tiles_y, int units, int splits, GridDecode gd) {
     using C = BwdFusedCfg<T, K>;
     using P = Patch<K>;
     static_assert(C::kThreads == 512, "launch bounds");
@@ -65,11 +65,9 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
 
     const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
     if (wg >= units * splits) return;
-    const int npos = units / heads;
-    const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
-    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
-    const int brange = batch_range_of(split, head, heads, splits);
-    const int b_begin = range_begin(brange, splits, nb), b_end = range_begin(brange + 1, splits, nb);
+    const WorkItem work = decode_work(wg, heads, tiles_y, splits, gd);
+    const int head = work.head, ty0 = work.ty * C::TY, tx0 = work.tx * kTileX;
+    const int b_begin = work.b_begin, b_end = work.b_end;
     if (b_begin >= b_end) return;
 
     const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);   // tile halo origin
@@ -250,7 +248,7 @@ static hipError_t launch_bwd_fused_t(const Problem &p, const void *attn, const v
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(attn), static_cast<const T *>(dout), static_cast<const T *>(v),
-                       static_cast<T *>(ds), p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits);
+                       static_cast<T *>(ds), p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd);
     return hipGetLastError();
 }
 

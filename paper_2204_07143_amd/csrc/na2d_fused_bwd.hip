@@ -76,7 +76,7 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
                                                         const float *__restrict__ lse, const T *__restrict__ dout,
                                                         T *__restrict__ dq,
                                                         float *__restrict__ delta_out, float *__restrict__ rpb_partial,
-                                                        int H, int W, int heads, int nb, int tiles_y, int units, int splits) {
+                                                        int H, int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd) {
     using C = FbwdQCfg<T, K>;
     using P = Patch<K>;
     static_assert(C::kThreads == 512, "launch bounds");
@@ -94,11 +94,9 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
     // neighbouring workgroups take neighbouring tile positions of the same planes (the position index
     // runs fastest), so the positions whose halos overlap run at the same time on the same XCD and
     // the overlap is read from HBM once
-    const int npos = units / heads;
-    const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
-    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
-    const int brange = batch_range_of(split, head, heads, splits);
-    const int b_begin = range_begin(brange, splits, nb), b_end = range_begin(brange + 1, splits, nb);
+    const WorkItem work = decode_work(wg, heads, tiles_y, splits, gd);
+    const int head = work.head, ty0 = work.ty * C::TY, tx0 = work.tx * kTileX;
+    const int b_begin = work.b_begin, b_end = work.b_end;
 
     const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);   // tile halo origin
     const int sy0 = ty0 + 4 * strip, px0 = tx0 + 4 * p;                                     // this wave's patch
@@ -338,7 +336,7 @@ static hipError_t launch_fbwd_q_t(const Problem &p, const void *q, const void *k
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
                        static_cast<const T *>(rpb), scale, lse, static_cast<const T *>(dout), static_cast<T *>(dq), delta,
-                       rpb_partial, p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits);
+                       rpb_partial, p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd);
     return hipGetLastError();
 }
 
@@ -393,7 +391,7 @@ template <typename T, int K, bool COMPACT>
 __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) void fbwd_kv_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, const T *__restrict__ rpb, float scale,
     const float *__restrict__ lse, const float *__restrict__ delta, const T *__restrict__ dout, T *__restrict__ dk,
-    T *__restrict__ dv, int H, int W, int heads, int nb, int tiles_y, int units, int splits) {
+    T *__restrict__ dv, int H, int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd) {
     using C = FbwdKvCfg<T, K, COMPACT>;
     using XHalo = typename C::XHalo;
     constexpr float kLog2e = 1.4426950408889634f;
@@ -402,10 +400,9 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
 
     const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
     if (wg >= units * splits) return;
-    const int npos = units / heads;
-    const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
-    const int brange = batch_range_of(split, head, heads, splits);
-    const int b_begin = range_begin(brange, splits, nb), b_end = range_begin(brange + 1, splits, nb);
+    const WorkItem work = decode_work(wg, heads, tiles_y, splits, gd);
+    const int head = work.head;
+    const int b_begin = work.b_begin, b_end = work.b_end;
     if (b_begin >= b_end) return;
 
     const int tid = threadIdx.x, lane = tid % kWave;
@@ -427,7 +424,7 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
         *lds_ptr<f16_t>(bias0 + i * 2) = (f16_t)val;
     }
 
-    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
+    const int ty0 = work.ty * C::TY, tx0 = work.tx * kTileX;
     const int tx1 = tx0 + kTileX - 1 < W - 1 ? tx0 + kTileX - 1 : W - 1;
     const int ry0 = inv_first(ty0, H, K);   // the rectangle (fits RH x RW: checked by the host)
     const int rx0 = inv_first(tx0, W, K), rx1 = inv_last(tx1, W, K);
@@ -589,7 +586,7 @@ static hipError_t launch_fbwd_kv_c(const Problem &p, const void *q, const void *
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(units * splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
                        static_cast<const T *>(rpb), scale, lse, delta, static_cast<const T *>(dout), static_cast<T *>(dk),
-                       static_cast<T *>(dv), p.H, p.W, p.heads, p.B, tiles_y, units, splits);
+                       static_cast<T *>(dv), p.H, p.W, p.heads, p.B, tiles_y, units, splits, make_grid_decode(tiles_x, tiles_y, p.heads, p.B, splits));
     return hipGetLastError();
 }
 

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
                                                                   const T *__restrict__ v, const T *__restrict__ rpb,
                                                                   float scale, T *__restrict__ out, float *__restrict__ lse,
                                                                   int H, int W, int heads, int nb, int tiles_y, int units,
-                                                                  int splits) {
+                                                                  int splits, GridDecode gd) {
     using C = FusedSmallCfg<T, K, NS>;
     using P = Patch<K>;
     static_assert(C::kThreads == 512, "launch bounds");
@@ -82,11 +82,9 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
     // neighbouring workgroups take neighbouring tile positions of the same planes (the position index
     // runs fastest), so the positions whose halos overlap run at the same time on the same XCD and
     // the overlap is read from HBM once
-    const int npos = units / heads;
-    const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
-    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
-    const int brange = batch_range_of(split, head, heads, splits);
-    const int b_begin = range_begin(brange, splits, nb), b_end = range_begin(brange + 1, splits, nb);
+    const WorkItem work = decode_work(wg, heads, tiles_y, splits, gd);
+    const int head = work.head, ty0 = work.ty * C::TY, tx0 = work.tx * kTileX;
+    const int b_begin = work.b_begin, b_end = work.b_end;
     if (b_begin >= b_end) return;
 
     const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);   // tile halo origin
@@ -283,7 +281,7 @@ static hipError_t launch_fused_mfma_small_ns(const Problem &p, const void *q, co
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
                        static_cast<const T *>(rpb), scale, static_cast<T *>(out), lse, p.H, p.W, p.heads, p.B, tiles_y,
-                       us.units, us.splits);
+                       us.units, us.splits, us.gd);
     return hipGetLastError();
 }
 

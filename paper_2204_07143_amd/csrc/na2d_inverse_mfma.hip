@@ -69,7 +69,7 @@ struct InvMfmaCfg {
 template <typename T, int K, int STRIPS, int PPW, bool COMPACT>
 __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>::kWavesPerSimd)) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
                                                                        float scale, T *__restrict__ out, int H, int W,
-                                                                       int heads, int nb, int tiles_y, int units, int splits,
+                                                                       int heads, int nb, int tiles_y, int units, int splits, GridDecode gd,
                                                                        int pitch) {
     // `pitch`: bytes between consecutive positions of x and out (a longer head vector is served one 32-channel
     // slice per launch, x and out pointing at the slice)
@@ -87,10 +87,9 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
     // adjacent tiles share are fetched from memory once and found in the L2 cache by the others.
     const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
     if (wg >= units * splits) return;
-    const int npos = units / heads;
-    const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
-    const int brange = batch_range_of(split, head, heads, splits);
-    const int b_begin = range_begin(brange, splits, nb), b_end = range_begin(brange + 1, splits, nb);
+    const WorkItem work = decode_work(wg, heads, tiles_y, splits, gd);
+    const int head = work.head;
+    const int b_begin = work.b_begin, b_end = work.b_end;
     if (b_begin >= b_end) return;
 
     const int tid = threadIdx.x, lane = tid % kWave;
@@ -110,7 +109,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
     // a lane then ends up with the eight consecutive channels 8g .. 8g + 7 of its key, one 16-byte store.
     const int xa_lane = lds0 + (4 * g + (n >> 2)) * Traits<T>::kKeyBytes + (n & 3) * 16;
 
-    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
+    const int ty0 = work.ty * C::TY, tx0 = work.tx * kTileX;
     const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
     const int tx1 = tx0 + kTileX - 1 < W - 1 ? tx0 + kTileX - 1 : W - 1;
     const int ry0 = inv_first(ty0, H, K), ry1 = inv_last(ty1, H, K);
@@ -290,13 +289,14 @@ static hipError_t launch_inverse_mfma_c(const Problem &p, const void *w, const v
     int splits = (256 * kWgPerCu) / units;
     splits = splits < 1 ? 1 : (splits < p.B ? splits : p.B);
     const int nwg = units * splits;
+    const GridDecode gd = make_grid_decode(tiles_x, tiles_y, p.heads, p.B, splits);
     auto kern = inverse_mfma_kernel<T, K, STRIPS, PPW, COMPACT>;
     static LdsAllowed allowed;
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     for (int sl = 0; sl < p.D / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector
         hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
                            static_cast<const T *>(w), static_cast<const T *>(x) + sl * kHeadDim, scale,
-                           static_cast<T *>(out) + sl * kHeadDim, p.H, p.W, p.heads, p.B, tiles_y, units, splits,
+                           static_cast<T *>(out) + sl * kHeadDim, p.H, p.W, p.heads, p.B, tiles_y, units, splits, gd,
                            p.D * (int)sizeof(T));
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
     }

@@ -55,7 +55,7 @@ struct InvRowsCfg {
 template <typename T, int K>
 __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restrict__ w, const T *__restrict__ x, float scale,
                                                               T *__restrict__ out, int H, int W, int heads, int nb,
-                                                              int tiles_y, int units, int splits, int pitch) {
+                                                              int tiles_y, int units, int splits, GridDecode gd, int pitch) {
     // `pitch`: bytes between consecutive positions of x and out (a longer head vector is served one 32-channel
     // slice per launch, x and out pointing at the slice)
     using C = InvRowsCfg<T, K>;
@@ -65,10 +65,9 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
 
     const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
     if (wg >= units * splits) return;
-    const int npos = units / heads;
-    const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
-    const int brange = batch_range_of(split, head, heads, splits);
-    const int b_begin = range_begin(brange, splits, nb), b_end = range_begin(brange + 1, splits, nb);
+    const WorkItem work = decode_work(wg, heads, tiles_y, splits, gd);
+    const int head = work.head;
+    const int b_begin = work.b_begin, b_end = work.b_end;
     if (b_begin >= b_end) return;
 
     const int tid = threadIdx.x, lane = tid % kWave;
@@ -79,7 +78,7 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
     // Everything the loads do not write must hold finite numbers (it meets zero weights only); the zero words too.
     for (int i = tid * 16; i < C::kLdsBytes; i += C::kThreads * 16) *lds_ptr<u32x4>(lds0 + i) = u32x4{0u, 0u, 0u, 0u};
 
-    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
+    const int ty0 = work.ty * C::TY, tx0 = work.tx * kTileX;
     const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
     const int tx1 = tx0 + kTileX - 1 < W - 1 ? tx0 + kTileX - 1 : W - 1;
     const int ry0 = inv_first(ty0, H, K), ry1 = inv_last(ty1, H, K);
@@ -254,7 +253,7 @@ static hipError_t launch_inverse_rows_t(const Problem &p, const void *w, const v
     for (int sl = 0; sl < p.D / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector
         hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                            static_cast<const T *>(w), static_cast<const T *>(x) + sl * kHeadDim, scale,
-                           static_cast<T *>(out) + sl * kHeadDim, p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits,
+                           static_cast<T *>(out) + sl * kHeadDim, p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd,
                            p.D * (int)sizeof(T));
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
     }

@@ -86,7 +86,7 @@ __device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, in
 template <typename T, int K, int NS>
 __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk_mfma_small_kernel(
     const T *__restrict__ x, const T *__restrict__ y, const T *__restrict__ rpb, float scale, T *__restrict__ logits, int H,
-    int W, int heads, int nb, int tiles_y, int units, int splits) {
+    int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd) {
     using C = QkSmallCfg<T, K, NS>;
     using P = Patch<K>;
     constexpr int kFlushPasses = (C::kRowBytes + kWave * 16 - 1) / (kWave * 16);   // 16-byte chunks per lane and row run
@@ -111,11 +111,9 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
     // neighbouring workgroups take neighbouring tile positions of the same planes (the position index
     // runs fastest), so the positions whose halos overlap run at the same time on the same XCD and
     // the overlap is read from HBM once
-    const int npos = units / heads;
-    const int pos = wg % npos, head = (wg / npos) % heads, split = wg / (npos * heads);
-    const int ty0 = (pos % tiles_y) * C::TY, tx0 = (pos / tiles_y) * kTileX;
-    const int brange = batch_range_of(split, head, heads, splits);
-    const int b_begin = range_begin(brange, splits, nb), b_end = range_begin(brange + 1, splits, nb);
+    const WorkItem work = decode_work(wg, heads, tiles_y, splits, gd);
+    const int head = work.head, ty0 = work.ty * C::TY, tx0 = work.tx * kTileX;
+    const int b_begin = work.b_begin, b_end = work.b_end;
     if (b_begin >= b_end) return;
 
     const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);   // tile halo origin
@@ -304,7 +302,7 @@ static hipError_t launch_qk_mfma_small_ns(const Problem &p, const void *x, const
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(x), static_cast<const T *>(y), static_cast<const T *>(rpb), scale,
-                       static_cast<T *>(logits), p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits);
+                       static_cast<T *>(logits), p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd);
     return hipGetLastError();
 }
 

@@ -6,6 +6,7 @@
 // Neighborhood Attention": key tile side = query tile side + k - 1), and every thread then
 // works out of LDS.  Tile sizes here are chosen for CDNA4's 160 KB LDS and 64-wide waves.
 #pragma once
+#include <stdint.h>
 
 #include "na2d_common.hpp"
 
@@ -95,10 +96,46 @@ template <int V> struct IntC {
 // active wave on every SIMD instead of two on half of them.
 __device__ inline int patch_of_wave(int wave) { return (wave + 2 * (wave >> 2)) & 3; }
 
+// Division of a non-negative int by a divisor known at launch: the host works out a multiplier and a shift
+// (m = ceil(2^(31+L) / d), L = ceil(log2 d)), the device needs a shift, a multiply-high and a shift, all on the
+// scalar unit for uniform values.  Exact for every 0 <= n < 2^31 (Granlund & Montgomery, "Division by invariant
+// integers using multiplication": n < 2^31 needs 31 + L fraction bits, and 2n keeps the product inside 64 bits).
+// A workgroup decodes its place in the grid before it can issue its first load; the runtime divisions of that
+// decode were two thirds of its scalar instructions.
+struct FastDiv {
+    uint32_t m, L;
+};
+static inline FastDiv make_fastdiv(int d) {
+    FastDiv f;
+    f.L = 0;
+    while ((1ll << f.L) < (long long)d) ++f.L;
+    f.m = (uint32_t)((((unsigned long long)1 << (31 + f.L)) + (unsigned long long)d - 1) / (unsigned long long)d);
+    return f;
+}
+__device__ __forceinline__ int fdiv(int n, FastDiv f) { return (int)(__umulhi((uint32_t)n << 1, f.m) >> f.L); }
+
+// What a workgroup of a position-stationary kernel needs to find its tile position, head and batch range.
+struct GridDecode {
+    FastDiv by_npos, by_heads, by_tiles_y, by_splits;
+    int npos, range_base, range_rem;   // nb = splits * base + rem; batch range r starts at r * base + ceil(r * rem / splits)
+};
+
 // Work split of the position-stationary kernels: a unit is a (tile position, head) pair; the batch is
 // cut into `splits` ranges so that about two workgroups per compute unit exist.
+static inline GridDecode make_grid_decode(int tiles_x, int tiles_y, int heads, int nb, int splits) {
+    GridDecode gd;
+    gd.npos = tiles_x * tiles_y;
+    gd.by_npos = make_fastdiv(gd.npos);
+    gd.by_heads = make_fastdiv(heads);
+    gd.by_tiles_y = make_fastdiv(tiles_y);
+    gd.by_splits = make_fastdiv(splits);
+    gd.range_base = nb / splits;
+    gd.range_rem = nb % splits;
+    return gd;
+}
 struct UnitSplit {
     int units, splits;
+    GridDecode gd;
 };
 static inline UnitSplit unit_split(int tiles_x, int tiles_y, int heads, int nb) {
     UnitSplit u;
@@ -106,16 +143,29 @@ static inline UnitSplit unit_split(int tiles_x, int tiles_y, int heads, int nb) 
     int s = (256 * 2) / u.units;
     s = s < 1 ? 1 : s;
     u.splits = s < nb ? s : nb;
+    u.gd = make_grid_decode(tiles_x, tiles_y, heads, nb, u.splits);
     return u;
 }
-// First batch item of range `split` of `splits`.  Ranges differ by at most one item and the longer ones come
-// first: the workgroups that are dispatched first carry the extra tile, not the ones that start last.
-__host__ __device__ inline int range_begin(int split, int splits, int nb) { return (split * nb + splits - 1) / splits; }
-// Which range the workgroups of (split, head) take: rotated per head, so that the longer ranges of different heads
-// sit in different parts of the grid (different XCDs) instead of side by side.  All tile positions of one
-// (split, head) keep the same range: they share halo rows and run together.
-__device__ inline int batch_range_of(int split, int head, int heads, int splits) {
-    return (split + (head * splits) / heads) % splits;
+struct WorkItem {
+    int pos, head, ty, tx, b_begin, b_end;   // tile row / column index; batch items [b_begin, b_end)
+};
+__device__ __forceinline__ WorkItem decode_work(int wg, int heads, int tiles_y, int splits, const GridDecode &gd) {
+    WorkItem w;
+    const int wq = fdiv(wg, gd.by_npos), split = fdiv(wq, gd.by_heads);
+    w.pos = wg - wq * gd.npos;
+    w.head = wq - split * heads;
+    w.tx = fdiv(w.pos, gd.by_tiles_y);
+    w.ty = w.pos - w.tx * tiles_y;
+    // Ranges differ by at most one item; where only one is longer it comes first, so that a workgroup dispatched
+    // early carries the extra tile.  Which range (split, head) takes is rotated per head, so that the longer ranges of different heads
+    // sit in different parts of the grid (different XCDs) instead of side by side; all tile positions of one
+    // (split, head) keep the same range: they share halo rows and run together.
+    int r = split + fdiv(w.head * splits, gd.by_heads);   // < 2 splits
+    r = r >= splits ? r - splits : r;
+    // range r = [ceil(r nb / splits), ceil((r + 1) nb / splits)): the ranges that hold one item more are spread evenly
+    w.b_begin = r * gd.range_base + fdiv(r * gd.range_rem + splits - 1, gd.by_splits);
+    w.b_end = (r + 1) * gd.range_base + fdiv((r + 1) * gd.range_rem + splits - 1, gd.by_splits);
+    return w;
 }
 
 }  // namespace na2d
