@@ -51,7 +51,8 @@ struct InvRingCfg {
 template <typename T, int K>
 __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restrict__ w, const T *__restrict__ x, float scale,
                                                               T *__restrict__ out, int H, int W, int tiles_x, int tiles_y,
-                                                              int nplanes, int nseg, int pitch) {
+                                                              int nplanes, int nseg, FastDiv by_tiles_x, FastDiv by_nseg,
+                                                              int pitch) {
     // `pitch`: bytes between consecutive positions of x and out (a longer head vector is served one 32-channel
     // slice per launch, x and out pointing at the slice)
     using C = InvRingCfg<T, K>;
@@ -63,8 +64,8 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
     // nseg segments of consecutive tiles when there are too few planes x columns to fill the chip.
     const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
     if (wg >= nplanes * tiles_x * nseg) return;
-    const int tix = wg % tiles_x, seg = (wg / tiles_x) % nseg, plane = wg / (tiles_x * nseg);
-    const int t_begin = (seg * tiles_y) / nseg, t_end = ((seg + 1) * tiles_y) / nseg;
+    const int wq = fdiv(wg, by_tiles_x), tix = wg - wq * tiles_x, plane = fdiv(wq, by_nseg), seg = wq - plane * nseg;
+    const int t_begin = fdiv(seg * tiles_y, by_nseg), t_end = fdiv((seg + 1) * tiles_y, by_nseg);
     if (t_begin >= t_end) return;
 
     const int tid = threadIdx.x, lane = tid % kWave;
@@ -262,7 +263,8 @@ static hipError_t launch_inverse_ring_t(const Problem &p, const void *w, const v
     for (int sl = 0; sl < p.D / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector
         hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s, static_cast<const T *>(w),
                            static_cast<const T *>(x) + sl * kHeadDim, scale, static_cast<T *>(out) + sl * kHeadDim, p.H, p.W,
-                           tiles_x, tiles_y, p.planes(), nseg, p.D * (int)sizeof(T));
+                           tiles_x, tiles_y, p.planes(), nseg, make_fastdiv(tiles_x), make_fastdiv(nseg),
+                           p.D * (int)sizeof(T));
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
     }
     return hipSuccess;
