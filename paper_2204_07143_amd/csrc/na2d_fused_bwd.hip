@@ -471,6 +471,9 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
         const bool ok = ix <= rx1 && key_ok && (unsigned)(jx - win_start(ix < W ? ix : W - 1, W, K)) < (unsigned)K;
         colok |= ok ? (1u << r) : 0u;
     }
+    float colmask[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) colmask[r] = ((colok >> r) & 1u) ? 0.f : -INFINITY;
     // bias: row u = jy - iy + K-1 of the table, mirrored columns NB-1 - (jx - ix + K-1) = vm0 + r
     const int ub = jy - oqy + K - 1;
     int vm0 = C::NB - 1 - (jx - (oqx + 4 * g) + K - 1);
@@ -517,16 +520,17 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
             const u32v2 b4 = *lds_ptr<u32v2>(cbase + u * C::BP * 2);
             const f32x4 sacc = mfma_16x16x32<T>(aq, kreg, f32x4{0.f, 0.f, 0.f, 0.f});
             const f32x4 pacc = mfma_16x16x32<T>(ad, vreg, f32x4{0.f, 0.f, 0.f, 0.f});
-            const bool row_in = (rowok >> blk) & 1u;
+            // the window test as an additive mask (0 inside, -inf outside: the weight becomes exactly 0), so that the
+            // block stays free of branches
+            const float rowmask = ((rowok >> blk) & 1u) ? 0.f : -INFINITY;
             float pw[4], ds[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const uint32_t two = r < 2 ? b4.x : b4.y;
                 const float bias = (float)__builtin_bit_cast(f16_t, (uint16_t)((r & 1) ? two >> 16 : two & 0xffffu));
-                float s2 = __builtin_fmaf(scale2, sacc[r], bias);
+                float s2 = __builtin_fmaf(scale2, sacc[r], bias + (colmask[r] + rowmask));
                 s2 = __builtin_fmaf(l4[r], -kLog2e, s2);
-                const float pe = __builtin_amdgcn_exp2f(s2);
-                pw[r] = (row_in && ((colok >> r) & 1u)) ? pe : 0.f;
+                pw[r] = __builtin_amdgcn_exp2f(s2);
                 ds[r] = pw[r] * (pacc[r] - e4[r]);
             }
             const uint32_t p0 = pack2_t<T>(pw[0], pw[1]), p1 = pack2_t<T>(pw[2], pw[3]);
