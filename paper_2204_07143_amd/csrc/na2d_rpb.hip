@@ -15,6 +15,7 @@
 //      index order, then the 16 sub-sums are added in wave order.
 #include "na2d_kernels.hpp"
 #include "na2d_common.hpp"
+#include "na2d_tile.hpp"
 
 namespace na2d {
 
@@ -165,7 +166,7 @@ __global__ __launch_bounds__(256) void rpb_partial_kernel(const T *__restrict__ 
 // index order, sixteen independent loads at a time; the 16 sub-sums are then added in wave order.
 __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const float *__restrict__ partial,
                                                                            float *__restrict__ d_rpb, int B, int heads,
-                                                                           int groups, int cells) {
+                                                                           int groups, int cells, FastDiv by_groups) {
     __shared__ float sub[kRpbFinalWaves][kWave];
     const int cell_blocks = (cells + kWave - 1) / kWave;
     const int h = blockIdx.x / cell_blocks;
@@ -180,7 +181,7 @@ __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int iu = i + u * kRpbFinalWaves;
-                const int b = iu / groups, g = iu - b * groups;
+                const int b = fdiv(iu, by_groups), g = iu - b * groups;   // (sixteen runtime divisions per round cost more than the loads)
                 v[u] = iu < n ? partial[((size_t)(b * heads + h) * groups + g) * cells + cell] : 0.f;
             }
 #pragma unroll
@@ -202,7 +203,7 @@ __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const 
 // order, sixteen loads at a time; the 16 sub-sums are added in wave order.
 __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_av_kernel(const float *__restrict__ partial,
                                                                               float *__restrict__ d_rpb, int heads, int npos,
-                                                                              int splits, int cells) {
+                                                                              int splits, int cells, FastDiv by_npos) {
     __shared__ float sub[kRpbFinalWaves][kWave];
     const int cell_blocks = (cells + kWave - 1) / kWave;
     const int h = blockIdx.x / cell_blocks;
@@ -213,7 +214,7 @@ __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_av_kernel(con
     if (cell < cells) {
         constexpr int U = 16;   // loads in flight per lane; past the end they are skipped (adding 0 changes nothing)
         auto at = [&](int i) {
-            const int sp = i / npos, ps = i - sp * npos;
+            const int sp = fdiv(i, by_npos), ps = i - sp * npos;
             return partial[((size_t)(sp * heads + h) * npos + ps) * cells + cell];
         };
         for (int i = wave; i < n; i += U * kRpbFinalWaves) {
@@ -236,7 +237,7 @@ __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_av_kernel(con
 hipError_t launch_rpb_final_av(const Problem &p, const float *partial, float *d_rpb, AvRpbSplit sp, hipStream_t s) {
     const int nb = 2 * p.K - 1, cells = nb * nb;
     hipLaunchKernelGGL(rpb_final_av_kernel, dim3(p.heads * ((cells + kWave - 1) / kWave)), dim3(kRpbFinalWaves * kWave), 0, s,
-                       partial, d_rpb, p.heads, sp.npos, sp.splits, cells);
+                       partial, d_rpb, p.heads, sp.npos, sp.splits, cells, make_fastdiv(sp.npos));
     return hipGetLastError();
 }
 
@@ -265,7 +266,8 @@ static hipError_t launch_rpb_bwd_t(const Problem &p, const void *ds, float *d_rp
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(rpb_final_kernel, dim3(p.heads * ((C::CELLS + kWave - 1) / kWave)), dim3(kRpbFinalWaves * kWave), 0, s,
-                       static_cast<const float *>(workspace), d_rpb, p.B, p.heads, sp.groups_per_plane, C::CELLS);
+                       static_cast<const float *>(workspace), d_rpb, p.B, p.heads, sp.groups_per_plane, C::CELLS,
+                       make_fastdiv(sp.groups_per_plane));
     return hipGetLastError();
 }
 
