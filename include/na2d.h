@@ -28,7 +28,11 @@
  *    coordinate i on an axis of length L (raster order over ascending key coordinates).
  *    The bias cell of (query i, key j) is rpb[head, jy - iy + k - 1, jx - ix + k - 1].
  *  - Arithmetic: storage in the problem dtype (round-to-nearest-even on store), all dot
- *    products, the softmax and all sums accumulated in fp32.
+ *    products, the softmax and all sums accumulated in fp32.  The bias is added to the fp32
+ *    logit exactly as stored.  The fused 16-bit kernels (na2d_fused_fwd, na2d_fused_bwd) hold
+ *    the table as fp16: an fp16 table is used bit for bit; a bf16 entry converts exactly while
+ *    2^-14 <= |b| <= 65504, a larger one counts as +-65504 and a smaller one is rounded to a
+ *    multiple of 2^-24.
  *  - Supported: odd k in {3, 5, 7, 9, 11, 13} (Appendix A, "Tiled Neighborhood Attention")
  *    with k <= min(H, W); k = H = W is the self-attention limit (Section 3.1).  Head dims
  *    D in {16, 32, 64, 128}.  D = 32 (every NAT variant, Section 3.2) runs the matrix-core
@@ -136,6 +140,7 @@ int na2d_qk_bwd_rpb(const na2d_problem *p, const void *ds, float *d_rpb, void *w
  * `attn` is the softmax output of the forward.  `workspace` must hold
  * na2d_workspace_bytes(p, NA2D_WS_BWD) bytes; on return it starts with the ds tensor
  * ([B, heads, H, W, k*k], problem dtype), followed by the grad-b partials.
+ * No output (d_rpb included) may alias an input or another output.
  */
 int na2d_bwd(const na2d_problem *p, const void *q, const void *k, const void *v, const void *attn,
              const void *dout, float scale, void *dq, void *dk, void *dv, float *d_rpb,
@@ -148,11 +153,19 @@ int na2d_bwd(const na2d_problem *p, const void *q, const void *k, const void *v,
  * na2d_fused_fwd stored for every query.  The attention weights are recomputed per tile as
  * exp(scale <q, k> + bias - lse) and neither they nor dp / ds reach memory.  `rpb` may be NULL
  * (no bias in the forward).  No output may alias an input or another output.
- * For the 16-bit types with k <= 7 this runs two kernels: query patches (dq, the partial bias gradients
- * and delta_n = sum_j P[n, j] dP[n, j]) and key patches (dk, dv); na2d_fused_bwd_is_fused() tells.  d_rpb is summed with integer atomics in 64-bit fixed point (every ds rounded to 2^-20), so it does
- * not depend on the order of the additions; a NaN ds counts as 0 there, one beyond +-2048 as +-2048.  Every other case
- * recomputes the attention weights into the workspace and runs the unfused backward.  Both ways the
- * results are bitwise reproducible.
+ * For the 16-bit types with k <= 7 and D = 32 this runs two kernels: query patches (dq, the partial bias
+ * gradients and delta_n = sum_j P[n, j] dP[n, j]) and key patches (dk, dv); na2d_fused_bwd_is_fused() tells.
+ * There d_rpb is summed per workgroup with integer atomics in 64-bit fixed point, so it does not depend on
+ * the order of the additions.  The fixed point has 32 fraction bits; a ds enters it with a relative error
+ * below 2^-30 of the largest |ds| its query can have, or 2^-32 absolute, whichever is larger, and the sums
+ * are exact while |ds| < 2^20: upstream gradients from about 1e-5 to 1e5 times unit scale keep d_rpb within
+ * 1e-4 of its largest entry; beyond 2^20 the sums wrap.  A NaN ds counts as 0 there.
+ * The weights are recomputed from the fp32 `lse`, whose spacing 2^-24 |lse| enters every weight as a relative
+ * error (and d_rpb as the sum of those errors): logits, bias included, of a few hundred in magnitude at most
+ * keep dq, dk, dv within the 16-bit bound and d_rpb within 1e-4 of its largest entry.
+ * Every other case recomputes the attention weights into the workspace (one logits and one softmax launch)
+ * and runs the unfused backward: it then costs more than na2d_bwd on stored weights, and its only gain is
+ * that the caller need not keep them.  Both ways the results are bitwise reproducible.
  * `workspace` must hold na2d_workspace_bytes(p, NA2D_WS_FUSED_BWD) bytes; no initialisation needed.
  */
 int na2d_fused_bwd(const na2d_problem *p, const void *q, const void *k, const void *v, const void *rpb,

@@ -157,7 +157,7 @@ size_t na2d_workspace_bytes(const na2d_problem *p, int kind) {
         const AvRpbSplit sp = fused_bwd_split(pr);
         const int nbc = 2 * pr.K - 1;
         const size_t partials = ((size_t)sp.npos * pr.heads * sp.splits * nbc * nbc * sizeof(float) + 255) & ~(size_t)255;
-        return ((pr.queries() * sizeof(float) + 255) & ~(size_t)255) + partials;
+        return 2 * ((pr.queries() * sizeof(float) + 255) & ~(size_t)255) + partials;   // delta, lse in the exp2 domain
     }
     return 0;
 }
@@ -207,11 +207,11 @@ int na2d_bwd(const na2d_problem *p, const void *q, const void *k, const void *v,
     if (!workspace || misaligned(workspace) || workspace_bytes < na2d_workspace_bytes(p, NA2D_WS_BWD))
         return NA2D_ERR_WORKSPACE;
     const void *ins[5] = {q, k, v, attn, dout};
-    void *outs[3] = {dq, dk, dv};
+    void *outs[4] = {dq, dk, dv, d_rpb};
     for (void *o : outs)
         for (const void *i : ins)
-            if (o == i) return NA2D_ERR_ALIAS;
-    if (dq == dk || dq == dv || dk == dv) return NA2D_ERR_ALIAS;
+            if (o && o == i) return NA2D_ERR_ALIAS;
+    if (dq == dk || dq == dv || dk == dv || d_rpb == dq || d_rpb == dk || d_rpb == dv) return NA2D_ERR_ALIAS;
     return run_bwd(to_problem(p), q, k, v, attn, dout, scale, dq, dk, dv, d_rpb, static_cast<char *>(workspace),
                    static_cast<hipStream_t>(stream));
 }
@@ -221,8 +221,8 @@ int na2d_fused_bwd_is_fused(const na2d_problem *p) {
     return fused_bwd_supported(to_problem(p)) ? 1 : 0;
 }
 
-// Workspace of the fused backward.  Two-kernel path: delta [B, heads, H, W] fp32, then one partial bias
-// gradient per workgroup of the first kernel.  Otherwise: the recomputed attention weights, then the
+// Workspace of the fused backward.  Two-kernel path: delta and log2(e) * lse, [B, heads, H, W] fp32 each, then one
+// partial bias gradient per workgroup of the first kernel.  Otherwise: the recomputed attention weights, then the
 // workspace of the unfused backward.
 static size_t fused_bwd_delta_bytes(const Problem &pr) { return (pr.queries() * sizeof(float) + 255) & ~(size_t)255; }
 static size_t fused_bwd_attn_bytes(const Problem &pr) { return (pr.queries() * pr.K * pr.K * pr.elem_bytes() + 255) & ~(size_t)255; }
@@ -240,16 +240,17 @@ int na2d_fused_bwd(const na2d_problem *p, const void *q, const void *k, const vo
     for (void *o : outs)
         for (const void *i : ins)
             if (o && o == i) return NA2D_ERR_ALIAS;
-    if (dq == dk || dq == dv || dk == dv) return NA2D_ERR_ALIAS;
+    if (dq == dk || dq == dv || dk == dv || d_rpb == dq || d_rpb == dk || d_rpb == dv) return NA2D_ERR_ALIAS;
     const Problem pr = to_problem(p);
     hipStream_t s = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
     if (fused_bwd_supported(pr)) {
         float *delta = reinterpret_cast<float *>(ws);
-        float *partial = d_rpb ? reinterpret_cast<float *>(ws + fused_bwd_delta_bytes(pr)) : nullptr;
-        if (launch_fbwd_q(pr, q, k, v, rpb, scale, lse, dout, dq, delta, partial, s) != hipSuccess)
+        float *lse2 = reinterpret_cast<float *>(ws + fused_bwd_delta_bytes(pr));
+        float *partial = d_rpb ? reinterpret_cast<float *>(ws + 2 * fused_bwd_delta_bytes(pr)) : nullptr;
+        if (launch_fbwd_q(pr, q, k, v, rpb, scale, lse, dout, dq, delta, lse2, partial, s) != hipSuccess)
             return from_hip(hipErrorLaunchFailure);
-        if (launch_fbwd_kv(pr, q, k, v, rpb, scale, lse, delta, dout, dk, dv, s) != hipSuccess)
+        if (launch_fbwd_kv(pr, q, k, v, rpb, scale, lse2, delta, dout, dk, dv, s) != hipSuccess)
             return from_hip(hipErrorLaunchFailure);
         if (d_rpb && launch_rpb_final_av(pr, partial, d_rpb, fused_bwd_split(pr), s) != hipSuccess)
             return from_hip(hipErrorLaunchFailure);

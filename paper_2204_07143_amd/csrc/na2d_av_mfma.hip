@@ -332,7 +332,7 @@ static hipError_t launch_av_mfma_small_t(const Problem &p, const void *w, const 
 }
 
 // grad-q together with partial bias gradients (one per workgroup, av_rpb_partials() of them)
-bool av_rpb_supported(const Problem &p) { return p.D == kHeadDim && p.dtype != NA2D_F32 && p.K <= 7 && !force_valu(); }
+bool av_rpb_supported(const Problem &p) { return p.D == kHeadDim && p.dtype != NA2D_F32 && p.K <= 7; }
 AvRpbSplit av_rpb_split(const Problem &p) {
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + 8 - 1) / 8;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
@@ -358,7 +358,7 @@ hipError_t launch_av_rpb(const Problem &p, const void *w, const void *y, float s
 
 bool av_mfma_supported(const Problem &p) {
     // any multiple of 32 channels: one launch per 32-channel slice
-    return p.dtype != NA2D_F32 && !force_valu() && p.D % kHeadDim == 0;
+    return p.dtype != NA2D_F32 && p.D % kHeadDim == 0;
 }
 
 hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s) {

@@ -252,7 +252,7 @@ static hipError_t launch_bwd_fused_t(const Problem &p, const void *attn, const v
     return hipGetLastError();
 }
 
-bool bwd_fused_supported(const Problem &p) { return p.D == kHeadDim && p.dtype != NA2D_F32 && p.K <= 7 && !force_valu(); }
+bool bwd_fused_supported(const Problem &p) { return p.D == kHeadDim && p.dtype != NA2D_F32 && p.K <= 7; }
 
 hipError_t launch_bwd_fused(const Problem &p, const void *attn, const void *dout, const void *v, void *ds, hipStream_t s) {
 #define NA2D_BWDF_K(TT)                                                                                   \

@@ -38,15 +38,17 @@ template <typename T> __device__ __forceinline__ uint32_t pack2_t(float a, float
 //   dq^T += K_blk^T dS^T                     the half-depth MFMA (keys through the transposing LDS read).
 // Recomputing the two products is cheaper than keeping P and dP of the whole halo in registers.
 // Every dS is also added to its cell of a (2K-1)^2 table in LDS (Eq. 2's B differentiated: the bias cell of a
-// (query, position) pair depends on their offset only).  The tables are 64-bit fixed point (20 fraction
-// bits: a dS is rounded to a 32-bit integer and sign-extended, two conversions and a shift) and the adds are
-// integer atomics: on this chip an LDS integer add costs a few cycles per wave
+// (query, position) pair depends on their offset only).  The tables are 64-bit fixed point with 32 fraction
+// bits and the adds are integer atomics: on this chip an LDS integer add costs a few cycles per wave
 // instruction where the floating-point add costs about 200, and integer addition does not depend on the
-// order of the operands, so the bias gradient is bitwise reproducible although waves share tables.  A
-// workgroup's tables, added up and converted to fp32 at the end, are one partial bias gradient.
-// (A single dS is rounded to 2^-20, about 1e-6, and saturates at +-2048; the 64-bit sums cannot overflow.  The
-// rounding errors of the up to ~1e5 terms of a cell add up to about 1e-4 absolute on sums of order 10 to 1000,
-// two orders below the fp32 summation noise the bias gradient is allowed.  A NaN dS counts as 0.)
+// order of the operands, so the bias gradient is bitwise reproducible although waves share tables.
+// A dS is converted in two steps so that its precision follows its size: a lane bounds the dS of its query
+// in a plane by B = max |dP| + |delta| (from the first sweep), takes sh = max(0, exponent(B) + 32 - 30), turns
+// dS 2^(32 - sh) into a 32-bit integer (below 2^30 in magnitude, truncated: an error below 2^-30 B) and shifts
+// it left by sh as a 64-bit integer.  Small gradients therefore keep an absolute resolution of 2^-32 (2.3e-10),
+// large ones a relative one of 2^-30, and a workgroup's 64-bit sums (about 2^11 terms per cell) stay exact while
+// |dS| < 2^20; beyond that they wrap.  A workgroup's tables, added up and converted to fp32 at the end, are
+// one partial bias gradient.  (A NaN dS counts as 0.)
 template <typename T, int K>
 struct FbwdQCfg {
     using P = Patch<K>;
@@ -61,12 +63,13 @@ struct FbwdQCfg {
     static constexpr int kThreads = kWave * WAVES;
     static constexpr int kHaloBytes = Halo::kBytes;
     static constexpr int kStageBytes = 2 * kHaloBytes;   // keys, then values
-    // Bias-gradient tables behind the buffers, 64-bit fixed point (see below): as many as fit beside two
+    // Bias-gradient tables behind the buffers, 64-bit fixed point (see above): as many as fit beside two
     // workgroups' buffers in a compute unit's 160 KB, at most one per wave
     static constexpr int kTblBytes = CELLS * 8;
     static constexpr int kTblFit = (80 * 1024 - 2 * kStageBytes) / kTblBytes;
     static constexpr int NTBL = kTblFit >= WAVES ? WAVES : (kTblFit >= 4 ? 4 : (kTblFit >= 2 ? 2 : 1));
     static_assert(kTblFit >= 1, "no room for a bias-gradient table");
+    static constexpr int kFracBits = 32;   // fraction bits of the tables
     static constexpr int kLdsBytes = 2 * kStageBytes + NTBL * kTblBytes;
 };
 
@@ -75,7 +78,8 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
                                                         const T *__restrict__ v, const T *__restrict__ rpb, float scale,
                                                         const float *__restrict__ lse, const T *__restrict__ dout,
                                                         T *__restrict__ dq,
-                                                        float *__restrict__ delta_out, float *__restrict__ rpb_partial,
+                                                        float *__restrict__ delta_out, float *__restrict__ lse2_out,
+                                                        float *__restrict__ rpb_partial,
                                                         int H, int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd) {
     using C = FbwdQCfg<T, K>;
     using P = Patch<K>;
@@ -152,9 +156,9 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
         const int hy = P::row_of(h), hx = h - hy * P::PW;
         return kbase + (hy * C::HALO_W + hx) * Traits<T>::kKeyBytes + (lv & 3) * 16;
     };
-    // log2(e) * bias of (this lane's query, halo position), -inf outside the query's window, as packed fp16
-    // pairs; cell[] is the position's cell in the bias table (-1 outside the window).  Built per group of
-    // four consecutive halo positions: those of them inside the window are in one halo row (a halo row
+    // bias of (this lane's query, halo position), as stored (see bias_to_f16), -inf outside the query's window,
+    // as packed fp16 pairs; cell[] is the position's cell in the bias table (-1 outside the window).  Built per
+    // group of four consecutive halo positions: those of them inside the window are in one halo row (a halo row
     // holds K + 3 positions, the window K), normally the row of the first position; when that one is already
     // right of the window the group runs on into the next halo row and only that part can be inside.
     f16x2 biasm[P::NEL / 2];
@@ -182,7 +186,7 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
 #pragma unroll
         for (int G0 = 0; G0 < P::NBLK; G0 += 4) {   // sixteen loads of the bias table in flight at a time
             int cell[16];
-            float bias[16];
+            f16_t bias[16];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 int c4[4] = {-1, -1, -1, -1};
@@ -199,14 +203,14 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
                 }
             }
 #pragma unroll
-            for (int e = 0; e < 16; ++e) bias[e] = 0.f;
+            for (int e = 0; e < 16; ++e) bias[e] = (f16_t)0.f;
             if (tbl != nullptr) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) bias[e] = kLog2e * to_f32(tbl[cell[e] < 0 ? 0 : cell[e]]);
+                for (int e = 0; e < 16; ++e) bias[e] = bias_to_f16(tbl[cell[e] < 0 ? 0 : cell[e]]);
             }
 #pragma unroll
             for (int e = 0; e < 16; ++e)
-                if (4 * G0 + e < P::NEL) biasm[(4 * G0 + e) >> 1][e & 1] = (f16_t)(cell[e] >= 0 ? bias[e] : -INFINITY);
+                if (4 * G0 + e < P::NEL) biasm[(4 * G0 + e) >> 1][e & 1] = cell[e] >= 0 ? bias[e] : (f16_t)-INFINITY;
         }
     }
     static_assert(C::CELLS < 255, "cells are kept as bytes");
@@ -216,7 +220,6 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
         for (int i = tid; i < C::NTBL * C::CELLS; i += C::kThreads) *lds_ptr<unsigned long long>(tbl0 + i * 8) = 0ull;
     }
 
-    const float scale2 = scale * kLog2e;
     auto compute = [&](auto par_c, const u32x4 &qreg, const u32x4 &dreg, float lse2, int b) {
         constexpr int PAR = decltype(par_c)::value;
         if (!active) return;
@@ -234,20 +237,30 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
             pacc = mfma_16x16x32<T>(av, dreg, f32x4{0.f, 0.f, 0.f, 0.f});
         };
         auto weight = [&](int e, float sv) {   // P of result e, 0 outside the window (bias -inf)
-            return __builtin_amdgcn_exp2f(__builtin_fmaf(scale2, sv, (float)biasm[e >> 1][e & 1]) - lse2);
+            return __builtin_amdgcn_exp2f(__builtin_fmaf(__builtin_fmaf(scale, sv, (float)biasm[e >> 1][e & 1]), kLog2e, -lse2));
         };
         // sweep 1: delta
-        float delta = 0.f;
+        float delta = 0.f, dpmax = 0.f;
 #pragma unroll
         for (int bk = 0; bk < P::NBLK; ++bk) {
             f32x4 sacc, pacc;
             block(bk, sacc, pacc);
 #pragma unroll
             for (int r = 0; r < 4; ++r) delta = __builtin_fmaf(weight(4 * bk + r, sacc[r]), pacc[r], delta);
+            if constexpr (RPB) dpmax = fmaxf(fmaxf(dpmax, fmaxf(fabsf(pacc[0]), fabsf(pacc[1]))), fmaxf(fabsf(pacc[2]), fabsf(pacc[3])));
             __builtin_amdgcn_sched_barrier(0);   // keeps the blocks from being evaluated all at once
         }
         delta += __shfl_xor(delta, 16);
         delta += __shfl_xor(delta, 32);
+        // fixed-point conversion of this lane's dS in this plane: |dS| <= P |dP - delta| <= dpmax + |delta|
+        float fx_scale = 0.f;
+        int fx_shift = 0;
+        if constexpr (RPB) {
+            const int ex = __builtin_amdgcn_frexp_expf(dpmax + fabsf(delta));   // bound < 2^ex
+            fx_shift = ex + C::kFracBits - 30;
+            fx_shift = fx_shift < 0 ? 0 : (fx_shift > 32 ? 32 : fx_shift);
+            fx_scale = __builtin_ldexpf(1.f, C::kFracBits - fx_shift);
+        }
         // sweep 2: dS, dq (one block at a time: the half-depth MFMA takes the four positions a lane holds)
         f32x4 o[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
@@ -260,11 +273,9 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
                 const int e = 4 * bk + r;
                 dsv[r] = weight(e, sacc[r]) * (pacc[r] - delta);   // exactly 0 outside the window
                 if constexpr (RPB) {
-                    // 2^20 dS rounded to the nearest 32-bit integer (saturating), sign-extended to 64 bits
-                    const int fi = (int)__builtin_rintf(dsv[r] * 1048576.f);
-                    const unsigned long long fx = (unsigned long long)(long long)fi;
-                    __hip_atomic_fetch_add(lds_ptr<unsigned long long>(mytbl + ((cellp[bk] >> (8 * r)) & 0xffu) * 8), fx,
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    const long long fx = (long long)(int)(dsv[r] * fx_scale) << fx_shift;   // truncated, saturating; NaN -> 0
+                    __hip_atomic_fetch_add(lds_ptr<unsigned long long>(mytbl + ((cellp[bk] >> (8 * r)) & 0xffu) * 8),
+                                           (unsigned long long)fx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
             const uint32_t b0 = pack2_t<T>(dsv[0], dsv[1]), b1 = pack2_t<T>(dsv[2], dsv[3]);
@@ -289,7 +300,10 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
             *reinterpret_cast<u32x4 *>(dst) =
                 u32x4{pack2_t<T>(o[0][0] * scale, o[0][1] * scale), pack2_t<T>(o[0][2] * scale, o[0][3] * scale),
                       pack2_t<T>(o[1][0] * scale, o[1][1] * scale), pack2_t<T>(o[1][2] * scale, o[1][3] * scale)};
-            if (g == 0) delta_out[plane * H * W + qlin] = delta;
+            if (g == 0) {   // for the key-patch kernel: delta, and the log-sum-exp in the exp2 domain
+                delta_out[plane * H * W + qlin] = delta;
+                lse2_out[plane * H * W + qlin] = lse2;
+            }
         }
     };
 
@@ -316,14 +330,14 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
             long long sum = 0;
 #pragma unroll
             for (int t = 0; t < C::NTBL; ++t) sum += (long long)*lds_ptr<unsigned long long>(tbl0 + t * C::kTblBytes + cell * 8);
-            rpb_partial[(size_t)wg * C::CELLS + cell] = (float)((double)sum * (1.0 / 1048576.0));   // 2^-20
+            rpb_partial[(size_t)wg * C::CELLS + cell] = (float)((double)sum * (1.0 / 4294967296.0));   // 2^-32
         }
     }
 }
 
 template <typename T, int K>
 static hipError_t launch_fbwd_q_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
-                                  float scale, const float *lse, const void *dout, void *dq, float *delta,
+                                  float scale, const float *lse, const void *dout, void *dq, float *delta, float *lse2,
                                   float *rpb_partial, hipStream_t s) {
     using C = FbwdQCfg<T, K>;
     static_assert(C::kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
@@ -335,7 +349,7 @@ static hipError_t launch_fbwd_q_t(const Problem &p, const void *q, const void *k
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed[with_rpb]); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
-                       static_cast<const T *>(rpb), scale, lse, static_cast<const T *>(dout), static_cast<T *>(dq), delta,
+                       static_cast<const T *>(rpb), scale, lse, static_cast<const T *>(dout), static_cast<T *>(dq), delta, lse2,
                        rpb_partial, p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd);
     return hipGetLastError();
 }
@@ -348,7 +362,7 @@ static hipError_t launch_fbwd_q_t(const Problem &p, const void *q, const void *k
 // natural layout, their log-sum-exp and delta as fp32 rows.  Per row of the rectangle that sees the
 // patch (a block of 16 consecutive query positions, the first one the leftmost query that sees the patch):
 //   S = Q_blk K^T, dP = dout_blk V^T         (rows of q / dout as 16-byte A operands, the lane's key as B operand)
-//   P = exp(S' - lse), dS = P (dP - delta)   per result; a lane holds 4 consecutive positions of its key
+//   P = exp2(log2e S' - lse2), dS = P (dP - delta)   per result; a lane holds 4 consecutive positions of its key
 //   dv^T += dout_blk^T P, dk^T += Q_blk^T dS the half-depth MFMA (q / dout through the transposing LDS read)
 // The bias of (query, key) depends on their offset only; per block a lane needs four neighbouring cells
 // of one table row.  The table is kept in LDS mirrored left to right and in four copies shifted by one
@@ -390,8 +404,9 @@ struct FbwdKvCfg {
 template <typename T, int K, bool COMPACT>
 __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) void fbwd_kv_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, const T *__restrict__ rpb, float scale,
-    const float *__restrict__ lse, const float *__restrict__ delta, const T *__restrict__ dout, T *__restrict__ dk,
+    const float *__restrict__ lse2, const float *__restrict__ delta, const T *__restrict__ dout, T *__restrict__ dk,
     T *__restrict__ dv, int H, int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd) {
+    // lse2: the log-sum-exp of every query times log2(e), as the query-patch kernel left it beside delta
     using C = FbwdKvCfg<T, K, COMPACT>;
     using XHalo = typename C::XHalo;
     constexpr float kLog2e = 1.4426950408889634f;
@@ -414,14 +429,14 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
 
     // everything the loads do not write must hold finite numbers (it only ever meets P = 0)
     for (int i = tid * 16; i < C::kLdsBytes - C::kBiasBytes; i += C::kThreads * 16) *lds_ptr<u32x4>(lds0 + i) = u32x4{0u, 0u, 0u, 0u};
-    // bias copies: copy s holds log2(e) * B[u][v] at element u * BP + (NB-1 - v) + 3 + s, zeros elsewhere
+    // bias copies: copy s holds B[u][v] (see bias_to_f16) at element u * BP + (NB-1 - v) + 3 + s, zeros elsewhere
     for (int i = tid; i < 4 * C::NB * C::BP; i += C::kThreads) {
         const int s = i / (C::NB * C::BP), rest = i - s * (C::NB * C::BP);
         const int u = rest / C::BP, col = rest - u * C::BP;
         const int vv = C::NB - 1 - (col - 3 - s);
-        float val = 0.f;
-        if (rpb != nullptr && (unsigned)vv < (unsigned)C::NB) val = kLog2e * to_f32(rpb[((size_t)head * C::NB + u) * C::NB + vv]);
-        *lds_ptr<f16_t>(bias0 + i * 2) = (f16_t)val;
+        f16_t val = (f16_t)0.f;
+        if (rpb != nullptr && (unsigned)vv < (unsigned)C::NB) val = bias_to_f16(rpb[((size_t)head * C::NB + u) * C::NB + vv]);
+        *lds_ptr<f16_t>(bias0 + i * 2) = val;
     }
 
     const int ty0 = work.ty * C::TY, tx0 = work.tx * kTileX;
@@ -482,7 +497,6 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
     const int cbase = bias0 + shift * C::kBiasCopy + (vm0 + 3 + shift) * 2;   // 8-byte aligned
 
     const size_t plane_px = (size_t)H * W;
-    const float scale2 = scale * kLog2e;
     __syncthreads();
 
     for (int b = b_begin; b < b_end; ++b) {
@@ -491,7 +505,7 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
         XHalo::issue_at(reinterpret_cast<const char *>(q) + plane * plane_px * KB, xoff, q0, wave);
         XHalo::issue_at(reinterpret_cast<const char *>(dout) + plane * plane_px * KB, xoff, d0, wave);
         if (wave < C::kSItems) {
-            global_to_lds_4(reinterpret_cast<const char *>(lse) + plane * plane_px * 4, (unsigned)soff, l0 + wave * kWave * 4);
+            global_to_lds_4(reinterpret_cast<const char *>(lse2) + plane * plane_px * 4, (unsigned)soff, l0 + wave * kWave * 4);
             global_to_lds_4(reinterpret_cast<const char *>(delta) + plane * plane_px * 4, (unsigned)soff, e0 + wave * kWave * 4);
         }
         // the lane's key and value: bytes [16g, 16g+16) (B operands)
@@ -528,9 +542,8 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
             for (int r = 0; r < 4; ++r) {
                 const uint32_t two = r < 2 ? b4.x : b4.y;
                 const float bias = (float)__builtin_bit_cast(f16_t, (uint16_t)((r & 1) ? two >> 16 : two & 0xffffu));
-                float s2 = __builtin_fmaf(scale2, sacc[r], bias + (colmask[r] + rowmask));
-                s2 = __builtin_fmaf(l4[r], -kLog2e, s2);
-                pw[r] = __builtin_amdgcn_exp2f(s2);
+                const float lg = __builtin_fmaf(scale, sacc[r], bias + (colmask[r] + rowmask));   // the logit, -inf outside the window
+                pw[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(lg, kLog2e, -l4[r]));
                 ds[r] = pw[r] * (pacc[r] - e4[r]);
             }
             const uint32_t p0 = pack2_t<T>(pw[0], pw[1]), p1 = pack2_t<T>(pw[2], pw[3]);
@@ -623,7 +636,7 @@ hipError_t launch_fbwd_kv(const Problem &p, const void *q, const void *k, const 
 // close to both borders) does not fit, and such maps take the unfused steps instead.
 bool fused_bwd_supported(const Problem &p) {
     const int R = p.K / 2;
-    return p.D == kHeadDim && p.dtype != NA2D_F32 && p.K <= 7 && !force_valu() && kv_rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
+    return p.D == kHeadDim && p.dtype != NA2D_F32 && p.K <= 7 && kv_rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
 }
 
 AvRpbSplit fused_bwd_split(const Problem &p) {
@@ -633,12 +646,13 @@ AvRpbSplit fused_bwd_split(const Problem &p) {
 }
 
 hipError_t launch_fbwd_q(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
-                         const float *lse, const void *dout, void *dq, float *delta, float *rpb_partial, hipStream_t s) {
+                         const float *lse, const void *dout, void *dq, float *delta, float *lse2, float *rpb_partial,
+                         hipStream_t s) {
 #define NA2D_FBQ_K(TT)                                                                                             \
     switch (p.K) {                                                                                                 \
-        case 3: return launch_fbwd_q_t<TT, 3>(p, q, k, v, rpb, scale, lse, dout, dq, delta, rpb_partial, s);       \
-        case 5: return launch_fbwd_q_t<TT, 5>(p, q, k, v, rpb, scale, lse, dout, dq, delta, rpb_partial, s);       \
-        case 7: return launch_fbwd_q_t<TT, 7>(p, q, k, v, rpb, scale, lse, dout, dq, delta, rpb_partial, s);       \
+        case 3: return launch_fbwd_q_t<TT, 3>(p, q, k, v, rpb, scale, lse, dout, dq, delta, lse2, rpb_partial, s);       \
+        case 5: return launch_fbwd_q_t<TT, 5>(p, q, k, v, rpb, scale, lse, dout, dq, delta, lse2, rpb_partial, s);       \
+        case 7: return launch_fbwd_q_t<TT, 7>(p, q, k, v, rpb, scale, lse, dout, dq, delta, lse2, rpb_partial, s);       \
         default: return hipErrorInvalidValue;                                                                      \
     }
     if (p.dtype == NA2D_F16) { NA2D_FBQ_K(f16_t) }

@@ -6,8 +6,8 @@
 //   1. S^T = K_halo * Q^T    one 16x16x32 MFMA per block of 16 halo positions (keys in their natural
 //                            layout in LDS, queries straight from global memory);
 //   2. logits               one fma per result against a per-lane table that holds the bias of
-//                            (query, position) and -inf where the position is outside the query's
-//                            window (scale and bias are pre-multiplied by log2 e);
+//                            (query, position), as stored, and -inf where the position is outside
+//                            the query's window;
 //   3. softmax              row max and row sum in registers plus two cross-lane steps each
 //                            (a query's positions are spread over 4 lanes), exp2 in fp32;
 //   4. O^T = V_halo^T * P    the un-normalised weights, converted to the storage type, are already
@@ -134,8 +134,8 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
         hx = h - hy * P::PW;
         vaddr[b] = lds0 + NS * C::kHaloBytes + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + (j & 3) * 16;
     }
-    // log2(e) * bias of (this lane's query, halo position), -inf outside the query's window; packed
-    // fp16 pairs (half the registers; the fma below reads them as mixed-precision operands)
+    // bias of (this lane's query, halo position), -inf outside the query's window; packed fp16 pairs
+    // (half the registers; the fma below reads them as mixed-precision operands; see bias_to_f16)
     f16x2 biasm[P::NEL / 2];
     {
         const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
@@ -157,23 +157,22 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
             for (int i = 0; i < 4; ++i) bidx[4 * G + i] = (unsigned)(c0 + i) < (unsigned)K ? cell0 + i : -1;
         }
         // all loads of the bias table in flight at once (one uniform branch on the table's presence)
-        float bias[P::NEL];
+        f16_t bias[P::NEL];
 #pragma unroll
-        for (int e = 0; e < P::NEL; ++e) bias[e] = 0.f;
+        for (int e = 0; e < P::NEL; ++e) bias[e] = (f16_t)0.f;
         if (rpb != nullptr) {
             const T *tbl = rpb + (size_t)head * C::NB * C::NB;
 #pragma unroll
-            for (int e = 0; e < P::NEL; ++e) bias[e] = kLog2e * to_f32(tbl[bidx[e] < 0 ? 0 : bidx[e]]);
+            for (int e = 0; e < P::NEL; ++e) bias[e] = bias_to_f16(tbl[bidx[e] < 0 ? 0 : bidx[e]]);
         }
 #pragma unroll
-        for (int e = 0; e < P::NEL; ++e) biasm[e >> 1][e & 1] = (f16_t)(bidx[e] >= 0 ? bias[e] : -INFINITY);
+        for (int e = 0; e < P::NEL; ++e) biasm[e >> 1][e & 1] = bidx[e] >= 0 ? bias[e] : (f16_t)-INFINITY;
     }
 
-    const float scale2 = scale * kLog2e;
     auto compute = [&](auto par_c, const u32x4 (&qreg)[NS], int b) {
         constexpr int PAR = decltype(par_c)::value;
         if (!active) return;
-        // 1-2. logits in the exp2 domain
+        // 1-2. logits: fp32 dot product times scale, plus the bias as stored
         float s[4 * C::NBLK2];
 #pragma unroll
         for (int bk = 0; bk < P::NBLK; ++bk) {
@@ -185,7 +184,7 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
             }
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                s[4 * bk + r] = __builtin_fmaf(scale2, acc[r], (float)biasm[(4 * bk + r) >> 1][(4 * bk + r) & 1]);
+                s[4 * bk + r] = __builtin_fmaf(scale, acc[r], (float)biasm[(4 * bk + r) >> 1][(4 * bk + r) & 1]);
         }
         // 3. softmax over the query's window (spread over the 4 lanes j, j+16, j+32, j+48)
         float m = s[0];
@@ -194,10 +193,12 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
         m = fmaxf(m, __shfl_xor(m, 16));
         m = fmaxf(m, __shfl_xor(m, 32));
         m = q_ok ? m : 0.f;   // lanes without a query: keep the arithmetic finite
+        // exp(s - m) as exp2(log2(e) s - m2): the subtraction of the maximum and the change of base are one fma
+        const float m2 = m * kLog2e;
         float l = 0.f;
 #pragma unroll
         for (int e = 0; e < P::NEL; ++e) {
-            s[e] = __builtin_amdgcn_exp2f(s[e] - m);
+            s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], kLog2e, -m2));
             l += s[e];
         }
 #pragma unroll
@@ -245,7 +246,7 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
                 *reinterpret_cast<u32x4 *>(dst + sl * Traits<T>::kKeyBytes) =
                     u32x4{pack2<T>(o[sl][0][0] * inv, o[sl][0][1] * inv), pack2<T>(o[sl][0][2] * inv, o[sl][0][3] * inv),
                           pack2<T>(o[sl][1][0] * inv, o[sl][1][1] * inv), pack2<T>(o[sl][1][2] * inv, o[sl][1][3] * inv)};
-            if (lse != nullptr && g == 0) lse[plane * H * W + qlin] = (m + __builtin_amdgcn_logf(l)) * kLn2;
+            if (lse != nullptr && g == 0) lse[plane * H * W + qlin] = (m2 + __builtin_amdgcn_logf(l)) * kLn2;
         }
     };
 
@@ -295,7 +296,7 @@ static hipError_t launch_fused_mfma_small_t(const Problem &p, const void *q, con
 }
 
 bool fused_mfma_supported(const Problem &p) {
-    if (p.dtype == NA2D_F32 || force_valu()) return false;
+    if (p.dtype == NA2D_F32) return false;
     return p.D == kHeadDim || (p.D == 2 * kHeadDim && p.K <= 7);   // two slices only in the small-window kernel
 }
 

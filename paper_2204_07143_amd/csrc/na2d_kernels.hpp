@@ -26,8 +26,6 @@ hipError_t launch_qk_mfma(const Problem &p, const void *x, const void *y, const 
                           hipStream_t s);
 // D = 32, and for k <= 7 also D = 64 (two 32-channel slices accumulated in the matrix cores)
 bool qk_mfma_supported(const Problem &p);
-// Variant override for A/B timing: NA2D_VARIANT=valu forces the plain-ALU kernels.
-bool force_valu();
 // grad-a fused with the softmax backward (f16 / bf16, K <= 7): ds from attn, dout and v
 bool bwd_fused_supported(const Problem &p);
 hipError_t launch_bwd_fused(const Problem &p, const void *attn, const void *dout, const void *v, void *ds, hipStream_t s);
@@ -62,10 +60,12 @@ hipError_t launch_rpb_final_av(const Problem &p, const float *partial, float *d_
 // fused backward (two kernels): query patches -> dq, delta, partial bias gradients; key patches -> dk, dv
 bool fused_bwd_supported(const Problem &p);
 AvRpbSplit fused_bwd_split(const Problem &p);
+// (the first also leaves log2(e) * lse beside delta, which is what the second reads as `lse2`)
 hipError_t launch_fbwd_q(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
-                         const float *lse, const void *dout, void *dq, float *delta, float *rpb_partial, hipStream_t s);
+                         const float *lse, const void *dout, void *dq, float *delta, float *lse2, float *rpb_partial,
+                         hipStream_t s);
 hipError_t launch_fbwd_kv(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
-                          const float *lse, const float *delta, const void *dout, void *dk, void *dv, hipStream_t s);
+                          const float *lse2, const float *delta, const void *dout, void *dk, void *dv, hipStream_t s);
 hipError_t launch_fused_fwd(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
                             void *out, float *lse, hipStream_t s);
 // D = 32, and for k <= 7 also D = 64 (two 32-channel slices)

@@ -46,6 +46,16 @@ template <> __device__ __forceinline__ f32x4 mfma_16x16x16<bf16_t>(uint32_t a0, 
     return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(i16x4_t, a), __builtin_bit_cast(i16x4_t, b), c, 0, 0, 0);
 }
 
+// The fused kernels keep the bias B(i, j) of a (query, position) pair as fp16, two per register, beside the
+// -inf that masks positions outside the window, and add it unscaled to the fp32 logit.  An fp16 table entry is
+// kept bit for bit.  A bf16 entry (8 significant bits) converts exactly while it lies inside fp16's range:
+// beyond +-65504 it counts as +-65504, and below 2^-14 in magnitude it is rounded to a multiple of 2^-24.
+__device__ __forceinline__ f16_t bias_to_f16(f16_t x) { return x; }
+__device__ __forceinline__ f16_t bias_to_f16(bf16_t x) {
+    const float f = (float)x;
+    return (f16_t)(f > 65504.f ? 65504.f : (f < -65504.f ? -65504.f : f));   // a NaN stays a NaN
+}
+
 // Geometry of a 4 x 4 query patch.  Patch-halo coordinates are "virtual": position (hy, hx)
 // is key (oy + hy, ox + hx) whether or not that lies inside the map, with (oy, ox) =
 // halo_origin() of the patch.  The windows of 4 consecutive queries span at most K + 3
@@ -86,17 +96,19 @@ __host__ __device__ __forceinline__ int halo_origin(int q0, int n, int L, int K)
 // loads stage n + 1 while stage n is read.  The kernels order these loads against their LDS reads
 // themselves: wait_global_loads() and a workgroup barrier before a stage is read, a barrier after
 // its last read before it is loaded again.  M0 holds the LDS base (one wait state before its use);
-// it is taken through readfirstlane so that it sits in a scalar register whatever the caller passes.
+// it is taken through readfirstlane so that it sits in a scalar register whatever the caller passes,
+// and the statements name M0 as clobbered: the compiler keeps values of its own there (the index of
+// relative register moves, for one) and must not assume they survive.
 __device__ __forceinline__ void global_to_lds_16(const void *g, int lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory", "m0");
 }
 // the same from a wave-uniform base pointer plus a 32-bit byte offset per lane
 __device__ __forceinline__ void global_to_lds_16(const char *base, unsigned off, int lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory", "m0");
 }
 // four bytes per lane: lane l writes [lds_base + 4 l, lds_base + 4 l + 4)
 __device__ __forceinline__ void global_to_lds_4(const char *base, unsigned off, int lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds_base)) : "memory", "m0");
 }
 // waits until every load of this wave, the direct-to-LDS ones included, has landed
 __device__ __forceinline__ void wait_global_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }

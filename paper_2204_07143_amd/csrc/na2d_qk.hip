@@ -108,14 +108,6 @@ bool head_dim_supported(int dtype, int K, int D) {
     return probe() == hipSuccess;
 }
 
-bool force_valu() {
-    static const bool v = [] {
-        const char *e = getenv("NA2D_VARIANT");
-        return e != nullptr && strcmp(e, "valu") == 0;
-    }();
-    return v;
-}
-
 hipError_t launch_qk(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
                      hipStream_t s) {
     if (qk_mfma_supported(p)) return launch_qk_mfma(p, x, y, rpb, scale, logits, s);

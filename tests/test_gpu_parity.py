@@ -11,7 +11,7 @@ import torch
 from paper_2204_07143_amd import binding as na
 from paper_2204_07143_amd import synth
 
-from gpu_util import Stages, assert_close, assert_close_rpb, plane, to_np
+from gpu_util import Stages, assert_close, assert_close_rpb, block, slices_of, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -19,56 +19,88 @@ KS = (3, 5, 7, 9, 11, 13)
 
 
 def check_planes(oracle, st: Stages, host: dict, planes, backward: bool, e2e_unfused: bool = True):
-    """Stage-wise and end-to-end parity on the given (b, h) planes."""
+    """Stage-wise and end-to-end parity on the given (b, h) planes; planes=None checks every plane."""
     p, k, scale = st.p, st.k, st.scale
-    flat = {}
-    for (b, h) in planes:
-        tag = f"plane({b},{h})"
-        q, key, v = (plane(host[n], b, h).astype(np.float64) for n in ("q", "k", "v"))
-        rpb = host["rpb"][h:h + 1].astype(np.float64) if st.rpb is not None else None
+    flat = {"logits": 0, "attn": 0, "out": 0, "fused": 0}
+    for sl in slices_of(p, planes):
+        tag = f"block{sl}"
+        q, key, v = (block(host[n], sl).astype(np.float64) for n in ("q", "k", "v"))
+        rpb = host["rpb"][sl[2]:sl[3]].astype(np.float64) if st.rpb is not None else None
         # forward, stage by stage
-        flat["logits"] = assert_close(f"{tag} logits", plane(st.logits, b, h), oracle.qk_rpb(q, key, rpb, scale, k), p.dtype)
-        g_logits = to_np(plane(st.logits, b, h))
-        flat["attn"] = assert_close(f"{tag} softmax", plane(st.attn, b, h), oracle.softmax(g_logits), p.dtype)
-        g_attn = to_np(plane(st.attn, b, h))
-        flat["out"] = assert_close(f"{tag} av", plane(st.out, b, h), oracle.av(g_attn, v, k), p.dtype)
+        flat["logits"] += assert_close(f"{tag} logits", block(st.logits, sl), oracle.qk_rpb(q, key, rpb, scale, k), p.dtype)
+        g_logits = to_np(block(st.logits, sl))
+        flat["attn"] += assert_close(f"{tag} softmax", block(st.attn, sl), oracle.softmax(g_logits), p.dtype)
+        del g_logits
+        g_attn = to_np(block(st.attn, sl))
+        flat["out"] += assert_close(f"{tag} av", block(st.out, sl), oracle.av(g_attn, v, k), p.dtype)
         # forward, end to end against the all-double oracle
         o_out, o_lse = oracle.fwd(q, key, v, rpb, scale, k, return_lse=True)
-        flat["fused"] = assert_close(f"{tag} fused", plane(st.out_fused, b, h), o_out, p.dtype)
-        assert_close(f"{tag} lse", plane(st.lse, b, h), o_lse, "f32")
+        flat["fused"] += assert_close(f"{tag} fused", block(st.out_fused, sl), o_out, p.dtype)
+        assert_close(f"{tag} lse", block(st.lse, sl), o_lse, "f32")
         # The unfused chain stores logits and weights in the problem dtype.  In bf16 (8 significant
         # bits) those two intermediate roundings alone move the output by more than the 2e-3
         # bound, so for bf16 the chain is covered by the stage-wise checks above and the fused
         # end-to-end check; for fp32 / fp16 it is also compared end to end.
+        # In fp16 the chain's own roundings are part of the result: a logit in [4, 8) is stored to +-2^-9, which
+        # moves the weights of its query by up to 0.4 % each (and the normalisation with them), the weights are
+        # rounded to 11 bits once more, so the output may differ from the exact one by up to about
+        # 2 * 2^-8 * sum_j P_j |v_j|: the end-to-end bound is 8e-3, four times the per-stage one (over millions
+        # of elements the tail of that error does pass 2e-3; every stage by itself is held to 2e-3 above).
         if e2e_unfused and p.dtype != "bf16":
-            assert_close(f"{tag} unfused chain", plane(st.out, b, h), o_out, p.dtype)
+            assert_close(f"{tag} unfused chain", block(st.out, sl), o_out, p.dtype, abs_tol=2e-3 if p.dtype == "f32" else 8e-3)
         if not backward:
             continue
-        dout = plane(host["dout"], b, h).astype(np.float64)
-        assert_close(f"{tag} grad-a", plane(st.dp, b, h), oracle.av_bwd_p(dout, v, k), p.dtype)
-        assert_close(f"{tag} grad-v", plane(st.dv, b, h), oracle.av_bwd_v(g_attn, dout, k), p.dtype)
-        g_dp = to_np(plane(st.dp, b, h))
-        assert_close(f"{tag} softmax-bwd", plane(st.ds, b, h), oracle.softmax_bwd(g_attn, g_dp), p.dtype)
-        g_ds = to_np(plane(st.ds, b, h))
-        assert_close(f"{tag} grad-q", plane(st.dq, b, h), oracle.qk_bwd_q(g_ds, key, scale, k), p.dtype)
-        assert_close(f"{tag} grad-k", plane(st.dk, b, h), oracle.qk_bwd_k(g_ds, q, scale, k), p.dtype)
+        dout = block(host["dout"], sl).astype(np.float64)
+        assert_close(f"{tag} grad-a", block(st.dp, sl), oracle.av_bwd_p(dout, v, k), p.dtype)
+        assert_close(f"{tag} grad-v", block(st.dv, sl), oracle.av_bwd_v(g_attn, dout, k), p.dtype)
+        g_dp = to_np(block(st.dp, sl))
+        assert_close(f"{tag} softmax-bwd", block(st.ds, sl), oracle.softmax_bwd(g_attn, g_dp), p.dtype)
+        del g_dp, g_attn
+        g_ds = to_np(block(st.ds, sl))
+        assert_close(f"{tag} grad-q", block(st.dq, sl), oracle.qk_bwd_q(g_ds, key, scale, k), p.dtype)
+        assert_close(f"{tag} grad-k", block(st.dk, sl), oracle.qk_bwd_k(g_ds, q, scale, k), p.dtype)
     return flat
 
 
-def run_all(oracle, p: synth.Problem, seed: int, planes=None, backward=True, use_rpb=True, scale=None):
-    host = synth.make_inputs(p, seed)
+def whole_rpb_grad(oracle, ds: torch.Tensor, k: int, p: synth.Problem) -> np.ndarray:
+    """The oracle's bias gradient of a whole ds tensor (a sum over the batch), taken in batch ranges."""
+    total = None
+    for sl in slices_of(p, None):
+        part = oracle.qk_bwd_rpb(to_np(block(ds, sl)), k)
+        total = part if total is None else total + part
+    return total
+
+
+def whole_bwd_rpb(oracle, host: dict, p: synth.Problem, scale: float, use_rpb: bool) -> np.ndarray:
+    """The all-double oracle's bias gradient of the whole problem, taken in batch ranges."""
+    # without a bias the gradient with respect to it still exists: the oracle gets a table of zeros
+    rpb_all = host["rpb"].astype(np.float64) if use_rpb else np.zeros_like(host["rpb"], dtype=np.float64)
+    total = None
+    for sl in slices_of(p, None):
+        part = oracle.bwd(*(block(host[n], sl).astype(np.float64) for n in ("q", "k", "v")), rpb_all, scale,
+                          block(host["dout"], sl).astype(np.float64), p.k)[3]
+        total = part if total is None else total + part
+    return total
+
+
+def run_all(oracle, p: synth.Problem, seed: int, planes=None, backward=True, use_rpb=True, scale=None, rpb_std=0.02,
+            host=None, fused_backward=True, e2e_unfused=True):
+    """planes: the (b, h) planes compared element by element; None = every plane of the problem.
+    e2e_unfused: also compare the unfused chain's output with the all-double oracle (fp32 / fp16 only, and only
+    sensible while the logits are small: an fp16 logit of 16 is stored to +-0.004, which by itself moves the
+    output by more than the bound; the stage-wise checks hold at any size)."""
+    if host is None:
+        host = synth.make_inputs(p, seed, rpb_std=rpb_std)
     st = Stages(p, host, scale=scale, use_rpb=use_rpb)
     st.forward_unfused()
     st.forward_fused()
     if backward:
         st.backward_unfused()
     torch.cuda.synchronize()
-    if planes is None:
-        planes = [(b, h) for b in range(p.B) for h in range(p.heads)]
-    flat = check_planes(oracle, st, host, planes, backward)
+    flat = check_planes(oracle, st, host, planes, backward, e2e_unfused=e2e_unfused)
     if backward and use_rpb:
         # grad-b sums over the batch: needs the whole ds tensor
-        assert_close_rpb("grad-b", st.d_rpb, oracle.qk_bwd_rpb(to_np(st.ds), p.k))
+        assert_close_rpb("grad-b", st.d_rpb, whole_rpb_grad(oracle, st.ds, p.k, p))
         # The composed backward either runs the same kernels as the stages (then everything is bitwise
         # equal to them) or fuses grad-a with the softmax backward (16-bit types, k <= 7: dp is never
         # rounded to the storage type).  The fused result is checked like the stages: its ds (left in
@@ -82,16 +114,17 @@ def run_all(oracle, p: synth.Problem, seed: int, planes=None, backward=True, use
                 assert torch.equal(a, b_), f"na2d_bwd {n} differs from the stage-by-stage result"
         else:
             assert p.dtype != "f32" and p.k <= 7, "only the 16-bit small-window backward is fused"
-            for (b, h) in planes:
-                tag = f"na2d_bwd plane({b},{h})"
-                q, key, v, dout = (plane(host[n], b, h).astype(np.float64) for n in ("q", "k", "v", "dout"))
-                g_attn = to_np(plane(st.attn, b, h))
-                assert_close(f"{tag} ds", plane(ds_c, b, h), oracle.softmax_bwd(g_attn, oracle.av_bwd_p(dout, v, p.k)), p.dtype)
-                g_ds = to_np(plane(ds_c, b, h))
-                assert_close(f"{tag} grad-q", plane(dq, b, h), oracle.qk_bwd_q(g_ds, key, st.scale, p.k), p.dtype)
-                assert_close(f"{tag} grad-k", plane(dk, b, h), oracle.qk_bwd_k(g_ds, q, st.scale, p.k), p.dtype)
-            assert_close_rpb("na2d_bwd grad-b", d_rpb, oracle.qk_bwd_rpb(to_np(ds_c), p.k))
-    if backward:
+            for sl in slices_of(p, planes):
+                tag = f"na2d_bwd block{sl}"
+                q, key, v, dout = (block(host[n], sl).astype(np.float64) for n in ("q", "k", "v", "dout"))
+                g_attn = to_np(block(st.attn, sl))
+                assert_close(f"{tag} ds", block(ds_c, sl), oracle.softmax_bwd(g_attn, oracle.av_bwd_p(dout, v, p.k)), p.dtype)
+                del g_attn
+                g_ds = to_np(block(ds_c, sl))
+                assert_close(f"{tag} grad-q", block(dq, sl), oracle.qk_bwd_q(g_ds, key, st.scale, p.k), p.dtype)
+                assert_close(f"{tag} grad-k", block(dk, sl), oracle.qk_bwd_k(g_ds, q, st.scale, p.k), p.dtype)
+            assert_close_rpb("na2d_bwd grad-b", d_rpb, whole_rpb_grad(oracle, ds_c, p.k, p))
+    if backward and fused_backward:
         check_fused_backward(oracle, st, host, planes, use_rpb)
     return st, host, flat
 
@@ -108,19 +141,15 @@ def check_fused_backward(oracle, st: Stages, host: dict, planes, use_rpb: bool):
     prob = na.problem(p.B, p.heads, p.H, p.W, p.D, p.k, st.tdtype)
     if na.na2d_fused_bwd_is_fused(prob):
         assert p.dtype != "f32" and p.k <= 7
-        for (b, h) in planes:
-            tag = f"na2d_fused_bwd plane({b},{h})"
-            q, key, v, dout = (plane(host[n], b, h).astype(np.float64) for n in ("q", "k", "v", "dout"))
-            rpb = host["rpb"][h:h + 1].astype(np.float64) if use_rpb else None
+        for sl in slices_of(p, planes):
+            tag = f"na2d_fused_bwd block{sl}"
+            q, key, v, dout = (block(host[n], sl).astype(np.float64) for n in ("q", "k", "v", "dout"))
+            rpb = host["rpb"][sl[2]:sl[3]].astype(np.float64) if use_rpb else None
             o_dq, o_dk, o_dv, _ = oracle.bwd(q, key, v, rpb, st.scale, dout, p.k)
-            assert_close(f"{tag} dq", plane(dq, b, h), o_dq, p.dtype)
-            assert_close(f"{tag} dk", plane(dk, b, h), o_dk, p.dtype)
-            assert_close(f"{tag} dv", plane(dv, b, h), o_dv, p.dtype)
-        # without a bias the gradient with respect to it still exists: the oracle gets a table of zeros
-        rpb_all = host["rpb"].astype(np.float64) if use_rpb else np.zeros_like(host["rpb"], dtype=np.float64)
-        want = oracle.bwd(*(host[n].astype(np.float64) for n in ("q", "k", "v")), rpb_all, st.scale,
-                          host["dout"].astype(np.float64), p.k)[3]
-        assert_close_rpb("na2d_fused_bwd d_rpb", d_rpb, want)
+            assert_close(f"{tag} dq", block(dq, sl), o_dq, p.dtype)
+            assert_close(f"{tag} dk", block(dk, sl), o_dk, p.dtype)
+            assert_close(f"{tag} dv", block(dv, sl), o_dv, p.dtype)
+        assert_close_rpb("na2d_fused_bwd d_rpb", d_rpb, whole_bwd_rpb(oracle, host, p, st.scale, use_rpb))
     else:
         c_dq, c_dk, c_dv, c_d_rpb, _ = st.backward_composed()
         torch.cuda.synchronize()
@@ -187,6 +216,55 @@ def test_large_bias_values(oracle):
     assert_close_rpb("grad-b", st.d_rpb, oracle.qk_bwd_rpb(to_np(st.ds), p.k))
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("rpb_std", [1.0, 4.0])
+@pytest.mark.parametrize("k", [3, 7, 13])
+def test_bias_that_matters_16bit(oracle, k, rpb_std, dtype):
+    # The matrix-core kernels with a bias of the size of the logits and larger (Eq. 2's B): logits, fused
+    # forward and its log-sum-exp, the composed backward and the fused backward (dq, dk, dv, d_rpb), every
+    # element.  The fused kernels hold the table as fp16 beside the window mask; it must be the stored bias.
+    run_all(oracle, synth.Problem(2, 2, 19, 37, 32, k, dtype), seed=300 + k, rpb_std=rpb_std, e2e_unfused=(rpb_std <= 1.0))
+
+
+@pytest.mark.parametrize("dtype,big,fused_backward", [("f16", 60000.0, False), ("f16", -60000.0, True),
+                                                      ("bf16", 30000.0, False), ("bf16", -65280.0, True)])
+def test_bias_entry_near_fp16_maximum(oracle, dtype, big, fused_backward):
+    # One cell of the table next to the largest finite fp16 value (the key one step to the right of and below
+    # the query), the rest N(0, 1): where it is positive that key takes all the weight, where it is negative
+    # none.  Logits, softmax, fused forward (+ lse) and the composed backward are checked in every case.  The
+    # fused backward recomputes the weights as exp(logit - lse) from the fp32 lse, whose spacing at 6e4 is
+    # 2^-8: that alone moves a weight by 0.4 % (and where one key holds all the weight every exact ds is 0, so
+    # d_rpb would be nothing but the sum of those errors), so it is checked for the negative entry, which
+    # leaves lse small.
+    p = synth.Problem(2, 2, 18, 21, 32, 7, dtype)
+    host = synth.make_inputs(p, 77, rpb_std=1.0)
+    host["rpb"][:, p.k, p.k] = synth.round_to(np.full((p.heads,), big, dtype=np.float32), dtype)
+    assert np.all(np.abs(host["rpb"][:, p.k, p.k]) >= 0.99 * abs(big))
+    run_all(oracle, p, seed=77, host=host, fused_backward=fused_backward, e2e_unfused=False)
+
+
+@pytest.mark.parametrize("dtype,log2_scale", [("bf16", -17), ("bf16", 13), ("f16", -7), ("f16", 5)])
+def test_fused_backward_follows_the_scale_of_dout(oracle, dtype, log2_scale):
+    # The fused backward sums d_rpb in fixed point whose resolution follows the size of the gradients:
+    # upstream gradients of 2^-17 (8e-6) and 2^13 (8e3) times unit scale must give the same relative accuracy
+    # as unit scale.  The factor is a power of two, so the scaled inputs are exact and every gradient is the
+    # unit-scale one times the factor: dq, dk, dv are compared after dividing the factor out again.
+    p = synth.Problem(6, 2, 20, 35, 32, 7, dtype)
+    host = synth.make_inputs(p, 55, rpb_std=0.5)
+    f = 2.0 ** log2_scale
+    host["dout"] = synth.round_to(host["dout"] * np.float32(f), dtype)
+    st = Stages(p, host)
+    st.forward_fused()
+    dq, dk, dv, d_rpb = st.backward_fused()
+    torch.cuda.synchronize()
+    assert na.na2d_fused_bwd_is_fused(na.problem(p.B, p.heads, p.H, p.W, p.D, p.k, st.tdtype))
+    f64 = {n: host[n].astype(np.float64) for n in host}
+    o_dq, o_dk, o_dv, o_db = oracle.bwd(f64["q"], f64["k"], f64["v"], f64["rpb"], st.scale, f64["dout"], p.k)
+    for name, g, o in (("dq", dq, o_dq), ("dk", dk, o_dk), ("dv", dv, o_dv)):
+        assert_close(f"{name} / 2^{log2_scale}", to_np(g) / f, o / f, dtype)
+    assert_close_rpb("d_rpb", d_rpb, o_db)
+
+
 def test_softmax_in_place_and_ds_in_place(oracle):
     p = synth.Problem(2, 1, 15, 16, 32, 7, "f16")
     host = synth.make_inputs(p, 3)
@@ -214,7 +292,7 @@ def test_indices_bit_exact(oracle, H, W, k):
     assert np.array_equal(ri.cpu().numpy(), want_r)
 
 
-# ---- full-size configs in the launch configuration bench.py times: sampled planes ----------
+# ---- full-size configs in the launch configuration bench.py times: every plane ---------------
 
 FULL = [
     ("nat_tiny_stage1", True),      # config 2 / config 5 at k = 7: forward and backward
@@ -224,32 +302,31 @@ FULL = [
     ("nat_tiny_l4_bf16", False),    # 7x7, k = 7: full self attention
     ("detection_like", True),       # 200 x 334: ragged tiles on both axes, many tiles per column
     ("segmentation_like", True),
-    ("stage1_head_dim_64", True),   # head dims other than 32 run the plain-ALU kernels
+    ("stage1_head_dim_64", True),   # head dims other than 32
     ("stage1_head_dim_16", True),
 ]
 
 
 @pytest.mark.parametrize("name,backward", FULL)
-def test_full_size_config_sampled_planes(oracle, name, backward):
+def test_full_size_config_every_plane(oracle, name, backward):
+    # The oracle runs a whole batch range at once on all host cores, so every plane of the full-size problem is
+    # compared element by element: a batch range that no workgroup takes, or two take, at the launch geometry
+    # the benchmark times would show here.
     p = synth.CONFIGS[name]
-    g = np.random.default_rng(17)
-    planes = {(0, 0), (p.B - 1, p.heads - 1)}
-    while len(planes) < 3 and p.B * p.heads > 2:
-        planes.add((int(g.integers(p.B)), int(g.integers(p.heads))))
-    st, host, flat = run_all(oracle, p, seed=1000 + len(name), planes=sorted(planes), backward=backward)
+    st, host, flat = run_all(oracle, p, seed=1000 + len(name), planes=None, backward=backward)
     # properties that hold at any size, on the whole tensors
     rows = st.attn.float().sum(-1)
     assert float((rows - 1).abs().max()) < (2e-5 if p.dtype == "f32" else 2e-2)
     # fused and unfused agree to a few storage ulps (the unfused chain rounds logits and weights)
     diff = ((st.out.float() - st.out_fused.float()).abs() / st.out_fused.float().abs().clamp(min=1.0)).max()
     assert float(diff) < 3e-2
-    print(f"{name}: elements outside a flat 2e-3 on sampled planes: {flat}")
+    print(f"{name}: elements outside a flat 2e-3: {flat}")
 
 
 @pytest.mark.parametrize("k", [3, 5, 9, 11, 13])
 def test_config5_kernel_size_sweep_fwd_bwd(oracle, k):
     p = synth.Problem(64, 2, 56, 56, 32, k, "f16")
-    run_all(oracle, p, seed=5000 + k, planes=[(0, 0), (63, 1)], backward=True)
+    run_all(oracle, p, seed=5000 + k, planes=None, backward=True)
 
 
 # ---- head dims other than 32: every (dtype, D, k) class the library accepts, and the ones it refuses ------------
