@@ -133,6 +133,22 @@ int na2d_qk_bwd_rpb(const na2d_problem *p, const void *ds, float *d_rpb, void *w
                     void *stream);
 
 /*
+ * na2d_qk_bwd_rpb for callers that cannot allocate device memory or carry a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same order of
+ * additions, same result bit for bit; the partial sums live in a device array of
+ * NA2D_NOALLOC_SCRATCH_BYTES that is part of the library's code object (every GPU the library runs on
+ * holds one copy from its first use until the process ends).  The call allocates and frees nothing; its
+ * first use on a device looks up the array's address on that device.
+ * A problem whose partials (na2d_workspace_bytes(p, NA2D_WS_QK_BWD_RPB) at most) do not fit the array is
+ * refused with NA2D_ERR_WORKSPACE before any HIP call: 4 MiB hold, for example, 1024 workgroups'
+ * partials at k = 13, or B * heads = 6000 planes at k = 7.
+ * All calls on one GPU share the array: calls that may overlap in time (different streams, different
+ * host threads) race on it and must be ordered by the caller.  Nothing needs clearing between calls.
+ */
+#define NA2D_NOALLOC_SCRATCH_BYTES (4u << 20)
+int na2d_qk_bwd_rpb_noalloc(const na2d_problem *p, const void *ds, float *d_rpb, void *stream);
+
+/*
  * Whole backward of out = NA(q, k, v, rpb): grad-a, grad-v, softmax backward, grad-q, grad-k
  * and (if d_rpb != NULL) grad-b.  For the 16-bit types with k <= 7, grad-a and the softmax
  * backward run as one kernel and dp is never stored (so ds is computed from the unrounded dp);

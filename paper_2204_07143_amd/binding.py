@@ -21,7 +21,7 @@ WS_QK_BWD_RPB, WS_BWD, WS_FUSED_BWD = 0, 1, 2
 
 EXPORTS = (
     "na2d_qk_rpb", "na2d_softmax", "na2d_av", "na2d_fused_fwd", "na2d_av_bwd_p", "na2d_av_bwd_v",
-    "na2d_softmax_bwd", "na2d_qk_bwd_q", "na2d_qk_bwd_k", "na2d_qk_bwd_rpb", "na2d_bwd", "na2d_fused_bwd",
+    "na2d_softmax_bwd", "na2d_qk_bwd_q", "na2d_qk_bwd_k", "na2d_qk_bwd_rpb", "na2d_qk_bwd_rpb_noalloc", "na2d_bwd", "na2d_fused_bwd",
     "na2d_fused_bwd_is_fused",
     "na2d_workspace_bytes", "na2d_debug_indices", "na2d_host_axis_tables", "na2d_validate_problem",
     "na2d_strerror", "na2d_version",
@@ -73,6 +73,7 @@ def load() -> ctypes.CDLL:
             "na2d_qk_bwd_q": [pp, vp, vp, f, vp, vp],
             "na2d_qk_bwd_k": [pp, vp, vp, f, vp, vp],
             "na2d_qk_bwd_rpb": [pp, vp, vp, vp, ctypes.c_size_t, vp],
+            "na2d_qk_bwd_rpb_noalloc": [pp, vp, vp, vp],
             "na2d_bwd": [pp, vp, vp, vp, vp, vp, f, vp, vp, vp, vp, vp, ctypes.c_size_t, vp],
             "na2d_fused_bwd": [pp, vp, vp, vp, vp, f, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp],
             "na2d_debug_indices": [pp, vp, vp, vp],
@@ -241,6 +242,17 @@ def na2d_qk_bwd_rpb(ds, kernel: int, like, d_rpb, workspace):
     _check(load().na2d_qk_bwd_rpb(ctypes.byref(p), _ptr(ds, like.dtype, _attn_shape(like, kernel)),
                                   _ptr(d_rpb, torch.float32, _rpb_shape(like, kernel)), _ptr(workspace),
                                   workspace.numel() * workspace.element_size(), _stream()))
+    return d_rpb
+
+
+NOALLOC_SCRATCH_BYTES = 4 << 20   # NA2D_NOALLOC_SCRATCH_BYTES of na2d.h
+
+
+def na2d_qk_bwd_rpb_noalloc(ds, kernel: int, like, d_rpb):
+    """na2d_qk_bwd_rpb with the partials in the library's own device array: no workspace argument."""
+    p = _problem_of(like, kernel)
+    _check(load().na2d_qk_bwd_rpb_noalloc(ctypes.byref(p), _ptr(ds, like.dtype, _attn_shape(like, kernel)),
+                                          _ptr(d_rpb, torch.float32, _rpb_shape(like, kernel)), _stream()))
     return d_rpb
 
 

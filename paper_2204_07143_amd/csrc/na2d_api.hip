@@ -171,6 +171,13 @@ int na2d_qk_bwd_rpb(const na2d_problem *p, const void *ds, float *d_rpb, void *w
     return from_hip(launch_rpb_bwd(to_problem(p), ds, d_rpb, workspace, static_cast<hipStream_t>(stream)));
 }
 
+int na2d_qk_bwd_rpb_noalloc(const na2d_problem *p, const void *ds, float *d_rpb, void *stream) {
+    NA2D_CHECK_PROBLEM(p);
+    NA2D_REQUIRE(ds); NA2D_REQUIRE(d_rpb);
+    if (rpb_bwd_partial_bytes(to_problem(p)) > (size_t)NA2D_NOALLOC_SCRATCH_BYTES) return NA2D_ERR_WORKSPACE;
+    return from_hip(launch_rpb_bwd_noalloc(to_problem(p), ds, d_rpb, static_cast<hipStream_t>(stream)));
+}
+
 // The unfused backward on validated arguments: `ws` holds NA2D_WS_BWD bytes.
 static int run_bwd(const Problem &pr, const void *q, const void *k, const void *v, const void *attn, const void *dout,
                    float scale, void *dq, void *dk, void *dv, float *d_rpb, char *ws, hipStream_t s) {
@@ -292,7 +299,7 @@ const char *na2d_strerror(int status) {
         case NA2D_ERR_HEAD_DIM: return "head dim must be 16, 32, 64 or 128 (and small enough for the kernel size: see na2d.h)";
         case NA2D_ERR_SHAPE: return "non-positive extent or tensor too large";
         case NA2D_ERR_ALIGN: return "pointer is not 16-byte aligned";
-        case NA2D_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case NA2D_ERR_WORKSPACE: return "workspace missing, misaligned or too small (or the problem exceeds the built-in scratch array)";
         case NA2D_ERR_LAUNCH: return "HIP reported a launch failure";
         case NA2D_ERR_ALIAS: return "an output aliases an input";
         default: return "unknown status";

@@ -47,6 +47,9 @@ hipError_t launch_softmax(const Problem &p, const void *logits, void *out, hipSt
 hipError_t launch_softmax_bwd(const Problem &p, const void *attn, const void *dp, void *ds, hipStream_t s);
 size_t rpb_bwd_workspace_bytes(const Problem &p);
 hipError_t launch_rpb_bwd(const Problem &p, const void *ds, float *d_rpb, void *workspace, hipStream_t s);
+// the same with the partials in the library's own device array (NA2D_NOALLOC_SCRATCH_BYTES); bytes it needs
+size_t rpb_bwd_partial_bytes(const Problem &p);
+hipError_t launch_rpb_bwd_noalloc(const Problem &p, const void *ds, float *d_rpb, hipStream_t s);
 // grad-q that also leaves partial bias gradients (f16 / bf16, K <= 7): workgroup wg of the launch covers
 // tile position wg % npos, head (wg / npos) % heads and batch range wg / (npos * heads) of `splits`
 struct AvRpbSplit {

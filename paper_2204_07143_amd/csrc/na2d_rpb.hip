@@ -276,4 +276,47 @@ hipError_t launch_rpb_bwd(const Problem &p, const void *ds, float *d_rpb, void *
     return hipErrorInvalidValue;
 }
 
+// ---- the same call for callers that cannot allocate -------------------------------------------------
+//
+// The partials live in a device array that is part of the library's code object instead of a workspace
+// the caller brings.  Every GPU the library runs on holds its own copy at its own address, from the
+// first use until the process ends.  In host code the array's name is only a handle: its device address
+// comes from hipGetSymbolAddress, asked once per device with that device current, and only that address
+// is ever handed to a kernel.  The first kernel writes every partial it owns in full, so nothing needs
+// clearing between calls; two calls that overlap on one GPU share the array and race.
+static __device__ __align__(256) unsigned char scratch[NA2D_NOALLOC_SCRATCH_BYTES];
+
+size_t rpb_bwd_partial_bytes(const Problem &p) {
+    const int nb = 2 * p.K - 1;
+    const RpbSplit sp = rpb_split(p.planes(), p.H, p.W, p.K, p.elem_bytes());
+    return (size_t)p.planes() * sp.groups_per_plane * nb * nb * sizeof(float);
+}
+
+static hipError_t scratch_address(void **out) {
+    constexpr int kMaxDev = 64;
+    static std::atomic<void *> known[kMaxDev];   // zero-initialised; a device's slot is written once
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < kMaxDev;
+    if (tracked) {
+        if (void *ptr = known[dev].load(std::memory_order_acquire)) {
+            *out = ptr;
+            return hipSuccess;
+        }
+    }
+    void *ptr = nullptr;
+    if (hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)); e != hipSuccess) return e;
+    if (ptr == nullptr) return hipErrorInvalidSymbol;
+    if (tracked) known[dev].store(ptr, std::memory_order_release);   // every thread would store the same address
+    *out = ptr;
+    return hipSuccess;
+}
+
+hipError_t launch_rpb_bwd_noalloc(const Problem &p, const void *ds, float *d_rpb, hipStream_t s) {
+    if (rpb_bwd_partial_bytes(p) > sizeof(scratch)) return hipErrorInvalidValue;   // the C ABI layer has refused it already
+    void *ptr = nullptr;
+    if (hipError_t e = scratch_address(&ptr); e != hipSuccess) return e;
+    return launch_rpb_bwd(p, ds, d_rpb, ptr, s);
+}
+
 }  // namespace na2d
