@@ -4,16 +4,24 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload nat_tiny_stage1] [--k 7]
 
 One "step" is one pass of the whole hot path over one batch of synthetic NAT-Tiny stage-1
-input (B=64, heads=2, 56x56, D=32, fp16, k=7 unless overridden), inputs resident in HBM:
+input (B=64, heads=2, 56x56, D=32, fp16, k=7 unless overridden), inputs resident in HBM: the ten
+scoped entry points, one call each,
   forward, unfused : na2d_qk_rpb -> na2d_softmax -> na2d_av
   forward, fused   : na2d_fused_fwd (with log-sum-exp)
-  backward         : na2d_bwd = grad-a, grad-v, softmax backward, grad-q, grad-k, grad-b
-The fused backward (na2d_fused_bwd, from the fused forward's log-sum-exp) is timed beside the step and
-reported in `kernels` and `us_per_call`; it is not part of the step or of `value`.
-`value` is the step's algorithmic HBM traffic divided by its wall time (GB/s); the per-call
-microseconds and per-kernel GB/s are in `kernels`.  Buffers rotate over several disjoint sets
-so that successive launches of one kernel do not find their operands in the 256 MB Infinity
-Cache.  Prints exactly one JSON line on stdout; progress goes to stderr.
+  backward         : na2d_av_bwd_p, na2d_av_bwd_v, na2d_softmax_bwd, na2d_qk_bwd_q, na2d_qk_bwd_k, na2d_qk_bwd_rpb
+`value` is the algorithmic HBM traffic of those ten calls divided by the step's time (GB/s).  The composed
+backward na2d_bwd (which fuses grad-a with the softmax backward and grad-b with grad-q where it can) and the
+fused backward na2d_fused_bwd are timed beside the step and reported in `kernels` and `us_per_call` with the
+bytes each of them has to move; they are not part of the step or of `value`.
+
+Timing: the step and every call are captured in HIP graphs (launches only: the library records no memset
+or copy nodes) and the graphs are replayed between HIP events on the launch stream, so that the host's
+issue rate is not part of a kernel's time; `--eager` times Python-issued launches instead.  Every kernel
+is timed over at least 200 launches: `us` is the median over the graph replays, `us_min` the fastest
+replay.  Buffers rotate over several disjoint sets so that successive launches of one kernel do not find
+their operands in the 256 MB Infinity Cache.  A plain device copy of 128 MiB is timed the same way as the
+practical ceiling of the memory system (`copy_ceiling_GBps`).
+Prints exactly one JSON line on stdout; progress goes to stderr.
 """
 from __future__ import annotations
 
@@ -47,7 +55,15 @@ def algorithmic_bytes(p) -> dict:
         "qk_bwd_q": contraction, "qk_bwd_k": contraction, "qk_bwd_rpb": nq * kk * e,
         # q, k, v, dout and lse in; dq, dk, dv out (the bias gradient is a few hundred bytes)
         "fused_bwd": nq * (7 * D * e + 4),
+        # the composed backward on stored weights; where it fuses (16-bit, k <= 7, D = 32) dp is never stored and
+        # ds is read by grad-q and grad-k only: grad-a + softmax backward (attn, dout, v in; ds out), grad-v,
+        # grad-q (+ grad-b), grad-k.  Elsewhere it is the six steps one after the other.
+        "bwd": (nq * ((2 * D * e + 2 * kk * e) + 3 * (2 * D * e + kk * e))
+                if (p.dtype != "f32" and p.k <= 7 and p.D == 32) else 4 * contraction + nq * 4 * kk * e),
     }
+
+
+STEP_CALLS = ("qk_rpb", "softmax", "av", "fused_fwd", "av_bwd_p", "av_bwd_v", "softmax_bwd", "qk_bwd_q", "qk_bwd_k", "qk_bwd_rpb")
 
 
 class BufferSet:
@@ -84,15 +100,65 @@ def make_calls(p, na, scale):
         "qk_bwd_rpb": lambda s: na.na2d_qk_bwd_rpb(s.dpds, k, s.q, s.d_rpb, s.ws_rpb),
         "fused_bwd": lambda s: na.na2d_fused_bwd(s.q, s.k, s.v, s.rpb, scale, s.lse, s.dout, k, s.dq, s.dk, s.dv,
                                                  s.d_rpb, s.ws_fused),
+        "bwd": lambda s: na.na2d_bwd(s.q, s.k, s.v, s.attn, s.dout, scale, k, s.dq, s.dk, s.dv, s.d_rpb, s.ws),
     }
 
 
-def step(s, calls, na, p, scale):
-    calls["qk_rpb"](s)
-    calls["softmax"](s)
-    calls["av"](s)
-    calls["fused_fwd"](s)
-    na.na2d_bwd(s.q, s.k, s.v, s.attn, s.dout, scale, p.k, s.dq, s.dk, s.dv, s.d_rpb, s.ws)
+def step(s, calls):
+    """One pass of the hot path: the ten scoped entry points, one call each."""
+    for n in STEP_CALLS:
+        calls[n](s)
+
+
+class Timer:
+    """Times a sequence of launches between HIP events on the launch stream.  With graphs (the default) the
+    sequence is captured once and replayed: `launches` launches per replay, `replays` replays, each replay
+    between its own pair of events; otherwise the launches are issued from Python between one pair of events
+    per replay.  Returns (median, min) microseconds per launch over the replays."""
+
+    def __init__(self, torch, use_graphs: bool):
+        self.torch, self.use_graphs = torch, use_graphs
+        self.mode = "hip graph replays" if use_graphs else "python-issued launches"
+
+    def per_launch_us(self, fn, sets, launches: int, replays: int):
+        torch = self.torch
+        for st in sets:   # untimed: the first launch of a kernel loads its code object and sets its LDS limit
+            fn(st)
+        torch.cuda.synchronize()
+        run = None
+        if self.use_graphs:
+            try:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    for i in range(launches):
+                        fn(sets[i % len(sets)])
+                run = g.replay
+            except Exception as e:   # capture refused: say so once and go on with python-issued launches
+                log(f"  (graph capture failed: {e!r}; timing python-issued launches)")
+                self.use_graphs, self.mode = False, "python-issued launches (graph capture failed)"
+                torch.cuda.synchronize()
+        if run is None:
+            def run():
+                for i in range(launches):
+                    fn(sets[i % len(sets)])
+        run()   # untimed replay
+        torch.cuda.synchronize()
+        stream = torch.cuda.current_stream()
+        times = []
+        for _ in range(replays):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            run()
+            b.record(stream)
+            torch.cuda.synchronize()
+            times.append(a.elapsed_time(b) * 1e3 / launches)
+        times.sort()
+        return times[len(times) // 2], times[0]
+
+
+def launches_for(us_guess: float) -> int:
+    """Launches per graph: enough that a replay lasts about a millisecond (its own launch cost then vanishes)."""
+    return max(24, min(240, int(1000.0 / max(us_guess, 1.0))))
 
 
 def cpu_baseline(p, synth, budget_s: float = 20.0) -> dict:
@@ -136,10 +202,24 @@ def cpu_baseline(p, synth, budget_s: float = 20.0) -> dict:
         reps += 1
     t = total / reps
     sp = synth.Problem(bs, p.heads, p.H, p.W, p.D, p.k, p.dtype)
-    nbytes = sum(v for n, v in algorithmic_bytes(sp).items() if n != "fused_bwd")
-    return {"value": round(nbytes / t / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": f"one full step (same 10 calls) on batch {bs} of {p.B}, mean of {reps} runs, {t:.2f} s each", "us_per_step_extrapolated":
-            round(t * p.B / bs * 1e6, 1)}
+    step_bytes = lambda q: sum(algorithmic_bytes(q)[n] for n in STEP_CALLS)
+    out = {"value": round(step_bytes(sp) / t / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+           "sample": f"one full step (same 10 calls) on batch {bs} of {p.B}, mean of {reps} runs, {t:.2f} s each",
+           "us_per_step_extrapolated": round(t * p.B / bs * 1e6, 1)}
+    # the same on one thread, on one batch item (best of 3)
+    o.set_threads(1)
+    try:
+        t1, spent = run(1), 0.0
+        while spent < 3.0:   # best of about three seconds of runs
+            t = run(1)
+            t1, spent = min(t1, t), spent + t
+    finally:
+        o.set_threads(cores)
+    s1 = synth.Problem(1, p.heads, p.H, p.W, p.D, p.k, p.dtype)
+    out["single_thread"] = {"value": round(step_bytes(s1) / t1 / 1e9, 4), "unit": "GB/s", "cores": 1,
+                            "sample": f"one full step on batch 1 of {p.B}, best run of about 3 s of runs, {t1 * 1e3:.1f} ms",
+                            "us_per_step_extrapolated": round(t1 * p.B * 1e6, 1)}
+    return out
 
 
 def measured_traffic(workload: str, p, kernel_group: str):
@@ -157,7 +237,7 @@ def measured_traffic(workload: str, p, kernel_group: str):
     return None
 
 
-def composite_nat_tiny(p1, na, synth, torch, stream, iters: int) -> dict:
+def composite_nat_tiny(p1, na, synth, torch, timer, replays: int) -> dict:
     """One NAT-Tiny forward's (and forward + backward's) worth of neighbourhood attention at the bench
     batch: the four stages of the model (Section 3.2: 3, 4, 18 and 5 layers on 56, 28, 14 and 7 wide
     maps with 2, 4, 8 and 16 heads of dim 32), each layer one fused forward (plus one fused backward),
@@ -171,17 +251,8 @@ def composite_nat_tiny(p1, na, synth, torch, stream, iters: int) -> dict:
         calls = make_calls(sp, na, sp.default_scale)
         ab = algorithmic_bytes(sp)
         us = {}
-        for name in ("fused_fwd", "fused_bwd"):
-            for st in sets:
-                calls[name](st)
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            a.record(stream)
-            for j in range(iters):
-                calls[name](sets[j % len(sets)])
-            b.record(stream)
-            torch.cuda.synchronize()
-            us[name] = a.elapsed_time(b) * 1e3 / iters
+        for name, guess in (("fused_fwd", 15.0), ("fused_bwd", 50.0)):
+            us[name], _ = timer.per_launch_us(calls[name], sets, launches_for(guess), replays)
         stages.append({"map": f"{sp.H}x{sp.W}", "heads": sp.heads, "layers": nl, "fused_fwd_us": round(us["fused_fwd"], 2),
                        "fused_bwd_us": round(us["fused_bwd"], 2)})
         fwd_us += nl * us["fused_fwd"]
@@ -196,7 +267,7 @@ def composite_nat_tiny(p1, na, synth, torch, stream, iters: int) -> dict:
             "stages": stages}
 
 
-def bench_na1d(na, synth, torch, stream, iters: int) -> dict:
+def bench_na1d(na, synth, torch, timer, replays: int) -> dict:
     """The 1D entry points on the sequence workload (NAT-Tiny's first-stage tokens read as a sequence:
     B=64, heads=2, L=3136, D=32, k=7, f16), each call timed on its own over rotating buffer sets.
     Algorithmic bytes per query: contractions 2*D*e + k*e, softmax 2*k*e, softmax backward 3*k*e, bias
@@ -239,18 +310,9 @@ def bench_na1d(na, synth, torch, stream, iters: int) -> dict:
     }
     res, total_us, total_bytes = {}, 0.0, 0
     for name, (fn, nbytes) in calls.items():
-        for st in sets:
-            fn(st)
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        a.record(stream)
-        for j in range(iters):
-            fn(sets[j % len(sets)])
-        b.record(stream)
-        torch.cuda.synchronize()
-        us = a.elapsed_time(b) * 1e3 / iters
-        res[name] = {"us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1), "pct_hbm_peak": round(100 * nbytes / us / 1e3 / HBM_PEAK_GBPS, 1),
-                     "MB": round(nbytes / 1e6, 2)}
+        us, us_min = timer.per_launch_us(fn, sets, launches_for(80.0 if name == "fused_bwd" else 12.0), replays)
+        res[name] = {"us": round(us, 2), "us_min": round(us_min, 2), "GBps": round(nbytes / us / 1e3, 1),
+                     "pct_hbm_peak": round(100 * nbytes / us / 1e3 / HBM_PEAK_GBPS, 1), "MB": round(nbytes / 1e6, 2)}
         if name != "fused_bwd":   # the fused backward is an alternative to the six unfused steps, not one more call
             total_us += us
             total_bytes += nbytes
@@ -280,11 +342,14 @@ def main() -> int:
     ap.add_argument("--workload", default="nat_tiny_stage1")
     ap.add_argument("--k", type=int, default=None, help="override the kernel size (config 5 sweeps 3..13)")
     ap.add_argument("--sets", type=int, default=3, help="disjoint buffer sets rotated between launches")
-    ap.add_argument("--kernel-iters", type=int, default=30)
+    ap.add_argument("--replays", type=int, default=10, help="timed graph replays per kernel (each at least 24 launches)")
+    ap.add_argument("--eager", action="store_true", help="time python-issued launches instead of HIP graph replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--skip-composite", action="store_true",
-                    help="leave out the NAT-Tiny composite (its smaller maps launch the same kernels: per-kernel counter "
-                         "averages of a profiler then mix shapes)")
+                    help="leave out the NAT-Tiny composite and the 1D workload (their maps launch the same kernels: "
+                         "per-kernel averages of a profiler then mix shapes)")
+    ap.add_argument("--only", default=None,
+                    help="comma-separated entry points (of the `kernels` table) to launch, nothing else: for counter runs")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch plain device copies of known size (calibration of rocprofv3's HBM counters)")
     args = ap.parse_args()
@@ -306,109 +371,148 @@ def main() -> int:
     sets = [BufferSet(p, host, na, synth, torch) for _ in range(args.sets)]
     calls = make_calls(p, na, scale)
     abytes = algorithmic_bytes(p)
-    step_bytes = sum(v for n, v in abytes.items() if n != "fused_bwd")
+    step_bytes = sum(abytes[n] for n in STEP_CALLS)
     log(f"workload {args.workload}: {p}  step = {step_bytes / 1e6:.1f} MB algorithmic, {args.sets} buffer sets")
 
+    # populate every set once (also the warm-up of every kernel: code objects, LDS limits)
+    for s in sets:
+        step(s, calls)
+        calls["fused_bwd"](s)
+        calls["bwd"](s)
+    torch.cuda.synchronize()
+
+    if args.only:   # a bare run of the named entry points for a profiler: 30 launches each, no timing, no JSON
+        for name in args.only.split(","):
+            for i in range(30):
+                calls[name](sets[i % len(sets)])
+        if args.copy_probe:
+            src = torch.empty(128 << 20, dtype=torch.uint8, device="cuda")
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+        torch.cuda.synchronize()
+        return 0
+
+    timer = Timer(torch, use_graphs=not args.eager)
     stream = torch.cuda.current_stream()
 
-    def timed(fn, iters):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        a.record(stream)
-        for i in range(iters):
-            fn(sets[i % len(sets)])
-        b.record(stream)
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) * 1e3 / iters  # microseconds per iteration
+    # W untimed warm-up steps, then the timed region: exactly K steps between events, one device synchronisation
+    # on each side.  With graphs, one graph per buffer set holds the ten launches of a step and the K steps are K
+    # graph replays, rotating over the sets.
+    step_graphs = None
+    if timer.use_graphs:
+        try:
+            step_graphs = []
+            for st in sets:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    step(st, calls)
+                step_graphs.append(g)
+        except Exception as e:
+            log(f"  (graph capture of the step failed: {e!r}; python-issued launches)")
+            step_graphs = None
+            timer.use_graphs, timer.mode = False, "python-issued launches (graph capture failed)"
+            torch.cuda.synchronize()
 
-    # populate every set once (also the warm-up of every kernel), then W untimed steps
-    for s in sets:
-        step(s, calls, na, p, scale)
+    def run_step(i):
+        if step_graphs is not None:
+            step_graphs[i % len(sets)].replay()
+        else:
+            step(sets[i % len(sets)], calls)
+
     for i in range(args.warmup):
-        step(sets[i % len(sets)], calls, na, p, scale)
+        run_step(i)
     torch.cuda.synchronize()
-
-    # the timed region: exactly K steps
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
-    us_step = timed(lambda s: step(s, calls, na, p, scale), args.steps)
+    a.record(stream)
+    for i in range(args.steps):
+        run_step(i)
+    b.record(stream)
+    torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    log(f"step: {us_step:.1f} us  ({step_bytes / us_step / 1e3:.1f} GB/s algorithmic; wall {wall:.2f} s for {args.steps} steps)")
+    us_step = a.elapsed_time(b) * 1e3 / args.steps
+    log(f"step: {us_step:.1f} us  ({step_bytes / us_step / 1e3:.1f} GB/s algorithmic; wall {wall * 1e3:.1f} ms for {args.steps} steps; {timer.mode})")
+    # the same K steps issued from Python, for comparison (host issue rate included)
+    torch.cuda.synchronize()
+    a2, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a2.record(stream)
+    for i in range(args.steps):
+        step(sets[i % len(sets)], calls)
+    b2.record(stream)
+    torch.cuda.synchronize()
+    us_step_eager = a2.elapsed_time(b2) * 1e3 / args.steps
 
-    # per-kernel: each call launched back to back over rotating buffer sets
+    # the practical ceiling of the memory system: a plain device copy of 128 MiB (read + write), timed the same way
+    # (four source / destination pairs in rotation, 1 GiB in all, so that no copy finds its source in the 256 MB
+    # Infinity Cache)
+    class _C:
+        pass
+    csets = []
+    for _ in range(4):
+        c = _C()
+        c.src = torch.empty(128 << 20, dtype=torch.uint8, device="cuda")
+        c.dst = torch.empty_like(c.src)
+        csets.append(c)
+    copy_us, copy_us_min = timer.per_launch_us(lambda c: c.dst.copy_(c.src), csets, 24, args.replays)
+    copy_ceiling = 2 * (128 << 20) / copy_us / 1e3
+    log(f"  device copy of 128 MiB: {copy_us:.1f} us = {copy_ceiling:.0f} GB/s (read + write)")
+    del csets
+
+    # per-kernel: every entry point over rotating buffer sets, at least 200 launches each
     kernels = {}
+    guess = {"softmax": 14.0, "softmax_bwd": 18.0, "qk_bwd_rpb": 10.0, "fused_bwd": 100.0, "bwd": 110.0}
     for name, fn in calls.items():
-        for st in sets:   # untimed: the first launch of a kernel loads its code object
-            fn(st)
-        us = timed(fn, args.kernel_iters)
+        n = launches_for(guess.get(name, 22.0) * (p.kk / 49.0 if p.kk > 49 else 1.0))
+        us, us_min = timer.per_launch_us(fn, sets, n, max(args.replays, (200 + n - 1) // n))
         gbps = abytes[name] / us / 1e3
-        kernels[name] = {"us": round(us, 2), "GBps": round(gbps, 1), "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 1),
-                         "MB": round(abytes[name] / 1e6, 2)}
-        log(f"  {name:12s} {us:9.2f} us  {gbps:8.1f} GB/s  {100 * gbps / HBM_PEAK_GBPS:5.1f}% of 8 TB/s")
+        kernels[name] = {"us": round(us, 2), "us_min": round(us_min, 2), "GBps": round(gbps, 1),
+                         "pct_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 1), "MB": round(abytes[name] / 1e6, 2)}
+        log(f"  {name:12s} {us:9.2f} us (min {us_min:7.2f})  {gbps:8.1f} GB/s  {100 * gbps / HBM_PEAK_GBPS:5.1f}% of 8 TB/s")
     unfused_fwd = sum(kernels[n]["us"] for n in ("qk_rpb", "softmax", "av"))
     bwd = sum(kernels[n]["us"] for n in ("av_bwd_p", "av_bwd_v", "softmax_bwd", "qk_bwd_q", "qk_bwd_k", "qk_bwd_rpb"))
-    log(f"  unfused fwd {unfused_fwd:.1f} us, fused fwd {kernels['fused_fwd']['us']:.1f} us, bwd {bwd:.1f} us, "
-        f"fused bwd {kernels['fused_bwd']['us']:.1f} us")
+    log(f"  unfused fwd {unfused_fwd:.1f} us, fused fwd {kernels['fused_fwd']['us']:.1f} us, bwd (six calls) {bwd:.1f} us, "
+        f"na2d_bwd {kernels['bwd']['us']:.1f} us, fused bwd {kernels['fused_bwd']['us']:.1f} us")
 
-    # The same K steps once more with HIP events around every launch (on the launch stream): the average
-    # duration of each kernel inside the step, where it runs between the others.  Entry points that
-    # run the same device kernel are grouped; the dominant kernel is the group with the most time.
-    order = ["qk_rpb", "softmax", "av", "fused_fwd", "av_bwd_p", "av_bwd_v", "softmax_bwd", "qk_bwd_q", "qk_bwd_k", "qk_bwd_rpb"]
-    evs = {n: [] for n in order}
-    torch.cuda.synchronize()
-    for i in range(args.steps):
-        st = sets[i % len(sets)]
-        for n in order:
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(stream)
-            calls[n](st)
-            b.record(stream)
-            evs[n].append((a, b))
-    torch.cuda.synchronize()
-    in_step = {n: sum(a.elapsed_time(b) for a, b in evs[n]) * 1e3 / len(evs[n]) for n in order}
+    # Entry points that run the same device kernel are grouped; the dominant kernel is the group with the most
+    # time in the step.  Its launch duration for the roofline is the median measured above (events on the launch
+    # stream around graph replays), which is what a kernel trace of the same command reports.
     inv = inverse_kernel_name(args.workload, p)
     groups = {"qk_mfma (qk_rpb, av_bwd_p)": ["qk_rpb", "av_bwd_p"], "av_mfma (av, qk_bwd_q)": ["av", "qk_bwd_q"],
               f"{inv} (av_bwd_v, qk_bwd_k)": ["av_bwd_v", "qk_bwd_k"], "fused_mfma (fused_fwd)": ["fused_fwd"],
               "softmax": ["softmax"], "softmax_bwd": ["softmax_bwd"], "rpb_partial + rpb_final (qk_bwd_rpb)": ["qk_bwd_rpb"]}
-    # The dominant kernel is the group with the most time in the step.  Its launch duration for the roofline is
-    # the one measured with events around a run of back-to-back launches (the table above): an event pair around
-    # every single launch adds about 2 us of its own to each, which the per-kernel trace of rocprofv3 does not see.
-    dominant = max(groups, key=lambda g: sum(in_step[n] for n in groups[g]))
+    dominant = max(groups, key=lambda g: sum(kernels[n]["us"] for n in groups[g]))
     members = groups[dominant]
     avg_us = sum(kernels[n]["us"] for n in members) / len(members)
-    avg_us_in_step = sum(in_step[n] for n in members) / len(members)
     avg_bytes = sum(abytes[n] for n in members) / len(members)
     achieved = avg_bytes / avg_us / 1e3
-    for n in order:
-        kernels[n]["us_in_step"] = round(in_step[n], 2)
-    log("  in-step per-launch us (an event pair around every launch): " + ", ".join(f"{n} {in_step[n]:.1f}" for n in order))
-    log(f"  dominant kernel: {dominant}: {avg_us:.2f} us per launch ({avg_us_in_step:.2f} between per-launch events), "
-        f"{achieved:.0f} GB/s algorithmic")
+    log(f"  dominant kernel: {dominant}: {avg_us:.2f} us per launch, {achieved:.0f} GB/s algorithmic")
+    traffic_file = f"profiles/hbm_traffic_{args.workload}_k{p.k}_{p.dtype}.txt"
+    traffic = measured_traffic(args.workload, p, dominant)
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args.workload, p, dominant),
-                "us_per_launch": round(avg_us, 2), "us_per_launch_between_events_in_step": round(avg_us_in_step, 2),
-                "algorithmic_bytes_per_launch": int(avg_bytes)}
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "traffic_source": (f"{traffic_file}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this "
+                                   "workload, scaled by a plain copy; not measured in this run") if traffic is not None else None,
+                "us_per_launch": round(avg_us, 2), "algorithmic_bytes_per_launch": int(avg_bytes),
+                "frac_of_copy_ceiling": round(achieved / copy_ceiling, 4)}
 
     composite, na1d = None, None
     if args.workload == "nat_tiny_stage1" and args.k is None:
         if not args.skip_composite:
-            composite = composite_nat_tiny(p, na, synth, torch, stream, args.kernel_iters)
-        na1d = bench_na1d(na, synth, torch, stream, args.kernel_iters)
-
-    if args.copy_probe:   # 128 MiB device-to-device copies: 2 x 128 MiB of HBM traffic each
-        src = torch.empty(128 << 20, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
+            composite = composite_nat_tiny(p, na, synth, torch, timer, args.replays)
+            na1d = bench_na1d(na, synth, torch, timer, args.replays)
 
     result = {
         "metric": METRIC, "value": round(step_bytes / us_step / 1e3, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us_step / 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": p.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload} (B={p.B}, heads={p.heads}, {p.H}x{p.W}, D={p.D}, k={p.k}, {p.dtype}): "
-                               "unfused fwd + fused fwd + bwd, one call each", "buffer_sets": args.sets},
+                               "the ten scoped calls (unfused fwd, fused fwd, six backward steps), one call each",
+                   "buffer_sets": args.sets, "timing": timer.mode},
+        "step_MB": round(step_bytes / 1e6, 1), "us_per_step_python_issued": round(us_step_eager, 1),
+        "copy_ceiling_GBps": round(copy_ceiling, 1),
         "us_per_call": {"unfused_fwd": round(unfused_fwd, 1), "fused_fwd": kernels["fused_fwd"]["us"],
-                        "bwd": round(bwd, 1), "fused_bwd": kernels["fused_bwd"]["us"],
+                        "bwd_six_calls": round(bwd, 1), "bwd": kernels["bwd"]["us"], "fused_bwd": kernels["fused_bwd"]["us"],
                         "fwd_bwd_unfused": round(unfused_fwd + bwd, 1),
                         "fwd_bwd_fused": round(kernels["fused_fwd"]["us"] + kernels["fused_bwd"]["us"], 1)},
         "kernels": kernels, "roofline": roofline,

@@ -142,6 +142,25 @@ class _NA1D(torch.autograd.Function):
         return dq, dk, dv, (d32.to(rpb.dtype) if want_bias else None), None, None
 
 
+class _NA2DSoftmax(torch.autograd.Function):
+    """attn = softmax(logits) over the k*k axis (Eq. 4), forward and backward by the library's kernels."""
+
+    @staticmethod
+    def forward(ctx, logits, like, kernel_size):
+        logits = logits.contiguous()
+        attn = na.na2d_softmax(logits, kernel_size, like, torch.empty_like(logits))
+        ctx.save_for_backward(attn)
+        ctx.kernel_size, ctx.like_shape = kernel_size, like.shape
+        return attn
+
+    @staticmethod
+    def backward(ctx, dattn):
+        (attn,) = ctx.saved_tensors
+        like = torch.empty(ctx.like_shape, dtype=attn.dtype, device="meta")   # shape and dtype only
+        ds = na.na2d_softmax_bwd(attn, dattn.contiguous(), ctx.kernel_size, like, torch.empty_like(attn))
+        return ds, None, None
+
+
 def _scale_of(q, scale):
     return float(q.shape[-1]) ** -0.5 if scale is None else float(scale)
 
@@ -166,7 +185,14 @@ def na1d(q, k, v, rpb=None, kernel_size: int = 7, scale: float | None = None):
     return _NA1D.apply(q, k, v, rpb, int(kernel_size), _scale_of(q, scale))
 
 
+def na2d_softmax(logits, like, kernel_size: int):
+    """Softmax over the k*k axis of neighbourhood logits; ``like`` is any [B, heads, H, W, D] tensor of the
+    problem (its shape and dtype describe it to the library).  Differentiable in logits."""
+    return _NA2DSoftmax.apply(logits, like, int(kernel_size))
+
+
 def na2d_unfused(q, k, v, rpb=None, kernel_size: int = 7, scale: float | None = None):
-    """The same operator as the paper composes it: QK+RPB, the framework's softmax, AV."""
+    """The same operator as the paper composes it: QK+RPB, softmax, AV; every step, forward and backward, is a
+    library kernel."""
     logits = na2d_qk_rpb(q, k, rpb, kernel_size, scale)
-    return na2d_av(torch.softmax(logits, dim=-1), v, kernel_size)
+    return na2d_av(na2d_softmax(logits, q, kernel_size), v, kernel_size)

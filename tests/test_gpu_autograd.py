@@ -90,9 +90,37 @@ def test_two_function_split_matches_stage_calls_and_oracle(oracle):
         tol = 4e-5 * np.maximum(np.abs(o), np.sqrt(np.mean(o * o)))
         assert (err <= tol).all(), f"{name}: max err / tol {np.max(err / tol):.2f}"
     assert_close_rpb("d_rpb", rpb.grad, o_drpb)
-    # the convenience composition gives the same forward bits
+    # the convenience composition runs the library's softmax instead of torch's: same result to fp32 rounding
     with torch.no_grad():
-        assert torch.equal(F.na2d_unfused(q, key, v, rpb, k), out)
+        assert torch.allclose(F.na2d_unfused(q, key, v, rpb, k), out, rtol=2e-5, atol=2e-6)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_unfused_composition_is_library_kernels_end_to_end(oracle, dtype):
+    """na2d_unfused = QK+RPB, softmax, AV with every step (and every gradient) a library call: forward and all
+    four gradients are the stage kernels' outputs bit for bit, and within the bounds of the oracle's."""
+    k = 7
+    p = synth.Problem(2, 2, 19, 23, 32, k, dtype)
+    host = synth.make_inputs(p, 7400)
+    q, key, v, rpb, dout = leaves(p, host)
+    out = F.na2d_unfused(q, key, v, rpb, k)
+    out.backward(dout)
+    torch.cuda.synchronize()
+    st = Stages(p, host)
+    st.forward_unfused()
+    st.backward_unfused()
+    torch.cuda.synchronize()
+    assert torch.equal(out.detach(), st.out)
+    assert torch.equal(v.grad, st.dv) and torch.equal(q.grad, st.dq) and torch.equal(key.grad, st.dk)
+    assert torch.equal(rpb.grad, st.d_rpb.to(rpb.dtype))
+    if dtype == "f32":
+        h64 = {n: host[n].astype(np.float64) for n in host}
+        o_dq, o_dk, o_dv, o_drpb = oracle.bwd(h64["q"], h64["k"], h64["v"], h64["rpb"], p.default_scale, h64["dout"], k)
+        for name, g, o in (("dq", q.grad, o_dq), ("dk", key.grad, o_dk), ("dv", v.grad, o_dv)):
+            err = np.abs(to_np(g) - o)
+            tol = 4e-5 * np.maximum(np.abs(o), np.sqrt(np.mean(o * o)))
+            assert (err <= tol).all(), f"{name}: max err / tol {np.max(err / tol):.2f}"
+        assert_close_rpb("d_rpb", rpb.grad, o_drpb)
 
 
 def test_1d_operator_gradients():
