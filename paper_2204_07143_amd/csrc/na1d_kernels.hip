@@ -90,9 +90,9 @@ __device__ __forceinline__ void run_out(char *gbase, size_t g0, int nbytes, cons
 template <typename T, int NT>
 __device__ __forceinline__ void store_tile(const float (&acc)[kHeadDim], bool live, char *stage, char *gdst, int n, int tid) {
     constexpr int CPK = Traits<T>::kKeyBytes / 16, STRIDE = Traits<T>::kKeyStride;
-    __syncthreads();
+    workgroup_sync();
     if (live) store_vec32<T>(stage + tid * STRIDE, acc);
-    __syncthreads();
+    workgroup_sync();
     const int nchunks = n * CPK;
     for (int c0 = tid; c0 < nchunks; c0 += 4 * NT) {
         u32x4 v[4];
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(TQ) void qk1d_kernel(const T *__restrict__ x, const
     load_vectors<T, TQ>(reinterpret_cast<const char *>(y) + ((size_t)t.plane * L + h0) * KBYTES, h1 - h0, halo, tid);
     for (int i = tid; i < 2 * K - 1; i += TQ)
         bias[i] = rpb ? to_f32(rpb[(size_t)(t.plane % heads) * (2 * K - 1) + i]) : 0.f;
-    __syncthreads();
+    workgroup_sync();
     const size_t g0 = ((size_t)t.plane * L + t.t0) * K * sizeof(T);   // the tile's run of logits
     if (tid < t.n) {
         const int i = t.t0 + tid;
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(TQ) void qk1d_kernel(const T *__restrict__ x, const
             orow[a] = from_f32<T>(__builtin_fmaf(scale, dot32(xv, kv), bb[a]));
         }
     }
-    __syncthreads();
+    workgroup_sync();
     run_out<T, TQ>(reinterpret_cast<char *>(out), g0, t.n * K * (int)sizeof(T), rows, tid);
 }
 
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(TQ) void av1d_kernel(const T *__restrict__ w, const
     load_vectors<T, TQ>(reinterpret_cast<const char *>(y) + ((size_t)t.plane * L + h0) * KBYTES, h1 - h0, halo, tid);
     const size_t g0 = ((size_t)t.plane * L + t.t0) * K * sizeof(T);
     run_in<T, TQ>(reinterpret_cast<const char *>(w), g0, t.n * K * (int)sizeof(T), rows, tid);
-    __syncthreads();
+    workgroup_sync();
     float acc[kHeadDim];
 #pragma unroll
     for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
@@ -226,7 +226,7 @@ __global__ __launch_bounds__(TQ) void inverse1d_kernel(const T *__restrict__ w, 
     load_vectors<T, TQ>(reinterpret_cast<const char *>(x) + ((size_t)t.plane * L + i0) * KBYTES, i1 - i0 + 1, halo, tid);
     const size_t g0 = ((size_t)t.plane * L + i0) * K * sizeof(T);
     run_in<T, TQ>(reinterpret_cast<const char *>(w), g0, (i1 - i0 + 1) * K * (int)sizeof(T), rows, tid);
-    __syncthreads();
+    workgroup_sync();
     float acc[kHeadDim];
 #pragma unroll
     for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(TQ) void softmax1d_kernel(const T *__restrict__ log
     const size_t g0 = ((size_t)t.plane * L + t.t0) * K * sizeof(T);
     const int nbytes = t.n * K * (int)sizeof(T);
     run_in<T, TQ>(reinterpret_cast<const char *>(logits), g0, nbytes, lds, tid);
-    __syncthreads();
+    workgroup_sync();
     if (tid < t.n) {
         T *row = reinterpret_cast<T *>(lds + (int)(g0 & 15)) + tid * K;
         constexpr float kLog2e = 1.4426950408889634f;
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(TQ) void softmax1d_kernel(const T *__restrict__ log
         const float inv = 1.0f / sum;
         for (int a = 0; a < K; ++a) row[a] = from_f32<T>(__builtin_amdgcn_exp2f((to_f32(row[a]) - m) * kLog2e) * inv);
     }
-    __syncthreads();
+    workgroup_sync();
     run_out<T, TQ>(reinterpret_cast<char *>(out), g0, nbytes, lds, tid);
 }
 
@@ -283,7 +283,7 @@ __global__ __launch_bounds__(TQ) void softmax_bwd1d_kernel(const T *__restrict__
     const int nbytes = t.n * K * (int)sizeof(T);
     run_in<T, TQ>(reinterpret_cast<const char *>(attn), g0, nbytes, pa, tid);
     run_in<T, TQ>(reinterpret_cast<const char *>(dp), g0, nbytes, pd, tid);
-    __syncthreads();
+    workgroup_sync();
     if (tid < t.n) {
         const T *prow = reinterpret_cast<const T *>(pa + (int)(g0 & 15)) + tid * K;
         T *drow = reinterpret_cast<T *>(pd + (int)(g0 & 15)) + tid * K;
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(TQ) void softmax_bwd1d_kernel(const T *__restrict__
         for (int a = 0; a < K; ++a) dot = __builtin_fmaf(to_f32(prow[a]), to_f32(drow[a]), dot);
         for (int a = 0; a < K; ++a) drow[a] = from_f32<T>(to_f32(prow[a]) * (to_f32(drow[a]) - dot));
     }
-    __syncthreads();
+    workgroup_sync();
     run_out<T, TQ>(reinterpret_cast<char *>(ds), g0, nbytes, pd, tid);
 }
 
@@ -320,7 +320,7 @@ __global__ __launch_bounds__(TQ) void fused1d_kernel(const T *__restrict__ q, co
     constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
     for (int i = tid; i < 2 * K - 1; i += TQ)
         bias[i] = rpb ? to_f32(rpb[(size_t)(t.plane % heads) * (2 * K - 1) + i]) * kLog2e : 0.f;
-    __syncthreads();
+    workgroup_sync();
     float acc[kHeadDim];
 #pragma unroll
     for (int d = 0; d < kHeadDim; ++d) acc[d] = 0.f;
@@ -387,7 +387,7 @@ __global__ __launch_bounds__(TQ) void rpb_partial1d_kernel(const T *__restrict__
     const size_t g0 = ((size_t)t.plane * L + t.t0) * K * sizeof(T);
     run_in<T, TQ>(reinterpret_cast<const char *>(ds), g0, t.n * K * (int)sizeof(T), lds, tid);
     for (int i = tid; i < NB; i += TQ) tbl[i] = 0ull;
-    __syncthreads();
+    workgroup_sync();
     const bool live = tid < t.n;
     const int i = t.t0 + tid;
     const int cell0 = live ? win_start(i, L, K) - i + K - 1 : R;
@@ -403,7 +403,7 @@ __global__ __launch_bounds__(TQ) void rpb_partial1d_kernel(const T *__restrict__
         if (live && !centred)
             __hip_atomic_fetch_add(tbl + cell0 + a, (unsigned long long)fx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
-    __syncthreads();
+    workgroup_sync();
     for (int u = tid; u < NB; u += TQ) partial[(size_t)blockIdx.x * NB + u] = (long long)tbl[u];
 }
 
@@ -428,7 +428,7 @@ __global__ __launch_bounds__(kFinalThreads) void rpb_final1d_kernel(const long l
 #pragma unroll
     for (int sh = 1; sh < kWave; sh <<= 1) sum += __shfl_xor(sum, sh, kWave);
     if ((threadIdx.x & (kWave - 1)) == 0) wave_sum[threadIdx.x / kWave] = sum;
-    __syncthreads();
+    workgroup_sync();
     if (threadIdx.x == 0) {
         long long tot = 0;
         for (int w = 0; w < kFinalThreads / kWave; ++w) tot += wave_sum[w];
@@ -477,7 +477,7 @@ __global__ __launch_bounds__(TQ) void fbwd1d_q_kernel(const T *__restrict__ q, c
         bias[i] = rpb ? to_f32(rpb[(size_t)(t.plane % heads) * NB + i]) * kLog2eF : 0.f;
         tbl[i] = 0ull;
     }
-    __syncthreads();
+    workgroup_sync();
     const bool live = tid < t.n;
     const int i = t.t0 + (live ? tid : 0);
     const size_t qi = (size_t)t.plane * L + i;
@@ -558,7 +558,7 @@ __global__ __launch_bounds__(TQ) void fbwd1d_kv_kernel(const T *__restrict__ q, 
         delta_s[u] = delta[ioff + u];
     }
     for (int u = tid; u < NB; u += TQ) bias[u] = rpb ? to_f32(rpb[(size_t)(t.plane % heads) * NB + u]) * kLog2eF : 0.f;
-    __syncthreads();
+    workgroup_sync();
     const bool live = tid < t.n;
     const int j = t.t0 + (live ? tid : 0);
     const size_t kj = (size_t)t.plane * L + j;

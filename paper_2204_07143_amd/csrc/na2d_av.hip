@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kTileX *TY) void av_kernel(const T *__restrict__ w,
                                                                 nvalid * C::KK * (int)sizeof(T), rows + r * C::kRowRegion, lane);
         }
     }
-    __syncthreads();
+    workgroup_sync();
 
     const int lx = tid % kTileX, ly = tid / kTileX;
     const int qy = ty0 + ly, qx = tx0 + lx;

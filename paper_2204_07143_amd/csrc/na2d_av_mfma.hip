@@ -277,7 +277,7 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
     auto step = [&](auto par_c) {
         constexpr int PAR = decltype(par_c)::value;
         wait_global_loads();   // this tile's halo and weight rows have landed
-        __syncthreads();       // ... for every wave, and nobody still reads the other stage
+        workgroup_sync();       // ... for every wave, and nobody still reads the other stage
         if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
         if (phase_varies) {   // the table follows the phase of this plane's row run (in-window entries only)
             const int ph = phase_of(b), d = ph - cur_phase;
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
     if constexpr (RPB) {
         // interior sums into the wave's table, then the eight tables are added in wave order
         if (wrow < H && lane < C::KK && xi1 > xi0) *lds_ptr<float>(rtbl + ((rpy * NB + P::R) + slot_cell) * 4) += racc;
-        __syncthreads();
+        workgroup_sync();
         for (int cell = tid; cell < CELLS; cell += C::kThreads) {
             float sum = *lds_ptr<float>(lds0 + C::kLdsStages + cell * 4);
 #pragma unroll

@@ -212,7 +212,7 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
     auto step = [&](auto par_c) {
         constexpr int PAR = decltype(par_c)::value;
         wait_global_loads();   // this plane's halo, row runs and dout chunk have landed
-        __syncthreads();       // ... for every wave; the previous plane's ds row runs are complete
+        workgroup_sync();       // ... for every wave; the previous plane's ds row runs are complete
         if (b > b_begin) {
             flush(b - 1, PAR ^ 1);
             // this wave's run is flushed (its LDS reads have returned) before its next load may land there
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
         step(IntC<0>{});
         if (b < b_end) step(IntC<1>{});
     }
-    __syncthreads();
+    workgroup_sync();
     flush(b_end - 1, (b_end - b_begin - 1) & 1);
 }
 

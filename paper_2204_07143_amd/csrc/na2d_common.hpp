@@ -194,6 +194,18 @@ __device__ __forceinline__ __attribute__((address_space(3))) T *lds_ptr(int addr
     return (__attribute__((address_space(3))) T *)(uintptr_t)(unsigned)addr;
 }
 
+// ---- workgroup barrier -----------------------------------------------------------------------
+// A workgroup barrier that orders LDS accesses across it.  __syncthreads() is a release fence, s_barrier
+// and an acquire fence; the wait for the wave's outstanding LDS accesses that the release fence stands for
+// is inserted by the compiler, and at the header of a loop whose back edge ends in LDS stores the compiler
+// has left it out (seen in the generated code of the fused grad-a / softmax-backward kernel: the wave passed
+// the barrier with its last stores still in flight and, once in a few million elements, another wave read
+// the old contents).  The wait is therefore written out in front of every barrier of this library.
+__device__ __forceinline__ void workgroup_sync() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();
+}
+
 // ---- alignment-preserving staging between global memory and LDS -------------------------
 //
 // A run of `nbytes` bytes starting at global byte offset g0 of `gbase` (gbase 16-byte

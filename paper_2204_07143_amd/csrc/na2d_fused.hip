@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kTileX *TY) void fused_fwd_kernel(const T *__restri
         for (int i = tid; i < C::NB * C::NB; i += C::kThreads)
             bias[i] = rpb ? to_f32(rpb[(size_t)head * C::NB * C::NB + i]) : 0.f;
     }
-    __syncthreads();
+    workgroup_sync();
 
     const int lx = tid % kTileX, ly = tid / kTileX;
     const int qy = ty0 + ly, qx = tx0 + lx;

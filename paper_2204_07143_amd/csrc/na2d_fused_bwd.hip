@@ -311,7 +311,7 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
     auto step = [&](auto par_c) {
         constexpr int PAR = decltype(par_c)::value;
         wait_global_loads();   // this tile's halos and the lane's query data have landed
-        __syncthreads();       // ... for every wave, and nobody still reads the other buffer pair
+        workgroup_sync();       // ... for every wave, and nobody still reads the other buffer pair
         const u32x4 qreg = qnext, dreg = dnext;
         const float lse2 = lnext * kLog2e;
         if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
 
     if constexpr (RPB) {
         // the tables added up (integers: any order), then to fp32: one partial bias gradient per workgroup
-        __syncthreads();
+        workgroup_sync();
         for (int cell = tid; cell < C::CELLS; cell += C::kThreads) {
             long long sum = 0;
 #pragma unroll
@@ -497,11 +497,11 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
     const int cbase = bias0 + shift * C::kBiasCopy + (vm0 + 3 + shift) * 2;   // 8-byte aligned
 
     const size_t plane_px = (size_t)H * W;
-    __syncthreads();
+    workgroup_sync();
 
     for (int b = b_begin; b < b_end; ++b) {
         const size_t plane = (size_t)b * heads + head;
-        if (b > b_begin) __syncthreads();   // the previous plane's images are no longer read
+        if (b > b_begin) workgroup_sync();   // the previous plane's images are no longer read
         XHalo::issue_at(reinterpret_cast<const char *>(q) + plane * plane_px * KB, xoff, q0, wave);
         XHalo::issue_at(reinterpret_cast<const char *>(dout) + plane * plane_px * KB, xoff, d0, wave);
         if (wave < C::kSItems) {
@@ -513,7 +513,7 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
         const u32x4 kreg = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(k) + koff);
         const u32x4 vreg = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(v) + koff);
         wait_global_loads();
-        __syncthreads();
+        workgroup_sync();
         if (!active) continue;
 
         f32x4 ak[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};   // dk^T, dv^T: channels 8g + 4 hf + r of the lane's key

@@ -254,7 +254,7 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
     auto step = [&](auto par_c) {
         constexpr int PAR = decltype(par_c)::value;
         wait_global_loads();   // this tile's halos and query chunk have landed
-        __syncthreads();       // ... for every wave, and nobody still reads the other buffer pair
+        workgroup_sync();       // ... for every wave, and nobody still reads the other buffer pair
         u32x4 qreg[NS];
 #pragma unroll
         for (int sl = 0; sl < NS; ++sl) qreg[sl] = qnext[sl];

@@ -31,7 +31,7 @@ __global__ __launch_bounds__(kTileX *TY) void inverse_kernel(const T *__restrict
     const char *xplane = reinterpret_cast<const char *>(x) + plane_q * KBYTES;
 
     load_halo<T, C::RECT_H, C::RECT_W, C::kThreads, false, D>(xplane, H, W, ry0, rx0, lds, tid);
-    __syncthreads();
+    workgroup_sync();
 
     const int lx = tid % kTileX, ly = tid / kTileX;
     const int jy = ty0 + ly, jx = tx0 + lx;

@@ -140,14 +140,14 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
         xpatch[p] = ((oqy - ry0) * C::RW + (oqx - rx0)) * Traits<T>::kKeyBytes;
     }
     int mis_tables = -1;   // weight-row phase the tables in LDS were built for
-    __syncthreads();
+    workgroup_sync();
 
     for (int b = b_begin; b < b_end; ++b) {
         const size_t plane_q = ((size_t)b * heads + head) * H * W;
         const size_t g0first = (plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ;   // first byte of the first weight row
         const int mis0 = (int)(g0first & 15);   // 16-byte phase of row r: (mis0 + r * pitch_phase) & 15
 
-        if (b > b_begin) __syncthreads();   // the previous tile's LDS images are no longer read
+        if (b > b_begin) workgroup_sync();   // the previous tile's LDS images are no longer read
         // Stage the rectangle.  Weight rows go from global memory straight into LDS (no registers): a
         // row is mirrored at its 16-byte phase, one 16-byte chunk per lane, 64 chunks per instruction;
         // the chunks at the two ends also bring in bytes of the neighbouring rows, which nothing reads.
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
             mis_tables = mis0;
         }
         wait_global_loads();
-        __syncthreads();
+        workgroup_sync();
         if (rebuild) {
 #pragma unroll
             for (int bb = 0; bb < C::NBLK; ++bb) rowterm[bb] = *lds_ptr<int>(tbl_row + ((strip * C::NBLK + bb) * 4 + ky) * 4);

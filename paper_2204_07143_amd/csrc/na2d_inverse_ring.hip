@@ -146,7 +146,7 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
     const int jx = px0 + kx;
     const int wphase0 = (int)(wbase & 15), pitch_phase = row_pitch_bytes & 15;   // phase of row iy: (wphase0 + iy * pitch_phase) & 15
 
-    __syncthreads();   // the zero fill is done
+    workgroup_sync();   // the zero fill is done
     // column terms: the same for every tile of the column
     for (int e = tid; e < C::kColEntries; e += C::kThreads) {
         const int r = e & 3, kxe = (e >> 2) & 3, ge = (e >> 4) & 3, pe = e >> 6;
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
         load_rows(inv_first(ty0, H, K), inv_last(ty1, H, K) + 1);
     }
     wait_global_loads();
-    __syncthreads();
+    workgroup_sync();
     int colterm[4];
     {
         const u32x4 ct = *lds_ptr<u32x4>(tbl_col + ((p * 4 + g) * 4 + kx) * 16);
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
                 term = w0 + (iy % C::NR) * C::kRowRegion + ((wphase0 + iy * pitch_phase) & 15) + a * K * SZ;
             *lds_ptr<int>(tbl_row + e * 4) = term;
         }
-        __syncthreads();
+        workgroup_sync();
 
         const int sy0 = ty0 + 4 * strip;   // first key row of this wave's strip
         if (sy0 < H && px0 < W) {
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
             }
         }
         wait_global_loads();   // the next tile's rows have landed
-        __syncthreads();       // ... for every wave; this tile's rows and row terms are no longer read
+        workgroup_sync();       // ... for every wave; this tile's rows and row terms are no longer read
     }
 }
 

@@ -222,12 +222,12 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
         }
     };
 
-    __syncthreads();   // the zero fill is done before the first loads land
+    workgroup_sync();   // the zero fill is done before the first loads land
     issue(b_begin, 0, 0);
     int b = b_begin, pr = 0, par = 0;
     while (b < b_end) {
         wait_global_loads();   // this step's rows have landed
-        __syncthreads();       // ... for every wave, and nobody still reads the other stage
+        workgroup_sync();       // ... for every wave, and nobody still reads the other stage
         int nb_ = b, npr = pr + 1;
         if (npr == npairs) {
             npr = 0;

@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kTileX *TY) void qk_kernel(const T *__restrict__ x,
         for (int i = tid; i < C::NB * C::NB; i += C::kThreads)
             bias[i] = rpb ? to_f32(rpb[(size_t)head * C::NB * C::NB + i]) : 0.f;
     }
-    __syncthreads();
+    workgroup_sync();
 
     const int lx = tid % kTileX, ly = tid / kTileX;
     const int qy = ty0 + ly, qx = tx0 + lx;
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kTileX *TY) void qk_kernel(const T *__restrict__ x,
             }
         }
     }
-    __syncthreads();
+    workgroup_sync();
 
     // Each wave streams out whole tile rows: one row's logits are contiguous in global memory.
     const int wave = tid / kWave, lane = tid % kWave;

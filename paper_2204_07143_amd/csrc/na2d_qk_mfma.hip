@@ -272,7 +272,7 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
     auto step = [&](auto par_c) {
         constexpr int PAR = decltype(par_c)::value;
         wait_global_loads();   // this tile's halo and query chunk have landed
-        __syncthreads();       // ... for every wave; the previous tile is fully staged, its halo no longer read
+        workgroup_sync();       // ... for every wave; the previous tile is fully staged, its halo no longer read
         u32x4 qreg[NS];
 #pragma unroll
         for (int sl = 0; sl < NS; ++sl) qreg[sl] = qnext[sl];
@@ -285,7 +285,7 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
         step(IntC<0>{});
         if (b < b_end) step(IntC<1>{});
     }
-    __syncthreads();
+    workgroup_sync();
     flush(b_end - 1, (b_end - b_begin - 1) & 1);
 }
 

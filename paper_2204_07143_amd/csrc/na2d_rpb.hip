@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void rpb_partial_kernel(const T *__restrict__ 
         const int slot = lane + s * kWave;
         if (slot < C::KK) mine[R * C::NB + R + cell_off[s]] += acc_int[s];
     }
-    __syncthreads();
+    workgroup_sync();
     for (int i = tid; i < C::CELLS; i += 256) {
         float s = tables[i];
 #pragma unroll
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const 
     const int n = B * groups;
     float acc = 0.f;
     if (cell < cells) {
-        constexpr int U = 16;   // loads in flight per lane; past the end they are skipped (adding 0 changes nothing)
+        constexpr int U = 32;   // loads in flight per lane (512 partials per round); past the end they are skipped (adding 0 changes nothing)
         for (int i = wave; i < n; i += U * kRpbFinalWaves) {
             float v[U];
 #pragma unroll
@@ -189,7 +189,7 @@ __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const 
         }
     }
     sub[wave][lane] = acc;
-    __syncthreads();
+    workgroup_sync();
     if (wave == 0 && cell < cells) {
         float s = sub[0][lane];
         for (int w = 1; w < kRpbFinalWaves; ++w) s += sub[w][lane];
@@ -226,7 +226,7 @@ __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_av_kernel(con
         }
     }
     sub[wave][lane] = acc;
-    __syncthreads();
+    workgroup_sync();
     if (wave == 0 && cell < cells) {
         float s = sub[0][lane];
         for (int w = 1; w < kRpbFinalWaves; ++w) s += sub[w][lane];

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(const T *in, T *out, size_
     const size_t g0 = row0 * C::KK * sizeof(T);
     const int nbytes = rows * C::KK * (int)sizeof(T);
     stage_in<T, C::kRows * C::KK * (int)sizeof(T), C::kThreads>(reinterpret_cast<const char *>(in), g0, nbytes, lds, tid);
-    __syncthreads();
+    workgroup_sync();
     T *tile = reinterpret_cast<T *>(lds + (int)(g0 & 15));
     const int sub = tid % S::G;
     for (int r = tid / S::G; r < rows; r += C::kThreads / S::G) {
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(const T *in, T *out, size_
             if (idx < C::KK) row[idx] = from_f32<T>(v[e] * inv);
         }
     }
-    __syncthreads();
+    workgroup_sync();
     stage_out<T, C::kRows * C::KK * (int)sizeof(T), C::kThreads>(reinterpret_cast<char *>(out), g0, nbytes, lds, tid);
 }
 
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(const T *attn, const T
         sp.commit(reg_p, tid);
         sg.commit(reg_g, tid);
     }
-    __syncthreads();
+    workgroup_sync();
     const T *tp = reinterpret_cast<const T *>(reg_p + (int)(g0 & 15));
     T *tg = reinterpret_cast<T *>(reg_g + (int)(g0 & 15));
     const int sub = tid % S::G;
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(const T *attn, const T
             if (idx < C::KK) grow[idx] = from_f32<T>(pv[e] * (gv[e] - inner));
         }
     }
-    __syncthreads();
+    workgroup_sync();
     stage_out<T, C::kRows * C::KK * (int)sizeof(T), C::kThreads>(reinterpret_cast<char *>(ds), g0, nbytes, reg_g, tid);
 }
 
