@@ -14,7 +14,7 @@ static int validate(const na2d_problem *p) {
     if (p->dtype != NA2D_F32 && p->dtype != NA2D_F16 && p->dtype != NA2D_BF16) return NA2D_ERR_DTYPE;
     if (p->B <= 0 || p->heads <= 0 || p->H <= 0 || p->W <= 0 || p->D <= 0 || p->k <= 0) return NA2D_ERR_SHAPE;
     const int k = p->k;
-    if ((k & 1) == 0 || k < 3 || k > 13) return NA2D_ERR_KERNEL_SIZE;
+    if ((k & 1) == 0 || k < 3 || k > kMaxGenericK) return NA2D_ERR_KERNEL_SIZE;
     if (k > p->H || k > p->W) return NA2D_ERR_TOO_SMALL;
     if (!head_dim_supported(p->dtype, k, p->D)) return NA2D_ERR_HEAD_DIM;
     // Index arithmetic inside the kernels is 64-bit for byte offsets, but element counts of a
@@ -52,6 +52,7 @@ __global__ void indices_kernel(int32_t *key_index, int32_t *rpb_index, int H, in
 }
 
 hipError_t launch_indices(const Problem &p, int32_t *key_index, int32_t *rpb_index, hipStream_t s) {
+    if (generic_window(p)) return launch_indices_generic(p, key_index, rpb_index, s);
     const int n = p.H * p.W * p.K * p.K;
     NA2D_DISPATCH_K(p.K, hipLaunchKernelGGL((indices_kernel<float, K>), dim3((n + 255) / 256), dim3(256), 0, s,
                                             key_index, rpb_index, p.H, p.W));
@@ -279,7 +280,7 @@ int na2d_debug_indices(const na2d_problem *p, int32_t *key_index, int32_t *rpb_i
 
 int na2d_host_axis_tables(int32_t L, int32_t k, int32_t *start, int32_t *qs, int32_t *qe) {
     if (L <= 0) return NA2D_ERR_SHAPE;
-    if ((k & 1) == 0 || k < 3 || k > 13) return NA2D_ERR_KERNEL_SIZE;
+    if ((k & 1) == 0 || k < 3 || k > kMaxGenericK) return NA2D_ERR_KERNEL_SIZE;
     if (k > L) return NA2D_ERR_TOO_SMALL;
     for (int i = 0; i < L; ++i) {
         if (start) start[i] = win_start(i, L, k);
@@ -294,7 +295,7 @@ const char *na2d_strerror(int status) {
         case NA2D_OK: return "ok";
         case NA2D_ERR_NULL: return "a required pointer is NULL";
         case NA2D_ERR_DTYPE: return "unknown dtype";
-        case NA2D_ERR_KERNEL_SIZE: return "kernel size must be odd and one of 3, 5, 7, 9, 11, 13";
+        case NA2D_ERR_KERNEL_SIZE: return "kernel size must be odd and between 3 and 63";
         case NA2D_ERR_TOO_SMALL: return "kernel size exceeds the feature map (k > min(H, W))";
         case NA2D_ERR_HEAD_DIM: return "head dim must be 16, 32, 64 or 128 (and small enough for the kernel size: see na2d.h)";
         case NA2D_ERR_SHAPE: return "non-positive extent or tensor too large";

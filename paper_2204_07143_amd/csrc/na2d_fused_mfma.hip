@@ -296,7 +296,7 @@ static hipError_t launch_fused_mfma_small_t(const Problem &p, const void *q, con
 }
 
 bool fused_mfma_supported(const Problem &p) {
-    if (p.dtype == NA2D_F32) return false;
+    if (p.dtype == NA2D_F32 || p.K > kMaxTunedK) return false;
     return p.D == kHeadDim || (p.D == 2 * kHeadDim && p.K <= 7);   // two slices only in the small-window kernel
 }
 

@@ -18,6 +18,21 @@ struct Problem {
     int elem_bytes() const { return dtype == NA2D_F32 ? 4 : 2; }
 };
 
+// Window sides: 3..13 (odd) run the tuned kernels, 15..63 (odd) the run-time-K kernels of na2d_generic.hip.
+constexpr int kMaxTunedK = 13, kMaxGenericK = 63;
+bool generic_window(const Problem &p);
+hipError_t launch_qk_generic(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
+                             hipStream_t s);
+hipError_t launch_av_generic(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);
+hipError_t launch_inverse_generic(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s);
+hipError_t launch_softmax_generic(const Problem &p, const void *in, void *out, hipStream_t s);
+hipError_t launch_softmax_bwd_generic(const Problem &p, const void *attn, const void *dp, void *ds, hipStream_t s);
+hipError_t launch_fused_generic(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
+                                void *out, float *lse, hipStream_t s);
+size_t rpb_generic_workspace_bytes(const Problem &p);
+hipError_t launch_rpb_generic(const Problem &p, const void *ds, float *d_rpb, void *workspace, hipStream_t s);
+hipError_t launch_indices_generic(const Problem &p, int32_t *key_index, int32_t *rpb_index, hipStream_t s);
+
 // logits = scale * <x, y_window> + bias   (QK+RPB, and grad-a with x = dout, y = v, no bias)
 hipError_t launch_qk(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
                      hipStream_t s);

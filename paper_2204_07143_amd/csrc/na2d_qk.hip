@@ -101,6 +101,7 @@ static hipError_t launch_qk_t(const Problem &p, const void *x, const void *y, co
 }
 
 bool head_dim_supported(int dtype, int K, int D) {
+    if (K > kMaxTunedK) return D == 16 || D == 32 || D == 64 || D == 128;   // the run-time-K kernels stage nothing in LDS
     auto probe = [&]() -> hipError_t {
         NA2D_DISPATCH_T(dtype, NA2D_DISPATCH_K(K, NA2D_DISPATCH_D(D, return (valu_fits<T, K, D>() ? hipSuccess : hipErrorInvalidValue))));
         return hipErrorInvalidValue;
@@ -110,6 +111,7 @@ bool head_dim_supported(int dtype, int K, int D) {
 
 hipError_t launch_qk(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
                      hipStream_t s) {
+    if (generic_window(p)) return launch_qk_generic(p, x, y, rpb, scale, logits, s);
     if (qk_mfma_supported(p)) return launch_qk_mfma(p, x, y, rpb, scale, logits, s);
     NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, NA2D_DISPATCH_D(p.D, return (launch_qk_t<T, K, D>(p, x, y, rpb, scale, logits, s)))));
     return hipErrorInvalidValue;

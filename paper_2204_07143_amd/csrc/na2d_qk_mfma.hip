@@ -316,7 +316,7 @@ static hipError_t launch_qk_mfma_small_t(const Problem &p, const void *x, const 
 }
 
 bool qk_mfma_supported(const Problem &p) {
-    if (p.dtype == NA2D_F32) return false;
+    if (p.dtype == NA2D_F32 || p.K > kMaxTunedK) return false;
     return p.D == kHeadDim || (p.D == 2 * kHeadDim && p.K <= 7);   // two slices only in the small-window kernel
 }
 

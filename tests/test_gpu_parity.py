@@ -172,6 +172,14 @@ def test_small_ragged_all_elements(oracle, k, dtype):
     run_all(oracle, p, seed=100 + k)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("H,W,k,D", [(23, 30, 15, 32), (25, 22, 21, 32), (15, 15, 15, 32), (24, 27, 15, 64), (21, 33, 21, 16)])
+def test_window_sides_beyond_the_tuned_ones(oracle, H, W, k, D, dtype):
+    # k >= 15 runs the kernels that take the window side at run time: every stage, the fused forward, the composed
+    # backward and na2d_fused_bwd (which recomputes the weights and runs the unfused steps there), every element
+    run_all(oracle, synth.Problem(2, 2, H, W, D, k, dtype), seed=1500 + k + D)
+
+
 def test_config1_tiny_fp32(oracle):
     run_all(oracle, synth.CONFIGS["tiny"], seed=1001)
 
@@ -281,7 +289,7 @@ def test_softmax_in_place_and_ds_in_place(oracle):
 # ---- neighbourhood indices: bit-exact ------------------------------------------------------
 
 @pytest.mark.parametrize("H,W,k", [(14, 14, 3), (56, 56, 7), (28, 28, 7), (7, 7, 7), (200, 334, 7), (128, 128, 7),
-                                   (56, 56, 13), (13, 29, 13), (9, 5, 5)])
+                                   (56, 56, 13), (13, 29, 13), (9, 5, 5), (23, 30, 15), (40, 33, 21), (63, 70, 63)])
 def test_indices_bit_exact(oracle, H, W, k):
     ki = torch.empty((H, W, k * k), dtype=torch.int32, device="cuda")
     ri = torch.empty_like(ki)

@@ -43,7 +43,9 @@ def P(B=1, heads=1, H=14, W=14, D=32, k=3, dtype=0):
     (P(), 0),
     (P(k=7, H=7, W=7), 0),
     (P(dtype=3), -2),
-    (P(k=4), -3), (P(k=1), -3), (P(k=15, H=20, W=20), -3),
+    (P(k=4), -3), (P(k=1), -3), (P(k=65, H=80, W=80), -3), (P(k=16, H=20, W=20), -3),
+    # window sides beyond the tuned ones take the run-time-k kernels: every dtype, every head dim
+    (P(k=15, H=20, W=20), 0), (P(k=63, H=63, W=70, D=128, dtype=0), 0), (P(k=21, H=20, W=30), -4), (P(k=21, H=30, W=30, D=48), -5),
     (P(k=7, H=6), -4), (P(k=7, W=5), -4),
     (P(D=64), 0), (P(D=16, k=13, H=20, W=20), 0), (P(D=128, k=9, H=20, W=20, dtype=1), 0),
     (P(D=48), -5), (P(D=8), -5), (P(D=128, k=5, H=20, W=20, dtype=0), -5), (P(D=64, k=11, H=20, W=20, dtype=0), -5),

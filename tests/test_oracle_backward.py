@@ -31,7 +31,8 @@ def test_bias_cell_counts_examples():
     assert bias_cell_counts(14, 3).tolist() == [1, 13, 14, 13, 1]
 
 
-@pytest.mark.parametrize("B,heads,H,W,k", [(3, 2, 9, 12, 5), (2, 1, 7, 7, 7), (1, 2, 14, 14, 3), (1, 1, 13, 20, 13)])
+@pytest.mark.parametrize("B,heads,H,W,k", [(3, 2, 9, 12, 5), (2, 1, 7, 7, 7), (1, 2, 14, 14, 3), (1, 1, 13, 20, 13), (2, 1, 18, 25, 15),
+                                           (1, 2, 21, 24, 21)])
 def test_bias_gradient_closed_form_for_constant_ds(oracle, B, heads, H, W, k):
     ds = np.ones((B, heads, H, W, k * k))
     want = B * np.outer(bias_cell_counts(H, k), bias_cell_counts(W, k))
@@ -83,7 +84,7 @@ def test_gradients_by_central_finite_differences(oracle, H, W, k):
         np.testing.assert_allclose(grad, num, rtol=2e-6, atol=2e-8, err_msg=name)
 
 
-@pytest.mark.parametrize("B,heads,H,W,D,k", [(2, 2, 9, 11, 8, 5), (1, 2, 10, 8, 4, 7), (1, 1, 14, 14, 32, 3)])
+@pytest.mark.parametrize("B,heads,H,W,D,k", [(2, 2, 9, 11, 8, 5), (1, 2, 10, 8, 4, 7), (1, 1, 14, 14, 32, 3), (1, 1, 16, 17, 4, 15)])
 def test_gradients_match_autograd_of_gather_matmul(oracle, B, heads, H, W, D, k):
     g = rng(40 + k)
     q, key, v, dout = (g.standard_normal((B, heads, H, W, D)) for _ in range(4))

@@ -94,7 +94,8 @@ def gather_matmul_reference(q, key, v, rpb, scale, k):
     return logits.reshape(B, heads, H, W, k * k), p.reshape(B, heads, H, W, k * k), out
 
 
-@pytest.mark.parametrize("B,heads,H,W,D,k", [(1, 1, 14, 14, 32, 3), (2, 2, 9, 11, 8, 5), (1, 2, 10, 8, 4, 7), (1, 1, 15, 13, 4, 13)])
+@pytest.mark.parametrize("B,heads,H,W,D,k", [(1, 1, 14, 14, 32, 3), (2, 2, 9, 11, 8, 5), (1, 2, 10, 8, 4, 7), (1, 1, 15, 13, 4, 13),
+                                               (1, 2, 17, 19, 4, 15), (1, 1, 23, 21, 4, 21)])
 def test_stages_match_gather_matmul_formulation(oracle, B, heads, H, W, D, k):
     g = rng(100 + H + k)
     q, key, v = (g.standard_normal((B, heads, H, W, D)) for _ in range(3))
