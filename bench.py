@@ -350,6 +350,9 @@ def main() -> int:
                          "per-kernel averages of a profiler then mix shapes)")
     ap.add_argument("--only", default=None,
                     help="comma-separated entry points (of the `kernels` table) to launch, nothing else: for counter runs")
+    ap.add_argument("--lib", default=None,
+                    help="time another build of the library (the memory-only measurement build of "
+                         "`python -m paper_2204_07143_amd.build --probe`); its results are not the method's")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch plain device copies of known size (calibration of rocprofv3's HBM counters)")
     args = ap.parse_args()
@@ -361,7 +364,7 @@ def main() -> int:
     from paper_2204_07143_amd import binding as na
     from paper_2204_07143_amd import synth
 
-    na.load()  # raises if the HIP library is missing: there is no fallback
+    na.load(args.lib)  # raises if the HIP library is missing: there is no fallback
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     base = synth.CONFIGS[args.workload]
@@ -508,7 +511,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": p.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload} (B={p.B}, heads={p.heads}, {p.H}x{p.W}, D={p.D}, k={p.k}, {p.dtype}): "
                                "the ten scoped calls (unfused fwd, fused fwd, six backward steps), one call each",
-                   "buffer_sets": args.sets, "timing": timer.mode},
+                   "buffer_sets": args.sets, "timing": timer.mode,
+                   **({"library": os.path.relpath(args.lib, ROOT) + " (measurement build: not the method's results)"} if args.lib else {})},
         "step_MB": round(step_bytes / 1e6, 1), "us_per_step_python_issued": round(us_step_eager, 1),
         "copy_ceiling_GBps": round(copy_ceiling, 1),
         "us_per_call": {"unfused_fwd": round(unfused_fwd, 1), "fused_fwd": kernels["fused_fwd"]["us"],

@@ -41,10 +41,9 @@
  *    D in {16, 32, 64, 128}.  D = 32 (every NAT variant, Section 3.2) runs the matrix-core
  *    kernels in the 16-bit types; so do the weighted sums (av, grad-q, grad-v, grad-k) for
  *    D = 64 and 128, and the logits, grad-a and the fused forward for D = 64 with k <= 7; the
- *    rest runs plain-ALU kernels.  Accepted are the combinations whose plain-ALU
- *    tiles fit the 160 KB LDS: every k for D = 16 and for D = 64 in the 16-bit types, k <= 9
- *    for D = 128 in the 16-bit types and for D = 64 in fp32, k = 3 for D = 128 in fp32
- *    (anything else: NA2D_ERR_HEAD_DIM); for k >= 15 every dtype takes all four head dims.
+ *    rest runs tiled plain-ALU kernels while their tiles fit the 160 KB LDS (every k for D = 16
+ *    and for D = 64 in the 16-bit types, k <= 9 for D = 128 in the 16-bit types and for D = 64
+ *    in fp32, k = 3 for D = 128 in fp32) and the run-time-k kernels otherwise.
  *  - Return value: NA2D_OK (0) or a negative na2d_status.  All argument errors are
  *    detected on the host before any HIP call; on error nothing is enqueued.
  */
@@ -66,7 +65,7 @@ typedef enum {
     NA2D_ERR_DTYPE = -2,       /* dtype is not one of na2d_dtype */
     NA2D_ERR_KERNEL_SIZE = -3, /* k even, below 3 or above 63 */
     NA2D_ERR_TOO_SMALL = -4,   /* k > min(H, W): the neighbourhood is undefined */
-    NA2D_ERR_HEAD_DIM = -5,    /* D not in {16, 32, 64, 128}, or too large for this k and dtype (see above) */
+    NA2D_ERR_HEAD_DIM = -5,    /* D not in {16, 32, 64, 128} */
     NA2D_ERR_SHAPE = -6,       /* non-positive extent, a tensor beyond 2^31-1 elements, or one (batch, head)
                                   plane of a tensor beyond 2^31-1 bytes */
     NA2D_ERR_ALIGN = -7,       /* a data pointer is not 16-byte aligned */

@@ -52,15 +52,17 @@ class Na1dProblem(ctypes.Structure):
 _lib = None
 
 
-def load() -> ctypes.CDLL:
-    """Load libna2d.so (once). Raises if it has not been built."""
+def load(path: str | None = None) -> ctypes.CDLL:
+    """Load libna2d.so (once). Raises if it has not been built.  ``path`` (first call only) names another build of
+    the same library, e.g. the benchmark's memory-only measurement build."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
+        lib_path = LIB_PATH if path is None else path
+        if not os.path.exists(lib_path):
             raise FileNotFoundError(
-                f"{LIB_PATH} is missing: build it with `python -m paper_2204_07143_amd.build` "
+                f"{lib_path} is missing: build it with `python -m paper_2204_07143_amd.build` "
                 "(there is no CPU or PyTorch fallback)")
-        lib = ctypes.CDLL(LIB_PATH)
+        lib = ctypes.CDLL(lib_path)
         vp, pp, f = ctypes.c_void_p, ctypes.POINTER(Na2dProblem), ctypes.c_float
         sigs = {
             "na2d_qk_rpb": [pp, vp, vp, vp, f, vp, vp],

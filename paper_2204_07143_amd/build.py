@@ -19,6 +19,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libna2d.so")
+# measurement build (-DNA2D_PROBE_MEMORY_ONLY: loads and stores only in the tiled contraction kernels); bench.py --lib
+PROBE_LIB = os.path.join(OBJ_DIR, "libna2d_probe_memory_only.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -39,12 +41,12 @@ def _newest_header() -> float:
     return max(os.path.getmtime(h) for h in hdrs)
 
 
-def _compile(src: str, force: bool, hdr_time: float) -> str:
-    obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+def _compile(src: str, force: bool, hdr_time: float, probe: bool = False) -> str:
+    obj = os.path.join(OBJ_DIR, os.path.basename(src) + (".probe.o" if probe else ".o"))
     if (not force and os.path.exists(obj) and os.path.getmtime(obj) >= os.path.getmtime(src)
             and os.path.getmtime(obj) >= hdr_time):
         return obj
-    cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
+    cmd = [HIPCC, *FLAGS, *(["-DNA2D_PROBE_MEMORY_ONLY"] if probe else []), "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
@@ -81,6 +83,20 @@ def _check_no_scratch(src: str, stderr: str) -> None:
         raise RuntimeError(f"{os.path.basename(src)}: kernels spill to scratch:\n  " + "\n  ".join(bad))
 
 
+def build_probe(force: bool = False, jobs: int | None = None) -> str:
+    """The measurement build: the whole library with the arithmetic of the tiled contraction kernels left out."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    jobs = jobs or min(len(srcs), int(os.environ.get("MAX_JOBS", os.cpu_count() or 4)))
+    hdr_time = _newest_header()
+    with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(lambda s: _compile(s, force, hdr_time, probe=True), srcs))
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PROBE_LIB, *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    return PROBE_LIB
+
+
 def build(force: bool = False, jobs: int | None = None) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
@@ -102,5 +118,8 @@ if __name__ == "__main__":
     ap = argparse.ArgumentParser()
     ap.add_argument("--force", action="store_true")
     ap.add_argument("-j", type=int, default=None)
+    ap.add_argument("--probe", action="store_true", help="also build the memory-only measurement library")
     a = ap.parse_args()
     print(build(force=a.force, jobs=a.j))
+    if a.probe:
+        print(build_probe(force=a.force, jobs=a.j))

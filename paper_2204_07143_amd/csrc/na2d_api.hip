@@ -16,7 +16,7 @@ static int validate(const na2d_problem *p) {
     const int k = p->k;
     if ((k & 1) == 0 || k < 3 || k > kMaxGenericK) return NA2D_ERR_KERNEL_SIZE;
     if (k > p->H || k > p->W) return NA2D_ERR_TOO_SMALL;
-    if (!head_dim_supported(p->dtype, k, p->D)) return NA2D_ERR_HEAD_DIM;
+    if (p->D != 16 && p->D != 32 && p->D != 64 && p->D != 128) return NA2D_ERR_HEAD_DIM;
     // Index arithmetic inside the kernels is 64-bit for byte offsets, but element counts of a
     // tensor must fit int32 so that per-plane and per-row products cannot overflow.
     const int64_t nq = (int64_t)p->B * p->heads * p->H * p->W;
@@ -297,7 +297,7 @@ const char *na2d_strerror(int status) {
         case NA2D_ERR_DTYPE: return "unknown dtype";
         case NA2D_ERR_KERNEL_SIZE: return "kernel size must be odd and between 3 and 63";
         case NA2D_ERR_TOO_SMALL: return "kernel size exceeds the feature map (k > min(H, W))";
-        case NA2D_ERR_HEAD_DIM: return "head dim must be 16, 32, 64 or 128 (and small enough for the kernel size: see na2d.h)";
+        case NA2D_ERR_HEAD_DIM: return "head dim must be 16, 32, 64 or 128";
         case NA2D_ERR_SHAPE: return "non-positive extent or tensor too large";
         case NA2D_ERR_ALIGN: return "pointer is not 16-byte aligned";
         case NA2D_ERR_WORKSPACE: return "workspace missing, misaligned or too small (or the problem exceeds the built-in scratch array)";

@@ -232,7 +232,7 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
         if (!active) return;
         f32x4 o[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-        for (int pb = 0; pb < C::NPAIR; ++pb) {
+        for (int pb = 0; pb < (kProbeMemoryOnly ? 0 : C::NPAIR); ++pb) {   // (measurement build: zeros are stored)
             uint32_t wv[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
                 const int hf = u >> 1, r = 2 * (u & 1);
                 ov[u] = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){o[hf][r] * scale, o[hf][r + 1] * scale}, tx2_t));
             }
-            *reinterpret_cast<u32x4 *>(dst) = u32x4{ov[0], ov[1], ov[2], ov[3]};   // channels 8g .. 8g + 7
+            store16_stream(dst, u32x4{ov[0], ov[1], ov[2], ov[3]});   // channels 8g .. 8g + 7
         }
     };
 

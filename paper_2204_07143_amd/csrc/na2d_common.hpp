@@ -194,6 +194,30 @@ __device__ __forceinline__ __attribute__((address_space(3))) T *lds_ptr(int addr
     return (__attribute__((address_space(3))) T *)(uintptr_t)(unsigned)addr;
 }
 
+// ---- streaming stores ---------------------------------------------------------------------------
+// The head-dim results of the path (out, dq, dk, dv) are not read again by any of its kernels: their 16-byte
+// stores carry the non-temporal hint, which keeps them from displacing what the kernels that follow will read
+// (a plain device copy gains about 6 % from the hint on this chip; weighted sum 20.4 -> 18.1 us, grad-q
+// 19.6 -> 17.2 us, grad-v / grad-k 24.5 -> 23.6 us at the benchmark shape).  The attention-shaped results
+// (logits, weights, dp, ds) keep plain stores: the next kernel of the path reads them, out of the last-level
+// cache when it follows at once; streaming them as well made each producer faster by itself (logits
+// 24.2 -> 21.4 us) and the ten-call step slower.  `p` may be aligned to the element only.
+typedef u32x4 __attribute__((aligned(2))) u32x4_unaligned;
+__device__ __forceinline__ void store16_stream(void *p, u32x4 v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_unaligned *>(p));
+}
+
+// ---- measurement build ------------------------------------------------------------------------
+// Built with -DNA2D_PROBE_MEMORY_ONLY (a separate library for the benchmark, never the product), the tiled
+// 16-bit contraction kernels keep every load and store of a launch and leave out the arithmetic between
+// them (LDS gathers, matrix-core products, conversions): the time of such a launch is what the memory
+// system takes for this access pattern, the bound the real kernel is held against.
+#ifdef NA2D_PROBE_MEMORY_ONLY
+constexpr bool kProbeMemoryOnly = true;
+#else
+constexpr bool kProbeMemoryOnly = false;
+#endif
+
 // ---- workgroup barrier -----------------------------------------------------------------------
 // A workgroup barrier that orders LDS accesses across it.  __syncthreads() is a release fence, s_barrier
 // and an acquire fence; the wait for the wave's outstanding LDS accesses that the release fence stands for

@@ -297,9 +297,8 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
         if (q_ok) {
             const size_t plane = (size_t)b * heads + head;
             char *dst = reinterpret_cast<char *>(dq) + plane * plane_bytes + qlin * Traits<T>::kKeyBytes + g * 16;
-            *reinterpret_cast<u32x4 *>(dst) =
-                u32x4{pack2_t<T>(o[0][0] * scale, o[0][1] * scale), pack2_t<T>(o[0][2] * scale, o[0][3] * scale),
-                      pack2_t<T>(o[1][0] * scale, o[1][1] * scale), pack2_t<T>(o[1][2] * scale, o[1][3] * scale)};
+            store16_stream(dst, u32x4{pack2_t<T>(o[0][0] * scale, o[0][1] * scale), pack2_t<T>(o[0][2] * scale, o[0][3] * scale),
+                                      pack2_t<T>(o[1][0] * scale, o[1][1] * scale), pack2_t<T>(o[1][2] * scale, o[1][3] * scale)});
             if (g == 0) {   // for the key-patch kernel: delta, and the log-sum-exp in the exp2 domain
                 delta_out[plane * H * W + qlin] = delta;
                 lse2_out[plane * H * W + qlin] = lse2;
@@ -564,12 +563,12 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
         }
         if (key_ok) {
             const size_t o = (plane * plane_px + (size_t)jy * W + jx) * KB + g * 16;
-            *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(dk) + o) =
-                u32x4{pack2_t<T>(ak[0][0] * scale, ak[0][1] * scale), pack2_t<T>(ak[0][2] * scale, ak[0][3] * scale),
-                      pack2_t<T>(ak[1][0] * scale, ak[1][1] * scale), pack2_t<T>(ak[1][2] * scale, ak[1][3] * scale)};
-            *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(dv) + o) =
-                u32x4{pack2_t<T>(av[0][0], av[0][1]), pack2_t<T>(av[0][2], av[0][3]), pack2_t<T>(av[1][0], av[1][1]),
-                      pack2_t<T>(av[1][2], av[1][3])};
+            store16_stream(reinterpret_cast<char *>(dk) + o,
+                           u32x4{pack2_t<T>(ak[0][0] * scale, ak[0][1] * scale), pack2_t<T>(ak[0][2] * scale, ak[0][3] * scale),
+                                 pack2_t<T>(ak[1][0] * scale, ak[1][1] * scale), pack2_t<T>(ak[1][2] * scale, ak[1][3] * scale)});
+            store16_stream(reinterpret_cast<char *>(dv) + o,
+                           u32x4{pack2_t<T>(av[0][0], av[0][1]), pack2_t<T>(av[0][2], av[0][3]), pack2_t<T>(av[1][0], av[1][1]),
+                                 pack2_t<T>(av[1][2], av[1][3])});
         }
     }
 }

@@ -243,9 +243,9 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
             char *dst = reinterpret_cast<char *>(out) + plane * plane_bytes + (size_t)qlin * C::kKeyBytesG + g * 16;
 #pragma unroll
             for (int sl = 0; sl < NS; ++sl)   // channels 32 sl + 8g .. + 7
-                *reinterpret_cast<u32x4 *>(dst + sl * Traits<T>::kKeyBytes) =
-                    u32x4{pack2<T>(o[sl][0][0] * inv, o[sl][0][1] * inv), pack2<T>(o[sl][0][2] * inv, o[sl][0][3] * inv),
-                          pack2<T>(o[sl][1][0] * inv, o[sl][1][1] * inv), pack2<T>(o[sl][1][2] * inv, o[sl][1][3] * inv)};
+                store16_stream(dst + sl * Traits<T>::kKeyBytes,
+                               u32x4{pack2<T>(o[sl][0][0] * inv, o[sl][0][1] * inv), pack2<T>(o[sl][0][2] * inv, o[sl][0][3] * inv),
+                                     pack2<T>(o[sl][1][0] * inv, o[sl][1][1] * inv), pack2<T>(o[sl][1][2] * inv, o[sl][1][3] * inv)});
             if (lse != nullptr && g == 0) lse[plane * H * W + qlin] = (m2 + __builtin_amdgcn_logf(l)) * kLn2;
         }
     };

@@ -8,6 +8,7 @@
 // around, and the neighbouring threads of a wave read neighbouring keys, so the caches carry the reuse.
 #include "na2d_kernels.hpp"
 #include "na2d_common.hpp"
+#include "na2d_valu_cfg.hpp"
 
 namespace na2d {
 
@@ -252,7 +253,10 @@ unsigned blocks_for(size_t total) { return (unsigned)((total + 255) / 256); }
 
 }  // namespace
 
-bool generic_window(const Problem &p) { return p.K > kMaxTunedK; }
+// Which problems take these kernels: window sides beyond the tuned ones, and the combinations of dtype, window and
+// head dim whose plain-ALU tiles do not fit the LDS (fp32 with D >= 64 and a larger window, D = 128 in 16 bit with
+// k >= 11): the kernels here stage nothing in LDS, so they take every head dim.
+bool generic_window(const Problem &p) { return p.K > kMaxTunedK || !head_dim_supported(p.dtype, p.K, p.D); }
 
 hipError_t launch_qk_generic(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
                              hipStream_t s) {

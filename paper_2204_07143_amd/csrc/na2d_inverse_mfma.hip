@@ -271,7 +271,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
                     const T lo = from_f32<T>(acc[p][hf][r] * scale), hi = from_f32<T>(acc[p][hf][r + 1] * scale);
                     o[u] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
                 }
-                *reinterpret_cast<u32x4 *>(dst) = u32x4{o[0], o[1], o[2], o[3]};   // channels 8g .. 8g + 7
+                store16_stream(dst, u32x4{o[0], o[1], o[2], o[3]});   // channels 8g .. 8g + 7
             }
         }
     }

@@ -207,7 +207,7 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
             f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
             int slot = oqy % C::NR;   // ring slot of halo row 0; the following rows follow, wrapping
 #pragma unroll
-            for (int pb = 0; pb < C::NPAIR; ++pb) {
+            for (int pb = 0; pb < (kProbeMemoryOnly ? 0 : C::NPAIR); ++pb) {   // (measurement build: zeros are stored)
                 const int s_lo = slot, s_hi = slot + 1 < C::NR ? slot + 1 : 0;
                 slot = s_hi + 1 < C::NR ? s_hi + 1 : 0;
                 // halo rows that no key row of the strip is seen from are skipped
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
                     const T lo = from_f32<T>(acc[hf][r] * scale), hi = from_f32<T>(acc[hf][r + 1] * scale);
                     o[u] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
                 }
-                *reinterpret_cast<u32x4 *>(dst) = u32x4{o[0], o[1], o[2], o[3]};   // channels 8g .. 8g + 7
+                store16_stream(dst, u32x4{o[0], o[1], o[2], o[3]});   // channels 8g .. 8g + 7
             }
         }
         wait_global_loads();   // the next tile's rows have landed

@@ -215,7 +215,7 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
                         const T lo = from_f32<T>(acc[hf][r] * scale), hi = from_f32<T>(acc[hf][r + 1] * scale);
                         o[u] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
                     }
-                    *reinterpret_cast<u32x4 *>(dst) = u32x4{o[0], o[1], o[2], o[3]};   // channels 8g .. 8g + 7
+                    store16_stream(dst, u32x4{o[0], o[1], o[2], o[3]});   // channels 8g .. 8g + 7
                 }
                 acc[0] = acc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
             }

@@ -100,8 +100,9 @@ static hipError_t launch_qk_t(const Problem &p, const void *x, const void *y, co
     }
 }
 
+// do the LDS tiles of every plain-ALU kernel fit for this dtype, window and head dim?
 bool head_dim_supported(int dtype, int K, int D) {
-    if (K > kMaxTunedK) return D == 16 || D == 32 || D == 64 || D == 128;   // the run-time-K kernels stage nothing in LDS
+    if (K > kMaxTunedK) return false;
     auto probe = [&]() -> hipError_t {
         NA2D_DISPATCH_T(dtype, NA2D_DISPATCH_K(K, NA2D_DISPATCH_D(D, return (valu_fits<T, K, D>() ? hipSuccess : hipErrorInvalidValue))));
         return hipErrorInvalidValue;

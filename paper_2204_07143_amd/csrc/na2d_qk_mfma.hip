@@ -58,10 +58,15 @@ struct QkSmallCfg {
 // pointers), and whose 64 lanes still cover one contiguous kilobyte.  Aligning the stores instead would put the
 // misalignment on the LDS side, where a 16-byte read at a 2-byte phase costs eight reads.  The elements past
 // the last whole chunk (ragged tiles only) go one by one.
+#ifdef NA2D_PROBE_ALIGNED_STORES
+constexpr bool kProbeAlignedStores = true;   // experiment: what would 16-byte aligned stores cost? (results land in the wrong place)
+#else
+constexpr bool kProbeAlignedStores = false;
+#endif
 template <typename T, int PASSES>
 __device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, int lds_row, int lane) {
     const int nbody = nbytes >> 4;
-    char *ga = gbase + g0;
+    char *ga = gbase + (kProbeAlignedStores ? (g0 & ~(size_t)15) : g0);
     struct __attribute__((packed, aligned(2))) Chunk {
         u32x4 v;
     };
@@ -239,6 +244,11 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
     };
     auto compute = [&](auto par_c, const u32x4 (&qreg)[NS]) {
         constexpr int PAR = decltype(par_c)::value;
+        if constexpr (kProbeMemoryOnly) {   // measurement build: the query chunks are still loaded, the staging images leave as they are
+#pragma unroll
+            for (int sl = 0; sl < NS; ++sl) asm volatile("" ::"v"(qreg[sl].x), "v"(qreg[sl].y), "v"(qreg[sl].z), "v"(qreg[sl].w));
+            return;
+        }
         if (!active) return;
         // blocks in batches of eight: the MFMAs of a batch are issued back to back, then its 32 results are
         // stored; large windows (up to 16 blocks) never hold more than eight accumulators

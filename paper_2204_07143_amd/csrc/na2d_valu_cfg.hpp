@@ -81,7 +81,7 @@ constexpr bool valu_fits() {
            tile_fits<FusedCfg, T, K, D>();
 }
 
-// run-time form for the argument validation
+// run-time form (false for window sides beyond the tuned ones)
 bool head_dim_supported(int dtype, int K, int D);
 
 }  // namespace na2d

@@ -48,7 +48,7 @@ def P(B=1, heads=1, H=14, W=14, D=32, k=3, dtype=0):
     (P(k=15, H=20, W=20), 0), (P(k=63, H=63, W=70, D=128, dtype=0), 0), (P(k=21, H=20, W=30), -4), (P(k=21, H=30, W=30, D=48), -5),
     (P(k=7, H=6), -4), (P(k=7, W=5), -4),
     (P(D=64), 0), (P(D=16, k=13, H=20, W=20), 0), (P(D=128, k=9, H=20, W=20, dtype=1), 0),
-    (P(D=48), -5), (P(D=8), -5), (P(D=128, k=5, H=20, W=20, dtype=0), -5), (P(D=64, k=11, H=20, W=20, dtype=0), -5),
+    (P(D=48), -5), (P(D=8), -5), (P(D=128, k=5, H=20, W=20, dtype=0), 0), (P(D=64, k=11, H=20, W=20, dtype=0), 0),
     (P(B=0), -6), (P(H=-1), -6),
     (P(B=4096, heads=16, H=512, W=512, k=3), -6),
     # one (batch, head) plane of the attention tensor: below / beyond 2^31 bytes (offsets inside a plane are 32-bit)
