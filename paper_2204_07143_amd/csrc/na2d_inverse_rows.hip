@@ -24,12 +24,15 @@
 
 namespace na2d {
 
-template <typename T, int K>
+// NP: key patches per wave, stacked eight key rows apart (the tile is 16 x 8 NP keys).  With two, a row of the
+// query rectangle that passes through LDS serves sixteen key rows instead of eight: at K = 13 the rectangle of a
+// tile has 8 NP + 18 rows, 3.25 per key row for NP = 1 and 2.1 for NP = 2, and that is what the kernel's time follows.
+template <typename T, int K, int NP = 1>
 struct InvRowsCfg {
     static constexpr int R = K / 2;
     static constexpr int PWI = K + R + 3;            // query columns (rows) that can see a 4 x 4 key patch
     static constexpr int NCB = (PWI + 15) / 16;      // 16-column MFMA blocks per row
-    static constexpr int STRIPS = 2, WAVES = 4 * STRIPS, TY = 4 * STRIPS;
+    static constexpr int STRIPS = 2, WAVES = 4 * STRIPS, TY = 4 * STRIPS * NP;
     static constexpr int RW = kTileX + K - 1 + R;    // columns of a tile's query rectangle (next to one border at most)
     static constexpr int CH = 2;                     // rows per stage
     static constexpr int KK = K * K;
@@ -52,13 +55,13 @@ struct InvRowsCfg {
     static_assert(16 * NCB >= PWI, "column blocks cover the patch halo");
 };
 
-template <typename T, int K>
+template <typename T, int K, int NP>
 __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restrict__ w, const T *__restrict__ x, float scale,
                                                               T *__restrict__ out, int H, int W, int heads, int nb,
                                                               int tiles_y, int units, int splits, GridDecode gd, int pitch) {
     // `pitch`: bytes between consecutive positions of x and out (a longer head vector is served one 32-channel
     // slice per launch, x and out pointing at the slice)
-    using C = InvRowsCfg<T, K>;
+    using C = InvRowsCfg<T, K, NP>;
     constexpr int SZ = (int)sizeof(T);
     constexpr int BIG = 1 << 24;   // invalid row / column terms push the sum past the zero word
     extern __shared__ __align__(16) char lds[];
@@ -90,15 +93,14 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
     const int wrow_bytes = ncols * C::KK * SZ;
     const size_t w_bytes = (size_t)nb * heads * H * W * C::KK * SZ;   // size of the weight tensor
 
-    // this wave's patch and this lane's key
+    // this wave's patches (one column of the tile, NP of them eight key rows apart) and this lane's keys
     const int strip = wave >> 2, p = patch_of_wave(wave);
-    const int sy0 = ty0 + 4 * strip, px0 = tx0 + 4 * p;
-    const bool active = sy0 < H && px0 < W;
-    const int jy = sy0 + ky, jx = px0 + kx;
-    const int oqx = inv_first(px0 < W ? px0 : W - 1, W, K);   // first query column that sees the patch
-    // query rows that see the strip: [sq0, sq1]
-    const int sq0 = inv_first(sy0 < H ? sy0 : H - 1, H, K);
-    const int sq1 = inv_last(sy0 + 3 < H - 1 ? sy0 + 3 : H - 1, H, K);
+    const int px0 = tx0 + 4 * p;
+    const int jx = px0 + kx;
+    const int oqx = inv_first(px0 < W ? px0 : W - 1, W, K);   // first query column that sees the patches
+    // per patch (all wave-uniform, worked out where they are used: nothing is held per patch but its accumulators)
+    auto patch_row0 = [&](int np) { return ty0 + 4 * strip + 8 * np; };   // first key row of patch np
+    const bool active = patch_row0(0) < H && px0 < W;   // the patches below the first one are inside the map only if it is
 
     // column terms: block cb, position 4g + r of it is query column oqx + 16 cb + 4g + r
     int colterm[C::NCB][4];
@@ -165,7 +167,9 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
         }
     };
 
-    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    f32x4 acc[NP][2];
+#pragma unroll
+    for (int np = 0; np < NP; ++np) acc[np][0] = acc[np][1] = f32x4{0.f, 0.f, 0.f, 0.f};
     // One step: pair `pr` of plane `b`, staged in `par`.
     auto compute = [&](int b, int pr, int par) {
         if (active) {
@@ -173,17 +177,24 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
             const int stage = lds0 + par * C::kStageBytes;
             const int zero_addr = stage + C::kXStage + C::kWStage;
             const int mis0 = (int)(((plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ) & 15);   // phase of the rectangle's first row
-            // row terms of the pair's two rows for this lane's key row
-            int rowterm[2];
-#pragma unroll
-            for (int rr = 0; rr < 2; ++rr) {
-                const int iy = ry0 + 2 * pr + rr;
-                const int a = jy - win_start(iy < H ? iy : H - 1, H, K);
-                const bool ok = iy <= ry1 && jy < H && (unsigned)a < (unsigned)K;
-                rowterm[rr] = ok ? stage + C::kXStage + rr * C::kRowRegion + ((mis0 + (iy - ry0) * pitch_phase) & 15) + a * K * SZ : BIG;
-            }
             const int iy0 = ry0 + 2 * pr;
-            if (iy0 + 1 >= sq0 && iy0 <= sq1) {   // the pair holds a row that sees the strip (wave-uniform)
+#pragma unroll
+            for (int np = 0; np < NP; ++np) {
+                // the pair holds a row that sees this patch's strip (wave-uniform): query rows [sq0, sq1] do
+                const int sy = patch_row0(np);
+                if (sy >= H) continue;
+                const int sq0 = inv_first(sy, H, K), sq1 = inv_last(sy + 3 < H - 1 ? sy + 3 : H - 1, H, K);
+                if (!(iy0 + 1 >= sq0 && iy0 <= sq1)) continue;
+                const int jyp = sy + ky;   // this lane's key row
+                // row terms of the pair's two rows for this lane's key row
+                int rowterm[2];
+#pragma unroll
+                for (int rr = 0; rr < 2; ++rr) {
+                    const int iy = iy0 + rr;
+                    const int a = jyp - win_start(iy < H ? iy : H - 1, H, K);
+                    const bool ok = iy <= ry1 && jyp < H && (unsigned)a < (unsigned)K;
+                    rowterm[rr] = ok ? stage + C::kXStage + rr * C::kRowRegion + ((mis0 + (iy - ry0) * pitch_phase) & 15) + a * K * SZ : BIG;
+                }
 #pragma unroll
                 for (int cb = 0; cb < C::NCB; ++cb) {
                     uint32_t wv[4];
@@ -201,23 +212,27 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
                         const int a0 = stage + xa_lane + cb * 16 * C::KB + hf * 8;
                         const u32x2 lo = lds_read_tr16(a0);
                         const u32x2 hi = lds_read_tr16(a0 + C::kXRow);
-                        acc[hf] = mfma_16x16x32<T>(u32x4{lo.x, lo.y, hi.x, hi.y}, bop, acc[hf]);
+                        acc[np][hf] = mfma_16x16x32<T>(u32x4{lo.x, lo.y, hi.x, hi.y}, bop, acc[np][hf]);
                     }
                 }
             }
-            if (pr == npairs - 1) {   // the rectangle is done: this lane's eight channels of its key
-                if (jy < H && jx < W) {
-                    char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * pitch + g * 16;
-                    uint32_t o[4];
+            if (pr == npairs - 1) {   // the rectangle is done: this lane's eight channels of its keys
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int hf = u >> 1, r = 2 * (u & 1);
-                        const T lo = from_f32<T>(acc[hf][r] * scale), hi = from_f32<T>(acc[hf][r + 1] * scale);
-                        o[u] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+                for (int np = 0; np < NP; ++np) {
+                    const int jyp = patch_row0(np) + ky;
+                    if (jyp < H && jx < W) {
+                        char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jyp * W + jx) * pitch + g * 16;
+                        uint32_t o[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int hf = u >> 1, r = 2 * (u & 1);
+                            const T lo = from_f32<T>(acc[np][hf][r] * scale), hi = from_f32<T>(acc[np][hf][r + 1] * scale);
+                            o[u] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+                        }
+                        store16_stream(dst, u32x4{o[0], o[1], o[2], o[3]});   // channels 8g .. 8g + 7
                     }
-                    store16_stream(dst, u32x4{o[0], o[1], o[2], o[3]});   // channels 8g .. 8g + 7
+                    acc[np][0] = acc[np][1] = f32x4{0.f, 0.f, 0.f, 0.f};
                 }
-                acc[0] = acc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
         }
     };
@@ -241,13 +256,13 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
     }
 }
 
-template <typename T, int K>
-static hipError_t launch_inverse_rows_t(const Problem &p, const void *w, const void *x, float scale, void *out,
-                                        hipStream_t s) {
-    using C = InvRowsCfg<T, K>;
+template <typename T, int K, int NP>
+static hipError_t launch_inverse_rows_np(const Problem &p, const void *w, const void *x, float scale, void *out,
+                                         hipStream_t s) {
+    using C = InvRowsCfg<T, K, NP>;
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
-    auto kern = inverse_rows_kernel<T, K>;
+    auto kern = inverse_rows_kernel<T, K, NP>;
     static LdsAllowed allowed;
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     for (int sl = 0; sl < p.D / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector
@@ -258,6 +273,19 @@ static hipError_t launch_inverse_rows_t(const Problem &p, const void *w, const v
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+// Several patches per wave where the windows are large (the rectangle's K + R - 1 extra rows then weigh most) and
+// the map has 8-row tiles to merge: grad-v / grad-k at B=64, 56 x 56, f16 take 153 / 120 / 96 us (K = 11) and
+// 194 / 146 / 119 us (K = 13) with one / two / four patches per wave.
+template <typename T, int K>
+static hipError_t launch_inverse_rows_t(const Problem &p, const void *w, const void *x, float scale, void *out,
+                                        hipStream_t s) {
+    if constexpr (K >= 9) {   // (eight patches per wave, a whole column of a 56-row map, no longer fit 128 registers)
+        if (p.H > 24) return launch_inverse_rows_np<T, K, 4>(p, w, x, scale, out, s);
+        if (p.H > 8) return launch_inverse_rows_np<T, K, 2>(p, w, x, scale, out, s);
+    }
+    return launch_inverse_rows_np<T, K, 1>(p, w, x, scale, out, s);
 }
 
 // Every tile's query rectangle must be at most RW columns wide (rows are streamed, any number of them), and a
