@@ -322,14 +322,15 @@ def bench_na1d(na, synth, torch, timer, replays: int) -> dict:
 
 
 def inverse_kernel_name(workload: str, p) -> str:
-    """grad-v / grad-k run one of two device kernels, chosen by the library from the map and kernel
-    size (the column-walking `inverse_ring` or the tile kernel `inverse_mfma`); the name reported is
-    the one the profile summary of this workload recorded, else the neutral `inverse`."""
+    """grad-v / grad-k run one of three device kernels, chosen by the library from the map and kernel
+    size (the column-walking `inverse_ring`, the tile kernel `inverse_mfma` or the row-streaming
+    `inverse_rows`); the name reported is the one the profile summary of this workload recorded, else
+    the neutral `inverse`."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}_k{p.k}_{p.dtype}.txt")
     if os.path.exists(path):
         for line in open(path):
             f = line.split()
-            if f and f[0] in ("inverse_ring", "inverse_mfma"):
+            if f and f[0] in ("inverse_ring", "inverse_mfma", "inverse_rows"):
                 return f[0]
     return "inverse"
 

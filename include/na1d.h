@@ -71,7 +71,10 @@ int na1d_qk_bwd_q(const na1d_problem *p, const void *ds, const void *k, float sc
 int na1d_qk_bwd_k(const na1d_problem *p, const void *ds, const void *q, float scale, void *dk, void *stream);
 /* grad-b: d_rpb[h, u] = sum over batch, queries and slots whose bias cell is u of ds.  Summed as
  * 64-bit fixed point (42 fraction bits), so the result does not depend on the order of the
- * additions (bitwise reproducible); a non-finite ds counts as 0.  `workspace` must hold
+ * additions (bitwise reproducible).  Range of that format: every ds is truncated to a multiple of
+ * 2^-42 (gradients whose ds are all below that sum to 0; at |ds| ~ 1e-6 the relative error of a
+ * term is 2e-7, that of fp32), and a ds with |ds| >= 2^21, or a non-finite one, counts as 0
+ * instead of saturating or poisoning the sum.  `workspace` must hold
  * na1d_workspace_bytes(p) bytes; no initialisation needed. */
 int na1d_qk_bwd_rpb(const na1d_problem *p, const void *ds, float *d_rpb, void *workspace, size_t workspace_bytes,
                     void *stream);

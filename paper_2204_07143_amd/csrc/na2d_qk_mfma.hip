@@ -58,15 +58,10 @@ struct QkSmallCfg {
 // pointers), and whose 64 lanes still cover one contiguous kilobyte.  Aligning the stores instead would put the
 // misalignment on the LDS side, where a 16-byte read at a 2-byte phase costs eight reads.  The elements past
 // the last whole chunk (ragged tiles only) go one by one.
-#ifdef NA2D_PROBE_ALIGNED_STORES
-constexpr bool kProbeAlignedStores = true;   // experiment: what would 16-byte aligned stores cost? (results land in the wrong place)
-#else
-constexpr bool kProbeAlignedStores = false;
-#endif
 template <typename T, int PASSES>
 __device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, int lds_row, int lane) {
     const int nbody = nbytes >> 4;
-    char *ga = gbase + (kProbeAlignedStores ? (g0 & ~(size_t)15) : g0);
+    char *ga = gbase + g0;
     struct __attribute__((packed, aligned(2))) Chunk {
         u32x4 v;
     };
