@@ -19,6 +19,8 @@
 
 namespace na2d {
 
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+
 template <typename T, int K>
 struct InvRingCfg {
     static constexpr int R = K / 2;
@@ -41,8 +43,10 @@ struct InvRingCfg {
     static constexpr int kWItems = (kRowRegion / 16 + kWave - 1) / kWave;   // 64-lane loads per weight row
     static constexpr int kWBytes = NR * kRowRegion;
     static constexpr int kColEntries = 4 * 4 * 4 * 4;             // [patch][g][kx][r]
-    static constexpr int kRowEntries = STRIPS * NBLK * 4;         // [strip][b][ky]
-    static constexpr int kLdsBytes = kXBytes + kWBytes + 16 + (kColEntries + kRowEntries) * 4;
+    static constexpr int kRowEntries = STRIPS * 4 * 16;           // [strip][ky][b], b padded to 16: a lane reads its terms a pair at a time
+    static_assert(NBLK <= 16, "sixteen row terms per lane");
+    // two row-term tables: the next tile's is written while this tile's is read
+    static constexpr int kLdsBytes = kXBytes + kWBytes + 16 + (kColEntries + 2 * kRowEntries) * 4;
     static_assert(kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
     static constexpr int kMaxNew = RH;                            // rows loaded at once: the first tile's
     static constexpr int kRowsPerWave = (kMaxNew + WAVES - 1) / WAVES;
@@ -99,7 +103,13 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
         xx = xx < W - 1 ? xx : W - 1;
         xcol[j] = q < C::RW * (C::KB / 16) ? xx * pitch + (q % (C::KB / 16)) * 16 : -1;
     }
-    // Loads the query rows [r_begin, r_end) into their ring slots: row r_begin + wave, + WAVES, ... per wave.
+    // Loads the query rows [r_begin, r_end) into their ring slots: row r_begin + wave, + WAVES, ... per wave.  All of a
+    // row's address arithmetic is wave-uniform and 32 bits wide from the plane's base pointers on (a plane of either
+    // tensor is shorter than 2 GB: checked by the host), so it runs on the scalar unit in a few instructions.
+    const char *const xplane = reinterpret_cast<const char *>(x) + plane_q * pitch;
+    const char *const wplane = reinterpret_cast<const char *>(w) + wbase;
+    const size_t wleft = w_bytes - wbase;   // bytes from wplane to the end of the weight tensor
+    const int wphase0 = (int)(wbase & 15);  // 16-byte phase of row iy: (wphase0 + iy * row_pitch_bytes) & 15
     auto load_rows = [&](int r_begin, int r_end) {
 #pragma unroll
         for (int u = 0; u < C::kRowsPerWave; ++u) {
@@ -107,28 +117,35 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
             if (iy >= r_end) break;
             const int slot = iy % C::NR;
             // x vectors
-            const char *xrow = reinterpret_cast<const char *>(x) + (plane_q + (size_t)iy * W) * pitch;
+            const char *xrow = xplane + iy * W * pitch;
 #pragma unroll
             for (int j = 0; j < C::kXItems; ++j)
                 if (xcol[j] >= 0) global_to_lds_16(xrow, (unsigned)xcol[j], x0 + slot * C::kXRow + j * kWave * 16);
             // weight row, mirrored at its 16-byte phase: one 16-byte chunk per lane; the chunks at the two ends also
-            // bring in bytes of the neighbouring rows, which nothing reads.  Only the one chunk that would cross the
-            // end of the tensor is copied element by element.
-            const size_t g0 = wbase + (size_t)iy * row_pitch_bytes;
-            const int mis = (int)(g0 & 15);
+            // bring in bytes of the neighbouring rows, which nothing reads.  Only in a row whose last chunk would
+            // cross the end of the tensor is that chunk copied element by element.
+            const int wo = iy * row_pitch_bytes;
+            const int mis = (wphase0 + wo) & 15;
             const int nchunks = (mis + wrow_bytes + 15) >> 4;
-            const char *src = reinterpret_cast<const char *>(w) + (g0 - mis);
-            const size_t left = w_bytes - (g0 - mis);
+            const char *src = wplane + (wo - mis);   // (wplane - mis stays inside the allocation: mis <= the phase of wplane + wo)
             const int region = w0 + slot * C::kRowRegion;
+            if ((size_t)(wo - mis) + (size_t)nchunks * 16 <= wleft) {
 #pragma unroll
-            for (int j = 0; j < C::kWItems; ++j) {
-                const int c = j * kWave + lane;
-                if (c < nchunks) {
-                    if ((size_t)(c + 1) * 16 <= left) {
-                        global_to_lds_16(src, (unsigned)(c * 16), region + j * kWave * 16);
-                    } else {
-                        for (int e = c * 16; e < mis + wrow_bytes; e += SZ)
-                            *lds_ptr<T>(region + e) = *reinterpret_cast<const T *>(src + e);
+                for (int j = 0; j < C::kWItems; ++j) {
+                    const int c = j * kWave + lane;
+                    if (c < nchunks) global_to_lds_16(src, (unsigned)(c * 16), region + j * kWave * 16);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < C::kWItems; ++j) {
+                    const int c = j * kWave + lane;
+                    if (c < nchunks) {
+                        if ((size_t)(wo - mis) + (size_t)(c + 1) * 16 <= wleft) {
+                            global_to_lds_16(src, (unsigned)(c * 16), region + j * kWave * 16);
+                        } else {
+                            for (int e = c * 16; e < mis + wrow_bytes; e += SZ)
+                                *lds_ptr<T>(region + e) = *reinterpret_cast<const T *>(src + e);
+                        }
                     }
                 }
             }
@@ -144,7 +161,7 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
     const int oqx = inv_first(px0 < W ? px0 : W - 1, W, K);   // first query column that sees the patch
     const int xa_lane = x0 + (oqx - rx0 + 4 * g + (n >> 2)) * C::KB + (n & 3) * 16;
     const int jx = px0 + kx;
-    const int wphase0 = (int)(wbase & 15), pitch_phase = row_pitch_bytes & 15;   // phase of row iy: (wphase0 + iy * pitch_phase) & 15
+    const int pitch_phase = row_pitch_bytes & 15;   // phase of row iy: (wphase0 + iy * pitch_phase) & 15
 
     workgroup_sync();   // the zero fill is done
     // column terms: the same for every tile of the column
@@ -157,12 +174,31 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
         if (pp0 < W && ix <= rx1 && jxe < W && (unsigned)c < (unsigned)K) term = (ix - rx0) * C::KK * SZ + c * SZ;
         *lds_ptr<int>(tbl_col + e * 4) = term;
     }
-    // the rows of the segment's first tile
+    // Row terms of tile t into table (t - t_begin) & 1, one entry per thread: the address of the weight that query
+    // (iy, ix) gives key (jy, jx) is rowterm(iy, jy) + colterm(ix, jx); a pair that does not meet gets BIG.
+    auto build_rowterms = [&](int t) {
+        const int e = tid;
+        if (e < C::kRowEntries) {
+            const int ty0 = t * C::TY;
+            const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
+            const int ry1 = inv_last(ty1, H, K);   // last query row of the tile's rectangle
+            const int bb = e & 15, kye = (e >> 4) & 3, st = e >> 6;
+            const int sy = ty0 + 4 * st, jyy = sy + kye;
+            const int iy = inv_first(sy < H ? sy : H - 1, H, K) + bb;   // halo row bb of the strip
+            const int a = jyy - win_start(iy < H ? iy : H - 1, H, K);
+            int term = BIG;
+            if (bb < C::PWI && iy <= ry1 && jyy < H && (unsigned)a < (unsigned)K)
+                term = w0 + (iy % C::NR) * C::kRowRegion + ((wphase0 + iy * pitch_phase) & 15) + a * K * SZ;
+            *lds_ptr<int>(tbl_row + (((t - t_begin) & 1) * C::kRowEntries + e) * 4) = term;
+        }
+    };
+    // the rows and the row terms of the segment's first tile
     {
         const int ty0 = t_begin * C::TY;
         const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
         load_rows(inv_first(ty0, H, K), inv_last(ty1, H, K) + 1);
     }
+    build_rowterms(t_begin);
     wait_global_loads();
     workgroup_sync();
     int colterm[4];
@@ -178,58 +214,79 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
         const int ty0 = t * C::TY;
         const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
         const int ry1 = inv_last(ty1, H, K);   // last query row of this tile's rectangle (the first is inv_first(ty0))
-        // the next tile's new rows go to the slots that the tile before this one has left
+        // the next tile's new rows go to the slots that the tile before this one has left, its row terms to the
+        // table that tile read: both are ordered against their last readers by the barrier that ended that tile
         if (t + 1 < t_end) {
             const int ny1 = ty1 + C::TY < H - 1 ? ty1 + C::TY : H - 1;
             load_rows(ry1 + 1, inv_last(ny1, H, K) + 1);
+            build_rowterms(t + 1);
         }
-        // row terms of this tile, one entry per thread: the address of the weight that query (iy, ix) gives key
-        // (jy, jx) is rowterm(iy, jy) + colterm(ix, jx); a pair that does not meet gets BIG
-        for (int e = tid; e < C::kRowEntries; e += C::kThreads) {
-            const int kye = e & 3, bb = (e >> 2) % C::NBLK, st = (e >> 2) / C::NBLK;
-            const int sy = ty0 + 4 * st, jyy = sy + kye;
-            const int iy = inv_first(sy < H ? sy : H - 1, H, K) + bb;   // halo row bb of the strip
-            const int a = jyy - win_start(iy < H ? iy : H - 1, H, K);
-            int term = BIG;
-            if (bb < C::PWI && iy <= ry1 && jyy < H && (unsigned)a < (unsigned)K)
-                term = w0 + (iy % C::NR) * C::kRowRegion + ((wphase0 + iy * pitch_phase) & 15) + a * K * SZ;
-            *lds_ptr<int>(tbl_row + e * 4) = term;
-        }
-        workgroup_sync();
 
         const int sy0 = ty0 + 4 * strip;   // first key row of this wave's strip
         if (sy0 < H && px0 < W) {
             const int jy = sy0 + ky;
             const int oqy = inv_first(sy0, H, K);   // first query row of the strip's halo
-            int rowterm[C::NBLK];
-#pragma unroll
-            for (int bb = 0; bb < C::NBLK; ++bb) rowterm[bb] = *lds_ptr<int>(tbl_row + ((strip * C::NBLK + bb) * 4 + ky) * 4);
+            // this lane's row terms, halo row b at rt_at + 4 b: read a pair at a time, one pair ahead of its use
+            const int rt_at = tbl_row + (((t - t_begin) & 1) * C::kRowEntries + (strip * 4 + ky) * 16) * 4;
             f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-            int slot = oqy % C::NR;   // ring slot of halo row 0; the following rows follow, wrapping
-#pragma unroll
-            for (int pb = 0; pb < (kProbeMemoryOnly ? 0 : C::NPAIR); ++pb) {   // (measurement build: zeros are stored)
-                const int s_lo = slot, s_hi = slot + 1 < C::NR ? slot + 1 : 0;
-                slot = s_hi + 1 < C::NR ? s_hi + 1 : 0;
-                // halo rows that no key row of the strip is seen from are skipped
-                if (__any(rowterm[2 * pb] < BIG || rowterm[2 * pb + 1] < BIG)) {
-                    uint32_t wv[4];
+            // Halo rows of the strip that some key row of it is seen from: oqy .. the last query row that sees the
+            // strip's last key row.  They are taken in pairs (one MFMA is two rows deep); the pair loop is free of
+            // branches, so that the gathers of one pair are in flight while the pair before it is multiplied, and
+            // comes in three lengths of which a wave picks the shortest that covers its rows.
+            const int sy1 = sy0 + 3 < H - 1 ? sy0 + 3 : H - 1;
+            const int npairs = (inv_last(sy1, H, K) - oqy + 2) >> 1;   // <= NPAIR: the host has checked the map
+            auto pairs = [&](auto npc) {
+                constexpr int NP = decltype(npc)::value;
+                // What a pair needs from LDS: eight gathered weights (the B operand: two halo rows x four columns
+                // per lane) and four transposing reads of x (the A operands of the two channel halves).  The reads
+                // of pair pb + 1 are issued before pair pb is multiplied, and the scheduling fences keep the
+                // compiler from sinking them back to their uses: a wave has twelve reads in flight behind every
+                // pair of MFMAs instead of waiting for each pair's reads in turn.
+                uint16_t wlo[2][4], whi[2][4];
+                u32x2 xlo[2][2], xhi[2][2];
+                int slot = oqy % C::NR;   // ring slot of halo row 0; the following rows follow, wrapping
+                i32x2 rt_next = *lds_ptr<i32x2>(rt_at);
+                auto fetch = [&](int pb, int st) {
+                    const int s_lo = slot, s_hi = slot + 1 < C::NR ? slot + 1 : 0;
+                    slot = s_hi + 1 < C::NR ? s_hi + 1 : 0;
+                    const int rowterm[2] = {rt_next.x, rt_next.y};
+                    if (pb + 1 < NP) rt_next = *lds_ptr<i32x2>(rt_at + (pb + 1) * 8);
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        const int bb = 2 * pb + (u >> 1);
+                        const int bb = u >> 1;
                         const int r0 = (u & 1) * 2;
                         int a_lo = rowterm[bb] + colterm[r0], a_hi = rowterm[bb] + colterm[r0 + 1];
                         a_lo = a_lo < zero_addr ? a_lo : zero_addr;
                         a_hi = a_hi < zero_addr ? a_hi : zero_addr;
-                        wv[u] = (uint32_t)*lds_ptr<uint16_t>(a_lo) | ((uint32_t)*lds_ptr<uint16_t>(a_hi) << 16);
+                        wlo[st][u] = *lds_ptr<uint16_t>(a_lo);
+                        whi[st][u] = *lds_ptr<uint16_t>(a_hi);
                     }
-                    const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
 #pragma unroll
                     for (int hf = 0; hf < 2; ++hf) {
-                        const u32x2 lo = lds_read_tr16(xa_lane + s_lo * C::kXRow + hf * 8);
-                        const u32x2 hi = lds_read_tr16(xa_lane + s_hi * C::kXRow + hf * 8);
-                        acc[hf] = mfma_16x16x32<T>(u32x4{lo.x, lo.y, hi.x, hi.y}, bop, acc[hf]);
+                        xlo[st][hf] = lds_read_tr16(xa_lane + s_lo * C::kXRow + hf * 8);
+                        xhi[st][hf] = lds_read_tr16(xa_lane + s_hi * C::kXRow + hf * 8);
                     }
+                };
+                fetch(0, 0);
+#pragma unroll
+                for (int pb = 0; pb < NP; ++pb) {
+                    const int st = pb & 1;
+                    if (pb + 1 < NP) fetch(pb + 1, st ^ 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    uint32_t wv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) wv[u] = (uint32_t)wlo[st][u] | ((uint32_t)whi[st][u] << 16);
+                    const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf)
+                        acc[hf] = mfma_16x16x32<T>(u32x4{xlo[st][hf].x, xlo[st][hf].y, xhi[st][hf].x, xhi[st][hf].y}, bop, acc[hf]);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+            };
+            if (!kProbeMemoryOnly) {   // (measurement build: zeros are stored)
+                if (npairs <= C::NPAIR - 2) pairs(IntC<(C::NPAIR > 2 ? C::NPAIR - 2 : 1)>{});
+                else if (npairs == C::NPAIR - 1) pairs(IntC<C::NPAIR - 1>{});
+                else pairs(IntC<C::NPAIR>{});
             }
             if (jy < H && jx < W) {
                 char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * pitch + g * 16;
@@ -278,6 +335,9 @@ bool inverse_ring_supported(const Problem &p) {
     // a 4 x 4 key patch seen from both clamped ends of an axis at once (axes of at most 2K + 2 positions) has
     // more than K + R + 3 query rows or columns: one MFMA block per row no longer covers it
     if ((p.H < p.W ? p.H : p.W) <= 2 * K + 2) return false;
+    // row offsets inside a plane are 32-bit
+    if ((size_t)p.H * p.W * K * K * p.elem_bytes() >= ((size_t)1 << 31) || (size_t)p.H * p.W * p.D * p.elem_bytes() >= ((size_t)1 << 31))
+        return false;
     for (int ty0 = 0; ty0 < p.H; ty0 += TY) {
         const int ty1 = ty0 + TY - 1 < p.H - 1 ? ty0 + TY - 1 : p.H - 1;
         if (inv_last(ty1, p.H, K) - inv_first(ty0, p.H, K) + 1 > TY + K - 1) return false;
