@@ -40,10 +40,16 @@
  *    correct and deterministic, not tuned).  Head dims
  *    D in {16, 32, 64, 128}.  D = 32 (every NAT variant, Section 3.2) runs the matrix-core
  *    kernels in the 16-bit types; so do the weighted sums (av, grad-q, grad-v, grad-k) for
- *    D = 64 and 128, and the logits, grad-a and the fused forward for D = 64 with k <= 7; the
- *    rest runs tiled plain-ALU kernels while their tiles fit the 160 KB LDS (every k for D = 16
- *    and for D = 64 in the 16-bit types, k <= 9 for D = 128 in the 16-bit types and for D = 64
- *    in fp32, k = 3 for D = 128 in fp32) and the run-time-k kernels otherwise.
+ *    D = 64 and 128, the logits, grad-a and the fused forward for D = 64 with k <= 7, and all
+ *    of these for D = 16 with k <= 7 (a 16-channel head rides in the lower half of the
+ *    32-channel kernels); the rest runs tiled plain-ALU kernels while their tiles fit the
+ *    160 KB LDS (every k for D = 16 and for D = 64 in the 16-bit types, k <= 9 for D = 128 in
+ *    the 16-bit types and for D = 64 in fp32, k = 3 for D = 128 in fp32) and the run-time-k
+ *    kernels otherwise.
+ *  - Inputs are expected to be finite.  The matrix-core kernels multiply values of
+ *    neighbouring positions (up to a tile's query rectangle away) by zero weights instead of
+ *    skipping them, so a NaN or an infinity in q, k, v, dout or a weight tensor can turn
+ *    results of positions beyond its own neighbourhood into NaN.
  *  - Return value: NA2D_OK (0) or a negative na2d_status.  All argument errors are
  *    detected on the host before any HIP call; on error nothing is enqueued.
  */

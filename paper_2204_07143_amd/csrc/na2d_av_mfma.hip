@@ -96,7 +96,8 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
     typename C::Halo halo;
     halo.init(wave, lane);
     int hoff[C::Halo::PER_WAVE];
-    halo.offsets(H, W, hoy, hox, hoff, pitch);
+    const bool half_dim = pitch < Traits<T>::kKeyBytes;   // 16-channel heads: see kHalfDimChunks
+    halo.offsets(H, W, hoy, hox, hoff, pitch, half_dim ? kHalfDimChunks : 3);
     const size_t plane_y = (size_t)H * W * pitch;                  // bytes per plane of y / out
     const size_t plane_w = (size_t)H * W * C::KK * SZ;             // ... of the weights
     const size_t w_bytes = plane_w * heads * nb;
@@ -231,35 +232,54 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
         constexpr int PAR = decltype(par_c)::value;
         if (!active) return;
         f32x4 o[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-        for (int pb = 0; pb < (kProbeMemoryOnly ? 0 : C::NPAIR); ++pb) {   // (measurement build: zeros are stored)
-            uint32_t wv[4];
+        // A pair of halo blocks needs eight gathered weights (the B operand) and four transposing reads of the
+        // values (the A operands of the two channel halves).  The reads of pair pb + 1 are issued before pair pb is
+        // multiplied, and the scheduling fences keep the compiler from sinking them back to their uses: a wave has
+        // twelve reads in flight behind every pair of MFMAs instead of waiting for each pair's reads in turn.
+        uint16_t wlo[2][4], whi[2][4];
+        u32x2 xlo[2][2], xhi[2][2];
+        auto fetch = [&](int pb, int st) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int e = 8 * pb + 2 * u;
                 if (e >= P::NEL) {
-                    wv[u] = 0u;
+                    wlo[st][u] = whi[st][u] = 0;
                     continue;
                 }
                 if constexpr (PACKED) {   // e is even: both addresses sit in one register
                     const uint32_t pk = (uint32_t)gaddr[e >> 1];
                     const int wbase = w0 + cur_phase + PAR * C::kStageBytes;
-                    wv[u] = (uint32_t)*lds_ptr<uint16_t>(wbase + (int)(pk & 0xffffu)) |
-                            ((uint32_t)*lds_ptr<uint16_t>(wbase + (int)(pk >> 16)) << 16);
+                    wlo[st][u] = *lds_ptr<uint16_t>(wbase + (int)(pk & 0xffffu));
+                    whi[st][u] = *lds_ptr<uint16_t>(wbase + (int)(pk >> 16));
                 } else {
-                    wv[u] = (uint32_t)*lds_ptr<uint16_t>(gaddr[e] + PAR * C::kStageBytes) |
-                            ((uint32_t)*lds_ptr<uint16_t>(gaddr[e + 1] + PAR * C::kStageBytes) << 16);
+                    wlo[st][u] = *lds_ptr<uint16_t>(gaddr[e] + PAR * C::kStageBytes);
+                    whi[st][u] = *lds_ptr<uint16_t>(gaddr[e + 1] + PAR * C::kStageBytes);
                 }
             }
-            const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
-                const u32x2 lo = lds_read_tr16(vaddr[2 * pb] + PAR * C::kStageBytes + hf * 8);
-                const u32x2 hi = lds_read_tr16(vaddr[2 * pb + 1 < P::NBLK ? 2 * pb + 1 : P::NBLK - 1] + PAR * C::kStageBytes + hf * 8);
-                o[hf] = mfma_16x16x32<T>(u32x4{lo.x, lo.y, hi.x, hi.y}, bop, o[hf]);
+                xlo[st][hf] = lds_read_tr16(vaddr[2 * pb] + PAR * C::kStageBytes + hf * 8);
+                xhi[st][hf] = lds_read_tr16(vaddr[2 * pb + 1 < P::NBLK ? 2 * pb + 1 : P::NBLK - 1] + PAR * C::kStageBytes + hf * 8);
+            }
+        };
+        if (!kProbeMemoryOnly) {   // (measurement build: zeros are stored)
+            fetch(0, 0);
+#pragma unroll
+            for (int pb = 0; pb < C::NPAIR; ++pb) {
+                const int st = pb & 1;
+                if (pb + 1 < C::NPAIR) fetch(pb + 1, st ^ 1);
+                __builtin_amdgcn_sched_barrier(0);
+                uint32_t wv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) wv[u] = (uint32_t)wlo[st][u] | ((uint32_t)whi[st][u] << 16);
+                const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf)
+                    o[hf] = mfma_16x16x32<T>(u32x4{xlo[st][hf].x, xlo[st][hf].y, xhi[st][hf].x, xhi[st][hf].y}, bop, o[hf]);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        if (q_ok) {
+        if (q_ok && (!half_dim || g < 2)) {
             char *dst = reinterpret_cast<char *>(out) + ((size_t)b * heads + head) * plane_y + (size_t)qlin * pitch + g * 16;
             uint32_t ov[4];
 #pragma unroll
@@ -321,7 +341,7 @@ static hipError_t launch_av_mfma_small_t(const Problem &p, const void *w, const 
     static LdsAllowed allowed;
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     // one launch per 32-channel slice of the head vector (the weights are read again by each)
-    for (int sl = 0; sl < p.D / kHeadDim; ++sl) {
+    for (int sl = 0; sl < (p.D + kHeadDim - 1) / kHeadDim; ++sl) {   // (a 16-channel head is half a slice)
         hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                            static_cast<const T *>(w), static_cast<const T *>(y) + sl * kHeadDim, scale,
                            static_cast<T *>(out) + sl * kHeadDim, rpb_partial, p.H, p.W, p.heads, p.B, tiles_y, us.units,
@@ -358,7 +378,7 @@ hipError_t launch_av_rpb(const Problem &p, const void *w, const void *y, float s
 
 bool av_mfma_supported(const Problem &p) {
     // any multiple of 32 channels: one launch per 32-channel slice
-    return p.dtype != NA2D_F32 && p.D % kHeadDim == 0 && p.K <= kMaxTunedK;
+    return p.dtype != NA2D_F32 && (p.D % kHeadDim == 0 || (p.D == kHalfDim && p.K <= 7)) && p.K <= kMaxTunedK;
 }
 
 hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s) {

@@ -14,6 +14,14 @@
 namespace na2d {
 
 constexpr int kHeadDim = 32;       // D of every NAT variant (Section 3.2): the matrix-core kernels are built for it
+// 16-channel heads on the 32-channel matrix-core kernels (16-bit types, small windows): a position's 32 bytes are
+// copied into both halves of its 64-byte slot in LDS (chunk index & kHalfDimChunks).  Where the contraction runs
+// over channels (logits, grad-a) the query operand of the lanes that hold channels 16..31 is zero, so the copy
+// meets zeros; where channels are independent (weighted sums) the upper 16 results repeat the lower ones and only
+// the lanes with channels 0..15 store.  Twice the matrix-core and LDS work the head needs, on pipelines that are
+// bound by neither; the plain-ALU kernels this replaces were three to six times slower.
+constexpr int kHalfDim = 16;
+constexpr int kHalfDimChunks = 1;
 constexpr int kWave = 64;          // CDNA wavefront width
 
 // ---- neighbourhood index functions (one axis of length L, odd window K <= L) -----------

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
                                                                   const T *__restrict__ v, const T *__restrict__ rpb,
                                                                   float scale, T *__restrict__ out, float *__restrict__ lse,
                                                                   int H, int W, int heads, int nb, int tiles_y, int units,
-                                                                  int splits, GridDecode gd) {
+                                                                  int splits, GridDecode gd, int half_dim) {
     using C = FusedSmallCfg<T, K, NS>;
     using P = Patch<K>;
     static_assert(C::kThreads == 512, "launch bounds");
@@ -99,9 +99,11 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
     typename C::Halo halo;
     halo.init(wave, lane);
     int hoff[C::Halo::PER_WAVE];
-    halo.offsets(H, W, hoy, hox, hoff, C::kKeyBytesG);
+    // (half_dim: 16-channel heads, NS = 1; see kHalfDimChunks)
+    const int pitch = half_dim ? C::kKeyBytesG / 2 : C::kKeyBytesG, chunk_mask = half_dim ? kHalfDimChunks : 3;
+    halo.offsets(H, W, hoy, hox, hoff, pitch, chunk_mask);
     const int qlin = (qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1);   // this lane's query inside a plane
-    const size_t plane_bytes = (size_t)H * W * C::kKeyBytesG;
+    const size_t plane_bytes = (size_t)H * W * pitch;
     u32x4 qnext[NS];
     auto issue = [&](int b, int par) {
         const size_t off = ((size_t)b * heads + head) * plane_bytes;
@@ -111,7 +113,7 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
             C::Halo::issue_at(reinterpret_cast<const char *>(k) + so, hoff, lds0 + par * C::kStageBytes + sl * C::kHaloBytes, wave);
             C::Halo::issue_at(reinterpret_cast<const char *>(v) + so, hoff,
                               lds0 + par * C::kStageBytes + (NS + sl) * C::kHaloBytes, wave);
-            qnext[sl] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(q) + so + (size_t)qlin * C::kKeyBytesG + g * 16);
+            qnext[sl] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(q) + so + (size_t)qlin * pitch + (g & chunk_mask) * 16);
         }
     };
     issue(b_begin, 0);
@@ -237,10 +239,10 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
             }
         }
         // 5. normalise and store this lane's 8 channels (8g .. 8g + 7) of its own query
-        if (q_ok) {
+        if (q_ok && (!half_dim || g < 2)) {
             const float inv = __builtin_amdgcn_rcpf(l);   // 1 ulp; the result is rounded to 11 or 8 bits
             const size_t plane = (size_t)b * heads + head;
-            char *dst = reinterpret_cast<char *>(out) + plane * plane_bytes + (size_t)qlin * C::kKeyBytesG + g * 16;
+            char *dst = reinterpret_cast<char *>(out) + plane * plane_bytes + (size_t)qlin * pitch + g * 16;
 #pragma unroll
             for (int sl = 0; sl < NS; ++sl)   // channels 32 sl + 8g .. + 7
                 store16_stream(dst + sl * Traits<T>::kKeyBytes,
@@ -257,7 +259,7 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
         workgroup_sync();       // ... for every wave, and nobody still reads the other buffer pair
         u32x4 qreg[NS];
 #pragma unroll
-        for (int sl = 0; sl < NS; ++sl) qreg[sl] = qnext[sl];
+        for (int sl = 0; sl < NS; ++sl) qreg[sl] = (half_dim && g >= 2) ? u32x4{0u, 0u, 0u, 0u} : qnext[sl];
         if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
         compute(par_c, qreg, b);
         ++b;
@@ -282,7 +284,7 @@ static hipError_t launch_fused_mfma_small_ns(const Problem &p, const void *q, co
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
                        static_cast<const T *>(rpb), scale, static_cast<T *>(out), lse, p.H, p.W, p.heads, p.B, tiles_y,
-                       us.units, us.splits, us.gd);
+                       us.units, us.splits, us.gd, p.D == kHalfDim ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -297,7 +299,7 @@ static hipError_t launch_fused_mfma_small_t(const Problem &p, const void *q, con
 
 bool fused_mfma_supported(const Problem &p) {
     if (p.dtype == NA2D_F32 || p.K > kMaxTunedK) return false;
-    return p.D == kHeadDim || (p.D == 2 * kHeadDim && p.K <= 7);   // two slices only in the small-window kernel
+    return p.D == kHeadDim || ((p.D == 2 * kHeadDim || p.D == kHalfDim) && p.K <= 7);   // two slices, or half a slice, only in the small-window kernel
 }
 
 hipError_t launch_fused_mfma(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,

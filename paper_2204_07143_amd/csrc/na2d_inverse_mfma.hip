@@ -123,7 +123,8 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
     XHalo xhalo;
     xhalo.init(wave, lane);
     int xoff[XHalo::PER_WAVE];
-    xhalo.offsets(H, W, ry0, rx0, xoff, pitch);
+    const bool half_dim = pitch < Traits<T>::kKeyBytes;   // 16-channel heads: see kHalfDimChunks
+    xhalo.offsets(H, W, ry0, rx0, xoff, pitch, half_dim ? kHalfDimChunks : 3);
 
     const int strip = wave / C::NWPS;
     const int sy0 = ty0 + 4 * strip;              // first key row of this wave's strip
@@ -262,7 +263,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
 #pragma unroll
         for (int p = 0; p < PPW; ++p) {
             const int jx = tx0 + 4 * (p0 + p) + kx;
-            if (jy < H && jx < W) {
+            if (jy < H && jx < W && (!half_dim || g < 2)) {
                 char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * pitch + g * 16;
                 uint32_t o[4];
 #pragma unroll
@@ -293,7 +294,7 @@ static hipError_t launch_inverse_mfma_c(const Problem &p, const void *w, const v
     auto kern = inverse_mfma_kernel<T, K, STRIPS, PPW, COMPACT>;
     static LdsAllowed allowed;
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
-    for (int sl = 0; sl < p.D / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector
+    for (int sl = 0; sl < (p.D + kHeadDim - 1) / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector (a 16-channel head is half a slice)
         hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s,
                            static_cast<const T *>(w), static_cast<const T *>(x) + sl * kHeadDim, scale,
                            static_cast<T *>(out) + sl * kHeadDim, p.H, p.W, p.heads, p.B, tiles_y, units, splits, gd,
@@ -332,7 +333,7 @@ static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const v
 bool inverse_mfma_supported(const Problem &p) {
     const int shortest = p.H < p.W ? p.H : p.W;
     const int R = p.K / 2;
-    return p.D % kHeadDim == 0 && p.dtype != NA2D_F32 && p.K <= 9 && shortest > 2 * p.K + 2 && rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
+    return (p.D % kHeadDim == 0 || (p.D == kHalfDim && p.K <= 7)) && p.dtype != NA2D_F32 && p.K <= 9 && shortest > 2 * p.K + 2 && rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
 }
 
 hipError_t launch_inverse_mfma(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s) {

@@ -95,13 +95,14 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
     const int wrow_bytes = ncols * C::KK * SZ;
 
     // x loads of a row: this lane's chunks, as byte offsets inside a query row (columns clamped into the map)
+    const bool half_dim = pitch < C::KB;   // 16-channel heads: see kHalfDimChunks
     int xcol[C::kXItems];
 #pragma unroll
     for (int j = 0; j < C::kXItems; ++j) {
         const int q = j * kWave + lane;
         int xx = rx0 + q / (C::KB / 16);
         xx = xx < W - 1 ? xx : W - 1;
-        xcol[j] = q < C::RW * (C::KB / 16) ? xx * pitch + (q % (C::KB / 16)) * 16 : -1;
+        xcol[j] = q < C::RW * (C::KB / 16) ? xx * pitch + ((q % (C::KB / 16)) & (half_dim ? kHalfDimChunks : 3)) * 16 : -1;
     }
     // Loads the query rows [r_begin, r_end) into their ring slots: row r_begin + wave, + WAVES, ... per wave.  All of a
     // row's address arithmetic is wave-uniform and 32 bits wide from the plane's base pointers on (a plane of either
@@ -288,7 +289,7 @@ __global__ __launch_bounds__(512, 4) void inverse_ring_kernel(const T *__restric
                 else if (npairs == C::NPAIR - 1) pairs(IntC<C::NPAIR - 1>{});
                 else pairs(IntC<C::NPAIR>{});
             }
-            if (jy < H && jx < W) {
+            if (jy < H && jx < W && (!half_dim || g < 2)) {
                 char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jy * W + jx) * pitch + g * 16;
                 uint32_t o[4];
 #pragma unroll
@@ -317,7 +318,7 @@ static hipError_t launch_inverse_ring_t(const Problem &p, const void *w, const v
     auto kern = inverse_ring_kernel<T, K>;
     static LdsAllowed allowed;
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
-    for (int sl = 0; sl < p.D / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector
+    for (int sl = 0; sl < (p.D + kHeadDim - 1) / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector (a 16-channel head is half a slice)
         hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(nwg)), dim3(C::kThreads), C::kLdsBytes, s, static_cast<const T *>(w),
                            static_cast<const T *>(x) + sl * kHeadDim, scale, static_cast<T *>(out) + sl * kHeadDim, p.H, p.W,
                            tiles_x, tiles_y, p.planes(), nseg, make_fastdiv(tiles_x), make_fastdiv(nseg),
@@ -330,7 +331,7 @@ static hipError_t launch_inverse_ring_t(const Problem &p, const void *w, const v
 // The ring holds 8 + K-1 rows per tile: every tile's query rectangle must fit that (and 16 + K-1 columns), which
 // excludes maps with a tile next to the far border whose clamped queries reach further (the tile kernel takes those).
 bool inverse_ring_supported(const Problem &p) {
-    if (p.D % kHeadDim != 0 || p.dtype == NA2D_F32 || p.K > 7) return false;
+    if ((p.D % kHeadDim != 0 && p.D != kHalfDim) || p.dtype == NA2D_F32 || p.K > 7) return false;
     const int K = p.K, TY = 8;
     // a 4 x 4 key patch seen from both clamped ends of an axis at once (axes of at most 2K + 2 positions) has
     // more than K + R + 3 query rows or columns: one MFMA block per row no longer covers it

@@ -120,13 +120,14 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
     const int xa_lane = (oqx - rx0 + 4 * g + (n >> 2)) * C::KB + (n & 3) * 16;
 
     // loads: this lane's x chunks of a row, as byte offsets inside a query row (columns clamped into the map)
+    const bool half_dim = pitch < C::KB;   // 16-channel heads: see kHalfDimChunks
     int xcol[C::kXItems];
 #pragma unroll
     for (int j = 0; j < C::kXItems; ++j) {
         const int q = j * kWave + lane;
         int xx = rx0 + q / (C::KB / 16);
         xx = xx < W - 1 ? xx : W - 1;
-        xcol[j] = q < C::RW * (C::KB / 16) ? xx * pitch + (q % (C::KB / 16)) * 16 : -1;
+        xcol[j] = q < C::RW * (C::KB / 16) ? xx * pitch + ((q % (C::KB / 16)) & (half_dim ? kHalfDimChunks : 3)) * 16 : -1;
     }
     // Loads pair `pr` of plane `b` into stage `par`: the stage's load instructions (per row: the weight row,
     // mirrored at its 16-byte phase, then the x vectors) are dealt round-robin to the waves.
@@ -220,7 +221,7 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
 #pragma unroll
                 for (int np = 0; np < NP; ++np) {
                     const int jyp = patch_row0(np) + ky;
-                    if (jyp < H && jx < W) {
+                    if (jyp < H && jx < W && (!half_dim || g < 2)) {
                         char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jyp * W + jx) * pitch + g * 16;
                         uint32_t o[4];
 #pragma unroll
@@ -265,7 +266,7 @@ static hipError_t launch_inverse_rows_np(const Problem &p, const void *w, const 
     auto kern = inverse_rows_kernel<T, K, NP>;
     static LdsAllowed allowed;
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
-    for (int sl = 0; sl < p.D / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector
+    for (int sl = 0; sl < (p.D + kHeadDim - 1) / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector (a 16-channel head is half a slice)
         hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                            static_cast<const T *>(w), static_cast<const T *>(x) + sl * kHeadDim, scale,
                            static_cast<T *>(out) + sl * kHeadDim, p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd,
@@ -292,7 +293,7 @@ static hipError_t launch_inverse_rows_t(const Problem &p, const void *w, const v
 // patch must be seen from at most 16 NCB columns: both hold for every map with K <= min(H, W) (a tile next to both
 // ends of a short axis has at most W <= 2K + 2 columns).  Checked anyway.
 bool inverse_rows_supported(const Problem &p) {
-    if (p.D % kHeadDim != 0 || p.dtype == NA2D_F32) return false;
+    if ((p.D % kHeadDim != 0 && !(p.D == kHalfDim && p.K <= 7)) || p.dtype == NA2D_F32) return false;
     const int K = p.K, RW = kTileX + K - 1 + K / 2, NCOL = 16 * ((K + K / 2 + 3 + 15) / 16);
     if ((int64_t)p.W * K * K * 4 >= (int64_t)1 << 31) return false;   // a row of weights as a 32-bit byte count
     for (int tx0 = 0; tx0 < p.W; tx0 += kTileX) {

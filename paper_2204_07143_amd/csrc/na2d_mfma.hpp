@@ -140,15 +140,17 @@ struct HaloDma {
     // Split form for loops that copy the same rectangle of many planes: the clamped byte offsets of
     // this lane's chunks inside a plane (-1: nothing), then one load per item from a plane's base.
     // `pitch`: bytes between consecutive positions in memory (more than 64 when the 32 channels copied are a
-    // slice of a longer head vector).
+    // slice of a longer head vector).  `chunk_mask` 1 serves 16-channel heads (pitch 32): the two 16-byte
+    // chunks of a position are copied twice, into the lower and the upper half of its 64-byte slot (see
+    // kHalfDimChunks).
     __device__ __forceinline__ void offsets(int H, int W, int oy, int ox, int (&off)[PER_WAVE],
-                                            int pitch = Traits<T>::kKeyBytes) const {
+                                            int pitch = Traits<T>::kKeyBytes, int chunk_mask = 3) const {
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             int y = oy + (pos[i] & 0xff), x = ox + ((pos[i] >> 8) & 0xff);
             y = y < 0 ? 0 : (y < H - 1 ? y : H - 1);
             x = x < 0 ? 0 : (x < W - 1 ? x : W - 1);
-            off[i] = pos[i] >= 0 ? (y * W + x) * pitch + (pos[i] >> 16) * 16 : -1;
+            off[i] = pos[i] >= 0 ? (y * W + x) * pitch + ((pos[i] >> 16) & chunk_mask) * 16 : -1;
         }
     }
     __device__ static __forceinline__ void issue_at(const char *plane_base, const int (&off)[PER_WAVE], int lds_base, int wave) {

@@ -86,7 +86,7 @@ __device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, in
 template <typename T, int K, int NS>
 __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk_mfma_small_kernel(
     const T *__restrict__ x, const T *__restrict__ y, const T *__restrict__ rpb, float scale, T *__restrict__ logits, int H,
-    int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd) {
+    int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd, int half_dim) {
     using C = QkSmallCfg<T, K, NS>;
     using P = Patch<K>;
     constexpr int kFlushPasses = (C::kRowBytes + kWave * 16 - 1) / (kWave * 16);   // 16-byte chunks per lane and row run
@@ -128,9 +128,11 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
     typename C::Halo halo;
     halo.init(wave, lane);
     int hoff[C::Halo::PER_WAVE];
-    halo.offsets(H, W, hoy, hox, hoff, C::kKeyBytesG);
-    const int qoff = ((qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1)) * C::kKeyBytesG + g * 16;
-    const size_t plane_in = (size_t)H * W * C::kKeyBytesG;          // bytes per plane of x / y
+    // (half_dim: 16-channel heads, NS = 1; see kHalfDimChunks)
+    const int pitch = half_dim ? C::kKeyBytesG / 2 : C::kKeyBytesG, chunk_mask = half_dim ? kHalfDimChunks : 3;
+    halo.offsets(H, W, hoy, hox, hoff, pitch, chunk_mask);
+    const int qoff = ((qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1)) * pitch + (g & chunk_mask) * 16;
+    const size_t plane_in = (size_t)H * W * pitch;          // bytes per plane of x / y
     const size_t plane_out = (size_t)H * W * C::KK * SZ;            // ... of the logits
     // stores: wave w streams row w of the tile
     const int frow = ty0 + wave;
@@ -280,7 +282,7 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
         workgroup_sync();       // ... for every wave; the previous tile is fully staged, its halo no longer read
         u32x4 qreg[NS];
 #pragma unroll
-        for (int sl = 0; sl < NS; ++sl) qreg[sl] = qnext[sl];
+        for (int sl = 0; sl < NS; ++sl) qreg[sl] = (half_dim && g >= 2) ? u32x4{0u, 0u, 0u, 0u} : qnext[sl];
         if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
         if (b > b_begin) flush(b - 1, PAR ^ 1);
         compute(par_c, qreg);
@@ -307,7 +309,8 @@ static hipError_t launch_qk_mfma_small_ns(const Problem &p, const void *x, const
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(x), static_cast<const T *>(y), static_cast<const T *>(rpb), scale,
-                       static_cast<T *>(logits), p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd);
+                       static_cast<T *>(logits), p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd,
+                       p.D == kHalfDim ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -322,7 +325,7 @@ static hipError_t launch_qk_mfma_small_t(const Problem &p, const void *x, const 
 
 bool qk_mfma_supported(const Problem &p) {
     if (p.dtype == NA2D_F32 || p.K > kMaxTunedK) return false;
-    return p.D == kHeadDim || (p.D == 2 * kHeadDim && p.K <= 7);   // two slices only in the small-window kernel
+    return p.D == kHeadDim || ((p.D == 2 * kHeadDim || p.D == kHalfDim) && p.K <= 7);   // two slices, or half a slice, only in the small-window kernel
 }
 
 hipError_t launch_qk_mfma(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,

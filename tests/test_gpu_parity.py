@@ -350,6 +350,16 @@ def test_generic_head_dims(oracle, dtype, D, k):
     run_all(oracle, p, seed=9000 + D + k)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("H,W,k", [(56, 56, 7), (30, 45, 5), (21, 37, 3), (14, 14, 7), (7, 7, 7), (9, 40, 7)])
+def test_sixteen_channel_heads_on_the_matrix_cores(oracle, dtype, H, W, k):
+    # 16-channel heads with k <= 7 ride in the lower half of the 32-channel matrix-core kernels: maps with several
+    # tiles and ragged borders (the column-walking grad-v / grad-k kernel), maps whose shortest side is at most
+    # 2k + 2 (the tile kernel or the row-streaming one), a bias that matters, every plane
+    p = synth.Problem(3, 4, H, W, 16, k, dtype)
+    run_all(oracle, p, seed=9500 + H + W + k, rpb_std=1.0, e2e_unfused=False)
+
+
 def test_head_dims_the_library_does_not_take():
     q = torch.zeros((1, 1, 14, 14, 48), dtype=torch.float16, device="cuda")
     with pytest.raises(na.Na2dError) as e:
