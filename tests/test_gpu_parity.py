@@ -360,6 +360,28 @@ def test_sixteen_channel_heads_on_the_matrix_cores(oracle, dtype, H, W, k):
     run_all(oracle, p, seed=9500 + H + W + k, rpb_std=1.0, e2e_unfused=False)
 
 
+def _seeded_shapes(n, seed):
+    """n problems drawn from a fixed seed: sides from k to 70 (so that windows clamp on either or both axes, tiles are
+    ragged and maps shorter than 2k + 2 occur), every tuned k, three head dims, three dtypes, small odd batches."""
+    rng = np.random.RandomState(seed)
+    out = []
+    for i in range(n):
+        k = int(rng.choice([3, 5, 7, 9, 11, 13]))
+        H, W = (int(rng.randint(k, 71)) for _ in range(2))
+        if i % 5 == 0:
+            H = k + int(rng.randint(0, 3))   # one axis barely longer than the window
+        D = int(rng.choice([16, 32, 32, 64]))
+        dtype = ["f32", "f16", "bf16"][i % 3]
+        out.append((int(rng.randint(1, 6)), int(rng.randint(1, 4)), H, W, D, k, dtype))
+    return out
+
+
+@pytest.mark.parametrize("B,heads,H,W,D,k,dtype", _seeded_shapes(36, 20260))
+def test_seeded_random_shapes(oracle, B, heads, H, W, D, k, dtype):
+    p = synth.Problem(B, heads, H, W, D, k, dtype)
+    run_all(oracle, p, seed=31000 + 71 * H + W + k + D)
+
+
 def test_head_dims_the_library_does_not_take():
     q = torch.zeros((1, 1, 14, 14, 48), dtype=torch.float16, device="cuda")
     with pytest.raises(na.Na2dError) as e:
