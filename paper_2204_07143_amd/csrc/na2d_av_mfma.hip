@@ -352,7 +352,7 @@ static hipError_t launch_av_mfma_small_t(const Problem &p, const void *w, const 
 }
 
 // grad-q together with partial bias gradients (one per workgroup, av_rpb_partials() of them)
-bool av_rpb_supported(const Problem &p) { return p.D == kHeadDim && p.dtype != NA2D_F32 && p.K <= 7; }
+bool av_rpb_supported(const Problem &p) { return (p.D == kHeadDim || p.D == kHalfDim) && p.dtype != NA2D_F32 && p.K <= 7; }
 AvRpbSplit av_rpb_split(const Problem &p) {
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + 8 - 1) / 8;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);

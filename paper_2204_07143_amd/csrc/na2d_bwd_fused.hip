@@ -48,7 +48,8 @@ struct BwdFusedCfg {
 template <typename T, int K>
 __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__restrict__ attn, const T *__restrict__ dout,
                                                                  const T *__restrict__ v, T *__restrict__ ds, int H, int W,
-                                                                 int heads, int nb, int tiles_y, int units, int splits, GridDecode gd) {
+                                                                 int heads, int nb, int tiles_y, int units, int splits, GridDecode gd,
+                                                                 int half_dim) {
     using C = BwdFusedCfg<T, K>;
     using P = Patch<K>;
     static_assert(C::kThreads == 512, "launch bounds");
@@ -81,8 +82,10 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
     typename C::Halo halo;
     halo.init(wave, lane);
     int hoff[C::Halo::PER_WAVE];
-    halo.offsets(H, W, hoy, hox, hoff);
-    const size_t plane_y = (size_t)H * W * Traits<T>::kKeyBytes;   // bytes per plane of dout / v / k / dq
+    // (half_dim: 16-channel heads; see kHalfDimChunks)
+    const int pitch = half_dim ? Traits<T>::kKeyBytes / 2 : Traits<T>::kKeyBytes, chunk_mask = half_dim ? kHalfDimChunks : 3;
+    halo.offsets(H, W, hoy, hox, hoff, pitch, chunk_mask);
+    const size_t plane_y = (size_t)H * W * pitch;   // bytes per plane of dout / v / k / dq
     const size_t plane_w = (size_t)H * W * C::KK * SZ;             // ... of attn / ds
     const int wrow = ty0 + wave;
     const int wrow_bytes = ((W - tx0) < kTileX ? (W - tx0) : kTileX) * C::KK * SZ;
@@ -116,8 +119,9 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
     // this lane's 16 bytes of dout of its query (B operand); the next plane's are loaded as soon as the
     // MFMAs of the current plane have consumed the register
     auto load_dout = [&](int b) {
-        return *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(dout) + ((size_t)b * heads + head) * plane_y +
-                                                qlin * Traits<T>::kKeyBytes + g * 16);
+        const u32x4 d = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(dout) + ((size_t)b * heads + head) * plane_y +
+                                                         qlin * pitch + (g & chunk_mask) * 16);
+        return (half_dim && g >= 2) ? u32x4{0u, 0u, 0u, 0u} : d;
     };
     *lds_ptr<uint32_t>(my_zero) = 0u;
     *lds_ptr<uint32_t>(my_zero + C::kStageBytes) = 0u;
@@ -248,11 +252,12 @@ static hipError_t launch_bwd_fused_t(const Problem &p, const void *attn, const v
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(attn), static_cast<const T *>(dout), static_cast<const T *>(v),
-                       static_cast<T *>(ds), p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd);
+                       static_cast<T *>(ds), p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd,
+                       p.D == kHalfDim ? 1 : 0);
     return hipGetLastError();
 }
 
-bool bwd_fused_supported(const Problem &p) { return p.D == kHeadDim && p.dtype != NA2D_F32 && p.K <= 7; }
+bool bwd_fused_supported(const Problem &p) { return (p.D == kHeadDim || p.D == kHalfDim) && p.dtype != NA2D_F32 && p.K <= 7; }
 
 hipError_t launch_bwd_fused(const Problem &p, const void *attn, const void *dout, const void *v, void *ds, hipStream_t s) {
 #define NA2D_BWDF_K(TT)                                                                                   \

@@ -80,7 +80,8 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
                                                         T *__restrict__ dq,
                                                         float *__restrict__ delta_out, float *__restrict__ lse2_out,
                                                         float *__restrict__ rpb_partial,
-                                                        int H, int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd) {
+                                                        int H, int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd,
+                                                        int half_dim) {
     using C = FbwdQCfg<T, K>;
     using P = Patch<K>;
     static_assert(C::kThreads == 512, "launch bounds");
@@ -113,9 +114,11 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
     typename C::Halo halo;
     halo.init(wave, lane);
     int hoff[C::Halo::PER_WAVE];
-    halo.offsets(H, W, hoy, hox, hoff);
+    // (half_dim: 16-channel heads; see kHalfDimChunks)
+    const int pitch = half_dim ? Traits<T>::kKeyBytes / 2 : Traits<T>::kKeyBytes, chunk_mask = half_dim ? kHalfDimChunks : 3;
+    halo.offsets(H, W, hoy, hox, hoff, pitch, chunk_mask);
     const int qlin = (qy < H - 1 ? qy : H - 1) * W + (qx < W - 1 ? qx : W - 1);   // this lane's query inside a plane
-    const size_t plane_bytes = (size_t)H * W * Traits<T>::kKeyBytes;
+    const size_t plane_bytes = (size_t)H * W * pitch;
     // per plane: both halos into LDS; this lane's 16 bytes (channels 8g .. 8g + 7) of q and dout of its query
     // and the query's log-sum-exp into registers
     u32x4 qnext, dnext;
@@ -125,7 +128,7 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
         const size_t off = plane * plane_bytes;
         C::Halo::issue_at(reinterpret_cast<const char *>(k) + off, hoff, lds0 + par * C::kStageBytes, wave);
         C::Halo::issue_at(reinterpret_cast<const char *>(v) + off, hoff, lds0 + par * C::kStageBytes + C::kHaloBytes, wave);
-        const size_t qo = off + qlin * Traits<T>::kKeyBytes + g * 16;
+        const size_t qo = off + qlin * pitch + (g & chunk_mask) * 16;
         qnext = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(q) + qo);
         dnext = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(dout) + qo);
         lnext = lse[plane * H * W + qlin];
@@ -296,9 +299,10 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
         }
         if (q_ok) {
             const size_t plane = (size_t)b * heads + head;
-            char *dst = reinterpret_cast<char *>(dq) + plane * plane_bytes + qlin * Traits<T>::kKeyBytes + g * 16;
-            store16_stream(dst, u32x4{pack2_t<T>(o[0][0] * scale, o[0][1] * scale), pack2_t<T>(o[0][2] * scale, o[0][3] * scale),
-                                      pack2_t<T>(o[1][0] * scale, o[1][1] * scale), pack2_t<T>(o[1][2] * scale, o[1][3] * scale)});
+            char *dst = reinterpret_cast<char *>(dq) + plane * plane_bytes + qlin * pitch + g * 16;
+            if (!half_dim || g < 2)
+                store16_stream(dst, u32x4{pack2_t<T>(o[0][0] * scale, o[0][1] * scale), pack2_t<T>(o[0][2] * scale, o[0][3] * scale),
+                                          pack2_t<T>(o[1][0] * scale, o[1][1] * scale), pack2_t<T>(o[1][2] * scale, o[1][3] * scale)});
             if (g == 0) {   // for the key-patch kernel: delta, and the log-sum-exp in the exp2 domain
                 delta_out[plane * H * W + qlin] = delta;
                 lse2_out[plane * H * W + qlin] = lse2;
@@ -311,7 +315,8 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
         constexpr int PAR = decltype(par_c)::value;
         wait_global_loads();   // this tile's halos and the lane's query data have landed
         workgroup_sync();       // ... for every wave, and nobody still reads the other buffer pair
-        const u32x4 qreg = qnext, dreg = dnext;
+        const bool upper = half_dim && g >= 2;   // lanes whose channels a 16-channel head does not have
+        const u32x4 qreg = upper ? u32x4{0u, 0u, 0u, 0u} : qnext, dreg = upper ? u32x4{0u, 0u, 0u, 0u} : dnext;
         const float lse2 = lnext * kLog2e;
         if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
         compute(par_c, qreg, dreg, lse2, b);
@@ -349,7 +354,7 @@ static hipError_t launch_fbwd_q_t(const Problem &p, const void *q, const void *k
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
                        static_cast<const T *>(rpb), scale, lse, static_cast<const T *>(dout), static_cast<T *>(dq), delta, lse2,
-                       rpb_partial, p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd);
+                       rpb_partial, p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd, p.D == kHalfDim ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -404,7 +409,7 @@ template <typename T, int K, bool COMPACT>
 __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) void fbwd_kv_kernel(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, const T *__restrict__ rpb, float scale,
     const float *__restrict__ lse2, const float *__restrict__ delta, const T *__restrict__ dout, T *__restrict__ dk,
-    T *__restrict__ dv, int H, int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd) {
+    T *__restrict__ dv, int H, int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd, int half_dim) {
     // lse2: the log-sum-exp of every query times log2(e), as the query-patch kernel left it beside delta
     using C = FbwdKvCfg<T, K, COMPACT>;
     using XHalo = typename C::XHalo;
@@ -447,7 +452,9 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
     XHalo xhalo;
     xhalo.init(wave, lane);
     int xoff[XHalo::PER_WAVE];
-    xhalo.offsets(H, W, ry0, rx0, xoff);
+    // (half_dim: 16-channel heads; see kHalfDimChunks)
+    const int pitch = half_dim ? KB / 2 : KB, chunk_mask = half_dim ? kHalfDimChunks : 3;
+    xhalo.offsets(H, W, ry0, rx0, xoff, pitch, chunk_mask);
     int soff;   // this lane's word of the fp32 images (waves 0 .. kSItems-1), clamped into the map
     {
         const int i = wave * kWave + lane;
@@ -501,16 +508,18 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
     for (int b = b_begin; b < b_end; ++b) {
         const size_t plane = (size_t)b * heads + head;
         if (b > b_begin) workgroup_sync();   // the previous plane's images are no longer read
-        XHalo::issue_at(reinterpret_cast<const char *>(q) + plane * plane_px * KB, xoff, q0, wave);
-        XHalo::issue_at(reinterpret_cast<const char *>(dout) + plane * plane_px * KB, xoff, d0, wave);
+        XHalo::issue_at(reinterpret_cast<const char *>(q) + plane * plane_px * pitch, xoff, q0, wave);
+        XHalo::issue_at(reinterpret_cast<const char *>(dout) + plane * plane_px * pitch, xoff, d0, wave);
         if (wave < C::kSItems) {
             global_to_lds_4(reinterpret_cast<const char *>(lse2) + plane * plane_px * 4, (unsigned)soff, l0 + wave * kWave * 4);
             global_to_lds_4(reinterpret_cast<const char *>(delta) + plane * plane_px * 4, (unsigned)soff, e0 + wave * kWave * 4);
         }
         // the lane's key and value: bytes [16g, 16g+16) (B operands)
-        const size_t koff = (plane * plane_px + (size_t)(jy < H ? jy : H - 1) * W + (jx < W ? jx : W - 1)) * KB + g * 16;
-        const u32x4 kreg = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(k) + koff);
-        const u32x4 vreg = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(v) + koff);
+        const size_t koff = (plane * plane_px + (size_t)(jy < H ? jy : H - 1) * W + (jx < W ? jx : W - 1)) * pitch + (g & chunk_mask) * 16;
+        const bool upper = half_dim && g >= 2;   // lanes whose channels a 16-channel head does not have
+        const u32x4 kload = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(k) + koff);
+        const u32x4 vload = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(v) + koff);
+        const u32x4 kreg = upper ? u32x4{0u, 0u, 0u, 0u} : kload, vreg = upper ? u32x4{0u, 0u, 0u, 0u} : vload;
         wait_global_loads();
         workgroup_sync();
         if (!active) continue;
@@ -561,8 +570,8 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
                 }
             }
         }
-        if (key_ok) {
-            const size_t o = (plane * plane_px + (size_t)jy * W + jx) * KB + g * 16;
+        if (key_ok && !upper) {
+            const size_t o = (plane * plane_px + (size_t)jy * W + jx) * pitch + g * 16;
             store16_stream(reinterpret_cast<char *>(dk) + o,
                            u32x4{pack2_t<T>(ak[0][0] * scale, ak[0][1] * scale), pack2_t<T>(ak[0][2] * scale, ak[0][3] * scale),
                                  pack2_t<T>(ak[1][0] * scale, ak[1][1] * scale), pack2_t<T>(ak[1][2] * scale, ak[1][3] * scale)});
@@ -602,7 +611,8 @@ static hipError_t launch_fbwd_kv_c(const Problem &p, const void *q, const void *
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(units * splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(q), static_cast<const T *>(k), static_cast<const T *>(v),
                        static_cast<const T *>(rpb), scale, lse, delta, static_cast<const T *>(dout), static_cast<T *>(dk),
-                       static_cast<T *>(dv), p.H, p.W, p.heads, p.B, tiles_y, units, splits, make_grid_decode(tiles_x, tiles_y, p.heads, p.B, splits));
+                       static_cast<T *>(dv), p.H, p.W, p.heads, p.B, tiles_y, units, splits, make_grid_decode(tiles_x, tiles_y, p.heads, p.B, splits),
+                       p.D == kHalfDim ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -635,7 +645,7 @@ hipError_t launch_fbwd_kv(const Problem &p, const void *q, const void *k, const 
 // close to both borders) does not fit, and such maps take the unfused steps instead.
 bool fused_bwd_supported(const Problem &p) {
     const int R = p.K / 2;
-    return p.D == kHeadDim && p.dtype != NA2D_F32 && p.K <= 7 && kv_rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
+    return (p.D == kHeadDim || p.D == kHalfDim) && p.dtype != NA2D_F32 && p.K <= 7 && kv_rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
 }
 
 AvRpbSplit fused_bwd_split(const Problem &p) {
