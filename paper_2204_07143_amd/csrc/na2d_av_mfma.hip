@@ -378,7 +378,7 @@ hipError_t launch_av_rpb(const Problem &p, const void *w, const void *y, float s
 
 bool av_mfma_supported(const Problem &p) {
     // any multiple of 32 channels: one launch per 32-channel slice
-    return p.dtype != NA2D_F32 && (p.D % kHeadDim == 0 || (p.D == kHalfDim && p.K <= 7)) && p.K <= kMaxTunedK;
+    return p.dtype != NA2D_F32 && (p.D % kHeadDim == 0 || p.D == kHalfDim) && p.K <= kMaxTunedK;
 }
 
 hipError_t launch_av_mfma(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s) {

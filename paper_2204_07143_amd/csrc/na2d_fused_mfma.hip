@@ -299,7 +299,7 @@ static hipError_t launch_fused_mfma_small_t(const Problem &p, const void *q, con
 
 bool fused_mfma_supported(const Problem &p) {
     if (p.dtype == NA2D_F32 || p.K > kMaxTunedK) return false;
-    return p.D == kHeadDim || ((p.D == 2 * kHeadDim || p.D == kHalfDim) && p.K <= 7);   // two slices, or half a slice, only in the small-window kernel
+    return p.D == kHeadDim || p.D == kHalfDim || (p.D == 2 * kHeadDim && p.K <= 7);   // two slices only in the small-window kernel
 }
 
 hipError_t launch_fused_mfma(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,

@@ -333,7 +333,7 @@ static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const v
 bool inverse_mfma_supported(const Problem &p) {
     const int shortest = p.H < p.W ? p.H : p.W;
     const int R = p.K / 2;
-    return (p.D % kHeadDim == 0 || (p.D == kHalfDim && p.K <= 7)) && p.dtype != NA2D_F32 && p.K <= 9 && shortest > 2 * p.K + 2 && rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
+    return (p.D % kHeadDim == 0 || p.D == kHalfDim) && p.dtype != NA2D_F32 && p.K <= 9 && shortest > 2 * p.K + 2 && rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
 }
 
 hipError_t launch_inverse_mfma(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s) {

@@ -293,7 +293,7 @@ static hipError_t launch_inverse_rows_t(const Problem &p, const void *w, const v
 // patch must be seen from at most 16 NCB columns: both hold for every map with K <= min(H, W) (a tile next to both
 // ends of a short axis has at most W <= 2K + 2 columns).  Checked anyway.
 bool inverse_rows_supported(const Problem &p) {
-    if ((p.D % kHeadDim != 0 && !(p.D == kHalfDim && p.K <= 7)) || p.dtype == NA2D_F32) return false;
+    if ((p.D % kHeadDim != 0 && p.D != kHalfDim) || p.dtype == NA2D_F32) return false;
     const int K = p.K, RW = kTileX + K - 1 + K / 2, NCOL = 16 * ((K + K / 2 + 3 + 15) / 16);
     if ((int64_t)p.W * K * K * 4 >= (int64_t)1 << 31) return false;   // a row of weights as a 32-bit byte count
     for (int tx0 = 0; tx0 < p.W; tx0 += kTileX) {

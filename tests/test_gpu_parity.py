@@ -351,9 +351,10 @@ def test_generic_head_dims(oracle, dtype, D, k):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("H,W,k", [(56, 56, 7), (30, 45, 5), (21, 37, 3), (14, 14, 7), (7, 7, 7), (9, 40, 7)])
+@pytest.mark.parametrize("H,W,k", [(56, 56, 7), (30, 45, 5), (21, 37, 3), (14, 14, 7), (7, 7, 7), (9, 40, 7), (40, 33, 9),
+                                   (35, 50, 11), (48, 30, 13), (13, 20, 13)])
 def test_sixteen_channel_heads_on_the_matrix_cores(oracle, dtype, H, W, k):
-    # 16-channel heads with k <= 7 ride in the lower half of the 32-channel matrix-core kernels: maps with several
+    # 16-channel heads ride in the lower half of the 32-channel matrix-core kernels: maps with several
     # tiles and ragged borders (the column-walking grad-v / grad-k kernel), maps whose shortest side is at most
     # 2k + 2 (the tile kernel or the row-streaming one), a bias that matters, every plane
     p = synth.Problem(3, 4, H, W, 16, k, dtype)
