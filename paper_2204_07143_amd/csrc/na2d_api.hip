@@ -157,7 +157,7 @@ size_t na2d_workspace_bytes(const na2d_problem *p, int kind) {
         if (!fused_bwd_supported(pr)) return attn + attn + rpb;
         const AvRpbSplit sp = fused_bwd_split(pr);
         const int nbc = 2 * pr.K - 1;
-        const size_t partials = ((size_t)sp.npos * pr.heads * sp.splits * nbc * nbc * sizeof(float) + 255) & ~(size_t)255;
+        const size_t partials = ((size_t)sp.npos * pr.heads * sp.splits * rpb_cell_stride(nbc * nbc) * sizeof(float) + 255) & ~(size_t)255;
         return 2 * ((pr.queries() * sizeof(float) + 255) & ~(size_t)255) + partials;   // delta, lse in the exp2 domain
     }
     return 0;

@@ -324,7 +324,8 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
             float sum = *lds_ptr<float>(lds0 + C::kLdsStages + cell * 4);
 #pragma unroll
             for (int wv_ = 1; wv_ < C::WAVES; ++wv_) sum += *lds_ptr<float>(lds0 + C::kLdsStages + (wv_ * CELLS + cell) * 4);
-            rpb_partial[(size_t)wg * CELLS + cell] = sum;
+            // row of this workgroup's partial: the partials of a head follow each other (rpb_cell_stride)
+            rpb_partial[(size_t)((head * splits + work.split) * gd.npos + work.pos) * rpb_cell_stride(CELLS) + cell] = sum;
         }
     }
 }

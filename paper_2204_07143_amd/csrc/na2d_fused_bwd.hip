@@ -334,7 +334,9 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
             long long sum = 0;
 #pragma unroll
             for (int t = 0; t < C::NTBL; ++t) sum += (long long)*lds_ptr<unsigned long long>(tbl0 + t * C::kTblBytes + cell * 8);
-            rpb_partial[(size_t)wg * C::CELLS + cell] = (float)((double)sum * (1.0 / 4294967296.0));   // 2^-32
+            // row of this workgroup's partial: the partials of a head follow each other (rpb_cell_stride)
+            rpb_partial[(size_t)((head * splits + work.split) * gd.npos + work.pos) * rpb_cell_stride(C::CELLS) + cell] =
+                (float)((double)sum * (1.0 / 4294967296.0));   // 2^-32
         }
     }
 }

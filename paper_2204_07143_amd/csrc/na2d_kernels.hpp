@@ -70,6 +70,11 @@ hipError_t launch_rpb_bwd_noalloc(const Problem &p, const void *ds, float *d_rpb
 struct AvRpbSplit {
     int npos, splits;
 };
+// Partial bias gradients in a workspace: one row of rpb_cell_stride(cells) floats per workgroup of the kernel that
+// leaves them (a whole number of 16-byte chunks; the floats past `cells` are never written and never used), the
+// rows of a head next to each other: row (h * n + i) is partial i of head h, n partials per head.  The final
+// reduction then walks a head's partials with a constant stride, four cells per lane and load.
+__host__ __device__ constexpr int rpb_cell_stride(int cells) { return (cells + 3) & ~3; }
 bool av_rpb_supported(const Problem &p);
 AvRpbSplit av_rpb_split(const Problem &p);
 hipError_t launch_av_rpb(const Problem &p, const void *w, const void *y, float scale, void *out, float *rpb_partial,

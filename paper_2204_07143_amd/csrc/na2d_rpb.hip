@@ -10,9 +10,10 @@
 //      bias row offset; the interior run of a segment also shares the column offset and is
 //      summed in registers with independent loads; the few border queries update the wave's
 //      private (2K-1)^2 LDS table one query at a time.  The workgroup's wave tables are added
-//      in wave order and written to the workspace as one partial per workgroup;
-//   2. a second kernel adds the partials of each head: 16 waves each sum a strided subset in
-//      index order, then the 16 sub-sums are added in wave order.
+//      in wave order and written to the workspace as one partial per workgroup, the partials
+//      of a head next to each other (rpb_cell_stride);
+//   2. a second kernel adds the partials of each head, four cells per lane: 16 waves each sum
+//      a strided subset in index order, then the 16 sub-sums are added in wave order.
 #include "na2d_kernels.hpp"
 #include "na2d_common.hpp"
 #include "na2d_tile.hpp"
@@ -58,7 +59,7 @@ static inline RpbSplit rpb_split(int planes, int H, int W, int K, int elem_bytes
 
 template <typename T, int K>
 __global__ __launch_bounds__(256) void rpb_partial_kernel(const T *__restrict__ ds, float *__restrict__ partial, int H,
-                                                          int W, RpbSplit sp) {
+                                                          int W, RpbSplit sp, int B, int heads) {
     using C = RpbCfg<T, K>;
     extern __shared__ __align__(16) char lds[];
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
@@ -152,37 +153,43 @@ __global__ __launch_bounds__(256) void rpb_partial_kernel(const T *__restrict__ 
         if (slot < C::KK) mine[R * C::NB + R + cell_off[s]] += acc_int[s];
     }
     workgroup_sync();
+    // partial (b, group) of head h: row h * (B * groups) + b * groups + group
+    const int b = plane / heads, h = plane - b * heads;
+    float *row = partial + (size_t)((h * B + b) * sp.groups_per_plane + group) * rpb_cell_stride(C::CELLS);
     for (int i = tid; i < C::CELLS; i += 256) {
         float s = tables[i];
 #pragma unroll
         for (int w = 1; w < kRpbWaves; ++w) s += tables[w * (C::kTableBytes / 4) + i];
-        partial[(size_t)blockIdx.x * C::CELLS + i] = s;
+        row[i] = s;
     }
 }
 
-// d_rpb[h, cell] = sum over (batch, group) of partial[(b * heads + h) * groups + group][cell].
-// One workgroup of 16 waves per head and block of 64 cells (a lane is a cell, so a wave reads 256
-// contiguous bytes of a partial): wave w adds the partials whose running index is w mod 16, in
-// index order, sixteen independent loads at a time; the 16 sub-sums are then added in wave order.
+// d_rpb[h, cell] = sum over i < n of partial[h * n + i][cell], rows of `stride` floats (rpb_cell_stride).
+// One workgroup of 16 waves per head and block of 64 x 4 cells: a lane owns four neighbouring cells (one 16-byte
+// load per partial, a wave reads a kilobyte of a row at once); wave w adds the partials whose index is w mod 16, in
+// index order, sixteen loads in flight; the 16 sub-sums are then added in wave order.  No index arithmetic beyond
+// one multiply per load: the rows of a head follow each other.
+struct __attribute__((packed, aligned(4))) RpbQuad {
+    f32x4 v;
+};
 __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const float *__restrict__ partial,
-                                                                           float *__restrict__ d_rpb, int B, int heads,
-                                                                           int groups, int cells, FastDiv by_groups) {
-    __shared__ float sub[kRpbFinalWaves][kWave];
-    const int cell_blocks = (cells + kWave - 1) / kWave;
-    const int h = blockIdx.x / cell_blocks;
+                                                                           float *__restrict__ d_rpb, int n, int cells,
+                                                                           int stride) {
+    __shared__ f32x4 sub[kRpbFinalWaves][kWave];
+    const int quad_blocks = (stride / 4 + kWave - 1) / kWave;
+    const int h = blockIdx.x / quad_blocks;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int cell = (blockIdx.x % cell_blocks) * kWave + lane;
-    const int n = B * groups;
-    float acc = 0.f;
-    if (cell < cells) {
-        constexpr int U = 32;   // loads in flight per lane (512 partials per round); past the end they are skipped (adding 0 changes nothing)
+    const int cell0 = ((blockIdx.x % quad_blocks) * kWave + lane) * 4;   // this lane's first cell
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (cell0 < stride) {
+        const float *base = partial + (size_t)h * n * stride + cell0;
+        constexpr int U = 16;   // loads in flight per lane; past the end they are skipped (adding 0 changes nothing)
         for (int i = wave; i < n; i += U * kRpbFinalWaves) {
-            float v[U];
+            f32x4 v[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int iu = i + u * kRpbFinalWaves;
-                const int b = fdiv(iu, by_groups), g = iu - b * groups;   // (sixteen runtime divisions per round cost more than the loads)
-                v[u] = iu < n ? partial[((size_t)(b * heads + h) * groups + g) * cells + cell] : 0.f;
+                v[u] = iu < n ? reinterpret_cast<const RpbQuad *>(base + (size_t)iu * stride)->v : f32x4{0.f, 0.f, 0.f, 0.f};
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) acc += v[u];
@@ -190,65 +197,37 @@ __global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_kernel(const 
     }
     sub[wave][lane] = acc;
     workgroup_sync();
-    if (wave == 0 && cell < cells) {
-        float s = sub[0][lane];
+    if (wave == 0 && cell0 < cells) {
+        f32x4 s = sub[0][lane];
         for (int w = 1; w < kRpbFinalWaves; ++w) s += sub[w][lane];
-        d_rpb[(size_t)h * cells + cell] = s;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (cell0 + c < cells) d_rpb[(size_t)h * cells + cell0 + c] = s[c];
     }
 }
 
-// d_rpb[h, cell] from the partials the grad-q kernel leaves: workgroup wg = (split * heads + h) * npos + pos
-// holds partial[wg][cell].  Same shape as rpb_final_kernel: one workgroup of 16 waves per head and block
-// of 64 cells, wave w adds the partials whose running index (split * npos + pos) is w mod 16, in index
-// order, sixteen loads at a time; the 16 sub-sums are added in wave order.
-__global__ __launch_bounds__(kRpbFinalWaves *kWave) void rpb_final_av_kernel(const float *__restrict__ partial,
-                                                                              float *__restrict__ d_rpb, int heads, int npos,
-                                                                              int splits, int cells, FastDiv by_npos) {
-    __shared__ float sub[kRpbFinalWaves][kWave];
-    const int cell_blocks = (cells + kWave - 1) / kWave;
-    const int h = blockIdx.x / cell_blocks;
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int cell = (blockIdx.x % cell_blocks) * kWave + lane;
-    const int n = npos * splits;
-    float acc = 0.f;
-    if (cell < cells) {
-        constexpr int U = 16;   // loads in flight per lane; past the end they are skipped (adding 0 changes nothing)
-        auto at = [&](int i) {
-            const int sp = fdiv(i, by_npos), ps = i - sp * npos;
-            return partial[((size_t)(sp * heads + h) * npos + ps) * cells + cell];
-        };
-        for (int i = wave; i < n; i += U * kRpbFinalWaves) {
-            float v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = i + u * kRpbFinalWaves < n ? at(i + u * kRpbFinalWaves) : 0.f;
-#pragma unroll
-            for (int u = 0; u < U; ++u) acc += v[u];
-        }
-    }
-    sub[wave][lane] = acc;
-    workgroup_sync();
-    if (wave == 0 && cell < cells) {
-        float s = sub[0][lane];
-        for (int w = 1; w < kRpbFinalWaves; ++w) s += sub[w][lane];
-        d_rpb[(size_t)h * cells + cell] = s;
-    }
-}
-
-hipError_t launch_rpb_final_av(const Problem &p, const float *partial, float *d_rpb, AvRpbSplit sp, hipStream_t s) {
-    const int nb = 2 * p.K - 1, cells = nb * nb;
-    hipLaunchKernelGGL(rpb_final_av_kernel, dim3(p.heads * ((cells + kWave - 1) / kWave)), dim3(kRpbFinalWaves * kWave), 0, s,
-                       partial, d_rpb, p.heads, sp.npos, sp.splits, cells, make_fastdiv(sp.npos));
+static hipError_t launch_rpb_final(const float *partial, float *d_rpb, int heads, int n, int cells, hipStream_t s) {
+    const int stride = rpb_cell_stride(cells);
+    hipLaunchKernelGGL(rpb_final_kernel, dim3(heads * ((stride / 4 + kWave - 1) / kWave)), dim3(kRpbFinalWaves * kWave), 0, s,
+                       partial, d_rpb, n, cells, stride);
     return hipGetLastError();
+}
+
+// d_rpb from the partials that the grad-q kernel (or the fused backward's query-patch kernel) leaves: workgroup
+// (position, head, split) of those kernels writes row head * (splits * npos) + split * npos + position.
+hipError_t launch_rpb_final_av(const Problem &p, const float *partial, float *d_rpb, AvRpbSplit sp, hipStream_t s) {
+    const int nb = 2 * p.K - 1;
+    return launch_rpb_final(partial, d_rpb, p.heads, sp.npos * sp.splits, nb * nb, s);
 }
 
 size_t rpb_bwd_workspace_bytes(const Problem &p) {
     if (generic_window(p)) return rpb_generic_workspace_bytes(p);
     const int nb = 2 * p.K - 1;
     const RpbSplit sp = rpb_split(p.planes(), p.H, p.W, p.K, p.elem_bytes());
-    size_t bytes = (size_t)p.planes() * sp.groups_per_plane * nb * nb * sizeof(float);
+    size_t bytes = (size_t)p.planes() * sp.groups_per_plane * rpb_cell_stride(nb * nb) * sizeof(float);
     if (av_rpb_supported(p)) {   // the composed backward keeps one partial per workgroup of the grad-q kernel
         const AvRpbSplit a = av_rpb_split(p);
-        const size_t alt = (size_t)a.npos * p.heads * a.splits * nb * nb * sizeof(float);
+        const size_t alt = (size_t)a.npos * p.heads * a.splits * rpb_cell_stride(nb * nb) * sizeof(float);
         bytes = bytes > alt ? bytes : alt;
     }
     return bytes;
@@ -263,13 +242,10 @@ static hipError_t launch_rpb_bwd_t(const Problem &p, const void *ds, float *d_rp
     static LdsAllowed allowed;
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.planes() * sp.groups_per_plane), dim3(256), C::kLdsBytes, s,
-                       static_cast<const T *>(ds), static_cast<float *>(workspace), p.H, p.W, sp);
+                       static_cast<const T *>(ds), static_cast<float *>(workspace), p.H, p.W, sp, p.B, p.heads);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(rpb_final_kernel, dim3(p.heads * ((C::CELLS + kWave - 1) / kWave)), dim3(kRpbFinalWaves * kWave), 0, s,
-                       static_cast<const float *>(workspace), d_rpb, p.B, p.heads, sp.groups_per_plane, C::CELLS,
-                       make_fastdiv(sp.groups_per_plane));
-    return hipGetLastError();
+    return launch_rpb_final(static_cast<const float *>(workspace), d_rpb, p.heads, p.B * sp.groups_per_plane, C::CELLS, s);
 }
 
 hipError_t launch_rpb_bwd(const Problem &p, const void *ds, float *d_rpb, void *workspace, hipStream_t s) {
@@ -292,7 +268,7 @@ size_t rpb_bwd_partial_bytes(const Problem &p) {
     if (generic_window(p)) return rpb_generic_workspace_bytes(p);
     const int nb = 2 * p.K - 1;
     const RpbSplit sp = rpb_split(p.planes(), p.H, p.W, p.K, p.elem_bytes());
-    return (size_t)p.planes() * sp.groups_per_plane * nb * nb * sizeof(float);
+    return (size_t)p.planes() * sp.groups_per_plane * rpb_cell_stride(nb * nb) * sizeof(float);
 }
 
 static hipError_t scratch_address(void **out) {

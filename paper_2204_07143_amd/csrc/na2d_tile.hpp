@@ -148,12 +148,14 @@ static inline UnitSplit unit_split(int tiles_x, int tiles_y, int heads, int nb) 
 }
 struct WorkItem {
     int pos, head, ty, tx, b_begin, b_end;   // tile row / column index; batch items [b_begin, b_end)
+    int split;                               // which of the `splits` workgroups of this (position, head) pair
 };
 __device__ __forceinline__ WorkItem decode_work(int wg, int heads, int tiles_y, int splits, const GridDecode &gd) {
     WorkItem w;
     const int wq = fdiv(wg, gd.by_npos), split = fdiv(wq, gd.by_heads);
     w.pos = wg - wq * gd.npos;
     w.head = wq - split * heads;
+    w.split = split;
     w.tx = fdiv(w.pos, gd.by_tiles_y);
     w.ty = w.pos - w.tx * tiles_y;
     // Ranges differ by at most one item; where only one is longer it comes first, so that a workgroup dispatched
