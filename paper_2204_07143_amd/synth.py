@@ -43,7 +43,7 @@ class Problem:
         return float(self.D) ** -0.5
 
 
-# The workloads the benchmark spec lists (shapes only; values are i.i.d. Gaussians).
+# The benchmark workloads: the map sizes and head counts of the NAT variants (Section 3.2) and of detection- and segmentation-sized inputs (shapes only; values are i.i.d. Gaussians).
 CONFIGS = {
     "tiny": Problem(1, 1, 14, 14, 32, 3, "f32"),
     "nat_tiny_stage1": Problem(64, 2, 56, 56, 32, 7, "f16"),
