@@ -482,8 +482,8 @@ def main() -> int:
     # time in the step.  Its launch duration for the roofline is the median measured above (events on the launch
     # stream around graph replays), which is what a kernel trace of the same command reports.
     inv = inverse_kernel_name(args.workload, p)
-    groups = {"qk_mfma (qk_rpb, av_bwd_p)": ["qk_rpb", "av_bwd_p"], "av_mfma (av, qk_bwd_q)": ["av", "qk_bwd_q"],
-              f"{inv} (av_bwd_v, qk_bwd_k)": ["av_bwd_v", "qk_bwd_k"], "fused_mfma (fused_fwd)": ["fused_fwd"],
+    groups = {"qk_mfma_small (qk_rpb, av_bwd_p)": ["qk_rpb", "av_bwd_p"], "av_mfma_small (av, qk_bwd_q)": ["av", "qk_bwd_q"],
+              f"{inv} (av_bwd_v, qk_bwd_k)": ["av_bwd_v", "qk_bwd_k"], "fused_mfma_small (fused_fwd)": ["fused_fwd"],
               "softmax": ["softmax"], "softmax_bwd": ["softmax_bwd"], "rpb_partial + rpb_final (qk_bwd_rpb)": ["qk_bwd_rpb"]}
     dominant = max(groups, key=lambda g: sum(kernels[n]["us"] for n in groups[g]))
     members = groups[dominant]
