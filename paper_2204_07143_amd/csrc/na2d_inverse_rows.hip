@@ -49,8 +49,6 @@ struct InvRowsCfg {
     static constexpr int kWStage = CH * kRowRegion;
     static constexpr int kStageBytes = kXStage + kWStage + 16;                // + the zero word
     static constexpr int kLdsBytes = 2 * kStageBytes;
-    static constexpr int kItems = CH * (kWItems + kXItems);                   // load instructions per stage
-    static constexpr int kItemsPerWave = (kItems + WAVES - 1) / WAVES;
     static_assert(kLdsBytes <= 80 * 1024, "two workgroups share the LDS of a compute unit");
     static_assert(16 * NCB >= PWI, "column blocks cover the patch halo");
 };
@@ -129,41 +127,63 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
         xx = xx < W - 1 ? xx : W - 1;
         xcol[j] = q < C::RW * (C::KB / 16) ? xx * pitch + ((q % (C::KB / 16)) & (half_dim ? kHalfDimChunks : 3)) * 16 : -1;
     }
-    // Loads pair `pr` of plane `b` into stage `par`: the stage's load instructions (per row: the weight row,
-    // mirrored at its 16-byte phase, then the x vectors) are dealt round-robin to the waves.
+    // Which pairs of the rectangle's rows a patch takes part in (wave-uniform, fixed for the workgroup): pair pr
+    // holds rows ry0 + 2 pr and + 1, and patch np is seen from the query rows [inv_first(first key row),
+    // inv_last(last key row)].  An empty range for a patch below the map.
+    int pair_lo[NP], pair_hi[NP];
+#pragma unroll
+    for (int np = 0; np < NP; ++np) {
+        const int sy = patch_row0(np);
+        const int sq0 = inv_first(sy < H ? sy : H - 1, H, K), sq1 = inv_last(sy + 3 < H - 1 ? sy + 3 : H - 1, H, K);
+        pair_lo[np] = sy < H ? (sq0 - ry0) >> 1 : 1;
+        pair_hi[np] = sy < H ? (sq1 - ry0) >> 1 : 0;
+    }
+    const int jy0 = ty0 + 4 * strip + ky;   // this lane's key row in patch 0; patch np: + 8 np
+
+    // Loads pair `pr` of plane `b` into stage `par`.  Per row kWItems 64-lane loads of the weight row (mirrored at
+    // its 16-byte phase) and kXItems of the x vectors; load j of a row is issued by wave j mod WAVES.  Everything
+    // about a row is wave-uniform and 32 bits wide from the plane's base pointers on (a plane of either tensor is
+    // shorter than 2 GB: checked by the host), so it runs on the scalar unit in a few instructions.
+    constexpr int kRowItems = C::kWItems + C::kXItems;
     auto issue = [&](int b, int pr, int par) {
         const size_t plane_q = ((size_t)b * heads + head) * H * W;
+        const char *const xplane = reinterpret_cast<const char *>(x) + plane_q * pitch;
+        const size_t wbase = (plane_q + rx0) * C::KK * SZ;   // first weight byte of query row 0 of the rectangle's columns
+        const char *const wplane = reinterpret_cast<const char *>(w) + wbase;
+        const size_t wleft = w_bytes - wbase;                 // bytes from wplane to the end of the weight tensor
+        const int wphase = (int)(wbase & 15);
         const int stage = lds0 + par * C::kStageBytes;
 #pragma unroll
-        for (int u = 0; u < C::kItemsPerWave; ++u) {
-            const int item = wave + u * C::WAVES;
-            if (item >= C::kItems) break;
-            const int rr = item / (C::kWItems + C::kXItems), j = item - rr * (C::kWItems + C::kXItems);
+        for (int rr = 0; rr < C::CH; ++rr) {
             const int iy = ry0 + 2 * pr + rr;
-            if (iy > ry1) continue;
-            if (j < C::kWItems) {
-                const size_t g0 = (plane_q + (size_t)iy * W + rx0) * C::KK * SZ;
-                const int mis = (int)(g0 & 15);
-                const int nchunks = (mis + wrow_bytes + 15) >> 4;
-                const char *src = reinterpret_cast<const char *>(w) + (g0 - mis);
-                const size_t left = w_bytes - (g0 - mis);   // bytes up to the end of the tensor
-                const int region = stage + C::kXStage + rr * C::kRowRegion;
-                const int c = j * kWave + lane;
-                if (c < nchunks) {
-                    if ((size_t)(c + 1) * 16 <= left) {
-                        global_to_lds_16(src, (unsigned)(c * 16), region + j * kWave * 16);
-                    } else {   // the chunk that would cross the end of the tensor: element by element
-                        for (int e = c * 16; e < mis + wrow_bytes; e += SZ)
-                            *lds_ptr<T>(region + e) = *reinterpret_cast<const T *>(src + e);
-                    }
-                }
-            } else {
-                const int jj = j - C::kWItems;
-                const char *xrow = reinterpret_cast<const char *>(x) + (plane_q + (size_t)iy * W) * pitch;
-                // (xcol is indexed by a compile-time constant after unrolling: jj takes each value once per row)
+            if (iy > ry1) break;
+            const int wo = iy * row_pitch_bytes;
+            const int mis = (wphase + wo) & 15;
+            const int nchunks = (mis + wrow_bytes + 15) >> 4;
+            const char *src = wplane + (wo - mis);
+            const bool whole = (size_t)(wo - mis) + (size_t)nchunks * 16 <= wleft;   // no chunk crosses the end of the tensor
+            const int region = stage + C::kXStage + rr * C::kRowRegion;
+            const char *xrow = xplane + iy * W * pitch;
 #pragma unroll
-                for (int q = 0; q < C::kXItems; ++q)
-                    if (q == jj && xcol[q] >= 0) global_to_lds_16(xrow, (unsigned)xcol[q], stage + rr * C::kXRow + q * kWave * 16);
+            for (int t = 0; t < (kRowItems + C::WAVES - 1) / C::WAVES; ++t) {
+                const int j = wave + t * C::WAVES;
+                if (j < C::kWItems) {
+                    const int c = j * kWave + lane;
+                    if (c < nchunks) {
+                        if (whole || (size_t)(wo - mis) + (size_t)(c + 1) * 16 <= wleft) {
+                            global_to_lds_16(src, (unsigned)(c * 16), region + j * kWave * 16);
+                        } else {   // the chunk that would cross the end of the tensor: element by element
+                            for (int e = c * 16; e < mis + wrow_bytes; e += SZ)
+                                *lds_ptr<T>(region + e) = *reinterpret_cast<const T *>(src + e);
+                        }
+                    }
+                } else if (j < kRowItems) {
+                    // (xcol is indexed by a compile-time constant after unrolling)
+#pragma unroll
+                    for (int q = 0; q < C::kXItems; ++q)
+                        if (q == j - C::kWItems && xcol[q] >= 0)
+                            global_to_lds_16(xrow, (unsigned)xcol[q], stage + rr * C::kXRow + q * kWave * 16);
+                }
             }
         }
     };
@@ -179,48 +199,64 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
             const int zero_addr = stage + C::kXStage + C::kWStage;
             const int mis0 = (int)(((plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ) & 15);   // phase of the rectangle's first row
             const int iy0 = ry0 + 2 * pr;
+            // the pair's two rows (wave-uniform): window start, whether the row exists, where its weights start
+            int ws[2], rbase[2];
+#pragma unroll
+            for (int rr = 0; rr < 2; ++rr) {
+                const int iy = iy0 + rr;
+                ws[rr] = win_start(iy < H ? iy : H - 1, H, K);
+                rbase[rr] = iy <= ry1 ? stage + C::kXStage + rr * C::kRowRegion + ((mis0 + (iy - ry0) * pitch_phase) & 15) : BIG;
+            }
 #pragma unroll
             for (int np = 0; np < NP; ++np) {
-                // the pair holds a row that sees this patch's strip (wave-uniform): query rows [sq0, sq1] do
-                const int sy = patch_row0(np);
-                if (sy >= H) continue;
-                const int sq0 = inv_first(sy, H, K), sq1 = inv_last(sy + 3 < H - 1 ? sy + 3 : H - 1, H, K);
-                if (!(iy0 + 1 >= sq0 && iy0 <= sq1)) continue;
-                const int jyp = sy + ky;   // this lane's key row
+                if (pr < pair_lo[np] || pr > pair_hi[np]) continue;   // no row of the pair sees this patch's strip
+                const int jyp = jy0 + 8 * np;   // this lane's key row
                 // row terms of the pair's two rows for this lane's key row
                 int rowterm[2];
 #pragma unroll
                 for (int rr = 0; rr < 2; ++rr) {
-                    const int iy = iy0 + rr;
-                    const int a = jyp - win_start(iy < H ? iy : H - 1, H, K);
-                    const bool ok = iy <= ry1 && jyp < H && (unsigned)a < (unsigned)K;
-                    rowterm[rr] = ok ? stage + C::kXStage + rr * C::kRowRegion + ((mis0 + (iy - ry0) * pitch_phase) & 15) + a * K * SZ : BIG;
+                    const int a = jyp - ws[rr];
+                    rowterm[rr] = (jyp < H && (unsigned)a < (unsigned)K) ? rbase[rr] + a * K * SZ : BIG;
                 }
+                // all LDS reads of the patch's column blocks are issued before the first block is multiplied (the
+                // scheduling fences keep the compiler from sinking them back to their uses, two at a time)
+                uint16_t wlo[C::NCB][4], whi[C::NCB][4];
+                u32x2 xlo[C::NCB][2], xhi[C::NCB][2];
 #pragma unroll
                 for (int cb = 0; cb < C::NCB; ++cb) {
-                    uint32_t wv[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         const int rr = u >> 1, r0 = (u & 1) * 2;
                         int a_lo = rowterm[rr] + colterm[cb][r0], a_hi = rowterm[rr] + colterm[cb][r0 + 1];
                         a_lo = a_lo < zero_addr ? a_lo : zero_addr;
                         a_hi = a_hi < zero_addr ? a_hi : zero_addr;
-                        wv[u] = (uint32_t)*lds_ptr<uint16_t>(a_lo) | ((uint32_t)*lds_ptr<uint16_t>(a_hi) << 16);
+                        wlo[cb][u] = *lds_ptr<uint16_t>(a_lo);
+                        whi[cb][u] = *lds_ptr<uint16_t>(a_hi);
                     }
-                    const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
 #pragma unroll
                     for (int hf = 0; hf < 2; ++hf) {
                         const int a0 = stage + xa_lane + cb * 16 * C::KB + hf * 8;
-                        const u32x2 lo = lds_read_tr16(a0);
-                        const u32x2 hi = lds_read_tr16(a0 + C::kXRow);
-                        acc[np][hf] = mfma_16x16x32<T>(u32x4{lo.x, lo.y, hi.x, hi.y}, bop, acc[np][hf]);
+                        xlo[cb][hf] = lds_read_tr16(a0);
+                        xhi[cb][hf] = lds_read_tr16(a0 + C::kXRow);
                     }
                 }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int cb = 0; cb < C::NCB; ++cb) {
+                    uint32_t wv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) wv[u] = (uint32_t)wlo[cb][u] | ((uint32_t)whi[cb][u] << 16);
+                    const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf)
+                        acc[np][hf] = mfma_16x16x32<T>(u32x4{xlo[cb][hf].x, xlo[cb][hf].y, xhi[cb][hf].x, xhi[cb][hf].y}, bop, acc[np][hf]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
             if (pr == npairs - 1) {   // the rectangle is done: this lane's eight channels of its keys
 #pragma unroll
                 for (int np = 0; np < NP; ++np) {
-                    const int jyp = patch_row0(np) + ky;
+                    const int jyp = jy0 + 8 * np;
                     if (jyp < H && jx < W && (!half_dim || g < 2)) {
                         char *dst = reinterpret_cast<char *>(out) + (plane_q + (size_t)jyp * W + jx) * pitch + g * 16;
                         uint32_t o[4];
@@ -295,7 +331,8 @@ static hipError_t launch_inverse_rows_t(const Problem &p, const void *w, const v
 bool inverse_rows_supported(const Problem &p) {
     if ((p.D % kHeadDim != 0 && p.D != kHalfDim) || p.dtype == NA2D_F32) return false;
     const int K = p.K, RW = kTileX + K - 1 + K / 2, NCOL = 16 * ((K + K / 2 + 3 + 15) / 16);
-    if ((int64_t)p.W * K * K * 4 >= (int64_t)1 << 31) return false;   // a row of weights as a 32-bit byte count
+    // offsets inside a plane of the weights and of x / out as 32-bit byte counts
+    if ((int64_t)p.H * p.W * K * K * 4 >= (int64_t)1 << 31 || (int64_t)p.H * p.W * p.D * 4 >= (int64_t)1 << 31) return false;
     for (int tx0 = 0; tx0 < p.W; tx0 += kTileX) {
         const int tx1 = tx0 + kTileX - 1 < p.W - 1 ? tx0 + kTileX - 1 : p.W - 1;
         if (inv_last(tx1, p.W, K) - inv_first(tx0, p.W, K) + 1 > RW) return false;
