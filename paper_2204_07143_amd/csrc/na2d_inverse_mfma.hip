@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
                     const int sy = ty0 + 4 * st, jyy = sy + kye;
                     const int iy = inv_first(sy < H ? sy : H - 1, H, K) + bb;   // halo row bb of the strip
                     const int a = jyy - win_start(iy < H ? iy : H - 1, H, K);
-                    if (bb < C::PWI && iy <= ry1 && jyy < H && (unsigned)a < (unsigned)K)
+                    if (iy <= ry1 && jyy < H && (unsigned)a < (unsigned)K)   // (every bb < NBLK is a row the loop visits)
                         term = w0 + (iy - ry0) * C::kRowRegion + ((mis0 + (iy - ry0) * pitch_phase) & 15) + a * K * SZ;
                 }
                 *lds_ptr<int>(tbl_col + e * 4) = term;
@@ -326,14 +326,27 @@ static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const v
                            : launch_inverse_mfma_c<T, K, false>(p, w, x, scale, out, s);
 }
 
-// The kernel sizes its LDS images for key patches and key tiles that are next to at most one border
-// per axis: a 4 x 4 patch seen from both clamped ends at once (axes of at most 2K + 2 positions) or a
-// 16 x 8 tile whose query rectangle exceeds (8 + K-1 + R) x (16 + K-1 + R) (short axes again) does not
-// fit, and such small maps take the plain gather kernel instead.
+// Is every 4-row strip of keys seen from at most NBLK query rows (the rows a wave walks from the strip's first
+// query row on) and every 4-column patch from at most 16 query columns (one MFMA block)?  Always so away from
+// short axes (K + R + 3 positions at most); on an axis of at most 2K + 2 positions a patch can be seen from both
+// clamped ends at once, and then it depends on the length: 14 x 14 and 7 x 7 maps at K = 7 fit, 16 x 16 at K = 9
+// does not.
+static bool patch_halo_fits(const Problem &p) {
+    const int K = p.K, PWI = K + K / 2 + 3, NBLK = PWI + (PWI & 1);
+    for (int sy = 0; sy < p.H; sy += 4)
+        if (inv_last(sy + 3 < p.H - 1 ? sy + 3 : p.H - 1, p.H, K) - inv_first(sy, p.H, K) + 1 > NBLK) return false;
+    for (int px = 0; px < p.W; px += 4)
+        if (inv_last(px + 3 < p.W - 1 ? px + 3 : p.W - 1, p.W, K) - inv_first(px, p.W, K) + 1 > 16) return false;
+    return true;
+}
+
+// The kernel sizes its LDS images for key tiles whose query rectangle has at most (8 + K-1 + R) x (16 + K-1 + R)
+// positions and walks NBLK query rows and 16 query columns per patch: maps where a tile or a patch is seen from
+// more (some short axes) take the row-streaming kernel instead.
 bool inverse_mfma_supported(const Problem &p) {
-    const int shortest = p.H < p.W ? p.H : p.W;
     const int R = p.K / 2;
-    return (p.D % kHeadDim == 0 || p.D == kHalfDim) && p.dtype != NA2D_F32 && p.K <= 9 && shortest > 2 * p.K + 2 && rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
+    return (p.D % kHeadDim == 0 || p.D == kHalfDim) && p.dtype != NA2D_F32 && p.K <= 9 && patch_halo_fits(p) &&
+           rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
 }
 
 hipError_t launch_inverse_mfma(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s) {

@@ -145,8 +145,15 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
     // about a row is wave-uniform and 32 bits wide from the plane's base pointers on (a plane of either tensor is
     // shorter than 2 GB: checked by the host), so it runs on the scalar unit in a few instructions.
     constexpr int kRowItems = C::kWItems + C::kXItems;
-    auto issue = [&](int b, int pr, int par) {
-        const size_t plane_q = ((size_t)b * heads + head) * H * W;
+    // (planes are walked by adding plane_stride_q to the first query of the plane: no 64-bit products of the batch
+    // index in the step loop)
+    const size_t plane_stride_q = (size_t)heads * H * W;
+    auto uniform = [](const char *ptr) {   // (wave-uniform by construction; said again so that a base sits in scalar registers)
+        const uint64_t v = (uint64_t)(uintptr_t)ptr;
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+        return reinterpret_cast<const char *>((uintptr_t)(((uint64_t)hi << 32) | lo));
+    };
+    auto issue = [&](size_t plane_q, int pr, int par) {
         const char *const xplane = reinterpret_cast<const char *>(x) + plane_q * pitch;
         const size_t wbase = (plane_q + rx0) * C::KK * SZ;   // first weight byte of query row 0 of the rectangle's columns
         const char *const wplane = reinterpret_cast<const char *>(w) + wbase;
@@ -160,10 +167,10 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
             const int wo = iy * row_pitch_bytes;
             const int mis = (wphase + wo) & 15;
             const int nchunks = (mis + wrow_bytes + 15) >> 4;
-            const char *src = wplane + (wo - mis);
+            const char *src = uniform(wplane + (wo - mis));
             const bool whole = (size_t)(wo - mis) + (size_t)nchunks * 16 <= wleft;   // no chunk crosses the end of the tensor
             const int region = stage + C::kXStage + rr * C::kRowRegion;
-            const char *xrow = xplane + iy * W * pitch;
+            const char *xrow = uniform(xplane + iy * W * pitch);
 #pragma unroll
             for (int t = 0; t < (kRowItems + C::WAVES - 1) / C::WAVES; ++t) {
                 const int j = wave + t * C::WAVES;
@@ -192,12 +199,12 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
 #pragma unroll
     for (int np = 0; np < NP; ++np) acc[np][0] = acc[np][1] = f32x4{0.f, 0.f, 0.f, 0.f};
     // One step: pair `pr` of plane `b`, staged in `par`.
-    auto compute = [&](int b, int pr, int par) {
+    auto compute = [&](size_t plane_q, int pr, int par) {
         if (active) {
-            const size_t plane_q = ((size_t)b * heads + head) * H * W;
             const int stage = lds0 + par * C::kStageBytes;
             const int zero_addr = stage + C::kXStage + C::kWStage;
-            const int mis0 = (int)(((plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ) & 15);   // phase of the rectangle's first row
+            // phase of the rectangle's first row (the low bits of its byte offset: 32-bit arithmetic will do)
+            const int mis0 = (int)((((uint32_t)plane_q + (uint32_t)(ry0 * W + rx0)) * (uint32_t)(C::KK * SZ)) & 15u);
             const int iy0 = ry0 + 2 * pr;
             // the pair's two rows (wave-uniform): window start, whether the row exists, where its weights start
             int ws[2], rbase[2];
@@ -275,20 +282,23 @@ __global__ __launch_bounds__(512, 4) void inverse_rows_kernel(const T *__restric
     };
 
     workgroup_sync();   // the zero fill is done before the first loads land
-    issue(b_begin, 0, 0);
+    size_t plane_q = ((size_t)b_begin * heads + head) * H * W;   // first query of plane b
+    issue(plane_q, 0, 0);
     int b = b_begin, pr = 0, par = 0;
     while (b < b_end) {
         wait_global_loads();   // this step's rows have landed
         workgroup_sync();       // ... for every wave, and nobody still reads the other stage
-        int nb_ = b, npr = pr + 1;
-        if (npr == npairs) {
-            npr = 0;
-            ++nb_;
-        }
-        if (nb_ < b_end) issue(nb_, npr, par ^ 1);
-        compute(b, pr, par);
-        b = nb_;
-        pr = npr;
+        // (the walk is wave-uniform; said again so that its arithmetic stays on the scalar unit)
+        b = __builtin_amdgcn_readfirstlane(b);
+        pr = __builtin_amdgcn_readfirstlane(pr);
+        par = __builtin_amdgcn_readfirstlane(par);
+        const bool last = pr + 1 == npairs;   // the last pair of a plane: the next plane's first pair loads under it
+        const size_t next_q = last ? plane_q + plane_stride_q : plane_q;
+        if (!last || b + 1 < b_end) issue(next_q, last ? 0 : pr + 1, par ^ 1);
+        compute(plane_q, pr, par);
+        plane_q = next_q;
+        b += last ? 1 : 0;
+        pr = last ? 0 : pr + 1;
         par ^= 1;
     }
 }
