@@ -383,6 +383,22 @@ def test_seeded_random_shapes(oracle, B, heads, H, W, D, k, dtype):
     run_all(oracle, p, seed=31000 + 71 * H + W + k + D)
 
 
+@pytest.mark.parametrize("B,heads,D,k", [(254, 8, 32, 13), (437, 16, 16, 7)])
+def test_attention_tensors_beyond_two_gigabytes(oracle, B, heads, D, k):
+    # k*k tensors of more than 2^31 bytes (byte offsets that no longer fit 32 bits): the first, a middle and the last
+    # plane element by element, and the bias gradient over the whole tensor
+    p = synth.Problem(B, heads, 56, 56, D, k, "f16")
+    assert p.n_queries * p.kk * 2 > 2 ** 31
+    run_all(oracle, p, seed=4242 + k, planes=[(0, 0), (B // 2, heads // 2), (B - 1, heads - 1)], fused_backward=False)
+
+
+def test_head_dim_tensors_beyond_two_gigabytes(oracle):
+    # q, k, v, dout and the three head-dim gradients of more than 2^31 bytes each, the fused backward included
+    p = synth.Problem(669, 16, 56, 56, 32, 3, "f16")
+    assert p.n_queries * p.D * 2 > 2 ** 31
+    run_all(oracle, p, seed=4250, planes=[(0, 0), (334, 7), (668, 15)])
+
+
 def test_head_dims_the_library_does_not_take():
     q = torch.zeros((1, 1, 14, 14, 48), dtype=torch.float16, device="cuda")
     with pytest.raises(na.Na2dError) as e:
