@@ -62,7 +62,8 @@ __global__ __launch_bounds__(256) void rpb_partial_kernel(const T *__restrict__ 
                                                           int W, RpbSplit sp, int B, int heads) {
     using C = RpbCfg<T, K>;
     extern __shared__ __align__(16) char lds[];
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // (scalar: everything about a segment is wave-uniform)
     char *region = lds + wave * C::kRegion;
     float *tables = reinterpret_cast<float *>(lds + kRpbWaves * C::kRegion);
     float *mine = tables + wave * (C::kTableBytes / 4);
@@ -107,16 +108,15 @@ __global__ __launch_bounds__(256) void rpb_partial_kernel(const T *__restrict__ 
                 if (slot < C::KK) {
                     const T *col = tile + (xi0 - x0) * C::KK + slot;
                     const int n = xi1 - xi0;
-                    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+                    // eight queries per round: eight reads at immediate offsets from one address, eight sums
+                    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                     int i = 0;
-                    for (; i + 4 <= n; i += 4) {
-                        a0 += to_f32(col[(i + 0) * C::KK]);
-                        a1 += to_f32(col[(i + 1) * C::KK]);
-                        a2 += to_f32(col[(i + 2) * C::KK]);
-                        a3 += to_f32(col[(i + 3) * C::KK]);
+                    for (; i + 8 <= n; i += 8) {
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) a[u] += to_f32(col[(i + u) * C::KK]);
                     }
-                    for (; i < n; ++i) a0 += to_f32(col[i * C::KK]);
-                    run[s] = (a0 + a1) + (a2 + a3);
+                    for (; i < n; ++i) a[0] += to_f32(col[i * C::KK]);
+                    run[s] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
                 }
             }
         }
