@@ -45,10 +45,14 @@ struct QkSmallCfg {
     static constexpr int kRowPitch = (kRowBytes + 15) & ~15;
     static constexpr int kStageBytes = TY * kRowPitch;
     static constexpr int kDumpBytes = kThreads * 4;              // one word per thread for results outside its window
-    static constexpr int kParity = kStageBytes + kDumpBytes;     // distance between the two staging images
-    static constexpr int kLdsBytes = 2 * kHaloAll + 2 * kParity;
+    static constexpr int kImage = kStageBytes + kDumpBytes;      // one staging image and the dump words
+    // Two staging images where two workgroups then still share a compute unit's LDS (or where one image would not
+    // make them fit either); one image, filled and streamed out in turn, where that is what makes them fit (k = 9)
+    static constexpr bool kOneImage = 2 * kHaloAll + 2 * kImage > 80 * 1024 && 2 * kHaloAll + kImage <= 80 * 1024;
+    static constexpr int kParity = kOneImage ? 0 : kImage;       // distance between the two staging images
+    static constexpr int kLdsBytes = 2 * kHaloAll + (kOneImage ? 1 : 2) * kImage;
     static constexpr int kWavesPerSimd = kLdsBytes <= 80 * 1024 ? 4 : 2;   // two workgroups, or one, per compute unit
-    static_assert(kParity < 65536, "the second staging image is reached through the 16-bit offset of the LDS store");
+    static_assert(kImage < 65536, "the second staging image is reached through the 16-bit offset of the LDS store");
 };
 
 
@@ -169,7 +173,7 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
     // Large windows (up to 64 results per lane) keep the store addresses two per register, as 16-bit offsets
     // from the first staging image; small windows keep them as absolute addresses, one per register.
     constexpr bool PACKED = K > 7;
-    static_assert(C::kParity < 65536, "offsets inside a staging image fit 16 bits");
+    static_assert(C::kImage < 65536, "offsets inside a staging image fit 16 bits");
     uint32_t bias2[P::NEL / 2];
     int slotaddr[PACKED ? P::NEL / 2 : P::NEL];
     auto slot_of = [&](int e) -> int {
@@ -248,8 +252,9 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
         }
         if (!active) return;
         // blocks in batches of eight: the MFMAs of a batch are issued back to back, then its 32 results are
-        // stored; large windows (up to 16 blocks) never hold more than eight accumulators
-        constexpr int BATCH = 8;
+        // stored; large windows (up to 16 blocks) never hold more than eight accumulators (five where two workgroups
+        // per compute unit leave a lane 128 registers: k = 9)
+        constexpr int BATCH = C::kOneImage ? 5 : 8;
 #pragma unroll
         for (int b0 = 0; b0 < P::NBLK; b0 += BATCH) {
             f32x4 acc[BATCH];
@@ -284,16 +289,26 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
 #pragma unroll
         for (int sl = 0; sl < NS; ++sl) qreg[sl] = (half_dim && g >= 2) ? u32x4{0u, 0u, 0u, 0u} : qnext[sl];
         if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
-        if (b > b_begin) flush(b - 1, PAR ^ 1);
-        compute(par_c, qreg);
+        if constexpr (C::kOneImage) {
+            // the one image: filled, then streamed out before the next tile's barrier lets anyone refill it (the
+            // workgroup that shares the compute unit computes meanwhile)
+            compute(par_c, qreg);
+            workgroup_sync();
+            flush(b, 0);
+        } else {
+            if (b > b_begin) flush(b - 1, PAR ^ 1);
+            compute(par_c, qreg);
+        }
         ++b;
     };
     while (b < b_end) {
         step(IntC<0>{});
         if (b < b_end) step(IntC<1>{});
     }
-    workgroup_sync();
-    flush(b_end - 1, (b_end - b_begin - 1) & 1);
+    if constexpr (!C::kOneImage) {
+        workgroup_sync();
+        flush(b_end - 1, (b_end - b_begin - 1) & 1);
+    }
 }
 
 template <typename T, int K, int NS>
