@@ -40,7 +40,11 @@ struct AvSmallCfg {
     static constexpr int kRowPasses = (kRowChunks + kWave - 1) / kWave;   // load instructions of one wave per row run
     static constexpr int kWBytes = TY * kRowRegion;
     static constexpr int kStageBytes = kHaloBytes + kWBytes + 16;   // + the zero word
-    static constexpr int kLdsStages = 2 * kStageBytes;
+    // Two stages (the next tile's loads arrive while this one is computed) where two workgroups then still share a
+    // compute unit's LDS or one stage would not make them fit either; one stage, reloaded between tiles while the
+    // workgroup that shares the compute unit computes, where that is what makes them fit (k = 9)
+    static constexpr bool kOneStage = 2 * kStageBytes > 80 * 1024 && kStageBytes <= 80 * 1024;
+    static constexpr int kLdsStages = (kOneStage ? 1 : 2) * kStageBytes;
     // per-wave bias-gradient tables (the grad-b variant exists for k <= 7 only)
     static constexpr int kRpbBytes = K <= 7 ? WAVES * (2 * K - 1) * (2 * K - 1) * 4 : 0;
     static constexpr int kLdsBytes = kLdsStages + kRpbBytes;
@@ -83,7 +87,7 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
     if (b_begin >= b_end) return;
 
     // the zero words (one per stage) are never written by the loads
-    if (tid < 8) *lds_ptr<uint32_t>(zero_addr + (tid >> 2) * C::kStageBytes + (tid & 3) * 4) = 0u;
+    if (tid < (C::kOneStage ? 4 : 8)) *lds_ptr<uint32_t>(zero_addr + (tid >> 2) * C::kStageBytes + (tid & 3) * 4) = 0u;
 
     const int hoy = halo_origin(ty0, C::TY, H, K), hox = halo_origin(tx0, kTileX, W, K);   // tile halo origin
     const int sy0 = ty0 + 4 * strip, px0 = tx0 + 4 * p;                                     // this wave's patch
@@ -111,18 +115,26 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
             const size_t g0 = plane * plane_w + wrow_off;
             const int mis = (int)(g0 & 15);
             const int nchunks = (mis + wrow_bytes + 15) >> 4;
-            const char *src = reinterpret_cast<const char *>(w) + (g0 - mis);
+            const char *src = reinterpret_cast<const char *>(w) + (g0 - mis);   // the same for the whole wave
             const size_t left = w_bytes - (g0 - mis);   // bytes up to the end of the tensor
             const int region = w0 + par * C::kStageBytes + wave * C::kRowRegion;
+            if ((size_t)nchunks * 16 <= left) {   // (wave-uniform) every chunk lies inside the tensor
 #pragma unroll
-            for (int it = 0; it < C::kRowPasses; ++it) {
-                const int c = lane + it * kWave;
-                if (c < nchunks) {
-                    if ((size_t)(c + 1) * 16 <= left) {
-                        global_to_lds_16(src + c * 16, region + it * kWave * 16);
-                    } else {   // the chunk that would cross the end of the tensor: element by element
-                        for (int e = c * 16; e < mis + wrow_bytes; e += SZ)
-                            *lds_ptr<T>(region + e) = *reinterpret_cast<const T *>(src + e);
+                for (int it = 0; it < C::kRowPasses; ++it) {
+                    const int c = lane + it * kWave;
+                    if (c < nchunks) global_to_lds_16(src, (unsigned)(c * 16), region + it * kWave * 16);
+                }
+            } else {   // the last row of the tensor: the chunk that would cross its end goes element by element
+#pragma unroll 1
+                for (int it = 0; it < C::kRowPasses; ++it) {
+                    const int c = lane + it * kWave;
+                    if (c < nchunks) {
+                        if ((size_t)(c + 1) * 16 <= left) {
+                            global_to_lds_16(src, (unsigned)(c * 16), region + it * kWave * 16);
+                        } else {
+                            for (int e = c * 16; e < mis + wrow_bytes; e += SZ)
+                                *lds_ptr<T>(region + e) = *reinterpret_cast<const T *>(src + e);
+                        }
                     }
                 }
             }
@@ -135,14 +147,26 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
     // position 16b + 4g + j / 4 and receives the j-th channel of positions 16b + 4g .. + 3.  The channels
     // are dealt so that MFMA row m of half hf is channel 8 (m / 4) + 4 hf + m % 4: a lane then ends
     // up with the eight consecutive channels 8g .. 8g + 7 of its query, one 16-byte store.
-    int vaddr[P::NBLK];   // a padding block of the last pair re-reads the last real block (its weights are zero)
+    // (one stage: the addresses two per register, as 16-bit offsets from the start of the stage, where a lane has
+    // 128 registers)
+    constexpr bool VPACKED = C::kOneStage;
+    static_assert(!VPACKED || C::kHaloBytes <= 65536, "value addresses as 16-bit offsets");
+    int vaddr[VPACKED ? (P::NBLK + 1) / 2 : P::NBLK];   // a padding block of the last pair re-reads the last real block (its weights are zero)
 #pragma unroll
     for (int b = 0; b < P::NBLK; ++b) {
         int h = 16 * b + 4 * g + (j >> 2);
         h = h < P::NKEY ? h : P::NKEY - 1;   // past the end: any real position (its weight is zero)
         const int hy = P::row_of(h), hx = h - hy * P::PW;
-        vaddr[b] = lds0 + ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + (j & 3) * 16;
+        const int off = ((oy - hoy + hy) * C::HALO_W + (ox - hox) + hx) * Traits<T>::kKeyBytes + (j & 3) * 16;
+        if constexpr (VPACKED) vaddr[b >> 1] = (b & 1) ? (vaddr[b >> 1] | (off << 16)) : off;
+        else vaddr[b] = lds0 + off;
     }
+    auto value_addr = [&](int b) -> int {
+        // (a patch halo that is 16 positions wide: block b is its row b)
+        if constexpr (VPACKED && P::PW == 16) return lds0 + (int)((uint32_t)vaddr[0] & 0xffffu) + b * C::HALO_W * Traits<T>::kKeyBytes;
+        else if constexpr (VPACKED) return lds0 + (int)((b & 1) ? (uint32_t)vaddr[b >> 1] >> 16 : (uint32_t)vaddr[b >> 1] & 0xffffu);
+        else return vaddr[b];
+    };
     // Weights: LDS address of this lane's query's weight for halo position 16 (e / 4) + 4g + e % 4, the
     // zero word where the position is outside the query's window.  The addresses hold the 16-byte
     // phase the query's row run has in the first plane of the range; later planes add the difference.
@@ -178,6 +202,7 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
             if constexpr (PACKED) {
                 gaddr[2 * G] = (ga[0] - w0) | ((ga[1] - w0) << 16);
                 gaddr[2 * G + 1] = (ga[2] - w0) | ((ga[3] - w0) << 16);
+                __builtin_amdgcn_sched_barrier(0);   // one group's temporaries at a time
             } else {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) gaddr[4 * G + i] = ga[i];
@@ -238,6 +263,14 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
         // twelve reads in flight behind every pair of MFMAs instead of waiting for each pair's reads in turn.
         uint16_t wlo[2][4], whi[2][4];
         u32x2 xlo[2][2], xhi[2][2];
+        if constexpr (C::kOneStage) {
+            // the packed tables stay packed: without this their unpacking is hoisted out of the loop over the planes
+            // and takes a register per address
+#pragma unroll
+            for (int e = 0; e < P::NEL / 2; ++e) asm volatile("" : "+v"(gaddr[e]));
+#pragma unroll
+            for (int e = 0; e < (P::NBLK + 1) / 2; ++e) asm volatile("" : "+v"(vaddr[e]));
+        }
         auto fetch = [&](int pb, int st) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -258,8 +291,8 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
             }
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
-                xlo[st][hf] = lds_read_tr16(vaddr[2 * pb] + PAR * C::kStageBytes + hf * 8);
-                xhi[st][hf] = lds_read_tr16(vaddr[2 * pb + 1 < P::NBLK ? 2 * pb + 1 : P::NBLK - 1] + PAR * C::kStageBytes + hf * 8);
+                xlo[st][hf] = lds_read_tr16(value_addr(2 * pb) + PAR * C::kStageBytes + hf * 8);
+                xhi[st][hf] = lds_read_tr16(value_addr(2 * pb + 1 < P::NBLK ? 2 * pb + 1 : P::NBLK - 1) + PAR * C::kStageBytes + hf * 8);
             }
         };
         if (!kProbeMemoryOnly) {   // (measurement build: zeros are stored)
@@ -298,7 +331,9 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
         constexpr int PAR = decltype(par_c)::value;
         wait_global_loads();   // this tile's halo and weight rows have landed
         workgroup_sync();       // ... for every wave, and nobody still reads the other stage
-        if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
+        if constexpr (!C::kOneStage) {
+            if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
+        }
         if (phase_varies) {   // the table follows the phase of this plane's row run (in-window entries only)
             const int ph = phase_of(b), d = ph - cur_phase;
             cur_phase = ph;
@@ -309,11 +344,19 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
         }
         compute(par_c, b);
         if constexpr (RPB) row_sums(par_c, b);
+        if constexpr (C::kOneStage) {
+            if (b + 1 < b_end) {
+                workgroup_sync();   // nobody still reads the stage
+                issue(b + 1, 0);
+            }
+        }
         ++b;
     };
     while (b < b_end) {
         step(IntC<0>{});
-        if (b < b_end) step(IntC<1>{});
+        if constexpr (!C::kOneStage) {
+            if (b < b_end) step(IntC<1>{});
+        }
     }
 
     if constexpr (RPB) {
