@@ -49,8 +49,12 @@ struct QkSmallCfg {
     // Two staging images where two workgroups then still share a compute unit's LDS (or where one image would not
     // make them fit either); one image, filled and streamed out in turn, where that is what makes them fit (k = 9)
     static constexpr bool kOneImage = 2 * kHaloAll + 2 * kImage > 80 * 1024 && 2 * kHaloAll + kImage <= 80 * 1024;
-    static constexpr int kParity = kOneImage ? 0 : kImage;       // distance between the two staging images
-    static constexpr int kLdsBytes = 2 * kHaloAll + (kOneImage ? 1 : 2) * kImage;
+    // ... and one halo buffer too, loaded between tiles, where only that makes them fit (k = 11, 13)
+    static constexpr bool kOneHalo = 2 * kHaloAll + kImage > 80 * 1024 && kHaloAll + kImage <= 80 * 1024;
+    static constexpr bool kOneBoth = kOneImage || kOneHalo;      // (one image either way)
+    static constexpr int kParity = kOneBoth ? 0 : kImage;        // distance between the two staging images
+    static constexpr int kHaloParity = kOneHalo ? 0 : kHaloAll;  // ... between the two halo buffers
+    static constexpr int kLdsBytes = (kOneHalo ? 1 : 2) * kHaloAll + (kOneBoth ? 1 : 2) * kImage;
     static constexpr int kWavesPerSimd = kLdsBytes <= 80 * 1024 ? 4 : 2;   // two workgroups, or one, per compute unit
     static_assert(kImage < 65536, "the second staging image is reached through the 16-bit offset of the LDS store");
 };
@@ -103,7 +107,7 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
     const int strip = wave >> 2, p = patch_of_wave(wave);
     const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
     const int lds0 = lds_addr(lds);
-    const int stage0 = lds0 + 2 * C::kHaloAll;
+    const int stage0 = lds0 + (C::kOneHalo ? 1 : 2) * C::kHaloAll;
     const int my_dump = stage0 + C::kStageBytes + tid * 4;
 
     // A workgroup keeps one tile position and one head and walks a range of the batch: everything
@@ -149,7 +153,7 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
 #pragma unroll
         for (int sl = 0; sl < NS; ++sl) {
             C::Halo::issue_at(reinterpret_cast<const char *>(y) + plane * plane_in + sl * Traits<T>::kKeyBytes, hoff,
-                              lds0 + par * C::kHaloAll + sl * C::kHaloBytes, wave);
+                              lds0 + par * C::kHaloParity + sl * C::kHaloBytes, wave);
             qnext[sl] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) + plane * plane_in + qoff +
                                                           sl * Traits<T>::kKeyBytes);
         }
@@ -158,9 +162,11 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
 
     // A operand: offsets of this lane's keys inside the tile halo (keys past the end of the patch halo
     // re-read its last one)
-    int koff[P::NBLK];
+    // (a patch halo that is 16 positions wide, k = 13: block b is its row b, one address and a stride)
+    constexpr bool KROWS = P::PW == 16;
+    int koff[KROWS ? 1 : P::NBLK];
 #pragma unroll
-    for (int b = 0; b < P::NBLK; ++b) {
+    for (int b = 0; b < (KROWS ? 1 : P::NBLK); ++b) {
         int h = 16 * b + j;
         h = h < P::NKEY ? h : P::NKEY - 1;
         const int hy = P::row_of(h), hx = h - hy * P::PW;
@@ -251,10 +257,16 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
             return;
         }
         if (!active) return;
+        if constexpr (PACKED) {
+            // the packed tables stay packed: without this their unpacking is hoisted out of the loop over the planes
+            // and takes a register per entry
+#pragma unroll
+            for (int e = 0; e < P::NEL / 2; ++e) asm volatile("" : "+v"(slotaddr[e]), "+v"(bias2[e]));
+        }
         // blocks in batches of eight: the MFMAs of a batch are issued back to back, then its 32 results are
         // stored; large windows (up to 16 blocks) never hold more than eight accumulators (five where two workgroups
         // per compute unit leave a lane 128 registers: k = 9)
-        constexpr int BATCH = C::kOneImage ? 5 : 8;
+        constexpr int BATCH = C::kOneBoth ? 5 : 8;
 #pragma unroll
         for (int b0 = 0; b0 < P::NBLK; b0 += BATCH) {
             f32x4 acc[BATCH];
@@ -265,7 +277,8 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
                 acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int sl = 0; sl < NS; ++sl) {
-                    const u32x4 a = *lds_ptr<u32x4>(koff[bk] + PAR * C::kHaloAll + sl * C::kHaloBytes);
+                    const int ka = KROWS ? koff[0] + bk * C::HALO_W * Traits<T>::kKeyBytes : koff[KROWS ? 0 : bk];
+                    const u32x4 a = *lds_ptr<u32x4>(ka + PAR * C::kHaloParity + sl * C::kHaloBytes);
                     acc[u] = mfma_16x16x32<T>(a, qreg[sl], acc[u]);
                 }
             }
@@ -288,14 +301,21 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
         u32x4 qreg[NS];
 #pragma unroll
         for (int sl = 0; sl < NS; ++sl) qreg[sl] = (half_dim && g >= 2) ? u32x4{0u, 0u, 0u, 0u} : qnext[sl];
-        if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
-        if constexpr (C::kOneImage) {
+        if constexpr (C::kOneHalo) {
+            // one halo buffer, one image: compute, then the next tile's loads and this tile's results leave together
+            compute(par_c, qreg);
+            workgroup_sync();
+            if (b + 1 < b_end) issue(b + 1, 0);
+            flush(b, 0);
+        } else if constexpr (C::kOneImage) {
+            if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
             // the one image: filled, then streamed out before the next tile's barrier lets anyone refill it (the
             // workgroup that shares the compute unit computes meanwhile)
             compute(par_c, qreg);
             workgroup_sync();
             flush(b, 0);
         } else {
+            if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
             if (b > b_begin) flush(b - 1, PAR ^ 1);
             compute(par_c, qreg);
         }
@@ -305,7 +325,7 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
         step(IntC<0>{});
         if (b < b_end) step(IntC<1>{});
     }
-    if constexpr (!C::kOneImage) {
+    if constexpr (!C::kOneBoth) {
         workgroup_sync();
         flush(b_end - 1, (b_end - b_begin - 1) & 1);
     }
