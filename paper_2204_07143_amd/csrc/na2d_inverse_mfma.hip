@@ -29,7 +29,11 @@ namespace na2d {
 // COMPACT: LDS images sized for the rectangle of a tile away from the ragged end of the map,
 // (TY + K-1) x (16 + K-1) positions; three workgroups then share a CU.  The launcher uses it when every
 // tile of the map fits (always the case when H and W are multiples of the tile, e.g. 56 x 56).
-template <typename T, int K, int STRIPS, int PPW, bool COMPACT>
+// CHUNK: 0, or the rows of the rectangle that LDS holds at a time.  At K = 9 a whole rectangle (up to 20 rows of
+// 28 positions: 129 KB) leaves room for one workgroup per compute unit, which then loads and multiplies in turn with
+// nothing to overlap either with; in chunks of 8 or 10 rows two or three workgroups fit, and one computes while
+// another loads.  A patch's accumulators stay in registers across the chunks of a plane.
+template <typename T, int K, int STRIPS, int PPW, bool COMPACT, int CHUNK = 0>
 struct InvMfmaCfg {
     static constexpr int R = K / 2;
     static constexpr int PWI = K + R + 3;          // query-halo side of a 4 x 4 key patch
@@ -42,15 +46,20 @@ struct InvMfmaCfg {
     static constexpr int TY = 4 * STRIPS;
     static constexpr int RH = COMPACT ? TY + K - 1 : 4 * (STRIPS - 1) + NBLK;   // rows of the tile's query rectangle held in LDS
     static constexpr int RW = COMPACT ? kTileX + K - 1 : kTileX + K - 1 + R;  // columns that hold data
+    static constexpr int LH = CHUNK ? CHUNK : RH;       // rows that LDS holds at a time
+    static constexpr int NCH = (RH + LH - 1) / LH;      // chunks of a rectangle, at most
+    // a pair of rows (one MFMA deep) must not straddle two chunks: chunks and the first row of every strip's halo
+    // (multiples of 4 minus R, or 0) are even
+    static_assert(CHUNK == 0 || (CHUNK % 2 == 0 && R % 2 == 0), "row pairs inside one chunk");
     static constexpr int KK = K * K;
     static constexpr int kThreads = kWave * WAVES;
-    using XHalo = HaloDma<T, RH, RW, WAVES>;
+    using XHalo = HaloDma<T, LH, RW, WAVES>;
     // the x rectangle in its natural layout, plus the positions an operand block can reach past it: a
     // 16-wide block that starts up to 12 columns into the row after the last one (they meet zero weights)
     static constexpr int kXBytes = XHalo::kBytes + 28 * Traits<T>::kKeyBytes;
     static constexpr int kRowBytes = RW * KK * (int)sizeof(T);
     static constexpr int kRowRegion = mirror_bytes(kRowBytes);
-    static constexpr int kWBytes = RH * kRowRegion;
+    static constexpr int kWBytes = LH * kRowRegion;
     // gather-address tables of the current tile: column terms [patch][g][kx][r], row terms [strip][b][ky]
     static constexpr int kColEntries = 4 * 4 * 4 * 4;
     static constexpr int kRowEntries = STRIPS * NBLK * 4;
@@ -58,22 +67,22 @@ struct InvMfmaCfg {
     static constexpr int kLdsBytes = kXBytes + kWBytes + 16 + kTblBytes;   // + the zero word
     // workgroups that share a CU (LDS is handed out in 512-byte units) and the waves per SIMD that gives
     static constexpr int kLdsAlloc = (kLdsBytes + 511) / 512 * 512;
-    static constexpr int kWgPerCu = (160 * 1024) / kLdsAlloc < (COMPACT ? 3 : 2) ? (160 * 1024) / kLdsAlloc : (COMPACT ? 3 : 2);
+    static constexpr int kWgCap = COMPACT && CHUNK == 0 ? 3 : 2;   // (three leave a lane 80 registers: not enough with chunk tables)
+    static constexpr int kWgPerCu = (160 * 1024) / kLdsAlloc < kWgCap ? (160 * 1024) / kLdsAlloc : kWgCap;
     static_assert(kWgPerCu >= 1, "tile does not fit the 160 KB LDS of a CDNA4 compute unit");
     static constexpr int kWavesPerSimd = kWgPerCu * WAVES / 4;
     // chunk grid of the weight-row copy
     static constexpr int kRowChunks = kRowRegion / 16;
-    static constexpr int kCopyIters = (RH * kRowChunks + kThreads - 1) / kThreads;
 };
 
-template <typename T, int K, int STRIPS, int PPW, bool COMPACT>
-__global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>::kWavesPerSimd)) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
+template <typename T, int K, int STRIPS, int PPW, bool COMPACT, int CHUNK>
+__global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS, PPW, COMPACT, CHUNK>::kWavesPerSimd)) void inverse_mfma_kernel(const T *__restrict__ w, const T *__restrict__ x,
                                                                        float scale, T *__restrict__ out, int H, int W,
                                                                        int heads, int nb, int tiles_y, int units, int splits, GridDecode gd,
                                                                        int pitch) {
     // `pitch`: bytes between consecutive positions of x and out (a longer head vector is served one 32-channel
     // slice per launch, x and out pointing at the slice)
-    using C = InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>;
+    using C = InvMfmaCfg<T, K, STRIPS, PPW, COMPACT, CHUNK>;
     using XHalo = typename C::XHalo;
     constexpr int WAVES = C::WAVES;
     constexpr int SZ = (int)sizeof(T);
@@ -122,9 +131,11 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
 
     XHalo xhalo;
     xhalo.init(wave, lane);
-    int xoff[XHalo::PER_WAVE];
+    int xoff[C::NCH][XHalo::PER_WAVE];   // per chunk of rows (rows past the rectangle repeat the map's last row)
     const bool half_dim = pitch < Traits<T>::kKeyBytes;   // 16-channel heads: see kHalfDimChunks
-    xhalo.offsets(H, W, ry0, rx0, xoff, pitch, half_dim ? kHalfDimChunks : 3);
+#pragma unroll
+    for (int c = 0; c < C::NCH; ++c) xhalo.offsets(H, W, ry0 + c * C::LH, rx0, xoff[c], pitch, half_dim ? kHalfDimChunks : 3);
+    const int nch = CHUNK ? (nrows + C::LH - 1) / C::LH : 1;   // chunks of this tile's rectangle
 
     const int strip = wave / C::NWPS;
     const int sy0 = ty0 + 4 * strip;              // first key row of this wave's strip
@@ -148,44 +159,65 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
         const size_t g0first = (plane_q + (size_t)ry0 * W + rx0) * C::KK * SZ;   // first byte of the first weight row
         const int mis0 = (int)(g0first & 15);   // 16-byte phase of row r: (mis0 + r * pitch_phase) & 15
 
-        if (b > b_begin) workgroup_sync();   // the previous tile's LDS images are no longer read
-        // Stage the rectangle.  Weight rows go from global memory straight into LDS (no registers): a
+        f32x4 acc[PPW][2];
+#pragma unroll
+        for (int p = 0; p < PPW; ++p) {
+            acc[p][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+            acc[p][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll 1
+        for (int c = 0; c < nch; ++c) {
+        const int r_first = c * C::LH;                                                   // rectangle rows of this chunk:
+        const int r_count = nrows - r_first < C::LH ? nrows - r_first : C::LH;           // [r_first, r_first + r_count)
+        if (b > b_begin || c > 0) workgroup_sync();   // the previous LDS images are no longer read
+        // Stage the rows.  Weight rows go from global memory straight into LDS (no registers): a
         // row is mirrored at its 16-byte phase, one 16-byte chunk per lane, 64 chunks per instruction;
         // the chunks at the two ends also bring in bytes of the neighbouring rows, which nothing reads.
         // Only the one chunk that would cross the end of the tensor is copied element by element.
         {
             constexpr int NI = (C::kRowChunks + kWave - 1) / kWave;   // instructions per row
-            constexpr int PER_WAVE = (C::RH * NI + WAVES - 1) / WAVES;
+            constexpr int PER_WAVE = (C::LH * NI + WAVES - 1) / WAVES;
             const char *wrow = reinterpret_cast<const char *>(w) + (g0first - mis0);   // 16-byte aligned
             const size_t left = w_bytes - (g0first - mis0);                             // bytes up to the tensor's end
             const int rem = left < (size_t)0x7fffffff ? (int)left : 0x7fffffff;
 #pragma unroll
             for (int i = 0; i < PER_WAVE; ++i) {
                 const int item = wave + i * WAVES;
-                const int r = item / NI, j = item - r * NI;
-                if (r < nrows) {
-                    const int rel = mis0 + r * row_pitch_bytes;   // row start, from wrow
+                const int rl = item / NI, j = item - rl * NI;   // row inside the chunk
+                if (rl < r_count) {
+                    const int rel = mis0 + (r_first + rl) * row_pitch_bytes;   // row start, from wrow
                     const int nchunks = ((rel & 15) + nbytes + 15) >> 4;
-                    const int c = j * kWave + lane;
-                    const int off = (rel & ~15) + c * 16;
-                    if (c < nchunks && off + 16 <= rem)
-                        global_to_lds_16(wrow + off, w0 + r * C::kRowRegion + j * kWave * 16);
+                    const int cc = j * kWave + lane;
+                    const int off = (rel & ~15) + cc * 16;
+                    if (cc < nchunks && off + 16 <= rem)
+                        global_to_lds_16(wrow + off, w0 + rl * C::kRowRegion + j * kWave * 16);
                 }
             }
             const int rel_last = mis0 + (nrows - 1) * row_pitch_bytes;
             const int end_last = rel_last + nbytes;
-            if (((end_last + 15) & ~15) > rem && wave == 0) {   // the tensor ends inside the last chunk of the last row
+            // the tensor ends inside the last chunk of the rectangle's last row
+            if (((end_last + 15) & ~15) > rem && wave == 0 && nrows - 1 >= r_first && nrows - 1 < r_first + r_count) {
                 const int off = (rem & ~15) + lane * SZ;
                 if (lane < 16 / SZ && off < end_last)
-                    *lds_ptr<T>(w0 + (nrows - 1) * C::kRowRegion + (off - (rel_last & ~15))) = *reinterpret_cast<const T *>(wrow + off);
+                    *lds_ptr<T>(w0 + (nrows - 1 - r_first) * C::kRowRegion + (off - (rel_last & ~15))) = *reinterpret_cast<const T *>(wrow + off);
             }
         }
         // x vectors, natural layout
-        XHalo::issue_at(reinterpret_cast<const char *>(x) + plane_q * pitch, xoff, lds0, wave);
+        {
+            int xo[XHalo::PER_WAVE];   // this chunk's offsets (selected, not indexed: the tables stay in registers)
+#pragma unroll
+            for (int i = 0; i < XHalo::PER_WAVE; ++i) {
+                xo[i] = xoff[0][i];
+#pragma unroll
+                for (int cc = 1; cc < C::NCH; ++cc) xo[i] = c == cc ? xoff[cc][i] : xo[i];
+            }
+            XHalo::issue_at(reinterpret_cast<const char *>(x) + plane_q * pitch, xo, lds0, wave);
+        }
 
         // Gather-address tables, one entry per thread: the address of the weight that query (iy, ix)
         // gives key (jy, jx) is rowterm(iy, jy) + colterm(ix, jx); a pair that does not meet gets BIG.
-        const bool rebuild = mis0 != mis_tables;   // same for the whole workgroup
+        // (Row terms address the rectangle as if all of it were in LDS; a chunk subtracts its first row.)
+        const bool rebuild = c == 0 && mis0 != mis_tables;   // same for the whole workgroup
         if (rebuild) {
             for (int e = tid; e < C::kColEntries + C::kRowEntries; e += C::kThreads) {
                 int term = BIG;
@@ -195,8 +227,8 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
                     // halo columns start at the first query column that sees the patch; the 16-wide block
                     // reaches the last such column (at most K + R + 3 <= 13 of them)
                     const int ix = inv_first(px0 < W ? px0 : W - 1, W, K) + 4 * ge + r;
-                    const int c = jx - win_start(ix < W ? ix : W - 1, W, K);
-                    if (px0 < W && ix <= rx1 && jx < W && (unsigned)c < (unsigned)K) term = (ix - rx0) * C::KK * SZ + c * SZ;
+                    const int cw = jx - win_start(ix < W ? ix : W - 1, W, K);
+                    if (px0 < W && ix <= rx1 && jx < W && (unsigned)cw < (unsigned)K) term = (ix - rx0) * C::KK * SZ + cw * SZ;
                 } else {
                     const int l = e - C::kColEntries;
                     const int kye = l & 3, bb = (l >> 2) % C::NBLK, st = (l >> 2) / C::NBLK;
@@ -226,16 +258,15 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
         }
         if (sy0 >= H) continue;
 
-        f32x4 acc[PPW][2];
-#pragma unroll
-        for (int p = 0; p < PPW; ++p) {
-            acc[p][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-            acc[p][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
+        const int wshift = r_first * C::kRowRegion;                       // what this chunk's LDS rows are short of
+        const int xshift = r_first * C::RW * Traits<T>::kKeyBytes;        // ... the rectangle's, weights and x
+        const int row_of_pair0 = oqy - ry0;                               // rectangle row of the strip's halo row 0
 #pragma unroll
         for (int pb = 0; pb < C::NPAIR; ++pb) {
-            // halo rows that no key row of the strip is seen from are skipped
-            if (__any(rowterm[2 * pb] < BIG || rowterm[2 * pb + 1] < BIG)) {
+            // halo rows that no key row of the strip is seen from are skipped, and (CHUNK) those of other chunks
+            const int rr = row_of_pair0 + 2 * pb;
+            const bool here = CHUNK == 0 || (rr >= r_first && rr < r_first + C::LH);
+            if (here && __any(rowterm[2 * pb] < BIG || rowterm[2 * pb + 1] < BIG)) {
 #pragma unroll
                 for (int p = 0; p < PPW; ++p) {
                     uint32_t wv[4];
@@ -243,7 +274,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
                     for (int u = 0; u < 4; ++u) {
                         const int bb = 2 * pb + (u >> 1);
                         const int r0 = (u & 1) * 2;
-                        int a_lo = rowterm[bb] + colterm[p][r0], a_hi = rowterm[bb] + colterm[p][r0 + 1];
+                        int a_lo = rowterm[bb] + colterm[p][r0] - wshift, a_hi = rowterm[bb] + colterm[p][r0 + 1] - wshift;
                         a_lo = a_lo < zero_addr ? a_lo : zero_addr;
                         a_hi = a_hi < zero_addr ? a_hi : zero_addr;
                         wv[u] = (uint32_t)*lds_ptr<uint16_t>(a_lo) | ((uint32_t)*lds_ptr<uint16_t>(a_hi) << 16);
@@ -251,7 +282,7 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
                     const u32x4 bop = u32x4{wv[0], wv[1], wv[2], wv[3]};
 #pragma unroll
                     for (int hf = 0; hf < 2; ++hf) {
-                        const int a0 = xa_lane + xpatch[p] + (2 * pb) * C::RW * Traits<T>::kKeyBytes + hf * 8;
+                        const int a0 = xa_lane + xpatch[p] - xshift + (2 * pb) * C::RW * Traits<T>::kKeyBytes + hf * 8;
                         const u32x2 lo = lds_read_tr16(a0);
                         const u32x2 hi = lds_read_tr16(a0 + C::RW * Traits<T>::kKeyBytes);
                         const u32x4 aop = u32x4{lo.x, lo.y, hi.x, hi.y};
@@ -260,6 +291,8 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
                 }
             }
         }
+        }   // chunks
+        if (sy0 >= H) continue;
 #pragma unroll
         for (int p = 0; p < PPW; ++p) {
             const int jx = tx0 + 4 * (p0 + p) + kx;
@@ -278,11 +311,11 @@ __global__ __launch_bounds__(kWave *STRIPS *(4 / PPW), (InvMfmaCfg<T, K, STRIPS,
     }
 }
 
-template <typename T, int K, bool COMPACT>
+template <typename T, int K, bool COMPACT, int CHUNK = 0>
 static hipError_t launch_inverse_mfma_c(const Problem &p, const void *w, const void *x, float scale, void *out,
                                         hipStream_t s) {
     constexpr int STRIPS = 2, PPW = 1;
-    using C = InvMfmaCfg<T, K, STRIPS, PPW, COMPACT>;
+    using C = InvMfmaCfg<T, K, STRIPS, PPW, COMPACT, CHUNK>;
     constexpr int kWgPerCu = C::kWgPerCu;
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     // (tile position, head) units, the batch cut into ranges so that every workgroup slot of the chip is used
@@ -291,7 +324,7 @@ static hipError_t launch_inverse_mfma_c(const Problem &p, const void *w, const v
     splits = splits < 1 ? 1 : (splits < p.B ? splits : p.B);
     const int nwg = units * splits;
     const GridDecode gd = make_grid_decode(tiles_x, tiles_y, p.heads, p.B, splits);
-    auto kern = inverse_mfma_kernel<T, K, STRIPS, PPW, COMPACT>;
+    auto kern = inverse_mfma_kernel<T, K, STRIPS, PPW, COMPACT, CHUNK>;
     static LdsAllowed allowed;
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     for (int sl = 0; sl < (p.D + kHeadDim - 1) / kHeadDim; ++sl) {   // one launch per 32-channel slice of the head vector (a 16-channel head is half a slice)
@@ -319,9 +352,24 @@ static bool rect_fits(const Problem &p, int rows, int cols) {
 }
 static bool compact_fits(const Problem &p) { return rect_fits(p, 8 + p.K - 1, kTileX + p.K - 1); }
 
+// Chunked variant: is the first halo row of every 4-row strip an even number of rows below the first row of its
+// tile's rectangle (so that no pair of rows straddles two chunks)?  True for K = 9 on every map (the rows in
+// question are 0 or multiples of 4 minus R = 4); checked all the same.
+static bool chunk_pairs_aligned(const Problem &p) {
+    for (int ty0 = 0; ty0 < p.H; ty0 += 8)
+        for (int sy = ty0; sy < ty0 + 8 && sy < p.H; sy += 4)
+            if ((inv_first(sy, p.H, p.K) - inv_first(ty0, p.H, p.K)) & 1) return false;
+    return true;
+}
+
 template <typename T, int K>
 static hipError_t launch_inverse_mfma_t(const Problem &p, const void *w, const void *x, float scale, void *out,
                                         hipStream_t s) {
+    if (K == 9 && chunk_pairs_aligned(p)) {   // the rectangle in chunks of rows: two or three workgroups per compute unit instead of one
+        if constexpr (K == 9)
+            return compact_fits(p) ? launch_inverse_mfma_c<T, K, true, 8>(p, w, x, scale, out, s)
+                                   : launch_inverse_mfma_c<T, K, false, 10>(p, w, x, scale, out, s);
+    }
     return compact_fits(p) ? launch_inverse_mfma_c<T, K, true>(p, w, x, scale, out, s)
                            : launch_inverse_mfma_c<T, K, false>(p, w, x, scale, out, s);
 }

@@ -193,7 +193,7 @@ def test_degenerate_and_border_heavy_maps(oracle, H, W, k, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("H,W,k", [(40, 50, 11), (45, 70, 13), (34, 33, 9)])
+@pytest.mark.parametrize("H,W,k", [(40, 50, 11), (45, 70, 13), (34, 33, 9), (52, 36, 9)])
 def test_large_windows_many_tiles_odd_batch(oracle, H, W, k, dtype):
     # several tile rows and columns, ragged on both axes, a batch that does not divide by the workgroups'
     # split of it, no bias on the 13-wide window
