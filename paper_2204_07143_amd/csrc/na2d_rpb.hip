@@ -21,10 +21,11 @@
 namespace na2d {
 
 constexpr int kRpbWaves = 4;
-// Queries per segment: at most one wave's worth, fewer when K*K rows are long, so that a
-// wave's staging region stays under 16 KB.
+// Queries per segment, at most: one wave's worth, fewer when K*K rows are long, so that a wave's staging region stays
+// under 10 KB and four or more workgroups share a compute unit.  An image row is cut into the fewest segments
+// that respect this, of equal length (rpb_split).
 __host__ __device__ constexpr int rpb_seg_q(int kk, int elem_bytes) {
-    const int q = (16 * 1024) / (kk * elem_bytes);
+    const int q = (10 * 1024) / (kk * elem_bytes);
     return q > 64 ? 64 : q;
 }
 constexpr int kRpbFinalWaves = 16;
@@ -32,9 +33,9 @@ constexpr int kRpbFinalWaves = 16;
 template <typename T, int K> struct RpbCfg {
     static constexpr int KK = K * K, NB = 2 * K - 1, CELLS = NB * NB;
     static constexpr int kSegQ = rpb_seg_q(KK, (int)sizeof(T));
-    static constexpr int kRegion = mirror_bytes(kSegQ * KK * (int)sizeof(T));   // per wave
+    static constexpr int kRegion = mirror_bytes(kSegQ * KK * (int)sizeof(T));   // per wave, at most
     static constexpr int kTableBytes = ((CELLS * 4) + 15) & ~15;
-    static constexpr int kLdsBytes = kRpbWaves * (kRegion + kTableBytes);
+    static constexpr int kLdsBytes = kRpbWaves * (kRegion + kTableBytes);        // at most
     static constexpr int kSlotsPerLane = (KK + kWave - 1) / kWave;
 };
 
@@ -42,13 +43,21 @@ template <typename T, int K> struct RpbCfg {
 // launch has on the order of a thousand workgroups (partials) whatever the batch size.
 struct RpbSplit {
     int segs_per_row, segs_per_plane, groups_per_plane, segs_per_group;
+    int seg_q;    // queries per segment (the last one of a row may be shorter)
+    int region;   // bytes of a wave's staging region
 };
 static inline RpbSplit rpb_split(int planes, int H, int W, int K, int elem_bytes) {
     RpbSplit s;
-    const int seg_q = rpb_seg_q(K * K, elem_bytes);
-    s.segs_per_row = (W + seg_q - 1) / seg_q;
+    const int max_q = rpb_seg_q(K * K, elem_bytes);
+    s.segs_per_row = (W + max_q - 1) / max_q;
+    s.seg_q = (W + s.segs_per_row - 1) / s.segs_per_row;   // <= max_q
+    s.region = mirror_bytes(s.seg_q * K * K * elem_bytes);
     s.segs_per_plane = H * s.segs_per_row;
-    int groups = (1024 + planes - 1) / planes;
+    // about as many workgroups as the chip holds at once (LDS: four wave regions and tables each), 1024 at most
+    const int nb = 2 * K - 1;
+    const int lds = kRpbWaves * (s.region + ((nb * nb * 4 + 15) & ~15));
+    const int per_cu = (160 * 1024) / lds < 4 ? ((160 * 1024) / lds < 1 ? 1 : (160 * 1024) / lds) : 4;
+    int groups = (256 * per_cu + planes - 1) / planes;
     const int max_groups = (s.segs_per_plane + kRpbWaves - 1) / kRpbWaves;
     if (groups > max_groups) groups = max_groups;
     if (groups < 1) groups = 1;
@@ -64,8 +73,8 @@ __global__ __launch_bounds__(256) void rpb_partial_kernel(const T *__restrict__ 
     extern __shared__ __align__(16) char lds[];
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // (scalar: everything about a segment is wave-uniform)
-    char *region = lds + wave * C::kRegion;
-    float *tables = reinterpret_cast<float *>(lds + kRpbWaves * C::kRegion);
+    char *region = lds + wave * sp.region;
+    float *tables = reinterpret_cast<float *>(lds + kRpbWaves * sp.region);
     float *mine = tables + wave * (C::kTableBytes / 4);
     const int plane = blockIdx.x / sp.groups_per_plane, group = blockIdx.x % sp.groups_per_plane;
     constexpr int R = K / 2;
@@ -85,8 +94,8 @@ __global__ __launch_bounds__(256) void rpb_partial_kernel(const T *__restrict__ 
                                                                             : sp.segs_per_plane;
     for (int seg = group * sp.segs_per_group + wave; seg < seg_end; seg += kRpbWaves) {
         const int qy = seg / sp.segs_per_row;
-        const int x0 = (seg - qy * sp.segs_per_row) * C::kSegQ;
-        const int x1 = x0 + C::kSegQ < W ? x0 + C::kSegQ : W;
+        const int x0 = (seg - qy * sp.segs_per_row) * sp.seg_q;
+        const int x1 = x0 + sp.seg_q < W ? x0 + sp.seg_q : W;
         const size_t g0 = (((size_t)plane * H + qy) * W + x0) * C::KK * sizeof(T);
         stage_in<T, C::kSegQ * C::KK * (int)sizeof(T), kWave>(reinterpret_cast<const char *>(ds), g0,
                                                               (x1 - x0) * C::KK * (int)sizeof(T), region, lane);
@@ -241,7 +250,8 @@ static hipError_t launch_rpb_bwd_t(const Problem &p, const void *ds, float *d_rp
     static_assert(C::kLdsBytes <= 160 * 1024, "segments do not fit the 160 KB LDS of a CDNA4 compute unit");
     static LdsAllowed allowed;
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(p.planes() * sp.groups_per_plane), dim3(256), C::kLdsBytes, s,
+    const int lds_bytes = kRpbWaves * (sp.region + C::kTableBytes);   // <= kLdsBytes: seg_q <= kSegQ
+    hipLaunchKernelGGL(kern, dim3(p.planes() * sp.groups_per_plane), dim3(256), lds_bytes, s,
                        static_cast<const T *>(ds), static_cast<float *>(workspace), p.H, p.W, sp, p.B, p.heads);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
