@@ -177,7 +177,7 @@ int na2d_bwd(const na2d_problem *p, const void *q, const void *k, const void *v,
  * na2d_fused_fwd stored for every query.  The attention weights are recomputed per tile as
  * exp(scale <q, k> + bias - lse) and neither they nor dp / ds reach memory.  `rpb` may be NULL
  * (no bias in the forward).  No output may alias an input or another output.
- * For the 16-bit types with k <= 7 and D = 32 or 16 this runs two kernels: query patches (dq, the partial bias
+ * For the 16-bit types with k <= 9 and D = 32 or 16 this runs two kernels: query patches (dq, the partial bias
  * gradients and delta_n = sum_j P[n, j] dP[n, j]) and key patches (dk, dv); na2d_fused_bwd_is_fused() tells.
  * There d_rpb is summed per workgroup with integer atomics in 64-bit fixed point, so it does not depend on
  * the order of the additions.  The fixed point has 32 fraction bits; a ds enters it with a relative error

@@ -1,4 +1,4 @@
-// Fused neighbourhood attention backward on the matrix cores (f16 / bf16, K <= 7): the gradients
+// Fused neighbourhood attention backward on the matrix cores (f16 / bf16, K <= 9): the gradients
 // of q, k, v and of the bias table from q, k, v, dout and the log-sum-exp of every query that the
 // fused forward left behind; the k*k attention weights and their gradients never reach memory
 // (arXiv 2204.07143: Eq. 2-4 differentiated; Appendix A lists the five gradients).
@@ -63,14 +63,19 @@ struct FbwdQCfg {
     static constexpr int kThreads = kWave * WAVES;
     static constexpr int kHaloBytes = Halo::kBytes;
     static constexpr int kStageBytes = 2 * kHaloBytes;   // keys, then values
+    // Two buffer pairs where two workgroups then still share a compute unit's LDS; one pair, reloaded between tiles
+    // while the other workgroup computes, where that is what makes them fit (K = 9)
+    static constexpr int kTblPad = 3;                    // cells in front of and behind a table (see the cell offsets)
+    static constexpr int kTblBytes = (CELLS + 2 * kTblPad) * 8;
+    static constexpr bool kOneStage = 2 * kStageBytes + kTblBytes > 80 * 1024;
+    static constexpr int NSTAGE = kOneStage ? 1 : 2;
     // Bias-gradient tables behind the buffers, 64-bit fixed point (see above): as many as fit beside two
     // workgroups' buffers in a compute unit's 160 KB, at most one per wave
-    static constexpr int kTblBytes = CELLS * 8;
-    static constexpr int kTblFit = (80 * 1024 - 2 * kStageBytes) / kTblBytes;
+    static constexpr int kTblFit = (80 * 1024 - NSTAGE * kStageBytes) / kTblBytes;
     static constexpr int NTBL = kTblFit >= WAVES ? WAVES : (kTblFit >= 4 ? 4 : (kTblFit >= 2 ? 2 : 1));
     static_assert(kTblFit >= 1, "no room for a bias-gradient table");
     static constexpr int kFracBits = 32;   // fraction bits of the tables
-    static constexpr int kLdsBytes = 2 * kStageBytes + NTBL * kTblBytes;
+    static constexpr int kLdsBytes = NSTAGE * kStageBytes + NTBL * kTblBytes;
 };
 
 template <typename T, int K, bool RPB>
@@ -180,47 +185,52 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
 #pragma unroll
         for (int i = 0; i < 4; ++i) cell[i] = (unsigned)(c0 + i) < (unsigned)K ? cell0 + i : -1;
     };
-    // table cell of result 4G + i in byte i of word G; outside the window (where dS is exactly 0 and adding it
-    // changes nothing) a cell that differs from lane to lane, so that the adds of one instruction do not pile
-    // up on one address
-    uint32_t cellp[RPB ? P::NBLK : 1];
+    // Where the results of block G are added: byte offset of the cell of result 4G inside a table; results 4G + 1 .. + 3
+    // go to the three cells behind it (the cells of a group that lie inside the window are neighbours in one row of
+    // the table).  Results outside the window are exactly 0 and adding them changes nothing, so they may go to any
+    // cell: those of a group with a position inside the window simply land next to it, up to three cells in front of
+    // or behind the table (kTblPad); a group with no position inside the window gets four cells that differ from lane
+    // to lane, so that the adds of one instruction do not pile up on one address.
+    int coff[RPB ? P::NBLK : 1];
     {
         const T *tbl = rpb != nullptr ? rpb + (size_t)head * C::CELLS : nullptr;
+        constexpr int GB = K > 7 ? 2 : 4;   // groups per batch of bias loads (a batch of temporaries at a time)
 #pragma unroll
-        for (int G0 = 0; G0 < P::NBLK; G0 += 4) {   // sixteen loads of the bias table in flight at a time
-            int cell[16];
-            f16_t bias[16];
+        for (int G0 = 0; G0 < P::NBLK; G0 += GB) {
+            int cell[4 * GB];
+            f16_t bias[4 * GB];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < GB; ++u) {
                 int c4[4] = {-1, -1, -1, -1};
                 if (G0 + u < P::NBLK) cell_group(lane, G0 + u, c4);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) cell[4 * u + i] = c4[i];
                 if constexpr (RPB) {
                     if (G0 + u < P::NBLK) {
-                        uint32_t w = 0;
+                        int first = -1;   // cell of result 4G, worked back from the first one inside the window
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) w |= (uint32_t)(c4[i] >= 0 ? c4[i] : lane % C::CELLS) << (8 * i);
-                        cellp[G0 + u] = w;
+                        for (int i = 3; i >= 0; --i) first = c4[i] >= 0 ? c4[i] - i : first;
+                        const bool any = (c4[0] & c4[1] & c4[2] & c4[3]) >= 0;
+                        coff[G0 + u] = ((any ? first : lane % (C::CELLS - 3)) + C::kTblPad) * 8;
                     }
                 }
             }
 #pragma unroll
-            for (int e = 0; e < 16; ++e) bias[e] = (f16_t)0.f;
+            for (int e = 0; e < 4 * GB; ++e) bias[e] = (f16_t)0.f;
             if (tbl != nullptr) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) bias[e] = bias_to_f16(tbl[cell[e] < 0 ? 0 : cell[e]]);
+                for (int e = 0; e < 4 * GB; ++e) bias[e] = bias_to_f16(tbl[cell[e] < 0 ? 0 : cell[e]]);
             }
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
+            for (int e = 0; e < 4 * GB; ++e)
                 if (4 * G0 + e < P::NEL) biasm[(4 * G0 + e) >> 1][e & 1] = cell[e] >= 0 ? bias[e] : (f16_t)-INFINITY;
+            if constexpr (K > 7) __builtin_amdgcn_sched_barrier(0);
         }
     }
-    static_assert(C::CELLS < 255, "cells are kept as bytes");
-    const int tbl0 = lds0 + 2 * C::kStageBytes;
+    const int tbl0 = lds0 + C::NSTAGE * C::kStageBytes;
     const int mytbl = tbl0 + (wave % C::NTBL) * C::kTblBytes;
     if constexpr (RPB) {
-        for (int i = tid; i < C::NTBL * C::CELLS; i += C::kThreads) *lds_ptr<unsigned long long>(tbl0 + i * 8) = 0ull;
+        for (int i = tid; i < C::NTBL * (C::kTblBytes / 8); i += C::kThreads) *lds_ptr<unsigned long long>(tbl0 + i * 8) = 0ull;
     }
 
     auto compute = [&](auto par_c, const u32x4 &qreg, const u32x4 &dreg, float lse2, int b) {
@@ -277,7 +287,7 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
                 dsv[r] = weight(e, sacc[r]) * (pacc[r] - delta);   // exactly 0 outside the window
                 if constexpr (RPB) {
                     const long long fx = (long long)(int)(dsv[r] * fx_scale) << fx_shift;   // truncated, saturating; NaN -> 0
-                    __hip_atomic_fetch_add(lds_ptr<unsigned long long>(mytbl + ((cellp[bk] >> (8 * r)) & 0xffu) * 8),
+                    __hip_atomic_fetch_add(lds_ptr<unsigned long long>(mytbl + coff[bk] + 8 * r),
                                            (unsigned long long)fx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
@@ -318,13 +328,23 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
         const bool upper = half_dim && g >= 2;   // lanes whose channels a 16-channel head does not have
         const u32x4 qreg = upper ? u32x4{0u, 0u, 0u, 0u} : qnext, dreg = upper ? u32x4{0u, 0u, 0u, 0u} : dnext;
         const float lse2 = lnext * kLog2e;
-        if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
-        compute(par_c, qreg, dreg, lse2, b);
+        if constexpr (C::kOneStage) {
+            compute(par_c, qreg, dreg, lse2, b);
+            if (b + 1 < b_end) {
+                workgroup_sync();   // nobody still reads the halos
+                issue(b + 1, 0);
+            }
+        } else {
+            if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
+            compute(par_c, qreg, dreg, lse2, b);
+        }
         ++b;
     };
     while (b < b_end) {
         step(IntC<0>{});
-        if (b < b_end) step(IntC<1>{});
+        if constexpr (!C::kOneStage) {
+            if (b < b_end) step(IntC<1>{});
+        }
     }
 
     if constexpr (RPB) {
@@ -333,7 +353,7 @@ __global__ __launch_bounds__(512, 4) void fbwd_q_kernel(const T *__restrict__ q,
         for (int cell = tid; cell < C::CELLS; cell += C::kThreads) {
             long long sum = 0;
 #pragma unroll
-            for (int t = 0; t < C::NTBL; ++t) sum += (long long)*lds_ptr<unsigned long long>(tbl0 + t * C::kTblBytes + cell * 8);
+            for (int t = 0; t < C::NTBL; ++t) sum += (long long)*lds_ptr<unsigned long long>(tbl0 + t * C::kTblBytes + (cell + C::kTblPad) * 8);
             // row of this workgroup's partial: the partials of a head follow each other (rpb_cell_stride)
             rpb_partial[(size_t)((head * splits + work.split) * gd.npos + work.pos) * rpb_cell_stride(C::CELLS) + cell] =
                 (float)((double)sum * (1.0 / 4294967296.0));   // 2^-32
@@ -384,8 +404,14 @@ struct FbwdKvCfg {
     static constexpr int STRIPS = 2;
     static constexpr int WAVES = 4 * STRIPS;
     static constexpr int TY = 4 * STRIPS;
-    static constexpr int RH = TY + K - 1 + (COMPACT ? 0 : R), RW = kTileX + K - 1 + (COMPACT ? 0 : R);   // the rectangle
-    static_assert(RH <= 32, "row flags");
+    // CHUNKED (K = 9): the images hold 16 rows of the rectangle at a time.  A rectangle of up to 20 rows (tiles next to
+    // the far border) is taken in two chunks, its first 16 rows and its last 16 (the rows they share are used from the
+    // first), so that two workgroups still share a compute unit; the accumulators stay in registers across them.
+    static constexpr bool CHUNKED = K > 7;
+    static_assert(!CHUNKED || !COMPACT, "the chunked images are always the wide ones");
+    static constexpr int kRowsMax = TY + K - 1 + (COMPACT ? 0 : R);   // rows of a rectangle, at most
+    static constexpr int RH = CHUNKED ? 16 : kRowsMax, RW = kTileX + K - 1 + (COMPACT ? 0 : R);   // the images
+    static_assert(kRowsMax <= 32 && kRowsMax <= 2 * RH, "row flags; two chunks");
     static constexpr int NB = 2 * K - 1;
     static constexpr int kThreads = kWave * WAVES;
     using XHalo = HaloDma<T, RH, RW, WAVES>;
@@ -395,8 +421,9 @@ struct FbwdKvCfg {
     static_assert(SP >= RW && SP % 4 == 0, "fp32 rows");
     static constexpr int kSItems = (RH * SP + kWave - 1) / kWave;   // 64-lane loads per fp32 image
     static_assert(kSItems <= WAVES, "one fp32 load per wave and image");
+    static_assert(!CHUNKED || kSItems * kWave <= RH * SP, "every word of a chunk's fp32 images is a row of the chunk");
     static constexpr int kSBytes = (kSItems * kWave + 32) * 4;      // + the reach of the last row's blocks
-    static constexpr int BP = 24;                                   // row pitch (elements) of a bias copy
+    static constexpr int BP = K > 7 ? 28 : 24;                      // row pitch (elements) of a bias copy (a multiple of 4)
     static_assert(NB + 3 + 3 + 3 < BP, "a shifted run of four stays inside its row");
     static constexpr int kBiasCopy = NB * BP * 2;
     static constexpr int kBiasBytes = 4 * kBiasCopy;
@@ -447,8 +474,12 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
 
     const int ty0 = work.ty * C::TY, tx0 = work.tx * kTileX;
     const int tx1 = tx0 + kTileX - 1 < W - 1 ? tx0 + kTileX - 1 : W - 1;
-    const int ry0 = inv_first(ty0, H, K);   // the rectangle (fits RH x RW: checked by the host)
+    const int ty1 = ty0 + C::TY - 1 < H - 1 ? ty0 + C::TY - 1 : H - 1;
+    const int ry0 = inv_first(ty0, H, K);   // the rectangle (fits kRowsMax x RW: checked by the host)
     const int rx0 = inv_first(tx0, W, K), rx1 = inv_last(tx1, W, K);
+    const int nrows = inv_last(ty1, H, K) - ry0 + 1;
+    const int nch = C::CHUNKED && nrows > C::RH ? 2 : 1;   // chunks of the rectangle
+    const int org1 = nrows - C::RH;                        // first rectangle row of the second chunk
 
     // loads of one plane
     XHalo xhalo;
@@ -483,7 +514,7 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
     // which of the lane's (position, key) pairs meet: the key must lie in the window of the query
     unsigned rowok = 0, colok = 0;
 #pragma unroll
-    for (int b = 0; b < C::RH; ++b) {
+    for (int b = 0; b < C::kRowsMax; ++b) {
         const int iy = oqy + b;
         const bool ok = b < nblk && key_ok && (unsigned)(jy - win_start(iy < H ? iy : H - 1, H, K)) < (unsigned)K;
         rowok |= ok ? (1u << b) : 0u;
@@ -509,28 +540,41 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
 
     for (int b = b_begin; b < b_end; ++b) {
         const size_t plane = (size_t)b * heads + head;
-        if (b > b_begin) workgroup_sync();   // the previous plane's images are no longer read
-        XHalo::issue_at(reinterpret_cast<const char *>(q) + plane * plane_px * pitch, xoff, q0, wave);
-        XHalo::issue_at(reinterpret_cast<const char *>(dout) + plane * plane_px * pitch, xoff, d0, wave);
-        if (wave < C::kSItems) {
-            global_to_lds_4(reinterpret_cast<const char *>(lse2) + plane * plane_px * 4, (unsigned)soff, l0 + wave * kWave * 4);
-            global_to_lds_4(reinterpret_cast<const char *>(delta) + plane * plane_px * 4, (unsigned)soff, e0 + wave * kWave * 4);
-        }
         // the lane's key and value: bytes [16g, 16g+16) (B operands)
         const size_t koff = (plane * plane_px + (size_t)(jy < H ? jy : H - 1) * W + (jx < W ? jx : W - 1)) * pitch + (g & chunk_mask) * 16;
         const bool upper = half_dim && g >= 2;   // lanes whose channels a 16-channel head does not have
         const u32x4 kload = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(k) + koff);
         const u32x4 vload = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(v) + koff);
         const u32x4 kreg = upper ? u32x4{0u, 0u, 0u, 0u} : kload, vreg = upper ? u32x4{0u, 0u, 0u, 0u} : vload;
+        f32x4 ak[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};   // dk^T, dv^T: channels 8g + 4 hf + r of the lane's key
+        f32x4 av[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll 1
+        for (int c = 0; c < nch; ++c) {
+        if (b > b_begin || c > 0) workgroup_sync();   // the previous images are no longer read
+        // rows of the rectangle in the images: [org, org + RH); the second chunk lies inside the map as a whole
+        const int org = c ? org1 : 0;
+        {
+            int xo[XHalo::PER_WAVE];
+#pragma unroll
+            for (int i = 0; i < XHalo::PER_WAVE; ++i) xo[i] = xoff[i] >= 0 ? xoff[i] + org * W * pitch : -1;
+            XHalo::issue_at(reinterpret_cast<const char *>(q) + plane * plane_px * pitch, xo, q0, wave);
+            XHalo::issue_at(reinterpret_cast<const char *>(dout) + plane * plane_px * pitch, xo, d0, wave);
+        }
+        if (wave < C::kSItems) {
+            global_to_lds_4(reinterpret_cast<const char *>(lse2) + plane * plane_px * 4, (unsigned)(soff + org * W * 4), l0 + wave * kWave * 4);
+            global_to_lds_4(reinterpret_cast<const char *>(delta) + plane * plane_px * 4, (unsigned)(soff + org * W * 4), e0 + wave * kWave * 4);
+        }
         wait_global_loads();
         workgroup_sync();
         if (!active) continue;
 
-        f32x4 ak[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};   // dk^T, dv^T: channels 8g + 4 hf + r of the lane's key
-        f32x4 av[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-        for (int blk = 0; blk < nblk; ++blk) {
-            const int xr = (row0 + blk) * C::RW * KB;   // this row inside the q / dout images
-            const int sr = (row0 + blk) * C::SP * 4;    // ... inside the fp32 images
+        // this chunk's part of the rows that see the patch: rectangle rows below RH in the first chunk, the others in
+        // the second
+        const int blk_lo = c ? (C::RH - row0 > 0 ? C::RH - row0 : 0) : 0;
+        const int blk_hi = (nch == 2 && c == 0) ? (nblk < C::RH - row0 ? nblk : C::RH - row0) : nblk;
+        for (int blk = blk_lo; blk < blk_hi; ++blk) {
+            const int xr = (row0 + blk - org) * C::RW * KB;   // this row inside the q / dout images
+            const int sr = (row0 + blk - org) * C::SP * 4;    // ... inside the fp32 images
             const u32x4 aq = *lds_ptr<u32x4>(q0 + xr + arow);
             const u32x4 ad = *lds_ptr<u32x4>(d0 + xr + arow);
             struct __attribute__((packed, aligned(4))) F4 {
@@ -572,6 +616,7 @@ __global__ __launch_bounds__(512, (FbwdKvCfg<T, K, COMPACT>::kWavesPerSimd)) voi
                 }
             }
         }
+        }   // chunks
         if (key_ok && !upper) {
             const size_t o = (plane * plane_px + (size_t)jy * W + jx) * pitch + g * 16;
             store16_stream(reinterpret_cast<char *>(dk) + o,
@@ -622,9 +667,13 @@ template <typename T, int K>
 static hipError_t launch_fbwd_kv_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
                                    float scale, const float *lse, const float *delta, const void *dout, void *dk, void *dv,
                                    hipStream_t s) {
-    return kv_rect_fits(p, 8 + K - 1, kTileX + K - 1)
-               ? launch_fbwd_kv_c<T, K, true>(p, q, k, v, rpb, scale, lse, delta, dout, dk, dv, s)
-               : launch_fbwd_kv_c<T, K, false>(p, q, k, v, rpb, scale, lse, delta, dout, dk, dv, s);
+    if constexpr (K > 7) {   // (chunked images: one size)
+        return launch_fbwd_kv_c<T, K, false>(p, q, k, v, rpb, scale, lse, delta, dout, dk, dv, s);
+    } else {
+        return kv_rect_fits(p, 8 + K - 1, kTileX + K - 1)
+                   ? launch_fbwd_kv_c<T, K, true>(p, q, k, v, rpb, scale, lse, delta, dout, dk, dv, s)
+                   : launch_fbwd_kv_c<T, K, false>(p, q, k, v, rpb, scale, lse, delta, dout, dk, dv, s);
+    }
 }
 
 hipError_t launch_fbwd_kv(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
@@ -634,6 +683,7 @@ hipError_t launch_fbwd_kv(const Problem &p, const void *q, const void *k, const 
         case 3: return launch_fbwd_kv_t<TT, 3>(p, q, k, v, rpb, scale, lse, delta, dout, dk, dv, s);      \
         case 5: return launch_fbwd_kv_t<TT, 5>(p, q, k, v, rpb, scale, lse, delta, dout, dk, dv, s);      \
         case 7: return launch_fbwd_kv_t<TT, 7>(p, q, k, v, rpb, scale, lse, delta, dout, dk, dv, s);      \
+        case 9: return launch_fbwd_kv_t<TT, 9>(p, q, k, v, rpb, scale, lse, delta, dout, dk, dv, s);      \
         default: return hipErrorInvalidValue;                                                             \
     }
     if (p.dtype == NA2D_F16) { NA2D_FBKV_K(f16_t) }
@@ -642,12 +692,22 @@ hipError_t launch_fbwd_kv(const Problem &p, const void *q, const void *k, const 
     return hipErrorInvalidValue;
 }
 
+// Is every 4-column key patch seen from at most 16 query columns (one MFMA block per rectangle row)?  Always so
+// away from short axes (K + (K-1)/2 + 3 <= 16 columns); on an axis of at most 2K + 2 positions a patch can be seen
+// from both clamped ends at once, and then it depends on the length.
+static bool kv_patch_cols_fit(const Problem &p) {
+    for (int px = 0; px < p.W; px += 4)
+        if (inv_last(px + 3 < p.W - 1 ? px + 3 : p.W - 1, p.W, p.K) - inv_first(px, p.W, p.K) + 1 > 16) return false;
+    return true;
+}
+
 // The second kernel sizes its images for key tiles that are next to at most one border per axis: a 16 x 8 tile
 // whose query rectangle exceeds (8 + K-1 + R) x (16 + K-1 + R) positions (short axes, where a ragged tile is
 // close to both borders) does not fit, and such maps take the unfused steps instead.
 bool fused_bwd_supported(const Problem &p) {
     const int R = p.K / 2;
-    return (p.D == kHeadDim || p.D == kHalfDim) && p.dtype != NA2D_F32 && p.K <= 7 && kv_rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
+    return (p.D == kHeadDim || p.D == kHalfDim) && p.dtype != NA2D_F32 && p.K <= 9 && kv_patch_cols_fit(p) &&
+           kv_rect_fits(p, 8 + p.K - 1 + R, kTileX + p.K - 1 + R);
 }
 
 AvRpbSplit fused_bwd_split(const Problem &p) {
@@ -664,6 +724,7 @@ hipError_t launch_fbwd_q(const Problem &p, const void *q, const void *k, const v
         case 3: return launch_fbwd_q_t<TT, 3>(p, q, k, v, rpb, scale, lse, dout, dq, delta, lse2, rpb_partial, s);       \
         case 5: return launch_fbwd_q_t<TT, 5>(p, q, k, v, rpb, scale, lse, dout, dq, delta, lse2, rpb_partial, s);       \
         case 7: return launch_fbwd_q_t<TT, 7>(p, q, k, v, rpb, scale, lse, dout, dq, delta, lse2, rpb_partial, s);       \
+        case 9: return launch_fbwd_q_t<TT, 9>(p, q, k, v, rpb, scale, lse, dout, dq, delta, lse2, rpb_partial, s);       \
         default: return hipErrorInvalidValue;                                                                      \
     }
     if (p.dtype == NA2D_F16) { NA2D_FBQ_K(f16_t) }
