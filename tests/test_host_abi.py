@@ -104,7 +104,7 @@ def test_workspace_sizes():
     fused = binding.na2d_workspace_bytes(p, binding.WS_FUSED_BWD)
     assert binding.na2d_fused_bwd_is_fused(p) == 1
     assert 64 * 2 * 56 * 56 * 4 <= fused < 64 * 2 * 56 * 56 * 49 * 2 and fused % 256 == 0
-    for other in (P(B=2, heads=2, H=56, W=56, k=7, dtype=0), P(B=2, heads=2, H=56, W=56, k=9, dtype=1)):   # fp32; k > 7
+    for other in (P(B=2, heads=2, H=56, W=56, k=7, dtype=0), P(B=2, heads=2, H=56, W=56, k=11, dtype=1)):   # fp32; k > 9
         assert binding.na2d_fused_bwd_is_fused(other) == 0
         assert binding.na2d_workspace_bytes(other, binding.WS_FUSED_BWD) >= binding.na2d_workspace_bytes(other, binding.WS_BWD)
     for H, W, k in ((28, 28, 7), (20, 16, 5), (19, 37, 5), (7, 7, 7), (14, 14, 7), (3, 3, 3)):   # ragged / far-border tiles included
