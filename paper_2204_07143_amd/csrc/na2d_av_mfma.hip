@@ -9,7 +9,8 @@
 // and one head and walks a range of the batch: the per-lane gather addresses of the weights and
 // the operand addresses of the values are built once.  Per tile the value halo (natural layout)
 // and the tile's eight weight row runs (mirrored at their 16-byte phase) reach one of two LDS
-// stages by direct loads while the previous tile is computed.  Halo positions are numbered
+// stages by direct loads while the previous tile is computed (large windows, k >= 9, keep one stage,
+// loaded between tiles, so that two workgroups still share a compute unit's LDS).  Halo positions are numbered
 // h = hy * (K+3) + hx; MFMA pair m contracts over the positions 32m .. 32m+31 in the lane order
 //   lane group g, element e:  position 32m + 16 (e / 4) + 4g + e % 4.
 //   A operand: channel j of those positions, two transposing LDS reads from the value halo;

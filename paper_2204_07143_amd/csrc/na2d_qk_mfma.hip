@@ -11,15 +11,16 @@
 // (scale, bias) and one 2-byte LDS store.
 //
 // Eight waves share a 16 x 8 query tile, one 4 x 4 patch each, so a SIMD holds four waves whose
-// LDS, matrix and conversion work overlap (two where the images of a large window or of a second
-// 32-channel slice fill the LDS: k >= 9, head dim 64).  The key halo reaches LDS by direct loads in its
+// LDS, matrix and conversion work overlap (two where the images of a second 32-channel slice fill the
+// LDS: head dim 64).  The key halo reaches LDS by direct loads in its
 // natural 64-byte-per-key layout (consecutive keys of an operand block are consecutive in LDS,
 // so the 16-byte operand reads do not collide), into one of two buffers: the next tile's halo
 // arrives while this tile is computed.  Results go to one of two staging images of the tile's
 // eight row runs (phase-free: slot tables do not depend on where a run starts in memory); wave w
 // streams row w of the previous tile to global memory while the current tile is computed.  One
-// workgroup barrier per tile.  Workgroups walk down the columns of a plane, so a wave's window
-// and bias tables change only at the top and bottom of the map.
+// workgroup barrier per tile.  Large windows keep one staging image (k = 9) and one halo buffer as well
+// (k = 11, 13) so that two workgroups still share a compute unit's LDS: a tile is then filled, and after a
+// second barrier streamed out (and the next halo loaded), while the other workgroup computes.
 #include "na2d_kernels.hpp"
 #include "na2d_mfma.hpp"
 #include "na2d_tile.hpp"
