@@ -58,8 +58,9 @@ def algorithmic_bytes(p) -> dict:
         # the composed backward on stored weights; where it fuses grad-a with the softmax backward (16-bit, k <= 7, D = 32) dp is never stored and
         # ds is read by grad-q and grad-k only: grad-a + softmax backward (attn, dout, v in; ds out), grad-v,
         # grad-q (+ grad-b), grad-k.  Elsewhere it is the six steps one after the other.
-        "bwd": (nq * ((2 * D * e + 2 * kk * e) + 3 * (2 * D * e + kk * e))
-                if (p.dtype != "f32" and p.k <= 7 and p.D == 32) else 4 * contraction + nq * 4 * kk * e),
+        # (k = 9: that fusion, but grad-b as a step of its own, reading ds once more.)
+        "bwd": (nq * ((2 * D * e + 2 * kk * e) + 3 * (2 * D * e + kk * e) + (kk * e if p.k > 7 else 0))
+                if (p.dtype != "f32" and p.k <= 9 and p.D == 32) else 4 * contraction + nq * 4 * kk * e),
     }
 
 

@@ -158,7 +158,7 @@ int na2d_qk_bwd_rpb_noalloc(const na2d_problem *p, const void *ds, float *d_rpb,
 
 /*
  * Whole backward of out = NA(q, k, v, rpb): grad-a, grad-v, softmax backward, grad-q, grad-k
- * and (if d_rpb != NULL) grad-b.  For the 16-bit types with k <= 7, grad-a and the softmax
+ * and (if d_rpb != NULL) grad-b.  For the 16-bit types with k <= 9 (D = 32 or 16), grad-a and the softmax
  * backward run as one kernel and dp is never stored (so ds is computed from the unrounded dp);
  * otherwise the six steps run one after the other exactly as the separate entry points do.
  * `attn` is the softmax output of the forward.  `workspace` must hold

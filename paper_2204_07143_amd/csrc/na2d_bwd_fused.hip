@@ -1,4 +1,4 @@
-// Grad-a fused with the softmax backward on the matrix cores (f16 / bf16, K <= 7):
+// Grad-a fused with the softmax backward on the matrix cores (f16 / bf16, K <= 9):
 //   dp[n, a, c] = <dout_n, v_{rho(n; a, c)}>                         (grad-a)
 //   ds[n, :]    = attn[n, :] * (dp[n, :] - <attn[n, :], dp[n, :]>)   (softmax backward)
 // (arXiv 2204.07143, Eq. 3-4 differentiated; Appendix A lists the gradients).  dp never leaves the
@@ -37,11 +37,19 @@ struct BwdFusedCfg {
     static constexpr int kRowBytes = kTileX * KK * (int)sizeof(T);
     static constexpr int kRowRegion = mirror_bytes(kRowBytes);
     static constexpr int kRowChunks = (kRowBytes + 15 + 15) / 16;
-    static_assert(kRowChunks <= 2 * kWave, "a row run is loaded by two instructions of one wave");
+    static constexpr int kRowPasses = (kRowChunks + kWave - 1) / kWave;   // load instructions of one wave per row run
     static constexpr int kWBytes = TY * kRowRegion;
-    static constexpr int kZeroBytes = kThreads * 4;   // one private word per thread
+    // Large windows keep the gather addresses two per register, as 16-bit offsets without the row run's 16-byte
+    // phase, which is added when they are used: a thread's private zero area is then 16 bytes, so that it reads
+    // zero (and takes the dropped results) at any phase.
+    static constexpr bool PACKED = K > 7;
+    static constexpr int kZeroEach = PACKED ? 16 : 4;
+    static constexpr int kZeroBytes = kThreads * kZeroEach;   // one private word (or four) per thread
     static constexpr int kStageBytes = kHaloBytes + kWBytes + kZeroBytes;
-    static constexpr int kLdsBytes = 2 * kStageBytes;
+    // Two stages where two workgroups then still share a compute unit's LDS; one stage (k = 9), computed in, streamed
+    // out and reloaded in turn while the other workgroup computes, where that is what makes them fit
+    static constexpr bool kOneStage = 2 * kStageBytes > 80 * 1024;
+    static constexpr int kLdsBytes = (kOneStage ? 1 : 2) * kStageBytes;
     static_assert(kStageBytes < 65536, "the second stage is reached through the 16-bit offset of the LDS accesses");
 };
 
@@ -62,7 +70,7 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
     const int j = lane & 15, g = lane >> 4, jy = j >> 2, jx = j & 3;
     const int lds0 = lds_addr(lds);
     const int w0 = lds0 + C::kHaloBytes;          // attention / ds row runs (the value halo comes first)
-    const int my_zero = w0 + C::kWBytes + tid * 4;
+    const int my_zero = w0 + C::kWBytes + tid * C::kZeroEach;
 
     const int wg = xcd_contiguous_block(blockIdx.x, gridDim.x);
     if (wg >= units * splits) return;
@@ -102,15 +110,23 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
             const int region = w0 + par * C::kStageBytes + wave * C::kRowRegion;
             // only the last row run of the tensor can end inside a chunk that reaches past the tensor
             const bool at_end = b == nb - 1 && head == heads - 1 && wrow == H - 1 && tx0 + kTileX >= W;
+            if (!at_end) {   // (wave-uniform) every chunk lies inside the tensor
 #pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const int c = lane + it * kWave;
-                if (c < nchunks) {
-                    if (!at_end || (c + 1) * 16 <= mis + wrow_bytes) {
-                        global_to_lds_16(src + c * 16, region + it * kWave * 16);
-                    } else {   // element by element
-                        for (int e = c * 16; e < mis + wrow_bytes; e += SZ)
-                            *lds_ptr<T>(region + e) = *reinterpret_cast<const T *>(src + e);
+                for (int it = 0; it < C::kRowPasses; ++it) {
+                    const int c = lane + it * kWave;
+                    if (c < nchunks) global_to_lds_16(src, (unsigned)(c * 16), region + it * kWave * 16);
+                }
+            } else {   // the chunk that would cross the tensor's end goes element by element
+#pragma unroll 1
+                for (int it = 0; it < C::kRowPasses; ++it) {
+                    const int c = lane + it * kWave;
+                    if (c < nchunks) {
+                        if ((c + 1) * 16 <= mis + wrow_bytes) {
+                            global_to_lds_16(src, (unsigned)(c * 16), region + it * kWave * 16);
+                        } else {
+                            for (int e = c * 16; e < mis + wrow_bytes; e += SZ)
+                                *lds_ptr<T>(region + e) = *reinterpret_cast<const T *>(src + e);
+                        }
                     }
                 }
             }
@@ -123,8 +139,12 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
                                                          qlin * pitch + (g & chunk_mask) * 16);
         return (half_dim && g >= 2) ? u32x4{0u, 0u, 0u, 0u} : d;
     };
-    *lds_ptr<uint32_t>(my_zero) = 0u;
-    *lds_ptr<uint32_t>(my_zero + C::kStageBytes) = 0u;
+    auto clear_zero = [&](int at) {
+        if constexpr (C::PACKED) *lds_ptr<u32x4>(at) = u32x4{0u, 0u, 0u, 0u};
+        else *lds_ptr<uint32_t>(at) = 0u;
+    };
+    clear_zero(my_zero);
+    if constexpr (!C::kOneStage) clear_zero(my_zero + C::kStageBytes);
     issue(b_begin, 0);
     u32x4 dreg = load_dout(b_begin);
 
@@ -144,10 +164,11 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
     // the query's window are in one halo row (a halo row holds K + 3 positions, the window K of them),
     // normally the row of the group's first position; when that one is already right of the window, the
     // group runs on into the next halo row and only that part can be inside.
-    int gaddr[P::NEL];
+    int gaddr[C::PACKED ? P::NEL / 2 : P::NEL];
+    static_assert(!C::PACKED || C::kWBytes + C::kZeroBytes <= 65536, "offsets from the first row run fit 16 bits");
     {
         const int wy = win_start(qy < H ? qy : H - 1, H, K) - oy, wx = win_start(qx < W ? qx : W - 1, W, K) - ox;
-        const int lane_row = w0 + (4 * strip + jy) * C::kRowRegion + phase0 + (4 * p + jx) * C::KK * SZ;
+        const int lane_row = w0 + (4 * strip + jy) * C::kRowRegion + (C::PACKED ? 0 : phase0) + (4 * p + jx) * C::KK * SZ;
 #pragma unroll
         for (int G = 0; G < P::NBLK; ++G) {
             const int h0 = 16 * G + 4 * g;
@@ -157,14 +178,38 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
             int c0 = hx0 - (wrap ? P::PW : 0) - wx;   // window column of the group's first position (may be negative)
             const int base = lane_row + (a * K + c0) * SZ;
             c0 = (q_ok && (unsigned)a < (unsigned)K) ? c0 : 64;   // no row of the window: every column test fails
+            int ga[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) gaddr[4 * G + i] = (unsigned)(c0 + i) < (unsigned)K ? base + i * SZ : my_zero;
+            for (int i = 0; i < 4; ++i) ga[i] = (unsigned)(c0 + i) < (unsigned)K ? base + i * SZ : my_zero;
+            if constexpr (C::PACKED) {
+                gaddr[2 * G] = (ga[0] - w0) | ((ga[1] - w0) << 16);
+                gaddr[2 * G + 1] = (ga[2] - w0) | ((ga[3] - w0) << 16);
+                __builtin_amdgcn_sched_barrier(0);   // one group's temporaries at a time
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) gaddr[4 * G + i] = ga[i];
+            }
         }
     }
+    // LDS address of the weight of result e in stage offset poff
+    auto weight_addr = [&](int e, int poff) -> int {
+        if constexpr (C::PACKED) {
+            const uint32_t pk = (uint32_t)gaddr[e >> 1];
+            return w0 + cur_phase + poff + (int)((e & 1) ? pk >> 16 : pk & 0xffffu);
+        } else {
+            return gaddr[e] + poff;
+        }
+    };
     auto compute = [&](auto par_c, int b) {
         constexpr int PAR = decltype(par_c)::value;
         constexpr int POFF = PAR * C::kStageBytes;
         if (!active) return;
+        if constexpr (C::PACKED) {
+            // the packed table stays packed: without this its unpacking is hoisted out of the loop over the planes
+            // and takes a register per address
+#pragma unroll
+            for (int e = 0; e < P::NEL / 2; ++e) asm volatile("" : "+v"(gaddr[e]));
+        }
         // 1. dp
         float dp[P::NEL];
         int lv = lane;
@@ -188,23 +233,30 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
         float delta = 0.f;
 #pragma unroll
         for (int e = 0; e < P::NEL; e += 2) {
-            pw2[e >> 1] = (uint32_t)*lds_ptr<uint16_t>(gaddr[e] + POFF) | ((uint32_t)*lds_ptr<uint16_t>(gaddr[e + 1] + POFF) << 16);
+            pw2[e >> 1] = (uint32_t)*lds_ptr<uint16_t>(weight_addr(e, POFF)) | ((uint32_t)*lds_ptr<uint16_t>(weight_addr(e + 1, POFF)) << 16);
             delta = __builtin_fmaf(half_of(pw2[e >> 1], 0), dp[e], delta);
             delta = __builtin_fmaf(half_of(pw2[e >> 1], 1), dp[e + 1], delta);
+            if constexpr (C::PACKED) {
+                if ((e & 15) == 14) __builtin_amdgcn_sched_barrier(0);   // sixteen gathers in flight at a time
+            }
         }
         delta += __shfl_xor(delta, 16);
         delta += __shfl_xor(delta, 32);
-        // 4. ds, back into the row run
+        // 4. ds, back into the row run (packed table: the addresses are unpacked again rather than kept since step 2)
+        if constexpr (C::PACKED) {
+#pragma unroll
+            for (int e = 0; e < P::NEL / 2; ++e) asm volatile("" : "+v"(gaddr[e]));
+        }
 #pragma unroll
         for (int e = 0; e < P::NEL; e += 2) {
             typedef float f32x2_t __attribute__((ext_vector_type(2)));
             typedef T tx2_t __attribute__((ext_vector_type(2)));
             const tx2_t d2 = __builtin_convertvector(
                 (f32x2_t){half_of(pw2[e >> 1], 0) * (dp[e] - delta), half_of(pw2[e >> 1], 1) * (dp[e + 1] - delta)}, tx2_t);
-            *lds_ptr<T>(gaddr[e] + POFF) = d2[0];
-            *lds_ptr<T>(gaddr[e + 1] + POFF) = d2[1];
+            *lds_ptr<T>(weight_addr(e, POFF)) = d2[0];
+            *lds_ptr<T>(weight_addr(e + 1, POFF)) = d2[1];
         }
-        *lds_ptr<uint32_t>(my_zero + POFF) = 0u;   // whatever the out-of-window results were, the word reads zero again
+        clear_zero(my_zero + POFF);   // whatever the out-of-window results were, the area reads zero again
     };
     auto flush = [&](int b, int par) {
         if (wrow < H)
@@ -217,27 +269,41 @@ __global__ __launch_bounds__(512, 4) void bwd_fused_small_kernel(const T *__rest
         constexpr int PAR = decltype(par_c)::value;
         wait_global_loads();   // this plane's halo, row runs and dout chunk have landed
         workgroup_sync();       // ... for every wave; the previous plane's ds row runs are complete
-        if (b > b_begin) {
-            flush(b - 1, PAR ^ 1);
-            // this wave's run is flushed (its LDS reads have returned) before its next load may land there
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if constexpr (!C::kOneStage) {
+            if (b > b_begin) {
+                flush(b - 1, PAR ^ 1);
+                // this wave's run is flushed (its LDS reads have returned) before its next load may land there
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+            if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
         }
-        if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
         if (phase_varies) {   // the table follows the phase of this plane's row run (in-window entries only)
             const int ph = phase_of(b), d = ph - cur_phase;
             cur_phase = ph;
+            if constexpr (!C::PACKED) {
 #pragma unroll
-            for (int e = 0; e < P::NEL; ++e) gaddr[e] += gaddr[e] != my_zero ? d : 0;
+                for (int e = 0; e < P::NEL; ++e) gaddr[e] += gaddr[e] != my_zero ? d : 0;
+            }
         }
         compute(par_c, b);
+        if constexpr (C::kOneStage) {
+            workgroup_sync();   // the ds row runs are complete, the halo is no longer read
+            flush(b, 0);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // (as above)
+            if (b + 1 < b_end) issue(b + 1, 0);
+        }
         ++b;
     };
     while (b < b_end) {
         step(IntC<0>{});
-        if (b < b_end) step(IntC<1>{});
+        if constexpr (!C::kOneStage) {
+            if (b < b_end) step(IntC<1>{});
+        }
     }
-    workgroup_sync();
-    flush(b_end - 1, (b_end - b_begin - 1) & 1);
+    if constexpr (!C::kOneStage) {
+        workgroup_sync();
+        flush(b_end - 1, (b_end - b_begin - 1) & 1);
+    }
 }
 
 template <typename T, int K>
@@ -257,7 +323,7 @@ static hipError_t launch_bwd_fused_t(const Problem &p, const void *attn, const v
     return hipGetLastError();
 }
 
-bool bwd_fused_supported(const Problem &p) { return (p.D == kHeadDim || p.D == kHalfDim) && p.dtype != NA2D_F32 && p.K <= 7; }
+bool bwd_fused_supported(const Problem &p) { return (p.D == kHeadDim || p.D == kHalfDim) && p.dtype != NA2D_F32 && p.K <= 9; }
 
 hipError_t launch_bwd_fused(const Problem &p, const void *attn, const void *dout, const void *v, void *ds, hipStream_t s) {
 #define NA2D_BWDF_K(TT)                                                                                   \
@@ -265,6 +331,7 @@ hipError_t launch_bwd_fused(const Problem &p, const void *attn, const void *dout
         case 3: return launch_bwd_fused_t<TT, 3>(p, attn, dout, v, ds, s);                               \
         case 5: return launch_bwd_fused_t<TT, 5>(p, attn, dout, v, ds, s);                               \
         case 7: return launch_bwd_fused_t<TT, 7>(p, attn, dout, v, ds, s);                               \
+        case 9: return launch_bwd_fused_t<TT, 9>(p, attn, dout, v, ds, s);                               \
         default: return hipErrorInvalidValue;                                                             \
     }
     if (p.dtype == NA2D_F16) { NA2D_BWDF_K(f16_t) }

@@ -102,7 +102,7 @@ def run_all(oracle, p: synth.Problem, seed: int, planes=None, backward=True, use
         # grad-b sums over the batch: needs the whole ds tensor
         assert_close_rpb("grad-b", st.d_rpb, whole_rpb_grad(oracle, st.ds, p.k, p))
         # The composed backward either runs the same kernels as the stages (then everything is bitwise
-        # equal to them) or fuses grad-a with the softmax backward (16-bit types, k <= 7: dp is never
+        # equal to them) or fuses grad-a with the softmax backward (16-bit types, k <= 9: dp is never
         # rounded to the storage type).  The fused result is checked like the stages: its ds (left in
         # the workspace) against the oracle's softmax backward of the exact dp, and grad-q / grad-k /
         # grad-b against the oracle fed that ds.  grad-v does not depend on ds: always bitwise equal.
@@ -113,7 +113,7 @@ def run_all(oracle, p: synth.Problem, seed: int, planes=None, backward=True, use
             for a, b_, n in ((dq, st.dq, "dq"), (dk, st.dk, "dk"), (d_rpb, st.d_rpb, "d_rpb")):
                 assert torch.equal(a, b_), f"na2d_bwd {n} differs from the stage-by-stage result"
         else:
-            assert p.dtype != "f32" and p.k <= 7, "only the 16-bit small-window backward is fused"
+            assert p.dtype != "f32" and p.k <= 9, "only the 16-bit backward with k <= 9 is fused"
             for sl in slices_of(p, planes):
                 tag = f"na2d_bwd block{sl}"
                 q, key, v, dout = (block(host[n], sl).astype(np.float64) for n in ("q", "k", "v", "dout"))
