@@ -55,11 +55,10 @@ def algorithmic_bytes(p) -> dict:
         "qk_bwd_q": contraction, "qk_bwd_k": contraction, "qk_bwd_rpb": nq * kk * e,
         # q, k, v, dout and lse in; dq, dk, dv out (the bias gradient is a few hundred bytes)
         "fused_bwd": nq * (7 * D * e + 4),
-        # the composed backward on stored weights; where it fuses grad-a with the softmax backward (16-bit, k <= 7, D = 32) dp is never stored and
+        # the composed backward on stored weights; where it fuses grad-a with the softmax backward (16-bit, k <= 9, D = 32) dp is never stored and
         # ds is read by grad-q and grad-k only: grad-a + softmax backward (attn, dout, v in; ds out), grad-v,
         # grad-q (+ grad-b), grad-k.  Elsewhere it is the six steps one after the other.
-        # (k = 9: that fusion, but grad-b as a step of its own, reading ds once more.)
-        "bwd": (nq * ((2 * D * e + 2 * kk * e) + 3 * (2 * D * e + kk * e) + (kk * e if p.k > 7 else 0))
+        "bwd": (nq * ((2 * D * e + 2 * kk * e) + 3 * (2 * D * e + kk * e))
                 if (p.dtype != "f32" and p.k <= 9 and p.D == 32) else 4 * contraction + nq * 4 * kk * e),
     }
 

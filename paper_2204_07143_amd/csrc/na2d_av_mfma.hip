@@ -46,8 +46,8 @@ struct AvSmallCfg {
     // workgroup that shares the compute unit computes, where that is what makes them fit (k = 9)
     static constexpr bool kOneStage = 2 * kStageBytes > 80 * 1024 && kStageBytes <= 80 * 1024;
     static constexpr int kLdsStages = (kOneStage ? 1 : 2) * kStageBytes;
-    // per-wave bias-gradient tables (the grad-b variant exists for k <= 7 only)
-    static constexpr int kRpbBytes = K <= 7 ? WAVES * (2 * K - 1) * (2 * K - 1) * 4 : 0;
+    // per-wave bias-gradient tables (the grad-b variant exists for k <= 9 only)
+    static constexpr int kRpbBytes = K <= 9 ? WAVES * (2 * K - 1) * (2 * K - 1) * 4 : 0;
     static constexpr int kLdsBytes = kLdsStages + kRpbBytes;
     static constexpr int kWavesPerSimd = kLdsBytes <= 80 * 1024 ? 4 : 2;   // two workgroups, or one, per compute unit
     static_assert(K > 7 || kStageBytes < 65536, "the second stage is reached through the 16-bit offset of the LDS reads");
@@ -218,37 +218,51 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
     // (2K-1)^2 table in LDS one at a time.
     constexpr int NB = 2 * K - 1, CELLS = NB * NB;
     const int rtbl = lds0 + C::kLdsStages + wave * CELLS * 4;
-    float racc = 0.f;
+    constexpr int SPL = (C::KK + kWave - 1) / kWave;   // window slots per lane (slot = lane + 64 s)
+    float racc[SPL];
+    int slot_cell[SPL];   // a slot's place inside the table, relative to (py, px)
+#pragma unroll
+    for (int sl = 0; sl < SPL; ++sl) {
+        const int slot = lane + sl * kWave;
+        racc[sl] = 0.f;
+        slot_cell[sl] = (slot / K) * NB + (slot % K);
+    }
     const int rpy = rpb_start(wrow < H ? wrow : H - 1, H, K);
     const int nvalid = (W - tx0) < kTileX ? (W - tx0) : kTileX;
     const int xi0 = (tx0 > P::R ? tx0 : P::R) - tx0;                                   // interior queries of the run:
     const int xi1 = ((tx0 + nvalid) < (W - P::R) ? (tx0 + nvalid) : (W - P::R)) - tx0;   // [xi0, xi1)
-    const int slot_cell = (lane / K) * NB + (lane % K);   // this lane's slot inside the table, relative to (py, px)
     if constexpr (RPB) {
         for (int i = tid; i < C::WAVES * CELLS; i += C::kThreads) *lds_ptr<float>(lds0 + C::kLdsStages + i * 4) = 0.f;
     }
     auto row_sums = [&](auto par_c, int b) {
         constexpr int PAR = decltype(par_c)::value;
-        if (wrow >= H || lane >= C::KK) return;
-        const int run = w0 + PAR * C::kStageBytes + wave * C::kRowRegion +
-                        (int)((((size_t)b * heads + head) * plane_w + wrow_off) & 15) + lane * SZ;
-        // all sixteen reads in flight at once (queries past the end of the run re-read its first one)
-        float v[kTileX];
+        if (wrow >= H) return;
+        const int run0 = w0 + PAR * C::kStageBytes + wave * C::kRowRegion +
+                         (int)((((size_t)b * heads + head) * plane_w + wrow_off) & 15);
 #pragma unroll
-        for (int i = 0; i < kTileX; ++i) v[i] = to_f32(*lds_ptr<T>(run + (i < nvalid ? i : 0) * C::KK * SZ));
-        float s0 = 0.f, s1 = 0.f;
+        for (int sl = 0; sl < SPL; ++sl) {
+            const int slot = lane + sl * kWave;
+            if (slot < C::KK) {
+                const int run = run0 + slot * SZ;
+                // all sixteen reads in flight at once (queries past the end of the run re-read its first one)
+                float v[kTileX];
 #pragma unroll
-        for (int i = 0; i < kTileX; i += 2) {
-            s0 += (i >= xi0 && i < xi1) ? v[i] : 0.f;
-            s1 += (i + 1 >= xi0 && i + 1 < xi1) ? v[i + 1] : 0.f;
-        }
-        racc += s0 + s1;
-        if (xi0 > 0 || xi1 < nvalid) {   // border queries (the leftmost / rightmost tile of the map only)
+                for (int i = 0; i < kTileX; ++i) v[i] = to_f32(*lds_ptr<T>(run + (i < nvalid ? i : 0) * C::KK * SZ));
+                float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-            for (int i = 0; i < kTileX; ++i) {
-                if (i < nvalid && !(i >= xi0 && i < xi1)) {
-                    const int cell = rtbl + ((rpy * NB + rpb_start(tx0 + i, W, K)) + slot_cell) * 4;
-                    *lds_ptr<float>(cell) += v[i];
+                for (int i = 0; i < kTileX; i += 2) {
+                    s0 += (i >= xi0 && i < xi1) ? v[i] : 0.f;
+                    s1 += (i + 1 >= xi0 && i + 1 < xi1) ? v[i + 1] : 0.f;
+                }
+                racc[sl] += s0 + s1;
+                if (xi0 > 0 || xi1 < nvalid) {   // border queries (the leftmost / rightmost tile of the map only)
+#pragma unroll
+                    for (int i = 0; i < kTileX; ++i) {
+                        if (i < nvalid && !(i >= xi0 && i < xi1)) {
+                            const int cell = rtbl + ((rpy * NB + rpb_start(tx0 + i, W, K)) + slot_cell[sl]) * 4;
+                            *lds_ptr<float>(cell) += v[i];
+                        }
+                    }
                 }
             }
         }
@@ -362,7 +376,9 @@ __global__ __launch_bounds__(512, (AvSmallCfg<T, K>::kWavesPerSimd)) void av_mfm
 
     if constexpr (RPB) {
         // interior sums into the wave's table, then the eight tables are added in wave order
-        if (wrow < H && lane < C::KK && xi1 > xi0) *lds_ptr<float>(rtbl + ((rpy * NB + P::R) + slot_cell) * 4) += racc;
+#pragma unroll
+        for (int sl = 0; sl < SPL; ++sl)
+            if (wrow < H && lane + sl * kWave < C::KK && xi1 > xi0) *lds_ptr<float>(rtbl + ((rpy * NB + P::R) + slot_cell[sl]) * 4) += racc[sl];
         workgroup_sync();
         for (int cell = tid; cell < CELLS; cell += C::kThreads) {
             float sum = *lds_ptr<float>(lds0 + C::kLdsStages + cell * 4);
@@ -397,7 +413,7 @@ static hipError_t launch_av_mfma_small_t(const Problem &p, const void *w, const 
 }
 
 // grad-q together with partial bias gradients (one per workgroup, av_rpb_partials() of them)
-bool av_rpb_supported(const Problem &p) { return (p.D == kHeadDim || p.D == kHalfDim) && p.dtype != NA2D_F32 && p.K <= 7; }
+bool av_rpb_supported(const Problem &p) { return (p.D == kHeadDim || p.D == kHalfDim) && p.dtype != NA2D_F32 && p.K <= 9; }
 AvRpbSplit av_rpb_split(const Problem &p) {
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + 8 - 1) / 8;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
@@ -413,6 +429,7 @@ hipError_t launch_av_rpb(const Problem &p, const void *w, const void *y, float s
         case 3: return launch_av_mfma_small_t<TT, 3, true>(p, w, y, scale, out, s, rpb_partial);              \
         case 5: return launch_av_mfma_small_t<TT, 5, true>(p, w, y, scale, out, s, rpb_partial);              \
         case 7: return launch_av_mfma_small_t<TT, 7, true>(p, w, y, scale, out, s, rpb_partial);              \
+        case 9: return launch_av_mfma_small_t<TT, 9, true>(p, w, y, scale, out, s, rpb_partial);              \
         default: return hipErrorInvalidValue;                                                                 \
     }
     if (p.dtype == NA2D_F16) { NA2D_AVR_K(f16_t) }
