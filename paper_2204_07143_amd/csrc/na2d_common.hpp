@@ -209,7 +209,8 @@ __device__ __forceinline__ __attribute__((address_space(3))) T *lds_ptr(int addr
 // 19.6 -> 17.2 us, grad-v / grad-k 24.5 -> 23.6 us at the benchmark shape).  The attention-shaped results
 // (logits, weights, dp, ds) keep plain stores: the next kernel of the path reads them, out of the last-level
 // cache when it follows at once; streaming them as well made each producer faster by itself (logits
-// 24.2 -> 21.4 us) and the ten-call step slower.  `p` may be aligned to the element only.
+// 24.2 -> 21.4 us) and the ten-call step slower.  (The logits kernel streams them all the same once the tensor
+// has 48 MB or more: see its launcher.)  `p` may be aligned to the element only.
 typedef u32x4 __attribute__((aligned(2))) u32x4_unaligned;
 __device__ __forceinline__ void store16_stream(void *p, u32x4 v) {
     __builtin_nontemporal_store(v, reinterpret_cast<u32x4_unaligned *>(p));

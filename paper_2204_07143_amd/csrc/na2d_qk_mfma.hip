@@ -67,8 +67,9 @@ struct QkSmallCfg {
 // pointers), and whose 64 lanes still cover one contiguous kilobyte.  Aligning the stores instead would put the
 // misalignment on the LDS side, where a 16-byte read at a 2-byte phase costs eight reads.  The elements past
 // the last whole chunk (ragged tiles only) go one by one.
+// `stream`: the stores carry the non-temporal hint (see launch_qk_mfma_small_ns for when).
 template <typename T, int PASSES>
-__device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, int lds_row, int lane) {
+__device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, int lds_row, int lane, bool stream) {
     const int nbody = nbytes >> 4;
     char *ga = gbase + g0;
     struct __attribute__((packed, aligned(2))) Chunk {
@@ -85,7 +86,10 @@ __device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, in
 #pragma unroll
         for (int it = it0; it < it0 + 2 && it < PASSES; ++it) {
             const int c = lane + it * kWave;
-            if (c < nbody) reinterpret_cast<Chunk *>(ga + 16 * c)->v = v[it - it0];
+            if (c < nbody) {
+                if (stream) store16_stream(ga + 16 * c, v[it - it0]);
+                else reinterpret_cast<Chunk *>(ga + 16 * c)->v = v[it - it0];
+            }
         }
     }
     const int tb = 16 * nbody + lane * (int)sizeof(T);
@@ -95,7 +99,7 @@ __device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, in
 template <typename T, int K, int NS>
 __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk_mfma_small_kernel(
     const T *__restrict__ x, const T *__restrict__ y, const T *__restrict__ rpb, float scale, T *__restrict__ logits, int H,
-    int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd, int half_dim) {
+    int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd, int half_dim, int stream_out) {
     using C = QkSmallCfg<T, K, NS>;
     using P = Patch<K>;
     constexpr int kFlushPasses = (C::kRowBytes + kWave * 16 - 1) / (kWave * 16);   // 16-byte chunks per lane and row run
@@ -248,7 +252,7 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
     auto flush = [&](int b, int par) {
         if (frow < H)
             flush_run<T, kFlushPasses>(reinterpret_cast<char *>(logits), ((size_t)b * heads + head) * plane_out + foff, fbytes,
-                         stage0 + par * C::kParity + wave * C::kRowPitch, lane);
+                         stage0 + par * C::kParity + wave * C::kRowPitch, lane, stream_out != 0);
     };
     auto compute = [&](auto par_c, const u32x4 (&qreg)[NS]) {
         constexpr int PAR = decltype(par_c)::value;
@@ -340,13 +344,19 @@ static hipError_t launch_qk_mfma_small_ns(const Problem &p, const void *x, const
     static_assert(C::kLdsBytes <= 160 * 1024, "LDS of a compute unit");
     const int tiles_x = (p.W + kTileX - 1) / kTileX, tiles_y = (p.H + C::TY - 1) / C::TY;
     const UnitSplit us = unit_split(tiles_x, tiles_y, p.heads, p.B);
+    // The logits (or dp) are read by the next kernel of the path.  A small tensor is still in the last-level cache
+    // then, so its stores are plain ones; from 48 MB on they carry the non-temporal hint, which keeps them from
+    // competing with the halo re-reads of this kernel: at the benchmark shape (39 MB at k = 7) the hint makes this
+    // kernel 2.6 us faster and the chain of calls 3 us slower, at k = 9, 11, 13 (65 to 136 MB) it makes the kernel
+    // 3 to 12 us faster and the chain 2 to 4 us faster (measured with the two builds run in turn).
+    const int stream_out = (size_t)p.queries() * C::KK * sizeof(T) >= ((size_t)48 << 20) ? 1 : 0;
     auto kern = qk_mfma_small_kernel<T, K, NS>;
     static LdsAllowed allowed;
     if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(x), static_cast<const T *>(y), static_cast<const T *>(rpb), scale,
                        static_cast<T *>(logits), p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd,
-                       p.D == kHalfDim ? 1 : 0);
+                       p.D == kHalfDim ? 1 : 0, stream_out);
     return hipGetLastError();
 }
 
