@@ -159,8 +159,8 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
         for (int sl = 0; sl < NS; ++sl) {
             C::Halo::issue_at(reinterpret_cast<const char *>(y) + plane * plane_in + sl * Traits<T>::kKeyBytes, hoff,
                               lds0 + par * C::kHaloParity + sl * C::kHaloBytes, wave);
-            qnext[sl] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) + plane * plane_in + qoff +
-                                                          sl * Traits<T>::kKeyBytes);
+            qnext[sl] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) + plane * plane_in + qoff +
+                                                                                   sl * Traits<T>::kKeyBytes));
         }
     };
     issue(b_begin, 0);   // the first tile's loads fly while the tables below are built
