@@ -96,10 +96,11 @@ __device__ __forceinline__ void flush_run(char *gbase, size_t g0, int nbytes, in
     if (tb < nbytes) *reinterpret_cast<T *>(ga + tb) = *lds_ptr<T>(lds_row + tb);
 }
 
-template <typename T, int K, int NS>
+template <typename T, int K, int NS, bool STREAM>
 __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk_mfma_small_kernel(
     const T *__restrict__ x, const T *__restrict__ y, const T *__restrict__ rpb, float scale, T *__restrict__ logits, int H,
-    int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd, int half_dim, int stream_out) {
+    int W, int heads, int nb, int tiles_y, int units, int splits, GridDecode gd, int half_dim) {
+    // STREAM: the stores of the results carry the non-temporal hint (see launch_qk_mfma_small_ns for when)
     using C = QkSmallCfg<T, K, NS>;
     using P = Patch<K>;
     constexpr int kFlushPasses = (C::kRowBytes + kWave * 16 - 1) / (kWave * 16);   // 16-byte chunks per lane and row run
@@ -159,8 +160,13 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
         for (int sl = 0; sl < NS; ++sl) {
             C::Halo::issue_at(reinterpret_cast<const char *>(y) + plane * plane_in + sl * Traits<T>::kKeyBytes, hoff,
                               lds0 + par * C::kHaloParity + sl * C::kHaloBytes, wave);
-            qnext[sl] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) + plane * plane_in + qoff +
-                                                                                   sl * Traits<T>::kKeyBytes));
+            // (read once: with the non-temporal hint where that gains, i.e. from k = 7 on while the stores are plain ones:
+            // grad-a 23.0 -> 21.7 us at k = 7.  For smaller windows, for two slices and beside streaming stores it
+            // loses: logits 14.7 -> 16.5 us at k = 5, 19.9 -> 27.7 us at D = 64, 39.4 -> 44.8 us at k = 11.)
+            const u32x4 *qsrc = reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x) + plane * plane_in + qoff +
+                                                                sl * Traits<T>::kKeyBytes);
+            if constexpr (K >= 7 && NS == 1 && !STREAM) qnext[sl] = __builtin_nontemporal_load(qsrc);
+            else qnext[sl] = *qsrc;
         }
     };
     issue(b_begin, 0);   // the first tile's loads fly while the tables below are built
@@ -252,7 +258,7 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
     auto flush = [&](int b, int par) {
         if (frow < H)
             flush_run<T, kFlushPasses>(reinterpret_cast<char *>(logits), ((size_t)b * heads + head) * plane_out + foff, fbytes,
-                         stage0 + par * C::kParity + wave * C::kRowPitch, lane, stream_out != 0);
+                         stage0 + par * C::kParity + wave * C::kRowPitch, lane, STREAM);
     };
     auto compute = [&](auto par_c, const u32x4 (&qreg)[NS]) {
         constexpr int PAR = decltype(par_c)::value;
@@ -349,14 +355,14 @@ static hipError_t launch_qk_mfma_small_ns(const Problem &p, const void *x, const
     // competing with the halo re-reads of this kernel: at the benchmark shape (39 MB at k = 7) the hint makes this
     // kernel 2.6 us faster and the chain of calls 3 us slower, at k = 9, 11, 13 (65 to 136 MB) it makes the kernel
     // 3 to 12 us faster and the chain 2 to 4 us faster (measured with the two builds run in turn).
-    const int stream_out = (size_t)p.queries() * C::KK * sizeof(T) >= ((size_t)48 << 20) ? 1 : 0;
-    auto kern = qk_mfma_small_kernel<T, K, NS>;
-    static LdsAllowed allowed;
-    if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed); e != hipSuccess) return e;
+    const bool stream_out = (size_t)p.queries() * C::KK * sizeof(T) >= ((size_t)48 << 20);
+    auto kern = stream_out ? qk_mfma_small_kernel<T, K, NS, true> : qk_mfma_small_kernel<T, K, NS, false>;
+    static LdsAllowed allowed[2];
+    if (hipError_t e = allow_lds(kern, C::kLdsBytes, allowed[stream_out]); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(xcd_padded_grid(us.units * us.splits)), dim3(C::kThreads), C::kLdsBytes, s,
                        static_cast<const T *>(x), static_cast<const T *>(y), static_cast<const T *>(rpb), scale,
                        static_cast<T *>(logits), p.H, p.W, p.heads, p.B, tiles_y, us.units, us.splits, us.gd,
-                       p.D == kHalfDim ? 1 : 0, stream_out);
+                       p.D == kHalfDim ? 1 : 0);
     return hipGetLastError();
 }
 
