@@ -201,6 +201,26 @@ def test_large_windows_many_tiles_odd_batch(oracle, H, W, k, dtype):
             planes=[(0, 0), (2, 1), (4, 2)])
 
 
+@pytest.mark.parametrize("k,side", [(k, k + d) for k in (7, 11, 13) for d in range(0, 30, 1)])
+def test_every_map_height_and_width(oracle, k, side):
+    # the same walk through the map geometries for the other window sides whose kernels depend on them (k = 7:
+    # column-walking, tile and row-streaming grad-v / grad-k kernels; k = 11, 13: one, two or four patches per wave,
+    # one halo buffer and one staging image in the logits kernel), bf16
+    for H, W in ((side, 24), (24, side)):
+        run_all(oracle, synth.Problem(2, 1, H, W, 32, k, "bf16"), seed=7000 + 50 * H + W + k)
+
+
+@pytest.mark.parametrize("side", list(range(9, 42)))
+def test_k9_every_map_height_and_width(oracle, side):
+    # k = 9 runs its kernels with LDS plans of their own (the query rectangle of a key tile in chunks of rows, one
+    # stage or one staging image instead of two, two window slots per lane in the bias-gradient sums): every map
+    # height from 9 to 41 on a 20-wide map, and every width on a 20-high one, so that every number of rectangle
+    # rows and columns, every position of the chunk boundary inside a patch's rows and the maps that fall back to
+    # other kernels (a patch seen from more than 16 columns) all occur; every stage and both backward calls
+    for H, W in ((side, 20), (20, side)):
+        run_all(oracle, synth.Problem(2, 1, H, W, 32, 9, "f16"), seed=9000 + 50 * H + W)
+
+
 @pytest.mark.parametrize("B,heads,H,W,k,dtype", [(40, 3, 20, 20, 7, "f16"), (37, 5, 9, 17, 5, "bf16"), (70, 1, 8, 16, 7, "f16")])
 def test_batch_ranges_cover_every_plane(oracle, B, heads, H, W, k, dtype):
     # more batch items than ranges, ranges of unequal length, rotated per head by an amount that does not
