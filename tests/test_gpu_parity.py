@@ -201,7 +201,7 @@ def test_large_windows_many_tiles_odd_batch(oracle, H, W, k, dtype):
             planes=[(0, 0), (2, 1), (4, 2)])
 
 
-@pytest.mark.parametrize("k,side", [(k, k + d) for k in (7, 11, 13) for d in range(0, 30, 1)])
+@pytest.mark.parametrize("k,side", [(k, k + d) for k in (3, 5, 7, 11, 13) for d in range(0, 30, 1)])
 def test_every_map_height_and_width(oracle, k, side):
     # the same walk through the map geometries for the other window sides whose kernels depend on them (k = 7:
     # column-walking, tile and row-streaming grad-v / grad-k kernels; k = 11, 13: one, two or four patches per wave,
