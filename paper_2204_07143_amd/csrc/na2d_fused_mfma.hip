@@ -54,7 +54,10 @@ struct FusedSmallCfg {
     static constexpr int kThreads = kWave * WAVES;
     static constexpr int kHaloBytes = Halo::kBytes;             // one slice of one operand
     static constexpr int kStageBytes = 2 * NS * kHaloBytes;     // the key slices, then the value slices
-    static constexpr int kLdsBytes = 2 * kStageBytes;
+    // Two buffer pairs (the next tile's halos arrive while this one is computed); one pair, loaded between tiles, where
+    // two exceed the LDS of a compute unit (two slices, k >= 9)
+    static constexpr bool kOneStage = 2 * kStageBytes > 160 * 1024;
+    static constexpr int kLdsBytes = (kOneStage ? 1 : 2) * kStageBytes;
     static constexpr int kKeyBytesG = NS * Traits<T>::kKeyBytes;   // bytes per position in memory
     static constexpr int kWavesPerSimd = kLdsBytes <= 80 * 1024 ? 4 : 2;   // two workgroups, or one, per compute unit
 };
@@ -260,13 +263,23 @@ __global__ __launch_bounds__(512, (FusedSmallCfg<T, K, NS>::kWavesPerSimd)) void
         u32x4 qreg[NS];
 #pragma unroll
         for (int sl = 0; sl < NS; ++sl) qreg[sl] = (half_dim && g >= 2) ? u32x4{0u, 0u, 0u, 0u} : qnext[sl];
-        if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
-        compute(par_c, qreg, b);
+        if constexpr (C::kOneStage) {
+            compute(par_c, qreg, b);
+            if (b + 1 < b_end) {
+                workgroup_sync();   // nobody still reads the halos
+                issue(b + 1, 0);
+            }
+        } else {
+            if (b + 1 < b_end) issue(b + 1, PAR ^ 1);
+            compute(par_c, qreg, b);
+        }
         ++b;
     };
     while (b < b_end) {
         step(IntC<0>{});
-        if (b < b_end) step(IntC<1>{});
+        if constexpr (!C::kOneStage) {
+            if (b < b_end) step(IntC<1>{});
+        }
     }
 }
 
@@ -291,15 +304,13 @@ static hipError_t launch_fused_mfma_small_ns(const Problem &p, const void *q, co
 template <typename T, int K>
 static hipError_t launch_fused_mfma_small_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
                                             float scale, void *out, float *lse, hipStream_t s) {
-    if constexpr (K <= 7) {
-        if (p.D == 2 * kHeadDim) return launch_fused_mfma_small_ns<T, K, 2>(p, q, k, v, rpb, scale, out, lse, s);
-    }
+    if (p.D == 2 * kHeadDim) return launch_fused_mfma_small_ns<T, K, 2>(p, q, k, v, rpb, scale, out, lse, s);
     return launch_fused_mfma_small_ns<T, K, 1>(p, q, k, v, rpb, scale, out, lse, s);
 }
 
 bool fused_mfma_supported(const Problem &p) {
     if (p.dtype == NA2D_F32 || p.K > kMaxTunedK) return false;
-    return p.D == kHeadDim || p.D == kHalfDim || (p.D == 2 * kHeadDim && p.K <= 7);   // two slices only in the small-window kernel
+    return p.D == kHeadDim || p.D == kHalfDim || p.D == 2 * kHeadDim;   // one or two 32-channel slices
 }
 
 hipError_t launch_fused_mfma(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,

@@ -51,7 +51,8 @@ struct QkSmallCfg {
     // make them fit either); one image, filled and streamed out in turn, where that is what makes them fit (k = 9)
     static constexpr bool kOneImage = 2 * kHaloAll + 2 * kImage > 80 * 1024 && 2 * kHaloAll + kImage <= 80 * 1024;
     // ... and one halo buffer too, loaded between tiles, where only that makes them fit (k = 11, 13)
-    static constexpr bool kOneHalo = 2 * kHaloAll + kImage > 80 * 1024 && kHaloAll + kImage <= 80 * 1024;
+    // (also where two buffers and two images exceed the LDS of a compute unit altogether: two slices, k >= 11)
+    static constexpr bool kOneHalo = 2 * kHaloAll + kImage > 80 * 1024 && (kHaloAll + kImage <= 80 * 1024 || 2 * kHaloAll + 2 * kImage > 160 * 1024);
     static constexpr bool kOneBoth = kOneImage || kOneHalo;      // (one image either way)
     static constexpr int kParity = kOneBoth ? 0 : kImage;        // distance between the two staging images
     static constexpr int kHaloParity = kOneHalo ? 0 : kHaloAll;  // ... between the two halo buffers
@@ -369,15 +370,13 @@ static hipError_t launch_qk_mfma_small_ns(const Problem &p, const void *x, const
 template <typename T, int K>
 static hipError_t launch_qk_mfma_small_t(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
                                          void *logits, hipStream_t s) {
-    if constexpr (K <= 7) {
-        if (p.D == 2 * kHeadDim) return launch_qk_mfma_small_ns<T, K, 2>(p, x, y, rpb, scale, logits, s);
-    }
+    if (p.D == 2 * kHeadDim) return launch_qk_mfma_small_ns<T, K, 2>(p, x, y, rpb, scale, logits, s);
     return launch_qk_mfma_small_ns<T, K, 1>(p, x, y, rpb, scale, logits, s);
 }
 
 bool qk_mfma_supported(const Problem &p) {
     if (p.dtype == NA2D_F32 || p.K > kMaxTunedK) return false;
-    return p.D == kHeadDim || p.D == kHalfDim || (p.D == 2 * kHeadDim && p.K <= 7);   // two slices only in the small-window kernel
+    return p.D == kHeadDim || p.D == kHalfDim || p.D == 2 * kHeadDim;   // one or two 32-channel slices
 }
 
 hipError_t launch_qk_mfma(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
