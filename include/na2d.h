@@ -40,9 +40,11 @@
  *    correct and deterministic, not tuned).  Head dims
  *    D in {16, 32, 64, 128}.  D = 32 (every NAT variant, Section 3.2) runs the matrix-core
  *    kernels in the 16-bit types; so do the weighted sums (av, grad-q, grad-v, grad-k) for
- *    D = 64 and 128, the logits, grad-a and the fused forward for D = 64, and all
+ *    D = 64 and 128, the logits, grad-a and the fused forward for D = 64 (for D = 128 the
+ *    logits and grad-a with k <= 11, the fused forward with k <= 7), and all
  *    of these for D = 16 (a 16-channel head rides in the lower half of the 32-channel
- *    kernels); the rest runs tiled plain-ALU kernels while their tiles fit the
+ *    kernels); the softmax kernels and grad-b do not depend on D; the rest runs tiled
+ *    plain-ALU kernels while their tiles fit the
  *    160 KB LDS (every k for D = 16 and for D = 64 in the 16-bit types, k <= 9 for D = 128 in
  *    the 16-bit types and for D = 64 in fp32, k = 3 for D = 128 in fp32) and the run-time-k
  *    kernels otherwise.

@@ -52,7 +52,7 @@ __global__ void indices_kernel(int32_t *key_index, int32_t *rpb_index, int H, in
 }
 
 hipError_t launch_indices(const Problem &p, int32_t *key_index, int32_t *rpb_index, hipStream_t s) {
-    if (generic_window(p)) return launch_indices_generic(p, key_index, rpb_index, s);
+    if (untuned_window(p)) return launch_indices_generic(p, key_index, rpb_index, s);
     const int n = p.H * p.W * p.K * p.K;
     NA2D_DISPATCH_K(p.K, hipLaunchKernelGGL((indices_kernel<float, K>), dim3((n + 255) / 256), dim3(256), 0, s,
                                             key_index, rpb_index, p.H, p.W));

@@ -87,8 +87,8 @@ static hipError_t launch_av_t(const Problem &p, const void *w, const void *y, fl
 }
 
 hipError_t launch_av(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s) {
-    if (generic_window(p)) return launch_av_generic(p, w, y, scale, out, s);
     if (av_mfma_supported(p)) return launch_av_mfma(p, w, y, scale, out, s);
+    if (generic_window(p)) return launch_av_generic(p, w, y, scale, out, s);
     NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, NA2D_DISPATCH_D(p.D, return (launch_av_t<T, K, D>(p, w, y, scale, out, s)))));
     return hipErrorInvalidValue;
 }

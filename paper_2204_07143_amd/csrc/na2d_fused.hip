@@ -112,8 +112,8 @@ static hipError_t launch_fused_t(const Problem &p, const void *q, const void *k,
 
 hipError_t launch_fused_fwd(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,
                             void *out, float *lse, hipStream_t s) {
-    if (generic_window(p)) return launch_fused_generic(p, q, k, v, rpb, scale, out, lse, s);
     if (fused_mfma_supported(p)) return launch_fused_mfma(p, q, k, v, rpb, scale, out, lse, s);
+    if (generic_window(p)) return launch_fused_generic(p, q, k, v, rpb, scale, out, lse, s);
     NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, NA2D_DISPATCH_D(p.D, return (launch_fused_t<T, K, D>(p, q, k, v, rpb, scale, out, lse, s)))));
     return hipErrorInvalidValue;
 }

@@ -305,12 +305,16 @@ template <typename T, int K>
 static hipError_t launch_fused_mfma_small_t(const Problem &p, const void *q, const void *k, const void *v, const void *rpb,
                                             float scale, void *out, float *lse, hipStream_t s) {
     if (p.D == 2 * kHeadDim) return launch_fused_mfma_small_ns<T, K, 2>(p, q, k, v, rpb, scale, out, lse, s);
+    if constexpr (K <= 7) {
+        if (p.D == 4 * kHeadDim) return launch_fused_mfma_small_ns<T, K, 4>(p, q, k, v, rpb, scale, out, lse, s);
+    }
     return launch_fused_mfma_small_ns<T, K, 1>(p, q, k, v, rpb, scale, out, lse, s);
 }
 
 bool fused_mfma_supported(const Problem &p) {
     if (p.dtype == NA2D_F32 || p.K > kMaxTunedK) return false;
-    return p.D == kHeadDim || p.D == kHalfDim || p.D == 2 * kHeadDim;   // one or two 32-channel slices
+    // one, two or (while the key and value halos of four slices fit the LDS: k <= 7) four 32-channel slices
+    return p.D == kHeadDim || p.D == kHalfDim || p.D == 2 * kHeadDim || (p.D == 4 * kHeadDim && p.K <= 7);
 }
 
 hipError_t launch_fused_mfma(const Problem &p, const void *q, const void *k, const void *v, const void *rpb, float scale,

@@ -257,6 +257,7 @@ unsigned blocks_for(size_t total) { return (unsigned)((total + 255) / 256); }
 // head dim whose plain-ALU tiles do not fit the LDS (fp32 with D >= 64 and a larger window, D = 128 in 16 bit with
 // k >= 11): the kernels here stage nothing in LDS, so they take every head dim.
 bool generic_window(const Problem &p) { return p.K > kMaxTunedK || !head_dim_supported(p.dtype, p.K, p.D); }
+bool untuned_window(const Problem &p) { return p.K > kMaxTunedK; }
 
 hipError_t launch_qk_generic(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
                              hipStream_t s) {

@@ -81,10 +81,12 @@ static hipError_t launch_inverse_t(const Problem &p, const void *w, const void *
 }
 
 hipError_t launch_inverse(const Problem &p, const void *w, const void *x, float scale, void *out, hipStream_t s) {
+    if (!untuned_window(p)) {
+        if (inverse_ring_supported(p)) return launch_inverse_ring(p, w, x, scale, out, s);
+        if (inverse_mfma_supported(p)) return launch_inverse_mfma(p, w, x, scale, out, s);
+        if (inverse_rows_supported(p)) return launch_inverse_rows(p, w, x, scale, out, s);
+    }
     if (generic_window(p)) return launch_inverse_generic(p, w, x, scale, out, s);
-    if (inverse_ring_supported(p)) return launch_inverse_ring(p, w, x, scale, out, s);
-    if (inverse_mfma_supported(p)) return launch_inverse_mfma(p, w, x, scale, out, s);
-    if (inverse_rows_supported(p)) return launch_inverse_rows(p, w, x, scale, out, s);
     NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, NA2D_DISPATCH_D(p.D, return (launch_inverse_t<T, K, D>(p, w, x, scale, out, s)))));
     return hipErrorInvalidValue;
 }

@@ -20,7 +20,8 @@ struct Problem {
 
 // Window sides: 3..13 (odd) run the tuned kernels, 15..63 (odd) the run-time-K kernels of na2d_generic.hip.
 constexpr int kMaxTunedK = 13, kMaxGenericK = 63;
-bool generic_window(const Problem &p);
+bool generic_window(const Problem &p);   // neither the tuned window sides nor a plain-ALU tile that fits the LDS
+bool untuned_window(const Problem &p);   // k beyond the tuned sides (what the kernels that do not depend on D ask)
 hipError_t launch_qk_generic(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
                              hipStream_t s);
 hipError_t launch_av_generic(const Problem &p, const void *w, const void *y, float scale, void *out, hipStream_t s);

@@ -112,8 +112,10 @@ bool head_dim_supported(int dtype, int K, int D) {
 
 hipError_t launch_qk(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,
                      hipStream_t s) {
-    if (generic_window(p)) return launch_qk_generic(p, x, y, rpb, scale, logits, s);
+    // matrix cores where they take the problem; else the tiled plain-ALU kernel while its tile fits the LDS; else the
+    // kernels that stage nothing
     if (qk_mfma_supported(p)) return launch_qk_mfma(p, x, y, rpb, scale, logits, s);
+    if (generic_window(p)) return launch_qk_generic(p, x, y, rpb, scale, logits, s);
     NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, NA2D_DISPATCH_D(p.D, return (launch_qk_t<T, K, D>(p, x, y, rpb, scale, logits, s)))));
     return hipErrorInvalidValue;
 }

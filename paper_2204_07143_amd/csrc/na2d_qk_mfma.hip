@@ -343,6 +343,12 @@ __global__ __launch_bounds__(512, (QkSmallCfg<T, K, NS>::kWavesPerSimd)) void qk
     }
 }
 
+// D = 128: do one halo buffer of four slices and one staging image fit the 160 KB of a compute unit?
+constexpr bool four_slices_fit(int K) {
+    const int halo = (8 + K - 1) * (kTileX + K - 1) * 64, image = 8 * ((kTileX * K * K * 2 + 15) & ~15) + 512 * 4;
+    return 4 * halo + image <= 160 * 1024;
+}
+
 template <typename T, int K, int NS>
 static hipError_t launch_qk_mfma_small_ns(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
                                           void *logits, hipStream_t s) {
@@ -371,12 +377,16 @@ template <typename T, int K>
 static hipError_t launch_qk_mfma_small_t(const Problem &p, const void *x, const void *y, const void *rpb, float scale,
                                          void *logits, hipStream_t s) {
     if (p.D == 2 * kHeadDim) return launch_qk_mfma_small_ns<T, K, 2>(p, x, y, rpb, scale, logits, s);
+    if constexpr (four_slices_fit(K)) {
+        if (p.D == 4 * kHeadDim) return launch_qk_mfma_small_ns<T, K, 4>(p, x, y, rpb, scale, logits, s);
+    }
     return launch_qk_mfma_small_ns<T, K, 1>(p, x, y, rpb, scale, logits, s);
 }
 
 bool qk_mfma_supported(const Problem &p) {
     if (p.dtype == NA2D_F32 || p.K > kMaxTunedK) return false;
-    return p.D == kHeadDim || p.D == kHalfDim || p.D == 2 * kHeadDim;   // one or two 32-channel slices
+    // one, two or (while one halo buffer and one staging image fit the LDS: k <= 11) four 32-channel slices
+    return p.D == kHeadDim || p.D == kHalfDim || p.D == 2 * kHeadDim || (p.D == 4 * kHeadDim && four_slices_fit(p.K));
 }
 
 hipError_t launch_qk_mfma(const Problem &p, const void *x, const void *y, const void *rpb, float scale, void *logits,

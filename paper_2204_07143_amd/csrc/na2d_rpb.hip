@@ -230,7 +230,7 @@ hipError_t launch_rpb_final_av(const Problem &p, const float *partial, float *d_
 }
 
 size_t rpb_bwd_workspace_bytes(const Problem &p) {
-    if (generic_window(p)) return rpb_generic_workspace_bytes(p);
+    if (untuned_window(p)) return rpb_generic_workspace_bytes(p);
     const int nb = 2 * p.K - 1;
     const RpbSplit sp = rpb_split(p.planes(), p.H, p.W, p.K, p.elem_bytes());
     size_t bytes = (size_t)p.planes() * sp.groups_per_plane * rpb_cell_stride(nb * nb) * sizeof(float);
@@ -259,7 +259,7 @@ static hipError_t launch_rpb_bwd_t(const Problem &p, const void *ds, float *d_rp
 }
 
 hipError_t launch_rpb_bwd(const Problem &p, const void *ds, float *d_rpb, void *workspace, hipStream_t s) {
-    if (generic_window(p)) return launch_rpb_generic(p, ds, d_rpb, workspace, s);
+    if (untuned_window(p)) return launch_rpb_generic(p, ds, d_rpb, workspace, s);
     NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, return (launch_rpb_bwd_t<T, K>(p, ds, d_rpb, workspace, s))));
     return hipErrorInvalidValue;
 }
@@ -275,7 +275,7 @@ hipError_t launch_rpb_bwd(const Problem &p, const void *ds, float *d_rpb, void *
 static __device__ __align__(256) unsigned char scratch[NA2D_NOALLOC_SCRATCH_BYTES];
 
 size_t rpb_bwd_partial_bytes(const Problem &p) {
-    if (generic_window(p)) return rpb_generic_workspace_bytes(p);
+    if (untuned_window(p)) return rpb_generic_workspace_bytes(p);
     const int nb = 2 * p.K - 1;
     const RpbSplit sp = rpb_split(p.planes(), p.H, p.W, p.K, p.elem_bytes());
     return (size_t)p.planes() * sp.groups_per_plane * rpb_cell_stride(nb * nb) * sizeof(float);

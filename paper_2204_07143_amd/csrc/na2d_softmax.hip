@@ -172,13 +172,13 @@ static hipError_t launch_softmax_bwd_t(const Problem &p, const void *attn, const
 }
 
 hipError_t launch_softmax(const Problem &p, const void *logits, void *out, hipStream_t s) {
-    if (generic_window(p)) return launch_softmax_generic(p, logits, out, s);
+    if (untuned_window(p)) return launch_softmax_generic(p, logits, out, s);
     NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, return (launch_softmax_t<T, K>(p, logits, out, s))));
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_softmax_bwd(const Problem &p, const void *attn, const void *dp, void *ds, hipStream_t s) {
-    if (generic_window(p)) return launch_softmax_bwd_generic(p, attn, dp, ds, s);
+    if (untuned_window(p)) return launch_softmax_bwd_generic(p, attn, dp, ds, s);
     NA2D_DISPATCH_T(p.dtype, NA2D_DISPATCH_K(p.K, return (launch_softmax_bwd_t<T, K>(p, attn, dp, ds, s))));
     return hipErrorInvalidValue;
 }

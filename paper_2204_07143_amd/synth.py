@@ -57,6 +57,8 @@ CONFIGS = {
     # 64, and as four heads of 16
     "stage1_head_dim_64": Problem(64, 1, 56, 56, 64, 7, "f16"),
     "stage1_head_dim_16": Problem(64, 4, 56, 56, 16, 7, "f16"),
+    # ... and half the batch with 128 channels as one head (the same tensor sizes)
+    "stage1_head_dim_128": Problem(32, 1, 56, 56, 128, 7, "f16"),
     # the first-stage map in fp32 (the plain-ALU kernels)
     "nat_tiny_stage1_f32": Problem(64, 2, 56, 56, 32, 7, "f32"),
 }

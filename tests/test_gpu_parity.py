@@ -360,7 +360,7 @@ def test_config5_kernel_size_sweep_fwd_bwd(oracle, k):
 # ---- head dims other than 32: every (dtype, D, k) class the library accepts, and the ones it refuses ------------
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
-@pytest.mark.parametrize("D,k", [(16, 3), (16, 7), (16, 13), (64, 5), (64, 9), (64, 13), (128, 3), (128, 9), (128, 13)])
+@pytest.mark.parametrize("D,k", [(16, 3), (16, 7), (16, 13), (64, 5), (64, 9), (64, 11), (64, 13), (128, 3), (128, 5), (128, 7), (128, 9), (128, 11), (128, 13)])
 def test_generic_head_dims(oracle, dtype, D, k):
     # (the fp32 tiles of the largest head dims do not fit the LDS for larger windows: (64, 13) and (128, 9) in fp32,
     # and (128, 13) in any type, run the kernels that take the window side at run time)
